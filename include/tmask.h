@@ -1,0 +1,151 @@
+/*
+ * tmask -- N:M transposable sparsity masks on AMD MI355X (gfx950), C ABI.
+ *
+ * Implements the mask-computation path of "Accelerated Sparse Neural Training: A Provable and
+ * Efficient Method to Find N:M Transposable Masks" (arXiv 2102.08124), Sec. 4:
+ * a weight matrix is cut into M x M blocks (grid origin (0,0), stride M both ways) and a binary
+ * mask S is computed per block so that both W and W^T obey the N:M pattern.
+ *
+ * Conventions
+ *   N            entries KEPT per row and per column of a block (Eq. 1: row/column sums of S are N);
+ *                K = M - N entries are pruned.  Supported: M in {4, 8, 16}, 0 < N < M.
+ *   S_ij = 1     W_ij is kept (Eq. 1).
+ *   magnitude    |W_ij| is ordered by its bit pattern with the sign cleared, compared as an unsigned
+ *                integer: -0 == +0, denormals are not flushed, +Inf > finite, NaN > Inf.
+ *   tie-break    equal magnitudes are ordered by the row-major index i*M + j inside the block.
+ *
+ * Memory and execution
+ *   Every `w`, `mask`, `vals*`, `idx*`, `objective`, `out`, `per_block_obj` and `workspace` pointer
+ *   is DEVICE memory owned by the caller; descriptor arrays (`tmask_mat*`, `tmask_pack_desc*`) are
+ *   HOST memory read before the call returns.  Work is enqueued on `hip_stream` (a hipStream_t,
+ *   NULL = default stream); the library never synchronises, allocates or frees device memory, and
+ *   holds no state between calls.  Outputs are valid once the stream has been synchronised.
+ *   The workspace (at least tmask_workspace_bytes(), 256-byte aligned) is scratch for the duration
+ *   of the enqueued work; calls that overlap on different streams need different workspaces.
+ *
+ * Layout requirements (checked; violations return TMASK_ERR_SHAPE / TMASK_ERR_ALIGN)
+ *   rows and cols multiples of M; ld >= cols (ld in elements); rows*cols/M^2 < 2^31;
+ *   `w` 16-byte aligned, ld*sizeof(element) and cols*sizeof(element) multiples of 16
+ *   (i.e. ld, cols multiples of 4 for fp32 and of 8 for bf16): tiles are read with 16-byte loads.
+ *   U8 mask: mask 4-byte aligned, mask_ld >= cols and a multiple of 4.
+ *   BITS mask: mask_ld >= cols/8 bytes.
+ *
+ * Errors
+ *   All argument errors are detected on the host before anything is enqueued and leave the outputs
+ *   untouched.  A mask that violates N:M is a *result* of tmask_score, never an error.
+ *   tmask_last_error() returns a thread-local, human-readable description of the last failure.
+ */
+#ifndef TMASK_H
+#define TMASK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { TMASK_F32 = 0, TMASK_BF16 = 1 } tmask_dtype;
+
+/* TMASK_MASK_U8  : one byte per weight (0 or 1), row-major, row stride mask_ld bytes.
+ * TMASK_MASK_BITS: one bit per weight, bit (c % 8) of byte [r*mask_ld + c/8], LSB first. */
+typedef enum { TMASK_MASK_U8 = 0, TMASK_MASK_BITS = 1 } tmask_mask_fmt;
+
+enum {
+    TMASK_OK = 0,
+    TMASK_ERR_NULL = -1,      /* a required pointer is NULL */
+    TMASK_ERR_SHAPE = -2,     /* sizes <= 0, rows/cols not multiples of M, ld < cols, too many blocks */
+    TMASK_ERR_NM = -3,        /* need M in {4,8,16} and 0 < N < M */
+    TMASK_ERR_DTYPE = -4,     /* unknown dtype or mask format */
+    TMASK_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or smaller than tmask_workspace_bytes() */
+    TMASK_ERR_HIP = -6,       /* a HIP call failed; text in tmask_last_error() */
+    TMASK_ERR_ALIGN = -7      /* pointer / leading-dimension alignment (see layout requirements) */
+};
+
+/* One 2-D weight matrix and where its mask goes. */
+typedef struct {
+    const void *w;     /* device, rows x cols elements of the call's dtype, row stride ld elements */
+    int64_t rows, cols, ld;
+    void *mask;        /* device; written by tmask_approx/tmask_exact, read by tmask_score */
+    int64_t mask_ld;   /* bytes */
+    double *objective; /* device, nullable: [0] <- retained L1 = sum_ij S_ij |W_ij| (Eq. 1's objective) */
+} tmask_mat;
+
+/*
+ * Greedy 2-approximation (Sec. 4, Algorithm 1) on every block of every matrix, one batched launch
+ * sequence.  Result per block: the set P of pruned entries produced by sweeping the block's entries
+ * from light to heavy and taking an entry while its row or its column still has fewer than K
+ * pruned entries; S = 1 - P.  P covers every row and column at least K times, so S keeps AT MOST N
+ * per row and column (it is not repaired to exactly N).  Bit-deterministic: the same input gives
+ * the same mask on every run, equal to a literal sort-and-sweep under the (magnitude, index) order.
+ */
+int tmask_approx(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Optimal mask of Eq. 1 per block (Sec. 4, "Reduction to Min-Cost Flow", Fig. 3): exactly N kept
+ * per row and column, maximum retained L1.  2:4 blocks are solved by evaluating all 90 feasible
+ * patterns in fp32; other (N, M) by successive shortest augmenting paths on the bipartite
+ * row/column network with magnitudes truncated per block to 27 (M<=8) or 26 (M=16) significant
+ * bits below the block maximum, which costs less than M*(M-N)*2^-26 (resp. 2^-25) of the block
+ * maximum in retained L1 (below 1e-5 relative for every supported N:M).  Among equally good
+ * masks the choice is deterministic but unspecified.  Inputs must be finite for optimality; with
+ * NaN/Inf present the mask is still valid (exactly N per row/column).
+ */
+int tmask_exact(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Apply a mask and compress both operands the two training matmuls read (Sec. 2 Eq. for the
+ * backward pass: forward uses W, backward uses W^T; Sec. 4: N non-zeros per M contiguous elements
+ * in both).  The paper fixes no storage format; this one is the library's own:
+ *   W (.) S is a select (pruned entries become +0, also when W_ij is NaN or Inf).
+ *   vals  : rows x (cols*N/M) elements, row-major, dense.  Group g of row r (columns gM..gM+M-1)
+ *           owns slots [g*N, g*N+N): the kept entries in ascending column order; if fewer than N
+ *           are kept (possible for approximate masks) the lowest-numbered unused positions are added
+ *           as +0 fillers and all N slots are ordered by position.
+ *   idx   : per row, one ceil(log2 M)-bit position per slot, slot-major, LSB-first in little-endian
+ *           bytes; row stride ceil(cols*N/M * log2(M) / 8) bytes.
+ *   valsT, idxT: the same for W^T (cols x rows), i.e. groups are M consecutive rows of one column.
+ * A group with more than N kept entries is a caller error (tmask_score reports it); the first N win.
+ */
+typedef struct {
+    const void *w; int64_t rows, cols, ld;
+    const void *mask; int64_t mask_ld;
+    void *vals;  void *idx;
+    void *valsT; void *idxT;
+} tmask_pack_desc;
+
+int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Score a mask (Eq. 1's objective and constraints).  out[m] (device) receives, for matrix m:
+ * retained_l1 = sum S|W|, total_l1 = sum |W|, kept = sum S, row_violations / col_violations =
+ * number of (block,row) / (block,column) pairs with more than N kept, row_not_n / col_not_n =
+ * pairs whose kept count differs from N (zero for an exact-solver mask).
+ * per_block_obj (device, nullable): retained L1 of every block as fp32, matrices concatenated in
+ * call order, each block-row-major.  mats[m].objective is ignored.
+ */
+typedef struct {
+    double retained_l1, total_l1;
+    uint64_t kept, row_violations, col_violations, row_not_n, col_not_n;
+} tmask_score_out;
+
+int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                tmask_score_out *out, float *per_block_obj,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Upper bound of the workspace any call above needs for these matrices (0 on invalid arguments). */
+size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char *tmask_last_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int tmask_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TMASK_H */

@@ -1,0 +1,235 @@
+"""Thin ctypes binding over libtmask.so (include/tmask.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch provides the
+device memory (tensors) and the stream; nothing here computes on tensors.  There is no CPU
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtmask.so")
+
+TMASK_F32, TMASK_BF16 = 0, 1
+TMASK_MASK_U8, TMASK_MASK_BITS = 0, 1
+TMASK_OK = 0
+TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
+TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
+
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_apply_pack", "tmask_score", "tmask_workspace_bytes",
+           "tmask_last_error", "tmask_version")
+
+
+class TmaskError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("tmask error %d: %s" % (code, text))
+        self.code = code
+
+
+class tmask_mat(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("mask", C.c_void_p), ("mask_ld", C.c_int64), ("objective", C.c_void_p)]
+
+
+class tmask_pack_desc(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("mask", C.c_void_p), ("mask_ld", C.c_int64),
+                ("vals", C.c_void_p), ("idx", C.c_void_p), ("valsT", C.c_void_p), ("idxT", C.c_void_p)]
+
+
+class tmask_score_out(C.Structure):
+    _fields_ = [("retained_l1", C.c_double), ("total_l1", C.c_double), ("kept", C.c_uint64),
+                ("row_violations", C.c_uint64), ("col_violations", C.c_uint64),
+                ("row_not_n", C.c_uint64), ("col_not_n", C.c_uint64)]
+
+
+SCORE_OUT_BYTES = C.sizeof(tmask_score_out)
+_lib = None
+
+
+def load_library():
+    """Loads libtmask.so; raises if it has not been built (python -m paper_2102_08124_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libtmask.so is missing: build it with `python -m paper_2102_08124_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, ci, sz = C.c_void_p, C.c_int, C.c_size_t
+    for name in ("tmask_approx", "tmask_exact"):
+        f = getattr(L, name)
+        f.restype = ci
+        f.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, sz, vp]
+    L.tmask_apply_pack.restype = ci
+    L.tmask_apply_pack.argtypes = [C.POINTER(tmask_pack_desc), ci, ci, ci, ci, ci, vp, sz, vp]
+    L.tmask_score.restype = ci
+    L.tmask_score.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    L.tmask_workspace_bytes.restype = sz
+    L.tmask_workspace_bytes.argtypes = [C.POINTER(tmask_mat), ci, ci, ci]
+    L.tmask_last_error.restype = C.c_char_p
+    L.tmask_last_error.argtypes = []
+    L.tmask_version.restype = ci
+    L.tmask_version.argtypes = []
+    _lib = L
+    return L
+
+
+def _check(rc: int):
+    if rc != TMASK_OK:
+        raise TmaskError(rc, load_library().tmask_last_error().decode())
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return TMASK_F32
+    if t.dtype == torch.bfloat16:
+        return TMASK_BF16
+    raise TypeError("weights must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _mat2d(t: torch.Tensor, what: str):
+    if t.dim() != 2 or not t.is_cuda or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("%s must be a 2-D CUDA tensor with unit column stride" % what)
+    return t.data_ptr(), int(t.shape[0]), int(t.shape[1]), int(t.stride(0))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def mask_shape(rows: int, cols: int, mask_fmt: int):
+    return (rows, cols) if mask_fmt == TMASK_MASK_U8 else (rows, (cols + 7) // 8)
+
+
+def alloc_masks(ws: Sequence[torch.Tensor], mask_fmt: int = TMASK_MASK_U8):
+    return [torch.empty(mask_shape(w.shape[0], w.shape[1], mask_fmt), dtype=torch.uint8, device=w.device)
+            for w in ws]
+
+
+def _mats(ws, masks, objective) -> "C.Array":
+    n = len(ws)
+    if len(masks) != n:
+        raise ValueError("one mask per matrix expected")
+    if objective is not None and (objective.dtype != torch.float64 or objective.numel() < n
+                                  or not objective.is_cuda or not objective.is_contiguous()):
+        raise ValueError("objective must be a contiguous CUDA float64 tensor with one entry per matrix")
+    arr = (tmask_mat * n)()
+    for k, (w, m) in enumerate(zip(ws, masks)):
+        p, r, c, ld = _mat2d(w, "w")
+        if m.dtype != torch.uint8:
+            raise TypeError("mask must be uint8")
+        mp, _, _, mld = _mat2d(m, "mask")
+        arr[k] = tmask_mat(p, r, c, ld, mp, mld, objective.data_ptr() + 8 * k if objective is not None else None)
+    return arr
+
+
+def tmask_workspace_bytes(ws: Sequence[torch.Tensor], N: int, M: int) -> int:
+    arr = (tmask_mat * len(ws))()
+    for k, w in enumerate(ws):
+        arr[k] = tmask_mat(None, int(w.shape[0]), int(w.shape[1]), int(w.stride(0)), None, 0, None)
+    return int(load_library().tmask_workspace_bytes(arr, len(ws), N, M))
+
+
+def alloc_workspace(ws: Sequence[torch.Tensor], N: int, M: int) -> torch.Tensor:
+    return torch.empty(max(tmask_workspace_bytes(ws, N, M), 256), dtype=torch.uint8, device=ws[0].device)
+
+
+def _ws_args(workspace):
+    if workspace is None:
+        return None, 0
+    return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def _run_mask(fn, ws, masks, N, M, objective, mask_fmt, workspace, stream):
+    ws = list(ws)
+    arr = _mats(ws, masks, objective)
+    dt = dtype_code(ws[0])
+    if any(dtype_code(w) != dt for w in ws):
+        raise TypeError("all matrices of one call share a dtype")
+    wp, wb = _ws_args(workspace)
+    _check(fn(arr, len(ws), dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
+
+
+def tmask_approx(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = None,
+                 mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Algorithm 1 on every M x M block of every matrix; masks (and objective[k]) are written in place."""
+    _run_mask(load_library().tmask_approx, ws, masks, N, M, objective, mask_fmt, workspace, stream)
+
+
+def tmask_exact(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = None,
+                mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Optimum of Eq. 1 on every block; masks (and objective[k]) are written in place."""
+    _run_mask(load_library().tmask_exact, ws, masks, N, M, objective, mask_fmt, workspace, stream)
+
+
+def tmask_score(ws, masks, N: int, M: int, out: torch.Tensor, per_block_obj: Optional[torch.Tensor] = None,
+                mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """out: CUDA uint8 tensor of len(ws) * SCORE_OUT_BYTES bytes (array of tmask_score_out)."""
+    ws = list(ws)
+    arr = _mats(ws, masks, None)
+    if out.numel() * out.element_size() < len(ws) * SCORE_OUT_BYTES or not out.is_cuda or not out.is_contiguous():
+        raise ValueError("out is too small")
+    if per_block_obj is not None and (per_block_obj.dtype != torch.float32 or not per_block_obj.is_contiguous()):
+        raise ValueError("per_block_obj must be contiguous float32")
+    wp, wb = _ws_args(workspace)
+    _check(load_library().tmask_score(arr, len(ws), dtype_code(ws[0]), N, M, mask_fmt, C.c_void_p(out.data_ptr()),
+                                      C.c_void_p(per_block_obj.data_ptr()) if per_block_obj is not None else None,
+                                      wp, wb, _stream_ptr(stream)))
+
+
+def read_scores(out: torch.Tensor, n: int):
+    """Copies the device array of tmask_score_out back and returns a list of dicts."""
+    raw = out.cpu().numpy().tobytes()
+    res = []
+    for k in range(n):
+        s = tmask_score_out.from_buffer_copy(raw, k * SCORE_OUT_BYTES)
+        res.append({f: getattr(s, f) for f, _ in tmask_score_out._fields_})
+    return res
+
+
+def index_bits(M: int) -> int:
+    return (M - 1).bit_length()
+
+
+def packed_shapes(rows: int, cols: int, N: int, M: int):
+    ib = index_bits(M)
+    sw, st = cols // M * N, rows // M * N
+    return (rows, sw), (rows, (sw * ib + 7) // 8), (cols, st), (cols, (st * ib + 7) // 8)
+
+
+def alloc_packed(w: torch.Tensor, N: int, M: int):
+    vs, is_, vts, its = packed_shapes(w.shape[0], w.shape[1], N, M)
+    return (torch.empty(vs, dtype=w.dtype, device=w.device), torch.empty(is_, dtype=torch.uint8, device=w.device),
+            torch.empty(vts, dtype=w.dtype, device=w.device), torch.empty(its, dtype=torch.uint8, device=w.device))
+
+
+def tmask_apply_pack(ws, masks, packed, N: int, M: int, mask_fmt: int = TMASK_MASK_U8,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """packed[k] = (vals, idx, valsT, idxT) tensors for matrix k (see alloc_packed), written in place."""
+    ws = list(ws)
+    n = len(ws)
+    arr = (tmask_pack_desc * n)()
+    for k, (w, m, pk) in enumerate(zip(ws, masks, packed)):
+        p, r, c, ld = _mat2d(w, "w")
+        mp, _, _, mld = _mat2d(m, "mask")
+        vs, is_, vts, its = packed_shapes(r, c, N, M)
+        vals, idx, valsT, idxT = pk
+        for t, shp, dty in ((vals, vs, w.dtype), (idx, is_, torch.uint8), (valsT, vts, w.dtype), (idxT, its, torch.uint8)):
+            if tuple(t.shape) != shp or t.dtype != dty or not t.is_contiguous() or not t.is_cuda:
+                raise ValueError("packed output has the wrong shape/dtype: %s vs %s" % (tuple(t.shape), shp))
+        arr[k] = tmask_pack_desc(p, r, c, ld, mp, mld, vals.data_ptr(), idx.data_ptr(), valsT.data_ptr(),
+                                 idxT.data_ptr())
+    wp, wb = _ws_args(workspace)
+    _check(load_library().tmask_apply_pack(arr, n, dtype_code(ws[0]), N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
+
+
+def tmask_version() -> int:
+    return int(load_library().tmask_version())

@@ -1,0 +1,548 @@
+// tmask: streaming kernels (approx / exact / score) and the C ABI.  gfx950 only.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "../../include/tmask.h"
+#include "tmask_device.hpp"
+#include "tmask_solvers.hpp"
+
+namespace tmask {
+
+// =================================================================================================
+// Kernels
+// =================================================================================================
+
+enum { kSolveApprox = 0, kSolveExact = 1 };
+
+// One workgroup = 256 consecutive strips of one matrix: load M rows x 16 B per lane, solve the
+// block(s) in registers, write the mask, leave one partial objective per workgroup.
+template <int SOLVER, int DT, int M, int FMT>
+__global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
+{
+    using Ge = Geo<DT, M>;
+    __shared__ double red[kThreads / 64];
+    const uint32_t tile = blockIdx.x;
+    const MatDev md = args.m[find_matrix(args, tile)];
+    const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
+    const uint32_t gpos = threadIdx.x & (Ge::G - 1);
+    double acc = 0.0;
+    if (s < md.n_strips) {
+        const StripPos pos = strip_pos(md, s);
+        uint32_t a[M][Ge::C];
+        u32x4 raw[M];
+        uint32_t bits[M];
+        load_strip<DT, M>(md, pos, a, raw);
+        if constexpr (SOLVER == kSolveApprox) {
+            approx_keep<DT, M>(a, args.K, gpos, bits);
+        } else if constexpr (M == 4) {
+            if (args.K == 2) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    bits[i] = 0;
+#pragma unroll
+                for (int b = 0; b < Ge::B; b++) {
+                    float v[4][4];
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+#pragma unroll
+                        for (int c = 0; c < 4; c++)
+                            v[i][c] = __uint_as_float(a[i][b * 4 + c]);
+                    const uint32_t m16 = exact24_block(v);
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+                        bits[i] |= ((m16 >> (4 * i)) & 0xFu) << (4 * b);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    bits[i] = 0;
+#pragma unroll
+                for (int b = 0; b < Ge::B; b++) {
+                    uint32_t key[4][4], xcol[4];
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+#pragma unroll
+                        for (int c = 0; c < 4; c++)
+                            key[i][c] = a[i][b * 4 + c];
+                    exact_general<4, 4, 1>(key, args.K, 0u, xcol);
+#pragma unroll
+                    for (int i = 0; i < 4; i++)
+#pragma unroll
+                        for (int c = 0; c < 4; c++)
+                            bits[i] |= (((xcol[c] >> i) & 1u) ^ 1u) << (4 * b + c);
+                }
+            }
+        } else {
+            uint32_t xcol[Ge::C];
+            exact_general<M, Ge::C, Ge::G>(a, args.K, gpos, xcol);
+#pragma unroll
+            for (int i = 0; i < M; i++) {
+                bits[i] = 0;
+#pragma unroll
+                for (int c = 0; c < Ge::C; c++)
+                    bits[i] |= (((xcol[c] >> i) & 1u) ^ 1u) << c;
+            }
+        }
+        store_mask<DT, M, FMT>(md, pos, bits);
+        acc = (double)kept_sum<M, Ge::C>(a, bits);
+    }
+    if (args.partials) {
+        const double t = block_sum(acc, red);
+        if (threadIdx.x == 0)
+            ((double *)args.partials)[args.partial0 + tile] = t;
+    }
+}
+
+struct ReduceArgs {
+    double *objective[kMaxBatch];
+    uint32_t tile0[kMaxBatch + 1];
+    uint32_t n_mats;
+    uint32_t partial0;
+    const double *partials;
+};
+
+// Second stage of the objective: workgroup m adds the partials of matrix m in a fixed order.
+__global__ __launch_bounds__(kThreads) void objective_reduce_kernel(const ReduceArgs args)
+{
+    __shared__ double red[kThreads / 64];
+    const uint32_t m = blockIdx.x;
+    double *dst = args.objective[m];
+    if (!dst)
+        return;
+    double acc = 0.0;
+    for (uint32_t t = args.tile0[m] + threadIdx.x; t < args.tile0[m + 1]; t += kThreads)
+        acc += args.partials[args.partial0 + t];
+    const double total = block_sum(acc, red);
+    if (threadIdx.x == 0)
+        dst[0] = total;
+}
+
+struct ScorePartial {
+    double retained, total;
+    unsigned long long kept, rowv, colv, rowne, colne;
+};
+
+template <int DT, int M, int FMT>
+__global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
+{
+    using Ge = Geo<DT, M>;
+    constexpr int C = Ge::C, CL = Ge::CL;
+    __shared__ double redd[kThreads / 64];
+    __shared__ unsigned long long redu[kThreads / 64];
+    const uint32_t tile = blockIdx.x;
+    const MatDev md = args.m[find_matrix(args, tile)];
+    const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
+    const uint32_t gpos = threadIdx.x & (Ge::G - 1);
+    const uint32_t N = args.N;
+    double retained = 0.0, total = 0.0;
+    unsigned long long kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
+    if (s < md.n_strips) {
+        const StripPos pos = strip_pos(md, s);
+        uint32_t a[M][C];
+        u32x4 raw[M];
+        uint32_t bits[M];
+        load_strip<DT, M>(md, pos, a, raw);
+        load_mask<DT, M, FMT>(md, pos, bits);
+        float tot = 0.f;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                tot += __uint_as_float(a[i][c]);
+        total = (double)tot;
+        // columns: lane-local
+#pragma unroll
+        for (int c = 0; c < C; c++) {
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                cnt += (bits[i] >> c) & 1u;
+            kept += cnt;
+            colv += cnt > N ? 1u : 0u;
+            colne += cnt != N ? 1u : 0u;
+        }
+        // rows: per block inside the lane, summed over the G lanes of the block, counted once
+#pragma unroll
+        for (int b = 0; b < Ge::B; b++) {
+            float blk = 0.f;
+#pragma unroll
+            for (int i = 0; i < M; i++) {
+                uint32_t cnt = __builtin_popcount((bits[i] >> (b * CL)) & ((1u << CL) - 1u));
+                if constexpr (Ge::G >= 2)
+                    cnt += quad_xor<1>(cnt);
+                if constexpr (Ge::G == 4)
+                    cnt += quad_xor<2>(cnt);
+                if (gpos == 0) {
+                    rowv += cnt > N ? 1u : 0u;
+                    rowne += cnt != N ? 1u : 0u;
+                }
+#pragma unroll
+                for (int c = 0; c < CL; c++)
+                    blk += ((bits[i] >> (b * CL + c)) & 1u) ? __uint_as_float(a[i][b * CL + c]) : 0.f;
+            }
+            retained += (double)blk;
+            if constexpr (Ge::G >= 2)
+                blk += __uint_as_float(quad_xor<1>(__float_as_uint(blk)));
+            if constexpr (Ge::G == 4)
+                blk += __uint_as_float(quad_xor<2>(__float_as_uint(blk)));
+            if (md.aux && gpos == 0) {
+                // block index inside the matrix: block-row-major
+                const uint32_t bpr = md.spr * Ge::B / Ge::G;
+                const uint32_t bc = pos.sc * Ge::B / Ge::G + b;
+                ((float *)md.aux)[(size_t)pos.br * bpr + bc] = blk;
+            }
+        }
+    }
+    ScorePartial *out = (ScorePartial *)args.partials + args.partial0 + tile;
+    const double r0 = block_sum(retained, redd);
+    const double r1 = block_sum(total, redd);
+    const unsigned long long u0 = block_sum(kept, redu);
+    const unsigned long long u1 = block_sum(rowv, redu);
+    const unsigned long long u2 = block_sum(colv, redu);
+    const unsigned long long u3 = block_sum(rowne, redu);
+    const unsigned long long u4 = block_sum(colne, redu);
+    if (threadIdx.x == 0) {
+        out->retained = r0; out->total = r1;
+        out->kept = u0; out->rowv = u1; out->colv = u2; out->rowne = u3; out->colne = u4;
+    }
+}
+
+struct ScoreReduceArgs {
+    uint32_t tile0[kMaxBatch + 1];
+    uint32_t n_mats;
+    uint32_t partial0;
+    const ScorePartial *partials;
+    tmask_score_out *out;   // entry of the first matrix of this launch
+};
+
+__global__ __launch_bounds__(kThreads) void score_reduce_kernel(const ScoreReduceArgs args)
+{
+    __shared__ double redd[kThreads / 64];
+    __shared__ unsigned long long redu[kThreads / 64];
+    const uint32_t m = blockIdx.x;
+    double retained = 0.0, total = 0.0;
+    unsigned long long kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
+    for (uint32_t t = args.tile0[m] + threadIdx.x; t < args.tile0[m + 1]; t += kThreads) {
+        const ScorePartial p = args.partials[args.partial0 + t];
+        retained += p.retained; total += p.total;
+        kept += p.kept; rowv += p.rowv; colv += p.colv; rowne += p.rowne; colne += p.colne;
+    }
+    const double r0 = block_sum(retained, redd);
+    const double r1 = block_sum(total, redd);
+    const unsigned long long u0 = block_sum(kept, redu);
+    const unsigned long long u1 = block_sum(rowv, redu);
+    const unsigned long long u2 = block_sum(colv, redu);
+    const unsigned long long u3 = block_sum(rowne, redu);
+    const unsigned long long u4 = block_sum(colne, redu);
+    if (threadIdx.x == 0) {
+        tmask_score_out *o = args.out + m;
+        o->retained_l1 = r0; o->total_l1 = r1;
+        o->kept = u0; o->row_violations = u1; o->col_violations = u2; o->row_not_n = u3; o->col_not_n = u4;
+    }
+}
+
+// =================================================================================================
+// Host side
+// =================================================================================================
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static bool valid_nm(int N, int M) { return (M == 4 || M == 8 || M == 16) && N > 0 && N < M; }
+
+static size_t elem_size(int dt) { return dt == TMASK_F32 ? 4 : 2; }
+
+// s / d == (uint64(s) * mul) >> shift for every s < 2^31 (d >= 1).
+static void magic_div(uint32_t d, uint32_t *mul, uint32_t *shift)
+{
+    uint32_t l = 0;
+    while ((1ull << l) < d)
+        l++;
+    const uint32_t k = 31 + l;
+    *mul = (uint32_t)(((1ull << k) / d) + 1);
+    *shift = k;
+}
+
+struct HostMat {
+    const void *w; int64_t rows, cols, ld;
+    void *mask; int64_t mask_ld;
+    double *objective;
+};
+
+// Validates one matrix for (dt, N, M, mf). what: text for error messages.
+static int check_mat(const HostMat &h, int idx, int dt, int M, int mf, bool need_mask)
+{
+    const size_t es = elem_size(dt);
+    const int64_t C = 16 / (int64_t)es;
+    if (!h.w || (need_mask && !h.mask))
+        return fail(TMASK_ERR_NULL, "matrix %d: w or mask is NULL", idx);
+    if (h.rows <= 0 || h.cols <= 0 || h.rows % M || h.cols % M || h.ld < h.cols)
+        return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld ld=%lld must be positive multiples of M=%d with ld >= cols",
+                    idx, (long long)h.rows, (long long)h.cols, (long long)h.ld, M);
+    if (h.ld > 0x7FFFFFFFll || h.mask_ld > 0x7FFFFFFFll || (h.rows / M) * (h.cols / C) >= 0x7FFFFFFFll)
+        return fail(TMASK_ERR_SHAPE, "matrix %d: too large (ld, mask_ld and strip count must stay below 2^31)", idx);
+    if (((uintptr_t)h.w & 15) || (h.ld * es) % 16 || (h.cols * es) % 16)
+        return fail(TMASK_ERR_ALIGN, "matrix %d: w must be 16-byte aligned and ld, cols multiples of %lld elements", idx,
+                    (long long)C);
+    if (need_mask) {
+        if (mf == TMASK_MASK_U8) {
+            if (h.mask_ld < h.cols)
+                return fail(TMASK_ERR_SHAPE, "matrix %d: mask_ld=%lld < cols", idx, (long long)h.mask_ld);
+            if (((uintptr_t)h.mask % C) || (h.mask_ld % C))
+                return fail(TMASK_ERR_ALIGN, "matrix %d: U8 mask and mask_ld must be multiples of %lld bytes", idx,
+                            (long long)C);
+        } else {
+            if (h.cols % 8)
+                return fail(TMASK_ERR_SHAPE, "matrix %d: BITS masks need cols to be a multiple of 8", idx);
+            if (h.mask_ld < h.cols / 8)
+                return fail(TMASK_ERR_SHAPE, "matrix %d: mask_ld=%lld < cols/8", idx, (long long)h.mask_ld);
+        }
+    }
+    return TMASK_OK;
+}
+
+static uint32_t strips_of(const HostMat &h, int dt, int M)
+{
+    const int64_t C = 16 / (int64_t)elem_size(dt);
+    return (uint32_t)((h.rows / M) * (h.cols / C));
+}
+
+static uint32_t tiles_of(uint32_t n_strips) { return (n_strips + kThreads - 1) / kThreads; }
+
+static void fill_desc(MatDev &d, const HostMat &h, int dt, int M, uint32_t tile0)
+{
+    const int64_t C = 16 / (int64_t)elem_size(dt);
+    d.w = h.w; d.mask = h.mask; d.aux = nullptr;
+    d.ld = (uint32_t)h.ld; d.mask_ld = (uint32_t)h.mask_ld;
+    d.spr = (uint32_t)(h.cols / C);
+    d.n_strips = strips_of(h, dt, M);
+    magic_div(d.spr, &d.div_mul, &d.div_shift);
+    d.tile0 = tile0; d.pad = 0;
+}
+
+typedef void (*batch_kernel_t)(const BatchArgs);
+
+template <int SOLVER>
+static batch_kernel_t pick_mask_kernel(int dt, int M, int mf)
+{
+#define TMASK_PICK(DT, MM, FM) \
+    if (dt == DT && M == MM && mf == FM) return mask_kernel<SOLVER, DT, MM, FM>;
+    TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
+    TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
+    TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
+    TMASK_PICK(kBF16, 4, kMaskBits) TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+#undef TMASK_PICK
+    return nullptr;
+}
+
+static batch_kernel_t pick_score_kernel(int dt, int M, int mf)
+{
+#define TMASK_PICK(DT, MM, FM) \
+    if (dt == DT && M == MM && mf == FM) return score_kernel<DT, MM, FM>;
+    TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
+    TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
+    TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
+    TMASK_PICK(kBF16, 4, kMaskBits) TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+#undef TMASK_PICK
+    return nullptr;
+}
+
+static int check_common(const void *mats, int n_mats, int dt, int N, int M, int mf)
+{
+    if (!mats)
+        return fail(TMASK_ERR_NULL, "descriptor array is NULL");
+    if (n_mats <= 0)
+        return fail(TMASK_ERR_SHAPE, "n_mats=%d must be positive", n_mats);
+    if (dt != TMASK_F32 && dt != TMASK_BF16)
+        return fail(TMASK_ERR_DTYPE, "unknown dtype %d", dt);
+    if (mf != TMASK_MASK_U8 && mf != TMASK_MASK_BITS)
+        return fail(TMASK_ERR_DTYPE, "unknown mask format %d", mf);
+    if (!valid_nm(N, M))
+        return fail(TMASK_ERR_NM, "unsupported N:M = %d:%d (need M in {4,8,16}, 0 < N < M)", N, M);
+    return TMASK_OK;
+}
+
+static size_t workspace_need(const tmask_mat *mats, int n_mats, int M)
+{
+    // Upper bound over dtypes: fp32 strips (4 columns) are the narrower ones.
+    size_t tiles = 0;
+    for (int i = 0; i < n_mats; i++) {
+        if (mats[i].rows <= 0 || mats[i].cols <= 0)
+            return 0;
+        const size_t strips = (size_t)((mats[i].rows + M - 1) / M) * (size_t)((mats[i].cols + 3) / 4);
+        tiles += (strips + kThreads - 1) / kThreads;
+    }
+    return tiles * sizeof(ScorePartial) + 256;
+}
+
+static int check_workspace(const tmask_mat *mats, int n_mats, int M, void *ws, size_t ws_bytes)
+{
+    if (!ws || ((uintptr_t)ws & 255))
+        return fail(TMASK_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+    const size_t need = workspace_need(mats, n_mats, M);
+    if (ws_bytes < need)
+        return fail(TMASK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+    return TMASK_OK;
+}
+
+static int hip_fail(hipError_t e, const char *what)
+{
+    return fail(TMASK_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+template <int SOLVER>
+static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, void *ws, size_t ws_bytes,
+                    void *stream_)
+{
+    int rc = check_common(mats, n_mats, dt, N, M, mf);
+    if (rc)
+        return rc;
+    bool want_obj = false;
+    for (int i = 0; i < n_mats; i++) {
+        const HostMat h{mats[i].w, mats[i].rows, mats[i].cols, mats[i].ld, mats[i].mask, mats[i].mask_ld,
+                        mats[i].objective};
+        if ((rc = check_mat(h, i, dt, M, mf, true)))
+            return rc;
+        want_obj = want_obj || mats[i].objective;
+    }
+    if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes)))
+        return rc;
+    const batch_kernel_t kern = pick_mask_kernel<SOLVER>(dt, M, mf);
+    hipStream_t stream = (hipStream_t)stream_;
+    uint32_t partial0 = 0;
+    for (int first = 0; first < n_mats; first += kMaxBatch) {
+        const int nb = n_mats - first < kMaxBatch ? n_mats - first : kMaxBatch;
+        BatchArgs args;
+        ReduceArgs rargs;
+        memset(&args, 0, sizeof args);
+        memset(&rargs, 0, sizeof rargs);
+        uint32_t tiles = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_mat &t = mats[first + k];
+            const HostMat h{t.w, t.rows, t.cols, t.ld, t.mask, t.mask_ld, t.objective};
+            fill_desc(args.m[k], h, dt, M, tiles);
+            rargs.objective[k] = t.objective;
+            rargs.tile0[k] = tiles;
+            tiles += tiles_of(args.m[k].n_strips);
+        }
+        rargs.tile0[nb] = tiles;
+        args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
+        args.partial0 = partial0; args.partials = want_obj ? ws : nullptr;
+        hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "mask kernel launch");
+        if (want_obj) {
+            rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)ws;
+            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
+            e = hipGetLastError();
+            if (e != hipSuccess)
+                return hip_fail(e, "objective reduce launch");
+        }
+        partial0 += tiles;
+    }
+    return TMASK_OK;
+}
+
+}  // namespace tmask
+
+using namespace tmask;
+
+extern "C" {
+
+int tmask_approx(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf, void *workspace,
+                 size_t workspace_bytes, void *hip_stream)
+{
+    return run_mask<kSolveApprox>(mats, n_mats, (int)dt, N, M, (int)mf, workspace, workspace_bytes, hip_stream);
+}
+
+int tmask_exact(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf, void *workspace,
+                size_t workspace_bytes, void *hip_stream)
+{
+    return run_mask<kSolveExact>(mats, n_mats, (int)dt, N, M, (int)mf, workspace, workspace_bytes, hip_stream);
+}
+
+int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                tmask_score_out *out, float *per_block_obj, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_common(mats, n_mats, (int)dt, N, M, (int)mf);
+    if (rc)
+        return rc;
+    if (!out)
+        return fail(TMASK_ERR_NULL, "out is NULL");
+    for (int i = 0; i < n_mats; i++) {
+        const HostMat h{mats[i].w, mats[i].rows, mats[i].cols, mats[i].ld, mats[i].mask, mats[i].mask_ld, nullptr};
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, true)))
+            return rc;
+    }
+    if ((rc = check_workspace(mats, n_mats, M, workspace, workspace_bytes)))
+        return rc;
+    const batch_kernel_t kern = pick_score_kernel((int)dt, M, (int)mf);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint32_t partial0 = 0;
+    size_t block0 = 0;
+    for (int first = 0; first < n_mats; first += kMaxBatch) {
+        const int nb = n_mats - first < kMaxBatch ? n_mats - first : kMaxBatch;
+        BatchArgs args;
+        ScoreReduceArgs rargs;
+        memset(&args, 0, sizeof args);
+        memset(&rargs, 0, sizeof rargs);
+        uint32_t tiles = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_mat &t = mats[first + k];
+            const HostMat h{t.w, t.rows, t.cols, t.ld, t.mask, t.mask_ld, nullptr};
+            fill_desc(args.m[k], h, (int)dt, M, tiles);
+            args.m[k].aux = per_block_obj ? (void *)(per_block_obj + block0) : nullptr;
+            block0 += (size_t)(t.rows / M) * (size_t)(t.cols / M);
+            rargs.tile0[k] = tiles;
+            tiles += tiles_of(args.m[k].n_strips);
+        }
+        rargs.tile0[nb] = tiles;
+        args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
+        args.partial0 = partial0; args.partials = workspace;
+        hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "score kernel launch");
+        rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0;
+        rargs.partials = (const ScorePartial *)workspace; rargs.out = out + first;
+        hipLaunchKernelGGL(score_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
+        e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "score reduce launch");
+        partial0 += tiles;
+    }
+    return TMASK_OK;
+}
+
+int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                     void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)descs; (void)n; (void)dt; (void)N; (void)M; (void)mf; (void)workspace; (void)workspace_bytes; (void)hip_stream;
+    return fail(TMASK_ERR_HIP, "tmask_apply_pack: not built yet");
+}
+
+size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M)
+{
+    if (!mats || n_mats <= 0 || !valid_nm(N, M))
+        return 0;
+    return workspace_need(mats, n_mats, M);
+}
+
+const char *tmask_last_error(void) { return g_err; }
+
+int tmask_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,381 @@
+// Per-block solvers working on the strip layout (see tmask_device.hpp).
+//   approx_keep   : Algorithm 1 of arXiv 2102.08124 (Sec. 4) in rank form
+//   exact24_block : Eq. 1 optimum for 2:4 by enumeration of the 90 feasible patterns
+//   exact_general : Eq. 1 optimum for any (N, M) by successive shortest augmenting paths on the
+//                   bipartite row/column network of Fig. 3
+#pragma once
+#include "tmask_device.hpp"
+
+namespace tmask {
+
+// =================================================================================================
+// Algorithm 1 in rank form.
+//
+// Under the strict total order (magnitude key, then row-major index) the greedy sweep of
+// Algorithm 1 -- take an entry while its row or its column has fewer than K taken entries --
+// ends with exactly the entries that are among the K lightest of their row or of their column:
+// the n-th lightest entry of a line (n <= K) meets fewer than K taken entries in that line when it
+// is visited, and an entry outside the K lightest of both its lines finds both saturated.
+// So  keep(i,j) <=> rank_in_row(i,j) >= K  and  rank_in_column(i,j) >= K,
+// where rank = number of entries of the line that precede (i,j) in the order.  Because positions
+// are static, "precedes" is `<=` against earlier positions and `<` against later ones.
+// =================================================================================================
+
+// Column direction: all M rows of a column live in the lane.
+template <int M, int C>
+__device__ __forceinline__ void col_rank_keep(const uint32_t (&a)[M][C], uint32_t K, uint32_t (&bits)[M])
+{
+#pragma unroll
+    for (int i = 0; i < M; i++)
+        bits[i] = 0;
+#pragma unroll
+    for (int c = 0; c < C; c++) {
+        uint32_t r[M];
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            r[i] = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+#pragma unroll
+            for (int i2 = i + 1; i2 < M; i2++) {
+                const uint32_t le = a[i][c] <= a[i2][c] ? 1u : 0u;   // row i precedes row i2
+                r[i2] += le;
+                r[i] += 1u - le;
+            }
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            bits[i] |= (r[i] >= K ? 1u : 0u) << c;
+    }
+}
+
+// Row direction: a block-row is spread over G lanes (CL columns each); B blocks share a lane.
+// gpos = position of the lane inside its group of G.  bits[i] &= row-keep.
+template <int M, int C, int G, int B>
+__device__ __forceinline__ void row_rank_keep(const uint32_t (&a)[M][C], uint32_t K, uint32_t gpos,
+                                              uint32_t (&bits)[M])
+{
+    constexpr int CL = C / B;
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        uint32_t keep = 0;
+#pragma unroll
+        for (int b = 0; b < B; b++) {
+            uint32_t r[CL];
+#pragma unroll
+            for (int c = 0; c < CL; c++)
+                r[c] = 0;
+#pragma unroll
+            for (int c = 0; c < CL; c++)
+#pragma unroll
+                for (int c2 = c + 1; c2 < CL; c2++) {
+                    const uint32_t le = a[i][b * CL + c] <= a[i][b * CL + c2] ? 1u : 0u;
+                    r[c2] += le;
+                    r[c] += 1u - le;
+                }
+            if constexpr (G >= 2) {
+                // keys are < 2^31, so "theirs <= mine" is "theirs < mine + 1"
+                const uint32_t pb1 = ((gpos ^ 1u) < gpos) ? 1u : 0u;
+#pragma unroll
+                for (int c2 = 0; c2 < CL; c2++) {
+                    const uint32_t t = quad_xor<1>(a[i][c2]);
+#pragma unroll
+                    for (int c = 0; c < CL; c++)
+                        r[c] += (t < a[i][c] + pb1) ? 1u : 0u;
+                }
+            }
+            if constexpr (G == 4) {
+                const uint32_t pb2 = ((gpos ^ 2u) < gpos) ? 1u : 0u;
+                const uint32_t pb3 = ((gpos ^ 3u) < gpos) ? 1u : 0u;
+#pragma unroll
+                for (int c2 = 0; c2 < CL; c2++) {
+                    const uint32_t t2 = quad_xor<2>(a[i][c2]);
+                    const uint32_t t3 = quad_xor<3>(a[i][c2]);
+#pragma unroll
+                    for (int c = 0; c < CL; c++) {
+                        r[c] += (t2 < a[i][c] + pb2) ? 1u : 0u;
+                        r[c] += (t3 < a[i][c] + pb3) ? 1u : 0u;
+                    }
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < CL; c++)
+                keep |= (r[c] >= K ? 1u : 0u) << (b * CL + c);
+        }
+        bits[i] &= keep;
+    }
+}
+
+template <int DT, int M>
+__device__ __forceinline__ void approx_keep(const uint32_t (&a)[M][Geo<DT, M>::C], uint32_t K, uint32_t gpos,
+                                            uint32_t (&bits)[M])
+{
+    using Ge = Geo<DT, M>;
+    col_rank_keep<M, Ge::C>(a, K, bits);
+    row_rank_keep<M, Ge::C, Ge::G, Ge::B>(a, K, gpos, bits);
+}
+
+// =================================================================================================
+// Exact 2:4: all 0/1 4x4 matrices with two ones in every row and column (there are 90), fp32 sums.
+// A row pattern is a pair of columns; pairs are numbered 0..5 = {01,02,03,12,13,23}.
+// =================================================================================================
+
+struct Patterns24 {
+    uint8_t p[90][4];
+    int n;
+};
+
+constexpr int kPairX[6] = {0, 0, 0, 1, 1, 2};
+constexpr int kPairY[6] = {1, 2, 3, 2, 3, 3};
+
+constexpr uint32_t pair_bits(int p) { return (1u << kPairX[p]) | (1u << kPairY[p]); }
+
+constexpr Patterns24 make_patterns24()
+{
+    Patterns24 t{};
+    t.n = 0;
+    for (int p0 = 0; p0 < 6; p0++)
+        for (int p1 = 0; p1 < 6; p1++)
+            for (int p2 = 0; p2 < 6; p2++)
+                for (int p3 = 0; p3 < 6; p3++) {
+                    bool ok = true;
+                    for (int c = 0; c < 4; c++) {
+                        int s = ((pair_bits(p0) >> c) & 1) + ((pair_bits(p1) >> c) & 1) +
+                                ((pair_bits(p2) >> c) & 1) + ((pair_bits(p3) >> c) & 1);
+                        ok = ok && (s == 2);
+                    }
+                    if (ok) {
+                        t.p[t.n][0] = (uint8_t)p0; t.p[t.n][1] = (uint8_t)p1;
+                        t.p[t.n][2] = (uint8_t)p2; t.p[t.n][3] = (uint8_t)p3;
+                        t.n++;
+                    }
+                }
+    return t;
+}
+
+constexpr Patterns24 kPatterns24 = make_patterns24();
+static_assert(kPatterns24.n == 90, "a 4x4 block has 90 feasible 2:4 transposable patterns");
+
+constexpr uint32_t pattern_mask16(int k)
+{
+    return pair_bits(kPatterns24.p[k][0]) | (pair_bits(kPatterns24.p[k][1]) << 4) |
+           (pair_bits(kPatterns24.p[k][2]) << 8) | (pair_bits(kPatterns24.p[k][3]) << 12);
+}
+
+// v[r][c] = |W| of one 4x4 block. Returns the 16-bit keep mask (row r in bits 4r..4r+3) of the
+// first pattern, in enumeration order, that attains the maximum kept sum.
+__device__ __forceinline__ uint32_t exact24_block(const float (&v)[4][4])
+{
+    float ps[4][6];
+#pragma unroll
+    for (int r = 0; r < 4; r++)
+#pragma unroll
+        for (int p = 0; p < 6; p++)
+            ps[r][p] = v[r][kPairX[p]] + v[r][kPairY[p]];
+    float best = 0.f;
+    uint32_t bm = 0;
+#pragma unroll
+    for (int k = 0; k < 90; k++) {
+        const float s = (ps[0][kPatterns24.p[k][0]] + ps[1][kPatterns24.p[k][1]]) +
+                        (ps[2][kPatterns24.p[k][2]] + ps[3][kPatterns24.p[k][3]]);
+        if (k == 0) {
+            best = s;
+            bm = pattern_mask16(0);
+        } else {
+            const bool better = s > best;        // false for NaN: the mask stays a feasible pattern
+            best = better ? s : best;
+            bm = better ? pattern_mask16(k) : bm;
+        }
+    }
+    return bm;
+}
+
+// =================================================================================================
+// Exact, general (N, M): min-cost flow on the network of Fig. 3 (source -> rows, rows -> columns
+// with unit capacity and cost |W_ij|, columns -> sink), solved by successive shortest paths.
+//
+// Costs are integers: c_ij = |W_ij| scaled by a power of two so that the block maximum lies in
+// [2^(S-1), 2^S) and truncated.  Integer arithmetic makes every path sum exact, so the residual
+// network never shows a negative cycle, label-correcting search converges, and the predecessor
+// graph is a forest; truncation costs less than M*K*2^-(S-1) of the block maximum in retained L1
+// (S = 27 for M <= 8, 26 for M = 16).
+//
+// Start: every column prunes its K lightest rows -- a flow that saturates the column->sink edges and
+// is cheapest among all flows with the same row imbalances.  Then, while some row has more than K
+// pruned entries, find the cheapest alternating path from any such row to a row with fewer than K
+// (row r -> column j through a pruned entry (r,j), column j -> row r' through an unpruned entry
+// (r',j)) with a label-correcting search over row labels, and flip the entries along it.
+//
+// One block is held by G lanes, CL columns each; row labels are replicated in the G lanes and
+// min-combined after each sweep, so all G lanes take the same decisions.
+// =================================================================================================
+
+constexpr int kInfDist = 0x70000000;   // unreachable label; kInfDist - 2^S is still above kReachable
+constexpr int kReachable = 0x40000000; // every real label is below this: |label| <= (M-1) * 2^S < 2^30
+constexpr uint32_t kNoPred = 0xFFFFFFFFu;
+
+template <int M, int CL, int G>
+__device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint32_t K, uint32_t gpos,
+                                              uint32_t (&xcol)[CL])
+{
+    constexpr int S = (M == 16) ? 26 : 27;
+    static_assert((M - 1) * (1ll << S) < kReachable, "labels must stay below the reachability threshold");
+
+    // ---- integer costs ----
+    uint32_t kmax = 0;
+#pragma unroll
+    for (int i = 0; i < M; i++)
+#pragma unroll
+        for (int c = 0; c < CL; c++)
+            kmax = key[i][c] > kmax ? key[i][c] : kmax;
+    if constexpr (G >= 2) {
+        const uint32_t o = quad_xor<1>(kmax);
+        kmax = o > kmax ? o : kmax;
+    }
+    if constexpr (G == 4) {
+        const uint32_t o = quad_xor<2>(kmax);
+        kmax = o > kmax ? o : kmax;
+    }
+    const uint32_t emax = (kmax >> 23) ? (kmax >> 23) : 1u;
+    int cost[M][CL];
+#pragma unroll
+    for (int i = 0; i < M; i++)
+#pragma unroll
+        for (int c = 0; c < CL; c++) {
+            const uint32_t e = key[i][c] >> 23;
+            const uint32_t mant = (key[i][c] & 0x7FFFFFu) | (e ? 0x800000u : 0u);
+            const uint32_t sh = emax - (e ? e : 1u);
+            cost[i][c] = sh < 32u ? (int)((mant << (S - 24)) >> sh) : 0;
+        }
+
+    // ---- start: K lightest rows of every column ----
+#pragma unroll
+    for (int c = 0; c < CL; c++) {
+        uint32_t r[M];
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            r[i] = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+#pragma unroll
+            for (int i2 = i + 1; i2 < M; i2++) {
+                const uint32_t le = cost[i][c] <= cost[i2][c] ? 1u : 0u;
+                r[i2] += le;
+                r[i] += 1u - le;
+            }
+        uint32_t x = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            x |= (r[i] < K ? 1u : 0u) << i;
+        xcol[c] = x;
+    }
+
+    // ---- augment until every row has exactly K pruned ----
+    for (int phase = 0; phase < M * M; phase++) {
+        int drow[M];
+        uint32_t prow[M];
+        uint32_t n_excess = 0;
+        uint32_t deficit = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int c = 0; c < CL; c++)
+                cnt += (xcol[c] >> i) & 1u;
+            if constexpr (G >= 2)
+                cnt += quad_xor<1>(cnt);
+            if constexpr (G == 4)
+                cnt += quad_xor<2>(cnt);
+            const bool ex = cnt > K;
+            n_excess += ex ? 1u : 0u;
+            deficit |= (cnt < K ? 1u : 0u) << i;
+            drow[i] = ex ? 0 : kInfDist;
+            prow[i] = kNoPred;
+        }
+        if (n_excess == 0)
+            break;
+
+        // label-correcting sweeps over the columns
+        uint32_t changed;
+        int sweeps = 0;
+        do {
+            changed = 0;
+#pragma unroll
+            for (int c = 0; c < CL; c++) {
+                int dcol = kInfDist;
+                uint32_t from = 0;
+#pragma unroll
+                for (int i = 0; i < M; i++) {
+                    const int t = drow[i] - cost[i][c];
+                    const bool better = ((xcol[c] >> i) & 1u) && (t < dcol);
+                    dcol = better ? t : dcol;
+                    from = better ? (uint32_t)i : from;
+                }
+                const bool ok = dcol < kReachable;
+                const uint32_t code = ((gpos * CL + c) << 4) | from;
+#pragma unroll
+                for (int i = 0; i < M; i++) {
+                    const int t = dcol + cost[i][c];
+                    const bool better = ok && !((xcol[c] >> i) & 1u) && (t < drow[i]);
+                    drow[i] = better ? t : drow[i];
+                    prow[i] = better ? code : prow[i];
+                    changed |= better ? 1u : 0u;
+                }
+            }
+            if constexpr (G >= 2) {
+                const bool before = (gpos ^ 1u) < gpos;
+#pragma unroll
+                for (int i = 0; i < M; i++) {
+                    const int od = (int)quad_xor<1>((uint32_t)drow[i]);
+                    const uint32_t op = quad_xor<1>(prow[i]);
+                    const bool take = (od < drow[i]) || (od == drow[i] && before);
+                    drow[i] = take ? od : drow[i];
+                    prow[i] = take ? op : prow[i];
+                }
+                changed |= quad_xor<1>(changed);
+            }
+            if constexpr (G == 4) {
+                const bool before = (gpos ^ 2u) < gpos;
+#pragma unroll
+                for (int i = 0; i < M; i++) {
+                    const int od = (int)quad_xor<2>((uint32_t)drow[i]);
+                    const uint32_t op = quad_xor<2>(prow[i]);
+                    const bool take = (od < drow[i]) || (od == drow[i] && before);
+                    drow[i] = take ? od : drow[i];
+                    prow[i] = take ? op : prow[i];
+                }
+                changed |= quad_xor<2>(changed);
+            }
+            sweeps++;
+        } while (changed && sweeps <= M);
+
+        // cheapest reachable row that still lacks pruned entries
+        int best = kInfDist;
+        uint32_t r = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            const bool better = ((deficit >> i) & 1u) && (drow[i] < best);
+            best = better ? drow[i] : best;
+            r = better ? (uint32_t)i : r;
+        }
+        if (best >= kReachable)
+            break;   // cannot happen for 0 < K < M; guards against looping on corrupt state
+
+        // flip the entries along the predecessor chain back to a row with excess
+        for (int step = 0; step < M; step++) {
+            uint32_t p = kNoPred;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                p = (r == (uint32_t)i) ? prow[i] : p;
+            if (p == kNoPred)
+                break;
+            const uint32_t j = p >> 4, f = p & 15u;
+#pragma unroll
+            for (int c = 0; c < CL; c++)
+                if (j == gpos * CL + c)
+                    xcol[c] ^= (1u << r) | (1u << f);
+            r = f;
+        }
+    }
+}
+
+}  // namespace tmask

@@ -1,0 +1,71 @@
+"""Helpers for the GPU parity tests: host <-> device marshalling around the C-ABI binding."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2102_08124_amd import binding as tm
+
+
+def to_dev(w: np.ndarray, ld: int | None = None) -> torch.Tensor:
+    """float32 array -> fp32 CUDA tensor; uint16 array (bf16 bit patterns) -> bfloat16 CUDA tensor.
+    With ld > cols the result is a column slice of a wider buffer (row stride ld)."""
+    if w.dtype == np.float32:
+        t = torch.from_numpy(np.ascontiguousarray(w))
+    elif w.dtype == np.uint16:
+        t = torch.from_numpy(np.ascontiguousarray(w).view(np.int16)).view(torch.bfloat16)
+    else:
+        raise TypeError(w.dtype)
+    if ld is None or ld == w.shape[1]:
+        return t.cuda()
+    buf = torch.zeros((w.shape[0], ld), dtype=t.dtype, device="cuda")
+    buf[:, :w.shape[1]] = t.cuda()
+    return buf[:, :w.shape[1]]
+
+
+def mask_to_host(mask: torch.Tensor, cols: int, fmt: int) -> np.ndarray:
+    m = mask.cpu().numpy()
+    if fmt == tm.TMASK_MASK_U8:
+        return m[:, :cols]
+    return np.unpackbits(m, axis=1, bitorder="little")[:, :cols]
+
+
+def mask_to_dev(mask: np.ndarray, fmt: int) -> torch.Tensor:
+    if fmt == tm.TMASK_MASK_U8:
+        return torch.from_numpy(np.ascontiguousarray(mask.astype(np.uint8))).cuda()
+    return torch.from_numpy(np.packbits(mask.astype(np.uint8), axis=1, bitorder="little")).cuda()
+
+
+def run_masks(fn, ws_np, N, M, fmt=tm.TMASK_MASK_U8, ld_pad=0, with_objective=True):
+    """Runs tmask_approx / tmask_exact over a batch; returns (list of host masks, objectives)."""
+    ws = [to_dev(w, ld=(w.shape[1] + ld_pad) if ld_pad else None) for w in ws_np]
+    masks = tm.alloc_masks(ws, fmt)
+    for m in masks:
+        m.fill_(0xCD)
+    obj = torch.full((len(ws),), -1.0, dtype=torch.float64, device="cuda") if with_objective else None
+    wsp = tm.alloc_workspace(ws, N, M)
+    fn(ws, masks, N, M, objective=obj, mask_fmt=fmt, workspace=wsp)
+    torch.cuda.synchronize()
+    host = [mask_to_host(m, w.shape[1], fmt) for m, w in zip(masks, ws_np)]
+    return host, (obj.cpu().numpy() if with_objective else None)
+
+
+def run_score(ws_np, masks_np, N, M, fmt=tm.TMASK_MASK_U8, per_block=True):
+    ws = [to_dev(w) for w in ws_np]
+    masks = [mask_to_dev(m, fmt) for m in masks_np]
+    out = torch.zeros(len(ws) * tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda")
+    n_blocks = sum((w.shape[0] // M) * (w.shape[1] // M) for w in ws_np)
+    pb = torch.full((n_blocks,), -1.0, dtype=torch.float32, device="cuda") if per_block else None
+    wsp = tm.alloc_workspace(ws, N, M)
+    tm.tmask_score(ws, masks, N, M, out, per_block_obj=pb, mask_fmt=fmt, workspace=wsp)
+    torch.cuda.synchronize()
+    scores = tm.read_scores(out, len(ws))
+    pbs = []
+    if per_block:
+        flat = pb.cpu().numpy()
+        o = 0
+        for w in ws_np:
+            br, bc = w.shape[0] // M, w.shape[1] // M
+            pbs.append(flat[o:o + br * bc].reshape(br, bc))
+            o += br * bc
+    return scores, pbs

@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: approximation masks bit-exact; exact-solver masks valid (exactly N per row/column) with every
+block's retained L1 equal to the oracle's within 1e-5 relative; objectives within 1e-5 relative
+(fp32 per strip, fp64 across strips on the GPU; fp64 in the oracle).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2102_08124_amd import workloads as wl
+from tests import refs
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2102_08124_amd import binding as tm   # noqa: E402
+from tests.gpu_util import run_masks, run_score  # noqa: E402
+
+NM = [(2, 4), (4, 8), (8, 16)]
+FMTS = [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS]
+
+
+def _inputs(kind, rows, cols, seed):
+    if kind == "f32":
+        return wl.gaussian_f32(rows, cols, seed)
+    if kind == "bf16":
+        return wl.f32_to_bf16_bits(wl.gaussian_f32(rows, cols, seed, std=0.02))
+    if kind == "ties":
+        return wl.tie_heavy_f32(rows, cols, seed, levels=4)
+    if kind == "ties_bf16":
+        return wl.f32_to_bf16_bits(wl.tie_heavy_f32(rows, cols, seed, levels=3))
+    if kind == "special":
+        return wl.special_values_f32(rows, cols, seed)
+    raise ValueError(kind)
+
+
+def _check_exact(w, mask, N, M, oracle_pb):
+    b = refs.to_blocks(mask, M)
+    assert np.all(b.sum(axis=3) == N) and np.all(b.sum(axis=2) == N), "mask is not exactly N per row/column"
+    got = refs.per_block_sums(refs.magnitudes(w) * mask, M)
+    np.testing.assert_allclose(got, oracle_pb, rtol=1e-5, atol=1e-30)
+
+
+# ---------------------------------------------------------------- approximation ----------------
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("N,M", NM)
+@pytest.mark.parametrize("kind", ["f32", "bf16", "ties", "ties_bf16", "special"])
+def test_approx_bit_exact_ragged(kind, N, M, fmt):
+    # 5 block-rows x 1008 columns: several 256-strip tiles and a ragged last tile
+    w = _inputs(kind, 5 * M, 1008, seed=1000 + M)
+    (mask,), obj = run_masks(tm.tmask_approx, [w], N, M, fmt)
+    omask, oobj = oracle.approx(w, N, M)
+    assert np.array_equal(mask, omask)
+    if kind != "special":
+        assert obj[0] == pytest.approx(oobj, rel=1e-5)
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (2, 8), (6, 8), (3, 16), (12, 16)])
+def test_approx_other_n(N, M):
+    for kind in ("f32", "bf16"):
+        w = _inputs(kind, 3 * M, 512, seed=1100 + N)
+        (mask,), obj = run_masks(tm.tmask_approx, [w], N, M)
+        omask, oobj = oracle.approx(w, N, M)
+        assert np.array_equal(mask, omask)
+        assert obj[0] == pytest.approx(oobj, rel=1e-5)
+
+
+def test_approx_config1():
+    w = wl.config1()
+    (mask,), obj = run_masks(tm.tmask_approx, [w], 2, 4)
+    omask, oobj = oracle.approx(w, 2, 4)
+    assert np.array_equal(mask, omask) and obj[0] == pytest.approx(oobj, rel=1e-6)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_approx_batched_many_matrices_and_strides(dt):
+    # 70 matrices (> one 64-matrix launch), mixed shapes incl. the smallest legal ones, ld > cols
+    rng = np.random.default_rng(5)
+    shapes = [(16, 16), (16, 32), (32, 16), (64, 48), (16, 1040), (128, 272)]
+    ws = [_inputs(dt, *shapes[int(rng.integers(len(shapes)))], seed=1200 + k) for k in range(70)]
+    for N, M in NM:
+        masks, obj = run_masks(tm.tmask_approx, ws, N, M, ld_pad=32)
+        for k, w in enumerate(ws):
+            omask, oobj = oracle.approx(w, N, M)
+            assert np.array_equal(masks[k], omask), "matrix %d" % k
+            assert obj[k] == pytest.approx(oobj, rel=1e-5)
+
+
+def test_approx_without_objective_or_workspace():
+    w = _inputs("f32", 32, 64, seed=1300)
+    wd = torch.from_numpy(w).cuda()
+    masks = tm.alloc_masks([wd])
+    tm.tmask_approx([wd], masks, 2, 4)            # no objective -> no workspace needed
+    torch.cuda.synchronize()
+    assert np.array_equal(masks[0].cpu().numpy(), oracle.approx(w, 2, 4)[0])
+
+
+# ---------------------------------------------------------------- exact ------------------------
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("N,M", NM)
+@pytest.mark.parametrize("kind", ["f32", "bf16", "ties", "ties_bf16"])
+def test_exact_optimal_ragged(kind, N, M, fmt):
+    w = _inputs(kind, 5 * M, 1008, seed=2000 + M)
+    (mask,), obj = run_masks(tm.tmask_exact, [w], N, M, fmt)
+    _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
+    _check_exact(w, mask, N, M, opb)
+    assert obj[0] == pytest.approx(oobj, rel=1e-5)
+
+
+def test_exact_config1_against_enumeration():
+    w = wl.config1()
+    (mask,), obj = run_masks(tm.tmask_exact, [w], 2, 4)
+    best = refs.brute_force_best(w, 2, 4)          # all 90 patterns per block
+    _check_exact(w, mask, 2, 4, best)
+    _, oobj, opb = oracle.exact(w, 2, 4, per_block=True)
+    np.testing.assert_allclose(opb, best, rtol=1e-12)
+    assert obj[0] == pytest.approx(oobj, rel=1e-6)
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (2, 8), (6, 8), (1, 8), (7, 8), (4, 16), (12, 16), (15, 16)])
+def test_exact_other_n(N, M):
+    for kind in ("f32", "bf16"):
+        w = _inputs(kind, 2 * M, 528, seed=2100 + N)
+        (mask,), obj = run_masks(tm.tmask_exact, [w], N, M)
+        _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
+        _check_exact(w, mask, N, M, opb)
+
+
+@pytest.mark.parametrize("N,M", NM)
+def test_exact_heavy_tailed_and_degenerate(N, M):
+    w = wl.laplace_f32(4 * M, 512, seed=2200 + M)
+    w[:M, :M] = 0.0                                   # an all-zero block
+    w[M:2 * M, :M] = 1.0                              # an all-equal block
+    w[:M, M:2 * M] = np.float32(1e-30)                # tiny magnitudes
+    w[M:2 * M, M:2 * M] *= np.float32(1e30)           # huge magnitudes
+    w[0, 2 * M] = np.float32(1e-42)                   # a denormal among normals
+    (mask,), obj = run_masks(tm.tmask_exact, [w], N, M)
+    _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
+    _check_exact(w, mask, N, M, opb)
+
+
+def test_exact_non_finite_stays_valid():
+    w = wl.special_values_f32(32, 256, seed=2300)
+    for N, M in NM:
+        (mask,), _ = run_masks(tm.tmask_exact, [w], N, M, with_objective=False)
+        b = refs.to_blocks(mask, M)
+        assert np.all(b.sum(axis=3) == N) and np.all(b.sum(axis=2) == N)
+
+
+def test_exact_batched():
+    ws = [_inputs("f32", 32, 48, 2400), _inputs("f32", 16, 1040, 2401), _inputs("f32", 64, 64, 2402)]
+    for N, M in NM:
+        masks, obj = run_masks(tm.tmask_exact, ws, N, M, ld_pad=16)
+        for k, w in enumerate(ws):
+            _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
+            _check_exact(w, masks[k], N, M, opb)
+            assert obj[k] == pytest.approx(oobj, rel=1e-5)
+
+
+# ---------------------------------------------------------------- score ------------------------
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("N,M", NM)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_score_matches_oracle(dt, N, M, fmt):
+    ws = [_inputs(dt, 5 * M, 1008, seed=3000 + M), _inputs(dt, 2 * M, 64, seed=3001)]
+    rng = np.random.default_rng(3002)
+    masks = [oracle.approx(ws[0], N, M)[0], (rng.random(ws[1].shape) < 0.55).astype(np.uint8)]
+    scores, pbs = run_score(ws, masks, N, M, fmt)
+    for w, m, sc, pb in zip(ws, masks, scores, pbs):
+        o = oracle.score(w, m, N, M)
+        assert sc["retained_l1"] == pytest.approx(o.retained_l1, rel=1e-5)
+        assert sc["total_l1"] == pytest.approx(o.total_l1, rel=1e-5)
+        assert (sc["kept"], sc["row_violations"], sc["col_violations"], sc["row_not_n"], sc["col_not_n"]) == \
+               (o.kept, o.row_violations, o.col_violations, o.row_not_n, o.col_not_n)
+        np.testing.assert_allclose(pb, o.per_block, rtol=1e-5, atol=1e-30)
+
+
+# ---------------------------------------------------------------- error paths (host-side) ------
+
+def test_argument_errors_leave_outputs_untouched():
+    w = torch.zeros((16, 32), dtype=torch.float32, device="cuda")
+    mask = torch.full((16, 32), 7, dtype=torch.uint8, device="cuda")
+    cases = [
+        (lambda: tm.tmask_approx([w], [mask], 2, 5), tm.TMASK_ERR_NM),
+        (lambda: tm.tmask_approx([w], [mask], 4, 4), tm.TMASK_ERR_NM),
+        (lambda: tm.tmask_approx([w[:12]], [mask[:12]], 4, 8), tm.TMASK_ERR_SHAPE),
+        (lambda: tm.tmask_approx([w[:, 1:17]], [mask[:, :16]], 2, 4), tm.TMASK_ERR_ALIGN),
+        (lambda: tm.tmask_approx([w], [mask], 2, 4, objective=torch.zeros(1, dtype=torch.float64, device="cuda")),
+         tm.TMASK_ERR_WORKSPACE),
+        (lambda: tm.tmask_exact([w], [mask[:, :16].contiguous()], 2, 4), tm.TMASK_ERR_SHAPE),
+    ]
+    for fn, code in cases:
+        with pytest.raises(tm.TmaskError) as e:
+            fn()
+        assert e.value.code == code, str(e.value)
+    torch.cuda.synchronize()
+    assert bool((mask == 7).all())
+    # a 64 x 147 stem-conv shape is not a multiple of 4 wide: rejected, the caller keeps it dense
+    stem = torch.zeros((64, 148), dtype=torch.float32, device="cuda")[:, :147]
+    with pytest.raises(tm.TmaskError) as e:
+        tm.tmask_approx([stem], [torch.zeros((64, 147), dtype=torch.uint8, device="cuda")], 2, 4)
+    assert e.value.code == tm.TMASK_ERR_SHAPE
