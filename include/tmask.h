@@ -27,8 +27,9 @@
  *   rows and cols multiples of M; ld >= cols (ld in elements); rows*cols/M^2 < 2^31;
  *   `w` 16-byte aligned, ld*sizeof(element) and cols*sizeof(element) multiples of 16
  *   (i.e. ld, cols multiples of 4 for fp32 and of 8 for bf16): tiles are read with 16-byte loads.
- *   U8 mask: mask 4-byte aligned, mask_ld >= cols and a multiple of 4.
- *   BITS mask: mask_ld >= cols/8 bytes.
+ *   U8 mask: mask_ld >= cols; mask pointer and mask_ld multiples of 4 (fp32) or 8 (bf16) bytes.
+ *   BITS mask: cols a multiple of 8, mask_ld >= cols/8 bytes.
+ *   Packed outputs: vals and valsT 4-byte aligned, dense (no leading dimension).
  *
  * Errors
  *   All argument errors are detected on the host before anything is enqueued and leave the outputs

@@ -4,11 +4,13 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/tmask.h"
 #include "tmask_device.hpp"
 #include "tmask_solvers.hpp"
+#include "tmask_pack.hpp"
 
 namespace tmask {
 
@@ -527,11 +529,61 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
     return TMASK_OK;
 }
 
+typedef void (*pack_kernel_t)(const PackArgs);
+
+static pack_kernel_t pick_pack_kernel(int dt, int M, int mf)
+{
+#define TMASK_PICK(DT, MM, FM) \
+    if (dt == DT && M == MM && mf == FM) return pack_kernel<DT, MM, FM>;
+    TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
+    TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
+    TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
+    TMASK_PICK(kBF16, 4, kMaskBits) TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+#undef TMASK_PICK
+    return nullptr;
+}
+
 int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
                      void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    (void)descs; (void)n; (void)dt; (void)N; (void)M; (void)mf; (void)workspace; (void)workspace_bytes; (void)hip_stream;
-    return fail(TMASK_ERR_HIP, "tmask_apply_pack: not built yet");
+    (void)workspace; (void)workspace_bytes;   // this call needs no scratch memory
+    int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
+    if (rc)
+        return rc;
+    for (int i = 0; i < n; i++) {
+        const tmask_pack_desc &p = descs[i];
+        const HostMat h{p.w, p.rows, p.cols, p.ld, const_cast<void *>(p.mask), p.mask_ld, nullptr};
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, true)))
+            return rc;
+        if (!p.vals || !p.idx || !p.valsT || !p.idxT)
+            return fail(TMASK_ERR_NULL, "matrix %d: a packed output pointer is NULL", i);
+        if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
+            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 4-byte aligned", i);
+    }
+    const pack_kernel_t kern = pick_pack_kernel((int)dt, M, (int)mf);
+    const uint32_t TC = 256 / (uint32_t)elem_size((int)dt);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    for (int first = 0; first < n; first += kMaxPackBatch) {
+        const int nb = n - first < kMaxPackBatch ? n - first : kMaxPackBatch;
+        PackArgs args;
+        memset(&args, 0, sizeof args);
+        uint32_t tiles = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_pack_desc &p = descs[first + k];
+            PackDev &d = args.d[k];
+            d.w = p.w; d.mask = p.mask; d.vals = p.vals; d.idx = p.idx; d.valsT = p.valsT; d.idxT = p.idxT;
+            d.rows = (uint32_t)p.rows; d.cols = (uint32_t)p.cols; d.ld = (uint32_t)p.ld; d.mask_ld = (uint32_t)p.mask_ld;
+            d.tiles_x = (d.cols + TC - 1) / TC;
+            d.tile0 = tiles;
+            tiles += d.tiles_x * ((d.rows + kPackTR - 1) / kPackTR);
+        }
+        args.n = (uint32_t)nb; args.N = (uint32_t)N;
+        hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "pack kernel launch");
+    }
+    return TMASK_OK;
 }
 
 size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M)

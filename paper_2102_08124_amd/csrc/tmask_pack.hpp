@@ -1,0 +1,290 @@
+// tmask_apply_pack: W (.) S and compression of W and W^T into N values + N positions per group of M.
+//
+// The paper (arXiv 2102.08124, Sec. 2 and Sec. 4) only states why both operands are needed: the
+// forward product reads W and the backward product reads W^T, and a transposable mask leaves N
+// non-zeros in every M contiguous elements of both.  The storage format is this library's own and
+// is described in include/tmask.h.
+//
+// One workgroup packs a 64-row x 256-byte tile (64 fp32 or 128 bf16 columns):
+//   A  coalesced 16-byte loads of W and of the mask; masked values and 0/1 flags go to LDS
+//   C  every thread pulls its row-direction units (one row x one group of M columns) and its
+//      column-direction units (one group of M rows x one column) from LDS into registers
+//   E  each unit is compacted (kept entries, then lowest unused positions as +0 fillers, in position
+//      order) and scattered into LDS staging: values row-major for W, column-major for W^T, index
+//      bits OR-ed into per-row bit strings
+//   G  staging is streamed out with coalesced stores (runs of 128..256 bytes per output row)
+#pragma once
+#include "tmask_device.hpp"
+
+namespace tmask {
+
+constexpr int kMaxPackBatch = 32;
+constexpr int kPackTR = 64;
+
+struct PackDev {
+    const void *w;
+    const void *mask;
+    void *vals, *idx, *valsT, *idxT;
+    uint32_t rows, cols, ld, mask_ld;
+    uint32_t tiles_x;   // tiles per tile-row
+    uint32_t tile0;     // first workgroup of this matrix inside the launch
+};
+
+struct PackArgs {
+    PackDev d[kMaxPackBatch];
+    uint32_t n;
+    uint32_t N;
+};
+
+template <int M>
+struct Log2 {
+    static constexpr int v = (M == 4) ? 2 : (M == 8) ? 3 : 4;
+};
+
+// Compacts one group. v[p] = masked value of position p, kbits = keep flags (bit p).
+// Calls emit(slot, value) for each of the N slots in position order and returns the slot positions
+// packed IB bits per slot (slot-major, LSB first).
+template <int M, typename T, typename Emit>
+__device__ __forceinline__ unsigned long long compact_group(const T (&v)[M], uint32_t kbits, uint32_t N, Emit emit)
+{
+    constexpr int IB = Log2<M>::v;
+    // kept entries beyond the N-th are dropped (a mask with more than N per group is a caller error)
+    uint32_t sel = 0, cnt = 0;
+#pragma unroll
+    for (int p = 0; p < M; p++) {
+        const uint32_t take = ((kbits >> p) & 1u) & (cnt < N ? 1u : 0u);
+        sel |= take << p;
+        cnt += take;
+    }
+    // fillers: lowest-numbered positions that are not selected, until N slots are used
+    uint32_t fill = N - cnt, chosen = sel;
+#pragma unroll
+    for (int p = 0; p < M; p++) {
+        const uint32_t take = (((sel >> p) & 1u) ^ 1u) & (fill > 0 ? 1u : 0u);
+        chosen |= take << p;
+        fill -= take;
+    }
+    unsigned long long code = 0;
+    uint32_t slot = 0;
+#pragma unroll
+    for (int p = 0; p < M; p++) {
+        if ((chosen >> p) & 1u) {
+            emit(slot, ((sel >> p) & 1u) ? v[p] : (T)0);
+            code |= (unsigned long long)p << (slot * IB);
+            slot++;
+        }
+    }
+    return code;
+}
+
+// ORs `nbits` (<= 60) bits of `code` into an LDS bit string at bit offset `off`.
+__device__ __forceinline__ void lds_or_bits(uint32_t *words, uint32_t off, unsigned long long code)
+{
+    const uint32_t w = off >> 5, sh = off & 31u;
+    const unsigned long long lo = code << sh;                       // bits landing in words w, w+1
+    const uint32_t hi = sh ? (uint32_t)(code >> (64 - sh)) : 0u;    // bits landing in word w+2
+    if ((uint32_t)lo)
+        atomicOr(&words[w], (uint32_t)lo);
+    if ((uint32_t)(lo >> 32))
+        atomicOr(&words[w + 1], (uint32_t)(lo >> 32));
+    if (hi)
+        atomicOr(&words[w + 2], hi);
+}
+
+template <int DT, int M, int FMT>
+__global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
+{
+    using T = typename std::conditional<DT == kF32, uint32_t, uint16_t>::type;
+    constexpr int ES = sizeof(T);
+    constexpr int C = 16 / ES;                 // elements per 16-byte chunk
+    constexpr int TR = kPackTR;
+    constexpr int TC = 256 / ES;               // tile columns
+    constexpr int IB = Log2<M>::v;
+    constexpr int GPT = TC / M;                // groups per tile row
+    constexpr int BPT = TR / M;                // block-rows per tile
+    constexpr int OTP = TR + 4 / ES;           // pitch of the transposed staging (bank-conflict free)
+    constexpr int IDXW = (GPT * (M - 1) * IB + 31) / 32 + 2;
+    constexpr int IDXTW = (BPT * (M - 1) * IB + 31) / 32 + 2 + 1;
+    constexpr int NRU = TR * GPT / kThreads;   // row-direction units per thread
+    constexpr int NCU = BPT * TC / kThreads;   // column-direction units per thread
+    static_assert(TR * GPT % kThreads == 0 && BPT * TC % kThreads == 0, "units must tile the workgroup");
+
+    __shared__ __attribute__((aligned(16))) T V[TR][TC];   // masked tile; later the W staging OV
+    __shared__ __attribute__((aligned(16))) uint8_t FB[TR][TC];
+    __shared__ T OT[TC][OTP];
+    __shared__ uint32_t IDX[TR][IDXW];
+    __shared__ uint32_t IDXT[TC][IDXTW];
+
+    // ---- which tile ----
+    const uint32_t tile = blockIdx.x;
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].tile0 <= tile)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const PackDev d = args.d[lo];
+    const uint32_t N = args.N;
+    const uint32_t tl = tile - d.tile0;
+    const uint32_t ty = tl / d.tiles_x, tx = tl - ty * d.tiles_x;
+    const uint32_t row0 = ty * TR, col0 = tx * TC;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t g_valid = min((uint32_t)GPT, (d.cols - col0) / M);   // groups of this tile inside the matrix
+    const uint32_t b_valid = min((uint32_t)BPT, (d.rows - row0) / M);
+    const uint32_t r_valid = b_valid * M, c_valid = g_valid * M;
+
+    // ---- A: load ----
+    for (uint32_t k = tid; k < TR * IDXW; k += kThreads)
+        (&IDX[0][0])[k] = 0;
+    for (uint32_t k = tid; k < TC * IDXTW; k += kThreads)
+        (&IDXT[0][0])[k] = 0;
+#pragma unroll
+    for (int pass = 0; pass < TR / 16; pass++) {
+        const uint32_t r = pass * 16 + (tid >> 4), ch = tid & 15u;
+        const uint32_t row = row0 + r, col = col0 + ch * C;
+        u32x4 raw = {0u, 0u, 0u, 0u};
+        uint32_t flags = 0;
+        if (row < d.rows && col < d.cols) {
+            raw = __builtin_nontemporal_load((const u32x4 *)((const char *)d.w + ((size_t)row * d.ld + col) * ES));
+            if constexpr (FMT == kMaskU8) {
+                const char *mp = (const char *)d.mask + (size_t)row * d.mask_ld + col;
+                if constexpr (C == 4) {
+                    flags = bytes4_to_bits(__builtin_nontemporal_load((const uint32_t *)mp));
+                } else {
+                    const u32x2 mv = __builtin_nontemporal_load((const u32x2 *)mp);
+                    flags = bytes4_to_bits(mv.x) | (bytes4_to_bits(mv.y) << 4);
+                }
+            } else {
+                const uint32_t byte = ((const unsigned char *)d.mask)[(size_t)row * d.mask_ld + (col >> 3)];
+                flags = (C == 8) ? byte : ((byte >> (col & 4u)) & 0xFu);
+            }
+        }
+        uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
+        if constexpr (DT == kF32) {
+#pragma unroll
+            for (int c = 0; c < 4; c++)
+                w4[c] = ((flags >> c) & 1u) ? w4[c] : 0u;
+            *(uint32_t *)&FB[r][ch * C] = bits_to_bytes4(flags);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                const uint32_t keep_lo = ((flags >> (2 * c)) & 1u) ? 0x0000FFFFu : 0u;
+                const uint32_t keep_hi = ((flags >> (2 * c + 1)) & 1u) ? 0xFFFF0000u : 0u;
+                w4[c] &= keep_lo | keep_hi;
+            }
+            *(uint32_t *)&FB[r][ch * C] = bits_to_bytes4(flags & 0xFu);
+            *(uint32_t *)&FB[r][ch * C + 4] = bits_to_bytes4(flags >> 4);
+        }
+        u32x4 mv = {w4[0], w4[1], w4[2], w4[3]};
+        *(u32x4 *)&V[r][ch * C] = mv;
+    }
+    __syncthreads();
+
+    // ---- C: units into registers ----
+    T rv[NRU][M], cv[NCU][M];
+    uint32_t rk[NRU], ck[NCU];
+#pragma unroll
+    for (int k = 0; k < NRU; k++) {
+        const uint32_t u = tid + k * kThreads, r = u / GPT, g = u % GPT;
+        rk[k] = 0;
+#pragma unroll
+        for (int p = 0; p < M; p++) {
+            rv[k][p] = V[r][g * M + p];
+            rk[k] |= (uint32_t)FB[r][g * M + p] << p;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < NCU; k++) {
+        const uint32_t u = tid + k * kThreads, b = u / TC, c = u % TC;
+        ck[k] = 0;
+#pragma unroll
+        for (int p = 0; p < M; p++) {
+            cv[k][p] = V[b * M + p][c];
+            ck[k] |= (uint32_t)FB[b * M + p][c] << p;
+        }
+    }
+    __syncthreads();
+
+    // ---- E: compact and scatter into staging ----
+    T(*OV)[TC] = V;
+#pragma unroll
+    for (int k = 0; k < NRU; k++) {
+        const uint32_t u = tid + k * kThreads, r = u / GPT, g = u % GPT;
+        if (r >= r_valid || g >= g_valid)
+            continue;   // outside the matrix: must not leave index bits in a row's padding
+        const unsigned long long code =
+            compact_group<M, T>(rv[k], rk[k], N, [&](uint32_t slot, T val) { OV[r][g * N + slot] = val; });
+        lds_or_bits(IDX[r], g * N * IB, code);
+    }
+#pragma unroll
+    for (int k = 0; k < NCU; k++) {
+        const uint32_t u = tid + k * kThreads, b = u / TC, c = u % TC;
+        if (b >= b_valid || c >= c_valid)
+            continue;
+        const unsigned long long code =
+            compact_group<M, T>(cv[k], ck[k], N, [&](uint32_t slot, T val) { OT[c][b * N + slot] = val; });
+        lds_or_bits(IDXT[c], b * N * IB, code);
+    }
+    __syncthreads();
+
+    // ---- G: stream out ----
+    {
+        // vals: r_valid rows, g_valid*N elements each
+        const uint32_t run = g_valid * N;
+        const size_t pitch = (size_t)(d.cols / M) * N;               // elements per output row
+        T *dst = (T *)d.vals + (size_t)row0 * pitch + (size_t)(col0 / M) * N;
+        if (ES == 4 || (((run | (uint32_t)pitch | (uint32_t)((col0 / M) * N)) & 1u) == 0)) {
+            const uint32_t rd = run * ES / 4;
+            for (uint32_t k = tid; k < r_valid * rd; k += kThreads) {
+                const uint32_t r = k / rd, x = k - r * rd;
+                ((uint32_t *)(dst + (size_t)r * pitch))[x] = ((const uint32_t *)&OV[r][0])[x];
+            }
+        } else {
+            for (uint32_t k = tid; k < r_valid * run; k += kThreads) {
+                const uint32_t r = k / run, x = k - r * run;
+                dst[(size_t)r * pitch + x] = OV[r][x];
+            }
+        }
+    }
+    {
+        // valsT: c_valid rows (columns of W), b_valid*N elements each
+        const uint32_t run = b_valid * N;
+        const size_t pitch = (size_t)(d.rows / M) * N;
+        T *dst = (T *)d.valsT + (size_t)col0 * pitch + (size_t)(row0 / M) * N;
+        if (ES == 4 || (((run | (uint32_t)pitch | (uint32_t)((row0 / M) * N)) & 1u) == 0)) {
+            const uint32_t rd = run * ES / 4;
+            for (uint32_t k = tid; k < c_valid * rd; k += kThreads) {
+                const uint32_t c = k / rd, x = k - c * rd;
+                ((uint32_t *)(dst + (size_t)c * pitch))[x] = ((const uint32_t *)&OT[c][0])[x];
+            }
+        } else {
+            for (uint32_t k = tid; k < c_valid * run; k += kThreads) {
+                const uint32_t c = k / run, x = k - c * run;
+                dst[(size_t)c * pitch + x] = OT[c][x];
+            }
+        }
+    }
+    {
+        // idx: per row, the tile's bit string starts on a byte boundary (GPT*N*IB is a multiple of 8)
+        const size_t pitch = ((size_t)(d.cols / M) * N * IB + 7) / 8;
+        const uint32_t nbytes = (g_valid * N * IB + 7) / 8;
+        unsigned char *dst = (unsigned char *)d.idx + (size_t)row0 * pitch + ((size_t)(col0 / M) * N * IB) / 8;
+        for (uint32_t k = tid; k < r_valid * nbytes; k += kThreads) {
+            const uint32_t r = k / nbytes, x = k - r * nbytes;
+            dst[(size_t)r * pitch + x] = ((const unsigned char *)&IDX[r][0])[x];
+        }
+    }
+    {
+        const size_t pitch = ((size_t)(d.rows / M) * N * IB + 7) / 8;
+        const uint32_t nbytes = (b_valid * N * IB + 7) / 8;
+        unsigned char *dst = (unsigned char *)d.idxT + (size_t)col0 * pitch + ((size_t)(row0 / M) * N * IB) / 8;
+        for (uint32_t k = tid; k < c_valid * nbytes; k += kThreads) {
+            const uint32_t c = k / nbytes, x = k - c * nbytes;
+            dst[(size_t)c * pitch + x] = ((const unsigned char *)&IDXT[c][0])[x];
+        }
+    }
+}
+
+}  // namespace tmask

@@ -69,3 +69,24 @@ def run_score(ws_np, masks_np, N, M, fmt=tm.TMASK_MASK_U8, per_block=True):
             pbs.append(flat[o:o + br * bc].reshape(br, bc))
             o += br * bc
     return scores, pbs
+
+
+def run_pack(ws_np, masks_np, N, M, fmt=tm.TMASK_MASK_U8, ld_pad=0):
+    ws = [to_dev(w, ld=(w.shape[1] + ld_pad) if ld_pad else None) for w in ws_np]
+    masks = [mask_to_dev(m, fmt) for m in masks_np]
+    packed = [tm.alloc_packed(w, N, M) for w in ws]
+    for pk in packed:
+        for t in pk:
+            t.view(torch.uint8).fill_(0xEE)
+    tm.tmask_apply_pack(ws, masks, packed, N, M, mask_fmt=fmt)
+    torch.cuda.synchronize()
+    out = []
+    for pk, w in zip(packed, ws_np):
+        host = []
+        for t in pk:
+            if t.dtype == torch.bfloat16:
+                host.append(t.view(torch.int16).cpu().numpy().view(np.uint16))
+            else:
+                host.append(t.cpu().numpy())
+        out.append(tuple(host))
+    return out

@@ -1,0 +1,80 @@
+"""GPU parity for tmask_apply_pack: every output byte equals the oracle's."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2102_08124_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2102_08124_amd import binding as tm   # noqa: E402
+from tests.gpu_util import run_pack              # noqa: E402
+
+
+def _w(dt, rows, cols, seed):
+    w = wl.gaussian_f32(rows, cols, seed, std=0.02)
+    w[0, 0] = -0.0
+    return w if dt == "f32" else wl.f32_to_bf16_bits(w)
+
+
+def _same(got, want):
+    for g, o, name in zip(got, want, ("vals", "idx", "valsT", "idxT")):
+        assert g.shape == o.shape, name
+        assert np.array_equal(g.view(np.uint8), o.view(np.uint8)), name
+
+
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (8, 16)])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_pack_matches_oracle_ragged(dt, N, M, fmt):
+    # 5 block-rows x 1008 columns: partial tiles on both edges
+    w = _w(dt, 5 * M, 1008, seed=4000 + M)
+    for mask in (oracle.approx(w, N, M)[0], oracle.exact(w, N, M, threads=8)[0]):
+        (got,) = run_pack([w], [mask], N, M, fmt)
+        _same(got, oracle.apply_pack(w, mask, N, M))
+
+
+@pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (3, 8), (7, 8), (1, 16), (5, 16), (15, 16)])
+def test_pack_other_n(N, M):
+    for dt in ("f32", "bf16"):
+        w = _w(dt, 8 * M + M, 272, seed=4100 + N)      # cols/M*N odd in places: element-wise store path
+        mask = oracle.approx(w, N, M)[0]
+        (got,) = run_pack([w], [mask], N, M)
+        _same(got, oracle.apply_pack(w, mask, N, M))
+
+
+def test_pack_non_finite_and_empty_mask():
+    w = wl.special_values_f32(64, 128, seed=4200)
+    mask = oracle.approx(w, 2, 4)[0]
+    (got,) = run_pack([w], [mask], 2, 4)
+    _same(got, oracle.apply_pack(w, mask, 2, 4))       # pruned NaN/Inf become +0
+    zero = np.zeros_like(mask)
+    (got,) = run_pack([w], [zero], 2, 4)
+    _same(got, oracle.apply_pack(w, zero, 2, 4))
+    full = np.ones_like(mask)                          # more than N kept: the first N of each group win
+    (got,) = run_pack([w], [full], 2, 4)
+    _same(got, oracle.apply_pack(w, full, 2, 4))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_pack_batched_with_strides(dt):
+    rng = np.random.default_rng(9)
+    shapes = [(16, 16), (16, 32), (64, 48), (144, 272), (32, 1040), (256, 64)]
+    ws = [_w(dt, *shapes[int(rng.integers(len(shapes)))], seed=4300 + k) for k in range(40)]   # > one 32-matrix launch
+    for N, M in ((2, 4), (4, 8), (8, 16)):
+        masks = [oracle.approx(w, N, M)[0] for w in ws]
+        got = run_pack(ws, masks, N, M, ld_pad=32)
+        for k, w in enumerate(ws):
+            _same(got[k], oracle.apply_pack(w, masks[k], N, M))
+
+
+def test_pack_roundtrip_and_l1():
+    w = wl.gaussian_f32(128, 256, seed=4400)
+    mask, obj = oracle.exact(w, 4, 8, threads=4)
+    (got,) = run_pack([w], [mask], 4, 8)
+    vals, idx, valsT, idxT = got
+    masked = np.where(mask != 0, w, np.float32(0))
+    assert np.array_equal(oracle.unpack(vals, idx, 128, 256, 4, 8), masked)
+    assert np.array_equal(oracle.unpack(valsT, idxT, 256, 128, 4, 8), masked.T)
+    assert np.abs(vals.astype(np.float64)).sum() == pytest.approx(obj, rel=1e-12)
