@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the transposable-mask hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input, everything resident in
+HBM: tmask_approx (Algorithm 1) + tmask_exact (Eq. 1 optimum) + tmask_apply_pack (with the exact
+mask) + tmask_score (of the approximate mask, per-block objectives included), each with its
+objective reduction.  Workload at N=1: the ResNet-50-shaped conv weight set (52 matrices,
+23,445,504 fp32 weights, Kaiming-normal, seeded), N:M = 2:4, every call one batched launch over all
+layers.  Several distinct copies of all buffers are rotated so the working set exceeds the
+last-level cache.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+N_KEEP, M_BLOCK = 2, 4
+
+
+class HipEvents:
+    """hipEvent timing on the stream the kernels are launched on (via the HIP runtime already loaded)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so.7")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+
+    def create(self) -> int:
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError("hipEventCreate failed: %d" % rc)
+        return ev.value
+
+    def elapsed_ms(self, start: int, stop: int) -> float:
+        self.hip.hipEventSynchronize(stop)
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), start, stop)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return float(ms.value)
+
+
+def algorithmic_bytes(weights: int, n_mats: int, es: int, N: int, M: int):
+    """Bytes each call must move per launch (U8 mask): what is read plus what is written."""
+    ib = (M - 1).bit_length()
+    mask = weights
+    blocks = weights // (M * M)
+    pack_out = 2 * (weights * N // M) * es + 2 * (weights * N // M) * ib // 8
+    return {
+        "approx": weights * es + mask + 8 * n_mats,
+        "exact": weights * es + mask + 8 * n_mats,
+        "pack": weights * es + mask + pack_out,
+        "score": weights * es + mask + 4 * blocks + 56 * n_mats,
+    }
+
+
+def read_pmc_traffic(path: str):
+    """Per-launch HBM traffic measured with rocprofv3 --pmc (committed summary), or {}.
+    Lines look like: `traffic <kernel> fetch_bytes=<int> write_bytes=<int>`."""
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            m = re.match(r"\s*traffic\s+(\w+)\s+fetch_bytes=(\d+)\s+write_bytes=(\d+)", line)
+            if m:
+                out[m.group(1)] = int(m.group(2)) + int(m.group(3))
+    return out
+
+
+def cpu_baseline(mats_np, budget_s: float = 30.0):
+    """The oracle as it stands, one thread, on the same workload (one full step)."""
+    import oracle
+    t0 = time.perf_counter()
+    weights = 0
+    for w in mats_np:
+        am, _ = oracle.approx(w, N_KEEP, M_BLOCK)
+        em, _ = oracle.exact(w, N_KEEP, M_BLOCK)
+        oracle.apply_pack(w, em, N_KEEP, M_BLOCK)
+        oracle.score(w, am, N_KEEP, M_BLOCK)
+        weights += w.size
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    total = sum(w.size for w in mats_np)
+    return {"value": weights / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
+            "sample": "one full step (approx+exact+pack+score) of the C oracle, -O2, 1 thread, on %d of %d "
+                      "weights of the same workload, %.1f s" % (weights, total, dt)}
+
+
+def largest_config_approx(tm, torch, ev, reps: int):
+    """Approximation alone on the largest configuration (16384^2 bf16, 2:4): kernel time and HBM fraction."""
+    side = 16384
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    sets = []
+    for _ in range(2):
+        w = (torch.randn((side, side), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        mask = torch.empty((side, side), dtype=torch.uint8, device="cuda")
+        obj = torch.zeros(1, dtype=torch.float64, device="cuda")
+        sets.append(tm.MatBatch([w], [mask], obj))
+    wsp = tm.alloc_workspace(sets[0].ws, N_KEEP, M_BLOCK)
+    evs = [(ev.create(), ev.create()) for _ in range(reps)]
+    for b in sets:
+        tm.tmask_approx(b, None, N_KEEP, M_BLOCK, workspace=wsp)
+    torch.cuda.synchronize()
+    for k in range(reps):
+        tm.tmask_profile_next(*evs[k])
+        tm.tmask_approx(sets[k % 2], None, N_KEEP, M_BLOCK, workspace=wsp)
+    torch.cuda.synchronize()
+    ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs]))
+    weights = side * side
+    byts = weights * 3 + 8
+    return {"workload": "16384x16384 bf16 N(0,0.02), 2:4, tmask_approx, U8 mask", "kernel_ms": ms,
+            "weights_per_s": weights / (ms * 1e-3), "achieved_GBs": byts / (ms * 1e-3) / 1e9,
+            "frac_of_hbm_peak": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--copies", type=int, default=8, help="distinct buffer sets rotated through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-largest", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (blocks are independent, see DESIGN.md); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2102_08124_amd import binding as tm
+    from paper_2102_08124_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    tm.load_library()
+    ev = HipEvents()
+
+    mats_np = wl.config2()
+    n_mats = len(mats_np)
+    weights = sum(w.size for w in mats_np)
+    N, M = N_KEEP, M_BLOCK
+
+    sets = []
+    for _ in range(args.copies):
+        ws = [torch.from_numpy(w).cuda() for w in mats_np]
+        amask, emask = tm.alloc_masks(ws), tm.alloc_masks(ws)
+        aobj = torch.zeros(n_mats, dtype=torch.float64, device="cuda")
+        eobj = torch.zeros(n_mats, dtype=torch.float64, device="cuda")
+        packed = [tm.alloc_packed(w, N, M) for w in ws]
+        sout = torch.zeros(n_mats * tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda")
+        pb = torch.zeros(weights // (M * M), dtype=torch.float32, device="cuda")
+        sets.append({
+            "approx": tm.MatBatch(ws, amask, aobj), "exact": tm.MatBatch(ws, emask, eobj),
+            "pack": tm.PackBatch(ws, emask, packed, N, M), "score": tm.MatBatch(ws, amask, None),
+            "sout": sout, "pb": pb,
+        })
+    wsp = tm.alloc_workspace(sets[0]["approx"].ws, N, M)
+    names = ("approx", "exact", "pack", "score")
+
+    def step(k: int, events=None):
+        s = sets[k % args.copies]
+        if events:
+            tm.tmask_profile_next(*events["approx"])
+        tm.tmask_approx(s["approx"], None, N, M, workspace=wsp)
+        if events:
+            tm.tmask_profile_next(*events["exact"])
+        tm.tmask_exact(s["exact"], None, N, M, workspace=wsp)
+        if events:
+            tm.tmask_profile_next(*events["pack"])
+        tm.tmask_apply_pack(s["pack"], None, None, N, M)
+        if events:
+            tm.tmask_profile_next(*events["score"])
+        tm.tmask_score(s["score"], None, N, M, s["sout"], per_block_obj=s["pb"], workspace=wsp)
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps steps; per-kernel hipEvents ride along inside it
+    evs = [{n: (ev.create(), ev.create()) for n in names} for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k, evs[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    kern_ms = {n: float(np.mean([ev.elapsed_ms(*e[n]) for e in evs])) for n in names}
+    alg = algorithmic_bytes(weights, n_mats, 4, N, M)
+    traffic = read_pmc_traffic(os.path.join(ROOT, "profiles", "pmc_traffic_resnet50_f32_2of4.md"))
+    kernels = {}
+    for n in names:
+        gbs = alg[n] / (kern_ms[n] * 1e-3) / 1e9
+        kernels[n] = {"kernel_ms": kern_ms[n], "algorithmic_bytes": alg[n], "achieved_GBs": gbs,
+                      "frac": gbs / HBM_PEAK_GBS, "weights_per_s": weights / (kern_ms[n] * 1e-3),
+                      "traffic": traffic.get(n)}
+    dom = max(names, key=lambda n: kern_ms[n])
+
+    result = {
+        "metric": "transposable-mask weights/sec (approx & exact) + % of HBM roofline, 1xMI355X",
+        "value": weights / (ms_per_step * 1e-3),
+        "unit": "weights/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "ResNet-50-shaped conv weight set: 52 fp32 matrices, 23445504 weights, "
+                               "Kaiming-normal, seeded; N:M=2:4; one step = approx+exact+apply_pack+score, "
+                               "each one batched launch over all layers; U8 masks; %d rotating buffer sets" % args.copies,
+                   "N": N, "M": M, "mask_format": "u8", "weights": weights, "matrices": n_mats},
+        "roofline": {"bound": "hbm", "kernel": dom + "_kernel", "achieved": kernels[dom]["achieved_GBs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["frac"],
+                     "traffic": kernels[dom]["traffic"]},
+        "kernels": kernels,
+        "approx_weights_per_s": kernels["approx"]["weights_per_s"],
+        "exact_weights_per_s": kernels["exact"]["weights_per_s"],
+        "exact_over_approx_time": kern_ms["exact"] / kern_ms["approx"],
+    }
+    if not args.no_largest:
+        result["largest_config"] = largest_config_approx(tm, torch, ev, reps=20)
+    del sets
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(mats_np)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -140,6 +140,15 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
 /* Upper bound of the workspace any call above needs for these matrices (0 on invalid arguments). */
 size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M);
 
+/*
+ * Profiling aid (not part of the paper's method).  The next tmask_approx / tmask_exact /
+ * tmask_score / tmask_apply_pack call made on this thread records `start_event` (a hipEvent_t) on
+ * the call's stream immediately before its main kernel and `stop_event` immediately after it, so
+ * hipEventElapsedTime gives that kernel's duration (for calls split into several launches: the last
+ * launch).  One-shot; pass NULLs to cancel.  The events are the caller's.
+ */
+int tmask_profile_next(void *start_event, void *stop_event);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char *tmask_last_error(void);
 

@@ -22,7 +22,7 @@ TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
 EXPORTS = ("tmask_approx", "tmask_exact", "tmask_apply_pack", "tmask_score", "tmask_workspace_bytes",
-           "tmask_last_error", "tmask_version")
+           "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
 class TmaskError(RuntimeError):
@@ -72,6 +72,8 @@ def load_library():
     L.tmask_score.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     L.tmask_workspace_bytes.restype = sz
     L.tmask_workspace_bytes.argtypes = [C.POINTER(tmask_mat), ci, ci, ci]
+    L.tmask_profile_next.restype = ci
+    L.tmask_profile_next.argtypes = [vp, vp]
     L.tmask_last_error.restype = C.c_char_p
     L.tmask_last_error.argtypes = []
     L.tmask_version.restype = ci
@@ -131,6 +133,41 @@ def _mats(ws, masks, objective) -> "C.Array":
     return arr
 
 
+class MatBatch:
+    """Host descriptor array for a batch of matrices, marshalled once and reusable across calls
+    (keeps the tensors alive).  Pass it in place of `ws` (with masks=None) to tmask_approx /
+    tmask_exact / tmask_score to skip per-call marshalling in tight loops."""
+
+    def __init__(self, ws, masks, objective=None):
+        self.ws, self.masks, self.objective = list(ws), list(masks), objective
+        self.arr = _mats(self.ws, self.masks, objective)
+        self.n = len(self.ws)
+        self.dt = dtype_code(self.ws[0])
+        if any(dtype_code(w) != self.dt for w in self.ws):
+            raise TypeError("all matrices of one call share a dtype")
+
+
+class PackBatch:
+    """Host descriptor array for tmask_apply_pack, marshalled once (keeps the tensors alive)."""
+
+    def __init__(self, ws, masks, packed, N: int, M: int):
+        self.ws, self.masks, self.packed = list(ws), list(masks), list(packed)
+        self.n = len(self.ws)
+        self.dt = dtype_code(self.ws[0])
+        self.arr = (tmask_pack_desc * self.n)()
+        for k, (w, m, pk) in enumerate(zip(self.ws, self.masks, self.packed)):
+            p, r, c, ld = _mat2d(w, "w")
+            mp, _, _, mld = _mat2d(m, "mask")
+            vs, is_, vts, its = packed_shapes(r, c, N, M)
+            vals, idx, valsT, idxT = pk
+            for t, shp, dty in ((vals, vs, w.dtype), (idx, is_, torch.uint8), (valsT, vts, w.dtype),
+                                (idxT, its, torch.uint8)):
+                if tuple(t.shape) != shp or t.dtype != dty or not t.is_contiguous() or not t.is_cuda:
+                    raise ValueError("packed output has the wrong shape/dtype: %s vs %s" % (tuple(t.shape), shp))
+            self.arr[k] = tmask_pack_desc(p, r, c, ld, mp, mld, vals.data_ptr(), idx.data_ptr(), valsT.data_ptr(),
+                                          idxT.data_ptr())
+
+
 def tmask_workspace_bytes(ws: Sequence[torch.Tensor], N: int, M: int) -> int:
     arr = (tmask_mat * len(ws))()
     for k, w in enumerate(ws):
@@ -149,13 +186,9 @@ def _ws_args(workspace):
 
 
 def _run_mask(fn, ws, masks, N, M, objective, mask_fmt, workspace, stream):
-    ws = list(ws)
-    arr = _mats(ws, masks, objective)
-    dt = dtype_code(ws[0])
-    if any(dtype_code(w) != dt for w in ws):
-        raise TypeError("all matrices of one call share a dtype")
+    b = ws if isinstance(ws, MatBatch) else MatBatch(ws, masks, objective)
     wp, wb = _ws_args(workspace)
-    _check(fn(arr, len(ws), dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
+    _check(fn(b.arr, b.n, b.dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
 
 
 def tmask_approx(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = None,
@@ -173,14 +206,13 @@ def tmask_exact(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = N
 def tmask_score(ws, masks, N: int, M: int, out: torch.Tensor, per_block_obj: Optional[torch.Tensor] = None,
                 mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     """out: CUDA uint8 tensor of len(ws) * SCORE_OUT_BYTES bytes (array of tmask_score_out)."""
-    ws = list(ws)
-    arr = _mats(ws, masks, None)
-    if out.numel() * out.element_size() < len(ws) * SCORE_OUT_BYTES or not out.is_cuda or not out.is_contiguous():
+    b = ws if isinstance(ws, MatBatch) else MatBatch(ws, masks, None)
+    if out.numel() * out.element_size() < b.n * SCORE_OUT_BYTES or not out.is_cuda or not out.is_contiguous():
         raise ValueError("out is too small")
     if per_block_obj is not None and (per_block_obj.dtype != torch.float32 or not per_block_obj.is_contiguous()):
         raise ValueError("per_block_obj must be contiguous float32")
     wp, wb = _ws_args(workspace)
-    _check(load_library().tmask_score(arr, len(ws), dtype_code(ws[0]), N, M, mask_fmt, C.c_void_p(out.data_ptr()),
+    _check(load_library().tmask_score(b.arr, b.n, b.dt, N, M, mask_fmt, C.c_void_p(out.data_ptr()),
                                       C.c_void_p(per_block_obj.data_ptr()) if per_block_obj is not None else None,
                                       wp, wb, _stream_ptr(stream)))
 
@@ -214,21 +246,14 @@ def alloc_packed(w: torch.Tensor, N: int, M: int):
 def tmask_apply_pack(ws, masks, packed, N: int, M: int, mask_fmt: int = TMASK_MASK_U8,
                      workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     """packed[k] = (vals, idx, valsT, idxT) tensors for matrix k (see alloc_packed), written in place."""
-    ws = list(ws)
-    n = len(ws)
-    arr = (tmask_pack_desc * n)()
-    for k, (w, m, pk) in enumerate(zip(ws, masks, packed)):
-        p, r, c, ld = _mat2d(w, "w")
-        mp, _, _, mld = _mat2d(m, "mask")
-        vs, is_, vts, its = packed_shapes(r, c, N, M)
-        vals, idx, valsT, idxT = pk
-        for t, shp, dty in ((vals, vs, w.dtype), (idx, is_, torch.uint8), (valsT, vts, w.dtype), (idxT, its, torch.uint8)):
-            if tuple(t.shape) != shp or t.dtype != dty or not t.is_contiguous() or not t.is_cuda:
-                raise ValueError("packed output has the wrong shape/dtype: %s vs %s" % (tuple(t.shape), shp))
-        arr[k] = tmask_pack_desc(p, r, c, ld, mp, mld, vals.data_ptr(), idx.data_ptr(), valsT.data_ptr(),
-                                 idxT.data_ptr())
+    b = ws if isinstance(ws, PackBatch) else PackBatch(ws, masks, packed, N, M)
     wp, wb = _ws_args(workspace)
-    _check(load_library().tmask_apply_pack(arr, n, dtype_code(ws[0]), N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
+    _check(load_library().tmask_apply_pack(b.arr, b.n, b.dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
+
+
+def tmask_profile_next(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """hipEvent_t handles (as integers) recorded around the main kernel of the next call; None cancels."""
+    _check(load_library().tmask_profile_next(C.c_void_p(start_event), C.c_void_p(stop_event)))
 
 
 def tmask_version() -> int:

@@ -50,6 +50,8 @@ struct BatchArgs {
     void *partials;      // workspace
 };
 
+static_assert(sizeof(BatchArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+
 template <int DT, int M>
 struct Geo {
     static constexpr int ES = (DT == kF32) ? 4 : 2;          // element bytes

@@ -404,6 +404,26 @@ static int hip_fail(hipError_t e, const char *what)
     return fail(TMASK_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
+// One-shot profiling events (tmask_profile_next): recorded around the main kernel of the next call.
+static thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
+struct ProfileScope {
+    hipStream_t stream;
+    bool active;
+    ProfileScope(hipStream_t s, bool last_chunk) : stream(s), active(last_chunk && g_prof_start && g_prof_stop)
+    {
+        if (active)
+            (void)hipEventRecord(g_prof_start, stream);
+    }
+    ~ProfileScope()
+    {
+        if (active) {
+            (void)hipEventRecord(g_prof_stop, stream);
+            g_prof_start = g_prof_stop = nullptr;
+        }
+    }
+};
+
 template <int SOLVER>
 static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, void *ws, size_t ws_bytes,
                     void *stream_)
@@ -442,7 +462,10 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         rargs.tile0[nb] = tiles;
         args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
         args.partial0 = partial0; args.partials = want_obj ? ws : nullptr;
-        hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        {
+            ProfileScope prof(stream, first + kMaxBatch >= n_mats);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return hip_fail(e, "mask kernel launch");
@@ -514,7 +537,10 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
         rargs.tile0[nb] = tiles;
         args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
         args.partial0 = partial0; args.partials = workspace;
-        hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        {
+            ProfileScope prof(stream, first + kMaxBatch >= n_mats);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return hip_fail(e, "score kernel launch");
@@ -578,7 +604,10 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
             tiles += d.tiles_x * ((d.rows + kPackTR - 1) / kPackTR);
         }
         args.n = (uint32_t)nb; args.N = (uint32_t)N;
-        hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        {
+            ProfileScope prof(stream, first + kMaxPackBatch >= n);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return hip_fail(e, "pack kernel launch");
@@ -591,6 +620,13 @@ size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M)
     if (!mats || n_mats <= 0 || !valid_nm(N, M))
         return 0;
     return workspace_need(mats, n_mats, M);
+}
+
+int tmask_profile_next(void *start_event, void *stop_event)
+{
+    g_prof_start = (hipEvent_t)start_event;
+    g_prof_stop = (hipEvent_t)stop_event;
+    return TMASK_OK;
 }
 
 const char *tmask_last_error(void) { return g_err; }

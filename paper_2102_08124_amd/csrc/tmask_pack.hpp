@@ -18,7 +18,7 @@
 
 namespace tmask {
 
-constexpr int kMaxPackBatch = 32;
+constexpr int kMaxPackBatch = 56;   // 56 descriptors of 72 bytes fit the 4 KiB kernel-argument segment
 constexpr int kPackTR = 64;
 
 struct PackDev {
@@ -35,6 +35,7 @@ struct PackArgs {
     uint32_t n;
     uint32_t N;
 };
+static_assert(sizeof(PackArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
 
 template <int M>
 struct Log2 {
