@@ -10,6 +10,7 @@
 #include "../../include/tmask.h"
 #include "tmask_device.hpp"
 #include "tmask_solvers.hpp"
+#include "tmask_approx4.hpp"
 #include "tmask_pack.hpp"
 
 namespace tmask {
@@ -91,6 +92,30 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
         }
         store_mask<DT, M, FMT>(md, pos, bits);
         acc = (double)kept_sum<M, Ge::C>(a, bits);
+    }
+    if (args.partials) {
+        const double t = block_sum(acc, red);
+        if (threadIdx.x == 0)
+            ((double *)args.partials)[args.partial0 + tile] = t;
+    }
+}
+
+// tmask_approx for 2:4: same tiling as mask_kernel, decisions taken as lane-mask logic.
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void approx24_kernel(const BatchArgs args)
+{
+    using Ge = Geo<DT, 4>;
+    __shared__ double red[kThreads / 64];
+    const uint32_t tile = blockIdx.x;
+    const MatDev md = args.m[find_matrix(args, tile)];
+    const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
+    double acc = 0.0;
+    if (s < md.n_strips) {
+        const StripPos pos = strip_pos(md, s);
+        uint32_t a[4][Ge::C];
+        u32x4 raw[4];
+        load_strip<DT, 4>(md, pos, a, raw);
+        acc = (double)approx_2of4_strip<DT, FMT>(md, pos, a);
     }
     if (args.partials) {
         const double t = block_sum(acc, red);
@@ -441,7 +466,13 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     }
     if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes)))
         return rc;
-    const batch_kernel_t kern = pick_mask_kernel<SOLVER>(dt, M, mf);
+    batch_kernel_t kern = pick_mask_kernel<SOLVER>(dt, M, mf);
+    if (SOLVER == kSolveApprox && M == 4 && N == 2) {
+        if (dt == kF32)
+            kern = mf == kMaskU8 ? approx24_kernel<kF32, kMaskU8> : approx24_kernel<kF32, kMaskBits>;
+        else
+            kern = mf == kMaskU8 ? approx24_kernel<kBF16, kMaskU8> : approx24_kernel<kBF16, kMaskBits>;
+    }
     hipStream_t stream = (hipStream_t)stream_;
     uint32_t partial0 = 0;
     for (int first = 0; first < n_mats; first += kMaxBatch) {
