@@ -12,18 +12,6 @@
 
 namespace tmask {
 
-// A wavefront-wide boolean: bit l = the predicate in lane l.  Held in a scalar register pair, so
-// logic on it is scalar-ALU work.
-typedef unsigned long long lanemask_t;
-
-__device__ __forceinline__ lanemask_t lm(bool pred) { return __builtin_amdgcn_ballot_w64(pred); }
-__device__ __forceinline__ bool lm_test(lanemask_t m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
-
-__device__ __forceinline__ lanemask_t maj3(lanemask_t x, lanemask_t y, lanemask_t z)
-{
-    return (x & y) | (z & (x | y));
-}
-
 // keep masks of one line of four keys given in position order
 __device__ __forceinline__ void top2_of_4(uint32_t k0, uint32_t k1, uint32_t k2, uint32_t k3, lanemask_t &e0,
                                           lanemask_t &e1, lanemask_t &e2, lanemask_t &e3)

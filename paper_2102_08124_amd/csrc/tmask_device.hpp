@@ -71,6 +71,18 @@ __device__ __forceinline__ uint32_t quad_xor(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, ctrl, 0xF, 0xF, false);
 }
 
+// A wavefront-wide boolean: bit l = the predicate in lane l.  Held in a scalar register pair, so
+// logic on it is scalar-ALU work.
+typedef unsigned long long lanemask_t;
+
+__device__ __forceinline__ lanemask_t lm(bool pred) { return __builtin_amdgcn_ballot_w64(pred); }
+__device__ __forceinline__ bool lm_test(lanemask_t m) { return __builtin_amdgcn_inverse_ballot_w64(m); }
+
+__device__ __forceinline__ lanemask_t maj3(lanemask_t x, lanemask_t y, lanemask_t z)
+{
+    return (x & y) | (z & (x | y));
+}
+
 __device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll

@@ -12,6 +12,7 @@
 #include "tmask_solvers.hpp"
 #include "tmask_approx4.hpp"
 #include "tmask_pack.hpp"
+#include "tmask_pack4.hpp"
 
 namespace tmask {
 
@@ -617,8 +618,18 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
         if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
             return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 4-byte aligned", i);
     }
-    const pack_kernel_t kern = pick_pack_kernel((int)dt, M, (int)mf);
-    const uint32_t TC = 256 / (uint32_t)elem_size((int)dt);
+    pack_kernel_t kern = pick_pack_kernel((int)dt, M, (int)mf);
+    uint32_t TC = 256 / (uint32_t)elem_size((int)dt);
+    bool fast24 = (M == 4 && N == 2);
+    for (int i = 0; i < n && fast24; i++)
+        fast24 = (((uintptr_t)descs[i].vals | (uintptr_t)descs[i].valsT) & 7) == 0;
+    if (fast24) {
+        if (dt == TMASK_F32)
+            kern = mf == TMASK_MASK_U8 ? pack24_kernel<kF32, kMaskU8> : pack24_kernel<kF32, kMaskBits>;
+        else
+            kern = mf == TMASK_MASK_U8 ? pack24_kernel<kBF16, kMaskU8> : pack24_kernel<kBF16, kMaskBits>;
+        TC = kPack4Strips * 16 / (uint32_t)elem_size((int)dt);
+    }
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int first = 0; first < n; first += kMaxPackBatch) {
         const int nb = n - first < kMaxPackBatch ? n - first : kMaxPackBatch;
