@@ -1,0 +1,144 @@
+// Algorithm 1 (arXiv 2102.08124, Sec. 4) for bf16 weights with N = M/2, M in {8, 16}, as a
+// threshold test on unique keys.
+//
+// In rank form an entry is kept iff at least K of its row precede it and at least K of its column
+// do, in the (magnitude, row-major index) order.  A bf16 magnitude has 15 bits, so the order can be
+// folded into one 32-bit key: |w| << 16 | j inside a row (fixed i, order by (|w|, j)) and
+// |w| << 16 | i inside a column (order by (|w|, i)): exactly the tie-break of the sweep.  Keys of a
+// line are distinct, hence "at least K = M/2 precede" <=> key >= t, where t is the N-th largest key of the
+// line.  t comes from a small min/max network: sort both halves of the line, pair the i-th smallest
+// of one half with the i-th largest of the other (the larger of each pair is in the upper half of
+// the line), take the minimum of those.
+//     keep(i,j) <=> rowkey(i,j) >= t_row(i)  and  colkey(i,j) >= t_col(j)
+#pragma once
+#include "tmask_device.hpp"
+
+namespace tmask {
+
+__device__ __forceinline__ void cmpx(uint32_t &a, uint32_t &b)
+{
+    const uint32_t lo = a < b ? a : b;
+    const uint32_t hi = a < b ? b : a;
+    a = lo;
+    b = hi;
+}
+
+template <int N>
+__device__ __forceinline__ void sort_asc(uint32_t (&v)[N]);
+
+template <>
+__device__ __forceinline__ void sort_asc<4>(uint32_t (&v)[4])
+{
+    cmpx(v[0], v[1]); cmpx(v[2], v[3]); cmpx(v[0], v[2]); cmpx(v[1], v[3]); cmpx(v[1], v[2]);
+}
+
+template <>
+__device__ __forceinline__ void sort_asc<8>(uint32_t (&v)[8])
+{
+    cmpx(v[0], v[1]); cmpx(v[2], v[3]); cmpx(v[4], v[5]); cmpx(v[6], v[7]);
+    cmpx(v[0], v[2]); cmpx(v[1], v[3]); cmpx(v[4], v[6]); cmpx(v[5], v[7]);
+    cmpx(v[1], v[2]); cmpx(v[5], v[6]);
+    cmpx(v[0], v[4]); cmpx(v[1], v[5]); cmpx(v[2], v[6]); cmpx(v[3], v[7]);
+    cmpx(v[2], v[4]); cmpx(v[3], v[5]);
+    cmpx(v[1], v[2]); cmpx(v[3], v[4]); cmpx(v[5], v[6]);
+}
+
+// (H)-th largest of the 2H distinct keys lo[0..H) u hi[0..H): both halves get sorted in place.
+template <int H>
+__device__ __forceinline__ uint32_t upper_half_min(uint32_t (&a)[H], uint32_t (&b)[H])
+{
+    sort_asc<H>(a);
+    sort_asc<H>(b);
+    uint32_t t = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < H; i++) {
+        const uint32_t m = a[i] > b[H - 1 - i] ? a[i] : b[H - 1 - i];
+        t = m < t ? m : t;
+    }
+    return t;
+}
+
+// Same when the other half lives in the neighbouring lane (lane ^ 1): a = this lane's H keys.
+template <int H>
+__device__ __forceinline__ uint32_t upper_half_min_pair(uint32_t (&a)[H])
+{
+    sort_asc<H>(a);
+    uint32_t t = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < H; i++) {
+        const uint32_t o = quad_xor<1>(a[H - 1 - i]);
+        const uint32_t m = a[i] > o ? a[i] : o;
+        t = m < t ? m : t;
+    }
+    return t;
+}
+
+// Magnitude of column c (0..7) of a row held as four dwords, as the upper half of a 32-bit key.
+__device__ __forceinline__ uint32_t bf16_mag_hi(const u32x4 &r, int c)
+{
+    const uint32_t d = (c >> 1) == 0 ? r.x : (c >> 1) == 1 ? r.y : (c >> 1) == 2 ? r.z : r.w;
+    return (c & 1) ? (d & 0x7FFF0000u) : ((d << 16) & 0x7FFF0000u);
+}
+
+// bf16, M = 8 (one lane = one block) or M = 16 (two lanes = one block, 8 columns each).
+// raw[i] = the 16 bytes (8 bf16) of row i of the lane's strip; gpos = lane's position in its block.
+// Returns the kept magnitudes' sum; emit_row(i, b0, b1) receives the keep flags of row i as 0/1 bytes.
+// Keys are built where they are used (column keys carry the row index, row keys the column index)
+// so that only the raw rows stay live between the two passes.
+template <int M, typename EmitRow>
+__device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_t gpos, EmitRow emit_row)
+{
+    constexpr int H = M / 2;
+    // column thresholds: all M rows of a column are in the lane; key = |w| << 16 | i
+    uint32_t tcol[8];
+#pragma unroll
+    for (int c = 0; c < 8; c++) {
+        uint32_t a[H], b[H];
+#pragma unroll
+        for (int i = 0; i < H; i++) {
+            a[i] = bf16_mag_hi(raw[i], c) | (uint32_t)i;
+            b[i] = bf16_mag_hi(raw[H + i], c) | (uint32_t)(H + i);
+        }
+        tcol[c] = upper_half_min<H>(a, b);
+        __builtin_amdgcn_sched_barrier(0);   // keep one column's network together: bounds register use
+    }
+    const uint32_t j0 = (M == 16) ? gpos * 8u : 0u;
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        // row threshold: key = |w| << 16 | j.  The row's dwords pass through an empty asm so that the
+        // magnitudes are extracted again here instead of being kept in registers since the column pass.
+        u32x4 r = raw[i];
+        asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w));
+        uint32_t mag[8], a[8];
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            mag[c] = bf16_mag_hi(r, c);
+            a[c] = mag[c] | (j0 + (uint32_t)c);
+        }
+        uint32_t trow;
+        if constexpr (M == 8) {
+            uint32_t lo[4] = {a[0], a[1], a[2], a[3]};
+            uint32_t hi[4] = {a[4], a[5], a[6], a[7]};
+            trow = upper_half_min<4>(lo, hi);
+        } else {
+            uint32_t srt[8];
+#pragma unroll
+            for (int c = 0; c < 8; c++)
+                srt[c] = a[c];
+            trow = upper_half_min_pair<8>(srt);
+        }
+        uint32_t bytes[2] = {0u, 0u};
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            const bool keep = (a[c] >= trow) & ((mag[c] | (uint32_t)i) >= tcol[c]);
+            bytes[c >> 2] |= keep ? (1u << (8 * (c & 3))) : 0u;
+            sum += keep ? __uint_as_float(mag[c]) : 0.f;
+        }
+        emit_row(i, bytes[0], bytes[1]);
+        __builtin_amdgcn_sched_barrier(0);   // finish (and store) a row before the next one starts
+    }
+    return sum;
+}
+
+}  // namespace tmask

@@ -11,6 +11,7 @@
 #include "tmask_device.hpp"
 #include "tmask_solvers.hpp"
 #include "tmask_approx4.hpp"
+#include "tmask_approx_sel.hpp"
 #include "tmask_pack.hpp"
 #include "tmask_pack4.hpp"
 
@@ -117,6 +118,49 @@ __global__ __launch_bounds__(kThreads) void approx24_kernel(const BatchArgs args
         u32x4 raw[4];
         load_strip<DT, 4>(md, pos, a, raw);
         acc = (double)approx_2of4_strip<DT, FMT>(md, pos, a);
+    }
+    if (args.partials) {
+        const double t = block_sum(acc, red);
+        if (threadIdx.x == 0)
+            ((double *)args.partials)[args.partial0 + tile] = t;
+    }
+}
+
+// tmask_approx for bf16 with N = M/2, M = 8 or 16: thresholds from min/max networks on unique keys.
+template <int M, int FMT>
+__global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchArgs args)
+{
+    using Ge = Geo<kBF16, M>;
+    __shared__ double red[kThreads / 64];
+    const uint32_t tile = blockIdx.x;
+    const MatDev md = args.m[find_matrix(args, tile)];
+    const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
+    const uint32_t gpos = threadIdx.x & (Ge::G - 1);
+    double acc = 0.0;
+    if (s < md.n_strips) {
+        const StripPos pos = strip_pos(md, s);
+        u32x4 raw[M];
+        const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * 8) * 2;
+        const size_t row_bytes = (size_t)md.ld * 2;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
+        if constexpr (FMT == kMaskU8) {
+            char *mb = (char *)md.mask + (size_t)pos.br * M * md.mask_ld + (size_t)pos.sc * 8;
+            const uint32_t mld = md.mask_ld;
+            acc = (double)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+                u32x2 v;
+                v.x = b0;
+                v.y = b1;
+                __builtin_nontemporal_store(v, (u32x2 *)(mb + (size_t)i * mld));
+            });
+        } else {
+            uint32_t bits[M];
+            acc = (double)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+                bits[i] = bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4);
+            });
+            store_mask<kBF16, M, kMaskBits>(md, pos, bits);
+        }
     }
     if (args.partials) {
         const double t = block_sum(acc, red);
@@ -474,6 +518,10 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         else
             kern = mf == kMaskU8 ? approx24_kernel<kBF16, kMaskU8> : approx24_kernel<kBF16, kMaskBits>;
     }
+    if (SOLVER == kSolveApprox && dt == kBF16 && M == 8 && N == 4)
+        kern = mf == kMaskU8 ? approx_sel_bf16_kernel<8, kMaskU8> : approx_sel_bf16_kernel<8, kMaskBits>;
+    if (SOLVER == kSolveApprox && dt == kBF16 && M == 16 && N == 8)
+        kern = mf == kMaskU8 ? approx_sel_bf16_kernel<16, kMaskU8> : approx_sel_bf16_kernel<16, kMaskBits>;
     hipStream_t stream = (hipStream_t)stream_;
     uint32_t partial0 = 0;
     for (int first = 0; first < n_mats; first += kMaxBatch) {
