@@ -83,6 +83,13 @@ __device__ __forceinline__ lanemask_t maj3(lanemask_t x, lanemask_t y, lanemask_
     return (x & y) | (z & (x | y));
 }
 
+// r += 1 in the lanes whose bit is set in m: one add-with-carry-in, the carry being the lane mask.
+__device__ __forceinline__ void lm_inc(uint32_t &r, lanemask_t m)
+{
+    lanemask_t carry_out;
+    asm("v_addc_co_u32_e64 %0, %1, 0, %0, %2" : "+v"(r), "=s"(carry_out) : "s"(m));
+}
+
 __device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll

@@ -21,6 +21,32 @@ namespace tmask {
 // are static, "precedes" is `<=` against earlier positions and `<` against later ones.
 // =================================================================================================
 
+// rank bookkeeping for one ordered pair: `first` precedes `second` iff le.  Up to M = 8 the compare
+// result stays a lane mask and feeds two add-with-carry instructions; at M = 16 that form costs
+// registers and occupancy, plain 0/1 arithmetic is faster there.
+template <int M>
+__device__ __forceinline__ void rank_pair(bool le, uint32_t &r_first, uint32_t &r_second)
+{
+    if constexpr (M <= 8) {
+        const lanemask_t m = lm(le);
+        lm_inc(r_second, m);
+        lm_inc(r_first, ~m);
+    } else {
+        const uint32_t v = le ? 1u : 0u;
+        r_second += v;
+        r_first += 1u - v;
+    }
+}
+
+template <int M>
+__device__ __forceinline__ void rank_one(bool precedes, uint32_t &r)
+{
+    if constexpr (M <= 8)
+        lm_inc(r, lm(precedes));
+    else
+        r += precedes ? 1u : 0u;
+}
+
 // Column direction: all M rows of a column live in the lane.
 template <int M, int C>
 __device__ __forceinline__ void col_rank_keep(const uint32_t (&a)[M][C], uint32_t K, uint32_t (&bits)[M])
@@ -38,9 +64,7 @@ __device__ __forceinline__ void col_rank_keep(const uint32_t (&a)[M][C], uint32_
         for (int i = 0; i < M; i++)
 #pragma unroll
             for (int i2 = i + 1; i2 < M; i2++) {
-                const uint32_t le = a[i][c] <= a[i2][c] ? 1u : 0u;   // row i precedes row i2
-                r[i2] += le;
-                r[i] += 1u - le;
+                rank_pair<M>(a[i][c] <= a[i2][c], r[i], r[i2]);   // row i precedes row i2
             }
 #pragma unroll
         for (int i = 0; i < M; i++)
@@ -68,9 +92,7 @@ __device__ __forceinline__ void row_rank_keep(const uint32_t (&a)[M][C], uint32_
             for (int c = 0; c < CL; c++)
 #pragma unroll
                 for (int c2 = c + 1; c2 < CL; c2++) {
-                    const uint32_t le = a[i][b * CL + c] <= a[i][b * CL + c2] ? 1u : 0u;
-                    r[c2] += le;
-                    r[c] += 1u - le;
+                    rank_pair<M>(a[i][b * CL + c] <= a[i][b * CL + c2], r[c], r[c2]);
                 }
             if constexpr (G >= 2) {
                 // keys are < 2^31, so "theirs <= mine" is "theirs < mine + 1"
@@ -80,7 +102,7 @@ __device__ __forceinline__ void row_rank_keep(const uint32_t (&a)[M][C], uint32_
                     const uint32_t t = quad_xor<1>(a[i][c2]);
 #pragma unroll
                     for (int c = 0; c < CL; c++)
-                        r[c] += (t < a[i][c] + pb1) ? 1u : 0u;
+                        rank_one<M>(t < a[i][c] + pb1, r[c]);
                 }
             }
             if constexpr (G == 4) {
@@ -92,8 +114,8 @@ __device__ __forceinline__ void row_rank_keep(const uint32_t (&a)[M][C], uint32_
                     const uint32_t t3 = quad_xor<3>(a[i][c2]);
 #pragma unroll
                     for (int c = 0; c < CL; c++) {
-                        r[c] += (t2 < a[i][c] + pb2) ? 1u : 0u;
-                        r[c] += (t3 < a[i][c] + pb3) ? 1u : 0u;
+                        rank_one<M>(t2 < a[i][c] + pb2, r[c]);
+                        rank_one<M>(t3 < a[i][c] + pb3, r[c]);
                     }
                 }
             }
@@ -258,9 +280,7 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
         for (int i = 0; i < M; i++)
 #pragma unroll
             for (int i2 = i + 1; i2 < M; i2++) {
-                const uint32_t le = cost[i][c] <= cost[i2][c] ? 1u : 0u;
-                r[i2] += le;
-                r[i] += 1u - le;
+                rank_pair<M>(cost[i][c] <= cost[i2][c], r[i], r[i2]);
             }
         uint32_t x = 0;
 #pragma unroll
