@@ -44,24 +44,7 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
         if constexpr (SOLVER == kSolveApprox) {
             approx_keep<DT, M>(a, args.K, gpos, bits);
         } else if constexpr (M == 4) {
-            if (args.K == 2) {
-#pragma unroll
-                for (int i = 0; i < 4; i++)
-                    bits[i] = 0;
-#pragma unroll
-                for (int b = 0; b < Ge::B; b++) {
-                    float v[4][4];
-#pragma unroll
-                    for (int i = 0; i < 4; i++)
-#pragma unroll
-                        for (int c = 0; c < 4; c++)
-                            v[i][c] = __uint_as_float(a[i][b * 4 + c]);
-                    const uint32_t m16 = exact24_block(v);
-#pragma unroll
-                    for (int i = 0; i < 4; i++)
-                        bits[i] |= ((m16 >> (4 * i)) & 0xFu) << (4 * b);
-                }
-            } else {
+            {
 #pragma unroll
                 for (int i = 0; i < 4; i++)
                     bits[i] = 0;
@@ -118,6 +101,48 @@ __global__ __launch_bounds__(kThreads) void approx24_kernel(const BatchArgs args
         u32x4 raw[4];
         load_strip<DT, 4>(md, pos, a, raw);
         acc = (double)approx_2of4_strip<DT, FMT>(md, pos, a);
+    }
+    if (args.partials) {
+        const double t = block_sum(acc, red);
+        if (threadIdx.x == 0)
+            ((double *)args.partials)[args.partial0 + tile] = t;
+    }
+}
+
+// tmask_exact for 2:4: every block by enumeration (all 90 patterns), the kept sum comes with the optimum.
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
+{
+    using Ge = Geo<DT, 4>;
+    __shared__ double red[kThreads / 64];
+    const uint32_t tile = blockIdx.x;
+    const MatDev md = args.m[find_matrix(args, tile)];
+    const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
+    double acc = 0.0;
+    if (s < md.n_strips) {
+        const StripPos pos = strip_pos(md, s);
+        uint32_t a[4][Ge::C];
+        u32x4 raw[4];
+        uint32_t bits[4] = {0u, 0u, 0u, 0u};
+        load_strip<DT, 4>(md, pos, a, raw);
+        float sum = 0.f;
+#pragma unroll
+        for (int b = 0; b < Ge::B; b++) {
+            float v[4][4];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+#pragma unroll
+                for (int c = 0; c < 4; c++)
+                    v[i][c] = __uint_as_float(a[i][b * 4 + c]);
+            float best;
+            const uint32_t m16 = exact24_block(v, best);
+            sum += best;
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                bits[i] |= ((m16 >> (4 * i)) & 0xFu) << (4 * b);
+        }
+        store_mask<DT, 4, FMT>(md, pos, bits);
+        acc = (double)sum;
     }
     if (args.partials) {
         const double t = block_sum(acc, red);
@@ -517,6 +542,12 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             kern = mf == kMaskU8 ? approx24_kernel<kF32, kMaskU8> : approx24_kernel<kF32, kMaskBits>;
         else
             kern = mf == kMaskU8 ? approx24_kernel<kBF16, kMaskU8> : approx24_kernel<kBF16, kMaskBits>;
+    }
+    if (SOLVER == kSolveExact && M == 4 && N == 2) {
+        if (dt == kF32)
+            kern = mf == kMaskU8 ? exact24_kernel<kF32, kMaskU8> : exact24_kernel<kF32, kMaskBits>;
+        else
+            kern = mf == kMaskU8 ? exact24_kernel<kBF16, kMaskU8> : exact24_kernel<kBF16, kMaskBits>;
     }
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 8 && N == 4)
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<8, kMaskU8> : approx_sel_bf16_kernel<8, kMaskBits>;

@@ -1,6 +1,6 @@
 // Per-block solvers working on the strip layout (see tmask_device.hpp).
 //   approx_keep   : Algorithm 1 of arXiv 2102.08124 (Sec. 4) in rank form
-//   exact24_block : Eq. 1 optimum for 2:4 by enumeration of the 90 feasible patterns
+//   exact24_block : Eq. 1 optimum for 2:4 over all 90 feasible patterns (factored enumeration)
 //   exact_general : Eq. 1 optimum for any (N, M) by successive shortest augmenting paths on the
 //                   bipartite row/column network of Fig. 3
 #pragma once
@@ -183,9 +183,84 @@ constexpr uint32_t pattern_mask16(int k)
            (pair_bits(kPatterns24.p[k][2]) << 8) | (pair_bits(kPatterns24.p[k][3]) << 12);
 }
 
-// v[r][c] = |W| of one 4x4 block. Returns the 16-bit keep mask (row r in bits 4r..4r+3) of the
-// first pattern, in enumeration order, that attains the maximum kept sum.
-__device__ __forceinline__ uint32_t exact24_block(const float (&v)[4][4])
+// The 90 patterns factor through the column-count vector left by rows 0 and 1: a pattern is a pair
+// (p0, p1) for rows 0,1 with column counts v, and a pair (p2, p3) for rows 2,3 with counts 2 - v.
+// There are 19 such vectors (6 of type 2200 reached by one pair of pairs, 12 of type 2110 reached by
+// two, 1 of type 1111 reached by six: 6*1*1 + 12*2*2 + 1*6*6 = 90), so the optimum is
+//     max over v of  best01[v] + best23[2 - v],
+// with best01 / best23 the best pair sums of the upper / lower two rows for each vector: 72 sums and
+// 19 combinations instead of 90 four-term sums.
+struct Halves24 {
+    int vec_of[36];      // (p, q) -> index of the count vector of pair_bits(p) + pair_bits(q)
+    int first_of[36];    // 1 if (p, q) is the first pair of pairs with that vector (enumeration order)
+    int compl_of[19];    // index of the vector 2 - v
+    int n_vec;
+};
+
+constexpr int count_code(int p, int q)
+{
+    int code = 0, mul = 1;
+    for (int c = 0; c < 4; c++) {
+        code += mul * (int)(((pair_bits(p) >> c) & 1u) + ((pair_bits(q) >> c) & 1u));
+        mul *= 3;
+    }
+    return code;
+}
+
+constexpr Halves24 make_halves24()
+{
+    Halves24 h{};
+    int codes[36] = {};
+    h.n_vec = 0;
+    for (int k = 0; k < 36; k++) {
+        const int code = count_code(k / 6, k % 6);
+        int idx = -1;
+        for (int j = 0; j < h.n_vec; j++)
+            if (codes[j] == code)
+                idx = j;
+        h.first_of[k] = idx < 0 ? 1 : 0;
+        if (idx < 0) {
+            idx = h.n_vec;
+            codes[h.n_vec++] = code;
+        }
+        h.vec_of[k] = idx;
+    }
+    for (int j = 0; j < h.n_vec; j++) {
+        const int want = 80 - codes[j];       // (2,2,2,2) in base 3 is 80; digits never borrow
+        h.compl_of[j] = -1;
+        for (int i = 0; i < h.n_vec; i++)
+            if (codes[i] == want)
+                h.compl_of[j] = i;
+    }
+    return h;
+}
+
+constexpr Halves24 kHalves24 = make_halves24();
+static_assert(kHalves24.n_vec == 19, "rows 0,1 of a 2:4 pattern leave 19 possible column-count vectors");
+
+// Best pair of row patterns per count vector for rows (r, r+1): value and 8-bit mask (row r in bits 0..3).
+__device__ __forceinline__ void best_pairs24(const float (&pa)[6], const float (&pb)[6], float (&val)[19],
+                                             uint32_t (&msk)[19])
+{
+#pragma unroll
+    for (int k = 0; k < 36; k++) {
+        const int idx = kHalves24.vec_of[k];
+        const float s = pa[k / 6] + pb[k % 6];
+        const uint32_t m = pair_bits(k / 6) | (pair_bits(k % 6) << 4);
+        if (kHalves24.first_of[k]) {
+            val[idx] = s;
+            msk[idx] = m;
+        } else {
+            const bool better = s > val[idx];     // false for NaN: a feasible choice stays in place
+            val[idx] = better ? s : val[idx];
+            msk[idx] = better ? m : msk[idx];
+        }
+    }
+}
+
+// v[r][c] = |W| of one 4x4 block.  Returns the 16-bit keep mask (row r in bits 4r..4r+3) of an
+// optimal pattern (the first one in a fixed evaluation order) and its kept sum in `best`.
+__device__ __forceinline__ uint32_t exact24_block(const float (&v)[4][4], float &best)
 {
     float ps[4][6];
 #pragma unroll
@@ -193,19 +268,23 @@ __device__ __forceinline__ uint32_t exact24_block(const float (&v)[4][4])
 #pragma unroll
         for (int p = 0; p < 6; p++)
             ps[r][p] = v[r][kPairX[p]] + v[r][kPairY[p]];
-    float best = 0.f;
+    float top[19], bot[19];
+    uint32_t topm[19], botm[19];
+    best_pairs24(ps[0], ps[1], top, topm);
+    best_pairs24(ps[2], ps[3], bot, botm);
     uint32_t bm = 0;
 #pragma unroll
-    for (int k = 0; k < 90; k++) {
-        const float s = (ps[0][kPatterns24.p[k][0]] + ps[1][kPatterns24.p[k][1]]) +
-                        (ps[2][kPatterns24.p[k][2]] + ps[3][kPatterns24.p[k][3]]);
-        if (k == 0) {
+    for (int j = 0; j < 19; j++) {
+        const int jc = kHalves24.compl_of[j];
+        const float s = top[j] + bot[jc];
+        const uint32_t m = topm[j] | (botm[jc] << 8);
+        if (j == 0) {
             best = s;
-            bm = pattern_mask16(0);
+            bm = m;
         } else {
-            const bool better = s > best;        // false for NaN: the mask stays a feasible pattern
+            const bool better = s > best;
             best = better ? s : best;
-            bm = better ? pattern_mask16(k) : bm;
+            bm = better ? m : bm;
         }
     }
     return bm;
