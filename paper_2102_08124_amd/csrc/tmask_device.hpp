@@ -90,6 +90,36 @@ __device__ __forceinline__ void lm_inc(uint32_t &r, lanemask_t m)
     asm("v_addc_co_u32_e64 %0, %1, 0, %0, %2" : "+v"(r), "=s"(carry_out) : "s"(m));
 }
 
+// Wavefront sums by DPP, in a fixed order (deterministic): quad, then the four quads of a row of 16
+// lanes by row rotation, then the four rows through scalar reads.  All 64 lanes must be active.
+// The result is uniform.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_read(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += __uint_as_float(dpp_read<0xB1>(__float_as_uint(v)));    // quad_perm [1,0,3,2]
+    v += __uint_as_float(dpp_read<0x4E>(__float_as_uint(v)));    // quad_perm [2,3,0,1]
+    v += __uint_as_float(dpp_read<0x124>(__float_as_uint(v)));   // row_ror:4
+    v += __uint_as_float(dpp_read<0x128>(__float_as_uint(v)));   // row_ror:8
+    const uint32_t u = __float_as_uint(v);
+    return (__uint_as_float(__builtin_amdgcn_readlane(u, 0)) + __uint_as_float(__builtin_amdgcn_readlane(u, 16))) +
+           (__uint_as_float(__builtin_amdgcn_readlane(u, 32)) + __uint_as_float(__builtin_amdgcn_readlane(u, 48)));
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+    v += dpp_read<0xB1>(v);
+    v += dpp_read<0x4E>(v);
+    v += dpp_read<0x124>(v);
+    v += dpp_read<0x128>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+
 __device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll
@@ -120,6 +150,21 @@ __device__ __forceinline__ T block_sum(T v, T *lds /* kThreads/64 entries */)
     for (int k = 1; k < kThreads / 64; k++)
         r += lds[k];
     __syncthreads();
+    return r;
+}
+
+// Workgroup sum of per-thread fp32 values: fp32 inside a wavefront, fp64 across wavefronts.
+__device__ __forceinline__ double block_sum_f32(float v, double *lds /* kThreads/64 entries */)
+{
+    const float w = wave_sum(v);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0)
+        lds[wave] = (double)w;
+    __syncthreads();
+    double r = lds[0];
+#pragma unroll
+    for (int k = 1; k < kThreads / 64; k++)
+        r += lds[k];
     return r;
 }
 

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
     const MatDev md = args.m[find_matrix(args, tile)];
     const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
     const uint32_t gpos = threadIdx.x & (Ge::G - 1);
-    double acc = 0.0;
+    float acc = 0.f;
     if (s < md.n_strips) {
         const StripPos pos = strip_pos(md, s);
         uint32_t a[M][Ge::C];
@@ -76,10 +76,10 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
             }
         }
         store_mask<DT, M, FMT>(md, pos, bits);
-        acc = (double)kept_sum<M, Ge::C>(a, bits);
+        acc = kept_sum<M, Ge::C>(a, bits);
     }
     if (args.partials) {
-        const double t = block_sum(acc, red);
+        const double t = block_sum_f32(acc, red);
         if (threadIdx.x == 0)
             ((double *)args.partials)[args.partial0 + tile] = t;
     }
@@ -94,16 +94,16 @@ __global__ __launch_bounds__(kThreads) void approx24_kernel(const BatchArgs args
     const uint32_t tile = blockIdx.x;
     const MatDev md = args.m[find_matrix(args, tile)];
     const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
-    double acc = 0.0;
+    float acc = 0.f;
     if (s < md.n_strips) {
         const StripPos pos = strip_pos(md, s);
         uint32_t a[4][Ge::C];
         u32x4 raw[4];
         load_strip<DT, 4>(md, pos, a, raw);
-        acc = (double)approx_2of4_strip<DT, FMT>(md, pos, a);
+        acc = approx_2of4_strip<DT, FMT>(md, pos, a);
     }
     if (args.partials) {
-        const double t = block_sum(acc, red);
+        const double t = block_sum_f32(acc, red);
         if (threadIdx.x == 0)
             ((double *)args.partials)[args.partial0 + tile] = t;
     }
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
     const uint32_t tile = blockIdx.x;
     const MatDev md = args.m[find_matrix(args, tile)];
     const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
-    double acc = 0.0;
+    float acc = 0.f;
     if (s < md.n_strips) {
         const StripPos pos = strip_pos(md, s);
         uint32_t a[4][Ge::C];
@@ -142,10 +142,10 @@ __global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
                 bits[i] |= ((m16 >> (4 * i)) & 0xFu) << (4 * b);
         }
         store_mask<DT, 4, FMT>(md, pos, bits);
-        acc = (double)sum;
+        acc = sum;
     }
     if (args.partials) {
-        const double t = block_sum(acc, red);
+        const double t = block_sum_f32(acc, red);
         if (threadIdx.x == 0)
             ((double *)args.partials)[args.partial0 + tile] = t;
     }
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
     const MatDev md = args.m[find_matrix(args, tile)];
     const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
     const uint32_t gpos = threadIdx.x & (Ge::G - 1);
-    double acc = 0.0;
+    float acc = 0.f;
     if (s < md.n_strips) {
         const StripPos pos = strip_pos(md, s);
         u32x4 raw[M];
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
         if constexpr (FMT == kMaskU8) {
             char *mb = (char *)md.mask + (size_t)pos.br * M * md.mask_ld + (size_t)pos.sc * 8;
             const uint32_t mld = md.mask_ld;
-            acc = (double)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+            acc = approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
                 u32x2 v;
                 v.x = b0;
                 v.y = b1;
@@ -181,14 +181,14 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
             });
         } else {
             uint32_t bits[M];
-            acc = (double)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+            acc = approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
                 bits[i] = bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4);
             });
             store_mask<kBF16, M, kMaskBits>(md, pos, bits);
         }
     }
     if (args.partials) {
-        const double t = block_sum(acc, red);
+        const double t = block_sum_f32(acc, red);
         if (threadIdx.x == 0)
             ((double *)args.partials)[args.partial0 + tile] = t;
     }
@@ -228,15 +228,15 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
 {
     using Ge = Geo<DT, M>;
     constexpr int C = Ge::C, CL = Ge::CL;
-    __shared__ double redd[kThreads / 64];
-    __shared__ unsigned long long redu[kThreads / 64];
+    __shared__ double redd[kThreads / 64][2];
+    __shared__ uint32_t redu[kThreads / 64][5];
     const uint32_t tile = blockIdx.x;
     const MatDev md = args.m[find_matrix(args, tile)];
     const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
     const uint32_t gpos = threadIdx.x & (Ge::G - 1);
     const uint32_t N = args.N;
-    double retained = 0.0, total = 0.0;
-    unsigned long long kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
+    float retained = 0.f, total = 0.f;
+    uint32_t kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
     if (s < md.n_strips) {
         const StripPos pos = strip_pos(md, s);
         uint32_t a[M][C];
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
 #pragma unroll
             for (int c = 0; c < C; c++)
                 tot += __uint_as_float(a[i][c]);
-        total = (double)tot;
+        total = tot;
         // columns: lane-local
 #pragma unroll
         for (int c = 0; c < C; c++) {
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
                 for (int c = 0; c < CL; c++)
                     blk += ((bits[i] >> (b * CL + c)) & 1u) ? __uint_as_float(a[i][b * CL + c]) : 0.f;
             }
-            retained += (double)blk;
+            retained += blk;
             if constexpr (Ge::G >= 2)
                 blk += __uint_as_float(quad_xor<1>(__float_as_uint(blk)));
             if constexpr (Ge::G == 4)
@@ -294,17 +294,38 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
             }
         }
     }
-    ScorePartial *out = (ScorePartial *)args.partials + args.partial0 + tile;
-    const double r0 = block_sum(retained, redd);
-    const double r1 = block_sum(total, redd);
-    const unsigned long long u0 = block_sum(kept, redu);
-    const unsigned long long u1 = block_sum(rowv, redu);
-    const unsigned long long u2 = block_sum(colv, redu);
-    const unsigned long long u3 = block_sum(rowne, redu);
-    const unsigned long long u4 = block_sum(colne, redu);
+    // One reduction pass: fp32 / packed 32-bit counts inside a wavefront (a lane contributes at most
+    // 128 kept, 16 row events and 8 column events, so 16-bit fields cannot overflow over 64 lanes),
+    // then the four wavefronts in fp64 / 64-bit through LDS.
+    const float w_ret = wave_sum(retained), w_tot = wave_sum(total);
+    const uint32_t w_a = wave_sum(kept | (rowv << 16));
+    const uint32_t w_b = wave_sum(colv | (colne << 16));
+    const uint32_t w_c = wave_sum(rowne);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        redd[wave][0] = (double)w_ret;
+        redd[wave][1] = (double)w_tot;
+        redu[wave][0] = w_a & 0xFFFFu;
+        redu[wave][1] = w_a >> 16;
+        redu[wave][2] = w_b & 0xFFFFu;
+        redu[wave][3] = w_c;
+        redu[wave][4] = w_b >> 16;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+        ScorePartial *out = (ScorePartial *)args.partials + args.partial0 + tile;
+        double r0 = 0.0, r1 = 0.0;
+        unsigned long long u[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < kThreads / 64; k++) {
+            r0 += redd[k][0];
+            r1 += redd[k][1];
+#pragma unroll
+            for (int q = 0; q < 5; q++)
+                u[q] += redu[k][q];
+        }
         out->retained = r0; out->total = r1;
-        out->kept = u0; out->rowv = u1; out->colv = u2; out->rowne = u3; out->colne = u4;
+        out->kept = u[0]; out->rowv = u[1]; out->colv = u[2]; out->rowne = u[3]; out->colne = u[4];
     }
 }
 
