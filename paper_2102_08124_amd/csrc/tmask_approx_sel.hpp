@@ -141,4 +141,117 @@ __device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_
     return sum;
 }
 
+
+// =================================================================================================
+// fp32, N = M/2, M = 8 or 16.  A 31-bit magnitude leaves no room for the index, so thresholds are
+// taken on magnitudes alone: t = N-th largest of a line, u = (N+1)-th largest.  If t > u in every
+// line of the strip, "key >= t" is exactly the rank test (no tie straddles the cut).  If some line has
+// t == u the index order matters there; the caller then redoes the strip with the rank form.
+// A line of a column (M rows) is lane-local; a line of a row is spread over G = M/4 lanes.
+// =================================================================================================
+
+// Both order statistics around the middle of 2H values held as two halves (sorted in place).
+template <int H>
+__device__ __forceinline__ void middle_pair(uint32_t (&a)[H], uint32_t (&b)[H], uint32_t &t, uint32_t &u)
+{
+    sort_asc<H>(a);
+    sort_asc<H>(b);
+    t = 0xFFFFFFFFu;
+    u = 0u;
+#pragma unroll
+    for (int i = 0; i < H; i++) {
+        const uint32_t x = a[i], y = b[H - 1 - i];
+        const uint32_t hi = x > y ? x : y, lo = x > y ? y : x;
+        t = hi < t ? hi : t;
+        u = lo > u ? lo : u;
+    }
+}
+
+// Row of 8 over two lanes (4 values each).
+__device__ __forceinline__ void middle_pair_row8(uint32_t (&s)[4], uint32_t &t, uint32_t &u)
+{
+    sort_asc<4>(s);
+    t = 0xFFFFFFFFu;
+    u = 0u;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const uint32_t y = quad_xor<1>(s[3 - i]);
+        const uint32_t hi = s[i] > y ? s[i] : y, lo = s[i] > y ? y : s[i];
+        t = hi < t ? hi : t;
+        u = lo > u ? lo : u;
+    }
+}
+
+// Row of 16 over four lanes (4 values each): merge lane pairs into sorted runs of 8, then split the
+// two runs against each other.
+__device__ __forceinline__ void middle_pair_row16(uint32_t (&s)[4], uint32_t gpos, uint32_t &t, uint32_t &u)
+{
+    sort_asc<4>(s);
+    const bool upper = (gpos & 1u) != 0u;     // this lane keeps the larger half of its pair
+    uint32_t m[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const uint32_t y = quad_xor<1>(s[3 - i]);
+        const uint32_t hi = s[i] > y ? s[i] : y, lo = s[i] > y ? y : s[i];
+        m[i] = upper ? hi : lo;
+    }
+    // m is bitonic: two merge stages sort it
+    cmpx(m[0], m[2]); cmpx(m[1], m[3]); cmpx(m[0], m[1]); cmpx(m[2], m[3]);
+    uint32_t tl = 0xFFFFFFFFu, ul = 0u;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const uint32_t y = quad_xor<3>(m[3 - i]);
+        const uint32_t hi = m[i] > y ? m[i] : y, lo = m[i] > y ? y : m[i];
+        tl = hi < tl ? hi : tl;
+        ul = lo > ul ? lo : ul;
+    }
+    const uint32_t to = quad_xor<1>(tl), uo = quad_xor<1>(ul);
+    t = to < tl ? to : tl;
+    u = uo > ul ? uo : ul;
+}
+
+// a[i][c] = magnitude keys of the lane's strip (4 columns).  Fills bits[i] (bit c = keep) and the
+// kept sum; returns true if some line had a tie across its cut (result then invalid).
+template <int M>
+__device__ __forceinline__ bool approx_half_f32(const uint32_t (&a)[M][4], uint32_t gpos, uint32_t (&rowbytes)[M],
+                                                float &sum)
+{
+    constexpr int H = M / 2;
+    uint32_t tcol[4];
+    bool tie = false;
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        uint32_t lo[H], hi[H], u;
+#pragma unroll
+        for (int i = 0; i < H; i++) {
+            lo[i] = a[i][c];
+            hi[i] = a[H + i][c];
+        }
+        middle_pair<H>(lo, hi, tcol[c], u);
+        tie |= tcol[c] == u;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        uint32_t s[4] = {a[i][0], a[i][1], a[i][2], a[i][3]};
+        uint32_t trow, u;
+        if constexpr (M == 8)
+            middle_pair_row8(s, trow, u);
+        else
+            middle_pair_row16(s, gpos, trow, u);
+        tie |= trow == u;
+        uint32_t bytes = 0;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            const bool keep = (a[i][c] >= trow) & (a[i][c] >= tcol[c]);
+            bytes |= keep ? (1u << (8 * c)) : 0u;
+            sum += keep ? __uint_as_float(a[i][c]) : 0.f;
+        }
+        rowbytes[i] = bytes;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    return tie;
+}
+
 }  // namespace tmask

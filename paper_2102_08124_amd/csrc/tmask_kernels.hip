@@ -109,6 +109,49 @@ __global__ __launch_bounds__(kThreads) void approx24_kernel(const BatchArgs args
     }
 }
 
+// tmask_approx for fp32 with N = M/2, M = 8 or 16: thresholds on magnitudes; a wavefront in which some
+// line has a tie across its cut redoes its strips with the rank form (uniform branch).
+template <int M, int FMT>
+__global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArgs args)
+{
+    using Ge = Geo<kF32, M>;
+    __shared__ double red[kThreads / 64];
+    const uint32_t tile = blockIdx.x;
+    const MatDev md = args.m[find_matrix(args, tile)];
+    const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
+    const uint32_t gpos = threadIdx.x & (Ge::G - 1);
+    float acc = 0.f;
+    if (s < md.n_strips) {
+        const StripPos pos = strip_pos(md, s);
+        uint32_t a[M][4];
+        u32x4 raw[M];
+        load_strip<kF32, M>(md, pos, a, raw);
+        uint32_t rowbytes[M];
+        const bool tie = approx_half_f32<M>(a, gpos, rowbytes, acc);
+        uint32_t bits[M];
+        if (__any(tie)) {
+            approx_keep<kF32, M>(a, (uint32_t)(M / 2), gpos, bits);
+            acc = kept_sum<M, 4>(a, bits);
+            store_mask<kF32, M, FMT>(md, pos, bits);
+        } else if constexpr (FMT == kMaskU8) {
+            char *mb = (char *)md.mask + (size_t)pos.br * M * md.mask_ld + (size_t)pos.sc * 4;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                __builtin_nontemporal_store(rowbytes[i], (uint32_t *)(mb + (size_t)i * md.mask_ld));
+        } else {
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                bits[i] = bytes4_to_bits(rowbytes[i]);
+            store_mask<kF32, M, kMaskBits>(md, pos, bits);
+        }
+    }
+    if (args.partials) {
+        const double t = block_sum_f32(acc, red);
+        if (threadIdx.x == 0)
+            ((double *)args.partials)[args.partial0 + tile] = t;
+    }
+}
+
 // tmask_exact for 2:4: every block by enumeration (all 90 patterns), the kept sum comes with the optimum.
 template <int DT, int FMT>
 __global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
@@ -210,10 +253,21 @@ __global__ __launch_bounds__(kThreads) void objective_reduce_kernel(const Reduce
     double *dst = args.objective[m];
     if (!dst)
         return;
-    double acc = 0.0;
-    for (uint32_t t = args.tile0[m] + threadIdx.x; t < args.tile0[m + 1]; t += kThreads)
-        acc += args.partials[args.partial0 + t];
-    const double total = block_sum(acc, red);
+    // four independent partial sums per thread keep several loads in flight (one matrix can have
+    // tens of thousands of partials); the order of additions is fixed
+    const uint32_t t0 = args.tile0[m], t1 = args.tile0[m + 1];
+    const double *src = args.partials + args.partial0;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    uint32_t t = t0 + threadIdx.x;
+    for (; t + 3 * kThreads < t1; t += 4 * kThreads) {
+        a0 += src[t];
+        a1 += src[t + kThreads];
+        a2 += src[t + 2 * kThreads];
+        a3 += src[t + 3 * kThreads];
+    }
+    for (; t < t1; t += kThreads)
+        a0 += src[t];
+    const double total = block_sum((a0 + a1) + (a2 + a3), red);
     if (threadIdx.x == 0)
         dst[0] = total;
 }
@@ -570,6 +624,10 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         else
             kern = mf == kMaskU8 ? exact24_kernel<kBF16, kMaskU8> : exact24_kernel<kBF16, kMaskBits>;
     }
+    if (SOLVER == kSolveApprox && dt == kF32 && M == 8 && N == 4)
+        kern = mf == kMaskU8 ? approx_sel_f32_kernel<8, kMaskU8> : approx_sel_f32_kernel<8, kMaskBits>;
+    if (SOLVER == kSolveApprox && dt == kF32 && M == 16 && N == 8)
+        kern = mf == kMaskU8 ? approx_sel_f32_kernel<16, kMaskU8> : approx_sel_f32_kernel<16, kMaskBits>;
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 8 && N == 4)
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<8, kMaskU8> : approx_sel_bf16_kernel<8, kMaskBits>;
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 16 && N == 8)

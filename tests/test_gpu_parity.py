@@ -67,6 +67,27 @@ def test_approx_other_n(N, M):
         assert obj[0] == pytest.approx(oobj, rel=1e-5)
 
 
+@pytest.mark.parametrize("N,M", NM)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_approx_sparse_ties_inside_random_data(dt, N, M):
+    # mostly distinct magnitudes with a few tied lines: the fp32 threshold kernels must notice a tie across the
+    # cut in single lanes of a wavefront and fall back to the rank form there
+    w = wl.gaussian_f32(4 * M, 1024, seed=1500 + M)
+    rng = np.random.default_rng(1501)
+    for _ in range(40):
+        r, c = int(rng.integers(0, w.shape[0])), int(rng.integers(0, w.shape[1] - M))
+        w[r, c:c + M] = np.float32(0.5) * np.sign(w[r, c:c + M] + np.float32(1e-9))      # one tied row segment
+    for _ in range(40):
+        r, c = int(rng.integers(0, w.shape[0] - M)), int(rng.integers(0, w.shape[1]))
+        w[r:r + M, c] = 0.0                                                               # one zero column segment
+    if dt == "bf16":
+        w = wl.f32_to_bf16_bits(w)
+    (mask,), obj = run_masks(tm.tmask_approx, [w], N, M)
+    omask, oobj = oracle.approx(w, N, M)
+    assert np.array_equal(mask, omask)
+    assert obj[0] == pytest.approx(oobj, rel=1e-5)
+
+
 def test_approx_config1():
     w = wl.config1()
     (mask,), obj = run_masks(tm.tmask_approx, [w], 2, 4)
