@@ -42,40 +42,25 @@ struct Log2 {
     static constexpr int v = (M == 4) ? 2 : (M == 8) ? 3 : 4;
 };
 
-// Compacts one group. v[p] = masked value of position p, kbits = keep flags (bit p).
-// Calls emit(slot, value) for each of the N slots in position order and returns the slot positions
-// packed IB bits per slot (slot-major, LSB first).
-template <int M, typename T, typename Emit>
-__device__ __forceinline__ unsigned long long compact_group(const T (&v)[M], uint32_t kbits, uint32_t N, Emit emit)
+// Which positions of a group of M fill its N slots.  kbits = keep flags (bit p = position p).
+// sel    = kept positions that get a slot: all of them, or the first N if the mask (wrongly) keeps more;
+// chosen = sel plus, if fewer than N are kept, the lowest-numbered other positions as +0 fillers.
+template <int M>
+__device__ __forceinline__ void choose_slots(uint32_t kbits, uint32_t N, uint32_t &sel, uint32_t &chosen)
 {
-    constexpr int IB = Log2<M>::v;
-    // kept entries beyond the N-th are dropped (a mask with more than N per group is a caller error)
-    uint32_t sel = 0, cnt = 0;
-#pragma unroll
-    for (int p = 0; p < M; p++) {
-        const uint32_t take = ((kbits >> p) & 1u) & (cnt < N ? 1u : 0u);
-        sel |= take << p;
-        cnt += take;
+    sel = kbits;
+    uint32_t cnt = (uint32_t)__builtin_popcount(sel);
+    while (cnt > N) {                                   // caller error, rare: drop the highest kept position
+        sel &= ~(0x80000000u >> __builtin_clz(sel));
+        cnt--;
     }
-    // fillers: lowest-numbered positions that are not selected, until N slots are used
-    uint32_t fill = N - cnt, chosen = sel;
-#pragma unroll
-    for (int p = 0; p < M; p++) {
-        const uint32_t take = (((sel >> p) & 1u) ^ 1u) & (fill > 0 ? 1u : 0u);
-        chosen |= take << p;
-        fill -= take;
+    uint32_t z = ~sel & ((1u << M) - 1u), f = 0;
+    for (uint32_t need = N - cnt; need > 0; need--) {   // approximate masks: usually zero to two rounds
+        const uint32_t low = z & (0u - z);
+        f |= low;
+        z ^= low;
     }
-    unsigned long long code = 0;
-    uint32_t slot = 0;
-#pragma unroll
-    for (int p = 0; p < M; p++) {
-        if ((chosen >> p) & 1u) {
-            emit(slot, ((sel >> p) & 1u) ? v[p] : (T)0);
-            code |= (unsigned long long)p << (slot * IB);
-            slot++;
-        }
-    }
-    return code;
+    chosen = sel | f;
 }
 
 // ORs `nbits` (<= 60) bits of `code` into an LDS bit string at bit offset `off`.
@@ -110,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
     constexpr int NCU = BPT * TC / kThreads;   // column-direction units per thread
     static_assert(TR * GPT % kThreads == 0 && BPT * TC % kThreads == 0, "units must tile the workgroup");
 
-    __shared__ __attribute__((aligned(16))) T V[TR][TC];   // masked tile; later the W staging OV
+    __shared__ __attribute__((aligned(16))) T V[TR][TC];   // masked tile
     __shared__ __attribute__((aligned(16))) uint8_t FB[TR][TC];
     __shared__ T OT[TC][OTP];
     __shared__ uint32_t IDX[TR][IDXW];
@@ -183,83 +168,78 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
     }
     __syncthreads();
 
-    // ---- C: units into registers ----
-    T rv[NRU][M], cv[NCU][M];
-    uint32_t rk[NRU], ck[NCU];
+    // ---- E: compact.  Row units write W's values straight to memory (consecutive threads own
+    // consecutive groups of a row); column units park W^T's values in LDS, column-major. ----
+    {
+        const size_t pitch = (size_t)(d.cols / M) * N;            // elements per row of vals
+        const bool pair_ok = ES == 2 && ((N | (uint32_t)pitch) & 1u) == 0;
 #pragma unroll
-    for (int k = 0; k < NRU; k++) {
-        const uint32_t u = tid + k * kThreads, r = u / GPT, g = u % GPT;
-        rk[k] = 0;
+        for (int k = 0; k < NRU; k++) {
+            const uint32_t u = tid + k * kThreads, r = u / GPT, g = u % GPT;
+            if (r >= r_valid || g >= g_valid)
+                continue;   // outside the matrix: must not leave index bits in a row's padding
+            uint32_t kb = 0;
 #pragma unroll
-        for (int p = 0; p < M; p++) {
-            rv[k][p] = V[r][g * M + p];
-            rk[k] |= (uint32_t)FB[r][g * M + p] << p;
+            for (int q = 0; q < M / 4; q++)
+                kb |= bytes4_to_bits(*(const uint32_t *)&FB[r][g * M + 4 * q]) << (4 * q);
+            uint32_t sel, rem;
+            choose_slots<M>(kb, N, sel, rem);
+            T *dst = (T *)d.vals + (size_t)(row0 + r) * pitch + (size_t)(col0 / M + g) * N;
+            unsigned long long code = 0;
+            uint32_t pend = 0;
+            for (uint32_t sl = 0; sl < N; sl++) {
+                const uint32_t p = (uint32_t)__builtin_ctz(rem);
+                rem &= rem - 1u;
+                const uint32_t val = ((sel >> p) & 1u) ? (uint32_t)V[r][g * M + p] : 0u;
+                if constexpr (ES == 4) {
+                    ((uint32_t *)dst)[sl] = val;
+                } else if (pair_ok) {
+                    if (sl & 1u)
+                        *(uint32_t *)(dst + sl - 1) = pend | (val << 16);
+                    else
+                        pend = val;
+                } else {
+                    dst[sl] = (T)val;
+                }
+                code |= (unsigned long long)p << (sl * IB);
+            }
+            lds_or_bits(IDX[r], g * N * IB, code);
         }
-    }
-#pragma unroll
-    for (int k = 0; k < NCU; k++) {
-        const uint32_t u = tid + k * kThreads, b = u / TC, c = u % TC;
-        ck[k] = 0;
-#pragma unroll
-        for (int p = 0; p < M; p++) {
-            cv[k][p] = V[b * M + p][c];
-            ck[k] |= (uint32_t)FB[b * M + p][c] << p;
-        }
-    }
-    __syncthreads();
-
-    // ---- E: compact and scatter into staging ----
-    T(*OV)[TC] = V;
-#pragma unroll
-    for (int k = 0; k < NRU; k++) {
-        const uint32_t u = tid + k * kThreads, r = u / GPT, g = u % GPT;
-        if (r >= r_valid || g >= g_valid)
-            continue;   // outside the matrix: must not leave index bits in a row's padding
-        const unsigned long long code =
-            compact_group<M, T>(rv[k], rk[k], N, [&](uint32_t slot, T val) { OV[r][g * N + slot] = val; });
-        lds_or_bits(IDX[r], g * N * IB, code);
     }
 #pragma unroll
     for (int k = 0; k < NCU; k++) {
         const uint32_t u = tid + k * kThreads, b = u / TC, c = u % TC;
         if (b >= b_valid || c >= c_valid)
             continue;
-        const unsigned long long code =
-            compact_group<M, T>(cv[k], ck[k], N, [&](uint32_t slot, T val) { OT[c][b * N + slot] = val; });
+        uint32_t kb = 0;
+#pragma unroll
+        for (int p = 0; p < M; p++)
+            kb |= (uint32_t)FB[b * M + p][c] << p;
+        uint32_t sel, rem;
+        choose_slots<M>(kb, N, sel, rem);
+        unsigned long long code = 0;
+        for (uint32_t sl = 0; sl < N; sl++) {
+            const uint32_t p = (uint32_t)__builtin_ctz(rem);
+            rem &= rem - 1u;
+            OT[c][b * N + sl] = ((sel >> p) & 1u) ? V[b * M + p][c] : (T)0;
+            code |= (unsigned long long)p << (sl * IB);
+        }
         lds_or_bits(IDXT[c], b * N * IB, code);
     }
     __syncthreads();
 
-    // ---- G: stream out ----
-    {
-        // vals: r_valid rows, g_valid*N elements each
-        const uint32_t run = g_valid * N;
-        const size_t pitch = (size_t)(d.cols / M) * N;               // elements per output row
-        T *dst = (T *)d.vals + (size_t)row0 * pitch + (size_t)(col0 / M) * N;
-        if (ES == 4 || (((run | (uint32_t)pitch | (uint32_t)((col0 / M) * N)) & 1u) == 0)) {
-            const uint32_t rd = run * ES / 4;
-            for (uint32_t k = tid; k < r_valid * rd; k += kThreads) {
-                const uint32_t r = k / rd, x = k - r * rd;
-                ((uint32_t *)(dst + (size_t)r * pitch))[x] = ((const uint32_t *)&OV[r][0])[x];
-            }
-        } else {
-            for (uint32_t k = tid; k < r_valid * run; k += kThreads) {
-                const uint32_t r = k / run, x = k - r * run;
-                dst[(size_t)r * pitch + x] = OV[r][x];
-            }
-        }
-    }
+    // ---- G: stream the staged W^T values and both index arrays out (row-per-lane-group, no divisions) ----
     {
         // valsT: c_valid rows (columns of W), b_valid*N elements each
         const uint32_t run = b_valid * N;
         const size_t pitch = (size_t)(d.rows / M) * N;
         T *dst = (T *)d.valsT + (size_t)col0 * pitch + (size_t)(row0 / M) * N;
         if (ES == 4 || (((run | (uint32_t)pitch | (uint32_t)((row0 / M) * N)) & 1u) == 0)) {
-            const uint32_t rd = run * ES / 4;
-            for (uint32_t k = tid; k < c_valid * rd; k += kThreads) {
-                const uint32_t c = k / rd, x = k - c * rd;
-                ((uint32_t *)(dst + (size_t)c * pitch))[x] = ((const uint32_t *)&OT[c][0])[x];
-            }
+            constexpr uint32_t LW = ES == 4 ? 64 : 32;       // lanes per output row (a run has at most LW dwords)
+            const uint32_t rd = run * ES / 4, x = tid % LW;
+            if (x < rd)
+                for (uint32_t c = tid / LW; c < c_valid; c += kThreads / LW)
+                    ((uint32_t *)(dst + (size_t)c * pitch))[x] = ((const uint32_t *)&OT[c][0])[x];
         } else {
             for (uint32_t k = tid; k < c_valid * run; k += kThreads) {
                 const uint32_t c = k / run, x = k - c * run;
@@ -269,22 +249,22 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
     }
     {
         // idx: per row, the tile's bit string starts on a byte boundary (GPT*N*IB is a multiple of 8)
+        constexpr uint32_t LW = IDXW * 4 <= 32 ? 32 : 64;
         const size_t pitch = ((size_t)(d.cols / M) * N * IB + 7) / 8;
-        const uint32_t nbytes = (g_valid * N * IB + 7) / 8;
+        const uint32_t nbytes = (g_valid * N * IB + 7) / 8, x = tid % LW;
         unsigned char *dst = (unsigned char *)d.idx + (size_t)row0 * pitch + ((size_t)(col0 / M) * N * IB) / 8;
-        for (uint32_t k = tid; k < r_valid * nbytes; k += kThreads) {
-            const uint32_t r = k / nbytes, x = k - r * nbytes;
-            dst[(size_t)r * pitch + x] = ((const unsigned char *)&IDX[r][0])[x];
-        }
+        if (x < nbytes)
+            for (uint32_t r = tid / LW; r < r_valid; r += kThreads / LW)
+                dst[(size_t)r * pitch + x] = ((const unsigned char *)&IDX[r][0])[x];
     }
     {
+        constexpr uint32_t LW = IDXTW * 4 <= 32 ? 32 : 64;
         const size_t pitch = ((size_t)(d.rows / M) * N * IB + 7) / 8;
-        const uint32_t nbytes = (b_valid * N * IB + 7) / 8;
+        const uint32_t nbytes = (b_valid * N * IB + 7) / 8, x = tid % LW;
         unsigned char *dst = (unsigned char *)d.idxT + (size_t)col0 * pitch + ((size_t)(row0 / M) * N * IB) / 8;
-        for (uint32_t k = tid; k < c_valid * nbytes; k += kThreads) {
-            const uint32_t c = k / nbytes, x = k - c * nbytes;
-            dst[(size_t)c * pitch + x] = ((const unsigned char *)&IDXT[c][0])[x];
-        }
+        if (x < nbytes)
+            for (uint32_t c = tid / LW; c < c_valid; c += kThreads / LW)
+                dst[(size_t)c * pitch + x] = ((const unsigned char *)&IDXT[c][0])[x];
     }
 }
 
