@@ -5,6 +5,7 @@
 //                   bipartite row/column network of Fig. 3
 #pragma once
 #include "tmask_device.hpp"
+#include "tmask_networks.hpp"
 
 namespace tmask {
 
@@ -314,6 +315,14 @@ constexpr int kInfDist = 0x70000000;   // unreachable label; kInfDist - 2^S is s
 constexpr int kReachable = 0x40000000; // every real label is below this: |label| <= (M-1) * 2^S < 2^30
 constexpr uint32_t kNoPred = 0xFFFFFFFFu;
 
+// r = lane-mask bit set ? a : b as exactly one v_cndmask (mask in a scalar register pair).
+__device__ __forceinline__ uint32_t lm_pick(lanemask_t m, uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(b), "v"(a), "s"(m));
+    return r;
+}
+
 template <int M, int CL, int G>
 __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint32_t K, uint32_t gpos,
                                               uint32_t (&xcol)[CL])
@@ -348,78 +357,116 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
             cost[i][c] = sh < 32u ? (int)((mant << (S - 24)) >> sh) : 0;
         }
 
-    // ---- start: K lightest rows of every column ----
+    // ---- start: K lightest rows of every column (ties: lower row first) ----
+    if (2 * K == (uint32_t)M) {
+        // cost << 4 | row is a distinct key (cost < 2^27, resp. 2^26 with 4 index bits at M = 16):
+        // the K lightest are the keys below the smallest key of the upper half
+        constexpr int H = M / 2;
 #pragma unroll
-    for (int c = 0; c < CL; c++) {
-        uint32_t r[M];
+        for (int c = 0; c < CL; c++) {
+            uint32_t lo[H], hi[H];
 #pragma unroll
-        for (int i = 0; i < M; i++)
-            r[i] = 0;
-#pragma unroll
-        for (int i = 0; i < M; i++)
-#pragma unroll
-            for (int i2 = i + 1; i2 < M; i2++) {
-                rank_pair<M>(cost[i][c] <= cost[i2][c], r[i], r[i2]);
+            for (int i = 0; i < H; i++) {
+                lo[i] = ((uint32_t)cost[i][c] << 4) | (uint32_t)i;
+                hi[i] = ((uint32_t)cost[H + i][c] << 4) | (uint32_t)(H + i);
             }
-        uint32_t x = 0;
+            const uint32_t t = upper_half_min<H>(lo, hi);
+            uint32_t x = 0;
 #pragma unroll
-        for (int i = 0; i < M; i++)
-            x |= (r[i] < K ? 1u : 0u) << i;
-        xcol[c] = x;
+            for (int i = 0; i < M; i++)
+                x |= ((((uint32_t)cost[i][c] << 4) | (uint32_t)i) < t ? 1u : 0u) << i;
+            xcol[c] = x;
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < CL; c++) {
+            uint32_t r[M];
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                r[i] = 0;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+#pragma unroll
+                for (int i2 = i + 1; i2 < M; i2++)
+                    rank_pair<M>(cost[i][c] <= cost[i2][c], r[i], r[i2]);
+            uint32_t x = 0;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                x |= (r[i] < K ? 1u : 0u) << i;
+            xcol[c] = x;
+        }
     }
+
+    // pruned entries per row, identical in the G lanes of the block; kept up to date after each flip
+    uint32_t cnt[M];
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        uint32_t n = 0;
+#pragma unroll
+        for (int c = 0; c < CL; c++)
+            n += (xcol[c] >> i) & 1u;
+        if constexpr (G >= 2)
+            n += quad_xor<1>(n);
+        if constexpr (G == 4)
+            n += quad_xor<2>(n);
+        cnt[i] = n;
+    }
+    uint32_t rowid[M];   // row numbers in registers, operands of the selects below
+#pragma unroll
+    for (int i = 0; i < M; i++)
+        rowid[i] = (uint32_t)i;
 
     // ---- augment until every row has exactly K pruned ----
     for (int phase = 0; phase < M * M; phase++) {
         int drow[M];
         uint32_t prow[M];
-        uint32_t n_excess = 0;
+        lanemask_t any_excess = 0;
         uint32_t deficit = 0;
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            uint32_t cnt = 0;
-#pragma unroll
-            for (int c = 0; c < CL; c++)
-                cnt += (xcol[c] >> i) & 1u;
-            if constexpr (G >= 2)
-                cnt += quad_xor<1>(cnt);
-            if constexpr (G == 4)
-                cnt += quad_xor<2>(cnt);
-            const bool ex = cnt > K;
-            n_excess += ex ? 1u : 0u;
-            deficit |= (cnt < K ? 1u : 0u) << i;
-            drow[i] = ex ? 0 : kInfDist;
+            const lanemask_t ex = lm(cnt[i] > K);
+            any_excess |= ex;
+            deficit |= (cnt[i] < K ? 1u : 0u) << i;
+            drow[i] = (int)lm_pick(ex, 0u, (uint32_t)kInfDist);
             prow[i] = kNoPred;
         }
-        if (n_excess == 0)
+        if (!lm_test(any_excess))
             break;
 
         // label-correcting sweeps over the columns
-        uint32_t changed;
+        lanemask_t changed;
         int sweeps = 0;
         do {
             changed = 0;
 #pragma unroll
             for (int c = 0; c < CL; c++) {
-                int dcol = kInfDist;
-                uint32_t from = 0;
+                lanemask_t pm[M];            // row i is pruned in this column
+#pragma unroll
+                for (int i = 0; i < M; i++)
+                    pm[i] = lm((xcol[c] & (1u << i)) != 0u);
+                // cheapest way to reach the column: through a pruned entry of a reached row
+                uint32_t dcol = (uint32_t)kInfDist, from = 0;
 #pragma unroll
                 for (int i = 0; i < M; i++) {
                     const int t = drow[i] - cost[i][c];
-                    const bool better = ((xcol[c] >> i) & 1u) && (t < dcol);
-                    dcol = better ? t : dcol;
-                    from = better ? (uint32_t)i : from;
+                    const lanemask_t better = pm[i] & lm(t < (int)dcol);
+                    dcol = lm_pick(better, (uint32_t)t, dcol);
+                    from = lm_pick(better, rowid[i], from);
                 }
-                const bool ok = dcol < kReachable;
+                // an unreachable column must not improve anything: kInfDist + cost >= every label
+                dcol = lm_pick(lm((int)dcol < kReachable), dcol, (uint32_t)kInfDist);
                 const uint32_t code = ((gpos * CL + c) << 4) | from;
+                // leave the column through its unpruned entries
 #pragma unroll
                 for (int i = 0; i < M; i++) {
-                    const int t = dcol + cost[i][c];
-                    const bool better = ok && !((xcol[c] >> i) & 1u) && (t < drow[i]);
-                    drow[i] = better ? t : drow[i];
-                    prow[i] = better ? code : prow[i];
-                    changed |= better ? 1u : 0u;
+                    const int t = (int)dcol + cost[i][c];
+                    const lanemask_t better = ~pm[i] & lm(t < drow[i]);
+                    drow[i] = (int)lm_pick(better, (uint32_t)t, (uint32_t)drow[i]);
+                    prow[i] = lm_pick(better, code, prow[i]);
+                    changed |= better;
                 }
             }
+            uint32_t chg = lm_test(changed) ? 1u : 0u;
             if constexpr (G >= 2) {
                 const bool before = (gpos ^ 1u) < gpos;
 #pragma unroll
@@ -430,7 +477,7 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
                     drow[i] = take ? od : drow[i];
                     prow[i] = take ? op : prow[i];
                 }
-                changed |= quad_xor<1>(changed);
+                chg |= quad_xor<1>(chg);
             }
             if constexpr (G == 4) {
                 const bool before = (gpos ^ 2u) < gpos;
@@ -442,10 +489,11 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
                     drow[i] = take ? od : drow[i];
                     prow[i] = take ? op : prow[i];
                 }
-                changed |= quad_xor<2>(changed);
+                chg |= quad_xor<2>(chg);
             }
+            changed = lm(chg != 0u);
             sweeps++;
-        } while (changed && sweeps <= M);
+        } while (lm_test(changed) && sweeps <= M);
 
         // cheapest reachable row that still lacks pruned entries
         int best = kInfDist;
@@ -458,6 +506,7 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
         }
         if (best >= kReachable)
             break;   // cannot happen for 0 < K < M; guards against looping on corrupt state
+        const uint32_t target = r;
 
         // flip the entries along the predecessor chain back to a row with excess
         for (int step = 0; step < M; step++) {
@@ -474,6 +523,10 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
                     xcol[c] ^= (1u << r) | (1u << f);
             r = f;
         }
+        // the chain ends in a row with excess: it loses one pruned entry, the target gains one
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            cnt[i] += (target == (uint32_t)i ? 1u : 0u) - (r == (uint32_t)i ? 1u : 0u);
     }
 }
 
