@@ -14,6 +14,7 @@
 #include "tmask_approx_sel.hpp"
 #include "tmask_pack.hpp"
 #include "tmask_pack4.hpp"
+#include "tmask_exact_balance.hpp"
 
 namespace tmask {
 
@@ -623,6 +624,14 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             kern = mf == kMaskU8 ? exact24_kernel<kF32, kMaskU8> : exact24_kernel<kF32, kMaskBits>;
         else
             kern = mf == kMaskU8 ? exact24_kernel<kBF16, kMaskU8> : exact24_kernel<kBF16, kMaskBits>;
+    }
+    if (SOLVER == kSolveExact && (M == 8 || M == 16) && 2 * N == M) {
+#define TMASK_PICK(DT, MM, FM) \
+    if (dt == DT && M == MM && mf == FM) kern = exact_balanced_kernel<DT, MM, FM>;
+        TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8)
+        TMASK_PICK(kBF16, 16, kMaskU8) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
+        TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+#undef TMASK_PICK
     }
     if (SOLVER == kSolveApprox && dt == kF32 && M == 8 && N == 4)
         kern = mf == kMaskU8 ? approx_sel_f32_kernel<8, kMaskU8> : approx_sel_f32_kernel<8, kMaskBits>;
