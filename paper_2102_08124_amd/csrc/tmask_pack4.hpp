@@ -10,6 +10,8 @@
 //   W^T : a lane gathers, per column, the 8 values of its four block-rows in registers, parks them in
 //         LDS ([column][block-row]) and the workgroup streams 128 B (fp32) / 64 B (bf16) runs per column.
 #pragma once
+#include <type_traits>
+
 #include "tmask_device.hpp"
 #include "tmask_pack.hpp"
 
@@ -95,144 +97,166 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
     const size_t pitchW = (size_t)(d.cols / 4) * 2;    // elements per row of vals
     const size_t pitchT = (size_t)(d.rows / 4) * 2;    // elements per row of valsT
 
-    uint32_t vt[C][VPC];
-    uint32_t tnib[C];
-#pragma unroll
-    for (int c = 0; c < C; c++)
-        tnib[c] = 0;
-
-#pragma unroll
-    for (int q = 0; q < 4; q++) {
-        const uint32_t brl = 4 * w + q;
-        const uint32_t row = row0 + 4 * brl;
-        const bool ok = strip_ok && row < d.rows;
-        u32x4 raw[4];
-        uint32_t m0[4], m1[4];   // the rows' mask entries: U8 bytes as dwords, or BITS in m0
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            raw[i] = u32x4{0u, 0u, 0u, 0u};
-            m0[i] = m1[i] = 0;
-        }
-        if (ok) {
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                raw[i] = __builtin_nontemporal_load(
-                    (const u32x4 *)((const char *)d.w + ((size_t)(row + i) * d.ld + col) * ES));
-                if constexpr (FMT == kMaskU8) {
-                    const char *mp = (const char *)d.mask + (size_t)(row + i) * d.mask_ld + col;
-                    if constexpr (C == 4) {
-                        m0[i] = __builtin_nontemporal_load((const uint32_t *)mp);
-                    } else {
-                        const u32x2 mv = __builtin_nontemporal_load((const u32x2 *)mp);
-                        m0[i] = mv.x;
-                        m1[i] = mv.y;
-                    }
-                } else {
-                    const uint32_t byte = ((const unsigned char *)d.mask)[(size_t)(row + i) * d.mask_ld + (col >> 3)];
-                    m0[i] = (C == 8) ? byte : ((byte >> (col & 4u)) & 0xFu);
-                }
-            }
-        }
-        uint32_t rowout[4][2];
-        uint32_t rownib[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int g = 0; g < NG; g++) {
-            uint32_t e[4][4];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const uint32_t dw[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
-#pragma unroll
-                for (int c = 0; c < 4; c++) {
-                    if constexpr (DT == kF32)
-                        e[i][c] = dw[c];
-                    else
-                        e[i][c] = (c & 1) ? (dw[2 * g + c / 2] >> 16) : (dw[2 * g + c / 2] & 0xFFFFu);
-                }
-            }
-            // Lane masks are formed per group right where they are used (and the scheduler is fenced
-            // between groups) so that only a handful of them are live at a time.
-            // W: groups along the row
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                uint32_t v0, v1, nib;
-                compact_2of4(keep_flag<FMT>(m0[i], m1[i], 4 * g), keep_flag<FMT>(m0[i], m1[i], 4 * g + 1),
-                             keep_flag<FMT>(m0[i], m1[i], 4 * g + 2), keep_flag<FMT>(m0[i], m1[i], 4 * g + 3), e[i][0],
-                             e[i][1], e[i][2], e[i][3], v0, v1, nib);
-                if constexpr (DT == kF32) {
-                    rowout[i][0] = v0;
-                    rowout[i][1] = v1;
-                } else {
-                    rowout[i][g] = v0 | (v1 << 16);
-                }
-                rownib[i] |= nib << (4 * g);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // W^T: groups down the column
-#pragma unroll
-            for (int c = 0; c < 4; c++) {
-                uint32_t v0, v1, nib;
-                compact_2of4(keep_flag<FMT>(m0[0], m1[0], 4 * g + c), keep_flag<FMT>(m0[1], m1[1], 4 * g + c),
-                             keep_flag<FMT>(m0[2], m1[2], 4 * g + c), keep_flag<FMT>(m0[3], m1[3], 4 * g + c), e[0][c],
-                             e[1][c], e[2][c], e[3][c], v0, v1, nib);
-                if constexpr (DT == kF32) {
-                    vt[c][2 * q] = v0;
-                    vt[c][2 * q + 1] = v1;
-                } else {
-                    vt[4 * g + c][q] = v0 | (v1 << 16);
-                }
-                tnib[4 * g + c] |= nib << (4 * q);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (!ok) {
-#pragma unroll
-            for (int i = 0; i < 4; i++)
-                rownib[i] = 0;   // nothing of this strip may show up in a row's padding bits
-        }
-        if (ok) {
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                u32x2 v;
-                v.x = rowout[i][0];
-                v.y = rowout[i][1];
-                __builtin_nontemporal_store(
-                    v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col / 4) * 2) * ES));
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            if constexpr (C == 4) {
-                const uint32_t other = quad_xor<1>(rownib[i]);
-                if ((l & 1u) == 0)
-                    IDX[4 * brl + i][l >> 1] = (uint8_t)(rownib[i] | (other << 4));
-            } else {
-                IDX[4 * brl + i][l] = (uint8_t)rownib[i];
-            }
-        }
-    }
-    if (!strip_ok) {
+    // Tiles that lie wholly inside the matrix take a copy of the code without any bounds test: no branch
+    // splits the loop, so the waits on the prefetched rows are exact.
+    auto compute = [&](auto edge_tag) {
+        constexpr bool EDGE = decltype(edge_tag)::value;
+        uint32_t vt[C][VPC];
+        uint32_t tnib[C];
 #pragma unroll
         for (int c = 0; c < C; c++)
             tnib[c] = 0;
-    }
-    // block-rows of this wavefront that lie outside the matrix must not leave position bits either
-    {
-        const uint32_t brs_in = (d.rows - row0) / 4;           // block-rows of the tile inside the matrix
-        const uint32_t mine = brs_in > 4 * w ? brs_in - 4 * w : 0;
-        const uint32_t keepmask = mine >= 4 ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
+
+        // Loads run one block-row ahead of the compaction: while block-row q is worked on, the 16-byte rows
+        // and mask entries of block-row q + 1 are already in flight.
+        u32x4 rawb[2][4];
+        uint32_t m0b[2][4], m1b[2][4];   // the rows' mask entries: U8 bytes as dwords, or BITS in m0
+        auto issue = [&](int q, u32x4 (&raw)[4], uint32_t (&m0)[4], uint32_t (&m1)[4]) {
+            const uint32_t row = row0 + 4 * (4 * w + (uint32_t)q);
 #pragma unroll
-        for (int c = 0; c < C; c++)
-            tnib[c] &= keepmask;
-    }
+            for (int i = 0; i < 4; i++) {
+                raw[i] = u32x4{0u, 0u, 0u, 0u};
+                m0[i] = m1[i] = 0;
+            }
+            if (!EDGE || (strip_ok && row < d.rows)) {
 #pragma unroll
-    for (int c = 0; c < C; c++) {
+                for (int i = 0; i < 4; i++) {
+                    raw[i] = __builtin_nontemporal_load(
+                        (const u32x4 *)((const char *)d.w + ((size_t)(row + i) * d.ld + col) * ES));
+                    if constexpr (FMT == kMaskU8) {
+                        const char *mp = (const char *)d.mask + (size_t)(row + i) * d.mask_ld + col;
+                        if constexpr (C == 4) {
+                            m0[i] = __builtin_nontemporal_load((const uint32_t *)mp);
+                        } else {
+                            const u32x2 mv = __builtin_nontemporal_load((const u32x2 *)mp);
+                            m0[i] = mv.x;
+                            m1[i] = mv.y;
+                        }
+                    } else {
+                        const uint32_t byte = ((const unsigned char *)d.mask)[(size_t)(row + i) * d.mask_ld + (col >> 3)];
+                        m0[i] = (C == 8) ? byte : ((byte >> (col & 4u)) & 0xFu);
+                    }
+                }
+            }
+        };
+        issue(0, rawb[0], m0b[0], m1b[0]);
+
 #pragma unroll
-        for (int h = 0; h < VPC / 4; h++) {
-            u32x4 v = {vt[c][4 * h], vt[c][4 * h + 1], vt[c][4 * h + 2], vt[c][4 * h + 3]};
-            *(u32x4 *)&OT[l * C + c][w * VPC + 4 * h] = v;
+        for (int q = 0; q < 4; q++) {
+            const uint32_t brl = 4 * w + q;
+            const uint32_t row = row0 + 4 * brl;
+            const bool ok = !EDGE || (strip_ok && row < d.rows);
+            if (q + 1 < 4)
+                issue(q + 1, rawb[(q + 1) & 1], m0b[(q + 1) & 1], m1b[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4(&raw)[4] = rawb[q & 1];
+            uint32_t(&m0)[4] = m0b[q & 1];
+            uint32_t(&m1)[4] = m1b[q & 1];
+            uint32_t rowout[4][2];
+            uint32_t rownib[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int g = 0; g < NG; g++) {
+                uint32_t e[4][4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const uint32_t dw[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        if constexpr (DT == kF32)
+                            e[i][c] = dw[c];
+                        else
+                            e[i][c] = (c & 1) ? (dw[2 * g + c / 2] >> 16) : (dw[2 * g + c / 2] & 0xFFFFu);
+                    }
+                }
+                // Lane masks are formed per group right where they are used (and the scheduler is fenced
+                // between groups) so that only a handful of them are live at a time.
+                // W: groups along the row
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    uint32_t v0, v1, nib;
+                    compact_2of4(keep_flag<FMT>(m0[i], m1[i], 4 * g), keep_flag<FMT>(m0[i], m1[i], 4 * g + 1),
+                                 keep_flag<FMT>(m0[i], m1[i], 4 * g + 2), keep_flag<FMT>(m0[i], m1[i], 4 * g + 3), e[i][0],
+                                 e[i][1], e[i][2], e[i][3], v0, v1, nib);
+                    if constexpr (DT == kF32) {
+                        rowout[i][0] = v0;
+                        rowout[i][1] = v1;
+                    } else {
+                        rowout[i][g] = v0 | (v1 << 16);
+                    }
+                    rownib[i] |= nib << (4 * g);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // W^T: groups down the column
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    uint32_t v0, v1, nib;
+                    compact_2of4(keep_flag<FMT>(m0[0], m1[0], 4 * g + c), keep_flag<FMT>(m0[1], m1[1], 4 * g + c),
+                                 keep_flag<FMT>(m0[2], m1[2], 4 * g + c), keep_flag<FMT>(m0[3], m1[3], 4 * g + c), e[0][c],
+                                 e[1][c], e[2][c], e[3][c], v0, v1, nib);
+                    if constexpr (DT == kF32) {
+                        vt[c][2 * q] = v0;
+                        vt[c][2 * q + 1] = v1;
+                    } else {
+                        vt[4 * g + c][q] = v0 | (v1 << 16);
+                    }
+                    tnib[4 * g + c] |= nib << (4 * q);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (!ok) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    rownib[i] = 0;   // nothing of this strip may show up in a row's padding bits
+            }
+            if (ok) {
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    u32x2 v;
+                    v.x = rowout[i][0];
+                    v.y = rowout[i][1];
+                    __builtin_nontemporal_store(
+                        v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col / 4) * 2) * ES));
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                if constexpr (C == 4) {
+                    const uint32_t other = quad_xor<1>(rownib[i]);
+                    if ((l & 1u) == 0)
+                        IDX[4 * brl + i][l >> 1] = (uint8_t)(rownib[i] | (other << 4));
+                } else {
+                    IDX[4 * brl + i][l] = (uint8_t)rownib[i];
+                }
+            }
         }
-        IDXT[l * C + c][w] = (uint16_t)tnib[c];
-    }
+        if (EDGE && !strip_ok) {
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                tnib[c] = 0;
+        }
+        // block-rows of this wavefront that lie outside the matrix must not leave position bits either
+        if (EDGE) {
+            const uint32_t brs_in = (d.rows - row0) / 4;           // block-rows of the tile inside the matrix
+            const uint32_t mine = brs_in > 4 * w ? brs_in - 4 * w : 0;
+            const uint32_t keepmask = mine >= 4 ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                tnib[c] &= keepmask;
+        }
+#pragma unroll
+        for (int c = 0; c < C; c++) {
+#pragma unroll
+            for (int h = 0; h < VPC / 4; h++) {
+                u32x4 v = {vt[c][4 * h], vt[c][4 * h + 1], vt[c][4 * h + 2], vt[c][4 * h + 3]};
+                *(u32x4 *)&OT[l * C + c][w * VPC + 4 * h] = v;
+            }
+            IDXT[l * C + c][w] = (uint16_t)tnib[c];
+        }
+    };
+    if (row0 + TR <= d.rows && col0 + TC <= d.cols)
+        compute(std::false_type{});
+    else
+        compute(std::true_type{});
     __syncthreads();
 
     const uint32_t cols_valid = min((uint32_t)TC, d.cols - col0);
