@@ -105,6 +105,51 @@ def largest_config_approx(tm, torch, ev, reps: int):
             "frac_of_hbm_peak": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def fused_approx_pack(tm, torch, ev, mats_np, copies: int, reps: int):
+    """tmask_approx_pack (Algorithm 1 + compression in one pass, no mask written) on the bench workload:
+    what a training step that refreshes its packed operands would call instead of approx + apply_pack."""
+    N, M = N_KEEP, M_BLOCK
+    weights = sum(w.size for w in mats_np)
+    sets = []
+    for _ in range(copies):
+        ws = [torch.from_numpy(w).cuda() for w in mats_np]
+        sets.append(tm.FusedBatch(ws, None, [tm.alloc_packed(w, N, M) for w in ws], N, M))
+    for b in sets:
+        tm.tmask_approx_pack(b, None, None, N, M)
+    torch.cuda.synchronize()
+    evs = [(ev.create(), ev.create()) for _ in range(reps)]
+    for k in range(reps):
+        tm.tmask_profile_next(*evs[k])
+        tm.tmask_approx_pack(sets[k % copies], None, None, N, M)
+    torch.cuda.synchronize()
+    ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
+    byts = weights * 4 + 2 * (weights * N // M) * 4 + 2 * (weights * N // M) * 2 // 8
+    return {"what": "tmask_approx_pack on the same workload, one batched launch, no mask written",
+            "kernel_ms": ms, "algorithmic_bytes": byts, "achieved_GBs": byts / (ms * 1e-3) / 1e9,
+            "frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "weights_per_s": weights / (ms * 1e-3)}
+
+
+def device_copy_rate(torch, mib: int = 256, reps: int = 10):
+    """Context for the roofline fractions: what a plain device-to-device copy (as many bytes written as read)
+    reaches on this GPU, three rotating buffer pairs, median of `reps`."""
+    n = mib * 1024 * 1024 // 4
+    src = [torch.ones(n, dtype=torch.float32, device="cuda") for _ in range(3)]
+    dst = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(3)]
+    for k in range(3):
+        dst[k].copy_(src[k])
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for k, (a, b) in enumerate(evs):
+        a.record()
+        dst[k % 3].copy_(src[k % 3])
+        b.record()
+    torch.cuda.synchronize()
+    ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
+    gbs = 2 * n * 4 / (ms * 1e-3) / 1e9
+    return {"what": "torch copy_ of %d MiB fp32, bytes read + bytes written" % mib, "ms": ms, "achieved_GBs": gbs,
+            "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +277,8 @@ def main():
     if not args.no_largest:
         result["largest_config"] = largest_config_approx(tm, torch, ev, reps=20)
     del sets
+    result["fused_approx_pack"] = fused_approx_pack(tm, torch, ev, mats_np, copies=min(args.copies, 6), reps=24)
+    result["device_copy"] = device_copy_rate(torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(mats_np)
     print(json.dumps(result))

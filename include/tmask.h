@@ -16,7 +16,7 @@
  *
  * Memory and execution
  *   Every `w`, `mask`, `vals*`, `idx*`, `objective`, `out`, `per_block_obj` and `workspace` pointer
- *   is DEVICE memory owned by the caller; descriptor arrays (`tmask_mat*`, `tmask_pack_desc*`) are
+ *   is DEVICE memory owned by the caller; descriptor arrays (`tmask_mat*`, `tmask_pack_desc*`, `tmask_fused_desc*`) are
  *   HOST memory read before the call returns.  Work is enqueued on `hip_stream` (a hipStream_t,
  *   NULL = default stream); the library never synchronises, allocates or frees device memory, and
  *   holds no state between calls.  Outputs are valid once the stream has been synchronised.
@@ -119,6 +119,29 @@ typedef struct {
 
 int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Algorithm 1 and the compression in one call (arXiv 2102.08124, Sec. 4: Algorithm 1; Sec. 2: the
+ * backward pass multiplies by W^T, so both W and W^T are compressed).  Outputs are exactly those of
+ * tmask_approx followed by tmask_apply_pack with that mask: `vals`, `idx`, `valsT`, `idxT` in the
+ * format above, `objective` (device, nullable) = sum S|W|, and the mask itself if `mask` is not
+ * NULL.  For N:M = 2:4 this is a single pass over W in which the mask never travels through
+ * memory (`mask` may be NULL for all matrices; give it for all or for none, else TMASK_ERR_NULL).
+ * For any other N:M the two steps run one after the other and `mask` is required.
+ * A workspace is needed only if some `objective` is given.  The `w`, mask and packed-output layout
+ * requirements are those of tmask_approx and tmask_apply_pack; for 2:4, `vals` and `valsT` must
+ * be 8-byte aligned (TMASK_ERR_ALIGN).
+ */
+typedef struct {
+    const void *w; int64_t rows, cols, ld;
+    void *mask; int64_t mask_ld;          /* output, nullable (see above) */
+    void *vals;  void *idx;
+    void *valsT; void *idxT;
+    double *objective;                    /* output, nullable */
+} tmask_fused_desc;
+
+int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Score a mask (Eq. 1's objective and constraints).  out[m] (device) receives, for matrix m:

@@ -21,8 +21,8 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_apply_pack", "tmask_score", "tmask_workspace_bytes",
-           "tmask_profile_next", "tmask_last_error", "tmask_version")
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_apply_pack", "tmask_approx_pack", "tmask_score",
+           "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
 class TmaskError(RuntimeError):
@@ -40,6 +40,13 @@ class tmask_pack_desc(C.Structure):
     _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
                 ("mask", C.c_void_p), ("mask_ld", C.c_int64),
                 ("vals", C.c_void_p), ("idx", C.c_void_p), ("valsT", C.c_void_p), ("idxT", C.c_void_p)]
+
+
+class tmask_fused_desc(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("mask", C.c_void_p), ("mask_ld", C.c_int64),
+                ("vals", C.c_void_p), ("idx", C.c_void_p), ("valsT", C.c_void_p), ("idxT", C.c_void_p),
+                ("objective", C.c_void_p)]
 
 
 class tmask_score_out(C.Structure):
@@ -68,6 +75,8 @@ def load_library():
         f.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, sz, vp]
     L.tmask_apply_pack.restype = ci
     L.tmask_apply_pack.argtypes = [C.POINTER(tmask_pack_desc), ci, ci, ci, ci, ci, vp, sz, vp]
+    L.tmask_approx_pack.restype = ci
+    L.tmask_approx_pack.argtypes = [C.POINTER(tmask_fused_desc), ci, ci, ci, ci, ci, vp, sz, vp]
     L.tmask_score.restype = ci
     L.tmask_score.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     L.tmask_workspace_bytes.restype = sz
@@ -168,6 +177,37 @@ class PackBatch:
                                           idxT.data_ptr())
 
 
+class FusedBatch:
+    """Host descriptor array for tmask_approx_pack, marshalled once (keeps the tensors alive).
+    masks: list of mask tensors, or None (2:4 only: no mask is written).
+    objective: float64 device tensor with one entry per matrix, or None."""
+
+    def __init__(self, ws, masks, packed, N: int, M: int, objective: Optional[torch.Tensor] = None):
+        self.ws, self.packed = list(ws), list(packed)
+        self.masks = None if masks is None else list(masks)
+        self.objective = objective
+        self.n = len(self.ws)
+        self.dt = dtype_code(self.ws[0])
+        if objective is not None and (objective.dtype != torch.float64 or objective.numel() < self.n
+                                      or not objective.is_cuda or not objective.is_contiguous()):
+            raise ValueError("objective must be a contiguous float64 device tensor with one entry per matrix")
+        self.arr = (tmask_fused_desc * self.n)()
+        for k, (w, pk) in enumerate(zip(self.ws, self.packed)):
+            p, r, c, ld = _mat2d(w, "w")
+            mp, mld = None, 0
+            if self.masks is not None:
+                mp, _, _, mld = _mat2d(self.masks[k], "mask")
+            vs, is_, vts, its = packed_shapes(r, c, N, M)
+            vals, idx, valsT, idxT = pk
+            for t, shp, dty in ((vals, vs, w.dtype), (idx, is_, torch.uint8), (valsT, vts, w.dtype),
+                                (idxT, its, torch.uint8)):
+                if tuple(t.shape) != shp or t.dtype != dty or not t.is_contiguous() or not t.is_cuda:
+                    raise ValueError("packed output has the wrong shape/dtype: %s vs %s" % (tuple(t.shape), shp))
+            op = None if objective is None else objective.data_ptr() + 8 * k
+            self.arr[k] = tmask_fused_desc(p, r, c, ld, mp, mld, vals.data_ptr(), idx.data_ptr(), valsT.data_ptr(),
+                                           idxT.data_ptr(), op)
+
+
 def tmask_workspace_bytes(ws: Sequence[torch.Tensor], N: int, M: int) -> int:
     arr = (tmask_mat * len(ws))()
     for k, w in enumerate(ws):
@@ -249,6 +289,14 @@ def tmask_apply_pack(ws, masks, packed, N: int, M: int, mask_fmt: int = TMASK_MA
     b = ws if isinstance(ws, PackBatch) else PackBatch(ws, masks, packed, N, M)
     wp, wb = _ws_args(workspace)
     _check(load_library().tmask_apply_pack(b.arr, b.n, b.dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
+
+
+def tmask_approx_pack(ws, masks, packed, N: int, M: int, objective: Optional[torch.Tensor] = None,
+                      mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Algorithm 1 and the compression of W and W^T in one call; masks may be None for 2:4."""
+    b = ws if isinstance(ws, FusedBatch) else FusedBatch(ws, masks, packed, N, M, objective)
+    wp, wb = _ws_args(workspace)
+    _check(load_library().tmask_approx_pack(b.arr, b.n, b.dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
 
 
 def tmask_profile_next(start_event: Optional[int], stop_event: Optional[int]) -> None:

@@ -1,0 +1,265 @@
+// tmask_approx_pack for M = 4, N = 2: Algorithm 1 (arXiv 2102.08124, Sec. 4) and the compression of
+// W and W^T in one pass over W.  The mask never travels through memory between the two steps; it is
+// written only if the caller wants it.
+//
+// Same tiling as pack24_kernel (64 rows x 64 strips per workgroup, a lane holds whole 4x4 blocks), so
+// the keep flags that Algorithm 1's rank form yields as lane masks (tmask_approx4.hpp) feed the slot
+// logic of the compaction (tmask_pack4.hpp) directly.
+#pragma once
+#include <type_traits>
+
+#include "tmask_approx4.hpp"
+#include "tmask_device.hpp"
+#include "tmask_pack.hpp"
+#include "tmask_pack4.hpp"
+
+namespace tmask {
+
+struct FusedArgs {
+    PackDev d[kMaxPackBatch];   // mask = output here (may be null when WMASK is false)
+    uint32_t n;
+    uint32_t partial0;          // index of this launch's first partial in the workspace
+    void *partials;             // one double per workgroup, or null
+};
+static_assert(sizeof(FusedArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+
+template <int DT, int FMT, bool WMASK>
+__global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs args)
+{
+    using PG = Pack4Geo<DT>;
+    constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, VPC = PG::VPC, OTW = PG::OTW,
+                  IDXB = PG::IDXB;
+
+    __shared__ __attribute__((aligned(16))) uint32_t OT[TC][OTW];
+    __shared__ __attribute__((aligned(8))) uint16_t IDXT[TC][4];
+    __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
+    __shared__ double red[kThreads / 64];
+
+    const uint32_t tile = blockIdx.x;
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].tile0 <= tile)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const PackDev d = args.d[lo];
+    const uint32_t tl = tile - d.tile0;
+    const uint32_t ty = tl / d.tiles_x, tx = tl - ty * d.tiles_x;
+    const uint32_t row0 = ty * TR, col0 = tx * TC;
+    const uint32_t tid = threadIdx.x, l = tid & 63u;
+    // the wavefront number as a scalar: row addresses below are then scalar too, and a lane adds only
+    // its fixed offset inside the 1 KiB run
+    const uint32_t w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t col = col0 + l * C;
+    const bool strip_ok = col < d.cols;
+    const size_t pitchW = (size_t)(d.cols / 4) * 2;    // elements per row of vals
+    float acc = 0.f;
+
+    // Tiles wholly inside the matrix run a copy of the loop without bounds tests (no branch splits it).
+    auto compute = [&](auto edge_tag) {
+        constexpr bool EDGE = decltype(edge_tag)::value;
+        uint32_t vt[C][VPC];
+        uint32_t tnib[C];
+#pragma unroll
+        for (int c = 0; c < C; c++)
+            tnib[c] = 0;
+
+        // loads run one block-row ahead of the work on them
+        u32x4 rawb[2][4];
+        auto issue = [&](int q, u32x4 (&raw)[4]) {
+            const uint32_t row = row0 + 4 * (4 * w + (uint32_t)q);
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                raw[i] = u32x4{0u, 0u, 0u, 0u};
+            if (!EDGE || (strip_ok && row < d.rows)) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    raw[i] = __builtin_nontemporal_load(
+                        (const u32x4 *)((const char *)d.w + ((size_t)(row + i) * d.ld + col0) * ES + l * 16u));
+            }
+        };
+        issue(0, rawb[0]);
+
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            const uint32_t brl = 4 * w + q;
+            const uint32_t row = row0 + 4 * brl;
+            const bool ok = !EDGE || (strip_ok && row < d.rows);
+            if (q + 1 < 4)
+                issue(q + 1, rawb[(q + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            u32x4(&raw)[4] = rawb[q & 1];
+            uint32_t rowout[4][2];
+            uint32_t rownib[4] = {0u, 0u, 0u, 0u};
+            uint32_t rowmask[4][NG];   // U8: four 0/1 bytes per group; BITS: four bits per group
+#pragma unroll
+            for (int g = 0; g < NG; g++) {
+                uint32_t e[4][4], k[4][4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    const uint32_t dw[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        if constexpr (DT == kF32) {
+                            e[i][c] = dw[c];
+                            k[i][c] = dw[c] & 0x7FFFFFFFu;
+                        } else {
+                            e[i][c] = (c & 1) ? (dw[2 * g + c / 2] >> 16) : (dw[2 * g + c / 2] & 0xFFFFu);
+                            k[i][c] = e[i][c] & 0x7FFFu;
+                        }
+                    }
+                }
+                // Algorithm 1 in rank form: kept iff among the two heaviest of its row and of its column
+                lanemask_t keep[4][4];
+#pragma unroll
+                for (int c = 0; c < 4; c++)
+                    top2_of_4(k[0][c], k[1][c], k[2][c], k[3][c], keep[0][c], keep[1][c], keep[2][c], keep[3][c]);
+                __builtin_amdgcn_sched_barrier(0);
+                // rows: finish the keep flags, then compress W along the row
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    lanemask_t rk[4];
+                    top2_of_4(k[i][0], k[i][1], k[i][2], k[i][3], rk[0], rk[1], rk[2], rk[3]);
+                    uint32_t mbits = 0;
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        keep[i][c] &= rk[c];
+                        const uint32_t magf = (DT == kF32) ? k[i][c] : (k[i][c] << 16);
+                        acc += __uint_as_float(lm_select(keep[i][c], magf, 0u));   // lanes outside the matrix hold zeros
+                        if constexpr (WMASK)
+                            mbits |= lm_select(keep[i][c], (FMT == kMaskU8) ? (1u << (8 * c)) : (1u << c), 0u);
+                    }
+                    // pin the running sum here: left alone, the compiler defers all 64 additions to the end of
+                    // the tile and keeps every addend in a register until then.  The same holds for the merges
+                    // of position nibbles and mask bits below; those are pinned at bf16 only, where the
+                    // registers would otherwise run out (at fp32 the freer schedule is the faster one)
+                    asm volatile("" : "+v"(acc));
+                    rowmask[i][g] = mbits;
+                    if constexpr (WMASK)
+                        asm volatile("" : "+v"(rowmask[i][g]));
+                    uint32_t v0, v1, nib;
+                    compact_2of4(keep[i][0], keep[i][1], keep[i][2], keep[i][3], e[i][0], e[i][1], e[i][2], e[i][3],
+                                 v0, v1, nib);
+                    if constexpr (DT == kF32) {
+                        rowout[i][0] = v0;
+                        rowout[i][1] = v1;
+                    } else {
+                        rowout[i][g] = v0 | (v1 << 16);
+                    }
+                    rownib[i] |= nib << (4 * g);
+                    if constexpr (DT == kBF16)
+                        asm volatile("" : "+v"(rownib[i]));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // columns: compress W^T down the column
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    uint32_t v0, v1, nib;
+                    compact_2of4(keep[0][c], keep[1][c], keep[2][c], keep[3][c], e[0][c], e[1][c], e[2][c], e[3][c],
+                                 v0, v1, nib);
+                    if constexpr (DT == kF32) {
+                        vt[c][2 * q] = v0;
+                        vt[c][2 * q + 1] = v1;
+                    } else {
+                        vt[4 * g + c][q] = v0 | (v1 << 16);
+                    }
+                    tnib[4 * g + c] |= nib << (4 * q);
+                    if constexpr (DT == kBF16)
+                        asm volatile("" : "+v"(tnib[4 * g + c]));   // merge now, as for the sum above
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (EDGE && !ok) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    rownib[i] = 0;   // nothing of this strip may show up in a row's padding bits
+            }
+            if constexpr (WMASK && FMT == kMaskBits && C == 4) {
+                // two lanes share a mask byte: the even one writes it (exchange outside the bounds test)
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    rowmask[i][0] |= quad_xor<1>(rowmask[i][0]) << 4;
+            }
+            if (ok) {
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    u32x2 v;
+                    v.x = rowout[i][0];
+                    v.y = rowout[i][1];
+                    __builtin_nontemporal_store(
+                        v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col0 / 4) * 2) * ES + l * 8u));
+                    if constexpr (WMASK) {
+                        char *mrow = (char *)const_cast<void *>(d.mask) + (size_t)(row + i) * d.mask_ld +
+                                     ((FMT == kMaskU8) ? col0 : (col0 >> 3));
+                        const uint32_t lcol = l * (uint32_t)C;   // the lane's first column inside the tile
+                        if constexpr (FMT == kMaskU8) {
+                            if constexpr (C == 4) {
+                                __builtin_nontemporal_store(rowmask[i][0], (uint32_t *)(mrow + lcol));
+                            } else {
+                                u32x2 mv;
+                                mv.x = rowmask[i][0];
+                                mv.y = rowmask[i][NG - 1];
+                                __builtin_nontemporal_store(mv, (u32x2 *)(mrow + lcol));
+                            }
+                        } else {
+                            if constexpr (C == 8) {
+                                mrow[lcol >> 3] = (char)(rowmask[i][0] | (rowmask[i][NG - 1] << 4));
+                            } else {
+                                if ((l & 1u) == 0)
+                                    mrow[lcol >> 3] = (char)rowmask[i][0];
+                            }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                if constexpr (C == 4) {
+                    const uint32_t other = quad_xor<1>(rownib[i]);
+                    if ((l & 1u) == 0)
+                        IDX[4 * brl + i][l >> 1] = (uint8_t)(rownib[i] | (other << 4));
+                } else {
+                    IDX[4 * brl + i][l] = (uint8_t)rownib[i];
+                }
+            }
+        }
+        if (EDGE && !strip_ok) {
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                tnib[c] = 0;
+        }
+        // block-rows of this wavefront that lie outside the matrix must not leave position bits either
+        if (EDGE) {
+            const uint32_t brs_in = (d.rows - row0) / 4;           // block-rows of the tile inside the matrix
+            const uint32_t mine = brs_in > 4 * w ? brs_in - 4 * w : 0;
+            const uint32_t keepmask = mine >= 4 ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                tnib[c] &= keepmask;
+        }
+#pragma unroll
+        for (int c = 0; c < C; c++) {
+#pragma unroll
+            for (int h = 0; h < VPC / 4; h++) {
+                u32x4 v = {vt[c][4 * h], vt[c][4 * h + 1], vt[c][4 * h + 2], vt[c][4 * h + 3]};
+                *(u32x4 *)&OT[l * C + c][w * VPC + 4 * h] = v;
+            }
+            IDXT[l * C + c][w] = (uint16_t)tnib[c];
+        }
+    };
+    if (row0 + TR <= d.rows && col0 + TC <= d.cols)
+        compute(std::false_type{});
+    else
+        compute(std::true_type{});
+    __syncthreads();
+    pack24_copy_out<DT>(d, row0, col0, OT, IDXT, IDX);
+    if (args.partials) {
+        const double t = block_sum_f32(acc, red);
+        if (threadIdx.x == 0)
+            ((double *)args.partials)[args.partial0 + tile] = t;
+    }
+}
+
+}  // namespace tmask

@@ -15,6 +15,7 @@
 #include "tmask_pack.hpp"
 #include "tmask_pack4.hpp"
 #include "tmask_exact_balance.hpp"
+#include "tmask_fused4.hpp"
 
 namespace tmask {
 
@@ -820,6 +821,105 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return hip_fail(e, "pack kernel launch");
+    }
+    return TMASK_OK;
+}
+
+int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
+    if (rc)
+        return rc;
+    const bool fused = (M == 4 && N == 2);
+    int with_mask = 0;
+    bool want_obj = false;
+    for (int i = 0; i < n; i++) {
+        const tmask_fused_desc &p = descs[i];
+        with_mask += p.mask ? 1 : 0;
+        want_obj = want_obj || p.objective;
+        const HostMat h{p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, p.objective};
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, p.mask != nullptr)))
+            return rc;
+        if (!p.vals || !p.idx || !p.valsT || !p.idxT)
+            return fail(TMASK_ERR_NULL, "matrix %d: a packed output pointer is NULL", i);
+        if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
+            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 4-byte aligned", i);
+        if (fused && ((((uintptr_t)p.vals | (uintptr_t)p.valsT) & 7) != 0))
+            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 8-byte aligned for 2:4", i);
+    }
+    if (with_mask != 0 && with_mask != n)
+        return fail(TMASK_ERR_NULL, "mask must be given for all matrices or for none (%d of %d have one)", with_mask, n);
+    if (!fused && with_mask == 0)
+        return fail(TMASK_ERR_NULL, "N:M = %d:%d runs as two steps and needs the mask buffers", N, M);
+
+    if (!fused) {
+        std::vector<tmask_mat> mats((size_t)n);
+        std::vector<tmask_pack_desc> pds((size_t)n);
+        for (int i = 0; i < n; i++) {
+            const tmask_fused_desc &p = descs[i];
+            mats[i] = tmask_mat{p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, p.objective};
+            pds[i] = tmask_pack_desc{p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, p.vals, p.idx, p.valsT, p.idxT};
+        }
+        if ((rc = run_mask<kSolveApprox>(mats.data(), n, (int)dt, N, M, (int)mf, workspace, workspace_bytes, hip_stream)))
+            return rc;
+        return tmask_apply_pack(pds.data(), n, dt, N, M, mf, workspace, workspace_bytes, hip_stream);
+    }
+
+    const uint32_t TC = kPack4Strips * 16 / (uint32_t)elem_size((int)dt);
+    if (want_obj) {
+        size_t tiles = 0;
+        for (int i = 0; i < n; i++)
+            tiles += (size_t)((descs[i].cols + TC - 1) / TC) * (size_t)((descs[i].rows + kPack4Rows - 1) / kPack4Rows);
+        if (!workspace || ((uintptr_t)workspace & 255))
+            return fail(TMASK_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+        if (workspace_bytes < tiles * sizeof(double))
+            return fail(TMASK_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, tiles * sizeof(double));
+    }
+    typedef void (*fused_kernel_t)(const FusedArgs);
+    fused_kernel_t kern = nullptr;
+#define TMASK_PICK(DT, FM) \
+    if ((int)dt == DT && (int)mf == FM) \
+        kern = with_mask ? approx_pack24_kernel<DT, FM, true> : approx_pack24_kernel<DT, FM, false>;
+    TMASK_PICK(kF32, kMaskU8) TMASK_PICK(kF32, kMaskBits) TMASK_PICK(kBF16, kMaskU8) TMASK_PICK(kBF16, kMaskBits)
+#undef TMASK_PICK
+    hipStream_t stream = (hipStream_t)hip_stream;
+    uint32_t partial0 = 0;
+    for (int first = 0; first < n; first += kMaxPackBatch) {
+        const int nb = n - first < kMaxPackBatch ? n - first : kMaxPackBatch;
+        FusedArgs args;
+        ReduceArgs rargs;
+        memset(&args, 0, sizeof args);
+        memset(&rargs, 0, sizeof rargs);
+        uint32_t tiles = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_fused_desc &p = descs[first + k];
+            PackDev &d = args.d[k];
+            d.w = p.w; d.mask = p.mask; d.vals = p.vals; d.idx = p.idx; d.valsT = p.valsT; d.idxT = p.idxT;
+            d.rows = (uint32_t)p.rows; d.cols = (uint32_t)p.cols; d.ld = (uint32_t)p.ld; d.mask_ld = (uint32_t)p.mask_ld;
+            d.tiles_x = (d.cols + TC - 1) / TC;
+            d.tile0 = tiles;
+            rargs.objective[k] = p.objective;
+            rargs.tile0[k] = tiles;
+            tiles += d.tiles_x * ((d.rows + kPack4Rows - 1) / kPack4Rows);
+        }
+        rargs.tile0[nb] = tiles;
+        args.n = (uint32_t)nb; args.partial0 = partial0; args.partials = want_obj ? workspace : nullptr;
+        {
+            ProfileScope prof(stream, first + kMaxPackBatch >= n);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "fused approx+pack kernel launch");
+        if (want_obj) {
+            rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)workspace;
+            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
+            e = hipGetLastError();
+            if (e != hipSuccess)
+                return hip_fail(e, "objective reduce launch");
+        }
+        partial0 += tiles;
     }
     return TMASK_OK;
 }

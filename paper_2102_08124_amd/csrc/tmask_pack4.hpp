@@ -62,17 +62,93 @@ __device__ __forceinline__ lanemask_t keep_flag(uint32_t m0, uint32_t m1, int c)
         return lm((m0 & (1u << c)) != 0u);
 }
 
+// Tile geometry of the 2:4 pack kernels for one element type.
+template <int DT>
+struct Pack4Geo {
+    static constexpr int ES = (DT == kF32) ? 4 : 2;
+    static constexpr int C = 16 / ES;                  // columns per strip
+    static constexpr int NG = C / 4;                   // groups per strip row
+    static constexpr int TR = kPack4Rows, TS = kPack4Strips, TC = TS * C;
+    static constexpr int VPC = (DT == kF32) ? 8 : 4;   // dwords a lane produces per column for W^T (4 block-rows)
+    static constexpr int OTD = 4 * VPC;                // data dwords per column in the tile (16 block-rows)
+    static constexpr int OTW = OTD + 4;                // padded, keeps 16-byte alignment
+    static constexpr int IDXB = TS * NG / 2;           // index bytes per tile row
+};
+
+// Streams a finished tile out of LDS: OT = W^T values per column, IDXT = W^T position nibbles per
+// column, IDX = W position nibbles per row.  Call after a barrier; all threads take part.
+template <int DT>
+__device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0, uint32_t col0,
+                                                const uint32_t (*OT)[Pack4Geo<DT>::OTW], const uint16_t (*IDXT)[4],
+                                                const uint8_t (*IDX)[Pack4Geo<DT>::IDXB])
+{
+    using PG = Pack4Geo<DT>;
+    constexpr int ES = PG::ES, TR = PG::TR, TC = PG::TC, OTD = PG::OTD;
+    const uint32_t tid = threadIdx.x;
+    const size_t pitchT = (size_t)(d.rows / 4) * 2;    // elements per row of valsT
+    const uint32_t cols_valid = min((uint32_t)TC, d.cols - col0);
+    const uint32_t brs_valid = min((uint32_t)(TR / 4), (d.rows - row0) / 4);
+    const uint32_t rows_valid = brs_valid * 4;
+    // ---- valsT ----
+    {
+        char *dst = (char *)d.valsT + ((size_t)col0 * pitchT + (size_t)(row0 / 4) * 2) * ES;
+        const size_t pitch_b = pitchT * ES;
+        if (brs_valid == TR / 4 && (pitch_b & 15) == 0 && (((uintptr_t)dst) & 15) == 0) {
+            constexpr int CH = OTD / 4;   // 16-byte chunks per column
+            for (uint32_t j = tid; j < cols_valid * CH; j += kThreads) {
+                const uint32_t cc = j / CH, part = j % CH;
+                const u32x4 v = *(const u32x4 *)&OT[cc][4 * part];
+                __builtin_nontemporal_store(v, (u32x4 *)(dst + (size_t)cc * pitch_b + 16 * part));
+            }
+        } else {
+            const uint32_t rd = brs_valid * 2 * ES / 4;   // dwords per column
+            for (uint32_t j = tid; j < cols_valid * rd; j += kThreads) {
+                const uint32_t cc = j / rd, x = j - cc * rd;
+                *(uint32_t *)(dst + (size_t)cc * pitch_b + 4 * x) = OT[cc][x];
+            }
+        }
+    }
+    // ---- idx ----
+    {
+        const size_t pitch = ((size_t)d.cols + 7) / 8;
+        const uint32_t nb = (cols_valid / 4 + 1) / 2;
+        unsigned char *dst = (unsigned char *)d.idx + (size_t)row0 * pitch + col0 / 8;
+        if ((nb & 3) == 0 && (pitch & 3) == 0 && (((uintptr_t)dst) & 3) == 0) {
+            const uint32_t nd = nb / 4;
+            for (uint32_t j = tid; j < rows_valid * nd; j += kThreads) {
+                const uint32_t r = j / nd, x = j - r * nd;
+                *(uint32_t *)(dst + (size_t)r * pitch + 4 * x) = ((const uint32_t *)&IDX[r][0])[x];
+            }
+        } else {
+            for (uint32_t j = tid; j < rows_valid * nb; j += kThreads) {
+                const uint32_t r = j / nb, x = j - r * nb;
+                dst[(size_t)r * pitch + x] = IDX[r][x];
+            }
+        }
+    }
+    // ---- idxT ----
+    {
+        const size_t pitch = ((size_t)d.rows + 7) / 8;
+        const uint32_t nb = (brs_valid + 1) / 2;
+        unsigned char *dst = (unsigned char *)d.idxT + (size_t)col0 * pitch + row0 / 8;
+        if (nb == 8 && (pitch & 7) == 0 && (((uintptr_t)dst) & 7) == 0) {
+            for (uint32_t cc = tid; cc < cols_valid; cc += kThreads)
+                *(u32x2 *)(dst + (size_t)cc * pitch) = *(const u32x2 *)&IDXT[cc][0];
+        } else {
+            for (uint32_t j = tid; j < cols_valid * nb; j += kThreads) {
+                const uint32_t cc = j / nb, x = j - cc * nb;
+                dst[(size_t)cc * pitch + x] = ((const unsigned char *)&IDXT[cc][0])[x];
+            }
+        }
+    }
+}
+
 template <int DT, int FMT>
 __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
 {
-    constexpr int ES = (DT == kF32) ? 4 : 2;
-    constexpr int C = 16 / ES;                  // columns per strip
-    constexpr int NG = C / 4;                   // groups per strip row
-    constexpr int TR = kPack4Rows, TS = kPack4Strips, TC = TS * C;
-    constexpr int VPC = (DT == kF32) ? 8 : 4;   // dwords a lane produces per column for W^T (4 block-rows)
-    constexpr int OTD = 4 * VPC;                // data dwords per column in the tile (16 block-rows)
-    constexpr int OTW = OTD + 4;                // padded, keeps 16-byte alignment
-    constexpr int IDXB = TS * NG / 2;           // index bytes per tile row
+    using PG = Pack4Geo<DT>;
+    constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, VPC = PG::VPC, OTW = PG::OTW,
+                  IDXB = PG::IDXB;
 
     __shared__ __attribute__((aligned(16))) uint32_t OT[TC][OTW];
     __shared__ __attribute__((aligned(8))) uint16_t IDXT[TC][4];
@@ -91,7 +167,10 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
     const uint32_t tl = tile - d.tile0;
     const uint32_t ty = tl / d.tiles_x, tx = tl - ty * d.tiles_x;
     const uint32_t row0 = ty * TR, col0 = tx * TC;
-    const uint32_t tid = threadIdx.x, w = tid >> 6, l = tid & 63u;
+    const uint32_t tid = threadIdx.x, l = tid & 63u;
+    // the wavefront number as a scalar: row addresses below are then scalar too, and a lane adds only
+    // its fixed offset inside the 1 KiB run
+    const uint32_t w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t col = col0 + l * C;
     const bool strip_ok = col < d.cols;
     const size_t pitchW = (size_t)(d.cols / 4) * 2;    // elements per row of vals
@@ -122,9 +201,9 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
                     raw[i] = __builtin_nontemporal_load(
-                        (const u32x4 *)((const char *)d.w + ((size_t)(row + i) * d.ld + col) * ES));
+                        (const u32x4 *)((const char *)d.w + ((size_t)(row + i) * d.ld + col0) * ES + l * 16u));
                     if constexpr (FMT == kMaskU8) {
-                        const char *mp = (const char *)d.mask + (size_t)(row + i) * d.mask_ld + col;
+                        const char *mp = (const char *)d.mask + ((size_t)(row + i) * d.mask_ld + col0) + l * (uint32_t)C;
                         if constexpr (C == 4) {
                             m0[i] = __builtin_nontemporal_load((const uint32_t *)mp);
                         } else {
@@ -215,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
                     v.x = rowout[i][0];
                     v.y = rowout[i][1];
                     __builtin_nontemporal_store(
-                        v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col / 4) * 2) * ES));
+                        v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col0 / 4) * 2) * ES + l * 8u));
                 }
             }
 #pragma unroll
@@ -259,61 +338,7 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
         compute(std::true_type{});
     __syncthreads();
 
-    const uint32_t cols_valid = min((uint32_t)TC, d.cols - col0);
-    const uint32_t brs_valid = min((uint32_t)(TR / 4), (d.rows - row0) / 4);
-    const uint32_t rows_valid = brs_valid * 4;
-    // ---- valsT ----
-    {
-        char *dst = (char *)d.valsT + ((size_t)col0 * pitchT + (size_t)(row0 / 4) * 2) * ES;
-        const size_t pitch_b = pitchT * ES;
-        if (brs_valid == TR / 4 && (pitch_b & 15) == 0 && (((uintptr_t)dst) & 15) == 0) {
-            constexpr int CH = OTD / 4;   // 16-byte chunks per column
-            for (uint32_t j = tid; j < cols_valid * CH; j += kThreads) {
-                const uint32_t cc = j / CH, part = j % CH;
-                const u32x4 v = *(const u32x4 *)&OT[cc][4 * part];
-                __builtin_nontemporal_store(v, (u32x4 *)(dst + (size_t)cc * pitch_b + 16 * part));
-            }
-        } else {
-            const uint32_t rd = brs_valid * 2 * ES / 4;   // dwords per column
-            for (uint32_t j = tid; j < cols_valid * rd; j += kThreads) {
-                const uint32_t cc = j / rd, x = j - cc * rd;
-                *(uint32_t *)(dst + (size_t)cc * pitch_b + 4 * x) = OT[cc][x];
-            }
-        }
-    }
-    // ---- idx ----
-    {
-        const size_t pitch = ((size_t)d.cols + 7) / 8;
-        const uint32_t nb = (cols_valid / 4 + 1) / 2;
-        unsigned char *dst = (unsigned char *)d.idx + (size_t)row0 * pitch + col0 / 8;
-        if ((nb & 3) == 0 && (pitch & 3) == 0 && (((uintptr_t)dst) & 3) == 0) {
-            const uint32_t nd = nb / 4;
-            for (uint32_t j = tid; j < rows_valid * nd; j += kThreads) {
-                const uint32_t r = j / nd, x = j - r * nd;
-                *(uint32_t *)(dst + (size_t)r * pitch + 4 * x) = ((const uint32_t *)&IDX[r][0])[x];
-            }
-        } else {
-            for (uint32_t j = tid; j < rows_valid * nb; j += kThreads) {
-                const uint32_t r = j / nb, x = j - r * nb;
-                dst[(size_t)r * pitch + x] = IDX[r][x];
-            }
-        }
-    }
-    // ---- idxT ----
-    {
-        const size_t pitch = ((size_t)d.rows + 7) / 8;
-        const uint32_t nb = (brs_valid + 1) / 2;
-        unsigned char *dst = (unsigned char *)d.idxT + (size_t)col0 * pitch + row0 / 8;
-        if (nb == 8 && (pitch & 7) == 0 && (((uintptr_t)dst) & 7) == 0) {
-            for (uint32_t cc = tid; cc < cols_valid; cc += kThreads)
-                *(u32x2 *)(dst + (size_t)cc * pitch) = *(const u32x2 *)&IDXT[cc][0];
-        } else {
-            for (uint32_t j = tid; j < cols_valid * nb; j += kThreads) {
-                const uint32_t cc = j / nb, x = j - cc * nb;
-                dst[(size_t)cc * pitch + x] = ((const unsigned char *)&IDXT[cc][0])[x];
-            }
-        }
-    }
+    pack24_copy_out<DT>(d, row0, col0, OT, IDXT, IDX);
 }
 
 }  // namespace tmask

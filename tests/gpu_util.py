@@ -90,3 +90,34 @@ def run_pack(ws_np, masks_np, N, M, fmt=tm.TMASK_MASK_U8, ld_pad=0):
                 host.append(t.cpu().numpy())
         out.append(tuple(host))
     return out
+
+
+def _packed_to_host(pk):
+    host = []
+    for t in pk:
+        if t.dtype == torch.bfloat16:
+            host.append(t.view(torch.int16).cpu().numpy().view(np.uint16))
+        else:
+            host.append(t.cpu().numpy())
+    return tuple(host)
+
+
+def run_fused(ws_np, N, M, fmt=tm.TMASK_MASK_U8, ld_pad=0, with_mask=True, with_objective=True):
+    """Runs tmask_approx_pack over a batch; returns (packed tuples, host masks or None, objectives or None)."""
+    ws = [to_dev(w, ld=(w.shape[1] + ld_pad) if ld_pad else None) for w in ws_np]
+    masks = None
+    if with_mask:
+        masks = tm.alloc_masks(ws, fmt)
+        for m in masks:
+            m.fill_(0xCD)
+    packed = [tm.alloc_packed(w, N, M) for w in ws]
+    for pk in packed:
+        for t in pk:
+            t.view(torch.uint8).fill_(0xEE)
+    obj = torch.full((len(ws),), -1.0, dtype=torch.float64, device="cuda") if with_objective else None
+    wsp = tm.alloc_workspace(ws, N, M) if with_objective else None
+    tm.tmask_approx_pack(ws, masks, packed, N, M, objective=obj, mask_fmt=fmt, workspace=wsp)
+    torch.cuda.synchronize()
+    out = [_packed_to_host(pk) for pk in packed]
+    host_masks = [mask_to_host(m, w.shape[1], fmt) for m, w in zip(masks, ws_np)] if with_mask else None
+    return out, host_masks, (obj.cpu().numpy() if with_objective else None)
