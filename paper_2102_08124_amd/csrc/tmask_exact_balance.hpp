@@ -68,13 +68,13 @@ __device__ __forceinline__ uint32_t predicted_excess(const uint32_t (&a)[M][C])
 }
 
 template <int DT, int M, int FMT>
-__global__ __launch_bounds__(kThreads) void exact_balanced_kernel(const BatchArgs args)
+__global__ __launch_bounds__(kThreads, (M == 8 ? 4 : 2)) void exact_balanced_kernel(const BatchArgs args)
 {
     using Ge = Geo<DT, M>;
     constexpr int C = Ge::C, G = Ge::G;
     constexpr int NB = kThreads / G;          // blocks per workgroup
     constexpr int NBUCKET = 16;
-    constexpr int RPR = 8;                    // rows exchanged per round (8 x 16 B x 256 lanes = 32 KiB)
+    constexpr int RPR = M;                    // all rows of the block stay in LDS (M x 16 B x 256 lanes)
     __shared__ __attribute__((aligned(16))) u32x4 xraw[kThreads][RPR];
     __shared__ uint32_t sorig[NB];
     __shared__ uint32_t wcnt[kThreads / 64][NBUCKET];
@@ -192,7 +192,15 @@ __global__ __launch_bounds__(kThreads) void exact_balanced_kernel(const BatchArg
         if (my_valid) {
             const StripPos pos = strip_pos(md, my_s + gpos);
             store_mask<DT, M, FMT>(md, pos, bits);
-            acc = kept_sum<M, C>(a, bits);
+            // the magnitudes are read again from LDS: they need not occupy registers during the solve
+#pragma unroll
+            for (int i = 0; i < M; i++) {
+                uint32_t ar[C];
+                unpack_row<DT>(xraw[tid][i], ar);
+#pragma unroll
+                for (int c = 0; c < C; c++)
+                    acc += ((bits[i] >> c) & 1u) ? __uint_as_float(ar[c]) : 0.f;
+            }
         }
     }
     if (args.partials) {
