@@ -2,7 +2,7 @@
 """Benchmark of the transposable-mask hot path on one MI355X.
 
 A "step" is one pass of the whole path over one batch of synthetic input, everything resident in
-HBM: tmask_approx (Algorithm 1) + tmask_exact (Eq. 1 optimum) + tmask_apply_pack (with the exact
+HBM: tmask_approx (Algorithm 1) + tmask_exact (Eq. 3 optimum) + tmask_apply_pack (with the exact
 mask) + tmask_score (of the approximate mask, per-block objectives included), each with its
 objective reduction.  Workload at N=1: the ResNet-50-shaped conv weight set (52 matrices,
 23,445,504 fp32 weights, Kaiming-normal, seeded), N:M = 2:4, every call one batched launch over all

@@ -7,9 +7,9 @@
  * mask S is computed per block so that both W and W^T obey the N:M pattern.
  *
  * Conventions
- *   N            entries KEPT per row and per column of a block (Eq. 1: row/column sums of S are N);
+ *   N            entries KEPT per row and per column of a block (Eq. 3: row/column sums of S are N);
  *                K = M - N entries are pruned.  Supported: M in {4, 8, 16}, 0 < N < M.
- *   S_ij = 1     W_ij is kept (Eq. 1).
+ *   S_ij = 1     W_ij is kept (Eq. 3).
  *   magnitude    |W_ij| is ordered by its bit pattern with the sign cleared, compared as an unsigned
  *                integer: -0 == +0, denormals are not flushed, +Inf > finite, NaN > Inf.
  *   tie-break    equal magnitudes are ordered by the row-major index i*M + j inside the block.
@@ -69,7 +69,7 @@ typedef struct {
     int64_t rows, cols, ld;
     void *mask;        /* device; written by tmask_approx/tmask_exact, read by tmask_score */
     int64_t mask_ld;   /* bytes */
-    double *objective; /* device, nullable: [0] <- retained L1 = sum_ij S_ij |W_ij| (Eq. 1's objective) */
+    double *objective; /* device, nullable: [0] <- retained L1 = sum_ij S_ij |W_ij| (Eq. 3's objective) */
 } tmask_mat;
 
 /*
@@ -84,7 +84,7 @@ int tmask_approx(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Optimal mask of Eq. 1 per block (Sec. 4, "Reduction to Min-Cost Flow", Fig. 3): exactly N kept
+ * Optimal mask of Eq. 3 per block (Sec. 4, "Reduction to Min-Cost Flow", Fig. 3): exactly N kept
  * per row and column, maximum retained L1.  2:4 blocks are solved by evaluating all 90 feasible
  * patterns in fp32; other (N, M) by successive shortest augmenting paths on the bipartite
  * row/column network with magnitudes truncated per block to 27 (M<=8) or 26 (M=16) significant
@@ -97,7 +97,7 @@ int tmask_exact(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Apply a mask and compress both operands the two training matmuls read (Sec. 2 Eq. for the
+ * Apply a mask and compress both operands the two training matmuls read (Sec. 1, Eq. 1, the
  * backward pass: forward uses W, backward uses W^T; Sec. 4: N non-zeros per M contiguous elements
  * in both).  The paper fixes no storage format; this one is the library's own:
  *   W (.) S is a select (pruned entries become +0, also when W_ij is NaN or Inf).
@@ -121,7 +121,7 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Algorithm 1 and the compression in one call (arXiv 2102.08124, Sec. 4: Algorithm 1; Sec. 2: the
+ * Algorithm 1 and the compression in one call (arXiv 2102.08124, Sec. 4: Algorithm 1; Sec. 1, Eq. 1: the
  * backward pass multiplies by W^T, so both W and W^T are compressed).  Outputs are exactly those of
  * tmask_approx followed by tmask_apply_pack with that mask: `vals`, `idx`, `valsT`, `idxT` in the
  * format above, `objective` (device, nullable) = sum S|W|, and the mask itself if `mask` is not
@@ -144,7 +144,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Score a mask (Eq. 1's objective and constraints).  out[m] (device) receives, for matrix m:
+ * Score a mask (Eq. 3's objective and constraints).  out[m] (device) receives, for matrix m:
  * retained_l1 = sum S|W|, total_l1 = sum |W|, kept = sum S, row_violations / col_violations =
  * number of (block,row) / (block,column) pairs with more than N kept, row_not_n / col_not_n =
  * pairs whose kept count differs from N (zero for an exact-solver mask).
@@ -159,6 +159,28 @@ typedef struct {
 int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
                 tmask_score_out *out, float *per_block_obj,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Product with a compressed 2:4 operand on the structured-sparse matrix cores (arXiv 2102.08124,
+ * Sec. 1 and Sec. 4: the forward pass multiplies by W, the backward pass by W^T (Eq. 1); with a
+ * transposable mask both are 2:4 sparse along the reduction dimension):
+ *
+ *     y[t][r] = sum_c x[t][c] * Wd[r][c]      t < tokens, r < rows
+ *
+ * where Wd (rows x cols) is the matrix whose compressed form (vals, idx) was written by
+ * tmask_apply_pack or tmask_approx_pack with N:M = 2:4 and bf16 weights.
+ *   forward : (vals,  idx,  rows = W.rows, cols = W.cols), x = activations [tokens][W.cols]
+ *   backward: (valsT, idxT, rows = W.cols, cols = W.rows), x = dLoss/dY   [tokens][W.rows]
+ * x is bf16, row-major with leading dimension ld_x (elements); y is fp32 or bf16 (out_dt), row-major
+ * with leading dimension ld_y.  Products are exact, sums are accumulated in fp32 in an unspecified
+ * order.  All pointers are device memory.  No workspace.
+ * Requirements (TMASK_ERR_SHAPE / TMASK_ERR_ALIGN): rows a multiple of 4, cols a multiple of 64,
+ * ld_x >= cols and a multiple of 8, ld_y >= rows with ld_y*sizeof(y element) a multiple of 16;
+ * vals, x, y 16-byte aligned, idx 8-byte aligned.
+ */
+int tmask_spmm24(const void *vals, const void *idx, int64_t rows, int64_t cols,
+                 const void *x, int64_t ld_x, void *y, int64_t ld_y, int64_t tokens,
+                 tmask_dtype out_dt, void *hip_stream);
 
 /* Upper bound of the workspace any call above needs for these matrices (0 on invalid arguments). */
 size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M);

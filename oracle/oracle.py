@@ -1,7 +1,7 @@
 """ctypes front-end to the C oracle (test infrastructure; see tmask_oracle.c for what it computes).
 
 Arrays: fp32 matrices are ``np.float32``; bfloat16 matrices are raw bit patterns in ``np.uint16``.
-Masks are ``np.uint8`` (1 = kept).  N = kept per row/column of an M x M block (Eq. 1).
+Masks are ``np.uint8`` (1 = kept).  N = kept per row/column of an M x M block (Eq. 3).
 """
 from __future__ import annotations
 
@@ -99,7 +99,7 @@ def approx(w: np.ndarray, N: int, M: int, threads: int = 1, per_block: bool = Fa
 
 
 def exact(w: np.ndarray, N: int, M: int, threads: int = 1, per_block: bool = False):
-    """Optimum of Eq. 1 on every block via the Fig. 3 min-cost flow -> (mask, retained L1[, per-block])."""
+    """Optimum of Eq. 3 on every block via the Fig. 3 min-cost flow -> (mask, retained L1[, per-block])."""
     return _run_mask("oracle_exact", w, N, M, threads, per_block)
 
 
@@ -165,6 +165,22 @@ def unpack(vals: np.ndarray, idx: np.ndarray, R: int, Ccols: int, N: int, M: int
     dense = np.zeros((R, Ccols), dtype=vals.dtype)
     _check(_load().oracle_unpack(_ptr(vals), _ptr(idx), dt, R, Ccols, N, M, _ptr(dense)), "oracle_unpack")
     return dense
+
+
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> float64, exactly."""
+    return (np.ascontiguousarray(bits).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def spmm(vals: np.ndarray, idx: np.ndarray, rows: int, cols: int, N: int, M: int, x: np.ndarray) -> np.ndarray:
+    """y[t][r] = sum_c x[t][c] * Wd[r][c] in float64, Wd = the rows x cols matrix stored as (vals, idx):
+    the forward product of Sec. 1 / Eq. 1's backward product, depending on which packed operand is passed.
+    The definition written out: expand the operand (oracle_unpack), then one float64 matrix product.
+    x: tokens x cols, float32 or bfloat16 bit patterns."""
+    wd = unpack(vals, idx, rows, cols, N, M)
+    wd = bf16_to_f64(wd) if wd.dtype == np.uint16 else wd.astype(np.float64)
+    xf = bf16_to_f64(x) if x.dtype == np.uint16 else np.asarray(x).astype(np.float64)
+    return xf @ wd.T
 
 
 def network_sizes(N: int, M: int):

@@ -2,22 +2,22 @@
  * CPU ORACLE for N:M transposable sparsity masks  --  TEST INFRASTRUCTURE, NOT THE PRODUCT.
  *
  * A plain, slow, obviously-correct implementation of what the GPU library computes, written from
- * the paper (arXiv 2102.08124, Sec. 4 "Computing transposable sparsity masks", Eq. 1, Fig. 3,
+ * the paper (arXiv 2102.08124, Sec. 4 "Computing transposable sparsity masks", Eq. 3, Fig. 3,
  * Algorithm 1, App. A.2-A.3).  Only tests, the smoke check and the benchmark's cpu_baseline leg
  * may call it.  It shares no code with the HIP path and does no blocking, fusion or reordering
  * beyond what the definitions state.
  *
  * Conventions (block = M x M tile of a row-major matrix, grid origin (0,0), stride M both ways):
- *   N = entries KEPT per row/column of a block (Eq. 1: row and column sums of the mask S equal N)
+ *   N = entries KEPT per row/column of a block (Eq. 3: row and column sums of the mask S equal N)
  *   K = M - N = entries PRUNED per row/column
  *   mask byte 1 = kept (S_ij = 1), 0 = pruned
  *   dtype 0 = IEEE fp32, dtype 1 = bfloat16 given as raw 16-bit patterns
  *
  * Functions and the passage each follows:
  *   oracle_approx      Algorithm 1 (greedy 2-approximation), literal sort + sweep
- *   oracle_exact       Eq. 1 optimum through the Fig. 3 min-cost-flow network, textbook
+ *   oracle_exact       Eq. 3 optimum through the Fig. 3 min-cost-flow network, textbook
  *                      successive shortest paths in fp64
- *   oracle_score       Eq. 1's objective and constraint counts for a given mask
+ *   oracle_score       Eq. 3's objective and constraint counts for a given mask
  *   oracle_apply_pack  W (.) S and compression of W and W^T into N values + N indices per group
  *                      of M (format is this project's; the paper only motivates it in Sec. 4)
  *   oracle_unpack      inverse of the packing, used by round-trip checks
@@ -210,7 +210,7 @@ static int mcf_solve(mcf_t *g, int s, int t, int demand)
     return sent;
 }
 
-/* Exact optimum of Eq. 1 on one block via the network of Fig. 3:
+/* Exact optimum of Eq. 3 on one block via the network of Fig. 3:
  *   source -> row i   capacity K, cost 0      (K entries of row i are selected for pruning)
  *   row i  -> col j   capacity 1, cost |W_ij| (unit flow <=> W_ij is pruned)
  *   col j  -> sink    capacity K, cost 0
@@ -335,7 +335,7 @@ int oracle_approx(const void *w, int dtype, int64_t rows, int64_t cols, int64_t 
     return run_mask(0, w, dtype, rows, cols, ld, N, M, mask, mask_ld, objective, per_block, n_threads);
 }
 
-/* Eq. 1 optimum over every block (Fig. 3 network). */
+/* Eq. 3 optimum over every block (Fig. 3 network). */
 int oracle_exact(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld, int N, int M,
                  uint8_t *mask, int64_t mask_ld, double *objective, double *per_block, int n_threads)
 {
@@ -344,7 +344,7 @@ int oracle_exact(const void *w, int dtype, int64_t rows, int64_t cols, int64_t l
 
 /* ------------------------------------------------------------------ score ------------------- */
 
-/* out[0] = retained L1 = sum S|W| (Eq. 1's objective), out[1] = total L1.
+/* out[0] = retained L1 = sum S|W| (Eq. 3's objective), out[1] = total L1.
  * cnt[0] = kept entries, cnt[1] = (block,row) pairs with more than N kept,
  * cnt[2] = (block,column) pairs with more than N kept,
  * cnt[3] = (block,row) pairs with kept != N, cnt[4] = same for columns.

@@ -21,7 +21,7 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_apply_pack", "tmask_approx_pack", "tmask_score",
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_apply_pack", "tmask_approx_pack", "tmask_spmm24", "tmask_score",
            "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
@@ -77,6 +77,8 @@ def load_library():
     L.tmask_apply_pack.argtypes = [C.POINTER(tmask_pack_desc), ci, ci, ci, ci, ci, vp, sz, vp]
     L.tmask_approx_pack.restype = ci
     L.tmask_approx_pack.argtypes = [C.POINTER(tmask_fused_desc), ci, ci, ci, ci, ci, vp, sz, vp]
+    L.tmask_spmm24.restype = ci
+    L.tmask_spmm24.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, vp, C.c_int64, C.c_int64, ci, vp]
     L.tmask_score.restype = ci
     L.tmask_score.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     L.tmask_workspace_bytes.restype = sz
@@ -239,7 +241,7 @@ def tmask_approx(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = 
 
 def tmask_exact(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = None,
                 mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
-    """Optimum of Eq. 1 on every block; masks (and objective[k]) are written in place."""
+    """Optimum of Eq. 3 on every block; masks (and objective[k]) are written in place."""
     _run_mask(load_library().tmask_exact, ws, masks, N, M, objective, mask_fmt, workspace, stream)
 
 
@@ -297,6 +299,23 @@ def tmask_approx_pack(ws, masks, packed, N: int, M: int, objective: Optional[tor
     b = ws if isinstance(ws, FusedBatch) else FusedBatch(ws, masks, packed, N, M, objective)
     wp, wb = _ws_args(workspace)
     _check(load_library().tmask_approx_pack(b.arr, b.n, b.dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))
+
+
+def tmask_spmm24(vals: torch.Tensor, idx: torch.Tensor, rows: int, cols: int, x: torch.Tensor, y: torch.Tensor,
+                 stream=None) -> None:
+    """y[t][r] = sum_c x[t][c] * Wd[r][c] with Wd (rows x cols) given by its compressed 2:4 form (vals, idx).
+    x: tokens x cols bfloat16 (row stride = leading dimension), y: tokens x rows float32 or bfloat16."""
+    if x.dtype != torch.bfloat16 or vals.dtype != torch.bfloat16 or idx.dtype != torch.uint8:
+        raise TypeError("vals and x must be bfloat16, idx uint8")
+    if x.dim() != 2 or y.dim() != 2 or x.stride(1) != 1 or y.stride(1) != 1 or not (x.is_cuda and y.is_cuda):
+        raise ValueError("x and y must be 2-D device tensors with unit column stride")
+    if x.shape[1] != cols or tuple(y.shape) != (x.shape[0], rows):
+        raise ValueError("shapes: x is tokens x cols, y is tokens x rows")
+    if tuple(vals.shape) != (rows, cols // 2) or tuple(idx.shape) != (rows, cols // 8) or not vals.is_contiguous() \
+            or not idx.is_contiguous():
+        raise ValueError("vals must be rows x cols/2 and idx rows x cols/8, contiguous")
+    _check(load_library().tmask_spmm24(vals.data_ptr(), idx.data_ptr(), rows, cols, x.data_ptr(), x.stride(0),
+                                       y.data_ptr(), y.stride(0), x.shape[0], dtype_code(y), _stream_ptr(stream)))
 
 
 def tmask_profile_next(start_event: Optional[int], stop_event: Optional[int]) -> None:

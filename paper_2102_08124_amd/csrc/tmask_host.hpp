@@ -1,0 +1,31 @@
+// Host-side helpers shared by the translation units of libtmask.so.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace tmask {
+
+// Records a thread-local, human-readable description of the failure and returns `code`.
+int fail(int code, const char *fmt, ...);
+int hip_fail(hipError_t e, const char *what);
+
+// One-shot profiling events (tmask_profile_next): recorded around the main kernel of the next call.
+extern thread_local hipEvent_t g_prof_start, g_prof_stop;
+
+struct ProfileScope {
+    hipStream_t stream;
+    bool active;
+    ProfileScope(hipStream_t s, bool last_chunk) : stream(s), active(last_chunk && g_prof_start && g_prof_stop)
+    {
+        if (active)
+            (void)hipEventRecord(g_prof_start, stream);
+    }
+    ~ProfileScope()
+    {
+        if (active) {
+            (void)hipEventRecord(g_prof_stop, stream);
+            g_prof_start = g_prof_stop = nullptr;
+        }
+    }
+};
+
+}  // namespace tmask

@@ -9,6 +9,7 @@
 
 #include "../../include/tmask.h"
 #include "tmask_device.hpp"
+#include "tmask_host.hpp"
 #include "tmask_solvers.hpp"
 #include "tmask_approx4.hpp"
 #include "tmask_approx_sel.hpp"
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(kThreads) void score_reduce_kernel(const ScoreReduc
 
 static thread_local char g_err[512] = "";
 
-static int fail(int code, const char *fmt, ...)
+int fail(int code, const char *fmt, ...)
 {
     va_list ap;
     va_start(ap, fmt);
@@ -571,30 +572,13 @@ static int check_workspace(const tmask_mat *mats, int n_mats, int M, void *ws, s
     return TMASK_OK;
 }
 
-static int hip_fail(hipError_t e, const char *what)
+int hip_fail(hipError_t e, const char *what)
 {
     return fail(TMASK_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
 // One-shot profiling events (tmask_profile_next): recorded around the main kernel of the next call.
-static thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
-
-struct ProfileScope {
-    hipStream_t stream;
-    bool active;
-    ProfileScope(hipStream_t s, bool last_chunk) : stream(s), active(last_chunk && g_prof_start && g_prof_stop)
-    {
-        if (active)
-            (void)hipEventRecord(g_prof_start, stream);
-    }
-    ~ProfileScope()
-    {
-        if (active) {
-            (void)hipEventRecord(g_prof_stop, stream);
-            g_prof_start = g_prof_stop = nullptr;
-        }
-    }
-};
+thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 
 template <int SOLVER>
 static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, void *ws, size_t ws_bytes,

@@ -1,6 +1,6 @@
 // tmask_apply_pack: W (.) S and compression of W and W^T into N values + N positions per group of M.
 //
-// The paper (arXiv 2102.08124, Sec. 2 and Sec. 4) only states why both operands are needed: the
+// The paper (arXiv 2102.08124, Sec. 1 (Eq. 1) and Sec. 4) only states why both operands are needed: the
 // forward product reads W and the backward product reads W^T, and a transposable mask leaves N
 // non-zeros in every M contiguous elements of both.  The storage format is this library's own and
 // is described in include/tmask.h.

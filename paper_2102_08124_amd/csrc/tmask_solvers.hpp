@@ -1,7 +1,7 @@
 // Per-block solvers working on the strip layout (see tmask_device.hpp).
 //   approx_keep   : Algorithm 1 of arXiv 2102.08124 (Sec. 4) in rank form
-//   exact24_block : Eq. 1 optimum for 2:4 over all 90 feasible patterns (factored enumeration)
-//   exact_general : Eq. 1 optimum for any (N, M) by successive shortest augmenting paths on the
+//   exact24_block : Eq. 3 optimum for 2:4 over all 90 feasible patterns (factored enumeration)
+//   exact_general : Eq. 3 optimum for any (N, M) by successive shortest augmenting paths on the
 //                   bipartite row/column network of Fig. 3
 #pragma once
 #include "tmask_device.hpp"

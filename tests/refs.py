@@ -1,7 +1,7 @@
 """Independent yardsticks the oracle is pinned to (numpy / scipy / networkx; tests only).
 
 Nothing here is derived from the oracle's code: each function is either a plain definition
-(enumeration of Eq. 1's feasible set), a library routine solving the same mathematical problem
+(enumeration of Eq. 3's feasible set), a library routine solving the same mathematical problem
 (LP, assignment, network simplex), or a characterisation proved separately (per-node K lightest).
 """
 from __future__ import annotations
@@ -58,7 +58,7 @@ def k_lightest_rule(w: np.ndarray, N: int, M: int) -> np.ndarray:
 
 
 def valid_patterns(N: int, M: int) -> np.ndarray:
-    """All 0/1 M x M matrices with every row sum and column sum equal to N (Eq. 1's feasible set)."""
+    """All 0/1 M x M matrices with every row sum and column sum equal to N (Eq. 3's feasible set)."""
     rows = [np.array([1 if j in c else 0 for j in range(M)], dtype=np.int8)
             for c in itertools.combinations(range(M), N)]
     out = []
@@ -91,7 +91,7 @@ def brute_force_best(w: np.ndarray, N: int, M: int, patterns: np.ndarray | None 
 
 def lp_best(block_abs: np.ndarray, N: int) -> float:
     """max sum S|W| s.t. row/col sums = N, 0 <= S <= 1, solved as an LP by HiGHS.  The constraint
-    matrix (bipartite incidence) is totally unimodular, so the LP optimum equals Eq. 1's."""
+    matrix (bipartite incidence) is totally unimodular, so the LP optimum equals Eq. 3's."""
     from scipy.optimize import linprog
     M = block_abs.shape[0]
     A = np.zeros((2 * M, M * M))

@@ -1,0 +1,117 @@
+"""GPU parity for tmask_spmm24: products with the packed 2:4 operands (forward with W, backward with W^T)
+against the oracle's float64 product of the expanded operand."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2102_08124_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2102_08124_amd import binding as tm   # noqa: E402
+from tests.gpu_util import to_dev                 # noqa: E402
+
+EPS32 = 2.0 ** -24
+
+
+def _bf16_dev(bits: np.ndarray):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def _run(vals, idx, rows, cols, x_bits, out_dtype=torch.float32, ld_pad=0):
+    xd = to_dev(x_bits, ld=(x_bits.shape[1] + ld_pad) if ld_pad else None)
+    tokens = x_bits.shape[0]
+    if ld_pad:
+        ybuf = torch.full((tokens, rows + ld_pad), -7.0, dtype=out_dtype, device="cuda")
+        y = ybuf[:, :rows]
+    else:
+        y = torch.full((tokens, rows), -7.0, dtype=out_dtype, device="cuda")
+    tm.tmask_spmm24(_bf16_dev(vals), torch.from_numpy(idx).cuda(), rows, cols, xd, y)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+def _bound(vals, idx, rows, cols, x_bits):
+    """Accumulation-order bound: products are exact in fp32, each of the cols/2 additions rounds once:
+    |y - exact| <= (cols/2) * 2^-24 * sum |x||w| (first order), doubled for slack."""
+    aw = (vals & 0x7FFF).astype(np.uint16)
+    ax = (x_bits & 0x7FFF).astype(np.uint16)
+    s = oracle.spmm(aw, idx, rows, cols, 2, 4, ax)
+    return 2.0 * (cols / 2) * EPS32 * s + 1e-30
+
+
+@pytest.mark.parametrize("rows,cols,tokens", [(128, 64, 128), (192, 128, 200), (64, 64, 16), (260, 192, 130),
+                                                (512, 1024, 384)])
+def test_forward_and_backward_products(rows, cols, tokens):
+    # W: rows x cols; forward operand is rows x cols, backward operand cols x rows (needs rows % 64 == 0)
+    w = wl.f32_to_bf16_bits(wl.gaussian_f32(rows, cols, seed=6000 + rows, std=0.05))
+    for mask in (oracle.approx(w, 2, 4)[0], oracle.exact(w, 2, 4, threads=4)[0]):
+        vals, idx, valsT, idxT = oracle.apply_pack(w, mask, 2, 4)
+        x = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, cols, seed=6001 + rows))
+        got = _run(vals, idx, rows, cols, x)
+        want = oracle.spmm(vals, idx, rows, cols, 2, 4, x)
+        assert (np.abs(got - want) <= _bound(vals, idx, rows, cols, x)).all()
+        if rows % 64 == 0:
+            g = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, rows, seed=6002 + rows))
+            got = _run(valsT, idxT, cols, rows, g)
+            want = oracle.spmm(valsT, idxT, cols, rows, 2, 4, g)
+            assert (np.abs(got - want) <= _bound(valsT, idxT, cols, rows, g)).all()
+
+
+def test_bf16_output_strides_and_identity():
+    rows, cols, tokens = 128, 128, 128
+    w = wl.f32_to_bf16_bits(wl.gaussian_f32(rows, cols, seed=6100, std=0.05))
+    mask = oracle.exact(w, 2, 4)[0]
+    vals, idx, _, _ = oracle.apply_pack(w, mask, 2, 4)
+    # x = identity: y = Wd^T exactly (one non-zero product per output), in both output types
+    eye = wl.f32_to_bf16_bits(np.eye(cols, dtype=np.float32))
+    want = oracle.spmm(vals, idx, rows, cols, 2, 4, eye)
+    assert np.array_equal(_run(vals, idx, rows, cols, eye), want)
+    assert np.array_equal(_run(vals, idx, rows, cols, eye, out_dtype=torch.bfloat16, ld_pad=8), want)
+    # random x, bf16 output with padded leading dimensions: one more rounding to 8 bits of mantissa
+    x = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, cols, seed=6101))
+    got = _run(vals, idx, rows, cols, x, out_dtype=torch.bfloat16, ld_pad=8)
+    want = oracle.spmm(vals, idx, rows, cols, 2, 4, x)
+    assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + _bound(vals, idx, rows, cols, x)).all()
+
+
+def test_operands_packed_on_the_device_feed_the_product():
+    rows, cols, tokens = 256, 256, 64
+    w_bits = wl.f32_to_bf16_bits(wl.gaussian_f32(rows, cols, seed=6200, std=0.05))
+    w = to_dev(w_bits)
+    pk = tm.alloc_packed(w, 2, 4)
+    tm.tmask_approx_pack([w], None, [pk], 2, 4)
+    x_bits = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, cols, seed=6201))
+    g_bits = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, rows, seed=6202))
+    y = torch.empty((tokens, rows), dtype=torch.float32, device="cuda")
+    dx = torch.empty((tokens, cols), dtype=torch.float32, device="cuda")
+    tm.tmask_spmm24(pk[0], pk[1], rows, cols, to_dev(x_bits), y)          # forward:  y  = x W^T
+    tm.tmask_spmm24(pk[2], pk[3], cols, rows, to_dev(g_bits), dx)         # backward: dx = g W
+    torch.cuda.synchronize()
+    mask = oracle.approx(w_bits, 2, 4)[0]
+    vals, idx, valsT, idxT = oracle.apply_pack(w_bits, mask, 2, 4)
+    assert (np.abs(y.cpu().numpy() - oracle.spmm(vals, idx, rows, cols, 2, 4, x_bits))
+            <= _bound(vals, idx, rows, cols, x_bits)).all()
+    assert (np.abs(dx.cpu().numpy() - oracle.spmm(valsT, idxT, cols, rows, 2, 4, g_bits))
+            <= _bound(valsT, idxT, cols, rows, g_bits)).all()
+
+
+def test_spmm_argument_errors():
+    lib = tm.load_library()
+    v = torch.zeros((64, 32), dtype=torch.bfloat16, device="cuda")
+    i = torch.zeros((64, 8), dtype=torch.uint8, device="cuda")
+    x = torch.zeros((16, 64), dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros((16, 64), dtype=torch.float32, device="cuda")
+    args = lambda **k: [k.get("vals", v.data_ptr()), i.data_ptr(), k.get("rows", 64), k.get("cols", 64),
+                        k.get("x", x.data_ptr()), k.get("ld_x", 64), y.data_ptr(), k.get("ld_y", 64), 16,
+                        k.get("dt", tm.TMASK_F32), None]
+    assert lib.tmask_spmm24(*args()) == tm.TMASK_OK
+    assert lib.tmask_spmm24(*args(vals=None)) == tm.TMASK_ERR_NULL
+    assert lib.tmask_spmm24(*args(cols=32)) == tm.TMASK_ERR_SHAPE
+    assert lib.tmask_spmm24(*args(rows=62)) == tm.TMASK_ERR_SHAPE
+    assert lib.tmask_spmm24(*args(ld_x=32)) == tm.TMASK_ERR_SHAPE
+    assert lib.tmask_spmm24(*args(ld_y=66)) == tm.TMASK_ERR_ALIGN
+    assert lib.tmask_spmm24(*args(x=x.data_ptr() + 2)) == tm.TMASK_ERR_ALIGN
+    assert lib.tmask_spmm24(*args(dt=7)) == tm.TMASK_ERR_DTYPE
+    torch.cuda.synchronize()

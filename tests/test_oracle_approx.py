@@ -150,7 +150,7 @@ def test_cover_structure(N, M):
 
 
 def test_lemma_bound_with_brute_force_optimum():
-    # Lemma (Sec. 4 / App. A.2): W(P) <= 2 W*, with W* from enumeration of Eq. 1's feasible set.
+    # Lemma (Sec. 4 / App. A.2): W(P) <= 2 W*, with W* from enumeration of Eq. 3's feasible set.
     for N, M in ((2, 4), (1, 4), (3, 4), (2, 5)):
         pats = refs.valid_patterns(N, M)
         for w in (wl.gaussian_f32(16 * M, 16 * M, seed=31), wl.tie_heavy_f32(16 * M, 16 * M, seed=32)):

@@ -1,4 +1,4 @@
-"""Pins for the oracle's exact solver (Eq. 1 through the Fig. 3 min-cost flow), CPU only."""
+"""Pins for the oracle's exact solver (Eq. 3 through the Fig. 3 min-cost flow), CPU only."""
 import numpy as np
 import pytest
 

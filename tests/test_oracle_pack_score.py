@@ -92,3 +92,54 @@ def test_empty_mask_packs_fillers_only():
     assert not vals.any() and not valsT.any()
     # fillers take positions 0 and 1 of each group: slots (0,1) -> bits 00,01 -> nibble 0b0100
     assert np.all(idx == 0x44) and np.all(idxT == 0x44)
+
+
+# ---- oracle.spmm: products with the packed operands (forward W, backward W^T) ----
+
+def _spmm_case(seed, rows=16, cols=64, tokens=5):
+    w = wl.f32_to_bf16_bits(wl.gaussian_f32(rows, cols, seed, std=0.5))
+    mask, _ = oracle.exact(w, 2, 4)
+    x = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, cols, seed + 1))
+    g = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, rows, seed + 2))
+    return w, mask, x, g
+
+
+def test_spmm_matches_pure_python_loops():
+    # brute force with Python floats (doubles), no numpy product, on a tiny case
+    w, mask, x, g = _spmm_case(700, rows=8, cols=8, tokens=3)
+    vals, idx, valsT, idxT = oracle.apply_pack(w, mask, 2, 4)
+    wf, xf, gf = oracle.bf16_to_f64(w), oracle.bf16_to_f64(x), oracle.bf16_to_f64(g)
+    fwd = oracle.spmm(vals, idx, 8, 8, 2, 4, x)
+    bwd = oracle.spmm(valsT, idxT, 8, 8, 2, 4, g)
+    for t in range(3):
+        for r in range(8):
+            acc = 0.0
+            for c in range(8):
+                if mask[r, c]:
+                    acc += float(xf[t, c]) * float(wf[r, c])
+            assert fwd[t, r] == pytest.approx(acc, rel=1e-14, abs=1e-300)
+        for c in range(8):
+            acc = 0.0
+            for r in range(8):
+                if mask[r, c]:
+                    acc += float(gf[t, r]) * float(wf[r, c])       # (W^T g)_c = sum_r W[r][c] g[r]
+            assert bwd[t, c] == pytest.approx(acc, rel=1e-14, abs=1e-300)
+
+
+def test_spmm_identity_and_linearity():
+    w, mask, x, g = _spmm_case(710)
+    vals, idx, valsT, idxT = oracle.apply_pack(w, mask, 2, 4)
+    masked = np.where(mask != 0, oracle.bf16_to_f64(w), 0.0)
+    eye_in = np.eye(64, dtype=np.float32)
+    assert np.array_equal(oracle.spmm(vals, idx, 16, 64, 2, 4, eye_in), masked.T)       # x = I  ->  y = Wd^T
+    eye_out = np.eye(16, dtype=np.float32)
+    assert np.array_equal(oracle.spmm(valsT, idxT, 64, 16, 2, 4, eye_out), masked)     # backward with g = I -> Wd
+    xf = oracle.bf16_to_f64(x)
+    y = oracle.spmm(vals, idx, 16, 64, 2, 4, x)
+    y2 = oracle.spmm(vals, idx, 16, 64, 2, 4, (2.0 * xf).astype(np.float32))
+    np.testing.assert_allclose(y2, 2.0 * y, rtol=1e-14)
+    # <W x, g> = <x, W^T g>: forward and backward operands describe the same matrix
+    gf = oracle.bf16_to_f64(g)
+    lhs = float((y * gf).sum())
+    rhs = float((xf * oracle.spmm(valsT, idxT, 64, 16, 2, 4, g)).sum())
+    assert lhs == pytest.approx(rhs, rel=1e-12)
