@@ -16,10 +16,11 @@
 // two consecutive groups, low nibble first, two bits per value in slot order: exactly eight index bits of
 // the instruction, so the packed operands feed it unchanged.
 //
-// Tiling: a workgroup (4 wavefronts, 2 x 2) computes 128 rows x 128 tokens; each wavefront 64 x 64 =
-// 4 x 4 instruction tiles (64 accumulator registers).  k advances by 64 per step; the compressed A tile
-// (128 x 32 values + 128 x 8 index bytes) and the B tile (128 tokens x 64) go global -> registers -> LDS,
-// double-buffered, one barrier per step.  LDS rows are padded so that fragment reads are conflict-free.
+// Tiling: a workgroup (4 wavefronts, 2 x 2) computes 256 rows x 128 tokens; each wavefront 128 x 64 =
+// 8 x 4 instruction tiles (128 accumulator registers).  k advances by 64 per step; the compressed A tile
+// (256 x 32 values + 256 x 8 index bytes) and the B tile (128 tokens x 64) go global -> registers -> LDS:
+// one register set and two LDS buffers, loads run one step ahead of the multiplication; one barrier per
+// step.  LDS rows are padded so that fragment reads are conflict-free.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -36,8 +37,12 @@ typedef uint32_t su32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t su32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kSpThreads = 256;
-constexpr int kSpTR = 128;          // rows of Wd per workgroup
-constexpr int kSpTT = 128;          // tokens per workgroup
+constexpr int kSpRT = 8;            // 16-row instruction tiles per wavefront
+constexpr int kSpCT = 4;            // 16-token instruction tiles per wavefront
+constexpr int kSpTR = 2 * kSpRT * 16;   // rows of Wd per workgroup (2 x 2 wavefronts)
+constexpr int kSpTT = 2 * kSpCT * 16;   // tokens per workgroup
+constexpr int kSpAL = kSpTR / 64;   // 16-byte pieces of A a thread moves per step
+constexpr int kSpBL = kSpTT / 32;   // 16-byte pieces of B a thread moves per step
 constexpr int kSpKS = 64;           // k per step (one instruction deep)
 constexpr int kSpAPitch = 72;       // bytes per LDS row of compressed A (64 data + 8 pad)
 constexpr int kSpBPitch = 144;      // bytes per LDS row of B (128 data + 16 pad)
@@ -54,14 +59,16 @@ struct SpmmArgs {
 };
 
 template <bool OUT_BF16>
-__global__ __launch_bounds__(kSpThreads) void spmm24_kernel(const SpmmArgs p)
+__global__ __launch_bounds__(kSpThreads, 2) void spmm24_kernel(const SpmmArgs p)
 {
     __shared__ __attribute__((aligned(16))) unsigned char As[2][kSpTR * kSpAPitch];
     __shared__ __attribute__((aligned(16))) unsigned char Bs[2][kSpTT * kSpBPitch];
     __shared__ __attribute__((aligned(16))) unsigned char Is[2][kSpTR * kSpIPitch];
 
-    // Workgroups are handed to the eight XCDs round-robin; give each XCD a contiguous range of tiles so
-    // that the tiles sharing rows of Wd meet in one L2.
+    // Workgroups are handed to the eight XCDs round-robin; give each XCD a contiguous range of tile numbers,
+    // and number the tiles so that 64 consecutive ones form an 8 x 8 block of the output: the workgroups
+    // that run on one XCD at the same time then share 8 row panels of Wd and 8 token panels of x in its L2
+    // instead of streaming 64 of each.
     const uint32_t n_tiles = p.tiles_r * p.tiles_t;
     uint32_t id = blockIdx.x;
     {
@@ -69,50 +76,80 @@ __global__ __launch_bounds__(kSpThreads) void spmm24_kernel(const SpmmArgs p)
         if (id < per * 8u)
             id = (id & 7u) * per + (id >> 3);
     }
-    const uint32_t tr = id / p.tiles_t, tt = id - tr * p.tiles_t;
+    constexpr uint32_t kGroup = 8;
+    const uint32_t in_group = kGroup * p.tiles_t;
+    const uint32_t group = id / in_group, rem = id - group * in_group;
+    const uint32_t first_r = group * kGroup;
+    const uint32_t group_rows = min(p.tiles_r - first_r, kGroup);
+    const uint32_t tt = rem / group_rows;
+    const uint32_t tr = first_r + (rem - tt * group_rows);
     const uint32_t row0 = tr * kSpTR, tok0 = tt * kSpTT;
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t wr = wave >> 1, wc = wave & 1u;
 
     // ---- global -> register staging (rows and tokens past the edge re-read the last valid one) ----
-    const uint32_t g_row = min(row0 + (tid >> 1), p.rows - 1u);       // A: 2 threads per row, 32 B each
-    const uint32_t g_tok = min(tok0 + (tid >> 1), p.tokens - 1u);     // B: 2 threads per token, 64 B each
-    const uint32_t i_row = min(row0 + (tid & 127u), p.rows - 1u);     // idx: threads 0..127, 8 B each
-    const unsigned char *ga = (const unsigned char *)p.vals + (size_t)g_row * p.cols + (tid & 1u) * 32u;
-    const unsigned char *gb = (const unsigned char *)p.x + (size_t)g_tok * p.ld_x * 2u + (tid & 1u) * 64u;
-    const unsigned char *gi = (const unsigned char *)p.idx + (size_t)i_row * (p.cols >> 3);
-    su32x4 ra[2], rb[4];
-    su32x2 ri = {0u, 0u};
-    auto fetch = [&](uint32_t k0) {
-        // compressed A: cols/2 values per row = cols bytes per row; a step covers 32 values = 64 bytes
-        ra[0] = *(const su32x4 *)(ga + (size_t)k0);
-        ra[1] = *(const su32x4 *)(ga + (size_t)k0 + 16);
+    // Consecutive lanes fetch consecutive 16-byte pieces of one row, so every load instruction covers whole
+    // runs: 8 lanes = the 128 bytes a token contributes to a step, 4 lanes = the 64 bytes of a row of
+    // compressed A.  (One lane per row with several pieces each touches four times as many cache lines per
+    // instruction and measured twice as slow overall.)
+    // Addresses are a wavefront-uniform base (scalar registers) plus a 32-bit lane offset.
+    const unsigned char *base_a = (const unsigned char *)p.vals + (size_t)row0 * p.cols;
+    const unsigned char *base_b = (const unsigned char *)p.x + (size_t)tok0 * p.ld_x * 2u;
+    uint32_t off_b[kSpBL], off_a[kSpAL];
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-            rb[i] = *(const su32x4 *)(gb + (size_t)k0 * 2u + 16 * i);
-        if (tid < 128u)
-            ri = *(const su32x2 *)(gi + (k0 >> 3));
+    for (int i = 0; i < kSpBL; i++) {
+        const uint32_t tok = min(tok0 + (uint32_t)i * 32u + (tid >> 3), p.tokens - 1u);
+        off_b[i] = (tok - tok0) * p.ld_x * 2u + (tid & 7u) * 16u;
+    }
+#pragma unroll
+    for (int i = 0; i < kSpAL; i++) {
+        const uint32_t row = min(row0 + (uint32_t)i * 64u + (tid >> 2), p.rows - 1u);
+        off_a[i] = (row - row0) * p.cols + (tid & 3u) * 16u;
+    }
+    const uint32_t i_row = min(row0 + (tid % kSpTR), p.rows - 1u);     // idx: 8 B per row and step
+    const unsigned char *base_i = (const unsigned char *)p.idx + (size_t)row0 * (p.cols >> 3);
+    const uint32_t off_i = (i_row - row0) * (p.cols >> 3);
+    // The loads of step s + 1 are in flight while step s is multiplied; they then move from registers into
+    // the other LDS buffer.  (A second register set, two steps ahead, measured no faster: the loop is bound
+    // by load and LDS throughput, not by latency.)  Steps past the end re-read the last one with the A
+    // values zeroed, so the loop body has no branch.
+    struct Stage {
+        su32x4 ra[kSpAL], rb[kSpBL];
+        su32x2 ri;
     };
-    auto stash = [&](int buf) {
-        unsigned char *da = &As[buf][(tid >> 1) * kSpAPitch + (tid & 1u) * 32u];
-        *(su32x2 *)(da) = su32x2{ra[0].x, ra[0].y};          // rows are 8-byte aligned only (pitch 72)
-        *(su32x2 *)(da + 8) = su32x2{ra[0].z, ra[0].w};
-        *(su32x2 *)(da + 16) = su32x2{ra[1].x, ra[1].y};
-        *(su32x2 *)(da + 24) = su32x2{ra[1].z, ra[1].w};
-        unsigned char *db = &Bs[buf][(tid >> 1) * kSpBPitch + (tid & 1u) * 64u];
+    Stage st[1];
+    const uint32_t steps = p.cols / kSpKS;
+    auto fetch = [&](Stage &r, uint32_t step) {
+        const uint32_t k0 = min(step, steps - 1u) * kSpKS;
+        // compressed A: cols/2 values per row = cols bytes per row; a step covers 32 values = 64 bytes
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-            *(su32x4 *)(db + 16 * i) = rb[i];
-        if (tid < 128u)
-            *(su32x2 *)&Is[buf][tid * kSpIPitch] = ri;
+        for (int i = 0; i < kSpAL; i++)
+            r.ra[i] = *(const su32x4 *)(base_a + k0 + off_a[i]);
+#pragma unroll
+        for (int i = 0; i < kSpBL; i++)
+            r.rb[i] = *(const su32x4 *)(base_b + (size_t)k0 * 2u + off_b[i]);
+        r.ri = *(const su32x2 *)(base_i + (k0 >> 3) + off_i);      // every thread loads (rows repeat if the tile has fewer than 256)
+    };
+    auto stash = [&](const Stage &r, int buf, uint32_t step) {
+        const uint32_t live = step < steps ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+        for (int i = 0; i < kSpAL; i++) {
+            unsigned char *da = &As[buf][((uint32_t)i * 64u + (tid >> 2)) * kSpAPitch + (tid & 3u) * 16u];
+            *(su32x2 *)(da) = su32x2{r.ra[i].x & live, r.ra[i].y & live};      // rows are 8-byte aligned only (pitch 72)
+            *(su32x2 *)(da + 8) = su32x2{r.ra[i].z & live, r.ra[i].w & live};
+        }
+#pragma unroll
+        for (int i = 0; i < kSpBL; i++)
+            *(su32x4 *)&Bs[buf][((uint32_t)i * 32u + (tid >> 3)) * kSpBPitch + (tid & 7u) * 16u] = r.rb[i];
+        *(su32x2 *)&Is[buf][(tid % kSpTR) * kSpIPitch] = r.ri;             // several writers of a row write the same bytes
     };
 
-    f32x4 acc[4][4];
+    f32x4 acc[kSpRT][kSpCT];
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int i = 0; i < kSpRT; i++)
 #pragma unroll
-        for (int j = 0; j < 4; j++)
+        for (int j = 0; j < kSpCT; j++)
             acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const uint32_t m = lane & 15u, a = lane >> 4;
@@ -121,27 +158,20 @@ __global__ __launch_bounds__(kSpThreads) void spmm24_kernel(const SpmmArgs p)
     const uint32_t a_off = g0 * 4u;                 // bytes: 2 values x 2 bytes per group
     const uint32_t i_off = g0 >> 1;                 // index byte of groups g0, g0+1; groups g0+4, g0+5 are 2 further
 
-    const uint32_t steps = p.cols / kSpKS;
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (uint32_t s = 0; s < steps; s++) {
-        const int cur = (int)(s & 1u);
-        if (s + 1 < steps)
-            fetch((s + 1) * kSpKS);
+    auto multiply = [&](int cur) {
         // B fragments of the wavefront's four token tiles
-        bf16x16 bfrag[4];
+        bf16x16 bfrag[kSpCT];
 #pragma unroll
-        for (int ct = 0; ct < 4; ct++) {
-            const unsigned char *src = &Bs[cur][(wc * 64u + ct * 16u + m) * kSpBPitch + a * 32u];
+        for (int ct = 0; ct < kSpCT; ct++) {
+            const unsigned char *src = &Bs[cur][(wc * (kSpCT * 16u) + ct * 16u + m) * kSpBPitch + a * 32u];
             union { su32x4 u[2]; bf16x16 v; } cv;
             cv.u[0] = *(const su32x4 *)src;
             cv.u[1] = *(const su32x4 *)(src + 16);
             bfrag[ct] = cv.v;
         }
 #pragma unroll
-        for (int rt = 0; rt < 4; rt++) {
-            const uint32_t r = wr * 64u + rt * 16u + m;
+        for (int rt = 0; rt < kSpRT; rt++) {
+            const uint32_t r = wr * (kSpRT * 16u) + rt * 16u + m;
             const unsigned char *src = &As[cur][r * kSpAPitch + a_off];
             union { su32x2 u[2]; bf16x8 v; } av;
             av.u[0] = *(const su32x2 *)src;
@@ -149,21 +179,39 @@ __global__ __launch_bounds__(kSpThreads) void spmm24_kernel(const SpmmArgs p)
             const unsigned char *is = &Is[cur][r * kSpIPitch + i_off];
             const int sel = (int)((uint32_t)is[0] | ((uint32_t)is[2] << 8));
 #pragma unroll
-            for (int ct = 0; ct < 4; ct++)
+            for (int ct = 0; ct < kSpCT; ct++)
                 acc[rt][ct] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av.v, bfrag[ct], acc[rt][ct], sel, 0, 0);
         }
-        if (s + 1 < steps)
-            stash(cur ^ 1);
+    };
+
+    fetch(st[0], 0);
+    stash(st[0], 0, 0);
+    __syncthreads();
+    // The scheduler fences keep the order "issue loads, multiply, then wait for the loads and move them to
+    // LDS": left alone, the compiler hoists the LDS writes (and with them the wait on the loads) above the
+    // multiplications.
+    for (uint32_t s = 0; s < steps; s += 2) {
+        fetch(st[0], s + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        __builtin_amdgcn_sched_barrier(0);
+        stash(st[0], 1, s + 1);
+        __syncthreads();
+        fetch(st[0], s + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(1);                  // step s + 1, all zeros in A if it lies past the end
+        __builtin_amdgcn_sched_barrier(0);
+        stash(st[0], 0, s + 2);
         __syncthreads();
     }
 
     // ---- store: lane holds rows 4a..4a+3 of token column m of each tile: 4 consecutive y entries ----
 #pragma unroll
-    for (int rt = 0; rt < 4; rt++) {
+    for (int rt = 0; rt < kSpRT; rt++) {
 #pragma unroll
-        for (int ct = 0; ct < 4; ct++) {
-            const uint32_t tok = tok0 + wc * 64u + ct * 16u + m;
-            const uint32_t r = row0 + wr * 64u + rt * 16u + a * 4u;
+        for (int ct = 0; ct < kSpCT; ct++) {
+            const uint32_t tok = tok0 + wc * (kSpCT * 16u) + ct * 16u + m;
+            const uint32_t r = row0 + wr * (kSpRT * 16u) + rt * 16u + a * 4u;
             if (tok < p.tokens && r < p.rows) {       // rows is a multiple of 4: the four entries are in or out together
                 const f32x4 v = acc[rt][ct];
                 if constexpr (OUT_BF16) {
@@ -200,8 +248,8 @@ extern "C" int tmask_spmm24(const void *vals, const void *idx, int64_t rows, int
         return fail(TMASK_ERR_SHAPE,
                     "rows=%lld (multiple of 4) cols=%lld (multiple of 64) tokens=%lld ld_x=%lld (>= cols) ld_y=%lld (>= rows)",
                     (long long)rows, (long long)cols, (long long)tokens, (long long)ld_x, (long long)ld_y);
-    if (rows > 0x7FFFFFFFll || cols > 0x7FFFFFFFll || tokens > 0x7FFFFFFFll || ld_x > 0x7FFFFFFFll || ld_y > 0x7FFFFFFFll)
-        return fail(TMASK_ERR_SHAPE, "sizes must stay below 2^31");
+    if (rows > 0x7FFFFFFFll || tokens > 0x7FFFFFFFll || ld_y > 0x7FFFFFFFll || cols > (1ll << 22) || ld_x > (1ll << 22))
+        return fail(TMASK_ERR_SHAPE, "rows, tokens, ld_y must stay below 2^31, cols and ld_x at or below 2^22");
     const int64_t ysz = out_dt == TMASK_F32 ? 4 : 2;
     if (((uintptr_t)vals & 15) || ((uintptr_t)idx & 7) || ((uintptr_t)x & 15) || (ld_x % 8) || ((uintptr_t)y & 15) ||
         (ld_y * ysz) % 16)
