@@ -97,6 +97,16 @@ int tmask_exact(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Structured (non-transposable) N:M magnitude pruning, the baseline the paper compares with (Sec. 3,
+ * constraint 2 of the mask-diversity list; Sec. 2): in every group of M consecutive elements of a row
+ * the N heaviest are kept, order = (magnitude, position) as in tmask_approx, so W is N:M sparse along
+ * its rows while W^T in general is not.  Same arguments, layout requirements, mask formats and
+ * objective (sum S|W|) as tmask_approx; blocks play no role beyond rows % M == 0, cols % M == 0.
+ */
+int tmask_prune_1d(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Apply a mask and compress both operands the two training matmuls read (Sec. 1, Eq. 1, the
  * backward pass: forward uses W, backward uses W^T; Sec. 4: N non-zeros per M contiguous elements
  * in both).  The paper fixes no storage format; this one is the library's own:
@@ -181,6 +191,34 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
 int tmask_spmm24(const void *vals, const void *idx, int64_t rows, int64_t cols,
                  const void *x, int64_t ld_x, void *y, int64_t ld_y, int64_t tokens,
                  tmask_dtype out_dt, void *hip_stream);
+
+/*
+ * Number of entries whose kept/pruned state differs between two masks of the same shape: the
+ * mask-flip count of a training loop that recomputes its transposable mask as the weights move
+ * (Sec. 4.1, training from scratch: the mask is extracted again every few iterations from the dense
+ * copy of the weights; flips[0] / (rows*cols) is the flip fraction between two extractions).
+ * mask_a, mask_b: device, format mf (U8: any non-zero byte = kept), leading dimensions in bytes;
+ * flips: device, 8-byte aligned, receives the count.  No workspace; the count is exact.
+ */
+typedef struct {
+    const void *mask_a; int64_t ld_a;
+    const void *mask_b; int64_t ld_b;
+    int64_t rows, cols;
+    uint64_t *flips;
+} tmask_flip_desc;
+
+int tmask_flip_count(const tmask_flip_desc *descs, int n, tmask_mask_fmt mf, void *hip_stream);
+
+/*
+ * Mask diversity (Sec. 3, Eq. 2): the number of masks a structure constraint admits on a tensor of
+ * T elements at sparsity level N/M, as the paper's four closed forms; *log10_md (HOST pointer)
+ * receives log10 of it (the counts overflow doubles already for small tensors).  Pure host arithmetic.
+ * Here, as in the paper's Sec. 3, the forms are symmetric in which N of M entries are zero or kept.
+ */
+typedef enum { TMASK_MD_UNSTRUCTURED = 0, TMASK_MD_STRUCTURED = 1, TMASK_MD_TRANSPOSABLE = 2,
+               TMASK_MD_SEQUENTIAL = 3 } tmask_md_kind;
+
+int tmask_mask_diversity(tmask_md_kind kind, int N, int M, int64_t T, double *log10_md);
 
 /* Upper bound of the workspace any call above needs for these matrices (0 on invalid arguments). */
 size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M);

@@ -49,6 +49,8 @@ def _load():
         L.oracle_apply_pack.argtypes = [vp, ci, i64, i64, i64, ci, ci, vp, i64, vp, vp, vp, vp]
         L.oracle_unpack.restype = ci
         L.oracle_unpack.argtypes = [vp, vp, ci, i64, i64, ci, ci, vp]
+        L.oracle_prune_1d.restype = ci
+        L.oracle_prune_1d.argtypes = [vp, ci, i64, i64, i64, ci, ci, vp, i64, vp]
         L.oracle_network_sizes.restype = None
         L.oracle_network_sizes.argtypes = [ci, ci, vp]
         _lib = L
@@ -165,6 +167,43 @@ def unpack(vals: np.ndarray, idx: np.ndarray, R: int, Ccols: int, N: int, M: int
     dense = np.zeros((R, Ccols), dtype=vals.dtype)
     _check(_load().oracle_unpack(_ptr(vals), _ptr(idx), dt, R, Ccols, N, M, _ptr(dense)), "oracle_unpack")
     return dense
+
+
+def prune_1d(w: np.ndarray, N: int, M: int):
+    """Structured N:M magnitude pruning along rows (groups of M consecutive elements keep their N heaviest)
+    -> (mask, retained L1).  The non-transposable baseline of Sec. 3."""
+    w, dt = _prep(w)
+    rows, cols = w.shape
+    mask = np.zeros((rows, cols), dtype=np.uint8)
+    obj = np.zeros(1, dtype=np.float64)
+    _check(_load().oracle_prune_1d(_ptr(w), dt, rows, cols, w.strides[0] // w.itemsize, N, M, _ptr(mask), cols,
+                                   _ptr(obj)), "oracle_prune_1d")
+    return mask, float(obj[0])
+
+
+def flip_count(mask_a: np.ndarray, mask_b: np.ndarray) -> int:
+    """Number of entries whose kept (non-zero) / pruned (zero) state differs between two masks."""
+    return int(((np.asarray(mask_a) != 0) != (np.asarray(mask_b) != 0)).sum())
+
+
+def mask_diversity_log10(kind: str, N: int, M: int, T: int) -> float:
+    """log10 of the mask diversity of Sec. 3 (Eq. 2) in exact integer arithmetic.
+    kind: 'unstructured' | 'structured' | 'transposable' | 'sequential'; T = tensor size, sparsity N/M."""
+    import math
+    if kind == "unstructured":
+        md = math.comb(T, N * T // M)
+    elif kind == "structured":
+        md = math.comb(M, N) ** (T // M)
+    elif kind == "transposable":
+        per_block = 1
+        for q in range(N):
+            per_block *= math.factorial(M - q)            # M! (M-1)! ... (M-N+1)!
+        md = per_block ** (T // (M * M))
+    elif kind == "sequential":
+        md = (M - N + 1) ** (T // M)
+    else:
+        raise ValueError(kind)
+    return math.log10(md)
 
 
 def bf16_to_f64(bits: np.ndarray) -> np.ndarray:

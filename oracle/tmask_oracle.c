@@ -21,6 +21,8 @@
  *   oracle_apply_pack  W (.) S and compression of W and W^T into N values + N indices per group
  *                      of M (format is this project's; the paper only motivates it in Sec. 4)
  *   oracle_unpack      inverse of the packing, used by round-trip checks
+ *   oracle_prune_1d    structured N:M magnitude pruning along rows (Sec. 3, constraint 2), the
+ *                      non-transposable baseline
  *
  * Pins (tests/test_oracle_*.py): brute force over all valid patterns for tiny (N,M), an LP
  * solved by an independent library, the assignment-problem special case, the appendix's 7/4
@@ -340,6 +342,44 @@ int oracle_exact(const void *w, int dtype, int64_t rows, int64_t cols, int64_t l
                  uint8_t *mask, int64_t mask_ld, double *objective, double *per_block, int n_threads)
 {
     return run_mask(1, w, dtype, rows, cols, ld, N, M, mask, mask_ld, objective, per_block, n_threads);
+}
+
+/* ------------------------------------------------------------------ 1-D N:M pruning --------- */
+
+/* Structured (non-transposable) N:M magnitude pruning, the baseline of Sec. 3 (constraint 2 of the
+ * mask-diversity list): in every group of M consecutive elements of a row the M - N lightest are pruned,
+ * lightest = smallest (magnitude key, position).  Written as the definition: order the group with a stable
+ * insertion sort, prune the first M - N.  objective = sum S|W|. */
+int oracle_prune_1d(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld, int N, int M,
+                    uint8_t *mask, int64_t mask_ld, double *objective)
+{
+    if (!w || !mask || rows <= 0 || cols <= 0 || M < 2 || M > ORACLE_MAX_M || N <= 0 || N >= M || cols % M ||
+        ld < cols || mask_ld < cols)
+        return ORACLE_ERR_ARG;
+    double obj = 0.0;
+    for (int64_t r = 0; r < rows; r++)
+        for (int64_t g = 0; g < cols / M; g++) {
+            int order[ORACLE_MAX_M];
+            for (int j = 0; j < M; j++) {          /* stable insertion sort by magnitude key */
+                uint32_t kj = abs_key(w, dtype, r * ld + g * M + j);
+                int pos = j;
+                while (pos > 0 && abs_key(w, dtype, r * ld + g * M + order[pos - 1]) > kj) {
+                    order[pos] = order[pos - 1];
+                    pos--;
+                }
+                order[pos] = j;
+            }
+            for (int q = 0; q < M; q++) {
+                int j = order[q];
+                uint8_t keep = q >= M - N;
+                mask[r * mask_ld + g * M + j] = keep;
+                if (keep)
+                    obj += abs_val(w, dtype, r * ld + g * M + j);
+            }
+        }
+    if (objective)
+        *objective = obj;
+    return ORACLE_OK;
 }
 
 /* ------------------------------------------------------------------ score ------------------- */

@@ -21,7 +21,7 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_apply_pack", "tmask_approx_pack", "tmask_spmm24", "tmask_score",
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_score",
            "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
@@ -49,6 +49,11 @@ class tmask_fused_desc(C.Structure):
                 ("objective", C.c_void_p)]
 
 
+class tmask_flip_desc(C.Structure):
+    _fields_ = [("mask_a", C.c_void_p), ("ld_a", C.c_int64), ("mask_b", C.c_void_p), ("ld_b", C.c_int64),
+                ("rows", C.c_int64), ("cols", C.c_int64), ("flips", C.c_void_p)]
+
+
 class tmask_score_out(C.Structure):
     _fields_ = [("retained_l1", C.c_double), ("total_l1", C.c_double), ("kept", C.c_uint64),
                 ("row_violations", C.c_uint64), ("col_violations", C.c_uint64),
@@ -69,7 +74,7 @@ def load_library():
                            "(there is no fallback path)")
     L = C.CDLL(LIB_PATH)
     vp, ci, sz = C.c_void_p, C.c_int, C.c_size_t
-    for name in ("tmask_approx", "tmask_exact"):
+    for name in ("tmask_approx", "tmask_exact", "tmask_prune_1d"):
         f = getattr(L, name)
         f.restype = ci
         f.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, sz, vp]
@@ -79,6 +84,10 @@ def load_library():
     L.tmask_approx_pack.argtypes = [C.POINTER(tmask_fused_desc), ci, ci, ci, ci, ci, vp, sz, vp]
     L.tmask_spmm24.restype = ci
     L.tmask_spmm24.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, vp, C.c_int64, C.c_int64, ci, vp]
+    L.tmask_flip_count.restype = ci
+    L.tmask_flip_count.argtypes = [C.POINTER(tmask_flip_desc), ci, ci, vp]
+    L.tmask_mask_diversity.restype = ci
+    L.tmask_mask_diversity.argtypes = [ci, ci, ci, C.c_int64, C.POINTER(C.c_double)]
     L.tmask_score.restype = ci
     L.tmask_score.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     L.tmask_workspace_bytes.restype = sz
@@ -245,6 +254,12 @@ def tmask_exact(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = N
     _run_mask(load_library().tmask_exact, ws, masks, N, M, objective, mask_fmt, workspace, stream)
 
 
+def tmask_prune_1d(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = None,
+                   mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Structured N:M magnitude pruning along rows (non-transposable baseline); same arguments as tmask_approx."""
+    _run_mask(load_library().tmask_prune_1d, ws, masks, N, M, objective, mask_fmt, workspace, stream)
+
+
 def tmask_score(ws, masks, N: int, M: int, out: torch.Tensor, per_block_obj: Optional[torch.Tensor] = None,
                 mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     """out: CUDA uint8 tensor of len(ws) * SCORE_OUT_BYTES bytes (array of tmask_score_out)."""
@@ -316,6 +331,32 @@ def tmask_spmm24(vals: torch.Tensor, idx: torch.Tensor, rows: int, cols: int, x:
         raise ValueError("vals must be rows x cols/2 and idx rows x cols/8, contiguous")
     _check(load_library().tmask_spmm24(vals.data_ptr(), idx.data_ptr(), rows, cols, x.data_ptr(), x.stride(0),
                                        y.data_ptr(), y.stride(0), x.shape[0], dtype_code(y), _stream_ptr(stream)))
+
+
+MD_KINDS = {"unstructured": 0, "structured": 1, "transposable": 2, "sequential": 3}
+
+
+def tmask_flip_count(masks_a, masks_b, cols, flips: torch.Tensor, mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
+    """flips[k] (uint64 held in an int64 device tensor) = entries of masks_a[k] and masks_b[k] that differ in
+    kept/pruned state.  cols[k] = logical columns of matrix k (the row length in entries)."""
+    n = len(masks_a)
+    if flips.dtype != torch.int64 or flips.numel() < n or not flips.is_cuda or not flips.is_contiguous():
+        raise ValueError("flips must be a contiguous int64 device tensor with one entry per matrix")
+    arr = (tmask_flip_desc * n)()
+    for k, (a, b) in enumerate(zip(masks_a, masks_b)):
+        pa, ra, _, lda = _mat2d(a, "mask_a")
+        pb, rb, _, ldb = _mat2d(b, "mask_b")
+        if ra != rb:
+            raise ValueError("masks must have the same shape")
+        arr[k] = tmask_flip_desc(pa, lda, pb, ldb, ra, int(cols[k]), flips.data_ptr() + 8 * k)
+    _check(load_library().tmask_flip_count(arr, n, mask_fmt, _stream_ptr(stream)))
+
+
+def tmask_mask_diversity(kind: str, N: int, M: int, T: int) -> float:
+    """log10 of the number of masks the constraint admits on T elements at sparsity N/M (host arithmetic)."""
+    out = C.c_double(0.0)
+    _check(load_library().tmask_mask_diversity(MD_KINDS[kind], N, M, T, C.byref(out)))
+    return out.value
 
 
 def tmask_profile_next(start_event: Optional[int], stop_event: Optional[int]) -> None:

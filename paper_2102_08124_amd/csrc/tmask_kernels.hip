@@ -24,7 +24,7 @@ namespace tmask {
 // Kernels
 // =================================================================================================
 
-enum { kSolveApprox = 0, kSolveExact = 1 };
+enum { kSolveApprox = 0, kSolveExact = 1, kSolveRow1D = 2 };
 
 // One workgroup = 256 consecutive strips of one matrix: load M rows x 16 B per lane, solve the
 // block(s) in registers, write the mask, leave one partial objective per workgroup.
@@ -46,6 +46,13 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
         load_strip<DT, M>(md, pos, a, raw);
         if constexpr (SOLVER == kSolveApprox) {
             approx_keep<DT, M>(a, args.K, gpos, bits);
+        } else if constexpr (SOLVER == kSolveRow1D) {
+            // structured N:M along rows only: an entry is kept iff at least K entries of its group of M
+            // precede it in the (magnitude, position) order
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                bits[i] = (1u << Ge::C) - 1u;
+            row_rank_keep<M, Ge::C, Ge::G, Ge::B>(a, args.K, gpos, bits);
         } else if constexpr (M == 4) {
             {
 #pragma unroll
@@ -675,6 +682,12 @@ int tmask_approx(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M
                  size_t workspace_bytes, void *hip_stream)
 {
     return run_mask<kSolveApprox>(mats, n_mats, (int)dt, N, M, (int)mf, workspace, workspace_bytes, hip_stream);
+}
+
+int tmask_prune_1d(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf, void *workspace,
+                   size_t workspace_bytes, void *hip_stream)
+{
+    return run_mask<kSolveRow1D>(mats, n_mats, (int)dt, N, M, (int)mf, workspace, workspace_bytes, hip_stream);
 }
 
 int tmask_exact(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf, void *workspace,

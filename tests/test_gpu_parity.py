@@ -225,3 +225,29 @@ def test_argument_errors_leave_outputs_untouched():
     with pytest.raises(tm.TmaskError) as e:
         tm.tmask_approx([stem], [torch.zeros((64, 147), dtype=torch.uint8, device="cuda")], 2, 4)
     assert e.value.code == tm.TMASK_ERR_SHAPE
+
+
+# ---------------------------------------------------------------- 1-D (non-transposable) pruning
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("N,M", NM + [(1, 4), (3, 4), (5, 8), (3, 16)])
+@pytest.mark.parametrize("kind", ["f32", "bf16", "ties", "ties_bf16", "special"])
+def test_prune_1d_bit_exact_ragged(kind, N, M, fmt):
+    w = _inputs(kind, 5 * M, 1008, seed=1900 + M)
+    (mask,), obj = run_masks(tm.tmask_prune_1d, [w], N, M, fmt)
+    omask, oobj = oracle.prune_1d(w, N, M)
+    assert np.array_equal(mask, omask)
+    if kind != "special":
+        assert obj[0] == pytest.approx(oobj, rel=1e-5)
+
+
+def test_prune_1d_batched_with_strides():
+    rng = np.random.default_rng(19)
+    shapes = [(16, 16), (16, 32), (64, 48), (144, 272), (32, 1040)]
+    ws = [_inputs("bf16" if k % 2 else "f32", *shapes[int(rng.integers(len(shapes)))], seed=1950 + k) for k in range(6)]
+    for group in (ws[0::2], ws[1::2]):                      # one dtype per call
+        masks, obj = run_masks(tm.tmask_prune_1d, group, 4, 8, ld_pad=32)
+        for w, m, o in zip(group, masks, obj):
+            omask, oobj = oracle.prune_1d(w, 4, 8)
+            assert np.array_equal(m, omask)
+            assert o == pytest.approx(oobj, rel=1e-5)

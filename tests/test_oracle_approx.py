@@ -207,3 +207,45 @@ def test_shape_errors():
         oracle.approx(np.zeros((8, 8), np.float32), 4, 4)
     with pytest.raises(ValueError):
         oracle.approx(np.zeros((8, 8), np.float32), 0, 4)
+
+
+# ---- oracle.prune_1d: structured (non-transposable) N:M pruning along rows ----
+
+def _prune_1d_numpy(w, N, M):
+    """Independent statement with numpy: per group of M, stable argsort of the magnitude keys, keep the last N."""
+    keys = refs.magnitude_keys(w) if hasattr(refs, "magnitude_keys") else None
+    if keys is None:
+        keys = (w.view(np.uint32) & 0x7FFFFFFF) if w.dtype == np.float32 else (w & 0x7FFF).astype(np.uint32)
+    rows, cols = w.shape
+    g = keys.reshape(rows, cols // M, M)
+    order = np.argsort(g, axis=2, kind="stable")
+    mask = np.zeros_like(g, dtype=np.uint8)
+    np.put_along_axis(mask, order[:, :, M - N:], 1, axis=2)
+    return mask.reshape(rows, cols)
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (8, 16), (1, 4), (3, 4), (5, 8), (1, 2)])
+def test_prune_1d_matches_numpy_statement(N, M):
+    for w in (wl.gaussian_f32(6, 16 * M, seed=900 + M), wl.tie_heavy_f32(8, 8 * M, seed=901 + N),
+              wl.special_values_f32(4, 16 * M, seed=902), wl.f32_to_bf16_bits(wl.gaussian_f32(8, 8 * M, seed=903, std=0.02))):
+        mask, obj = oracle.prune_1d(w, N, M)
+        want = _prune_1d_numpy(w, N, M)
+        assert np.array_equal(mask, want)
+        assert (mask.reshape(w.shape[0], -1, M).sum(axis=2) == N).all()        # exactly N kept per group
+        a = refs.magnitudes(w)
+        with np.errstate(invalid="ignore"):
+            kept = float((a * mask).sum())
+        assert (np.isnan(obj) and np.isnan(kept)) or obj == pytest.approx(kept, rel=1e-12)
+
+
+def test_prune_1d_hand_example_and_relation_to_transposable():
+    w = np.array([[0.1, -0.4, 0.3, 0.4, 0.0, -0.0, 0.0, 1.0]], dtype=np.float32)
+    mask, obj = oracle.prune_1d(w, 2, 4)
+    # group 1: |.| = .1 .4 .3 .4 -> keep the two 0.4 (positions 1, 3); group 2: ties at zero -> later position kept
+    assert mask.tolist() == [[0, 1, 0, 1, 0, 0, 1, 1]]
+    assert obj == pytest.approx(0.4 + 0.4 + 1.0, rel=1e-6)
+    # row-only pruning keeps at least as much L1 as any transposable mask (it is a relaxation of Eq. 3)
+    wb = wl.gaussian_f32(32, 32, seed=910)
+    _, obj1 = oracle.prune_1d(wb, 2, 4)
+    _, obj_t = oracle.exact(wb, 2, 4)
+    assert obj1 >= obj_t * (1 - 1e-12)
