@@ -129,6 +129,49 @@ def fused_approx_pack(tm, torch, ev, mats_np, copies: int, reps: int):
             "frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "weights_per_s": weights / (ms * 1e-3)}
 
 
+def spmm24_products(tm, torch, ev, reps: int = 20, tokens: int = 8192):
+    """The two training products with the packed 2:4 operands of one BERT-large-shaped bf16 layer
+    (W: 4096 x 1024): forward y = x W^T with (vals, idx), backward dx = g W with (valsT, idxT).  MFMA-bound work
+    with its own roofline: dense-equivalent flops (2 * tokens * rows * cols) against the dense bf16 peak."""
+    rows, cols = 4096, 1024
+    w = (torch.randn((rows, cols), device="cuda") * 0.02).to(torch.bfloat16)
+    pk = tm.alloc_packed(w, N_KEEP, M_BLOCK)
+    tm.tmask_approx_pack([w], None, [pk], N_KEEP, M_BLOCK)
+    out = {}
+    ovh = ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
+    for name, vals, idx, r, c in (("forward", pk[0], pk[1], rows, cols), ("backward", pk[2], pk[3], cols, rows)):
+        xs = [torch.randn((tokens, c), device="cuda").to(torch.bfloat16) for _ in range(3)]
+        ys = [torch.empty((tokens, r), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+        for k in range(3):
+            tm.tmask_spmm24(vals, idx, r, c, xs[k], ys[k])
+        torch.cuda.synchronize()
+        evs = [(ev.create(), ev.create()) for _ in range(reps)]
+        for k in range(reps):
+            tm.tmask_profile_next(*evs[k])
+            tm.tmask_spmm24(vals, idx, r, c, xs[k % 3], ys[k % 3])
+        torch.cuda.synchronize()
+        ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - ovh
+        tflops = 2.0 * tokens * r * c / (ms * 1e-3) / 1e12
+        # the dense library product of the same shape, for context
+        wd = torch.randn((r, c), device="cuda").to(torch.bfloat16)
+        for k in range(3):
+            torch.matmul(xs[k], wd.t(), out=ys[k])
+        torch.cuda.synchronize()
+        tev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for k, (a, b) in enumerate(tev):
+            a.record()
+            torch.matmul(xs[k % 3], wd.t(), out=ys[k % 3])
+            b.record()
+        torch.cuda.synchronize()
+        dms = float(np.median([a.elapsed_time(b) for a, b in tev]))
+        out[name] = {"shape": "tokens %d x Wd %d x %d, bf16 in, bf16 out" % (tokens, r, c), "kernel_ms": ms,
+                     "roofline": {"bound": "mfma", "achieved": tflops, "peak": 2500.0, "unit": "TFLOP/s",
+                                  "frac": tflops / 2500.0, "traffic": None,
+                                  "note": "dense-equivalent flops against the dense bf16 peak"},
+                     "dense_library_ms": dms}
+    return out
+
+
 def device_copy_rate(torch, mib: int = 256, reps: int = 10):
     """Context for the roofline fractions: what a plain device-to-device copy (as many bytes written as read)
     reaches on this GPU, three rotating buffer pairs, median of `reps`."""
@@ -278,6 +321,7 @@ def main():
         result["largest_config"] = largest_config_approx(tm, torch, ev, reps=20)
     del sets
     result["fused_approx_pack"] = fused_approx_pack(tm, torch, ev, mats_np, copies=min(args.copies, 6), reps=24)
+    result["spmm24"] = spmm24_products(tm, torch, ev)
     result["device_copy"] = device_copy_rate(torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(mats_np)
