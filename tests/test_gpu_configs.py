@@ -76,6 +76,17 @@ def test_config2_resnet50_full():
         want = oracle.apply_pack(w, em, N, M)
         for g, t in zip(packed[k], want):
             assert np.array_equal(g.cpu().numpy().view(np.uint8), t.view(np.uint8)), "pack, matrix %d" % k
+    # the same 52 matrices through the one-pass call, as bench.py times it (no mask written)
+    fpacked = [tm.alloc_packed(w, N, M) for w in ws]
+    fobj = torch.zeros(len(ws), dtype=torch.float64, device="cuda")
+    tm.tmask_approx_pack(ws, None, fpacked, N, M, objective=fobj, workspace=tm.alloc_workspace(ws, N, M))
+    torch.cuda.synchronize()
+    fobj = fobj.cpu().numpy()
+    for k, w in enumerate(mats):
+        want = oracle.apply_pack(w, amasks[k].cpu().numpy(), N, M)      # amasks equal the oracle's (checked above)
+        for g, t in zip(fpacked[k], want):
+            assert np.array_equal(g.cpu().numpy().view(np.uint8), t.view(np.uint8)), "fused pack, matrix %d" % k
+        assert fobj[k] == pytest.approx(aobj[k], rel=1e-5)
     # the 7x7 stem conv (64 x 147) is not a multiple of 4 wide: rejected, the caller keeps it dense
     stem = torch.zeros((64, 148), device="cuda")[:, :147]
     with pytest.raises(tm.TmaskError) as e:

@@ -97,6 +97,27 @@ def test_operands_packed_on_the_device_feed_the_product():
             <= _bound(valsT, idxT, cols, rows, g_bits)).all()
 
 
+def test_bench_shape_sampled_tokens():
+    """The layer shape bench.py times (W 4096 x 1024 bf16, 8192 tokens, bf16 out), forward and backward, full-size
+    launches; the oracle's float64 product is taken on every 61st token (135 of 8192), all output features."""
+    rows, cols, tokens = 4096, 1024, 8192
+    w_bits = wl.f32_to_bf16_bits(wl.gaussian_f32(rows, cols, seed=6300, std=0.02))
+    w = to_dev(w_bits)
+    pk = tm.alloc_packed(w, 2, 4)
+    tm.tmask_approx_pack([w], None, [pk], 2, 4)
+    mask = oracle.approx(w_bits, 2, 4, threads=8)[0]
+    vals, idx, valsT, idxT = oracle.apply_pack(w_bits, mask, 2, 4)
+    sample = np.arange(0, tokens, 61)
+    for (dv, di, hv, hi, r, c, seed) in ((pk[0], pk[1], vals, idx, rows, cols, 6301), (pk[2], pk[3], valsT, idxT, cols, rows, 6302)):
+        x_bits = wl.f32_to_bf16_bits(wl.gaussian_f32(tokens, c, seed=seed))
+        y = torch.empty((tokens, r), dtype=torch.bfloat16, device="cuda")
+        tm.tmask_spmm24(dv, di, r, c, to_dev(x_bits), y)
+        torch.cuda.synchronize()
+        got = y[torch.from_numpy(sample).cuda()].float().cpu().numpy().astype(np.float64)
+        want = oracle.spmm(hv, hi, r, c, 2, 4, x_bits[sample])
+        assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + _bound(hv, hi, r, c, x_bits[sample])).all()
+
+
 def test_spmm_argument_errors():
     lib = tm.load_library()
     v = torch.zeros((64, 32), dtype=torch.bfloat16, device="cuda")
