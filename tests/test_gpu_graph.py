@@ -1,0 +1,75 @@
+"""The four calls of a benchmark step recorded into a HIP graph: every replay must reproduce the eager results."""
+import numpy as np
+import pytest
+
+from paper_2102_08124_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2102_08124_amd import binding as tm   # noqa: E402
+
+
+def _state(ws, N, M):
+    n = len(ws)
+    return {
+        "amask": tm.alloc_masks(ws), "emask": tm.alloc_masks(ws),
+        "aobj": torch.zeros(n, dtype=torch.float64, device="cuda"),
+        "eobj": torch.zeros(n, dtype=torch.float64, device="cuda"),
+        "packed": [tm.alloc_packed(w, N, M) for w in ws],
+        "sout": torch.zeros(n * tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda"),
+    }
+
+
+def _step(ws, st, wsp, N, M, stream=None):
+    tm.tmask_approx(ws, st["amask"], N, M, objective=st["aobj"], workspace=wsp, stream=stream)
+    tm.tmask_exact(ws, st["emask"], N, M, objective=st["eobj"], workspace=wsp, stream=stream)
+    tm.tmask_apply_pack(ws, st["emask"], st["packed"], N, M, stream=stream)
+    tm.tmask_score(ws, st["amask"], N, M, st["sout"], workspace=wsp, stream=stream)
+
+
+def _snapshot(st):
+    out = [m.clone() for m in st["amask"]] + [m.clone() for m in st["emask"]] + [st["aobj"].clone(), st["eobj"].clone(),
+                                                                              st["sout"].clone()]
+    for pk in st["packed"]:
+        out += [t.clone() for t in pk]
+    return out
+
+
+def test_step_in_a_graph_replays_exactly():
+    N, M = 2, 4
+    shapes = [(64, 64), (128, 576), (256, 1024), (512, 2304)]
+    ws = [torch.from_numpy(wl.gaussian_f32(r, c, seed=8000 + k, std=0.05)).cuda() for k, (r, c) in enumerate(shapes)]
+    wsp = tm.alloc_workspace(ws, N, M)
+    eager = _state(ws, N, M)
+    _step(ws, eager, wsp, N, M)
+    torch.cuda.synchronize()
+    want = _snapshot(eager)
+
+    st = _state(ws, N, M)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        _step(ws, st, wsp, N, M)                  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        _step(ws, st, wsp, N, M)
+    for rep in range(4):
+        # spoil the outputs and do unrelated eager work between replays
+        for m in st["amask"] + st["emask"]:
+            m.fill_(0x5A)
+        st["aobj"].fill_(-1.0)
+        for pk in st["packed"]:
+            for t in pk:
+                t.view(torch.uint8).fill_(0xEE)
+        junk = torch.randn(1 << 20, device="cuda").sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = _snapshot(st)
+        assert len(got) == len(want)
+        for a, b in zip(got, want):
+            assert np.array_equal(a.cpu().numpy().view(np.uint8), b.cpu().numpy().view(np.uint8)), rep
+        del junk
