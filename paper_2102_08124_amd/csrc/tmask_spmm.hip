@@ -16,11 +16,15 @@
 // two consecutive groups, low nibble first, two bits per value in slot order: exactly eight index bits of
 // the instruction, so the packed operands feed it unchanged.
 //
-// Tiling: a workgroup (4 wavefronts, 2 x 2) computes 256 rows x 128 tokens; each wavefront 128 x 64 =
-// 8 x 4 instruction tiles (128 accumulator registers).  k advances by 64 per step; the compressed A tile
-// (256 x 32 values + 256 x 8 index bytes) and the B tile (128 tokens x 64) go global -> registers -> LDS:
-// one register set and two LDS buffers, loads run one step ahead of the multiplication; one barrier per
-// step.  LDS rows are padded so that fragment reads are conflict-free.
+// Tiling: a workgroup computes 256 rows x 128 tokens with eight wavefronts in two roles.  Wavefronts 0-3
+// multiply (2 x 2, each 128 x 64 = 8 x 4 instruction tiles, 128 accumulator registers): they only read
+// fragments from LDS and issue matrix instructions.  Wavefronts 4-7 feed them: per step of k = 64 they move
+// the compressed A tile (256 x 32 values + 256 x 8 index bytes) and the x tile (128 tokens x 64) from global
+// memory through registers into a ring of three LDS buffers, with three register sets, so a load is in flight
+// for three steps before it is needed.  One barrier per step joins the two roles; each SIMD holds one wavefront
+// of each role, so the feeders' waits and LDS writes overlap the multipliers' matrix instructions.  A workgroup
+// is persistent: it takes every G-th tile and treats their steps as one stream, so nothing drains between
+// tiles.  LDS rows are padded so that fragment reads are conflict-free.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -36,7 +40,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t su32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t su32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kSpThreads = 256;
+constexpr int kSpThreads = 512;      // 4 multiplying + 4 feeding wavefronts
+constexpr int kSpFeed = 256;         // threads that move tiles
+constexpr int kSpRing = 3;           // LDS buffers
 constexpr int kSpRT = 8;            // 16-row instruction tiles per wavefront
 constexpr int kSpCT = 4;            // 16-token instruction tiles per wavefront
 constexpr int kSpTR = 2 * kSpRT * 16;   // rows of Wd per workgroup (2 x 2 wavefronts)
@@ -59,177 +65,257 @@ struct SpmmArgs {
 };
 
 template <bool OUT_BF16>
-__global__ __launch_bounds__(kSpThreads, 2) void spmm24_kernel(const SpmmArgs p)
+__global__ __launch_bounds__(kSpThreads, 1) void spmm24_kernel(const SpmmArgs p)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char As[2][kSpTR * kSpAPitch];
-    __shared__ __attribute__((aligned(16))) unsigned char Bs[2][kSpTT * kSpBPitch];
-    __shared__ __attribute__((aligned(16))) unsigned char Is[2][kSpTR * kSpIPitch];
+    __shared__ __attribute__((aligned(16))) unsigned char As[kSpRing][kSpTR * kSpAPitch];
+    __shared__ __attribute__((aligned(16))) unsigned char Bs[kSpRing][kSpTT * kSpBPitch];
+    __shared__ __attribute__((aligned(16))) unsigned char Is[kSpRing][kSpTR * kSpIPitch];
 
-    // Workgroups are handed to the eight XCDs round-robin; give each XCD a contiguous range of tile numbers,
-    // and number the tiles so that 64 consecutive ones form an 8 x 8 block of the output: the workgroups
-    // that run on one XCD at the same time then share 8 row panels of Wd and 8 token panels of x in its L2
-    // instead of streaming 64 of each.
+    // The grid is one workgroup per compute unit (or per tile if there are fewer); workgroup b works through
+    // tiles b, b + G, b + 2G, ... as ONE stream of steps, so the loads of a tile's first steps are in flight
+    // while the previous tile is still being multiplied and stored.
+    // Tile numbers -> output position: workgroups are handed to the eight XCDs round-robin (b % 8 with G a
+    // multiple of 8), so give each XCD a contiguous range of tile numbers, and number the tiles so that 64
+    // consecutive ones form an 8 x 8 block of the output: the workgroups that run on one XCD at the same time
+    // then share a few row panels of Wd and token panels of x in its L2 instead of streaming one each.
     const uint32_t n_tiles = p.tiles_r * p.tiles_t;
-    uint32_t id = blockIdx.x;
-    {
+    const uint32_t G = gridDim.x, b = blockIdx.x;
+    const uint32_t my_tiles = (n_tiles - b + G - 1u) / G;       // b < G <= n_tiles
+    const uint32_t steps = p.cols / kSpKS;
+    const uint32_t total = my_tiles * steps;                    // steps of this workgroup's stream
+    auto locate = [&](uint32_t j, uint32_t &row0, uint32_t &tok0) {
+        uint32_t id = b + j * G;
         const uint32_t per = n_tiles / 8u;
         if (id < per * 8u)
             id = (id & 7u) * per + (id >> 3);
-    }
-    constexpr uint32_t kGroup = 8;
-    const uint32_t in_group = kGroup * p.tiles_t;
-    const uint32_t group = id / in_group, rem = id - group * in_group;
-    const uint32_t first_r = group * kGroup;
-    const uint32_t group_rows = min(p.tiles_r - first_r, kGroup);
-    const uint32_t tt = rem / group_rows;
-    const uint32_t tr = first_r + (rem - tt * group_rows);
-    const uint32_t row0 = tr * kSpTR, tok0 = tt * kSpTT;
-    const uint32_t tid = threadIdx.x, lane = tid & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t wr = wave >> 1, wc = wave & 1u;
+        constexpr uint32_t kGroup = 8;
+        const uint32_t in_group = kGroup * p.tiles_t;
+        const uint32_t group = id / in_group, rem = id - group * in_group;
+        const uint32_t first_r = group * kGroup;
+        const uint32_t group_rows = min(p.tiles_r - first_r, kGroup);
+        const uint32_t tt = rem / group_rows;
+        row0 = (first_r + (rem - tt * group_rows)) * kSpTR;
+        tok0 = tt * kSpTT;
+    };
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool feeder = wave >= 4u;
 
-    // ---- global -> register staging (rows and tokens past the edge re-read the last valid one) ----
-    // Consecutive lanes fetch consecutive 16-byte pieces of one row, so every load instruction covers whole
-    // runs: 8 lanes = the 128 bytes a token contributes to a step, 4 lanes = the 64 bytes of a row of
-    // compressed A.  (One lane per row with several pieces each touches four times as many cache lines per
-    // instruction and measured twice as slow overall.)
-    // Addresses are a wavefront-uniform base (scalar registers) plus a 32-bit lane offset.
-    const unsigned char *base_a = (const unsigned char *)p.vals + (size_t)row0 * p.cols;
-    const unsigned char *base_b = (const unsigned char *)p.x + (size_t)tok0 * p.ld_x * 2u;
-    uint32_t off_b[kSpBL], off_a[kSpAL];
+    if (feeder) {
+        // ---- global -> registers -> LDS (rows and tokens past the edge re-read the last valid one) ----
+        // Consecutive lanes fetch consecutive 16-byte pieces of one row, so every load instruction covers whole
+        // runs: 8 lanes = the 128 bytes a token contributes to a step, 4 lanes = the 64 bytes of a row of
+        // compressed A.  (One lane per row with several pieces each touches four times as many cache lines per
+        // instruction and measured twice as slow overall.)
+        // Addresses are a wavefront-uniform base (scalar registers) plus a 32-bit lane offset.
+        const uint32_t tid = threadIdx.x & (kSpFeed - 1);          // index among the feeding threads
+        const unsigned char *base_a, *base_b, *base_i;
+        uint32_t off_b[kSpBL], off_a[kSpAL], off_i;
+        auto set_tile = [&](uint32_t j) {
+            uint32_t row0, tok0;
+            locate(j, row0, tok0);
+            base_a = (const unsigned char *)p.vals + (size_t)row0 * p.cols;
+            base_b = (const unsigned char *)p.x + (size_t)tok0 * p.ld_x * 2u;
+            base_i = (const unsigned char *)p.idx + (size_t)row0 * (p.cols >> 3);
 #pragma unroll
-    for (int i = 0; i < kSpBL; i++) {
-        const uint32_t tok = min(tok0 + (uint32_t)i * 32u + (tid >> 3), p.tokens - 1u);
-        off_b[i] = (tok - tok0) * p.ld_x * 2u + (tid & 7u) * 16u;
-    }
+            for (int i = 0; i < kSpBL; i++) {
+                const uint32_t tok = min(tok0 + (uint32_t)i * 32u + (tid >> 3), p.tokens - 1u);
+                off_b[i] = (tok - tok0) * p.ld_x * 2u + (tid & 7u) * 16u;
+            }
 #pragma unroll
-    for (int i = 0; i < kSpAL; i++) {
-        const uint32_t row = min(row0 + (uint32_t)i * 64u + (tid >> 2), p.rows - 1u);
-        off_a[i] = (row - row0) * p.cols + (tid & 3u) * 16u;
-    }
-    const uint32_t i_row = min(row0 + (tid % kSpTR), p.rows - 1u);     // idx: 8 B per row and step
-    const unsigned char *base_i = (const unsigned char *)p.idx + (size_t)row0 * (p.cols >> 3);
-    const uint32_t off_i = (i_row - row0) * (p.cols >> 3);
-    // The loads of step s + 1 are in flight while step s is multiplied; they then move from registers into
-    // the other LDS buffer.  (A second register set, two steps ahead, measured no faster: the loop is bound
-    // by load and LDS throughput, not by latency.)  Steps past the end re-read the last one with the A
-    // values zeroed, so the loop body has no branch.
-    struct Stage {
-        su32x4 ra[kSpAL], rb[kSpBL];
-        su32x2 ri;
-    };
-    Stage st[1];
-    const uint32_t steps = p.cols / kSpKS;
-    auto fetch = [&](Stage &r, uint32_t step) {
-        const uint32_t k0 = min(step, steps - 1u) * kSpKS;
-        // compressed A: cols/2 values per row = cols bytes per row; a step covers 32 values = 64 bytes
+            for (int i = 0; i < kSpAL; i++) {
+                const uint32_t row = min(row0 + (uint32_t)i * 64u + (tid >> 2), p.rows - 1u);
+                off_a[i] = (row - row0) * p.cols + (tid & 3u) * 16u;
+            }
+            const uint32_t i_row = min(row0 + (tid % kSpTR), p.rows - 1u);     // idx: 8 B per row and step
+            off_i = (i_row - row0) * (p.cols >> 3);
+        };
+        struct Stage {
+            su32x4 ra[kSpAL], rb[kSpBL];
+            su32x2 ri;
+        };
+        Stage st[kSpRing];
+        uint32_t fj = 0, fk = 0;          // tile ordinal and k-step of the next fetch
+        set_tile(0);
+        // fetch the next step of the stream; past its end the last step is read again (and never consumed)
+        auto fetch = [&](Stage &r) {
+            const uint32_t k0 = fk * kSpKS;
+            // compressed A: cols/2 values per row = cols bytes per row; a step covers 32 values = 64 bytes
 #pragma unroll
-        for (int i = 0; i < kSpAL; i++)
-            r.ra[i] = *(const su32x4 *)(base_a + k0 + off_a[i]);
+            for (int i = 0; i < kSpAL; i++)
+                r.ra[i] = *(const su32x4 *)(base_a + k0 + off_a[i]);
 #pragma unroll
-        for (int i = 0; i < kSpBL; i++)
-            r.rb[i] = *(const su32x4 *)(base_b + (size_t)k0 * 2u + off_b[i]);
-        r.ri = *(const su32x2 *)(base_i + (k0 >> 3) + off_i);      // every thread loads (rows repeat if the tile has fewer than 256)
-    };
-    auto stash = [&](const Stage &r, int buf, uint32_t step) {
-        const uint32_t live = step < steps ? 0xFFFFFFFFu : 0u;
+            for (int i = 0; i < kSpBL; i++)
+                r.rb[i] = *(const su32x4 *)(base_b + (size_t)k0 * 2u + off_b[i]);
+            r.ri = *(const su32x2 *)(base_i + (k0 >> 3) + off_i);
+            // advance (address arithmetic only: no memory operation inside the branch)
+            if (fk + 1u < steps) {
+                fk++;
+            } else if (fj + 1u < my_tiles) {
+                fk = 0;
+                fj++;
+                set_tile(fj);
+            }
+        };
+        auto stash = [&](const Stage &r, int buf) {
 #pragma unroll
-        for (int i = 0; i < kSpAL; i++) {
-            unsigned char *da = &As[buf][((uint32_t)i * 64u + (tid >> 2)) * kSpAPitch + (tid & 3u) * 16u];
-            *(su32x2 *)(da) = su32x2{r.ra[i].x & live, r.ra[i].y & live};      // rows are 8-byte aligned only (pitch 72)
-            *(su32x2 *)(da + 8) = su32x2{r.ra[i].z & live, r.ra[i].w & live};
+            for (int i = 0; i < kSpAL; i++) {
+                unsigned char *da = &As[buf][((uint32_t)i * 64u + (tid >> 2)) * kSpAPitch + (tid & 3u) * 16u];
+                *(su32x2 *)(da) = su32x2{r.ra[i].x, r.ra[i].y};      // rows are 8-byte aligned only (pitch 72)
+                *(su32x2 *)(da + 8) = su32x2{r.ra[i].z, r.ra[i].w};
+            }
+#pragma unroll
+            for (int i = 0; i < kSpBL; i++)
+                *(su32x4 *)&Bs[buf][((uint32_t)i * 32u + (tid >> 3)) * kSpBPitch + (tid & 7u) * 16u] = r.rb[i];
+            *(su32x2 *)&Is[buf][(tid % kSpTR) * kSpIPitch] = r.ri;
+        };
+        // Stream step g is multiplied out of LDS buffer g % 3 while the feeders write step g + 2 into buffer
+        // (g + 2) % 3 (last read at step g - 1, before the previous barrier) and issue the loads of step g + 5
+        // into the register set they have just emptied.  Both roles run the same number of barriers; each has
+        // its own loop, unrolled by three so that buffers and register sets are static, and its own registers.
+        fetch(st[0]);
+        fetch(st[1]);
+        stash(st[0], 0);
+        stash(st[1], 1);
+        fetch(st[2]);
+        fetch(st[0]);
+        fetch(st[1]);
+        __syncthreads();
+        auto feed = [&](int pos) {                    // pos = g % 3, a compile-time constant at every call
+            const int nxt = (pos + 2) % kSpRing;
+            stash(st[nxt], nxt);                      // step g + 2
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(st[nxt]);                           // step g + 5
+            __syncthreads();
+        };
+        uint32_t g = 0;
+        for (; g + 3 <= total; g += 3) {
+            feed(0);
+            feed(1);
+            feed(2);
         }
+        if (g < total)
+            feed(0);
+        if (g + 1 < total)
+            feed(1);
+    } else {
+        const uint32_t wr = (wave >> 1) & 1u, wc = wave & 1u;     // position of this wavefront in the tile
+        f32x4 acc[kSpRT][kSpCT];
 #pragma unroll
-        for (int i = 0; i < kSpBL; i++)
-            *(su32x4 *)&Bs[buf][((uint32_t)i * 32u + (tid >> 3)) * kSpBPitch + (tid & 7u) * 16u] = r.rb[i];
-        *(su32x2 *)&Is[buf][(tid % kSpTR) * kSpIPitch] = r.ri;             // several writers of a row write the same bytes
-    };
+        for (int i = 0; i < kSpRT; i++)
+#pragma unroll
+            for (int j = 0; j < kSpCT; j++)
+                acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    f32x4 acc[kSpRT][kSpCT];
-#pragma unroll
-    for (int i = 0; i < kSpRT; i++)
-#pragma unroll
-        for (int j = 0; j < kSpCT; j++)
-            acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t m = lane & 15u, a = lane >> 4;
+        // the lane's two runs of compressed A inside a step: groups g0, g0+1 (8 bytes) and g0+4, g0+5
+        const uint32_t g0 = 8u * (a & 1u) + 2u * (a >> 1);
+        const uint32_t a_off = g0 * 4u;                 // bytes: 2 values x 2 bytes per group
+        const uint32_t i_off = g0 >> 1;                 // index byte of groups g0, g0+1; groups g0+4, g0+5 are 2 further
 
-    const uint32_t m = lane & 15u, a = lane >> 4;
-    // the lane's two runs of compressed A inside a step: groups g0, g0+1 (8 bytes) and g0+4, g0+5
-    const uint32_t g0 = 8u * (a & 1u) + 2u * (a >> 1);
-    const uint32_t a_off = g0 * 4u;                 // bytes: 2 values x 2 bytes per group
-    const uint32_t i_off = g0 >> 1;                 // index byte of groups g0, g0+1; groups g0+4, g0+5 are 2 further
-
-    auto multiply = [&](int cur) {
-        // B fragments of the wavefront's four token tiles
-        bf16x16 bfrag[kSpCT];
+        // Fragments of x for a step are read one step ahead (the ring buffer of step g + 1 is complete when step
+        // g starts), and so is the first A fragment: the matrix instructions of a step start without waiting
+        // for LDS, and the remaining A fragments arrive while they run.
+        auto read_b = [&](int buf, bf16x16 (&bfrag)[kSpCT]) {
 #pragma unroll
-        for (int ct = 0; ct < kSpCT; ct++) {
-            const unsigned char *src = &Bs[cur][(wc * (kSpCT * 16u) + ct * 16u + m) * kSpBPitch + a * 32u];
-            union { su32x4 u[2]; bf16x16 v; } cv;
-            cv.u[0] = *(const su32x4 *)src;
-            cv.u[1] = *(const su32x4 *)(src + 16);
-            bfrag[ct] = cv.v;
-        }
+            for (int ct = 0; ct < kSpCT; ct++) {
+                const unsigned char *src = &Bs[buf][(wc * (kSpCT * 16u) + ct * 16u + m) * kSpBPitch + a * 32u];
+                union { su32x4 u[2]; bf16x16 v; } cv;
+                cv.u[0] = *(const su32x4 *)src;
+                cv.u[1] = *(const su32x4 *)(src + 16);
+                bfrag[ct] = cv.v;
+            }
+        };
+        auto read_a = [&](int buf, int rt, bf16x8 &av, int &sel) {
+            const uint32_t r = wr * (kSpRT * 16u) + (uint32_t)rt * 16u + m;
+            const unsigned char *src = &As[buf][r * kSpAPitch + a_off];
+            union { su32x2 u[2]; bf16x8 v; } cv;
+            cv.u[0] = *(const su32x2 *)src;
+            cv.u[1] = *(const su32x2 *)(src + 16);
+            av = cv.v;
+            const unsigned char *is = &Is[buf][r * kSpIPitch + i_off];
+            sel = (int)((uint32_t)is[0] | ((uint32_t)is[2] << 8));
+        };
+        bf16x16 bcur[kSpCT];
+        bf16x8 a0;
+        int sel0;
+        auto multiply = [&](int cur) {
+            const int nxt = (cur + 1) % kSpRing;
+            bf16x16 bnext[kSpCT];
+            bf16x8 a0n;
+            int sel0n;
+            read_b(nxt, bnext);
+            read_a(nxt, 0, a0n, sel0n);
 #pragma unroll
-        for (int rt = 0; rt < kSpRT; rt++) {
-            const uint32_t r = wr * (kSpRT * 16u) + rt * 16u + m;
-            const unsigned char *src = &As[cur][r * kSpAPitch + a_off];
-            union { su32x2 u[2]; bf16x8 v; } av;
-            av.u[0] = *(const su32x2 *)src;
-            av.u[1] = *(const su32x2 *)(src + 16);
-            const unsigned char *is = &Is[cur][r * kSpIPitch + i_off];
-            const int sel = (int)((uint32_t)is[0] | ((uint32_t)is[2] << 8));
+            for (int rt = 0; rt < kSpRT; rt++) {
+                bf16x8 av = a0;
+                int sel = sel0;
+                if (rt > 0)
+                    read_a(cur, rt, av, sel);
+#pragma unroll
+                for (int ct = 0; ct < kSpCT; ct++)
+                    acc[rt][ct] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bcur[ct], acc[rt][ct], sel, 0, 0);
+            }
 #pragma unroll
             for (int ct = 0; ct < kSpCT; ct++)
-                acc[rt][ct] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av.v, bfrag[ct], acc[rt][ct], sel, 0, 0);
-        }
-    };
-
-    fetch(st[0], 0);
-    stash(st[0], 0, 0);
-    __syncthreads();
-    // The scheduler fences keep the order "issue loads, multiply, then wait for the loads and move them to
-    // LDS": left alone, the compiler hoists the LDS writes (and with them the wait on the loads) above the
-    // multiplications.
-    for (uint32_t s = 0; s < steps; s += 2) {
-        fetch(st[0], s + 1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(0);
-        __builtin_amdgcn_sched_barrier(0);
-        stash(st[0], 1, s + 1);
-        __syncthreads();
-        fetch(st[0], s + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(1);                  // step s + 1, all zeros in A if it lies past the end
-        __builtin_amdgcn_sched_barrier(0);
-        stash(st[0], 0, s + 2);
-        __syncthreads();
-    }
-
-    // ---- store: lane holds rows 4a..4a+3 of token column m of each tile: 4 consecutive y entries ----
+                bcur[ct] = bnext[ct];
+            a0 = a0n;
+            sel0 = sel0n;
+        };
+        // lane holds rows 4a..4a+3 of token column m of each instruction tile: 4 consecutive y entries
+        auto store_tile = [&](uint32_t j) {
+            uint32_t row0, tok0;
+            locate(j, row0, tok0);
 #pragma unroll
-    for (int rt = 0; rt < kSpRT; rt++) {
+            for (int rt = 0; rt < kSpRT; rt++) {
 #pragma unroll
-        for (int ct = 0; ct < kSpCT; ct++) {
-            const uint32_t tok = tok0 + wc * (kSpCT * 16u) + ct * 16u + m;
-            const uint32_t r = row0 + wr * (kSpRT * 16u) + rt * 16u + a * 4u;
-            if (tok < p.tokens && r < p.rows) {       // rows is a multiple of 4: the four entries are in or out together
-                const f32x4 v = acc[rt][ct];
-                if constexpr (OUT_BF16) {
-                    su32x2 o;
-                    auto rne = [](float f) -> uint32_t {
-                        const uint32_t u = __float_as_uint(f);
-                        if ((u & 0x7FFFFFFFu) > 0x7F800000u)
-                            return (u >> 16) | 0x40u;                     // NaN stays NaN
-                        return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;    // round to nearest even
-                    };
-                    o.x = rne(v.x) | (rne(v.y) << 16);
-                    o.y = rne(v.z) | (rne(v.w) << 16);
-                    *(su32x2 *)((unsigned char *)p.y + ((size_t)tok * p.ld_y + r) * 2u) = o;
-                } else {
-                    *(f32x4 *)((unsigned char *)p.y + ((size_t)tok * p.ld_y + r) * 4u) = v;
+                for (int ct = 0; ct < kSpCT; ct++) {
+                    const uint32_t tok = tok0 + wc * (kSpCT * 16u) + ct * 16u + m;
+                    const uint32_t r = row0 + wr * (kSpRT * 16u) + rt * 16u + a * 4u;
+                    if (tok < p.tokens && r < p.rows) {       // rows is a multiple of 4: the four entries are in or out together
+                        const f32x4 v = acc[rt][ct];
+                        if constexpr (OUT_BF16) {
+                            su32x2 o;
+                            auto rne = [](float f) -> uint32_t {
+                                const uint32_t u = __float_as_uint(f);
+                                if ((u & 0x7FFFFFFFu) > 0x7F800000u)
+                                    return (u >> 16) | 0x40u;                     // NaN stays NaN
+                                return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;    // round to nearest even
+                            };
+                            o.x = rne(v.x) | (rne(v.y) << 16);
+                            o.y = rne(v.z) | (rne(v.w) << 16);
+                            *(su32x2 *)((unsigned char *)p.y + ((size_t)tok * p.ld_y + r) * 2u) = o;
+                        } else {
+                            *(f32x4 *)((unsigned char *)p.y + ((size_t)tok * p.ld_y + r) * 4u) = v;
+                        }
+                    }
+                    acc[rt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
             }
+        };
+        uint32_t mj = 0, mk = 0;          // tile ordinal and k-step being multiplied
+        auto mult = [&](int pos) {
+            multiply(pos);
+            __syncthreads();
+            if (++mk == steps) {          // the tile is complete: write it while the feeders run ahead
+                store_tile(mj);
+                mk = 0;
+                mj++;
+            }
+        };
+        __syncthreads();
+        read_b(0, bcur);
+        read_a(0, 0, a0, sel0);
+        uint32_t g = 0;
+        for (; g + 3 <= total; g += 3) {
+            mult(0);
+            mult(1);
+            mult(2);
         }
+        if (g < total)
+            mult(0);
+        if (g + 1 < total)
+            mult(1);
     }
 }
 
@@ -264,13 +350,24 @@ extern "C" int tmask_spmm24(const void *vals, const void *idx, int64_t rows, int
     const uint64_t n_tiles = (uint64_t)p.tiles_r * p.tiles_t;
     if (n_tiles > 0x7FFFFFFFull)
         return fail(TMASK_ERR_SHAPE, "too many tiles");
+    // one workgroup per compute unit, a multiple of 8 (the XCD count) when there are that many tiles
+    static thread_local int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    uint32_t grid = n_tiles < (uint64_t)cus ? (uint32_t)n_tiles : (uint32_t)cus;
+    if (grid >= 8)
+        grid &= ~7u;
     hipStream_t stream = (hipStream_t)hip_stream;
     {
         ProfileScope prof(stream, true);
         if (out_dt == TMASK_BF16)
-            hipLaunchKernelGGL(spmm24_kernel<true>, dim3((uint32_t)n_tiles), dim3(kSpThreads), 0, stream, p);
+            hipLaunchKernelGGL(spmm24_kernel<true>, dim3(grid), dim3(kSpThreads), 0, stream, p);
         else
-            hipLaunchKernelGGL(spmm24_kernel<false>, dim3((uint32_t)n_tiles), dim3(kSpThreads), 0, stream, p);
+            hipLaunchKernelGGL(spmm24_kernel<false>, dim3(grid), dim3(kSpThreads), 0, stream, p);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess)
