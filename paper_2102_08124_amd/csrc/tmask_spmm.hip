@@ -275,15 +275,13 @@ __global__ __launch_bounds__(kSpThreads, 1) void spmm24_kernel(const SpmmArgs p)
                     if (tok < p.tokens && r < p.rows) {       // rows is a multiple of 4: the four entries are in or out together
                         const f32x4 v = acc[rt][ct];
                         if constexpr (OUT_BF16) {
-                            su32x2 o;
-                            auto rne = [](float f) -> uint32_t {
-                                const uint32_t u = __float_as_uint(f);
-                                if ((u & 0x7FFFFFFFu) > 0x7F800000u)
-                                    return (u >> 16) | 0x40u;                     // NaN stays NaN
-                                return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;    // round to nearest even
-                            };
-                            o.x = rne(v.x) | (rne(v.y) << 16);
-                            o.y = rne(v.z) | (rne(v.w) << 16);
+                            // fp32 -> bf16, round to nearest even, by the hardware's packed conversion
+                            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                            typedef float f32x2 __attribute__((ext_vector_type(2)));
+                            union { bf16x2 h; uint32_t u; } c0, c1;
+                            c0.h = __builtin_convertvector(f32x2{v.x, v.y}, bf16x2);
+                            c1.h = __builtin_convertvector(f32x2{v.z, v.w}, bf16x2);
+                            const su32x2 o = {c0.u, c1.u};
                             *(su32x2 *)((unsigned char *)p.y + ((size_t)tok * p.ld_y + r) * 2u) = o;
                         } else {
                             *(f32x4 *)((unsigned char *)p.y + ((size_t)tok * p.ld_y + r) * 4u) = v;
