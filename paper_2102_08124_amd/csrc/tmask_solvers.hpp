@@ -323,13 +323,14 @@ __device__ __forceinline__ uint32_t lm_pick(lanemask_t m, uint32_t a, uint32_t b
     return r;
 }
 
-template <int M, int CL, int G>
-__device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint32_t K, uint32_t gpos,
-                                              uint32_t (&xcol)[CL])
-{
-    constexpr int S = (M == 16) ? 26 : 27;
-    static_assert((M - 1) * (1ll << S) < kReachable, "labels must stay below the reachability threshold");
+constexpr int exact_cost_bits(int M) { return (M == 16) ? 26 : 27; }
 
+// |W| keys (fp32 bit patterns) of one block -> integer costs, see above.
+template <int M, int CL, int G>
+__device__ __forceinline__ void exact_costs(const uint32_t (&key)[M][CL], int (&cost)[M][CL])
+{
+    constexpr int S = exact_cost_bits(M);
+    static_assert((M - 1) * (1ll << S) < kReachable, "labels must stay below the reachability threshold");
     // ---- integer costs ----
     uint32_t kmax = 0;
 #pragma unroll
@@ -346,7 +347,6 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
         kmax = o > kmax ? o : kmax;
     }
     const uint32_t emax = (kmax >> 23) ? (kmax >> 23) : 1u;
-    int cost[M][CL];
 #pragma unroll
     for (int i = 0; i < M; i++)
 #pragma unroll
@@ -357,6 +357,12 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
             cost[i][c] = sh < 32u ? (int)((mant << (S - 24)) >> sh) : 0;
         }
 
+}
+
+// Start: xcol[c] bit i = entry (i, c) pruned.
+template <int M, int CL, int G>
+__device__ __forceinline__ void exact_start(const int (&cost)[M][CL], uint32_t K, uint32_t (&xcol)[CL])
+{
     // ---- start: K lightest rows of every column (ties: lower row first) ----
     if (2 * K == (uint32_t)M) {
         // cost << 4 | row is a distinct key (cost < 2^27, resp. 2^26 with 4 index bits at M = 16):
@@ -397,8 +403,12 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
         }
     }
 
-    // pruned entries per row, identical in the G lanes of the block; kept up to date after each flip
-    uint32_t cnt[M];
+}
+
+// Pruned entries per row, identical in the G lanes of the block.
+template <int M, int CL, int G>
+__device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_t (&cnt)[M])
+{
 #pragma unroll
     for (int i = 0; i < M; i++) {
         uint32_t n = 0;
@@ -411,13 +421,21 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
             n += quad_xor<2>(n);
         cnt[i] = n;
     }
+}
+
+// Up to max_phases searches, each followed by its augmentations; cnt is kept up to date.  Returns true when
+// every row has exactly K pruned entries (always after at most M*M searches).
+template <int M, int CL, int G>
+__device__ __forceinline__ bool exact_phases(const int (&cost)[M][CL], uint32_t K, uint32_t gpos, uint32_t (&xcol)[CL],
+                                             uint32_t (&cnt)[M], int max_phases)
+{
     uint32_t rowid[M];   // row numbers in registers, operands of the selects below
 #pragma unroll
     for (int i = 0; i < M; i++)
         rowid[i] = (uint32_t)i;
 
     // ---- augment until every row has exactly K pruned ----
-    for (int phase = 0; phase < M * M; phase++) {
+    for (int phase = 0; phase < max_phases; phase++) {
         int drow[M];
         uint32_t prow[M];
         lanemask_t any_excess = 0;
@@ -431,7 +449,7 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
             prow[i] = kNoPred;
         }
         if (!lm_test(any_excess))
-            break;
+            return true;
 
         // label-correcting sweeps over the columns
         lanemask_t changed;
@@ -495,39 +513,87 @@ __device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint
             sweeps++;
         } while (lm_test(changed) && sweeps <= M);
 
-        // cheapest reachable row that still lacks pruned entries
-        int best = kInfDist;
-        uint32_t r = 0;
-#pragma unroll
-        for (int i = 0; i < M; i++) {
-            const bool better = ((deficit >> i) & 1u) && (drow[i] < best);
-            best = better ? drow[i] : best;
-            r = better ? (uint32_t)i : r;
-        }
-        if (best >= kReachable)
-            break;   // cannot happen for 0 < K < M; guards against looping on corrupt state
-        const uint32_t target = r;
-
-        // flip the entries along the predecessor chain back to a row with excess
-        for (int step = 0; step < M; step++) {
-            uint32_t p = kNoPred;
-#pragma unroll
-            for (int i = 0; i < M; i++)
-                p = (r == (uint32_t)i) ? prow[i] : p;
-            if (p == kNoPred)
-                break;
-            const uint32_t j = p >> 4, f = p & 15u;
-#pragma unroll
-            for (int c = 0; c < CL; c++)
-                if (j == gpos * CL + c)
-                    xcol[c] ^= (1u << r) | (1u << f);
-            r = f;
-        }
-        // the chain ends in a row with excess: it loses one pruned entry, the target gains one
+        // At convergence every predecessor edge is tight (label of the head = label of the tail + edge cost), so
+        // flipping along ANY predecessor chain keeps the reduced costs of the residual network non-negative:
+        // the pruning stays cheapest for its row imbalances.  One search therefore serves several augmentations:
+        // every reachable row that lacks pruned entries takes its chain, as long as the chains use different
+        // columns and different rows (a row with excess may end several chains while its excess lasts).
+        uint32_t cand = 0;
 #pragma unroll
         for (int i = 0; i < M; i++)
-            cnt[i] += (target == (uint32_t)i ? 1u : 0u) - (r == (uint32_t)i ? 1u : 0u);
+            cand |= (((deficit >> i) & 1u) && drow[i] < kReachable ? 1u : 0u) << i;
+        if (cand == 0u)
+            break;   // cannot happen for 0 < K < M; guards against looping on corrupt state
+        uint32_t used_rows = 0, used_cols = 0;
+        while (cand) {
+            const uint32_t target = (uint32_t)__builtin_ctz(cand);
+            cand &= cand - 1u;
+            // first walk: which rows and columns does the chain use, and where does it end
+            uint32_t r = target, rows = 0, cols = 0;
+            bool ended = false;
+            for (int step = 0; step < M; step++) {
+                uint32_t pp = kNoPred;
+#pragma unroll
+                for (int i = 0; i < M; i++)
+                    pp = (r == (uint32_t)i) ? prow[i] : pp;
+                if (pp == kNoPred) {
+                    ended = true;
+                    break;
+                }
+                rows |= 1u << r;
+                cols |= 1u << (pp >> 4);
+                r = pp & 15u;
+            }
+            uint32_t src_cnt = 0;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                src_cnt = (r == (uint32_t)i) ? cnt[i] : src_cnt;
+            const bool ok = ended && (rows & used_rows) == 0u && (cols & used_cols) == 0u &&
+                            ((used_rows >> r) & 1u) == 0u && src_cnt > K;
+            if (!ok)
+                continue;   // left for the next search
+            used_rows |= rows;
+            used_cols |= cols;
+            // second walk: flip the entries along the chain back to the row with excess
+            const uint32_t src = r;
+            r = target;
+            for (int step = 0; step < M; step++) {
+                uint32_t pp = kNoPred;
+#pragma unroll
+                for (int i = 0; i < M; i++)
+                    pp = (r == (uint32_t)i) ? prow[i] : pp;
+                if (pp == kNoPred)
+                    break;
+                const uint32_t j = pp >> 4, f = pp & 15u;
+#pragma unroll
+                for (int c = 0; c < CL; c++)
+                    if (j == gpos * CL + c)
+                        xcol[c] ^= (1u << r) | (1u << f);
+                r = f;
+            }
+            // the chain's end loses one pruned entry, the target gains one
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                cnt[i] += (target == (uint32_t)i ? 1u : 0u) - (src == (uint32_t)i ? 1u : 0u);
+        }
     }
+    bool excess = false;
+#pragma unroll
+    for (int i = 0; i < M; i++)
+        excess |= cnt[i] > K;
+    return !excess;
+}
+
+template <int M, int CL, int G>
+__device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint32_t K, uint32_t gpos,
+                                              uint32_t (&xcol)[CL])
+{
+    int cost[M][CL];
+    uint32_t cnt[M];
+    exact_costs<M, CL, G>(key, cost);
+    exact_start<M, CL, G>(cost, K, xcol);
+    exact_counts<M, CL, G>(xcol, cnt);
+    (void)exact_phases<M, CL, G>(cost, K, gpos, xcol, cnt, M * M);
 }
 
 }  // namespace tmask
