@@ -220,6 +220,15 @@ typedef enum { TMASK_MD_UNSTRUCTURED = 0, TMASK_MD_STRUCTURED = 1, TMASK_MD_TRAN
 
 int tmask_mask_diversity(tmask_md_kind kind, int N, int M, int64_t T, double *log10_md);
 
+/*
+ * Probability that a block of M independent entries, each prunable with probability rho, is N:M
+ * sparse in the sense of Sec. 5 (at least N of the M can be pruned): Eq. 4, the upper tail of a
+ * binomial distribution.  *prob is a HOST pointer.  Pure host arithmetic.  (The number of
+ * "pattern violations" that forcing an N:M mask onto an unstructured one costs is what
+ * tmask_flip_count returns for the two masks.)
+ */
+int tmask_nm_sparse_probability(int N, int M, double rho, double *prob);
+
 /* Upper bound of the workspace any call above needs for these matrices (0 on invalid arguments). */
 size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M);
 

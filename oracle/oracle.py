@@ -206,6 +206,14 @@ def mask_diversity_log10(kind: str, N: int, M: int, T: int) -> float:
     return math.log10(md)
 
 
+def nm_sparse_probability(N: int, M: int, rho) -> float:
+    """Sec. 5, Eq. 4 in exact rational arithmetic: sum_{i >= N} C(M, i) rho^i (1 - rho)^(M - i)."""
+    import math
+    from fractions import Fraction
+    r = Fraction(rho)
+    return float(sum(math.comb(M, i) * r ** i * (1 - r) ** (M - i) for i in range(N, M + 1)))
+
+
 def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
     """bfloat16 bit patterns (uint16) -> float64, exactly."""
     return (np.ascontiguousarray(bits).astype(np.uint32) << 16).view(np.float32).astype(np.float64)

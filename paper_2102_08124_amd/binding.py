@@ -21,7 +21,7 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_score",
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
            "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
@@ -88,6 +88,8 @@ def load_library():
     L.tmask_flip_count.argtypes = [C.POINTER(tmask_flip_desc), ci, ci, vp]
     L.tmask_mask_diversity.restype = ci
     L.tmask_mask_diversity.argtypes = [ci, ci, ci, C.c_int64, C.POINTER(C.c_double)]
+    L.tmask_nm_sparse_probability.restype = ci
+    L.tmask_nm_sparse_probability.argtypes = [ci, ci, C.c_double, C.POINTER(C.c_double)]
     L.tmask_score.restype = ci
     L.tmask_score.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     L.tmask_workspace_bytes.restype = sz
@@ -356,6 +358,13 @@ def tmask_mask_diversity(kind: str, N: int, M: int, T: int) -> float:
     """log10 of the number of masks the constraint admits on T elements at sparsity N/M (host arithmetic)."""
     out = C.c_double(0.0)
     _check(load_library().tmask_mask_diversity(MD_KINDS[kind], N, M, T, C.byref(out)))
+    return out.value
+
+
+def tmask_nm_sparse_probability(N: int, M: int, rho: float) -> float:
+    """P(at least N of M i.i.d. entries are prunable), each with probability rho (host arithmetic)."""
+    out = C.c_double(0.0)
+    _check(load_library().tmask_nm_sparse_probability(N, M, float(rho), C.byref(out)))
     return out.value
 
 

@@ -1,5 +1,5 @@
 // Small companions of the mask kernels: the mask-flip counter of a dynamic-mask training loop and the
-// mask-diversity formulas (arXiv 2102.08124, Sec. 3, Eq. 2).
+// mask-diversity formulas (arXiv 2102.08124, Sec. 3, Eq. 2) with the N:M probability of Sec. 5, Eq. 4.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -213,5 +213,30 @@ extern "C" int tmask_mask_diversity(tmask_md_kind kind, int N, int M, int64_t T,
         return fail(TMASK_ERR_DTYPE, "unknown constraint kind %d", (int)kind);
     }
     *log10_md = ln / ln10;
+    return TMASK_OK;
+}
+
+// Probability that a block of M i.i.d. entries, each prunable with probability rho, has at least N prunable
+// ones (Sec. 5, Eq. 4): the upper tail of the binomial distribution.
+extern "C" int tmask_nm_sparse_probability(int N, int M, double rho, double *prob)
+{
+    if (!prob)
+        return fail(TMASK_ERR_NULL, "prob is NULL");
+    if (M < 1 || M > 1024 || N < 0 || N > M || !(rho >= 0.0 && rho <= 1.0))
+        return fail(TMASK_ERR_NM, "need 0 <= N <= M <= 1024 and 0 <= rho <= 1 (N=%d M=%d rho=%g)", N, M, rho);
+    double sum = 0.0;
+    for (int i = N; i <= M; i++) {
+        // C(M, i) rho^i (1 - rho)^(M - i), in logs to stay in range; the end points 0 and 1 need no logs
+        double term;
+        if (rho == 0.0)
+            term = i == 0 ? 1.0 : 0.0;
+        else if (rho == 1.0)
+            term = i == M ? 1.0 : 0.0;
+        else
+            term = std::exp(std::lgamma(M + 1.0) - std::lgamma(i + 1.0) - std::lgamma(M - i + 1.0) + i * std::log(rho) +
+                            (M - i) * std::log1p(-rho));
+        sum += term;
+    }
+    *prob = sum > 1.0 ? 1.0 : sum;
     return TMASK_OK;
 }

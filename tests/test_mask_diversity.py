@@ -59,3 +59,32 @@ def test_library_argument_errors():
     with pytest.raises(tm.TmaskError) as e:
         tm.tmask_mask_diversity("transposable", 2, 4, 24)
     assert e.value.code == tm.TMASK_ERR_SHAPE
+
+
+# ---- Sec. 5, Eq. 4: probability that a block is N:M sparse ----
+
+def test_probability_closed_forms_pin_the_oracle():
+    from fractions import Fraction
+    assert oracle.nm_sparse_probability(1, 2, Fraction(1, 2)) == 0.75                 # 1 - P(no prunable entry)
+    assert oracle.nm_sparse_probability(0, 8, Fraction(1, 3)) == 1.0
+    assert oracle.nm_sparse_probability(8, 8, Fraction(1, 2)) == 0.5 ** 8
+    assert oracle.nm_sparse_probability(4, 8, Fraction(1, 2)) == pytest.approx(163 / 256, rel=1e-15)   # (1 + C(8,4)/2^8)/2
+    # complement symmetry: P(at least N | rho) + P(at least M-N+1 | 1-rho) = 1
+    for N, M, rho in ((2, 4, Fraction(3, 10)), (5, 8, Fraction(43, 50)), (9, 16, Fraction(1, 7))):
+        assert oracle.nm_sparse_probability(N, M, rho) + oracle.nm_sparse_probability(M - N + 1, M, 1 - rho) == \
+            pytest.approx(1.0, abs=1e-15)
+    # brute force over all 2^M outcomes on a small block
+    import itertools
+    rho = 0.86
+    want = sum(rho ** sum(o) * (1 - rho) ** (6 - sum(o)) for o in itertools.product((0, 1), repeat=6) if sum(o) >= 4)
+    assert oracle.nm_sparse_probability(4, 6, Fraction(43, 50)) == pytest.approx(want, rel=1e-13)
+
+
+@pytest.mark.parametrize("N,M", [(1, 2), (2, 4), (4, 8), (6, 8), (8, 16), (0, 4), (4, 4), (100, 256)])
+def test_probability_library_matches_oracle(N, M):
+    from fractions import Fraction
+    for rho in (Fraction(0), Fraction(1, 2), Fraction(43, 50), Fraction(1), Fraction(1, 100)):
+        assert tm.tmask_nm_sparse_probability(N, M, float(rho)) == pytest.approx(oracle.nm_sparse_probability(N, M, rho),
+                                                                                 rel=1e-10, abs=1e-300)
+    with pytest.raises(tm.TmaskError):
+        tm.tmask_nm_sparse_probability(5, 4, 0.5)
