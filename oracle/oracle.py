@@ -181,6 +181,27 @@ def prune_1d(w: np.ndarray, N: int, M: int):
     return mask, float(obj[0])
 
 
+def apply_dense(w: np.ndarray, mask: np.ndarray, M: int = 0, absorb_mean: bool = False) -> np.ndarray:
+    """The masked weights W (.) S as a dense fp64 matrix (Sec. 4: what a training step multiplies with when the
+    hardware product is emulated).  With absorb_mean, the bias fix of Sec. 5: in every group of M consecutive
+    entries of a row, the arithmetic mean of the pruned weights is added to each kept weight (groups with
+    nothing pruned, or nothing kept, change nothing beyond the masking)."""
+    w = np.asarray(w, dtype=np.float64)
+    keep = np.asarray(mask) != 0
+    out = np.where(keep, w, 0.0)
+    if absorb_mean:
+        rows, cols = w.shape
+        for r in range(rows):
+            for g in range(0, cols, M):
+                k = keep[r, g:g + M]
+                n_pruned = int((~k).sum())
+                if n_pruned == 0 or n_pruned == M:
+                    continue
+                mean = float(w[r, g:g + M][~k].sum()) / n_pruned
+                out[r, g:g + M][k] += mean
+    return out
+
+
 def flip_count(mask_a: np.ndarray, mask_b: np.ndarray) -> int:
     """Number of entries whose kept (non-zero) / pruned (zero) state differs between two masks."""
     return int(((np.asarray(mask_a) != 0) != (np.asarray(mask_b) != 0)).sum())
