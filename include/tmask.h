@@ -210,6 +210,31 @@ typedef struct {
 int tmask_flip_count(const tmask_flip_desc *descs, int n, tmask_mask_fmt mf, void *hip_stream);
 
 /*
+ * Dense masked copy: out = W (.) S in W's own type, pruned entries as +0 -- the masked weights a
+ * training step multiplies with where the sparse products are emulated by dense ones (Sec. 4.1; the
+ * dense copy W stays untouched and the mask is taken from it again later).  out may be w itself
+ * (in place).  With absorb_mean != 0 the bias fix of Sec. 5 is applied on the way: in every group of
+ * M consecutive entries of a row, the arithmetic mean of the group's pruned weights is added to each
+ * of its kept weights; groups with nothing pruned or nothing kept are only masked.  The mean and the
+ * sums are fp32 (pruned weights in position order inside 16-byte pieces, pieces combined pairwise);
+ * bf16 results are rounded to nearest even.  Any mask is accepted (transposable, 1-D, unstructured):
+ * neither N nor the pattern is checked.  Without absorb_mean, M is ignored.
+ * w, mask, out: device; ld, ld_out in elements, mask_ld in bytes; mask in format mf.
+ * Requirements (checked): cols a multiple of 16 bytes' worth of elements (and of M with absorb_mean,
+ * M in {2, 4, 8, 16, 32}); w, out and their row pitches 16-byte aligned; a U8 mask and its pitch
+ * aligned to 4 (fp32) or 8 (bf16) bytes; BITS masks need cols to be a multiple of 8.  No workspace.
+ */
+typedef struct {
+    const void *w; int64_t ld;
+    const void *mask; int64_t mask_ld;
+    void *out; int64_t ld_out;
+    int64_t rows, cols;
+} tmask_dense_desc;
+
+int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int M, int absorb_mean,
+                      tmask_mask_fmt mf, void *hip_stream);
+
+/*
  * Mask diversity (Sec. 3, Eq. 2): the number of masks a structure constraint admits on a tensor of
  * T elements at sparsity level N/M, as the paper's four closed forms; *log10_md (HOST pointer)
  * receives log10 of it (the counts overflow doubles already for small tensors).  Pure host arithmetic.

@@ -21,7 +21,7 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_apply_dense", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
            "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
@@ -52,6 +52,11 @@ class tmask_fused_desc(C.Structure):
 class tmask_flip_desc(C.Structure):
     _fields_ = [("mask_a", C.c_void_p), ("ld_a", C.c_int64), ("mask_b", C.c_void_p), ("ld_b", C.c_int64),
                 ("rows", C.c_int64), ("cols", C.c_int64), ("flips", C.c_void_p)]
+
+
+class tmask_dense_desc(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("ld", C.c_int64), ("mask", C.c_void_p), ("mask_ld", C.c_int64),
+                ("out", C.c_void_p), ("ld_out", C.c_int64), ("rows", C.c_int64), ("cols", C.c_int64)]
 
 
 class tmask_score_out(C.Structure):
@@ -86,6 +91,8 @@ def load_library():
     L.tmask_spmm24.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, vp, C.c_int64, C.c_int64, ci, vp]
     L.tmask_flip_count.restype = ci
     L.tmask_flip_count.argtypes = [C.POINTER(tmask_flip_desc), ci, ci, vp]
+    L.tmask_apply_dense.restype = ci
+    L.tmask_apply_dense.argtypes = [C.POINTER(tmask_dense_desc), ci, ci, ci, ci, ci, vp]
     L.tmask_mask_diversity.restype = ci
     L.tmask_mask_diversity.argtypes = [ci, ci, ci, C.c_int64, C.POINTER(C.c_double)]
     L.tmask_nm_sparse_probability.restype = ci
@@ -352,6 +359,25 @@ def tmask_flip_count(masks_a, masks_b, cols, flips: torch.Tensor, mask_fmt: int 
             raise ValueError("masks must have the same shape")
         arr[k] = tmask_flip_desc(pa, lda, pb, ldb, ra, int(cols[k]), flips.data_ptr() + 8 * k)
     _check(load_library().tmask_flip_count(arr, n, mask_fmt, _stream_ptr(stream)))
+
+
+def tmask_apply_dense(ws, masks, outs, M: int = 0, absorb_mean: bool = False, mask_fmt: int = TMASK_MASK_U8,
+                      stream=None) -> None:
+    """outs[k] = ws[k] masked by masks[k], in the weights' dtype (outs[k] may be ws[k]); with absorb_mean the mean
+    of the pruned weights of every group of M along a row is added to the group's kept weights."""
+    n = len(ws)
+    arr = (tmask_dense_desc * n)()
+    dt = dtype_code(ws[0])
+    for k, (w, m, o) in enumerate(zip(ws, masks, outs)):
+        if dtype_code(w) != dt or o.dtype != w.dtype:
+            raise ValueError("all matrices and outputs of a call share one dtype")
+        pw, rows, cols, ld = _mat2d(w, "w")
+        pm, mr, _, mld = _mat2d(m, "mask")
+        po, orows, ocols, old = _mat2d(o, "out")
+        if (orows, ocols) != (rows, cols) or mr != rows:
+            raise ValueError("w, mask and out must describe the same matrix")
+        arr[k] = tmask_dense_desc(pw, ld, pm, mld, po, old, rows, cols)
+    _check(load_library().tmask_apply_dense(arr, n, dt, M, 1 if absorb_mean else 0, mask_fmt, _stream_ptr(stream)))
 
 
 def tmask_mask_diversity(kind: str, N: int, M: int, T: int) -> float:

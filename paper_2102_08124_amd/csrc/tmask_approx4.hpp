@@ -72,12 +72,12 @@ __device__ __forceinline__ float approx_2of4_strip(const MatDev &md, StripPos p,
 #pragma unroll
         for (int i = 0; i < 4; i++) {
             if constexpr (C == 4) {
-                __builtin_nontemporal_store(bytes[0][i], (uint32_t *)(base + (size_t)i * md.mask_ld));
+                stream_store(bytes[0][i], (uint32_t *)(base + (size_t)i * md.mask_ld));
             } else {
                 u32x2 v;
                 v.x = bytes[0][i];
                 v.y = bytes[1][i];
-                __builtin_nontemporal_store(v, (u32x2 *)(base + (size_t)i * md.mask_ld));
+                stream_store(v, (u32x2 *)(base + (size_t)i * md.mask_ld));
             }
         }
     } else {

@@ -1,5 +1,5 @@
-// Small companions of the mask kernels: the mask-flip counter of a dynamic-mask training loop and the
-// mask-diversity formulas (arXiv 2102.08124, Sec. 3, Eq. 2) with the N:M probability of Sec. 5, Eq. 4.
+// Small companions of the mask kernels: the mask-flip counter of a dynamic-mask training loop, the dense masked
+// copy with mean absorption, and the mask-diversity formulas (arXiv 2102.08124, Sec. 3, Eq. 2) with the N:M probability of Sec. 5, Eq. 4.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -168,6 +168,231 @@ extern "C" int tmask_flip_count(const tmask_flip_desc *descs, int n, tmask_mask_
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return hip_fail(e, "flip count launch");
+    }
+    return TMASK_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Dense masked copy (Sec. 4) with the optional mean absorption of Sec. 5.
+// ---------------------------------------------------------------------------------------------------------
+namespace tmask {
+
+constexpr int kMaxDenseBatch = 64;
+
+struct DenseDev {
+    const char *w;
+    const unsigned char *mask;
+    char *out;
+    uint32_t rows, chunks_per_row;          // chunk = 16 bytes of a row of W
+    uint32_t ld_b, ld_out_b, mask_ld;       // leading dimensions in bytes
+    uint32_t wg0, n_wg, pad;
+};
+
+struct DenseArgs {
+    DenseDev d[kMaxDenseBatch];
+    uint32_t n;
+};
+static_assert(sizeof(DenseArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+
+// A lane owns 16 bytes of a row: C = 4 (fp32) or 8 (bf16) entries.  A group of M entries is either a part of
+// the lane's chunk (M <= C) or spans G = M / C neighbouring lanes, whose partial sums meet in a butterfly.
+template <int DT, int FMT, int M, bool ABSORB>
+__global__ __launch_bounds__(kThreads) void apply_dense_kernel(const DenseArgs args)
+{
+    constexpr int C = DT == kF32 ? 4 : 8;
+    constexpr int S = M < C ? M : C;          // entries of one group inside a lane
+    constexpr int G = M > C ? M / C : 1;      // lanes per group
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].wg0 <= blockIdx.x)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const DenseDev d = args.d[lo];
+    const uint32_t total = d.rows * d.chunks_per_row;
+    const uint32_t stride = d.n_wg * kThreads;
+    constexpr int U = 4;
+    for (uint32_t base = (blockIdx.x - d.wg0) * U * kThreads; base < total; base += U * stride) {
+        u32x4 raw[U];
+        uint32_t keep[U];                       // C keep bits
+        size_t out_off[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const uint32_t c = base + (uint32_t)u * kThreads + threadIdx.x;
+            raw[u] = u32x4{0u, 0u, 0u, 0u};
+            keep[u] = 0u;
+            out_off[u] = 0;
+            if (c < total) {
+                const uint32_t r = c / d.chunks_per_row, j = c - r * d.chunks_per_row;
+                raw[u] = __builtin_nontemporal_load((const u32x4 *)(d.w + (size_t)r * d.ld_b + (size_t)j * 16u));
+                const unsigned char *mrow = d.mask + (size_t)r * d.mask_ld;
+                if constexpr (FMT == kMaskU8) {
+                    if constexpr (C == 4) {
+                        keep[u] = bytes4_to_bits(__builtin_nontemporal_load((const uint32_t *)(mrow + (size_t)j * 4u)));
+                    } else {
+                        const u32x2 mb = __builtin_nontemporal_load((const u32x2 *)(mrow + (size_t)j * 8u));
+                        keep[u] = bytes4_to_bits(mb.x) | (bytes4_to_bits(mb.y) << 4);
+                    }
+                } else {
+                    if constexpr (C == 4)
+                        keep[u] = ((uint32_t)mrow[j >> 1] >> ((j & 1u) * 4u)) & 0xFu;
+                    else
+                        keep[u] = (uint32_t)mrow[j];
+                }
+                out_off[u] = (size_t)r * d.ld_out_b + (size_t)j * 16u;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            float v[C];
+            const uint32_t q[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+            if constexpr (DT == kF32) {
+#pragma unroll
+                for (int c = 0; c < 4; c++)
+                    v[c] = __uint_as_float(q[c]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    v[2 * c] = __uint_as_float(q[c] << 16);
+                    v[2 * c + 1] = __uint_as_float(q[c] & 0xFFFF0000u);
+                }
+            }
+            if constexpr (ABSORB) {
+#pragma unroll
+                for (int g = 0; g < C / S; g++) {
+                    float ps = 0.f;
+                    uint32_t pc = 0;
+#pragma unroll
+                    for (int c = g * S; c < (g + 1) * S; c++) {
+                        const bool k = (keep[u] >> c) & 1u;
+                        ps += k ? 0.f : v[c];
+                        pc += k ? 0u : 1u;
+                    }
+#pragma unroll
+                    for (int o = 1; o < G; o <<= 1) {
+                        ps += __shfl_xor(ps, o);
+                        pc += (uint32_t)__shfl_xor((int)pc, o);
+                    }
+                    const float mean = (pc != 0u && pc != (uint32_t)M) ? ps / (float)pc : 0.f;
+#pragma unroll
+                    for (int c = g * S; c < (g + 1) * S; c++)
+                        v[c] = ((keep[u] >> c) & 1u) ? v[c] + mean : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < C; c++)
+                    v[c] = ((keep[u] >> c) & 1u) ? v[c] : 0.f;
+            }
+            u32x4 o;
+            if constexpr (DT == kF32) {
+                o = u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+            } else {
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                union { bf16x2 h; uint32_t w; } cv[4];
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    if constexpr (ABSORB) {
+                        cv[c].h = __builtin_convertvector(f32x2{v[2 * c], v[2 * c + 1]}, bf16x2);   // round to nearest even
+                    } else {
+                        cv[c].w = (__float_as_uint(v[2 * c]) >> 16) | (__float_as_uint(v[2 * c + 1]) & 0xFFFF0000u);
+                    }
+                }
+                o = u32x4{cv[0].w, cv[1].w, cv[2].w, cv[3].w};
+            }
+            const uint32_t c = base + (uint32_t)u * kThreads + threadIdx.x;
+            if (c < total)
+                stream_store(o, (u32x4 *)(d.out + out_off[u]));
+        }
+    }
+}
+
+typedef void (*dense_kernel_t)(const DenseArgs);
+
+template <int DT, int FMT>
+static dense_kernel_t pick_dense(int M, bool absorb)
+{
+    if (!absorb)
+        return apply_dense_kernel<DT, FMT, 4, false>;
+    switch (M) {
+    case 2: return apply_dense_kernel<DT, FMT, 2, true>;
+    case 4: return apply_dense_kernel<DT, FMT, 4, true>;
+    case 8: return apply_dense_kernel<DT, FMT, 8, true>;
+    case 16: return apply_dense_kernel<DT, FMT, 16, true>;
+    case 32: return apply_dense_kernel<DT, FMT, 32, true>;
+    }
+    return nullptr;
+}
+
+}  // namespace tmask
+
+extern "C" int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int M, int absorb_mean,
+                                 tmask_mask_fmt mf, void *hip_stream)
+{
+    if (!descs)
+        return fail(TMASK_ERR_NULL, "descriptor array is NULL");
+    if (n <= 0)
+        return fail(TMASK_ERR_SHAPE, "n=%d must be positive", n);
+    if (dt != TMASK_F32 && dt != TMASK_BF16)
+        return fail(TMASK_ERR_DTYPE, "unknown dtype %d", (int)dt);
+    if (mf != TMASK_MASK_U8 && mf != TMASK_MASK_BITS)
+        return fail(TMASK_ERR_DTYPE, "unknown mask format %d", (int)mf);
+    if (absorb_mean && M != 2 && M != 4 && M != 8 && M != 16 && M != 32)
+        return fail(TMASK_ERR_NM, "mean absorption needs M in {2, 4, 8, 16, 32} (M=%d)", M);
+    const int64_t es = dt == TMASK_F32 ? 4 : 2, per_chunk = 16 / es;
+    for (int i = 0; i < n; i++) {
+        const tmask_dense_desc &f = descs[i];
+        if (!f.w || !f.mask || !f.out)
+            return fail(TMASK_ERR_NULL, "matrix %d: w, mask or out is NULL", i);
+        if (f.rows <= 0 || f.cols <= 0 || f.cols % per_chunk || (absorb_mean && f.cols % M) ||
+            (mf == TMASK_MASK_BITS && f.cols % 8))
+            return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld (cols must be a multiple of %lld%s%s)", i,
+                        (long long)f.rows, (long long)f.cols, (long long)per_chunk, absorb_mean ? " and of M" : "",
+                        mf == TMASK_MASK_BITS ? " and of 8 for BITS masks" : "");
+        const int64_t mask_row = mf == TMASK_MASK_U8 ? f.cols : f.cols / 8;
+        if (f.ld < f.cols || f.ld_out < f.cols || f.mask_ld < mask_row || f.ld * es > 0x7FFFFFFFll ||
+            f.ld_out * es > 0x7FFFFFFFll || f.mask_ld > 0x7FFFFFFFll || f.rows * (f.cols / per_chunk) >= 0xFFFFFFFFll)
+            return fail(TMASK_ERR_SHAPE, "matrix %d: leading dimensions must cover a row; at most 2^32 - 1 chunks of 16 bytes",
+                        i);
+        if (((uintptr_t)f.w | (uintptr_t)f.out | (uint64_t)(f.ld * es) | (uint64_t)(f.ld_out * es)) & 15)
+            return fail(TMASK_ERR_ALIGN, "matrix %d: w, out and their row pitches must be 16-byte aligned", i);
+        if (mf == TMASK_MASK_U8 && (((uintptr_t)f.mask | (uint64_t)f.mask_ld) & (uint64_t)(per_chunk - 1)))
+            return fail(TMASK_ERR_ALIGN, "matrix %d: a U8 mask and its row pitch must be %lld-byte aligned", i,
+                        (long long)per_chunk);
+    }
+    const bool absorb = absorb_mean != 0;
+    dense_kernel_t kern = dt == TMASK_F32 ? (mf == TMASK_MASK_U8 ? pick_dense<kF32, kMaskU8>(M, absorb)
+                                                                 : pick_dense<kF32, kMaskBits>(M, absorb))
+                                          : (mf == TMASK_MASK_U8 ? pick_dense<kBF16, kMaskU8>(M, absorb)
+                                                                 : pick_dense<kBF16, kMaskBits>(M, absorb));
+    hipStream_t stream = (hipStream_t)hip_stream;
+    for (int first = 0; first < n; first += kMaxDenseBatch) {
+        const int nb = n - first < kMaxDenseBatch ? n - first : kMaxDenseBatch;
+        DenseArgs args;
+        memset(&args, 0, sizeof args);
+        uint32_t wgs = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_dense_desc &f = descs[first + k];
+            DenseDev &d = args.d[k];
+            d.w = (const char *)f.w; d.mask = (const unsigned char *)f.mask; d.out = (char *)f.out;
+            d.rows = (uint32_t)f.rows; d.chunks_per_row = (uint32_t)(f.cols / per_chunk);
+            d.ld_b = (uint32_t)(f.ld * es); d.ld_out_b = (uint32_t)(f.ld_out * es); d.mask_ld = (uint32_t)f.mask_ld;
+            const uint64_t chunks = (uint64_t)d.rows * d.chunks_per_row;
+            uint64_t nw = (chunks + 4ull * kThreads - 1) / (4ull * kThreads);
+            nw = nw < 1 ? 1 : nw > 8192 ? 8192 : nw;
+            d.n_wg = (uint32_t)nw; d.wg0 = wgs;
+            wgs += d.n_wg;
+        }
+        args.n = (uint32_t)nb;
+        {
+            ProfileScope prof(stream, first + kMaxDenseBatch >= n);
+            hipLaunchKernelGGL(kern, dim3(wgs), dim3(kThreads), 0, stream, args);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "apply_dense launch");
     }
     return TMASK_OK;
 }

@@ -27,11 +27,11 @@ template <int DT, int FMT, bool WMASK>
 __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs args)
 {
     using PG = Pack4Geo<DT>;
-    constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, VPC = PG::VPC, OTW = PG::OTW,
-                  IDXB = PG::IDXB;
+    constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, OTD = PG::OTD, TCP = PG::TCP,
+                  IDXB = PG::IDXB, NQ = PG::NQ;
 
-    __shared__ __attribute__((aligned(16))) uint32_t OT[TC][OTW];
-    __shared__ __attribute__((aligned(8))) uint16_t IDXT[TC][4];
+    __shared__ __attribute__((aligned(16))) uint32_t OT[OTD][TCP];      // [position down the column][column]
+    __shared__ __attribute__((aligned(16))) uint16_t IDXT[NQ][TC];
     __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
     __shared__ double red[kThreads / 64];
 
@@ -60,7 +60,6 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
     // Tiles wholly inside the matrix run a copy of the loop without bounds tests (no branch splits it).
     auto compute = [&](auto edge_tag) {
         constexpr bool EDGE = decltype(edge_tag)::value;
-        uint32_t vt[C][VPC];
         uint32_t tnib[C];
 #pragma unroll
         for (int c = 0; c < C; c++)
@@ -153,22 +152,26 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
                         asm volatile("" : "+v"(rownib[i]));
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // columns: compress W^T down the column
+                // columns: compress W^T down the column; the slots of the four columns go straight to LDS
+                uint32_t t0[4], t1[4];
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
-                    uint32_t v0, v1, nib;
+                    uint32_t nib;
                     compact_2of4(keep[0][c], keep[1][c], keep[2][c], keep[3][c], e[0][c], e[1][c], e[2][c], e[3][c],
-                                 v0, v1, nib);
-                    if constexpr (DT == kF32) {
-                        vt[c][2 * q] = v0;
-                        vt[c][2 * q + 1] = v1;
-                    } else {
-                        vt[4 * g + c][q] = v0 | (v1 << 16);
-                    }
+                                 t0[c], t1[c], nib);
                     tnib[4 * g + c] |= nib << (4 * q);
-                    if constexpr (DT == kBF16)
+                    if constexpr (DT == kBF16) {
+                        t0[c] |= t1[c] << 16;
                         asm volatile("" : "+v"(tnib[4 * g + c]));   // merge now, as for the sum above
+                        asm volatile("" : "+v"(t0[c]));
+                    }
                     __builtin_amdgcn_sched_barrier(0);
+                }
+                if constexpr (DT == kF32) {
+                    *(u32x4 *)&OT[brl * 2][l * C] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl * 2 + 1][l * C] = u32x4{t1[0], t1[1], t1[2], t1[3]};
+                } else {
+                    *(u32x4 *)&OT[brl][l * C + 4 * g] = u32x4{t0[0], t0[1], t0[2], t0[3]};
                 }
             }
             if (EDGE && !ok) {
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
                     u32x2 v;
                     v.x = rowout[i][0];
                     v.y = rowout[i][1];
-                    __builtin_nontemporal_store(
+                    stream_store(
                         v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col0 / 4) * 2) * ES + l * 8u));
                     if constexpr (WMASK) {
                         char *mrow = (char *)const_cast<void *>(d.mask) + (size_t)(row + i) * d.mask_ld +
@@ -196,12 +199,12 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
                         const uint32_t lcol = l * (uint32_t)C;   // the lane's first column inside the tile
                         if constexpr (FMT == kMaskU8) {
                             if constexpr (C == 4) {
-                                __builtin_nontemporal_store(rowmask[i][0], (uint32_t *)(mrow + lcol));
+                                stream_store(rowmask[i][0], (uint32_t *)(mrow + lcol));
                             } else {
                                 u32x2 mv;
                                 mv.x = rowmask[i][0];
                                 mv.y = rowmask[i][NG - 1];
-                                __builtin_nontemporal_store(mv, (u32x2 *)(mrow + lcol));
+                                stream_store(mv, (u32x2 *)(mrow + lcol));
                             }
                         } else {
                             if constexpr (C == 8) {
@@ -239,14 +242,14 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
             for (int c = 0; c < C; c++)
                 tnib[c] &= keepmask;
         }
-#pragma unroll
-        for (int c = 0; c < C; c++) {
-#pragma unroll
-            for (int h = 0; h < VPC / 4; h++) {
-                u32x4 v = {vt[c][4 * h], vt[c][4 * h + 1], vt[c][4 * h + 2], vt[c][4 * h + 3]};
-                *(u32x4 *)&OT[l * C + c][w * VPC + 4 * h] = v;
-            }
-            IDXT[l * C + c][w] = (uint16_t)tnib[c];
+        if constexpr (C == 4) {
+            u32x2 v;
+            v.x = tnib[0] | (tnib[1] << 16);
+            v.y = tnib[2] | (tnib[3] << 16);
+            *(u32x2 *)&IDXT[w][l * C] = v;
+        } else {
+            *(u32x4 *)&IDXT[w][l * C] = u32x4{tnib[0] | (tnib[1] << 16), tnib[2] | (tnib[3] << 16),
+                                              tnib[4] | (tnib[5] << 16), tnib[6] | (tnib[7] << 16)};
         }
     };
     if (row0 + TR <= d.rows && col0 + TC <= d.cols)

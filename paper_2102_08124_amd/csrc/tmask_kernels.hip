@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArg
             char *mb = (char *)md.mask + (size_t)pos.br * M * md.mask_ld + (size_t)pos.sc * 4;
 #pragma unroll
             for (int i = 0; i < M; i++)
-                __builtin_nontemporal_store(rowbytes[i], (uint32_t *)(mb + (size_t)i * md.mask_ld));
+                stream_store(rowbytes[i], (uint32_t *)(mb + (size_t)i * md.mask_ld));
         } else {
 #pragma unroll
             for (int i = 0; i < M; i++)
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
                 u32x2 v;
                 v.x = b0;
                 v.y = b1;
-                __builtin_nontemporal_store(v, (u32x2 *)(mb + (size_t)i * mld));
+                stream_store(v, (u32x2 *)(mb + (size_t)i * mld));
             });
         } else {
             uint32_t bits[M];
@@ -788,12 +788,19 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
     bool fast24 = (M == 4 && N == 2);
     for (int i = 0; i < n && fast24; i++)
         fast24 = (((uintptr_t)descs[i].vals | (uintptr_t)descs[i].valsT) & 7) == 0;
+    uint32_t TR = kPackTR, lds_reserve = 0;
     if (fast24) {
+        // tile widths in strips: measured best per element type (bf16: narrower and taller, so the runs written
+        // per column of W^T are 128 bytes long)
+        constexpr int SF = 64, SB = 32;
         if (dt == TMASK_F32)
-            kern = mf == TMASK_MASK_U8 ? pack24_kernel<kF32, kMaskU8> : pack24_kernel<kF32, kMaskBits>;
+            kern = mf == TMASK_MASK_U8 ? pack24_kernel<kF32, kMaskU8, SF, 4> : pack24_kernel<kF32, kMaskBits, SF, 4>;
         else
-            kern = mf == TMASK_MASK_U8 ? pack24_kernel<kBF16, kMaskU8> : pack24_kernel<kBF16, kMaskBits>;
-        TC = kPack4Strips * 16 / (uint32_t)elem_size((int)dt);
+            kern = mf == TMASK_MASK_U8 ? pack24_kernel<kBF16, kMaskU8, SB, 4> : pack24_kernel<kBF16, kMaskBits, SB, 4>;
+        const uint32_t strips = dt == TMASK_F32 ? SF : SB;
+        TC = strips * 16 / (uint32_t)elem_size((int)dt);
+        TR = 4096 / strips;
+        lds_reserve = dt == TMASK_F32 ? kPack4LdsReserveF32 : 0;
     }
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int first = 0; first < n; first += kMaxPackBatch) {
@@ -808,12 +815,12 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
             d.rows = (uint32_t)p.rows; d.cols = (uint32_t)p.cols; d.ld = (uint32_t)p.ld; d.mask_ld = (uint32_t)p.mask_ld;
             d.tiles_x = (d.cols + TC - 1) / TC;
             d.tile0 = tiles;
-            tiles += d.tiles_x * ((d.rows + kPackTR - 1) / kPackTR);
+            tiles += d.tiles_x * ((d.rows + TR - 1) / TR);
         }
         args.n = (uint32_t)nb; args.N = (uint32_t)N;
         {
             ProfileScope prof(stream, first + kMaxPackBatch >= n);
-            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), lds_reserve, stream, args);
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess)
@@ -864,6 +871,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     }
 
     const uint32_t TC = kPack4Strips * 16 / (uint32_t)elem_size((int)dt);
+    constexpr uint32_t kPack4Rows = 4096 / kPack4Strips;
     if (want_obj) {
         size_t tiles = 0;
         for (int i = 0; i < n; i++)
@@ -904,7 +912,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
         args.n = (uint32_t)nb; args.partial0 = partial0; args.partials = want_obj ? workspace : nullptr;
         {
             ProfileScope prof(stream, first + kMaxPackBatch >= n);
-            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), dt == TMASK_F32 ? kPack4LdsReserveF32 : 0, stream, args);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)

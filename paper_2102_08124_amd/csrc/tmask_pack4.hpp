@@ -1,14 +1,15 @@
 // tmask_apply_pack specialised to M = 4, N = 2 (the 2:4 transposable case); same output format as
 // the general kernel in tmask_pack.hpp (described in include/tmask.h).
 //
-// One workgroup packs 64 rows x 64 strips (256 fp32 / 512 bf16 columns).  Wavefront w owns block-rows
-// 4w..4w+3 of the tile, lane l owns strip l, so every load is a contiguous 1 KiB run.  A lane holds
+// One workgroup packs a tile of 64 KiB of W: S strips of 16 bytes wide, 4096 / S rows high (Pack4Geo).  A
+// wavefront owns 64 / S runs of four block-rows, a lane one strip of one run, so every load is a contiguous
+// run of 16 S bytes.  A lane holds
 // whole groups in both directions (4 columns of a row, 4 rows of a column), so compaction needs no
 // exchange: the slot logic runs on lane masks in the scalar ALU and picks values with selects.
 //   W   : N values per group go straight from registers to memory (8 B per lane and row);
 //         position nibbles are collected per row in LDS and written as whole rows of bytes.
-//   W^T : a lane gathers, per column, the 8 values of its four block-rows in registers, parks them in
-//         LDS ([column][block-row]) and the workgroup streams 128 B (fp32) / 64 B (bf16) runs per column.
+//   W^T : the two slots of every column group go to LDS as [position down the column][column], written
+//         in 16-byte pieces (a lane's columns are neighbours); the workgroup then streams whole runs per column.
 #pragma once
 #include <type_traits>
 
@@ -17,8 +18,11 @@
 
 namespace tmask {
 
-constexpr int kPack4Rows = 64;     // tile rows
-constexpr int kPack4Strips = 64;   // tile strips (16 bytes each)
+constexpr int kPack4Strips = 64;   // default tile width in strips of 16 bytes
+// Three resident tiles per compute unit run faster than four (117 against 123 us on 8192 x 8192 fp32: fewer
+// rows of the matrix are open at a time).  The fp32 kernels would fit four times, so their launches ask for
+// this much dynamic LDS on top, which nobody uses.
+constexpr unsigned kPack4LdsReserveF32 = 4096;
 
 // r = lane-mask bit set ? a : b, as exactly one v_cndmask with the mask in a scalar register pair
 // (written as an instruction because the compiler otherwise turns chains of such selects into
@@ -62,27 +66,36 @@ __device__ __forceinline__ lanemask_t keep_flag(uint32_t m0, uint32_t m1, int c)
         return lm((m0 & (1u << c)) != 0u);
 }
 
-// Tile geometry of the 2:4 pack kernels for one element type.
-template <int DT>
+// Tile geometry of the 2:4 pack kernels for one element type.  A tile is S strips wide; a wavefront
+// covers 64 / S block-rows per step (lane l: strip l % S, sub-row l / S) and takes four steps, so a tile
+// has 4096 / S rows: 64 KiB of W whatever S is.  A narrower, taller tile makes the runs written per
+// column of W^T longer at the price of shorter runs per row of W.
+template <int DT, int S = kPack4Strips, int NW = 4>
 struct Pack4Geo {
     static constexpr int ES = (DT == kF32) ? 4 : 2;
     static constexpr int C = 16 / ES;                  // columns per strip
     static constexpr int NG = C / 4;                   // groups per strip row
-    static constexpr int TR = kPack4Rows, TS = kPack4Strips, TC = TS * C;
-    static constexpr int VPC = (DT == kF32) ? 8 : 4;   // dwords a lane produces per column for W^T (4 block-rows)
-    static constexpr int OTD = 4 * VPC;                // data dwords per column in the tile (16 block-rows)
-    static constexpr int OTW = OTD + 4;                // padded, keeps 16-byte alignment
+    static constexpr int LPR = 64 / S;                 // block-rows a wavefront touches per step
+    static constexpr int NT = 64 * NW;                 // threads per workgroup
+    static constexpr int TS = S, TR = 16 * LPR * NW, TC = TS * C;
+    static constexpr int VPB = (DT == kF32) ? 2 : 1;   // dwords per column and block-row for W^T
+    static constexpr int OTD = (TR / 4) * VPB;         // data dwords per column in the tile
+    static constexpr int TCP = TC + 4;                 // pitch of the staging rows (keeps 16-byte alignment, and
+                                                       // spreads the copy-out's strided reads over the banks)
     static constexpr int IDXB = TS * NG / 2;           // index bytes per tile row
+    static constexpr int NQ = NW * LPR;                // runs of four block-rows per tile (one uint16 of nibbles each)
 };
 
 // Streams a finished tile out of LDS: OT = W^T values per column, IDXT = W^T position nibbles per
 // column, IDX = W position nibbles per row.  Call after a barrier; all threads take part.
-template <int DT>
+template <int DT, int S = kPack4Strips, int NW = 4>
 __device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0, uint32_t col0,
-                                                const uint32_t (*OT)[Pack4Geo<DT>::OTW], const uint16_t (*IDXT)[4],
-                                                const uint8_t (*IDX)[Pack4Geo<DT>::IDXB])
+                                                const uint32_t (*OT)[Pack4Geo<DT, S, NW>::TCP],
+                                                const uint16_t (*IDXT)[Pack4Geo<DT, S, NW>::TC],
+                                                const uint8_t (*IDX)[Pack4Geo<DT, S, NW>::IDXB])
 {
-    using PG = Pack4Geo<DT>;
+    using PG = Pack4Geo<DT, S, NW>;
+    constexpr uint32_t kNT = PG::NT;
     constexpr int ES = PG::ES, TR = PG::TR, TC = PG::TC, OTD = PG::OTD;
     const uint32_t tid = threadIdx.x;
     const size_t pitchT = (size_t)(d.rows / 4) * 2;    // elements per row of valsT
@@ -95,16 +108,16 @@ __device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0,
         const size_t pitch_b = pitchT * ES;
         if (brs_valid == TR / 4 && (pitch_b & 15) == 0 && (((uintptr_t)dst) & 15) == 0) {
             constexpr int CH = OTD / 4;   // 16-byte chunks per column
-            for (uint32_t j = tid; j < cols_valid * CH; j += kThreads) {
+            for (uint32_t j = tid; j < cols_valid * CH; j += kNT) {
                 const uint32_t cc = j / CH, part = j % CH;
-                const u32x4 v = *(const u32x4 *)&OT[cc][4 * part];
-                __builtin_nontemporal_store(v, (u32x4 *)(dst + (size_t)cc * pitch_b + 16 * part));
+                const u32x4 v = {OT[4 * part][cc], OT[4 * part + 1][cc], OT[4 * part + 2][cc], OT[4 * part + 3][cc]};
+                stream_store(v, (u32x4 *)(dst + (size_t)cc * pitch_b + 16 * part));
             }
         } else {
             const uint32_t rd = brs_valid * 2 * ES / 4;   // dwords per column
-            for (uint32_t j = tid; j < cols_valid * rd; j += kThreads) {
+            for (uint32_t j = tid; j < cols_valid * rd; j += kNT) {
                 const uint32_t cc = j / rd, x = j - cc * rd;
-                *(uint32_t *)(dst + (size_t)cc * pitch_b + 4 * x) = OT[cc][x];
+                *(uint32_t *)(dst + (size_t)cc * pitch_b + 4 * x) = OT[x][cc];
             }
         }
     }
@@ -115,12 +128,12 @@ __device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0,
         unsigned char *dst = (unsigned char *)d.idx + (size_t)row0 * pitch + col0 / 8;
         if ((nb & 3) == 0 && (pitch & 3) == 0 && (((uintptr_t)dst) & 3) == 0) {
             const uint32_t nd = nb / 4;
-            for (uint32_t j = tid; j < rows_valid * nd; j += kThreads) {
+            for (uint32_t j = tid; j < rows_valid * nd; j += kNT) {
                 const uint32_t r = j / nd, x = j - r * nd;
                 *(uint32_t *)(dst + (size_t)r * pitch + 4 * x) = ((const uint32_t *)&IDX[r][0])[x];
             }
         } else {
-            for (uint32_t j = tid; j < rows_valid * nb; j += kThreads) {
+            for (uint32_t j = tid; j < rows_valid * nb; j += kNT) {
                 const uint32_t r = j / nb, x = j - r * nb;
                 dst[(size_t)r * pitch + x] = IDX[r][x];
             }
@@ -131,27 +144,35 @@ __device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0,
         const size_t pitch = ((size_t)d.rows + 7) / 8;
         const uint32_t nb = (brs_valid + 1) / 2;
         unsigned char *dst = (unsigned char *)d.idxT + (size_t)col0 * pitch + row0 / 8;
-        if (nb == 8 && (pitch & 7) == 0 && (((uintptr_t)dst) & 7) == 0) {
-            for (uint32_t cc = tid; cc < cols_valid; cc += kThreads)
-                *(u32x2 *)(dst + (size_t)cc * pitch) = *(const u32x2 *)&IDXT[cc][0];
+        if (nb == TR / 8 && (pitch & 7) == 0 && (((uintptr_t)dst) & 7) == 0) {
+            constexpr uint32_t P = TR / 64;   // 8-byte pieces per column
+            for (uint32_t j = tid; j < cols_valid * P; j += kNT) {
+                const uint32_t cc = j / P, x = j % P;
+                u32x2 v;
+                v.x = (uint32_t)IDXT[4 * x][cc] | ((uint32_t)IDXT[4 * x + 1][cc] << 16);
+                v.y = (uint32_t)IDXT[4 * x + 2][cc] | ((uint32_t)IDXT[4 * x + 3][cc] << 16);
+                *(u32x2 *)(dst + (size_t)cc * pitch + 8 * x) = v;
+            }
         } else {
-            for (uint32_t j = tid; j < cols_valid * nb; j += kThreads) {
+            for (uint32_t j = tid; j < cols_valid * nb; j += kNT) {
                 const uint32_t cc = j / nb, x = j - cc * nb;
-                dst[(size_t)cc * pitch + x] = ((const unsigned char *)&IDXT[cc][0])[x];
+                dst[(size_t)cc * pitch + x] = (unsigned char)(IDXT[x >> 1][cc] >> (8 * (x & 1)));
             }
         }
     }
 }
 
-template <int DT, int FMT>
-__global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
+template <int DT, int FMT, int S, int NW>
+__global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
 {
-    using PG = Pack4Geo<DT>;
-    constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, VPC = PG::VPC, OTW = PG::OTW,
-                  IDXB = PG::IDXB;
+    using PG = Pack4Geo<DT, S, NW>;
+    constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, OTD = PG::OTD,
+                  TCP = PG::TCP, IDXB = PG::IDXB, LPR = PG::LPR, NQ = PG::NQ;
 
-    __shared__ __attribute__((aligned(16))) uint32_t OT[TC][OTW];
-    __shared__ __attribute__((aligned(8))) uint16_t IDXT[TC][4];
+    // Staging for W^T, indexed [position down the column][column]: a lane's columns are neighbours, so it
+    // writes whole 16-byte pieces and the lanes of a wavefront write one contiguous run.
+    __shared__ __attribute__((aligned(16))) uint32_t OT[OTD][TCP];
+    __shared__ __attribute__((aligned(16))) uint16_t IDXT[NQ][TC];
     __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
 
     const uint32_t tile = blockIdx.x;
@@ -169,18 +190,23 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
     const uint32_t row0 = ty * TR, col0 = tx * TC;
     const uint32_t tid = threadIdx.x, l = tid & 63u;
     // the wavefront number as a scalar: row addresses below are then scalar too, and a lane adds only
-    // its fixed offset inside the 1 KiB run
+    // its fixed offsets (its strip inside the run, the distance of its sub-row)
     const uint32_t w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t col = col0 + l * C;
+    const uint32_t strip = l % (uint32_t)S, sub = l / (uint32_t)S;
+    const uint32_t q4 = w * LPR + sub;                 // this lane's run of four block-rows inside the tile
+    const uint32_t col = col0 + strip * C;
+    const uint32_t tcol = strip * C;                   // first column of the lane inside the tile
     const bool strip_ok = col < d.cols;
     const size_t pitchW = (size_t)(d.cols / 4) * 2;    // elements per row of vals
-    const size_t pitchT = (size_t)(d.rows / 4) * 2;    // elements per row of valsT
+    // byte offsets of the lane against row 16 * LPR * w of the tile, column col0
+    const size_t lane_w = (size_t)sub * 16u * d.ld * ES + strip * 16u;
+    const size_t lane_m = (size_t)sub * 16u * d.mask_ld;
+    const size_t lane_v = (size_t)sub * 16u * pitchW * ES + strip * 8u;
 
     // Tiles that lie wholly inside the matrix take a copy of the code without any bounds test: no branch
     // splits the loop, so the waits on the prefetched rows are exact.
     auto compute = [&](auto edge_tag) {
         constexpr bool EDGE = decltype(edge_tag)::value;
-        uint32_t vt[C][VPC];
         uint32_t tnib[C];
 #pragma unroll
         for (int c = 0; c < C; c++)
@@ -188,10 +214,12 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
 
         // Loads run one block-row ahead of the compaction: while block-row q is worked on, the 16-byte rows
         // and mask entries of block-row q + 1 are already in flight.
-        u32x4 rawb[2][4];
-        uint32_t m0b[2][4], m1b[2][4];   // the rows' mask entries: U8 bytes as dwords, or BITS in m0
+        constexpr int DEPTH = 2;
+        u32x4 rawb[DEPTH][4];
+        uint32_t m0b[DEPTH][4], m1b[DEPTH][4];   // the rows' mask entries: U8 bytes as dwords, or BITS in m0
         auto issue = [&](int q, u32x4 (&raw)[4], uint32_t (&m0)[4], uint32_t (&m1)[4]) {
-            const uint32_t row = row0 + 4 * (4 * w + (uint32_t)q);
+            const uint32_t wrow = row0 + 16u * LPR * w + 4u * (uint32_t)q;    // scalar: the row of sub-row 0
+            const uint32_t row = wrow + 16u * sub;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
                 raw[i] = u32x4{0u, 0u, 0u, 0u};
@@ -201,9 +229,9 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
                     raw[i] = __builtin_nontemporal_load(
-                        (const u32x4 *)((const char *)d.w + ((size_t)(row + i) * d.ld + col0) * ES + l * 16u));
+                        (const u32x4 *)((const char *)d.w + ((size_t)(wrow + i) * d.ld + col0) * ES + lane_w));
                     if constexpr (FMT == kMaskU8) {
-                        const char *mp = (const char *)d.mask + ((size_t)(row + i) * d.mask_ld + col0) + l * (uint32_t)C;
+                        const char *mp = (const char *)d.mask + ((size_t)(wrow + i) * d.mask_ld + col0) + lane_m + tcol;
                         if constexpr (C == 4) {
                             m0[i] = __builtin_nontemporal_load((const uint32_t *)mp);
                         } else {
@@ -212,25 +240,29 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
                             m1[i] = mv.y;
                         }
                     } else {
-                        const uint32_t byte = ((const unsigned char *)d.mask)[(size_t)(row + i) * d.mask_ld + (col >> 3)];
+                        const uint32_t byte =
+                            ((const unsigned char *)d.mask)[(size_t)(wrow + i) * d.mask_ld + lane_m + (col >> 3)];
                         m0[i] = (C == 8) ? byte : ((byte >> (col & 4u)) & 0xFu);
                     }
                 }
             }
         };
-        issue(0, rawb[0], m0b[0], m1b[0]);
+#pragma unroll
+        for (int q = 0; q < DEPTH - 1; q++)
+            issue(q, rawb[q], m0b[q], m1b[q]);
 
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const uint32_t brl = 4 * w + q;
-            const uint32_t row = row0 + 4 * brl;
+            const uint32_t brl = 4 * q4 + q;                       // block-row inside the tile
+            const uint32_t wrow = row0 + 16u * LPR * w + 4u * (uint32_t)q;
+            const uint32_t row = wrow + 16u * sub;
             const bool ok = !EDGE || (strip_ok && row < d.rows);
-            if (q + 1 < 4)
-                issue(q + 1, rawb[(q + 1) & 1], m0b[(q + 1) & 1], m1b[(q + 1) & 1]);
+            if (q + DEPTH - 1 < 4)
+                issue(q + DEPTH - 1, rawb[(q + DEPTH - 1) % DEPTH], m0b[(q + DEPTH - 1) % DEPTH], m1b[(q + DEPTH - 1) % DEPTH]);
             __builtin_amdgcn_sched_barrier(0);
-            u32x4(&raw)[4] = rawb[q & 1];
-            uint32_t(&m0)[4] = m0b[q & 1];
-            uint32_t(&m1)[4] = m1b[q & 1];
+            u32x4(&raw)[4] = rawb[q % DEPTH];
+            uint32_t(&m0)[4] = m0b[q % DEPTH];
+            uint32_t(&m1)[4] = m1b[q % DEPTH];
             uint32_t rowout[4][2];
             uint32_t rownib[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -263,23 +295,34 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
                         rowout[i][g] = v0 | (v1 << 16);
                     }
                     rownib[i] |= nib << (4 * g);
+                    // bf16: without the pins the compiler keeps every select result alive and merges at the end
+                    if constexpr (DT == kBF16) {
+                        asm volatile("" : "+v"(rownib[i]));
+                        asm volatile("" : "+v"(rowout[i][g]));
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // W^T: groups down the column
+                // W^T: groups down the column; the slots of the four columns go straight to LDS
+                uint32_t t0[4], t1[4];
 #pragma unroll
                 for (int c = 0; c < 4; c++) {
-                    uint32_t v0, v1, nib;
+                    uint32_t nib;
                     compact_2of4(keep_flag<FMT>(m0[0], m1[0], 4 * g + c), keep_flag<FMT>(m0[1], m1[1], 4 * g + c),
                                  keep_flag<FMT>(m0[2], m1[2], 4 * g + c), keep_flag<FMT>(m0[3], m1[3], 4 * g + c), e[0][c],
-                                 e[1][c], e[2][c], e[3][c], v0, v1, nib);
-                    if constexpr (DT == kF32) {
-                        vt[c][2 * q] = v0;
-                        vt[c][2 * q + 1] = v1;
-                    } else {
-                        vt[4 * g + c][q] = v0 | (v1 << 16);
-                    }
+                                 e[1][c], e[2][c], e[3][c], t0[c], t1[c], nib);
                     tnib[4 * g + c] |= nib << (4 * q);
+                    if constexpr (DT == kBF16) {
+                        t0[c] |= t1[c] << 16;
+                        asm volatile("" : "+v"(tnib[4 * g + c]));
+                        asm volatile("" : "+v"(t0[c]));
+                    }
                     __builtin_amdgcn_sched_barrier(0);
+                }
+                if constexpr (DT == kF32) {
+                    *(u32x4 *)&OT[brl * 2][tcol] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl * 2 + 1][tcol] = u32x4{t1[0], t1[1], t1[2], t1[3]};
+                } else {
+                    *(u32x4 *)&OT[brl][tcol + 4 * g] = u32x4{t0[0], t0[1], t0[2], t0[3]};
                 }
             }
             if (!ok) {
@@ -293,8 +336,7 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
                     u32x2 v;
                     v.x = rowout[i][0];
                     v.y = rowout[i][1];
-                    __builtin_nontemporal_store(
-                        v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col0 / 4) * 2) * ES + l * 8u));
+                    stream_store(v, (u32x2 *)((char *)d.vals + ((size_t)(wrow + i) * pitchW + (size_t)(col0 / 4) * 2) * ES + lane_v));
                 }
             }
 #pragma unroll
@@ -302,34 +344,30 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
                 if constexpr (C == 4) {
                     const uint32_t other = quad_xor<1>(rownib[i]);
                     if ((l & 1u) == 0)
-                        IDX[4 * brl + i][l >> 1] = (uint8_t)(rownib[i] | (other << 4));
+                        IDX[4 * brl + i][strip >> 1] = (uint8_t)(rownib[i] | (other << 4));
                 } else {
-                    IDX[4 * brl + i][l] = (uint8_t)rownib[i];
+                    IDX[4 * brl + i][strip] = (uint8_t)rownib[i];
                 }
             }
         }
-        if (EDGE && !strip_ok) {
-#pragma unroll
-            for (int c = 0; c < C; c++)
-                tnib[c] = 0;
-        }
-        // block-rows of this wavefront that lie outside the matrix must not leave position bits either
         if (EDGE) {
+            // strips and block-rows outside the matrix must not leave position bits
             const uint32_t brs_in = (d.rows - row0) / 4;           // block-rows of the tile inside the matrix
-            const uint32_t mine = brs_in > 4 * w ? brs_in - 4 * w : 0;
-            const uint32_t keepmask = mine >= 4 ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
+            const uint32_t mine = brs_in > 4 * q4 ? brs_in - 4 * q4 : 0;
+            const uint32_t keepmask = !strip_ok ? 0u : mine >= 4 ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
 #pragma unroll
             for (int c = 0; c < C; c++)
                 tnib[c] &= keepmask;
         }
-#pragma unroll
-        for (int c = 0; c < C; c++) {
-#pragma unroll
-            for (int h = 0; h < VPC / 4; h++) {
-                u32x4 v = {vt[c][4 * h], vt[c][4 * h + 1], vt[c][4 * h + 2], vt[c][4 * h + 3]};
-                *(u32x4 *)&OT[l * C + c][w * VPC + 4 * h] = v;
-            }
-            IDXT[l * C + c][w] = (uint16_t)tnib[c];
+        // the lane's columns are neighbours here too: one 8-byte (fp32) or 16-byte (bf16) piece
+        if constexpr (C == 4) {
+            u32x2 v;
+            v.x = tnib[0] | (tnib[1] << 16);
+            v.y = tnib[2] | (tnib[3] << 16);
+            *(u32x2 *)&IDXT[q4][tcol] = v;
+        } else {
+            *(u32x4 *)&IDXT[q4][tcol] = u32x4{tnib[0] | (tnib[1] << 16), tnib[2] | (tnib[3] << 16),
+                                              tnib[4] | (tnib[5] << 16), tnib[6] | (tnib[7] << 16)};
         }
     };
     if (row0 + TR <= d.rows && col0 + TC <= d.cols)
@@ -338,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void pack24_kernel(const PackArgs args)
         compute(std::true_type{});
     __syncthreads();
 
-    pack24_copy_out<DT>(d, row0, col0, OT, IDXT, IDX);
+    pack24_copy_out<DT, S, NW>(d, row0, col0, OT, IDXT, IDX);
 }
 
 }  // namespace tmask

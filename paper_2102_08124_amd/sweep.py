@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Per-kernel timing of the four entry points over dtype x N:M on one square matrix.
 
-    python -m paper_2102_08124_amd.sweep [--side 8192] [--calls approx,exact,score,pack,fused,fusedm,prune1d,flip] [--dts f32,bf16] [--ms 4,8,16]
+    python -m paper_2102_08124_amd.sweep [--side 8192] [--calls approx,exact,score,pack,fused,fusedm,prune1d,flip,dense,absorb] [--dts f32,bf16] [--ms 4,8,16]
 
 Each line: main-kernel time from hipEvents recorded around the kernel (marker overhead removed),
 algorithmic GB/s, fraction of the 8 TB/s HBM peak, weights/s.  Inputs are N(0, 0.02) generated on the
@@ -43,19 +43,22 @@ def main():
             wsp = tm.alloc_workspace([ws[0]], N, M)
             sout = torch.zeros(tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda")
             pb = torch.zeros(side * side // (M * M), dtype=torch.float32, device="cuda")
-            packed = tm.alloc_packed(ws[0], N, M)
+            # outputs rotate like the inputs: a buffer rewritten by every call would partly stay in the
+            # memory-side cache and flatter kernels whose stores allocate there
+            packeds = [tm.alloc_packed(ws[0], N, M) for _ in range(nb)]
             flips = torch.zeros(1, dtype=torch.int64, device="cuda")
+            dense_outs = [torch.empty_like(ws[0]) for _ in range(nb)]
             T = side * side
             mb = T if a.fmt == 0 else T // 8
             ib = (M - 1).bit_length()
             byts = {"approx": T * es + mb, "exact": T * es + mb, "score": T * es + mb + 4 * T // (M * M),
                     "pack": T * es + mb + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8,
-                    "prune1d": T * es + mb, "flip": 2 * mb,
+                    "prune1d": T * es + mb, "flip": 2 * mb, "dense": 2 * T * es + mb, "absorb": 2 * T * es + mb,
                     "fused": T * es + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8,
                     "fusedm": T * es + mb + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8}
             for call in a.calls.split(","):
                 def run(k):
-                    w, m = ws[k % nb], masks[k % nb]
+                    w, m, packed, dense_out = ws[k % nb], masks[k % nb], packeds[k % nb], dense_outs[k % nb]
                     if call == "approx":
                         tm.tmask_approx([w], [m], N, M, objective=obj, mask_fmt=a.fmt, workspace=wsp)
                     elif call == "exact":
@@ -66,13 +69,15 @@ def main():
                         tm.tmask_prune_1d([w], [m], N, M, objective=obj, mask_fmt=a.fmt, workspace=wsp)
                     elif call == "flip":
                         tm.tmask_flip_count([m], [masks[(k + 1) % nb]], [side], flips, mask_fmt=a.fmt)
+                    elif call in ("dense", "absorb"):   # masked copy, without / with mean absorption
+                        tm.tmask_apply_dense([w], [m], [dense_out], M, call == "absorb", mask_fmt=a.fmt)
                     elif call == "fused":      # Algorithm 1 + compression in one call, no mask written (2:4 only)
                         tm.tmask_approx_pack([w], None, [packed], N, M, mask_fmt=a.fmt)
                     elif call == "fusedm":     # the same with the mask written too
                         tm.tmask_approx_pack([w], [m], [packed], N, M, mask_fmt=a.fmt)
                     else:
                         tm.tmask_apply_pack([w], [m], [packed], N, M, mask_fmt=a.fmt)
-                if call in ("score", "pack", "flip"):
+                if call in ("score", "pack", "flip", "dense", "absorb"):
                     for k in range(nb):
                         tm.tmask_approx([ws[k]], [masks[k]], N, M, mask_fmt=a.fmt)
                 run(0)

@@ -39,4 +39,5 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(tm.tmask_pack_desc) == 80
     assert ctypes.sizeof(tm.tmask_fused_desc) == 88
     assert ctypes.sizeof(tm.tmask_flip_desc) == 56
+    assert ctypes.sizeof(tm.tmask_dense_desc) == 64
     assert ctypes.sizeof(tm.tmask_score_out) == 56

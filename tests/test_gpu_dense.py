@@ -1,0 +1,101 @@
+"""GPU parity for tmask_apply_dense: the masked copy is bit-exact; mean absorption (Sec. 5) within the fp32
+rounding of its sums (plus half a unit in the last place of the bf16 result, at most 2^-8 of it, for bf16 weights) of the fp64 oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2102_08124_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2102_08124_amd import binding as tm            # noqa: E402
+from tests.gpu_util import mask_to_dev, to_dev             # noqa: E402
+
+
+def _weights(rows, cols, seed, dt):
+    w = wl.gaussian_f32(rows, cols, seed=seed)
+    return w if dt == "f32" else wl.f32_to_bf16_bits(w)
+
+
+def _as_f64(w):
+    return w.astype(np.float64) if w.dtype == np.float32 else wl.bf16_bits_to_f32(w).astype(np.float64)
+
+
+def _out_f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def _check_absorb(got, w64, mask, M, bf16):
+    want = oracle.apply_dense(w64, mask, M, True)
+    rows, cols = w64.shape
+    group_l1 = np.repeat(np.abs(w64).reshape(rows, cols // M, M).sum(-1), M, axis=1)
+    tol = 2.0 ** -20 * group_l1 + (2.0 ** -8 * np.abs(want) if bf16 else 0.0)
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (int(bad.sum()), np.argwhere(bad)[:4])
+    assert ((got != 0) <= (mask != 0)).all()
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+def test_masked_copy_is_exact_batch(dt, fmt):
+    shapes = [(64, 64), (5, 1008), (128, 4096), (3, 8), (17, 24), (1000, 1040)]
+    ws = [_weights(r, c, 8000 + k, dt) for k, (r, c) in enumerate(shapes)]
+    rng = np.random.default_rng(8)
+    masks = [(rng.random(w.shape) < 0.5).astype(np.uint8) for w in ws]
+    dws = [to_dev(w) for w in ws]
+    outs = [torch.full_like(d, 7.0) for d in dws]
+    tm.tmask_apply_dense(dws, [mask_to_dev(m, fmt) for m in masks], outs, mask_fmt=fmt)
+    torch.cuda.synchronize()
+    for w, m, o in zip(ws, masks, outs):
+        np.testing.assert_array_equal(_out_f64(o), oracle.apply_dense(_as_f64(w), m))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("M", [2, 4, 8, 16, 32])
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+def test_mean_absorption_random_masks(dt, M, fmt):
+    # unstructured random masks: every pruned count from 0 to M occurs, groups span 1 to 8 lanes
+    shapes = [(33, 32 * 5), (200, 1024), (7, 32)]
+    ws = [_weights(r, c, 8100 + 10 * M + k, dt) for k, (r, c) in enumerate(shapes)]
+    rng = np.random.default_rng(80 + M)
+    masks = [(rng.random(w.shape) < 0.5).astype(np.uint8) for w in ws]
+    masks[0][:2] = 1
+    masks[0][2:4] = 0
+    dws = [to_dev(w) for w in ws]
+    outs = [torch.empty_like(d) for d in dws]
+    tm.tmask_apply_dense(dws, [mask_to_dev(m, fmt) for m in masks], outs, M, True, mask_fmt=fmt)
+    torch.cuda.synchronize()
+    for w, m, o in zip(ws, masks, outs):
+        _check_absorb(_out_f64(o), _as_f64(w), m, M, dt == "bf16")
+
+
+@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("bf16", 4, 8), ("f32", 8, 16)])
+def test_transposable_mask_in_place_with_padding(dt, N, M):
+    # the mask of Algorithm 1, applied in place on a matrix that is a column slice of a wider buffer
+    w = _weights(256, 512, 8200 + M, dt)
+    mask, _ = oracle.approx(w, N, M)
+    d = to_dev(w, ld=512 + 64)
+    tm.tmask_apply_dense([d], [mask_to_dev(mask, tm.TMASK_MASK_U8)], [d], M, True)
+    torch.cuda.synchronize()
+    _check_absorb(_out_f64(d), _as_f64(w), mask, M, dt == "bf16")
+    # at N = M/2 with full rows the group sums survive (up to the same rounding)
+    full = (mask.reshape(256, 512 // M, M).sum(-1) == N)
+    got = _out_f64(d).reshape(256, 512 // M, M).sum(-1)
+    ref = _as_f64(w).reshape(256, 512 // M, M).sum(-1)
+    l1 = np.abs(_as_f64(w)).reshape(256, 512 // M, M).sum(-1)
+    tol = (2.0 ** -8 if dt == "bf16" else 2.0 ** -19) * l1
+    assert (np.abs(got - ref)[full] <= tol[full]).all()
+
+
+def test_rejects_bad_arguments():
+    w = torch.zeros((8, 64), device="cuda")
+    m = torch.zeros((8, 64), dtype=torch.uint8, device="cuda")
+    with pytest.raises(tm.TmaskError):
+        tm.tmask_apply_dense([w], [m], [w], 6, True)                    # M not a power of two
+    with pytest.raises(tm.TmaskError):
+        tm.tmask_apply_dense([w[:, :62]], [m[:, :62]], [w[:, :62]])     # cols not a whole number of 16-byte pieces
+    with pytest.raises(tm.TmaskError):
+        tm.tmask_apply_dense([w[:, :48]], [m[:, :48]], [w[:, :48]], 32, True)   # cols not a multiple of M
+    with pytest.raises(tm.TmaskError):
+        tm.tmask_apply_dense([w[:, 1:5]], [m[:, :4]], [w[:, 1:5]])      # misaligned
