@@ -15,6 +15,7 @@
 #include "tmask_approx_sel.hpp"
 #include "tmask_pack.hpp"
 #include "tmask_pack4.hpp"
+#include "tmask_pack8.hpp"
 #include "tmask_exact_balance.hpp"
 #include "tmask_fused4.hpp"
 
@@ -801,6 +802,14 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
         TC = strips * 16 / (uint32_t)elem_size((int)dt);
         TR = 4096 / strips;
         lds_reserve = dt == TMASK_F32 ? kPack4LdsReserveF32 : 0;
+    }
+    bool fast48 = (M == 8 && N == 4 && dt == TMASK_BF16);
+    for (int i = 0; i < n && fast48; i++)
+        fast48 = (((uintptr_t)descs[i].vals | (uintptr_t)descs[i].valsT) & 7) == 0;
+    if (fast48) {
+        kern = mf == TMASK_MASK_U8 ? pack48_bf16_kernel<kMaskU8> : pack48_bf16_kernel<kMaskBits>;
+        TC = Pack8Geo::TC;
+        TR = Pack8Geo::TR;
     }
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int first = 0; first < n; first += kMaxPackBatch) {

@@ -1,0 +1,308 @@
+// tmask_apply_pack specialised to bf16, M = 8, N = 4 (the 4:8 transposable case); same output format as
+// the general kernel in tmask_pack.hpp (described in include/tmask.h).
+//
+// A strip of 16 bytes is one group of eight bf16 values, so a lane holds a whole 8 x 8 block per step: its
+// eight rows are the row groups, and the same registers read down are the column groups.  A group is
+// compacted without loops over slots: the 8-bit set of chosen positions indexes a table (built in LDS by
+// the workgroup) that holds the byte selectors of four v_perm_b32 and the 12 position bits, so four
+// permutes pick the four slots out of the group's four dwords.  Pruned values are zeroed once per block,
+// which also makes fillers +0.  Tile = 128 rows x 32 strips (256 columns); a wavefront covers two runs of
+// two block-rows per step pair, W values go straight to memory (8 B per lane and row), W^T values and the
+// position bits of both directions are staged in LDS and streamed out in whole runs.
+#pragma once
+#include "tmask_device.hpp"
+#include "tmask_pack.hpp"
+
+namespace tmask {
+
+struct Pack8Geo {
+    static constexpr int S = 32;                 // strips per tile row
+    static constexpr int LPR = 64 / S;           // runs of block-rows a wavefront covers at a time
+    static constexpr int NSTEP = 2;              // block-rows per run
+    static constexpr int TR = 4 * LPR * NSTEP * 8, TC = S * 8;
+    static constexpr int NBR = TR / 8;           // block-rows per tile
+    static constexpr int OTD = NBR * 2;          // dwords per column of W^T in the tile
+    static constexpr int TCP = TC + 4;
+    static constexpr int IDXB = S * 12 / 8;      // position bytes per tile row
+    static constexpr int IDXTB = NBR * 12 / 8;   // position bytes per tile column
+};
+
+// the 8 x 8 bit matrix rb (bit c of rb[i] = entry (i, c)) transposed: bit i of the result's byte c
+__device__ __forceinline__ void transpose_bits8(const uint32_t (&rb)[8], uint32_t &x, uint32_t &y)
+{
+    x = rb[0] | (rb[1] << 8) | (rb[2] << 16) | (rb[3] << 24);
+    y = rb[4] | (rb[5] << 8) | (rb[6] << 16) | (rb[7] << 24);
+    uint32_t t;
+    t = (x ^ (x >> 7)) & 0x00AA00AAu;  x ^= t ^ (t << 7);      // 2 x 2 blocks
+    t = (y ^ (y >> 7)) & 0x00AA00AAu;  y ^= t ^ (t << 7);
+    t = (x ^ (x >> 14)) & 0x0000CCCCu; x ^= t ^ (t << 14);     // 4 x 4 blocks
+    t = (y ^ (y >> 14)) & 0x0000CCCCu; y ^= t ^ (t << 14);
+    t = (x & 0x0F0F0F0Fu) | ((y << 4) & 0xF0F0F0F0u);          // the two 4 x 4 blocks off the diagonal
+    y = ((x >> 4) & 0x0F0F0F0Fu) | (y & 0xF0F0F0F0u);
+    x = t;
+}
+
+// One group of eight bf16 values given as four dwords (pruned ones already zero): the four slots as two
+// dwords, and the 12 position bits.
+__device__ __forceinline__ void compact_4of8(uint32_t kbits, uint32_t d0, uint32_t d1, uint32_t d2, uint32_t d3,
+                                             const u32x4 *luts, const uint16_t *lutc, uint32_t &o0, uint32_t &o1,
+                                             uint32_t &code)
+{
+    uint32_t sel, chosen;
+    choose_slots<8>(kbits, 4u, sel, chosen);
+    const u32x4 L = luts[chosen];
+    code = lutc[chosen];
+    o0 = __builtin_amdgcn_perm(d1, d0, L.x) | __builtin_amdgcn_perm(d3, d2, L.y);
+    o1 = __builtin_amdgcn_perm(d1, d0, L.z) | __builtin_amdgcn_perm(d3, d2, L.w);
+}
+
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs args)
+{
+    using PG = Pack8Geo;
+    constexpr int ES = 2, S = PG::S, LPR = PG::LPR, NSTEP = PG::NSTEP, TR = PG::TR, TC = PG::TC, OTD = PG::OTD,
+                  TCP = PG::TCP, IDXB = PG::IDXB, IDXTB = PG::IDXTB;
+
+    __shared__ __attribute__((aligned(16))) uint32_t OT[OTD][TCP];      // [position down the column][column]
+    __shared__ __attribute__((aligned(16))) uint8_t IDXT[IDXTB][TC];    // [byte of the column's bit string][column]
+    __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
+    __shared__ __attribute__((aligned(16))) u32x4 LUTS[256];
+    __shared__ uint16_t LUTC[256];
+
+    const uint32_t tid = threadIdx.x, l = tid & 63u;
+    // ---- the table: entry m describes the set m of chosen positions (used only for sets of four) ----
+    {
+        uint32_t sa0 = 0x0C0C0C0Cu, sa1 = 0x0C0C0C0Cu, sb0 = 0x0C0C0C0Cu, sb1 = 0x0C0C0C0Cu, code = 0, s = 0;
+#pragma unroll
+        for (uint32_t p = 0; p < 8; p++) {
+            if (((tid >> p) & 1u) && s < 4u) {
+                const uint32_t b = 2u * (p & 3u);
+                const uint32_t pair = (b | ((b + 1u) << 8)) << (16u * (s & 1u));
+                const uint32_t clear = ~(0xFFFFu << (16u * (s & 1u)));
+                if (p < 4) {          // first half of the group: dwords 0 and 1
+                    if (s < 2u) sa0 = (sa0 & clear) | pair; else sa1 = (sa1 & clear) | pair;
+                } else {
+                    if (s < 2u) sb0 = (sb0 & clear) | pair; else sb1 = (sb1 & clear) | pair;
+                }
+                code |= p << (3u * s);
+                s++;
+            }
+        }
+        LUTS[tid] = u32x4{sa0, sb0, sa1, sb1};
+        LUTC[tid] = (uint16_t)code;
+    }
+
+    const uint32_t tile = blockIdx.x;
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].tile0 <= tile)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const PackDev d = args.d[lo];
+    const uint32_t tl = tile - d.tile0;
+    const uint32_t ty = tl / d.tiles_x, tx = tl - ty * d.tiles_x;
+    const uint32_t row0 = ty * TR, col0 = tx * TC;
+    const uint32_t w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t strip = l % (uint32_t)S, sub = l / (uint32_t)S;
+    const uint32_t q2 = w * LPR + sub;                   // this lane's run of NSTEP block-rows inside the tile
+    const uint32_t tcol = strip * 8u;
+    const uint32_t col = col0 + tcol;
+    const bool strip_ok = col < d.cols;
+    const size_t pitchW = (size_t)(d.cols / 8) * 4;      // elements per row of vals
+    const size_t lane_w = (size_t)sub * (8u * NSTEP) * d.ld * ES + strip * 16u;
+    const size_t lane_m = (size_t)sub * (8u * NSTEP) * d.mask_ld + (FMT == kMaskU8 ? tcol : (col >> 3));
+    const size_t lane_v = (size_t)sub * (8u * NSTEP) * pitchW * ES + strip * 8u;
+    const size_t mcol0 = FMT == kMaskU8 ? col0 : 0;
+    __syncthreads();                                      // the table is complete
+
+    // ---- all loads of the lane's two blocks first ----
+    u32x4 raw[NSTEP][8];
+    uint32_t mk0[NSTEP][8], mk1[NSTEP][8];               // U8: the row's eight mask bytes; BITS: the byte in mk0
+    bool okq[NSTEP];
+#pragma unroll
+    for (int q = 0; q < NSTEP; q++) {
+        const uint32_t wrow = row0 + 8u * NSTEP * LPR * w + 8u * (uint32_t)q;     // scalar: the row of sub-run 0
+        const uint32_t row = wrow + 8u * NSTEP * sub;
+        okq[q] = strip_ok && row < d.rows;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            raw[q][i] = u32x4{0u, 0u, 0u, 0u};
+            mk0[q][i] = mk1[q][i] = 0;
+        }
+        if (okq[q]) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                raw[q][i] = __builtin_nontemporal_load(
+                    (const u32x4 *)((const char *)d.w + ((size_t)(wrow + i) * d.ld + col0) * ES + lane_w));
+                const unsigned char *mp = (const unsigned char *)d.mask + (size_t)(wrow + i) * d.mask_ld + mcol0 + lane_m;
+                if constexpr (FMT == kMaskU8) {
+                    const u32x2 mv = __builtin_nontemporal_load((const u32x2 *)mp);
+                    mk0[q][i] = mv.x;
+                    mk1[q][i] = mv.y;
+                } else {
+                    mk0[q][i] = (uint32_t)*mp;
+                }
+            }
+        }
+    }
+
+    uint32_t tcode[8];                                    // position bits of the lane's columns, 12 per block-row
+#pragma unroll
+    for (int c = 0; c < 8; c++)
+        tcode[c] = 0;
+
+#pragma unroll
+    for (int q = 0; q < NSTEP; q++) {
+        const uint32_t brl = NSTEP * q2 + (uint32_t)q;   // block-row inside the tile
+        const uint32_t wrow = row0 + 8u * NSTEP * LPR * w + 8u * (uint32_t)q;
+        const bool ok = okq[q];
+        // keep bits per row, and the block with its pruned values zeroed
+        uint32_t rb[8], e[8][4];
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const uint32_t dw[4] = {raw[q][i].x, raw[q][i].y, raw[q][i].z, raw[q][i].w};
+            if constexpr (FMT == kMaskU8) {
+                // bytes -> 0x00 / 0xFF, then every byte doubled into a halfword mask
+                uint32_t f[2] = {mk0[q][i], mk1[q][i]};
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    uint32_t nz = (((f[h] & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | f[h]) & 0x80808080u;
+                    f[h] = nz | (nz - (nz >> 7));
+                }
+                rb[i] = bytes4_to_bits(f[0]) | (bytes4_to_bits(f[1]) << 4);
+                e[i][0] = dw[0] & __builtin_amdgcn_perm(0u, f[0], 0x01010000u);
+                e[i][1] = dw[1] & __builtin_amdgcn_perm(0u, f[0], 0x03030202u);
+                e[i][2] = dw[2] & __builtin_amdgcn_perm(0u, f[1], 0x01010000u);
+                e[i][3] = dw[3] & __builtin_amdgcn_perm(0u, f[1], 0x03030202u);
+            } else {
+                rb[i] = mk0[q][i];
+#pragma unroll
+                for (int h = 0; h < 4; h++) {
+                    const uint32_t t = rb[i] >> (2 * h);
+                    e[i][h] = dw[h] & (((0u - (t & 1u)) & 0xFFFFu) | ((0u - ((t >> 1) & 1u)) << 16));
+                }
+            }
+        }
+        // ---- W: the rows ----
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            uint32_t o0, o1, code;
+            compact_4of8(rb[i], e[i][0], e[i][1], e[i][2], e[i][3], LUTS, LUTC, o0, o1, code);
+            if (!ok)
+                code = 0;                                 // nothing of this strip may show up in a row's padding bits
+            const uint32_t other = quad_xor<1>(code);
+            if (ok) {
+                u32x2 v;
+                v.x = o0;
+                v.y = o1;
+                stream_store(v, (u32x2 *)((char *)d.vals + ((size_t)(wrow + i) * pitchW + (size_t)(col0 / 8) * 4) * ES + lane_v));
+            }
+            // two lanes share three bytes: the even one writes the first two, the odd one the third
+            uint8_t *ip = &IDX[8 * brl + i][3 * (strip >> 1)];
+            if ((l & 1u) == 0) {
+                ip[0] = (uint8_t)code;
+                ip[1] = (uint8_t)((code >> 8) | (other << 4));
+            } else {
+                ip[2] = (uint8_t)(code >> 4);
+            }
+        }
+        // ---- W^T: the columns ----
+        uint32_t cx, cy;
+        transpose_bits8(rb, cx, cy);
+        uint32_t oc0[8], oc1[8];
+#pragma unroll
+        for (int c = 0; c < 8; c++) {
+            const uint32_t kb = ((c < 4 ? cx : cy) >> (8 * (c & 3))) & 0xFFu;
+            const uint32_t selh = (c & 1) ? 0x07060302u : 0x05040100u;     // the column's halfword of two rows
+            const uint32_t d0 = __builtin_amdgcn_perm(e[1][c >> 1], e[0][c >> 1], selh);
+            const uint32_t d1 = __builtin_amdgcn_perm(e[3][c >> 1], e[2][c >> 1], selh);
+            const uint32_t d2 = __builtin_amdgcn_perm(e[5][c >> 1], e[4][c >> 1], selh);
+            const uint32_t d3 = __builtin_amdgcn_perm(e[7][c >> 1], e[6][c >> 1], selh);
+            uint32_t code;
+            compact_4of8(kb, d0, d1, d2, d3, LUTS, LUTC, oc0[c], oc1[c], code);
+            tcode[c] |= (ok ? code : 0u) << (12 * q);
+        }
+        *(u32x4 *)&OT[2 * brl][tcol] = u32x4{oc0[0], oc0[1], oc0[2], oc0[3]};
+        *(u32x4 *)&OT[2 * brl][tcol + 4] = u32x4{oc0[4], oc0[5], oc0[6], oc0[7]};
+        *(u32x4 *)&OT[2 * brl + 1][tcol] = u32x4{oc1[0], oc1[1], oc1[2], oc1[3]};
+        *(u32x4 *)&OT[2 * brl + 1][tcol + 4] = u32x4{oc1[4], oc1[5], oc1[6], oc1[7]};
+    }
+    // the lane's two block-rows are neighbours: 24 position bits = three whole bytes per column
+#pragma unroll
+    for (int t = 0; t < 3; t++) {
+        u32x2 v;
+        v.x = ((tcode[0] >> (8 * t)) & 0xFFu) | (((tcode[1] >> (8 * t)) & 0xFFu) << 8) |
+              (((tcode[2] >> (8 * t)) & 0xFFu) << 16) | (((tcode[3] >> (8 * t)) & 0xFFu) << 24);
+        v.y = ((tcode[4] >> (8 * t)) & 0xFFu) | (((tcode[5] >> (8 * t)) & 0xFFu) << 8) |
+              (((tcode[6] >> (8 * t)) & 0xFFu) << 16) | (((tcode[7] >> (8 * t)) & 0xFFu) << 24);
+        *(u32x2 *)&IDXT[3 * q2 + t][tcol] = v;
+    }
+    __syncthreads();
+
+    // ---- stream the tile's W^T values and both position arrays out ----
+    const uint32_t cols_valid = min((uint32_t)TC, d.cols - col0);
+    const uint32_t brs_valid = min((uint32_t)(TR / 8), (d.rows - row0) / 8);
+    const uint32_t rows_valid = brs_valid * 8;
+    {
+        const size_t pitch_b = (size_t)(d.rows / 8) * 4 * ES;          // bytes per row of valsT
+        char *dst = (char *)d.valsT + (size_t)col0 * pitch_b + (size_t)(row0 / 8) * 4 * ES;
+        if (brs_valid == TR / 8 && (pitch_b & 15) == 0 && (((uintptr_t)dst) & 15) == 0) {
+            constexpr uint32_t CH = OTD / 4;                           // 16-byte pieces per column
+            for (uint32_t j = tid; j < cols_valid * CH; j += kThreads) {
+                const uint32_t cc = j / CH, part = j % CH;
+                const u32x4 v = {OT[4 * part][cc], OT[4 * part + 1][cc], OT[4 * part + 2][cc], OT[4 * part + 3][cc]};
+                stream_store(v, (u32x4 *)(dst + (size_t)cc * pitch_b + 16 * part));
+            }
+        } else {
+            const uint32_t rd = brs_valid * 2;                         // dwords per column
+            for (uint32_t j = tid; j < cols_valid * rd; j += kThreads) {
+                const uint32_t cc = j / rd, x = j - cc * rd;
+                *(uint32_t *)(dst + (size_t)cc * pitch_b + 4 * x) = OT[x][cc];
+            }
+        }
+    }
+    {
+        const size_t pitch = ((size_t)(d.cols / 8) * 12 + 7) / 8;
+        const uint32_t nb = ((cols_valid / 8) * 12 + 7) / 8;
+        unsigned char *dst = (unsigned char *)d.idx + (size_t)row0 * pitch + (size_t)(col0 / 8) * 12 / 8;
+        if ((nb & 3) == 0 && (pitch & 3) == 0 && (((uintptr_t)dst) & 3) == 0) {
+            const uint32_t nd = nb / 4;
+            for (uint32_t j = tid; j < rows_valid * nd; j += kThreads) {
+                const uint32_t r = j / nd, x = j - r * nd;
+                *(uint32_t *)(dst + (size_t)r * pitch + 4 * x) = ((const uint32_t *)&IDX[r][0])[x];
+            }
+        } else {
+            for (uint32_t j = tid; j < rows_valid * nb; j += kThreads) {
+                const uint32_t r = j / nb, x = j - r * nb;
+                dst[(size_t)r * pitch + x] = IDX[r][x];
+            }
+        }
+    }
+    {
+        const size_t pitch = ((size_t)(d.rows / 8) * 12 + 7) / 8;
+        const uint32_t nb = (brs_valid * 12 + 7) / 8;
+        unsigned char *dst = (unsigned char *)d.idxT + (size_t)col0 * pitch + (size_t)(row0 / 8) * 12 / 8;
+        if (nb == IDXTB && (pitch & 7) == 0 && (((uintptr_t)dst) & 7) == 0) {
+            for (uint32_t j = tid; j < cols_valid * (IDXTB / 8); j += kThreads) {
+                const uint32_t piece = j / cols_valid, cc = j - piece * cols_valid;
+                u32x2 v = {0u, 0u};
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    v.x |= (uint32_t)IDXT[8 * piece + k][cc] << (8 * k);
+                    v.y |= (uint32_t)IDXT[8 * piece + 4 + k][cc] << (8 * k);
+                }
+                *(u32x2 *)(dst + (size_t)cc * pitch + 8 * piece) = v;
+            }
+        } else {
+            for (uint32_t j = tid; j < cols_valid * nb; j += kThreads) {
+                const uint32_t x = j / cols_valid, cc = j - x * cols_valid;
+                dst[(size_t)cc * pitch + x] = IDXT[x][cc];
+            }
+        }
+    }
+}
+
+}  // namespace tmask

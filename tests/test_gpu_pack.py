@@ -78,3 +78,18 @@ def test_pack_roundtrip_and_l1():
     assert np.array_equal(oracle.unpack(vals, idx, 128, 256, 4, 8), masked)
     assert np.array_equal(oracle.unpack(valsT, idxT, 256, 128, 4, 8), masked.T)
     assert np.abs(vals.astype(np.float64)).sum() == pytest.approx(obj, rel=1e-12)
+
+
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+def test_pack48_bf16_multi_tile_and_degenerate_masks(fmt):
+    # several whole tiles of the 4:8 bf16 kernel (128 rows x 256 columns) plus ragged edges in both directions
+    w = wl.f32_to_bf16_bits(wl.special_values_f32(392, 776, seed=4500))
+    rng = np.random.default_rng(45)
+    masks = [oracle.approx(w, 4, 8)[0],
+             (rng.random(w.shape) < 0.5).astype(np.uint8),      # unstructured: 0 to 8 kept per group
+             np.zeros(w.shape, dtype=np.uint8), np.ones(w.shape, dtype=np.uint8)]
+    masks[1][:, :16] = 0
+    masks[1][:16, :] = 1
+    for mask in masks:
+        (got,) = run_pack([w], [mask], 4, 8, fmt)
+        _same(got, oracle.apply_pack(w, mask, 4, 8))
