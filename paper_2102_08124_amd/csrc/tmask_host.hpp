@@ -28,4 +28,21 @@ struct ProfileScope {
     }
 };
 
+// Compute units of the current device (256 if the query fails); asked once per thread and device.
+inline int cu_count()
+{
+    static thread_local int cached_dev = -1, cached = 256;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return 256;
+    if (dev != cached_dev) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached = n;
+        cached_dev = dev;
+    }
+    return cached;
+}
+
 }  // namespace tmask

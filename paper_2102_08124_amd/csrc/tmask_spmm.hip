@@ -349,13 +349,7 @@ extern "C" int tmask_spmm24(const void *vals, const void *idx, int64_t rows, int
     if (n_tiles > 0x7FFFFFFFull)
         return fail(TMASK_ERR_SHAPE, "too many tiles");
     // one workgroup per compute unit, a multiple of 8 (the XCD count) when there are that many tiles
-    static thread_local int cus = 0;
-    if (!cus) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        cus = n;
-    }
+    const int cus = cu_count();
     uint32_t grid = n_tiles < (uint64_t)cus ? (uint32_t)n_tiles : (uint32_t)cus;
     if (grid >= 8)
         grid &= ~7u;
