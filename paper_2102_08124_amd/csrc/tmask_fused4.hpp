@@ -2,7 +2,7 @@
 // W and W^T in one pass over W.  The mask never travels through memory between the two steps; it is
 // written only if the caller wants it.
 //
-// Same tiling as pack24_kernel (64 rows x 64 strips per workgroup, a lane holds whole 4x4 blocks), so
+// Same tiling as pack24_kernel (S strips x 4096 / S rows per workgroup, a lane holds whole 4x4 blocks), so
 // the keep flags that Algorithm 1's rank form yields as lane masks (tmask_approx4.hpp) feed the slot
 // logic of the compaction (tmask_pack4.hpp) directly.
 #pragma once
@@ -23,12 +23,12 @@ struct FusedArgs {
 };
 static_assert(sizeof(FusedArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
 
-template <int DT, int FMT, bool WMASK>
+template <int DT, int FMT, bool WMASK, int S>
 __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs args)
 {
-    using PG = Pack4Geo<DT>;
+    using PG = Pack4Geo<DT, S>;
     constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, OTD = PG::OTD, TCP = PG::TCP,
-                  IDXB = PG::IDXB, NQ = PG::NQ;
+                  IDXB = PG::IDXB, NQ = PG::NQ, LPR = PG::LPR;
 
     __shared__ __attribute__((aligned(16))) uint32_t OT[OTD][TCP];      // [position down the column][column]
     __shared__ __attribute__((aligned(16))) uint16_t IDXT[NQ][TC];
@@ -50,11 +50,17 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
     const uint32_t row0 = ty * TR, col0 = tx * TC;
     const uint32_t tid = threadIdx.x, l = tid & 63u;
     // the wavefront number as a scalar: row addresses below are then scalar too, and a lane adds only
-    // its fixed offset inside the 1 KiB run
+    // its fixed offsets (its strip inside the run, the distance of its sub-row)
     const uint32_t w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t col = col0 + l * C;
+    const uint32_t strip = l % (uint32_t)S, sub = l / (uint32_t)S;
+    const uint32_t q4 = w * LPR + sub;                 // this lane's run of four block-rows inside the tile
+    const uint32_t tcol = strip * C;                   // first column of the lane inside the tile
+    const uint32_t col = col0 + tcol;
     const bool strip_ok = col < d.cols;
     const size_t pitchW = (size_t)(d.cols / 4) * 2;    // elements per row of vals
+    const size_t lane_w = (size_t)sub * 16u * d.ld * ES + strip * 16u;
+    const size_t lane_v = (size_t)sub * 16u * pitchW * ES + strip * 8u;
+    const size_t lane_m = (size_t)sub * 16u * d.mask_ld;
     float acc = 0.f;
 
     // Tiles wholly inside the matrix run a copy of the loop without bounds tests (no branch splits it).
@@ -68,7 +74,8 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
         // loads run one block-row ahead of the work on them
         u32x4 rawb[2][4];
         auto issue = [&](int q, u32x4 (&raw)[4]) {
-            const uint32_t row = row0 + 4 * (4 * w + (uint32_t)q);
+            const uint32_t wrow = row0 + 16u * LPR * w + 4u * (uint32_t)q;    // scalar: the row of sub-row 0
+            const uint32_t row = wrow + 16u * sub;
 #pragma unroll
             for (int i = 0; i < 4; i++)
                 raw[i] = u32x4{0u, 0u, 0u, 0u};
@@ -76,15 +83,16 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
 #pragma unroll
                 for (int i = 0; i < 4; i++)
                     raw[i] = __builtin_nontemporal_load(
-                        (const u32x4 *)((const char *)d.w + ((size_t)(row + i) * d.ld + col0) * ES + l * 16u));
+                        (const u32x4 *)((const char *)d.w + ((size_t)(wrow + i) * d.ld + col0) * ES + lane_w));
             }
         };
         issue(0, rawb[0]);
 
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-            const uint32_t brl = 4 * w + q;
-            const uint32_t row = row0 + 4 * brl;
+            const uint32_t brl = 4 * q4 + q;                       // block-row inside the tile
+            const uint32_t wrow = row0 + 16u * LPR * w + 4u * (uint32_t)q;
+            const uint32_t row = wrow + 16u * sub;
             const bool ok = !EDGE || (strip_ok && row < d.rows);
             if (q + 1 < 4)
                 issue(q + 1, rawb[(q + 1) & 1]);
@@ -168,10 +176,10 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if constexpr (DT == kF32) {
-                    *(u32x4 *)&OT[brl * 2][l * C] = u32x4{t0[0], t0[1], t0[2], t0[3]};
-                    *(u32x4 *)&OT[brl * 2 + 1][l * C] = u32x4{t1[0], t1[1], t1[2], t1[3]};
+                    *(u32x4 *)&OT[brl * 2][tcol] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl * 2 + 1][tcol] = u32x4{t1[0], t1[1], t1[2], t1[3]};
                 } else {
-                    *(u32x4 *)&OT[brl][l * C + 4 * g] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl][tcol + 4 * g] = u32x4{t0[0], t0[1], t0[2], t0[3]};
                 }
             }
             if (EDGE && !ok) {
@@ -192,11 +200,11 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
                     v.x = rowout[i][0];
                     v.y = rowout[i][1];
                     stream_store(
-                        v, (u32x2 *)((char *)d.vals + ((size_t)(row + i) * pitchW + (size_t)(col0 / 4) * 2) * ES + l * 8u));
+                        v, (u32x2 *)((char *)d.vals + ((size_t)(wrow + i) * pitchW + (size_t)(col0 / 4) * 2) * ES + lane_v));
                     if constexpr (WMASK) {
-                        char *mrow = (char *)const_cast<void *>(d.mask) + (size_t)(row + i) * d.mask_ld +
+                        char *mrow = (char *)const_cast<void *>(d.mask) + (size_t)(wrow + i) * d.mask_ld + lane_m +
                                      ((FMT == kMaskU8) ? col0 : (col0 >> 3));
-                        const uint32_t lcol = l * (uint32_t)C;   // the lane's first column inside the tile
+                        const uint32_t lcol = tcol;              // the lane's first column inside the tile
                         if constexpr (FMT == kMaskU8) {
                             if constexpr (C == 4) {
                                 stream_store(rowmask[i][0], (uint32_t *)(mrow + lcol));
@@ -222,9 +230,9 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
                 if constexpr (C == 4) {
                     const uint32_t other = quad_xor<1>(rownib[i]);
                     if ((l & 1u) == 0)
-                        IDX[4 * brl + i][l >> 1] = (uint8_t)(rownib[i] | (other << 4));
+                        IDX[4 * brl + i][strip >> 1] = (uint8_t)(rownib[i] | (other << 4));
                 } else {
-                    IDX[4 * brl + i][l] = (uint8_t)rownib[i];
+                    IDX[4 * brl + i][strip] = (uint8_t)rownib[i];
                 }
             }
         }
@@ -236,7 +244,7 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
         // block-rows of this wavefront that lie outside the matrix must not leave position bits either
         if (EDGE) {
             const uint32_t brs_in = (d.rows - row0) / 4;           // block-rows of the tile inside the matrix
-            const uint32_t mine = brs_in > 4 * w ? brs_in - 4 * w : 0;
+            const uint32_t mine = brs_in > 4 * q4 ? brs_in - 4 * q4 : 0;
             const uint32_t keepmask = mine >= 4 ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
 #pragma unroll
             for (int c = 0; c < C; c++)
@@ -246,9 +254,9 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
             u32x2 v;
             v.x = tnib[0] | (tnib[1] << 16);
             v.y = tnib[2] | (tnib[3] << 16);
-            *(u32x2 *)&IDXT[w][l * C] = v;
+            *(u32x2 *)&IDXT[q4][tcol] = v;
         } else {
-            *(u32x4 *)&IDXT[w][l * C] = u32x4{tnib[0] | (tnib[1] << 16), tnib[2] | (tnib[3] << 16),
+            *(u32x4 *)&IDXT[q4][tcol] = u32x4{tnib[0] | (tnib[1] << 16), tnib[2] | (tnib[3] << 16),
                                               tnib[4] | (tnib[5] << 16), tnib[6] | (tnib[7] << 16)};
         }
     };
@@ -257,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
     else
         compute(std::true_type{});
     __syncthreads();
-    pack24_copy_out<DT>(d, row0, col0, OT, IDXT, IDX);
+    pack24_copy_out<DT, S>(d, row0, col0, OT, IDXT, IDX);
     if (args.partials) {
         const double t = block_sum_f32(acc, red);
         if (threadIdx.x == 0)

@@ -879,8 +879,11 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
         return tmask_apply_pack(pds.data(), n, dt, N, M, mf, workspace, workspace_bytes, hip_stream);
     }
 
-    const uint32_t TC = kPack4Strips * 16 / (uint32_t)elem_size((int)dt);
-    constexpr uint32_t kPack4Rows = 4096 / kPack4Strips;
+    // tile widths in strips as in tmask_apply_pack
+    constexpr int SF = 64, SB = 32;
+    const uint32_t strips = dt == TMASK_F32 ? SF : SB;
+    const uint32_t TC = strips * 16 / (uint32_t)elem_size((int)dt);
+    const uint32_t kPack4Rows = 4096 / strips;
     if (want_obj) {
         size_t tiles = 0;
         for (int i = 0; i < n; i++)
@@ -892,10 +895,10 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     }
     typedef void (*fused_kernel_t)(const FusedArgs);
     fused_kernel_t kern = nullptr;
-#define TMASK_PICK(DT, FM) \
+#define TMASK_PICK(DT, FM, SS) \
     if ((int)dt == DT && (int)mf == FM) \
-        kern = with_mask ? approx_pack24_kernel<DT, FM, true> : approx_pack24_kernel<DT, FM, false>;
-    TMASK_PICK(kF32, kMaskU8) TMASK_PICK(kF32, kMaskBits) TMASK_PICK(kBF16, kMaskU8) TMASK_PICK(kBF16, kMaskBits)
+        kern = with_mask ? approx_pack24_kernel<DT, FM, true, SS> : approx_pack24_kernel<DT, FM, false, SS>;
+    TMASK_PICK(kF32, kMaskU8, SF) TMASK_PICK(kF32, kMaskBits, SF) TMASK_PICK(kBF16, kMaskU8, SB) TMASK_PICK(kBF16, kMaskBits, SB)
 #undef TMASK_PICK
     hipStream_t stream = (hipStream_t)hip_stream;
     uint32_t partial0 = 0;
