@@ -213,7 +213,7 @@ def main():
                     help="also run a plain 256 MiB device copy (known traffic) for scaling rocprofv3 --pmc counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (blocks are independent, see DESIGN.md); "
+        print("bench.py measures one GPU: this build has no multi-GPU path (blocks are independent: the path shards by matrix or by block-row band without any exchange); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

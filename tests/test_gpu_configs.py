@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of the benchmark configurations (benchmark configs 2-5).
+"""GPU parity at the full sizes of the benchmark workloads (the ResNet-50, BERT-large, 8192^2 and 16384^2 cases).
 
 Where the oracle finishes in seconds the comparison is complete; where it does not (exact 4:8 /
 8:16 on hundreds of millions of weights) the GPU result is checked for validity everywhere and
