@@ -167,7 +167,10 @@ __global__ __launch_bounds__(kSpThreads, 1) void spmm24_kernel(const SpmmArgs p)
 #pragma unroll
             for (int i = 0; i < kSpBL; i++)
                 *(su32x4 *)&Bs[buf][((uint32_t)i * 32u + (tid >> 3)) * kSpBPitch + (tid & 7u) * 16u] = r.rb[i];
-            *(su32x2 *)&Is[buf][(tid % kSpTR) * kSpIPitch] = r.ri;
+            // index bytes regrouped as (0, 2, 4, 6, 1, 3, 5, 7): the two bytes a lane needs (groups g0, g0+1 and
+            // g0+4, g0+5) then sit side by side and come with one 16-bit read
+            *(su32x2 *)&Is[buf][(tid % kSpTR) * kSpIPitch] =
+                su32x2{__builtin_amdgcn_perm(r.ri.y, r.ri.x, 0x06040200u), __builtin_amdgcn_perm(r.ri.y, r.ri.x, 0x07050301u)};
         };
         // Stream step g is multiplied out of LDS buffer g % 3 while the feeders write step g + 2 into buffer
         // (g + 2) % 3 (last read at step g - 1, before the previous barrier) and issue the loads of step g + 5
@@ -211,20 +214,22 @@ __global__ __launch_bounds__(kSpThreads, 1) void spmm24_kernel(const SpmmArgs p)
         // the lane's two runs of compressed A inside a step: groups g0, g0+1 (8 bytes) and g0+4, g0+5
         const uint32_t g0 = 8u * (a & 1u) + 2u * (a >> 1);
         const uint32_t a_off = g0 * 4u;                 // bytes: 2 values x 2 bytes per group
-        const uint32_t i_off = g0 >> 1;                 // index byte of groups g0, g0+1; groups g0+4, g0+5 are 2 further
+        const uint32_t i_off = 2u * a;                  // the lane's two index bytes in the regrouped order
 
         // Fragments of x for a step are read one step ahead (the ring buffer of step g + 1 is complete when step
         // g starts), and so is the first A fragment: the matrix instructions of a step start without waiting
         // for LDS, and the remaining A fragments arrive while they run.
+        auto read_b1 = [&](int buf, int ct, bf16x16 &bfrag) {
+            const unsigned char *src = &Bs[buf][(wc * (kSpCT * 16u) + (uint32_t)ct * 16u + m) * kSpBPitch + a * 32u];
+            union { su32x4 u[2]; bf16x16 v; } cv;
+            cv.u[0] = *(const su32x4 *)src;
+            cv.u[1] = *(const su32x4 *)(src + 16);
+            bfrag = cv.v;
+        };
         auto read_b = [&](int buf, bf16x16 (&bfrag)[kSpCT]) {
 #pragma unroll
-            for (int ct = 0; ct < kSpCT; ct++) {
-                const unsigned char *src = &Bs[buf][(wc * (kSpCT * 16u) + ct * 16u + m) * kSpBPitch + a * 32u];
-                union { su32x4 u[2]; bf16x16 v; } cv;
-                cv.u[0] = *(const su32x4 *)src;
-                cv.u[1] = *(const su32x4 *)(src + 16);
-                bfrag[ct] = cv.v;
-            }
+            for (int ct = 0; ct < kSpCT; ct++)
+                read_b1(buf, ct, bfrag[ct]);
         };
         auto read_a = [&](int buf, int rt, bf16x8 &av, int &sel) {
             const uint32_t r = wr * (kSpRT * 16u) + (uint32_t)rt * 16u + m;
@@ -233,28 +238,41 @@ __global__ __launch_bounds__(kSpThreads, 1) void spmm24_kernel(const SpmmArgs p)
             cv.u[0] = *(const su32x2 *)src;
             cv.u[1] = *(const su32x2 *)(src + 16);
             av = cv.v;
-            const unsigned char *is = &Is[buf][r * kSpIPitch + i_off];
-            sel = (int)((uint32_t)is[0] | ((uint32_t)is[2] << 8));
+            sel = (int)*(const uint16_t *)&Is[buf][r * kSpIPitch + i_off];
         };
         bf16x16 bcur[kSpCT];
         bf16x8 a0;
         int sel0;
+        // A fragments travel through a ring of three register sets, read two instruction rows ahead of their use,
+        // and the reads of the next step's x fragments are spread over the rows: every matrix instruction finds
+        // its operands in registers, and LDS latency hides behind the 4 x 16 cycles of a row of instructions.
+        // (Left to itself the compiler reads every fragment into the registers of the one before, i.e. after the
+        // instructions that use those have issued, and waits for it.)
         auto multiply = [&](int cur) {
             const int nxt = (cur + 1) % kSpRing;
             bf16x16 bnext[kSpCT];
             bf16x8 a0n;
             int sel0n;
-            read_b(nxt, bnext);
-            read_a(nxt, 0, a0n, sel0n);
+            bf16x8 av[3];
+            int sel[3];
+            av[0] = a0;
+            sel[0] = sel0;
+            read_a(cur, 1, av[1], sel[1]);
+            read_a(cur, 2, av[2], sel[2]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int rt = 0; rt < kSpRT; rt++) {
-                bf16x8 av = a0;
-                int sel = sel0;
-                if (rt > 0)
-                    read_a(cur, rt, av, sel);
 #pragma unroll
                 for (int ct = 0; ct < kSpCT; ct++)
-                    acc[rt][ct] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av, bcur[ct], acc[rt][ct], sel, 0, 0);
+                    acc[rt][ct] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(av[rt % 3], bcur[ct], acc[rt][ct], sel[rt % 3], 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (rt + 3 < kSpRT)
+                    read_a(cur, rt + 3, av[rt % 3], sel[rt % 3]);
+                if (rt < kSpCT)
+                    read_b1(nxt, rt, bnext[rt]);
+                if (rt == kSpCT)
+                    read_a(nxt, 0, a0n, sel0n);
+                __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int ct = 0; ct < kSpCT; ct++)
