@@ -94,6 +94,9 @@ __device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_
             sum += keep ? __uint_as_float(mag[c]) : 0.f;
         }
         emit_row(i, bytes[0], bytes[1]);
+        // the row's part of the sum is added here, not wherever the caller first needs the total (it would keep
+        // every keep flag alive as a lane mask until then)
+        asm volatile("" : "+v"(sum));
         __builtin_amdgcn_sched_barrier(0);   // finish (and store) a row before the next one starts
     }
     return sum;

@@ -15,14 +15,6 @@
 
 namespace tmask {
 
-struct FusedArgs {
-    PackDev d[kMaxPackBatch];   // mask = output here (may be null when WMASK is false)
-    uint32_t n;
-    uint32_t partial0;          // index of this launch's first partial in the workspace
-    void *partials;             // one double per workgroup, or null
-};
-static_assert(sizeof(FusedArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
-
 template <int DT, int FMT, bool WMASK, int S>
 __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs args)
 {

@@ -807,7 +807,8 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
     for (int i = 0; i < n && fast48; i++)
         fast48 = (((uintptr_t)descs[i].vals | (uintptr_t)descs[i].valsT) & 7) == 0;
     if (fast48) {
-        kern = mf == TMASK_MASK_U8 ? pack48_bf16_kernel<kMaskU8> : pack48_bf16_kernel<kMaskBits>;
+        kern = mf == TMASK_MASK_U8 ? pack48_bf16_kernel<kMaskU8, false, false, PackArgs>
+                                   : pack48_bf16_kernel<kMaskBits, false, false, PackArgs>;
         TC = Pack8Geo::TC;
         TR = Pack8Geo::TR;
     }
@@ -844,7 +845,8 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
     if (rc)
         return rc;
-    const bool fused = (M == 4 && N == 2);
+    const bool fused24 = (M == 4 && N == 2);
+    bool fused48 = (M == 8 && N == 4 && dt == TMASK_BF16);     // needs 8-byte aligned outputs, else two steps
     int with_mask = 0;
     bool want_obj = false;
     for (int i = 0; i < n; i++) {
@@ -858,9 +860,11 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
             return fail(TMASK_ERR_NULL, "matrix %d: a packed output pointer is NULL", i);
         if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
             return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 4-byte aligned", i);
-        if (fused && ((((uintptr_t)p.vals | (uintptr_t)p.valsT) & 7) != 0))
+        if (fused24 && ((((uintptr_t)p.vals | (uintptr_t)p.valsT) & 7) != 0))
             return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 8-byte aligned for 2:4", i);
+        fused48 = fused48 && ((((uintptr_t)p.vals | (uintptr_t)p.valsT) & 7) == 0);
     }
+    const bool fused = fused24 || fused48;
     if (with_mask != 0 && with_mask != n)
         return fail(TMASK_ERR_NULL, "mask must be given for all matrices or for none (%d of %d have one)", with_mask, n);
     if (!fused && with_mask == 0)
@@ -879,11 +883,11 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
         return tmask_apply_pack(pds.data(), n, dt, N, M, mf, workspace, workspace_bytes, hip_stream);
     }
 
-    // tile widths in strips as in tmask_apply_pack
+    // tile shapes as in tmask_apply_pack
     constexpr int SF = 64, SB = 32;
     const uint32_t strips = dt == TMASK_F32 ? SF : SB;
-    const uint32_t TC = strips * 16 / (uint32_t)elem_size((int)dt);
-    const uint32_t kPack4Rows = 4096 / strips;
+    const uint32_t TC = fused48 ? (uint32_t)Pack8Geo::TC : strips * 16 / (uint32_t)elem_size((int)dt);
+    const uint32_t kPack4Rows = fused48 ? (uint32_t)Pack8Geo::TR : 4096 / strips;
     if (want_obj) {
         size_t tiles = 0;
         for (int i = 0; i < n; i++)
@@ -900,6 +904,13 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
         kern = with_mask ? approx_pack24_kernel<DT, FM, true, SS> : approx_pack24_kernel<DT, FM, false, SS>;
     TMASK_PICK(kF32, kMaskU8, SF) TMASK_PICK(kF32, kMaskBits, SF) TMASK_PICK(kBF16, kMaskU8, SB) TMASK_PICK(kBF16, kMaskBits, SB)
 #undef TMASK_PICK
+    if (fused48) {
+        if (mf == TMASK_MASK_U8)
+            kern = with_mask ? pack48_bf16_kernel<kMaskU8, true, true, FusedArgs> : pack48_bf16_kernel<kMaskU8, true, false, FusedArgs>;
+        else
+            kern = with_mask ? pack48_bf16_kernel<kMaskBits, true, true, FusedArgs>
+                             : pack48_bf16_kernel<kMaskBits, true, false, FusedArgs>;
+    }
     hipStream_t stream = (hipStream_t)hip_stream;
     uint32_t partial0 = 0;
     for (int first = 0; first < n; first += kMaxPackBatch) {
@@ -924,7 +935,8 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
         args.n = (uint32_t)nb; args.partial0 = partial0; args.partials = want_obj ? workspace : nullptr;
         {
             ProfileScope prof(stream, first + kMaxPackBatch >= n);
-            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), dt == TMASK_F32 ? kPack4LdsReserveF32 : 0, stream, args);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), (fused24 && dt == TMASK_F32) ? kPack4LdsReserveF32 : 0, stream,
+                               args);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)

@@ -37,6 +37,16 @@ struct PackArgs {
 };
 static_assert(sizeof(PackArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
 
+// Arguments of the kernels that compute the mask themselves (tmask_approx_pack).
+struct FusedArgs {
+    PackDev d[kMaxPackBatch];   // mask = output here (may be null when WMASK is false)
+    uint32_t n;
+    uint32_t partial0;          // index of this launch's first partial in the workspace
+    void *partials;             // one double per workgroup, or null
+};
+static_assert(sizeof(FusedArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+
+
 template <int M>
 struct Log2 {
     static constexpr int v = (M == 4) ? 2 : (M == 8) ? 3 : 4;

@@ -10,6 +10,7 @@
 // two block-rows per step pair, W values go straight to memory (8 B per lane and row), W^T values and the
 // position bits of both directions are staged in LDS and streamed out in whole runs.
 #pragma once
+#include "tmask_approx_sel.hpp"
 #include "tmask_device.hpp"
 #include "tmask_pack.hpp"
 
@@ -56,8 +57,11 @@ __device__ __forceinline__ void compact_4of8(uint32_t kbits, uint32_t d0, uint32
     o1 = __builtin_amdgcn_perm(d1, d0, L.z) | __builtin_amdgcn_perm(d3, d2, L.w);
 }
 
-template <int FMT>
-__global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs args)
+// APPROX = false: tmask_apply_pack (ARGS = PackArgs, the mask is read).  APPROX = true: tmask_approx_pack
+// (ARGS = FusedArgs): the keep flags come from Algorithm 1 in its threshold form (approx_half_bf16) on the
+// lane's block; the mask is written if WMASK, the kept magnitudes' sum goes to the workgroup's partial.
+template <int FMT, bool APPROX, bool WMASK, typename ARGS>
+__global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const ARGS args)
 {
     using PG = Pack8Geo;
     constexpr int ES = 2, S = PG::S, LPR = PG::LPR, NSTEP = PG::NSTEP, TR = PG::TR, TC = PG::TC, OTD = PG::OTD,
@@ -68,6 +72,7 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs ar
     __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
     __shared__ __attribute__((aligned(16))) u32x4 LUTS[256];
     __shared__ uint16_t LUTC[256];
+    __shared__ double red[kThreads / 64];
 
     const uint32_t tid = threadIdx.x, l = tid & 63u;
     // ---- the table: entry m describes the set m of chosen positions (used only for sets of four) ----
@@ -118,12 +123,12 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs ar
     const size_t mcol0 = FMT == kMaskU8 ? col0 : 0;
     __syncthreads();                                      // the table is complete
 
-    // ---- all loads of the lane's two blocks first ----
+    // ---- loads: both blocks of the lane first; when the mask is computed here, the second block's rows are
+    // requested only after the first block's thresholds are done (they would occupy registers meanwhile) ----
     u32x4 raw[NSTEP][8];
     uint32_t mk0[NSTEP][8], mk1[NSTEP][8];               // U8: the row's eight mask bytes; BITS: the byte in mk0
     bool okq[NSTEP];
-#pragma unroll
-    for (int q = 0; q < NSTEP; q++) {
+    auto issue = [&](int q) {
         const uint32_t wrow = row0 + 8u * NSTEP * LPR * w + 8u * (uint32_t)q;     // scalar: the row of sub-run 0
         const uint32_t row = wrow + 8u * NSTEP * sub;
         okq[q] = strip_ok && row < d.rows;
@@ -137,6 +142,8 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs ar
             for (int i = 0; i < 8; i++) {
                 raw[q][i] = __builtin_nontemporal_load(
                     (const u32x4 *)((const char *)d.w + ((size_t)(wrow + i) * d.ld + col0) * ES + lane_w));
+                if constexpr (APPROX)
+                    continue;
                 const unsigned char *mp = (const unsigned char *)d.mask + (size_t)(wrow + i) * d.mask_ld + mcol0 + lane_m;
                 if constexpr (FMT == kMaskU8) {
                     const u32x2 mv = __builtin_nontemporal_load((const u32x2 *)mp);
@@ -147,8 +154,13 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs ar
                 }
             }
         }
-    }
+    };
+    issue(0);
+    if constexpr (!APPROX)
+        issue(1);
+    static_assert(NSTEP == 2, "the load schedule above is written for two blocks per lane");
 
+    float acc = 0.f;
     uint32_t tcode[8];                                    // position bits of the lane's columns, 12 per block-row
 #pragma unroll
     for (int c = 0; c < 8; c++)
@@ -159,12 +171,43 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs ar
         const uint32_t brl = NSTEP * q2 + (uint32_t)q;   // block-row inside the tile
         const uint32_t wrow = row0 + 8u * NSTEP * LPR * w + 8u * (uint32_t)q;
         const bool ok = okq[q];
+        if constexpr (APPROX) {
+            // Algorithm 1 on the lane's block: 0/1 bytes per row, stored as the mask on request.  (Lanes outside
+            // the matrix hold zeros: their flags are discarded below and their sum is zero.)
+            acc += approx_half_bf16<8>(raw[q], 0u, [&](int i, uint32_t b0, uint32_t b1) {
+                mk0[q][i] = b0;
+                mk1[q][i] = b1;
+                // the flags exist as bytes from here on (otherwise the compiler carries the compare results of all
+                // 64 entries as lane masks into the compaction below and runs out of scalar registers)
+                asm volatile("" : "+v"(mk0[q][i]), "+v"(mk1[q][i]));
+                if constexpr (WMASK) {
+                    if (ok) {
+                        unsigned char *mp = (unsigned char *)const_cast<void *>(d.mask) + (size_t)(wrow + i) * d.mask_ld + mcol0 + lane_m;
+                        if constexpr (FMT == kMaskU8) {
+                            u32x2 v;
+                            v.x = b0;
+                            v.y = b1;
+                            stream_store(v, (u32x2 *)mp);
+                        } else {
+                            *mp = (unsigned char)(bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4));
+                        }
+                    }
+                }
+            });
+            // the sum is needed only at the very end, and only if an objective is asked for: left alone, the compiler
+            // moves all its additions there and keeps every keep flag and magnitude alive until then
+            asm volatile("" : "+v"(acc));
+            __builtin_amdgcn_sched_barrier(0);
+            if (q == 0)
+                issue(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         // keep bits per row, and the block with its pruned values zeroed
         uint32_t rb[8], e[8][4];
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const uint32_t dw[4] = {raw[q][i].x, raw[q][i].y, raw[q][i].z, raw[q][i].w};
-            if constexpr (FMT == kMaskU8) {
+            if constexpr (FMT == kMaskU8 || APPROX) {
                 // bytes -> 0x00 / 0xFF, then every byte doubled into a halfword mask
                 uint32_t f[2] = {mk0[q][i], mk1[q][i]};
 #pragma unroll
@@ -301,6 +344,13 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const PackArgs ar
                 const uint32_t x = j / cols_valid, cc = j - x * cols_valid;
                 dst[(size_t)cc * pitch + x] = IDXT[x][cc];
             }
+        }
+    }
+    if constexpr (APPROX) {
+        if (args.partials) {
+            const double t = block_sum_f32(acc, red);
+            if (threadIdx.x == 0)
+                ((double *)args.partials)[args.partial0 + tile] = t;
         }
     }
 }

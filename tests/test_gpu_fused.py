@@ -71,6 +71,18 @@ def test_fused_batched_with_strides_and_no_objective(dt):
     _check(ws[:5], 2, 4, got, masks, objs, with_mask=False)
 
 
+@pytest.mark.parametrize("with_mask", [True, False])
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+def test_fused_4of8_bf16_one_pass(fmt, with_mask):
+    # bf16 4:8 has its own one-pass kernel (128 x 256 tiles): whole tiles, ragged edges, a single block, and a
+    # tie-heavy matrix with special values (the index tie-break decides many entries there)
+    ws = [_w("bf16", 392, 776, seed=5200), _w("bf16", 256, 512, seed=5201), _w("bf16", 8, 8, seed=5202),
+          wl.f32_to_bf16_bits(wl.tie_heavy_f32(136, 264, seed=5203)),
+          wl.f32_to_bf16_bits(wl.special_values_f32(64, 128, seed=5204))]
+    got, masks, objs = run_fused(ws, 4, 8, fmt, with_mask=with_mask, ld_pad=24)
+    _check(ws, 4, 8, got, masks, objs, with_mask)
+
+
 @pytest.mark.parametrize("N,M", [(4, 8), (8, 16), (1, 4), (3, 4), (5, 8)])
 def test_fused_other_nm_runs_both_steps(N, M):
     for dt in ("f32", "bf16"):
