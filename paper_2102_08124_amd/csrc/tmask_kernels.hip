@@ -46,14 +46,14 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
         uint32_t bits[M];
         load_strip<DT, M>(md, pos, a, raw);
         if constexpr (SOLVER == kSolveApprox) {
-            approx_keep<DT, M>(a, args.K, gpos, bits);
+            approx_keep<DT, M, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
         } else if constexpr (SOLVER == kSolveRow1D) {
             // structured N:M along rows only: an entry is kept iff at least K entries of its group of M
             // precede it in the (magnitude, position) order
 #pragma unroll
             for (int i = 0; i < M; i++)
                 bits[i] = (1u << Ge::C) - 1u;
-            row_rank_keep<M, Ge::C, Ge::G, Ge::B>(a, args.K, gpos, bits);
+            row_rank_keep<M, Ge::C, Ge::G, Ge::B, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
         } else if constexpr (M == 4) {
             {
 #pragma unroll
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArg
         const bool tie = approx_half_f32<M>(a, gpos, rowbytes, acc);
         uint32_t bits[M];
         if (__any(tie)) {
-            approx_keep<kF32, M>(a, (uint32_t)(M / 2), gpos, bits);
+            approx_keep<kF32, M, (M >= 16 && FMT == kMaskBits)>(a, (uint32_t)(M / 2), gpos, bits);
             acc = kept_sum<M, 4>(a, bits);
             store_mask<kF32, M, FMT>(md, pos, bits);
         } else if constexpr (FMT == kMaskU8) {

@@ -49,7 +49,11 @@ __device__ __forceinline__ void rank_one(bool precedes, uint32_t &r)
 }
 
 // Column direction: all M rows of a column live in the lane.
-template <int M, int C>
+// PIN: merge every flag into its row's bits at once.  Wanted at M = 16 when the flags are stored as bit masks:
+// left alone the compiler carries all the compare results as lane masks to the place where the flags are
+// stored (hundreds of spilled scalar registers, one wavefront per SIMD).  With byte masks the freer schedule is
+// the faster one.
+template <int M, int C, bool PIN = false>
 __device__ __forceinline__ void col_rank_keep(const uint32_t (&a)[M][C], uint32_t K, uint32_t (&bits)[M])
 {
 #pragma unroll
@@ -68,14 +72,17 @@ __device__ __forceinline__ void col_rank_keep(const uint32_t (&a)[M][C], uint32_
                 rank_pair<M>(a[i][c] <= a[i2][c], r[i], r[i2]);   // row i precedes row i2
             }
 #pragma unroll
-        for (int i = 0; i < M; i++)
+        for (int i = 0; i < M; i++) {
             bits[i] |= (r[i] >= K ? 1u : 0u) << c;
+            if constexpr (PIN)
+                asm volatile("" : "+v"(bits[i]));
+        }
     }
 }
 
 // Row direction: a block-row is spread over G lanes (CL columns each); B blocks share a lane.
 // gpos = position of the lane inside its group of G.  bits[i] &= row-keep.
-template <int M, int C, int G, int B>
+template <int M, int C, int G, int B, bool PIN = false>
 __device__ __forceinline__ void row_rank_keep(const uint32_t (&a)[M][C], uint32_t K, uint32_t gpos,
                                               uint32_t (&bits)[M])
 {
@@ -125,16 +132,18 @@ __device__ __forceinline__ void row_rank_keep(const uint32_t (&a)[M][C], uint32_
                 keep |= (r[c] >= K ? 1u : 0u) << (b * CL + c);
         }
         bits[i] &= keep;
+        if constexpr (PIN)
+            asm volatile("" : "+v"(bits[i]));
     }
 }
 
-template <int DT, int M>
+template <int DT, int M, bool PIN = false>
 __device__ __forceinline__ void approx_keep(const uint32_t (&a)[M][Geo<DT, M>::C], uint32_t K, uint32_t gpos,
                                             uint32_t (&bits)[M])
 {
     using Ge = Geo<DT, M>;
-    col_rank_keep<M, Ge::C>(a, K, bits);
-    row_rank_keep<M, Ge::C, Ge::G, Ge::B>(a, K, gpos, bits);
+    col_rank_keep<M, Ge::C, PIN>(a, K, bits);
+    row_rank_keep<M, Ge::C, Ge::G, Ge::B, PIN>(a, K, gpos, bits);
 }
 
 // =================================================================================================
