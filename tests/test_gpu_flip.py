@@ -78,3 +78,17 @@ def test_flip_count_argument_errors():
     arr[0] = tm.tmask_flip_desc(a.data_ptr(), 16, a.data_ptr(), 16, 8, 16, flips.data_ptr() + 4)
     assert lib.tmask_flip_count(arr, 1, tm.TMASK_MASK_U8, None) == tm.TMASK_ERR_ALIGN
     torch.cuda.synchronize()
+
+
+def test_dynamic_masks_loop_runs_and_reports(capsys):
+    # the drifting-weights loop of the package at a small size: masks per step, flip counts, rates
+    import sys
+    from paper_2102_08124_amd import dynamic_masks
+    argv = sys.argv
+    sys.argv = ["dynamic_masks", "--side", "512", "--steps", "4"]
+    try:
+        dynamic_masks.main()
+    finally:
+        sys.argv = argv
+    out = capsys.readouterr().out
+    assert "flip fraction per step" in out and "weights/s" in out
