@@ -38,7 +38,8 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
     }
     const PackDev d = args.d[lo];
     const uint32_t tl = tile - d.tile0;
-    const uint32_t ty = tl / d.tiles_x, tx = tl - ty * d.tiles_x;
+    uint32_t ty, tx;
+    tile_coords(tl, d.tiles_x, (d.rows + TR - 1) / TR, kPackRunRows / TR, ty, tx);
     const uint32_t row0 = ty * TR, col0 = tx * TC;
     const uint32_t tid = threadIdx.x, l = tid & 63u;
     // the wavefront number as a scalar: row addresses below are then scalar too, and a lane adds only

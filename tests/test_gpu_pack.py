@@ -93,3 +93,17 @@ def test_pack48_bf16_multi_tile_and_degenerate_masks(fmt):
     for mask in masks:
         (got,) = run_pack([w], [mask], 4, 8, fmt)
         _same(got, oracle.apply_pack(w, mask, 4, 8))
+
+
+@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("bf16", 4, 8)])
+def test_pack_tile_order_bands_and_runs(dt, N, M):
+    # 4352 x 2304: nine tile columns (one group of eight bands plus a ninth band) and more tile rows than one
+    # vertical run of 4096 rows, so every branch of the tile numbering is taken; the fused call shares it
+    w = _w(dt, 4352, 2304, seed=4600 + M)
+    mask = oracle.approx(w, N, M)[0]
+    want = oracle.apply_pack(w, mask, N, M)
+    (got,) = run_pack([w], [mask], N, M)
+    _same(got, want)
+    from tests.gpu_util import run_fused
+    got_f, _, _ = run_fused([w], N, M, with_mask=(M != 4), with_objective=False)
+    _same(got_f[0], want)
