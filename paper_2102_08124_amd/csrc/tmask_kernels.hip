@@ -801,7 +801,7 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
         const uint32_t strips = dt == TMASK_F32 ? SF : SB;
         TC = strips * 16 / (uint32_t)elem_size((int)dt);
         TR = 4096 / strips;
-        lds_reserve = dt == TMASK_F32 ? kPack4LdsReserveF32 : 0;
+        lds_reserve = dt == TMASK_F32 ? kPack4LdsReservePackF32 : 0;
     }
     bool fast48 = (M == 8 && N == 4 && dt == TMASK_BF16);
     for (int i = 0; i < n && fast48; i++)
@@ -935,7 +935,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
         args.n = (uint32_t)nb; args.partial0 = partial0; args.partials = want_obj ? workspace : nullptr;
         {
             ProfileScope prof(stream, first + kMaxPackBatch >= n);
-            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), (fused24 && dt == TMASK_F32) ? kPack4LdsReserveF32 : 0, stream,
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), (fused24 && dt == TMASK_F32) ? kPack4LdsReserveFusedF32 : 0, stream,
                                args);
         }
         hipError_t e = hipGetLastError();

@@ -19,10 +19,13 @@
 namespace tmask {
 
 constexpr int kPack4Strips = 64;   // default tile width in strips of 16 bytes
-// Three resident tiles per compute unit run faster than four (117 against 123 us on 8192 x 8192 fp32: fewer
-// rows of the matrix are open at a time).  The fp32 kernels would fit four times, so their launches ask for
-// this much dynamic LDS on top, which nobody uses.
-constexpr unsigned kPack4LdsReserveF32 = 4096;
+// Fewer resident tiles per compute unit than would fit run faster at fp32 (a tile stays resident for about 20 us
+// with four of them, half of a short launch; fewer of them finish sooner and leave a shorter tail, and fewer rows of
+// the matrix are open at a time): two for pack24_kernel (41.1 against 42.4 us on the ResNet-50 set, 75 against 72 %
+// of the HBM peak on 8192 x 8192), three for the one-pass kernel (37.5 against 40.9 us with two).  The launches ask
+// for this much dynamic LDS on top, which nobody uses, so that no further workgroup fits.
+constexpr unsigned kPack4LdsReservePackF32 = 18432;
+constexpr unsigned kPack4LdsReserveFusedF32 = 4096;
 
 // r = lane-mask bit set ? a : b, as exactly one v_cndmask with the mask in a scalar register pair
 // (written as an instruction because the compiler otherwise turns chains of such selects into
