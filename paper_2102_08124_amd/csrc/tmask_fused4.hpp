@@ -20,10 +20,10 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
 {
     using PG = Pack4Geo<DT, S>;
     constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, OTD = PG::OTD, TCP = PG::TCP,
-                  IDXB = PG::IDXB, NQ = PG::NQ, LPR = PG::LPR;
+                  IDXB = PG::IDXB, IDXTB = PG::IDXTB, LPR = PG::LPR;
 
     __shared__ __attribute__((aligned(16))) uint32_t OT[OTD][TCP];      // [position down the column][column]
-    __shared__ __attribute__((aligned(16))) uint16_t IDXT[NQ][TC];
+    __shared__ __attribute__((aligned(16))) uint8_t IDXT[IDXTB][TC];
     __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
     __shared__ double red[kThreads / 64];
 
@@ -243,14 +243,22 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
             for (int c = 0; c < C; c++)
                 tnib[c] &= keepmask;
         }
-        if constexpr (C == 4) {
-            u32x2 v;
-            v.x = tnib[0] | (tnib[1] << 16);
-            v.y = tnib[2] | (tnib[3] << 16);
-            *(u32x2 *)&IDXT[q4][tcol] = v;
-        } else {
-            *(u32x4 *)&IDXT[q4][tcol] = u32x4{tnib[0] | (tnib[1] << 16), tnib[2] | (tnib[3] << 16),
-                                              tnib[4] | (tnib[5] << 16), tnib[6] | (tnib[7] << 16)};
+        // a lane's four nibbles per column are two bytes: two rows of C bytes each
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            uint32_t b[C / 4];
+#pragma unroll
+            for (int h = 0; h < C / 4; h++)
+                b[h] = ((tnib[4 * h] >> (8 * t)) & 0xFFu) | (((tnib[4 * h + 1] >> (8 * t)) & 0xFFu) << 8) |
+                       (((tnib[4 * h + 2] >> (8 * t)) & 0xFFu) << 16) | (((tnib[4 * h + 3] >> (8 * t)) & 0xFFu) << 24);
+            if constexpr (C == 4) {
+                *(uint32_t *)&IDXT[2 * q4 + t][tcol] = b[0];
+            } else {
+                u32x2 v;
+                v.x = b[0];
+                v.y = b[1];
+                *(u32x2 *)&IDXT[2 * q4 + t][tcol] = v;
+            }
         }
     };
     if (row0 + TR <= d.rows && col0 + TC <= d.cols)

@@ -73,31 +73,31 @@ __device__ __forceinline__ lanemask_t keep_flag(uint32_t m0, uint32_t m1, int c)
 // covers 64 / S block-rows per step (lane l: strip l % S, sub-row l / S) and takes four steps, so a tile
 // has 4096 / S rows: 64 KiB of W whatever S is.  A narrower, taller tile makes the runs written per
 // column of W^T longer at the price of shorter runs per row of W.
-template <int DT, int S = kPack4Strips, int NW = 4>
+template <int DT, int S = kPack4Strips, int NW = 4, int QN = 4>
 struct Pack4Geo {
     static constexpr int ES = (DT == kF32) ? 4 : 2;
     static constexpr int C = 16 / ES;                  // columns per strip
     static constexpr int NG = C / 4;                   // groups per strip row
     static constexpr int LPR = 64 / S;                 // block-rows a wavefront touches per step
     static constexpr int NT = 64 * NW;                 // threads per workgroup
-    static constexpr int TS = S, TR = 16 * LPR * NW, TC = TS * C;
+    static constexpr int TS = S, TR = 4 * QN * LPR * NW, TC = TS * C;   // QN = block-rows a lane works through
     static constexpr int VPB = (DT == kF32) ? 2 : 1;   // dwords per column and block-row for W^T
     static constexpr int OTD = (TR / 4) * VPB;         // data dwords per column in the tile
     static constexpr int TCP = TC + 4;                 // pitch of the staging rows (keeps 16-byte alignment, and
                                                        // spreads the copy-out's strided reads over the banks)
     static constexpr int IDXB = TS * NG / 2;           // index bytes per tile row
-    static constexpr int NQ = NW * LPR;                // runs of four block-rows per tile (one uint16 of nibbles each)
+    static constexpr int IDXTB = TR / 8;               // index bytes per tile column (a nibble per block-row)
 };
 
 // Streams a finished tile out of LDS: OT = W^T values per column, IDXT = W^T position nibbles per
 // column, IDX = W position nibbles per row.  Call after a barrier; all threads take part.
-template <int DT, int S = kPack4Strips, int NW = 4>
+template <int DT, int S = kPack4Strips, int NW = 4, int QN = 4>
 __device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0, uint32_t col0,
-                                                const uint32_t (*OT)[Pack4Geo<DT, S, NW>::TCP],
-                                                const uint16_t (*IDXT)[Pack4Geo<DT, S, NW>::TC],
-                                                const uint8_t (*IDX)[Pack4Geo<DT, S, NW>::IDXB])
+                                                const uint32_t (*OT)[Pack4Geo<DT, S, NW, QN>::TCP],
+                                                const uint8_t (*IDXT)[Pack4Geo<DT, S, NW, QN>::TC],
+                                                const uint8_t (*IDX)[Pack4Geo<DT, S, NW, QN>::IDXB])
 {
-    using PG = Pack4Geo<DT, S, NW>;
+    using PG = Pack4Geo<DT, S, NW, QN>;
     constexpr uint32_t kNT = PG::NT;
     constexpr int ES = PG::ES, TR = PG::TR, TC = PG::TC, OTD = PG::OTD;
     const uint32_t tid = threadIdx.x;
@@ -152,30 +152,33 @@ __device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0,
             for (uint32_t j = tid; j < cols_valid * P; j += kNT) {
                 const uint32_t cc = j / P, x = j % P;
                 u32x2 v;
-                v.x = (uint32_t)IDXT[4 * x][cc] | ((uint32_t)IDXT[4 * x + 1][cc] << 16);
-                v.y = (uint32_t)IDXT[4 * x + 2][cc] | ((uint32_t)IDXT[4 * x + 3][cc] << 16);
+                v.x = (uint32_t)IDXT[8 * x][cc] | ((uint32_t)IDXT[8 * x + 1][cc] << 8) |
+                      ((uint32_t)IDXT[8 * x + 2][cc] << 16) | ((uint32_t)IDXT[8 * x + 3][cc] << 24);
+                v.y = (uint32_t)IDXT[8 * x + 4][cc] | ((uint32_t)IDXT[8 * x + 5][cc] << 8) |
+                      ((uint32_t)IDXT[8 * x + 6][cc] << 16) | ((uint32_t)IDXT[8 * x + 7][cc] << 24);
                 *(u32x2 *)(dst + (size_t)cc * pitch + 8 * x) = v;
             }
         } else {
             for (uint32_t j = tid; j < cols_valid * nb; j += kNT) {
                 const uint32_t cc = j / nb, x = j - cc * nb;
-                dst[(size_t)cc * pitch + x] = (unsigned char)(IDXT[x >> 1][cc] >> (8 * (x & 1)));
+                dst[(size_t)cc * pitch + x] = IDXT[x][cc];
             }
         }
     }
 }
 
-template <int DT, int FMT, int S, int NW>
+template <int DT, int FMT, int S, int NW, int QN>
 __global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
 {
-    using PG = Pack4Geo<DT, S, NW>;
+    static_assert(QN == 2 || QN == 4, "a lane works through two or four block-rows");
+    using PG = Pack4Geo<DT, S, NW, QN>;
     constexpr int ES = PG::ES, C = PG::C, NG = PG::NG, TR = PG::TR, TC = PG::TC, OTD = PG::OTD,
-                  TCP = PG::TCP, IDXB = PG::IDXB, LPR = PG::LPR, NQ = PG::NQ;
+                  TCP = PG::TCP, IDXB = PG::IDXB, LPR = PG::LPR, IDXTB = PG::IDXTB;
 
     // Staging for W^T, indexed [position down the column][column]: a lane's columns are neighbours, so it
     // writes whole 16-byte pieces and the lanes of a wavefront write one contiguous run.
     __shared__ __attribute__((aligned(16))) uint32_t OT[OTD][TCP];
-    __shared__ __attribute__((aligned(16))) uint16_t IDXT[NQ][TC];
+    __shared__ __attribute__((aligned(16))) uint8_t IDXT[IDXTB][TC];
     __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
 
     const uint32_t tile = blockIdx.x;
@@ -203,9 +206,10 @@ __global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
     const bool strip_ok = col < d.cols;
     const size_t pitchW = (size_t)(d.cols / 4) * 2;    // elements per row of vals
     // byte offsets of the lane against row 16 * LPR * w of the tile, column col0
-    const size_t lane_w = (size_t)sub * 16u * d.ld * ES + strip * 16u;
-    const size_t lane_m = (size_t)sub * 16u * d.mask_ld;
-    const size_t lane_v = (size_t)sub * 16u * pitchW * ES + strip * 8u;
+    constexpr uint32_t RUN = 4u * QN;                   // rows of a lane's run of block-rows
+    const size_t lane_w = (size_t)sub * RUN * d.ld * ES + strip * 16u;
+    const size_t lane_m = (size_t)sub * RUN * d.mask_ld;
+    const size_t lane_v = (size_t)sub * RUN * pitchW * ES + strip * 8u;
 
     // Tiles that lie wholly inside the matrix take a copy of the code without any bounds test: no branch
     // splits the loop, so the waits on the prefetched rows are exact.
@@ -222,8 +226,8 @@ __global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
         u32x4 rawb[DEPTH][4];
         uint32_t m0b[DEPTH][4], m1b[DEPTH][4];   // the rows' mask entries: U8 bytes as dwords, or BITS in m0
         auto issue = [&](int q, u32x4 (&raw)[4], uint32_t (&m0)[4], uint32_t (&m1)[4]) {
-            const uint32_t wrow = row0 + 16u * LPR * w + 4u * (uint32_t)q;    // scalar: the row of sub-row 0
-            const uint32_t row = wrow + 16u * sub;
+            const uint32_t wrow = row0 + RUN * LPR * w + 4u * (uint32_t)q;    // scalar: the row of sub-row 0
+            const uint32_t row = wrow + RUN * sub;
 #pragma unroll
             for (int i = 0; i < 4; i++) {
                 raw[i] = u32x4{0u, 0u, 0u, 0u};
@@ -256,12 +260,12 @@ __global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
             issue(q, rawb[q], m0b[q], m1b[q]);
 
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-            const uint32_t brl = 4 * q4 + q;                       // block-row inside the tile
-            const uint32_t wrow = row0 + 16u * LPR * w + 4u * (uint32_t)q;
-            const uint32_t row = wrow + 16u * sub;
+        for (int q = 0; q < QN; q++) {
+            const uint32_t brl = QN * q4 + q;                      // block-row inside the tile
+            const uint32_t wrow = row0 + RUN * LPR * w + 4u * (uint32_t)q;
+            const uint32_t row = wrow + RUN * sub;
             const bool ok = !EDGE || (strip_ok && row < d.rows);
-            if (q + DEPTH - 1 < 4)
+            if (q + DEPTH - 1 < QN)
                 issue(q + DEPTH - 1, rawb[(q + DEPTH - 1) % DEPTH], m0b[(q + DEPTH - 1) % DEPTH], m1b[(q + DEPTH - 1) % DEPTH]);
             __builtin_amdgcn_sched_barrier(0);
             u32x4(&raw)[4] = rawb[q % DEPTH];
@@ -357,21 +361,29 @@ __global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
         if (EDGE) {
             // strips and block-rows outside the matrix must not leave position bits
             const uint32_t brs_in = (d.rows - row0) / 4;           // block-rows of the tile inside the matrix
-            const uint32_t mine = brs_in > 4 * q4 ? brs_in - 4 * q4 : 0;
-            const uint32_t keepmask = !strip_ok ? 0u : mine >= 4 ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
+            const uint32_t mine = brs_in > QN * q4 ? brs_in - QN * q4 : 0;
+            const uint32_t keepmask = !strip_ok ? 0u : mine >= (uint32_t)QN ? 0xFFFFu : ((1u << (4 * mine)) - 1u);
 #pragma unroll
             for (int c = 0; c < C; c++)
                 tnib[c] &= keepmask;
         }
-        // the lane's columns are neighbours here too: one 8-byte (fp32) or 16-byte (bf16) piece
-        if constexpr (C == 4) {
-            u32x2 v;
-            v.x = tnib[0] | (tnib[1] << 16);
-            v.y = tnib[2] | (tnib[3] << 16);
-            *(u32x2 *)&IDXT[q4][tcol] = v;
-        } else {
-            *(u32x4 *)&IDXT[q4][tcol] = u32x4{tnib[0] | (tnib[1] << 16), tnib[2] | (tnib[3] << 16),
-                                              tnib[4] | (tnib[5] << 16), tnib[6] | (tnib[7] << 16)};
+        // the lane's columns are neighbours here too: its QN nibbles per column are QN / 2 bytes, written as
+        // QN / 2 rows of C bytes
+#pragma unroll
+        for (int t = 0; t < QN / 2; t++) {
+            uint32_t b[C / 4];
+#pragma unroll
+            for (int h = 0; h < C / 4; h++)
+                b[h] = ((tnib[4 * h] >> (8 * t)) & 0xFFu) | (((tnib[4 * h + 1] >> (8 * t)) & 0xFFu) << 8) |
+                       (((tnib[4 * h + 2] >> (8 * t)) & 0xFFu) << 16) | (((tnib[4 * h + 3] >> (8 * t)) & 0xFFu) << 24);
+            if constexpr (C == 4) {
+                *(uint32_t *)&IDXT[(QN / 2) * q4 + t][tcol] = b[0];
+            } else {
+                u32x2 v;
+                v.x = b[0];
+                v.y = b[1];
+                *(u32x2 *)&IDXT[(QN / 2) * q4 + t][tcol] = v;
+            }
         }
     };
     if (row0 + TR <= d.rows && col0 + TC <= d.cols)
@@ -380,7 +392,7 @@ __global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
         compute(std::true_type{});
     __syncthreads();
 
-    pack24_copy_out<DT, S, NW>(d, row0, col0, OT, IDXT, IDX);
+    pack24_copy_out<DT, S, NW, QN>(d, row0, col0, OT, IDXT, IDX);
 }
 
 }  // namespace tmask
