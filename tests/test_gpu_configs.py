@@ -130,6 +130,16 @@ def test_config3_bert_large_bf16():
                 assert np.array_equal(g.view(torch.uint8).cpu().numpy().reshape(-1),
                                       t.view(np.uint8).reshape(-1)), "pack %d:%d matrix %d" % (N, M, k)
         del emasks, packed
+        # the one-pass call on the same three shapes: Algorithm 1's mask, compressed
+        fpacked = [tm.alloc_packed(ws[k], N, M) for k in sel]
+        tm.tmask_approx_pack([ws[k] for k in sel], None, fpacked, N, M)
+        torch.cuda.synchronize()
+        for pk, k in zip(fpacked, sel):
+            want = oracle.apply_pack(mats[k], oracle.approx(mats[k], N, M, threads=THREADS)[0], N, M)
+            for g, t in zip(pk, want):
+                assert np.array_equal(g.view(torch.uint8).cpu().numpy().reshape(-1),
+                                      t.view(np.uint8).reshape(-1)), "approx_pack %d:%d matrix %d" % (N, M, k)
+        del fpacked
     say("config3: done (%.1fs)" % (time.time() - t0))
 
 
