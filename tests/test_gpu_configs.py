@@ -189,6 +189,11 @@ def test_config5_dynamic_mask_loop():
             say("config5: step %d bit-exact (%.1fs)" % (step, time.time() - t0))
         if step:
             flips.append(float((cur != masks[(step - 1) % 2]).sum().item()) / (side * side))
+            if step in (1, 199):       # the library's own counter against the count above
+                cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+                tm.tmask_flip_count([cur], [masks[(step - 1) % 2]], [side], cnt)
+                torch.cuda.synchronize()
+                assert int(cnt[0]) == round(flips[-1] * side * side), "flip count at step %d" % step
         noise = torch.randn((side, side), generator=gen, device="cuda", dtype=torch.float32) * 0.02e-3
         w = (w.float() + noise).to(torch.bfloat16)
         del noise
