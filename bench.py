@@ -27,7 +27,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 N_KEEP, M_BLOCK = 2, 4
 # main kernel behind each call on this workload (names as rocprofv3 lists them)
-KERNEL_NAMES = {"approx": "approx24_kernel<0, 0>", "exact": "exact24_kernel<0, 0>", "pack": "pack24_kernel<0, 0, 64, 4>",
+KERNEL_NAMES = {"approx": "approx24_kernel<0, 0>", "exact": "exact24_kernel<0, 0>", "pack": "pack24_kernel<0, 0, 64, 4, 4>",
                 "score": "score_kernel<0, 4, 0>"}
 
 
