@@ -81,30 +81,32 @@ def cpu_baseline(mats_np, min_s: float = 10.0, budget_s: float = 30.0):
                       "(the workload has %d), %.1f s" % (weights, total, dt)}
 
 
-def largest_config_approx(tm, torch, ev, reps: int):
-    """Approximation alone on the largest configuration (16384^2 bf16, 2:4): kernel time and HBM fraction."""
+def largest_config_approx(tm, torch, ev, reps: int, bit_masks: bool = False):
+    """Approximation alone on the largest configuration (16384^2 bf16, 2:4): kernel time and HBM fraction,
+    with the mask written as bytes (as in the step above) or as bits."""
     side = 16384
+    fmt = tm.TMASK_MASK_BITS if bit_masks else tm.TMASK_MASK_U8
     gen = torch.Generator(device="cuda").manual_seed(5)
     sets = []
     for _ in range(2):
         w = (torch.randn((side, side), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
-        mask = torch.empty((side, side), dtype=torch.uint8, device="cuda")
+        mask = tm.alloc_masks([w], fmt)[0]
         obj = torch.zeros(1, dtype=torch.float64, device="cuda")
         sets.append(tm.MatBatch([w], [mask], obj))
     wsp = tm.alloc_workspace(sets[0].ws, N_KEEP, M_BLOCK)
     evs = [(ev.create(), ev.create()) for _ in range(reps)]
     for b in sets:
-        tm.tmask_approx(b, None, N_KEEP, M_BLOCK, workspace=wsp)
+        tm.tmask_approx(b, None, N_KEEP, M_BLOCK, mask_fmt=fmt, workspace=wsp)
     torch.cuda.synchronize()
     for k in range(reps):
         tm.tmask_profile_next(*evs[k])
-        tm.tmask_approx(sets[k % 2], None, N_KEEP, M_BLOCK, workspace=wsp)
+        tm.tmask_approx(sets[k % 2], None, N_KEEP, M_BLOCK, mask_fmt=fmt, workspace=wsp)
     torch.cuda.synchronize()
     ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
     weights = side * side
-    byts = weights * 3 + 8
-    return {"workload": "16384x16384 bf16 N(0,0.02), 2:4, tmask_approx, U8 mask", "kernel_ms": ms,
-            "weights_per_s": weights / (ms * 1e-3), "achieved_GBs": byts / (ms * 1e-3) / 1e9,
+    byts = weights * 2 + (weights // 8 if bit_masks else weights) + 8
+    return {"workload": "16384x16384 bf16 N(0,0.02), 2:4, tmask_approx, %s mask" % ("bit" if bit_masks else "U8"),
+            "kernel_ms": ms, "weights_per_s": weights / (ms * 1e-3), "achieved_GBs": byts / (ms * 1e-3) / 1e9,
             "frac_of_hbm_peak": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
@@ -351,6 +353,7 @@ def main():
         del src, dst
     if not args.no_largest:
         result["largest_config"] = largest_config_approx(tm, torch, ev, reps=20)
+        result["largest_config_bit_masks"] = largest_config_approx(tm, torch, ev, reps=20, bit_masks=True)
     del sets
     result["fused_approx_pack"] = fused_approx_pack(tm, torch, ev, mats_np, copies=min(args.copies, 6), reps=24)
     result["spmm24"] = spmm24_products(tm, torch, ev)
