@@ -107,3 +107,25 @@ def test_pack_tile_order_bands_and_runs(dt, N, M):
     from tests.gpu_util import run_fused
     got_f, _, _ = run_fused([w], N, M, with_mask=(M != 4), with_objective=False)
     _same(got_f[0], want)
+
+
+@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("bf16", 4, 8)])
+def test_pack_and_one_pass_random_shapes(dt, N, M):
+    # a batch of matrices with random (seeded) shapes, from a single block to several tiles either way, with row
+    # strides wider than the rows; apply_pack with unstructured masks, the one-pass call against the oracle's pair
+    rng = np.random.default_rng(4700 + M)
+    step = 8 if dt == "bf16" else 4                    # 16-byte rows
+    step = max(step, M)
+    shapes = [(int(rng.integers(1, 40)) * M, int(rng.integers(1, 150)) * step) for _ in range(10)]
+    shapes += [(M, step), (M * 33, step), (M, step * 130)]
+    ws = [_w(dt, r, c, seed=4710 + k) for k, (r, c) in enumerate(shapes)]
+    masks = [(rng.random(w.shape) < 0.5).astype(np.uint8) for w in ws]
+    got = run_pack(ws, masks, N, M, ld_pad=40)
+    for k, w in enumerate(ws):
+        _same(got[k], oracle.apply_pack(w, masks[k], N, M))
+    from tests.gpu_util import run_fused
+    got_f, gmasks, _ = run_fused(ws, N, M, ld_pad=40)
+    for k, w in enumerate(ws):
+        om = oracle.approx(w, N, M)[0]
+        assert np.array_equal(gmasks[k] != 0, om != 0), k
+        _same(got_f[k], oracle.apply_pack(w, om, N, M))
