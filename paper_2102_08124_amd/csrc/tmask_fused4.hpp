@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
     __shared__ __attribute__((aligned(16))) uint32_t OT[OTD][TCP];      // [position down the column][column]
     __shared__ __attribute__((aligned(16))) uint8_t IDXT[IDXTB][TC];
     __shared__ __attribute__((aligned(16))) uint8_t IDX[TR][IDXB];
-    __shared__ double red[kThreads / 64];
+    // the four doubles of the objective's workgroup sum reuse the first bytes of IDX once the tile is written out
 
     const uint32_t tile = blockIdx.x;
     int lo = 0, hi = (int)args.n - 1;
@@ -169,10 +169,10 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if constexpr (DT == kF32) {
-                    *(u32x4 *)&OT[brl * 2][tcol] = u32x4{t0[0], t0[1], t0[2], t0[3]};
-                    *(u32x4 *)&OT[brl * 2 + 1][tcol] = u32x4{t1[0], t1[1], t1[2], t1[3]};
+                    *(u32x4 *)&OT[brl * 2][ot_col(brl * 2, tcol)] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl * 2 + 1][ot_col(brl * 2 + 1, tcol)] = u32x4{t1[0], t1[1], t1[2], t1[3]};
                 } else {
-                    *(u32x4 *)&OT[brl][tcol + 4 * g] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl][ot_col(brl, tcol + 4 * g)] = u32x4{t0[0], t0[1], t0[2], t0[3]};
                 }
             }
             if (EDGE && !ok) {
@@ -268,6 +268,8 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
     __syncthreads();
     pack24_copy_out<DT, S>(d, row0, col0, OT, IDXT, IDX);
     if (args.partials) {
+        __syncthreads();                                   // every wavefront is done reading IDX
+        double *red = (double *)&IDX[0][0];
         const double t = block_sum_f32(acc, red);
         if (threadIdx.x == 0)
             ((double *)args.partials)[args.partial0 + tile] = t;

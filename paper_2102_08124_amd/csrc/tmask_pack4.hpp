@@ -25,7 +25,7 @@ constexpr int kPack4Strips = 64;   // default tile width in strips of 16 bytes
 // of the HBM peak on 8192 x 8192), three for the one-pass kernel (37.5 against 40.9 us with two).  The launches ask
 // for this much dynamic LDS on top, which nobody uses, so that no further workgroup fits.
 constexpr unsigned kPack4LdsReservePackF32 = 18432;
-constexpr unsigned kPack4LdsReserveFusedF32 = 4096;
+constexpr unsigned kPack4LdsReserveFusedF32 = 8192;
 
 // r = lane-mask bit set ? a : b, as exactly one v_cndmask with the mask in a scalar register pair
 // (written as an instruction because the compiler otherwise turns chains of such selects into
@@ -83,11 +83,16 @@ struct Pack4Geo {
     static constexpr int TS = S, TR = 4 * QN * LPR * NW, TC = TS * C;   // QN = block-rows a lane works through
     static constexpr int VPB = (DT == kF32) ? 2 : 1;   // dwords per column and block-row for W^T
     static constexpr int OTD = (TR / 4) * VPB;         // data dwords per column in the tile
-    static constexpr int TCP = TC + 4;                 // pitch of the staging rows (keeps 16-byte alignment, and
-                                                       // spreads the copy-out's strided reads over the banks)
+    static constexpr int TCP = TC;                     // pitch of the staging rows: no padding, see ot_col
     static constexpr int IDXB = TS * NG / 2;           // index bytes per tile row
     static constexpr int IDXTB = TR / 8;               // index bytes per tile column (a nibble per block-row)
 };
+
+// Where column `col` of staging row `r` lives: the rows are a whole number of bank cycles long, so the copy-out,
+// which reads four consecutive rows of one column per lane, would meet one bank over and over; the column is
+// therefore exchanged in units of four (16-byte pieces stay whole) with a pattern that changes every four rows.
+// (Padding the rows instead would cost 512 bytes, exactly what keeps a fourth bf16 workgroup off a compute unit.)
+__device__ __forceinline__ uint32_t ot_col(uint32_t r, uint32_t col) { return col ^ (((r >> 2) & 7u) << 2); }
 
 // Streams a finished tile out of LDS: OT = W^T values per column, IDXT = W^T position nibbles per
 // column, IDX = W position nibbles per row.  Call after a barrier; all threads take part.
@@ -113,14 +118,15 @@ __device__ __forceinline__ void pack24_copy_out(const PackDev &d, uint32_t row0,
             constexpr int CH = OTD / 4;   // 16-byte chunks per column
             for (uint32_t j = tid; j < cols_valid * CH; j += kNT) {
                 const uint32_t cc = j / CH, part = j % CH;
-                const u32x4 v = {OT[4 * part][cc], OT[4 * part + 1][cc], OT[4 * part + 2][cc], OT[4 * part + 3][cc]};
+                const uint32_t sc = ot_col(4 * part, cc);          // the same for the four rows 4 part .. 4 part + 3
+                const u32x4 v = {OT[4 * part][sc], OT[4 * part + 1][sc], OT[4 * part + 2][sc], OT[4 * part + 3][sc]};
                 stream_store(v, (u32x4 *)(dst + (size_t)cc * pitch_b + 16 * part));
             }
         } else {
             const uint32_t rd = brs_valid * 2 * ES / 4;   // dwords per column
             for (uint32_t j = tid; j < cols_valid * rd; j += kNT) {
                 const uint32_t cc = j / rd, x = j - cc * rd;
-                *(uint32_t *)(dst + (size_t)cc * pitch_b + 4 * x) = OT[x][cc];
+                *(uint32_t *)(dst + (size_t)cc * pitch_b + 4 * x) = OT[x][ot_col(x, cc)];
             }
         }
     }
@@ -327,10 +333,10 @@ __global__ __launch_bounds__(64 * NW) void pack24_kernel(const PackArgs args)
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if constexpr (DT == kF32) {
-                    *(u32x4 *)&OT[brl * 2][tcol] = u32x4{t0[0], t0[1], t0[2], t0[3]};
-                    *(u32x4 *)&OT[brl * 2 + 1][tcol] = u32x4{t1[0], t1[1], t1[2], t1[3]};
+                    *(u32x4 *)&OT[brl * 2][ot_col(brl * 2, tcol)] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl * 2 + 1][ot_col(brl * 2 + 1, tcol)] = u32x4{t1[0], t1[1], t1[2], t1[3]};
                 } else {
-                    *(u32x4 *)&OT[brl][tcol + 4 * g] = u32x4{t0[0], t0[1], t0[2], t0[3]};
+                    *(u32x4 *)&OT[brl][ot_col(brl, tcol + 4 * g)] = u32x4{t0[0], t0[1], t0[2], t0[3]};
                 }
             }
             if (!ok) {
