@@ -1,12 +1,13 @@
 // tmask_exact for N = M/2, M = 8 or 16: the augmenting-path solver of tmask_solvers.hpp behind a
 // load-balancing stage.
 //
-// The solver needs one augmentation per unit of row excess left by its start (every column prunes its
-// K lightest rows), and lanes of a wavefront run in lockstep: a wavefront takes as long as its worst
-// block while the others idle (measured: about 40 % of the lanes active).  The start's excess is cheap
-// to predict, so each workgroup first sorts its blocks by predicted excess (stable counting sort,
-// deterministic), exchanges the raw rows through LDS, and every wavefront then solves blocks that need
-// about the same number of augmentations.  Results go back to each block's own place.
+// The solver needs one augmentation per unit of row excess left by its start, and lanes of a wavefront
+// run in lockstep: a wavefront takes as long as its worst block while the others idle (measured: about
+// 40 % of the lanes active).  So every lane first computes the start of the block it loaded (the price
+// rounds included: uniform work, every lane busy), each workgroup sorts its blocks by the excess that is
+// left (stable counting sort, deterministic), exchanges the raw rows and the start through LDS, and every
+// wavefront then runs the searches of blocks that need about the same number of augmentations.  Results
+// go back to each block's own place.
 #pragma once
 #include "tmask_device.hpp"
 #include "tmask_networks.hpp"
@@ -31,51 +32,20 @@ __device__ __forceinline__ void unpack_row(const u32x4 &r, uint32_t (&a)[16 / ((
     }
 }
 
-// Row excess of the "every column prunes its K = M/2 lightest rows" start, predicted on the magnitude
-// keys (low four bits replaced by the row index to break ties).  Same value in all lanes of a block.
-template <int M, int C, int G>
-__device__ __forceinline__ uint32_t predicted_excess(const uint32_t (&a)[M][C])
-{
-    constexpr int H = M / 2;
-    uint32_t cnt[M];
-#pragma unroll
-    for (int i = 0; i < M; i++)
-        cnt[i] = 0;
-#pragma unroll
-    for (int c = 0; c < C; c++) {
-        uint32_t lo[H], hi[H];
-#pragma unroll
-        for (int i = 0; i < H; i++) {
-            lo[i] = (a[i][c] & ~0xFu) | (uint32_t)i;
-            hi[i] = (a[H + i][c] & ~0xFu) | (uint32_t)(H + i);
-        }
-        const uint32_t t = upper_half_min<H>(lo, hi);
-#pragma unroll
-        for (int i = 0; i < M; i++)
-            cnt[i] += (((a[i][c] & ~0xFu) | (uint32_t)i) < t) ? 1u : 0u;
-    }
-    uint32_t e = 0;
-#pragma unroll
-    for (int i = 0; i < M; i++) {
-        uint32_t n = cnt[i];
-        if constexpr (G >= 2)
-            n += quad_xor<1>(n);
-        if constexpr (G == 4)
-            n += quad_xor<2>(n);
-        e += n > (uint32_t)H ? n - (uint32_t)H : 0u;
-    }
-    return e;
-}
-
+// Workgroups per compute unit: a bf16 lane holds eight columns of its block (an fp32 lane four), and at M = 8
+// that needs more than the 128 registers that four workgroups would leave it.
 template <int DT, int M, int FMT>
-__global__ __launch_bounds__(kThreads, (M == 8 ? 4 : 2)) void exact_balanced_kernel(const BatchArgs args)
+__global__ __launch_bounds__(kThreads, (M == 16 ? 2 : DT == kF32 ? 4 : 3)) void exact_balanced_kernel(const BatchArgs args)
 {
     using Ge = Geo<DT, M>;
     constexpr int C = Ge::C, G = Ge::G;
     constexpr int NB = kThreads / G;          // blocks per workgroup
     constexpr int NBUCKET = 16;
-    constexpr int RPR = M;                    // all rows of the block stay in LDS (M x 16 B x 256 lanes)
-    __shared__ __attribute__((aligned(16))) u32x4 xraw[kThreads][RPR];
+    constexpr int XPW = 32 / M;               // pruned-row sets (M bits per column) per exchanged word
+    constexpr int XW = C / XPW;
+    __shared__ __attribute__((aligned(16))) u32x4 xraw[kThreads][M];     // the raw rows of every block, at the loading lane's place
+    __shared__ uint32_t xstart[kThreads][XW];
+    __shared__ uint16_t ssrc[kThreads];
     __shared__ uint32_t sorig[NB];
     __shared__ uint32_t wcnt[kThreads / 64][NBUCKET];
     __shared__ double red[kThreads / 64];
@@ -116,15 +86,31 @@ __global__ __launch_bounds__(kThreads, (M == 8 ? 4 : 2)) void exact_balanced_ker
             raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
     }
 
-    // ---- predicted work, stable counting sort of the workgroup's blocks by it ----
-    uint32_t e;
+    // ---- the solver's start on the block this lane sits on (every lane busy), then a stable counting sort
+    //      of the workgroup's blocks by the row excess that start leaves: the number of augmentations to come ----
+    uint32_t e = 0;
     {
-        uint32_t a[M][C];
+        uint32_t a[M][C], xcol[C];
+        int cost[M][C];
 #pragma unroll
-        for (int i = 0; i < M; i++)
+        for (int i = 0; i < M; i++) {
             unpack_row<DT>(raw[i], a[i]);
-        e = predicted_excess<M, C, G>(a);
+            xraw[tid][i] = raw[i];      // parked in LDS for the lane that will run this block's searches
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                asm volatile("" : "+v"(a[i][c]));   // the raw rows end here
+        }
+        exact_costs<M, C, G>(a, cost);
+        e = exact_priced_start<M, C, G>(cost, xcol);
         e = e < (uint32_t)(NBUCKET - 1) ? e : (uint32_t)(NBUCKET - 1);
+#pragma unroll
+        for (int q = 0; q < XW; q++) {
+            uint32_t xp = 0;
+#pragma unroll
+            for (int c = 0; c < XPW; c++)
+                xp |= xcol[q * XPW + c] << (c * M);
+            xstart[tid][q] = xp;
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     const bool leader = gpos == 0;
@@ -148,25 +134,22 @@ __global__ __launch_bounds__(kThreads, (M == 8 ? 4 : 2)) void exact_balanced_ker
         rank = dpp_read<0xA0>(rank);   // quad_perm [0,0,2,2]
     if constexpr (G == 4)
         rank = dpp_read<0x00>(rank);   // quad_perm [0,0,0,0]
-    const uint32_t slot = rank * G + gpos;
+    ssrc[rank * G + gpos] = (uint16_t)tid;
     if (leader)
         sorig[rank] = valid ? s : 0xFFFFFFFFu;
+    __syncthreads();
 
-    // ---- exchange the raw rows: this lane continues with the block sorted into its position ----
-#pragma unroll
-    for (int round = 0; round < M / RPR; round++) {
-        if (round)
-            __syncthreads();
-#pragma unroll
-        for (int i = 0; i < RPR; i++)
-            xraw[slot][i] = raw[round * RPR + i];
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < RPR; i++)
-            raw[round * RPR + i] = xraw[tid][i];
-    }
+    // ---- this lane continues with the block sorted into its position: rows and start of the lane that loaded it ----
+    const uint32_t from = ssrc[tid];
     const uint32_t my_s = sorig[tid / G];
     const bool my_valid = my_s != 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < M; i++)
+        raw[i] = xraw[from][i];
+    uint32_t xpack[XW];
+#pragma unroll
+    for (int q = 0; q < XW; q++)
+        xpack[q] = xstart[from][q];
 
     // ---- solve ----
     __builtin_amdgcn_sched_barrier(0);
@@ -181,7 +164,16 @@ __global__ __launch_bounds__(kThreads, (M == 8 ? 4 : 2)) void exact_balanced_ker
             for (int c = 0; c < C; c++)
                 asm volatile("" : "+v"(a[i][c]));
         }
-        exact_general<M, C, G>(a, (uint32_t)(M / 2), gpos, xcol);
+        {
+            int cost[M][C];
+            uint32_t cnt[M];
+            exact_costs<M, C, G>(a, cost);
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                xcol[c] = (xpack[c / XPW] >> ((c % XPW) * M)) & ((1u << M) - 1u);
+            exact_counts<M, C, G>(xcol, cnt);
+            (void)exact_phases<M, C, G>(cost, (uint32_t)(M / 2), gpos, xcol, cnt, M * M);
+        }
 #pragma unroll
         for (int i = 0; i < M; i++) {
             bits[i] = 0;
@@ -196,7 +188,7 @@ __global__ __launch_bounds__(kThreads, (M == 8 ? 4 : 2)) void exact_balanced_ker
 #pragma unroll
             for (int i = 0; i < M; i++) {
                 uint32_t ar[C];
-                unpack_row<DT>(xraw[tid][i], ar);
+                unpack_row<DT>(xraw[from][i], ar);
 #pragma unroll
                 for (int c = 0; c < C; c++)
                     acc += ((bits[i] >> c) & 1u) ? __uint_as_float(ar[c]) : 0.f;

@@ -432,6 +432,101 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
     }
 }
 
+// Start for N = M/2 with row prices: column c prunes the K rows with the smallest cost + price (ties: lower
+// row first).  Whatever the prices, the result is the cheapest pruning for the row counts it has: the price
+// term of any pruning with those counts is the same sum over rows of price x count, so being cheapest under
+// cost + price means being cheapest under cost alone.  That is all the augmenting searches ask of their
+// start, so prices can even out the row counts before the first search: a row with too many pruned entries
+// becomes dearer to prune, one with too few cheaper, every column chooses again, in rounds with a step that
+// shrinks by a quarter each time (first step: largest cost / 32 .. / 16 at M = 8, half that at M = 16).
+// The prices of the round with the smallest total excess are kept; xcol is that round's choice and the
+// return value its excess.  On random blocks the searches that follow drop from 3.1 per block (no prices) to
+// 0.4 at M = 8 with eight rounds, and from 6.3 to 1.3 at M = 16 with twelve; a round costs about a third of
+// one sweep of a search and runs with every lane busy, where the searches keep 40-50 % of the lanes busy.
+//
+// Keys are (cost + price + 2^(S-1)) << 4 | row with |price| < 2^(S-1): below 2^(S+5) <= 2^32 for costs < 2^S.
+template <int M, int CL, int G>
+__device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL], uint32_t (&xcol)[CL])
+{
+    constexpr int K = M / 2, H = M / 2;
+    constexpr int S = exact_cost_bits(M);
+    constexpr int ROUNDS = (M == 16) ? 12 : 8;
+    constexpr int PMIN = 1, PMAX = (1 << S) - 1;                // price + 2^(S-1)
+    uint32_t ck[M][CL];
+    int price[M];
+    uint32_t pk[M], best_pk[M];                                 // (price + 2^(S-1)) << 4
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        price[i] = 1 << (S - 1);
+        pk[i] = (uint32_t)price[i] << 4;
+#pragma unroll
+        for (int c = 0; c < CL; c++)
+            ck[i][c] = ((uint32_t)cost[i][c] << 4) | (uint32_t)i;
+    }
+    // the column's threshold key under the prices p: the K pruned rows are the keys below it
+    auto threshold = [&](int c, const uint32_t (&p)[M], uint32_t (&k)[M]) {
+        uint32_t lo[H], hi[H];
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            k[i] = ck[i][c] + p[i];
+#pragma unroll
+        for (int i = 0; i < H; i++) {
+            lo[i] = k[i];
+            hi[i] = k[H + i];
+        }
+        return upper_half_min<H>(lo, hi);
+    };
+    int step = (M == 16) ? (1 << (S - 6)) : (1 << (S - 5));
+    uint32_t best = 0xFFFFFFFFu;
+#pragma unroll 1
+    for (int round = 0; round <= ROUNDS; round++) {
+        uint32_t n[M];
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            n[i] = 0;
+#pragma unroll
+        for (int c = 0; c < CL; c++) {
+            uint32_t k[M];
+            const uint32_t t = threshold(c, pk, k);
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                lm_inc(n[i], lm(k[i] < t));
+            if constexpr (CL > 4)
+                __builtin_amdgcn_sched_barrier(0);   // one column at a time: interleaving them costs M registers each
+        }
+        uint32_t e = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            if constexpr (G >= 2)
+                n[i] += quad_xor<1>(n[i]);
+            if constexpr (G == 4)
+                n[i] += quad_xor<2>(n[i]);
+            e += n[i] > (uint32_t)K ? n[i] - (uint32_t)K : 0u;
+        }
+        const bool better = e < best;
+        best = better ? e : best;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            best_pk[i] = better ? pk[i] : best_pk[i];
+            const int p = price[i] + step * ((int)n[i] - K);
+            price[i] = p > PMAX ? PMAX : p < PMIN ? PMIN : p;
+            pk[i] = (uint32_t)price[i] << 4;
+        }
+        step -= step >> 2;
+    }
+#pragma unroll
+    for (int c = 0; c < CL; c++) {
+        uint32_t k[M];
+        const uint32_t t = threshold(c, best_pk, k);
+        uint32_t x = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            x |= (k[i] < t ? 1u : 0u) << i;
+        xcol[c] = x;
+    }
+    return best;
+}
+
 // Up to max_phases searches, each followed by its augmentations; cnt is kept up to date.  Returns true when
 // every row has exactly K pruned entries (always after at most M*M searches).
 template <int M, int CL, int G>
