@@ -438,10 +438,10 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
 // cost + price means being cheapest under cost alone.  That is all the augmenting searches ask of their
 // start, so prices can even out the row counts before the first search: a row with too many pruned entries
 // becomes dearer to prune, one with too few cheaper, every column chooses again, in rounds with a step that
-// shrinks by a quarter each time (first step: largest cost / 32 .. / 16 at M = 8, half that at M = 16).
+// shrinks to 11/16 each time (first step: 3/64 .. 3/32 of the largest cost at M = 8, half that at M = 16).
 // The prices of the round with the smallest total excess are kept; xcol is that round's choice and the
 // return value its excess.  On random blocks the searches that follow drop from 3.1 per block (no prices) to
-// 0.4 at M = 8 with eight rounds, and from 6.3 to 1.3 at M = 16 with twelve; a round costs about a third of
+// 0.2 at M = 8 with ten rounds, and from 6.3 to 0.5 at M = 16 with twelve; a round costs about a third of
 // one sweep of a search and runs with every lane busy, where the searches keep 40-50 % of the lanes busy.
 //
 // Keys are (cost + price + 2^(S-1)) << 4 | row with |price| < 2^(S-1): below 2^(S+5) <= 2^32 for costs < 2^S.
@@ -450,7 +450,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
 {
     constexpr int K = M / 2, H = M / 2;
     constexpr int S = exact_cost_bits(M);
-    constexpr int ROUNDS = (M == 16) ? 12 : 8;
+    constexpr int ROUNDS = (M == 16) ? 12 : 10;
     constexpr int PMIN = 1, PMAX = (1 << S) - 1;                // price + 2^(S-1)
     uint32_t ck[M][CL];
     int price[M];
@@ -476,7 +476,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
         }
         return upper_half_min<H>(lo, hi);
     };
-    int step = (M == 16) ? (1 << (S - 6)) : (1 << (S - 5));
+    int step = (M == 16) ? (3 << (S - 7)) : (3 << (S - 6));
     uint32_t best = 0xFFFFFFFFu;
 #pragma unroll 1
     for (int round = 0; round <= ROUNDS; round++) {
@@ -512,7 +512,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
             price[i] = p > PMAX ? PMAX : p < PMIN ? PMIN : p;
             pk[i] = (uint32_t)price[i] << 4;
         }
-        step -= step >> 2;
+        step = (step * 11) >> 4;
     }
 #pragma unroll
     for (int c = 0; c < CL; c++) {

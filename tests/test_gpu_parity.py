@@ -163,6 +163,43 @@ def test_exact_heavy_tailed_and_degenerate(N, M):
     _check_exact(w, mask, N, M, opb)
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("N,M", NM)
+def test_exact_structured_blocks(N, M, dt):
+    """Blocks on which "every column prunes its lightest rows" is as lopsided as it gets (whole rows lighter than
+    the others by factors up to 2^-40, products a_i * b_j, one dominant row or column, a checkerboard of two
+    values): the start under row prices must stay a valid start whatever it does to them."""
+    rng = np.random.default_rng(2500 + M)
+    rows, cols = 3 * M, 64 * M
+    w = rng.standard_normal((rows, cols)).astype(np.float32)
+    i = np.arange(rows)[:, None] % M
+    j = np.arange(cols)[None, :] % M
+    nb = cols // M
+    for b in range(nb):
+        c = slice(b * M, (b + 1) * M)
+        k = b % 8
+        if k == 0:
+            w[:, c] *= np.float32(2.0) ** (-(i * (1 + b % 5))).astype(np.float32)     # geometric row scales
+        elif k == 1:
+            w[:, c] = (1.0 + i) * (1.0 + j[:, c]) * np.float32(0.01)                   # rank one, many equal sums
+        elif k == 2:
+            w[:, c] *= np.where(i == b % M, np.float32(1e6), np.float32(1.0))          # one dominant row
+        elif k == 3:
+            w[:, c] *= np.where(j[:, c] == b % M, np.float32(1e6), np.float32(1.0))    # one dominant column
+        elif k == 4:
+            w[:, c] = np.where((i + j[:, c]) % 2 == 0, np.float32(3.0), np.float32(1.0))
+        elif k == 5:
+            w[:, c] *= np.float32(2.0) ** (-40.0 * (i >= M // 2)).astype(np.float32)    # half the rows negligible
+        elif k == 6:
+            w[:, c] = np.round(w[:, c] * 2.0) / 2.0                                     # few distinct values
+    if dt == "bf16":
+        w = wl.f32_to_bf16_bits(w)
+    (mask,), obj = run_masks(tm.tmask_exact, [w], N, M)
+    _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
+    _check_exact(w, mask, N, M, opb)
+    assert obj[0] == pytest.approx(oobj, rel=1e-5)
+
+
 def test_exact_non_finite_stays_valid():
     w = wl.special_values_f32(32, 256, seed=2300)
     for N, M in NM:
