@@ -135,13 +135,13 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
  * backward pass multiplies by W^T, so both W and W^T are compressed).  Outputs are exactly those of
  * tmask_approx followed by tmask_apply_pack with that mask: `vals`, `idx`, `valsT`, `idxT` in the
  * format above, `objective` (device, nullable) = sum S|W|, and the mask itself if `mask` is not
- * NULL.  For N:M = 2:4 (both types) and for bf16 4:8 this is a single pass over W in which the
+ * NULL.  For N:M = 2:4 and 4:8 (both types) this is a single pass over W in which the
  * mask never travels through memory (`mask` may be NULL for all matrices; give it for all or for
  * none, else TMASK_ERR_NULL).  For any other (type, N:M) the two steps run one after the other
  * and `mask` is required (TMASK_ERR_NULL without it).
  * A workspace is needed only if some `objective` is given.  The `w`, mask and packed-output layout
  * requirements are those of tmask_approx and tmask_apply_pack; for 2:4, `vals` and `valsT` must
- * be 8-byte aligned (TMASK_ERR_ALIGN); for bf16 4:8 outputs that are not 8-byte aligned take the
+ * be 8-byte aligned (TMASK_ERR_ALIGN); for 4:8 outputs that are not 8-byte aligned take the
  * two-step path (and then need `mask`).
  */
 typedef struct {

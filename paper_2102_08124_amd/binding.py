@@ -199,7 +199,7 @@ class PackBatch:
 
 class FusedBatch:
     """Host descriptor array for tmask_approx_pack, marshalled once (keeps the tensors alive).
-    masks: list of mask tensors, or None (2:4 and bf16 4:8 only: no mask is written).
+    masks: list of mask tensors, or None (2:4 and 4:8 only: no mask is written).
     objective: float64 device tensor with one entry per matrix, or None."""
 
     def __init__(self, ws, masks, packed, N: int, M: int, objective: Optional[torch.Tensor] = None):
@@ -319,7 +319,7 @@ def tmask_apply_pack(ws, masks, packed, N: int, M: int, mask_fmt: int = TMASK_MA
 
 def tmask_approx_pack(ws, masks, packed, N: int, M: int, objective: Optional[torch.Tensor] = None,
                       mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
-    """Algorithm 1 and the compression of W and W^T in one call; masks may be None for 2:4 and for bf16 4:8."""
+    """Algorithm 1 and the compression of W and W^T in one call; masks may be None for 2:4 and for 4:8."""
     b = ws if isinstance(ws, FusedBatch) else FusedBatch(ws, masks, packed, N, M, objective)
     wp, wb = _ws_args(workspace)
     _check(load_library().tmask_approx_pack(b.arr, b.n, b.dt, N, M, mask_fmt, wp, wb, _stream_ptr(stream)))

@@ -560,14 +560,17 @@ static int check_common(const void *mats, int n_mats, int dt, int N, int M, int 
 static size_t workspace_need(const tmask_mat *mats, int n_mats, int M)
 {
     // Upper bound over dtypes: fp32 strips (4 columns) are the narrower ones.
-    size_t tiles = 0;
+    size_t tiles = 0, pack_tiles = 0;
     for (int i = 0; i < n_mats; i++) {
         if (mats[i].rows <= 0 || mats[i].cols <= 0)
             return 0;
         const size_t strips = (size_t)((mats[i].rows + M - 1) / M) * (size_t)((mats[i].cols + 3) / 4);
         tiles += (strips + kThreads - 1) / kThreads;
+        // tmask_approx_pack keeps one fp64 partial per tile of its one-pass kernels (64 rows x 256 columns at least)
+        pack_tiles += (size_t)((mats[i].rows + 63) / 64) * (size_t)((mats[i].cols + 255) / 256);
     }
-    return tiles * sizeof(ScorePartial) + 256;
+    const size_t a = tiles * sizeof(ScorePartial), b = pack_tiles * sizeof(double);
+    return (a > b ? a : b) + 256;
 }
 
 static int check_workspace(const tmask_mat *mats, int n_mats, int M, void *ws, size_t ws_bytes)
@@ -816,6 +819,15 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
         TC = Pack8Geo::TC;
         TR = Pack8Geo::TR;
     }
+    bool fast48f = (M == 8 && N == 4 && dt == TMASK_F32);
+    for (int i = 0; i < n && fast48f; i++)
+        fast48f = (((uintptr_t)descs[i].vals | (uintptr_t)descs[i].valsT) & 7) == 0;
+    if (fast48f) {
+        kern = mf == TMASK_MASK_U8 ? pack48_f32_kernel<kMaskU8, kPack8F32Strips, false, false, PackArgs>
+                                   : pack48_f32_kernel<kMaskBits, kPack8F32Strips, false, false, PackArgs>;
+        TC = Pack8F32Geo<kPack8F32Strips>::TC;
+        TR = Pack8F32Geo<kPack8F32Strips>::TR;
+    }
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int first = 0; first < n; first += kMaxPackBatch) {
         const int nb = n - first < kMaxPackBatch ? n - first : kMaxPackBatch;
@@ -850,7 +862,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     if (rc)
         return rc;
     const bool fused24 = (M == 4 && N == 2);
-    bool fused48 = (M == 8 && N == 4 && dt == TMASK_BF16);     // needs 8-byte aligned outputs, else two steps
+    bool fused48 = (M == 8 && N == 4);                         // needs 8-byte aligned outputs, else two steps
     int with_mask = 0;
     bool want_obj = false;
     for (int i = 0; i < n; i++) {
@@ -890,8 +902,10 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     // tile shapes as in tmask_apply_pack
     constexpr int SF = 64, SB = 32;
     const uint32_t strips = dt == TMASK_F32 ? SF : SB;
-    const uint32_t TC = fused48 ? (uint32_t)Pack8Geo::TC : strips * 16 / (uint32_t)elem_size((int)dt);
-    const uint32_t kPack4Rows = fused48 ? (uint32_t)Pack8Geo::TR : 4096 / strips;
+    using G8F = Pack8F32Geo<kPack8F32Strips>;
+    const uint32_t TC = fused48 ? (dt == TMASK_F32 ? (uint32_t)G8F::TC : (uint32_t)Pack8Geo::TC)
+                                : strips * 16 / (uint32_t)elem_size((int)dt);
+    const uint32_t kPack4Rows = fused48 ? (dt == TMASK_F32 ? (uint32_t)G8F::TR : (uint32_t)Pack8Geo::TR) : 4096 / strips;
     if (want_obj) {
         size_t tiles = 0;
         for (int i = 0; i < n; i++)
@@ -908,7 +922,14 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
         kern = with_mask ? approx_pack24_kernel<DT, FM, true, SS> : approx_pack24_kernel<DT, FM, false, SS>;
     TMASK_PICK(kF32, kMaskU8, SF) TMASK_PICK(kF32, kMaskBits, SF) TMASK_PICK(kBF16, kMaskU8, SB) TMASK_PICK(kBF16, kMaskBits, SB)
 #undef TMASK_PICK
-    if (fused48) {
+    if (fused48 && dt == TMASK_F32) {
+        constexpr int S8 = kPack8F32Strips;
+        if (mf == TMASK_MASK_U8)
+            kern = with_mask ? pack48_f32_kernel<kMaskU8, S8, true, true, FusedArgs> : pack48_f32_kernel<kMaskU8, S8, true, false, FusedArgs>;
+        else
+            kern = with_mask ? pack48_f32_kernel<kMaskBits, S8, true, true, FusedArgs>
+                             : pack48_f32_kernel<kMaskBits, S8, true, false, FusedArgs>;
+    } else if (fused48) {
         if (mf == TMASK_MASK_U8)
             kern = with_mask ? pack48_bf16_kernel<kMaskU8, true, true, FusedArgs> : pack48_bf16_kernel<kMaskU8, true, false, FusedArgs>;
         else

@@ -73,17 +73,19 @@ def test_fused_batched_with_strides_and_no_objective(dt):
 
 @pytest.mark.parametrize("with_mask", [True, False])
 @pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
-def test_fused_4of8_bf16_one_pass(fmt, with_mask):
-    # bf16 4:8 has its own one-pass kernel (128 x 256 tiles): whole tiles, ragged edges, a single block, and a
-    # tie-heavy matrix with special values (the index tie-break decides many entries there)
-    ws = [_w("bf16", 392, 776, seed=5200), _w("bf16", 256, 512, seed=5201), _w("bf16", 8, 8, seed=5202),
-          wl.f32_to_bf16_bits(wl.tie_heavy_f32(136, 264, seed=5203)),
-          wl.f32_to_bf16_bits(wl.special_values_f32(64, 128, seed=5204))]
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_fused_4of8_one_pass(dt, fmt, with_mask):
+    # 4:8 has one-pass kernels of its own (bf16: 128 x 256 tiles, fp32: 64 x 256): whole tiles, ragged edges, a
+    # single block, and tie-heavy matrices with special values (the index tie-break decides many entries there;
+    # at fp32 a tie across a cut sends the whole wavefront through the rank form)
+    conv = (lambda w: wl.f32_to_bf16_bits(w)) if dt == "bf16" else (lambda w: w)
+    ws = [_w(dt, 392, 776, seed=5200), _w(dt, 256, 512, seed=5201), _w(dt, 8, 8, seed=5202),
+          conv(wl.tie_heavy_f32(136, 264, seed=5203)), conv(wl.special_values_f32(64, 128, seed=5204))]
     got, masks, objs = run_fused(ws, 4, 8, fmt, with_mask=with_mask, ld_pad=24)
     _check(ws, 4, 8, got, masks, objs, with_mask)
 
 
-@pytest.mark.parametrize("N,M", [(4, 8), (8, 16), (1, 4), (3, 4), (5, 8)])
+@pytest.mark.parametrize("N,M", [(8, 16), (1, 4), (3, 4), (5, 8)])
 def test_fused_other_nm_runs_both_steps(N, M):
     for dt in ("f32", "bf16"):
         ws = [_w(dt, 5 * M, 272, seed=5300 + N), _w(dt, 8 * M, 1008, seed=5301 + N)]
@@ -120,7 +122,7 @@ def test_fused_argument_errors():
     # other N:M without mask buffers
     w8 = to_dev(_w("f32", 16, 16, seed=5402))
     with pytest.raises(tm.TmaskError) as e:
-        tm.tmask_approx_pack([w8], None, [tm.alloc_packed(w8, 4, 8)], 4, 8)
+        tm.tmask_approx_pack([w8], None, [tm.alloc_packed(w8, 8, 16)], 8, 16)
     assert e.value.code == tm.TMASK_ERR_NULL
     # objective without workspace
     obj = torch.zeros(1, dtype=torch.float64, device="cuda")

@@ -81,9 +81,13 @@ def test_pack_roundtrip_and_l1():
 
 
 @pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
-def test_pack48_bf16_multi_tile_and_degenerate_masks(fmt):
-    # several whole tiles of the 4:8 bf16 kernel (128 rows x 256 columns) plus ragged edges in both directions
-    w = wl.f32_to_bf16_bits(wl.special_values_f32(392, 776, seed=4500))
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_pack48_multi_tile_and_degenerate_masks(dt, fmt):
+    # several whole tiles of the 4:8 kernels (bf16: 128 rows x 256 columns, fp32: 64 x 256) plus ragged edges in
+    # both directions; masks with 0 to 8 kept entries per group exercise fillers and the "first four win" rule
+    w = wl.special_values_f32(392, 776, seed=4500)
+    if dt == "bf16":
+        w = wl.f32_to_bf16_bits(w)
     rng = np.random.default_rng(45)
     masks = [oracle.approx(w, 4, 8)[0],
              (rng.random(w.shape) < 0.5).astype(np.uint8),      # unstructured: 0 to 8 kept per group
@@ -95,7 +99,7 @@ def test_pack48_bf16_multi_tile_and_degenerate_masks(fmt):
         _same(got, oracle.apply_pack(w, mask, 4, 8))
 
 
-@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("bf16", 4, 8)])
+@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("bf16", 4, 8), ("f32", 4, 8)])
 def test_pack_tile_order_bands_and_runs(dt, N, M):
     # 4352 x 2304: nine tile columns (one group of eight bands plus a ninth band) and more tile rows than one
     # vertical run of 4096 rows, so every branch of the tile numbering is taken; the fused call shares it
@@ -109,7 +113,7 @@ def test_pack_tile_order_bands_and_runs(dt, N, M):
     _same(got_f[0], want)
 
 
-@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("bf16", 4, 8)])
+@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("bf16", 4, 8), ("f32", 4, 8)])
 def test_pack_and_one_pass_random_shapes(dt, N, M):
     # a batch of matrices with random (seeded) shapes, from a single block to several tiles either way, with row
     # strides wider than the rows; apply_pack with unstructured masks, the one-pass call against the oracle's pair
