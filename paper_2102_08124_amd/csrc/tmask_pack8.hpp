@@ -3,7 +3,7 @@
 //
 // A strip of 16 bytes is one group of eight bf16 values, so a lane holds a whole 8 x 8 block per step: its
 // eight rows are the row groups, and the same registers read down are the column groups.  A group is
-// compacted without loops over slots: the 8-bit set of chosen positions indexes a table (built in LDS by
+// compacted without loops over slots: the 8-bit set of kept positions indexes a table (built in LDS by
 // the workgroup) that holds the byte selectors of four v_perm_b32 and the 12 position bits, so four
 // permutes pick the four slots out of the group's four dwords.  Pruned values are zeroed once per block,
 // which also makes fillers +0.  Tile = 128 rows x 32 strips (256 columns); a wavefront covers two runs of
@@ -50,10 +50,8 @@ __device__ __forceinline__ void compact_4of8(uint32_t kbits, uint32_t d0, uint32
                                              const u32x4 *luts, const uint16_t *lutc, uint32_t &o0, uint32_t &o1,
                                              uint32_t &code)
 {
-    uint32_t sel, chosen;
-    choose_slots<8>(kbits, 4u, sel, chosen);
-    const u32x4 L = luts[chosen];
-    code = lutc[chosen];
+    const u32x4 L = luts[kbits];
+    code = lutc[kbits];
     o0 = __builtin_amdgcn_perm(d1, d0, L.x) | __builtin_amdgcn_perm(d3, d2, L.y);
     o1 = __builtin_amdgcn_perm(d1, d0, L.z) | __builtin_amdgcn_perm(d3, d2, L.w);
 }
@@ -159,12 +157,15 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const ARGS args)
     __shared__ double red[kThreads / 64];
 
     const uint32_t tid = threadIdx.x, l = tid & 63u;
-    // ---- the table: entry m describes the set m of chosen positions (used only for sets of four) ----
+    // ---- the table: entry m describes the slots for the set m of kept positions (the kept ones in order, at most
+    //      four; if fewer, the lowest-numbered other positions as fillers: choose_slots, worked out once per entry) ----
     {
+        uint32_t sel, chosen;
+        choose_slots<8>(tid, 4u, sel, chosen);
         uint32_t sa0 = 0x0C0C0C0Cu, sa1 = 0x0C0C0C0Cu, sb0 = 0x0C0C0C0Cu, sb1 = 0x0C0C0C0Cu, code = 0, s = 0;
 #pragma unroll
         for (uint32_t p = 0; p < 8; p++) {
-            if (((tid >> p) & 1u) && s < 4u) {
+            if (((chosen >> p) & 1u) && s < 4u) {
                 const uint32_t b = 2u * (p & 3u);
                 const uint32_t pair = (b | ((b + 1u) << 8)) << (16u * (s & 1u));
                 const uint32_t clear = ~(0xFFFFu << (16u * (s & 1u)));
