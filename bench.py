@@ -134,6 +134,41 @@ def fused_approx_pack(tm, torch, ev, mats_np, copies: int, reps: int):
             "frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "weights_per_s": weights / (ms * 1e-3)}
 
 
+def four_of_eight(tm, torch, ev, mats_np, copies: int, reps: int):
+    """The same workload at 4:8, the paper's transposable setting for M = 8 (Sec. 4, Table 2): kernel times of the
+    approximation, the exact solver (augmenting paths from a priced start), the compression and the one-pass call.
+    The 7x7 stem aside every ResNet-50 conv matrix has dimensions that are multiples of 8."""
+    N, M = 4, 8
+    keep = [w for w in mats_np if w.shape[0] % M == 0 and w.shape[1] % M == 0]
+    weights = sum(w.size for w in keep)
+    sets = []
+    for _ in range(copies):
+        ws = [torch.from_numpy(w).cuda() for w in keep]
+        masks = tm.alloc_masks(ws)
+        obj = torch.zeros(len(ws), dtype=torch.float64, device="cuda")
+        packed = [tm.alloc_packed(w, N, M) for w in ws]
+        sets.append((tm.MatBatch(ws, masks, obj), tm.PackBatch(ws, masks, packed, N, M), tm.FusedBatch(ws, None, packed, N, M)))
+    wsp = tm.alloc_workspace(sets[0][0].ws, N, M)
+    calls = {"approx": lambda b: tm.tmask_approx(b[0], None, N, M, workspace=wsp),
+             "exact": lambda b: tm.tmask_exact(b[0], None, N, M, workspace=wsp),
+             "apply_pack": lambda b: tm.tmask_apply_pack(b[1], None, None, N, M),
+             "approx_pack": lambda b: tm.tmask_approx_pack(b[2], None, None, N, M)}
+    out = {"what": "4:8 on %d of the %d matrices (%d weights), one batched launch per call" % (len(keep), len(mats_np), weights)}
+    empty = ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
+    for name, fn in calls.items():
+        for b in sets:
+            fn(b)
+        torch.cuda.synchronize()
+        evs = [(ev.create(), ev.create()) for _ in range(reps)]
+        for k in range(reps):
+            tm.tmask_profile_next(*evs[k])
+            fn(sets[k % copies])
+        torch.cuda.synchronize()
+        ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - empty
+        out[name] = {"kernel_ms": ms, "weights_per_s": weights / (ms * 1e-3)}
+    return out
+
+
 def spmm24_products(tm, torch, ev, reps: int = 20, tokens: int = 8192):
     """The two training products with the packed 2:4 operands of one BERT-large-shaped bf16 layer
     (W: 4096 x 1024): forward y = x W^T with (vals, idx), backward dx = g W with (valsT, idxT).  MFMA-bound work
@@ -356,6 +391,7 @@ def main():
         result["largest_config_bit_masks"] = largest_config_approx(tm, torch, ev, reps=20, bit_masks=True)
     del sets
     result["fused_approx_pack"] = fused_approx_pack(tm, torch, ev, mats_np, copies=min(args.copies, 6), reps=24)
+    result["four_of_eight"] = four_of_eight(tm, torch, ev, mats_np, copies=min(args.copies, 3), reps=12)
     result["spmm24"] = spmm24_products(tm, torch, ev)
     result["device_copy"] = device_copy_rate(torch)
     if not args.no_cpu_baseline:
