@@ -453,12 +453,10 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
     constexpr int ROUNDS = (M == 16) ? 12 : 10;
     constexpr int PMIN = 1, PMAX = (1 << S) - 1;                // price + 2^(S-1)
     uint32_t ck[M][CL];
-    int price[M];
     uint32_t pk[M], best_pk[M];                                 // (price + 2^(S-1)) << 4
 #pragma unroll
     for (int i = 0; i < M; i++) {
-        price[i] = 1 << (S - 1);
-        pk[i] = (uint32_t)price[i] << 4;
+        pk[i] = (uint32_t)(1 << (S - 1)) << 4;
 #pragma unroll
         for (int c = 0; c < CL; c++)
             ck[i][c] = ((uint32_t)cost[i][c] << 4) | (uint32_t)i;
@@ -508,9 +506,8 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
 #pragma unroll
         for (int i = 0; i < M; i++) {
             best_pk[i] = better ? pk[i] : best_pk[i];
-            const int p = price[i] + step * ((int)n[i] - K);
-            price[i] = p > PMAX ? PMAX : p < PMIN ? PMIN : p;
-            pk[i] = (uint32_t)price[i] << 4;
+            const int p = (int)(pk[i] >> 4) + step * ((int)n[i] - K);
+            pk[i] = (uint32_t)(p > PMAX ? PMAX : p < PMIN ? PMIN : p) << 4;
         }
         step = (step * 11) >> 4;
     }
