@@ -34,16 +34,25 @@ __device__ __forceinline__ void unpack_row(const u32x4 &r, uint32_t (&a)[16 / ((
 
 // Workgroups per compute unit: a bf16 lane holds eight columns of its block (an fp32 lane four), and at M = 8
 // that needs more than the 128 registers that four workgroups would leave it.
+// Where the raw rows wait for the lane that runs their block's searches: in LDS (M x 16 bytes per lane), except at
+// fp32 M = 16, where those 64 KiB would hold the compute unit to two workgroups; there the rows are read from memory
+// again (the second and third reading mostly hit the cache) and three workgroups fit, registers permitting
+// (8192 x 8192: 890 -> 714 us; the other cases measured the same or 2-4 % slower without the LDS copy).
+constexpr bool exact_rows_in_lds(int dt, int M) { return !(dt == kF32 && M == 16); }
+constexpr int exact_workgroups_per_cu(int dt, int M) { return M == 16 ? (dt == kF32 ? 3 : 2) : (dt == kF32 ? 4 : 3); }
+
 template <int DT, int M, int FMT>
-__global__ __launch_bounds__(kThreads, (M == 16 ? 2 : DT == kF32 ? 4 : 3)) void exact_balanced_kernel(const BatchArgs args)
+__global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exact_balanced_kernel(const BatchArgs args)
 {
+    constexpr bool PARK = exact_rows_in_lds(DT, M);
     using Ge = Geo<DT, M>;
     constexpr int C = Ge::C, G = Ge::G;
     constexpr int NB = kThreads / G;          // blocks per workgroup
     constexpr int NBUCKET = 16;
     constexpr int XPW = 32 / M;               // pruned-row sets (M bits per column) per exchanged word
     constexpr int XW = C / XPW;
-    __shared__ __attribute__((aligned(16))) u32x4 xraw[kThreads][M];     // the raw rows of every block, at the loading lane's place
+    // PARK: the raw rows of every block stay in LDS, at the loading lane's place; else they are read from memory again
+    __shared__ __attribute__((aligned(16))) u32x4 xraw[PARK ? kThreads : 1][M];
     __shared__ uint32_t xstart[kThreads][XW];
     __shared__ uint16_t ssrc[kThreads];
     __shared__ uint32_t sorig[NB];
@@ -61,6 +70,7 @@ __global__ __launch_bounds__(kThreads, (M == 16 ? 2 : DT == kF32 ? 4 : 3)) void 
     // Lanes past the matrix' last strip take part in the exchange with a filler block whose start has
     // no excess (a band of ones: entry (i, j) is 1 iff (i + j) mod M < M/2), so they cost the solver nothing.
     u32x4 raw[M];
+    auto load_block = [&](bool ok, uint32_t strip_no) {
 #pragma unroll
     for (int i = 0; i < M; i++) {
         uint32_t d[4];
@@ -77,14 +87,20 @@ __global__ __launch_bounds__(kThreads, (M == 16 ? 2 : DT == kF32 ? 4 : 3)) void 
         }
         raw[i] = u32x4{d[0], d[1], d[2], d[3]};
     }
-    if (valid) {
-        const StripPos pos = strip_pos(md, s);
+    if (ok) {
+        const StripPos pos = strip_pos(md, strip_no);
         const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * C) * Ge::ES;
         const size_t row_bytes = (size_t)md.ld * Ge::ES;
 #pragma unroll
-        for (int i = 0; i < M; i++)
-            raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
+        for (int i = 0; i < M; i++) {
+            if constexpr (PARK)
+                raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
+            else
+                raw[i] = *(const u32x4 *)(base + i * row_bytes);     // read again below: may stay in the cache
+        }
     }
+    };
+    load_block(valid, s);
 
     // ---- the solver's start on the block this lane sits on (every lane busy), then a stable counting sort
     //      of the workgroup's blocks by the row excess that start leaves: the number of augmentations to come ----
@@ -95,7 +111,8 @@ __global__ __launch_bounds__(kThreads, (M == 16 ? 2 : DT == kF32 ? 4 : 3)) void 
 #pragma unroll
         for (int i = 0; i < M; i++) {
             unpack_row<DT>(raw[i], a[i]);
-            xraw[tid][i] = raw[i];      // parked in LDS for the lane that will run this block's searches
+            if constexpr (PARK)
+                xraw[tid][i] = raw[i];  // parked in LDS for the lane that will run this block's searches
 #pragma unroll
             for (int c = 0; c < C; c++)
                 asm volatile("" : "+v"(a[i][c]));   // the raw rows end here
@@ -143,9 +160,13 @@ __global__ __launch_bounds__(kThreads, (M == 16 ? 2 : DT == kF32 ? 4 : 3)) void 
     const uint32_t from = ssrc[tid];
     const uint32_t my_s = sorig[tid / G];
     const bool my_valid = my_s != 0xFFFFFFFFu;
+    if constexpr (PARK) {
 #pragma unroll
-    for (int i = 0; i < M; i++)
-        raw[i] = xraw[from][i];
+        for (int i = 0; i < M; i++)
+            raw[i] = xraw[from][i];
+    } else {
+        load_block(my_valid, my_s + gpos);
+    }
     uint32_t xpack[XW];
 #pragma unroll
     for (int q = 0; q < XW; q++)
@@ -184,11 +205,16 @@ __global__ __launch_bounds__(kThreads, (M == 16 ? 2 : DT == kF32 ? 4 : 3)) void 
         if (my_valid) {
             const StripPos pos = strip_pos(md, my_s + gpos);
             store_mask<DT, M, FMT>(md, pos, bits);
-            // the magnitudes are read again from LDS: they need not occupy registers during the solve
+            // the magnitudes are read again (from LDS, or from memory): they need not occupy registers during the solve
+            const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * C) * Ge::ES;
+            const size_t row_bytes = (size_t)md.ld * Ge::ES;
 #pragma unroll
             for (int i = 0; i < M; i++) {
                 uint32_t ar[C];
-                unpack_row<DT>(xraw[from][i], ar);
+                if constexpr (PARK)
+                    unpack_row<DT>(xraw[from][i], ar);
+                else
+                    unpack_row<DT>(__builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes)), ar);
 #pragma unroll
                 for (int c = 0; c < C; c++)
                     acc += ((bits[i] >> c) & 1u) ? __uint_as_float(ar[c]) : 0.f;
