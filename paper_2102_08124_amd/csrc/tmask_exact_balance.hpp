@@ -15,17 +15,20 @@
 
 namespace tmask {
 
-template <int DT>
-__device__ __forceinline__ void unpack_row(const u32x4 &r, uint32_t (&a)[16 / ((DT == kF32) ? 4 : 2)])
+// Magnitude keys (fp32 bit patterns) of the C values a lane holds of one row: four dwords (fp32, or eight bf16),
+// or two dwords (four bf16) where a lane takes half a 16-byte strip.
+template <int DT, int C>
+__device__ __forceinline__ void unpack_row(const u32x4 &r, uint32_t (&a)[C])
 {
     const uint32_t d[4] = {r.x, r.y, r.z, r.w};
     if constexpr (DT == kF32) {
+        static_assert(C == 4, "an fp32 lane holds four columns");
 #pragma unroll
         for (int c = 0; c < 4; c++)
             a[c] = d[c] & 0x7FFFFFFFu;
     } else {
 #pragma unroll
-        for (int c = 0; c < 4; c++) {
+        for (int c = 0; c < C / 2; c++) {
             a[2 * c] = (d[c] << 16) & 0x7FFF0000u;
             a[2 * c + 1] = d[c] & 0x7FFF0000u;
         }
@@ -33,20 +36,24 @@ __device__ __forceinline__ void unpack_row(const u32x4 &r, uint32_t (&a)[16 / ((
 }
 
 // Workgroups per compute unit: a bf16 lane holds eight columns of its block (an fp32 lane four), and at M = 8
-// that needs more than the 128 registers that four workgroups would leave it.
+// that needs more than the 128 registers that four workgroups would leave it.  At M = 16 eight columns of sixteen
+// rows do not fit a lane at all (256 registers, spills): there a bf16 lane takes half a strip, four columns, and
+// four lanes share a block as at fp32 (exact_half_strips; the host launches twice the workgroups).
 // Where the raw rows wait for the lane that runs their block's searches: in LDS (M x 16 bytes per lane), except at
-// fp32 M = 16, where those 64 KiB would hold the compute unit to two workgroups; there the rows are read from memory
+// M = 16, where those 64 KiB would hold the compute unit to two workgroups; there the rows are read from memory
 // again (the second and third reading mostly hit the cache) and three workgroups fit, registers permitting
-// (8192 x 8192: 890 -> 714 us; the other cases measured the same or 2-4 % slower without the LDS copy).
-constexpr bool exact_rows_in_lds(int dt, int M) { return !(dt == kF32 && M == 16); }
-constexpr int exact_workgroups_per_cu(int dt, int M) { return M == 16 ? (dt == kF32 ? 3 : 2) : (dt == kF32 ? 4 : 3); }
+// (8192 x 8192 fp32: 890 -> 714 us; the M = 8 cases measured the same or 2-4 % slower without the LDS copy).
+constexpr bool exact_half_strips(int dt, int M) { return dt == kBF16 && M == 16; }
+constexpr bool exact_rows_in_lds(int dt, int M) { return M != 16; }
+constexpr int exact_workgroups_per_cu(int dt, int M) { return M == 16 ? 3 : (dt == kF32 ? 4 : 3); }
 
 template <int DT, int M, int FMT>
 __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exact_balanced_kernel(const BatchArgs args)
 {
     constexpr bool PARK = exact_rows_in_lds(DT, M);
     using Ge = Geo<DT, M>;
-    constexpr int C = Ge::C, G = Ge::G;
+    constexpr bool HALF = exact_half_strips(DT, M);
+    constexpr int C = HALF ? 4 : Ge::C, G = HALF ? 4 : Ge::G;     // columns per lane, lanes per block
     constexpr int NB = kThreads / G;          // blocks per workgroup
     constexpr int NBUCKET = 16;
     constexpr int XPW = 32 / M;               // pruned-row sets (M bits per column) per exchanged word
@@ -64,12 +71,18 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t s = (tile - md.tile0) * kThreads + tid;
     const uint32_t gpos = tid & (G - 1);
-    const bool valid = s < md.n_strips;
+    const bool valid = s < md.n_strips * (HALF ? 2u : 1u);      // s counts half strips if HALF
 
     // ---- load the block this lane sits on ----
     // Lanes past the matrix' last strip take part in the exchange with a filler block whose start has
     // no excess (a band of ones: entry (i, j) is 1 iff (i + j) mod M < M/2), so they cost the solver nothing.
     u32x4 raw[M];
+    // first byte of the lane's part of row 0 of the block that strip (or half strip) `unit` belongs to
+    auto block_base = [&](uint32_t unit) {
+        const StripPos pos = strip_pos(md, HALF ? unit >> 1 : unit);
+        const size_t col = (size_t)pos.sc * Ge::C + (HALF ? (unit & 1u) * 4u : 0u);
+        return (const char *)md.w + ((size_t)pos.br * M * md.ld + col) * Ge::ES;
+    };
     auto load_block = [&](bool ok, uint32_t strip_no) {
 #pragma unroll
     for (int i = 0; i < M; i++) {
@@ -79,8 +92,10 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
             if constexpr (DT == kF32) {
                 const uint32_t j = gpos * 4u + (uint32_t)q;
                 d[q] = (((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u;
+            } else if (HALF && q >= 2) {
+                d[q] = 0u;
             } else {
-                const uint32_t j = gpos * 8u + 2u * (uint32_t)q;
+                const uint32_t j = gpos * (uint32_t)C + 2u * (uint32_t)q;
                 d[q] = ((((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F80u : 0u) |
                        ((((uint32_t)i + j + 1u) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u);
             }
@@ -88,15 +103,18 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
         raw[i] = u32x4{d[0], d[1], d[2], d[3]};
     }
     if (ok) {
-        const StripPos pos = strip_pos(md, strip_no);
-        const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * C) * Ge::ES;
+        const char *base = block_base(strip_no);
         const size_t row_bytes = (size_t)md.ld * Ge::ES;
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            if constexpr (PARK)
+            if constexpr (PARK) {
                 raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
-            else
+            } else if constexpr (HALF) {
+                const u32x2 h = *(const u32x2 *)(base + i * row_bytes);
+                raw[i] = u32x4{h.x, h.y, 0u, 0u};
+            } else {
                 raw[i] = *(const u32x4 *)(base + i * row_bytes);     // read again below: may stay in the cache
+            }
         }
     }
     };
@@ -110,7 +128,7 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
         int cost[M][C];
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            unpack_row<DT>(raw[i], a[i]);
+            unpack_row<DT, C>(raw[i], a[i]);
             if constexpr (PARK)
                 xraw[tid][i] = raw[i];  // parked in LDS for the lane that will run this block's searches
 #pragma unroll
@@ -179,7 +197,7 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
         uint32_t a[M][C], xcol[C], bits[M];
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            unpack_row<DT>(raw[i], a[i]);
+            unpack_row<DT, C>(raw[i], a[i]);
             // the raw rows end here: the keys must not be re-derived from them later
 #pragma unroll
             for (int c = 0; c < C; c++)
@@ -203,18 +221,39 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
                 bits[i] |= (((xcol[c] >> i) & 1u) ^ 1u) << c;
         }
         if (my_valid) {
-            const StripPos pos = strip_pos(md, my_s + gpos);
-            store_mask<DT, M, FMT>(md, pos, bits);
+            const uint32_t unit = my_s + gpos;
+            if constexpr (HALF) {
+                // four mask entries per row and lane: four bytes, or a nibble that the even lane of a pair completes
+                const StripPos pos = strip_pos(md, unit >> 1);
+                const size_t col = (size_t)pos.sc * 8u + (unit & 1u) * 4u;
+                char *mrow = (char *)md.mask + (size_t)pos.br * M * md.mask_ld;
+#pragma unroll
+                for (int i = 0; i < M; i++) {
+                    if constexpr (FMT == kMaskU8) {
+                        stream_store(bits_to_bytes4(bits[i]), (uint32_t *)(mrow + (size_t)i * md.mask_ld + col));
+                    } else {
+                        const uint32_t other = quad_xor<1>(bits[i]);
+                        if ((unit & 1u) == 0)
+                            mrow[(size_t)i * md.mask_ld + (col >> 3)] = (char)(bits[i] | (other << 4));
+                    }
+                }
+            } else {
+                store_mask<DT, M, FMT>(md, strip_pos(md, unit), bits);
+            }
             // the magnitudes are read again (from LDS, or from memory): they need not occupy registers during the solve
-            const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * C) * Ge::ES;
+            const char *base = block_base(unit);
             const size_t row_bytes = (size_t)md.ld * Ge::ES;
 #pragma unroll
             for (int i = 0; i < M; i++) {
                 uint32_t ar[C];
-                if constexpr (PARK)
-                    unpack_row<DT>(xraw[from][i], ar);
-                else
-                    unpack_row<DT>(__builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes)), ar);
+                if constexpr (PARK) {
+                    unpack_row<DT, C>(xraw[from][i], ar);
+                } else if constexpr (HALF) {
+                    const u32x2 h = __builtin_nontemporal_load((const u32x2 *)(base + i * row_bytes));
+                    unpack_row<DT, C>(u32x4{h.x, h.y, 0u, 0u}, ar);
+                } else {
+                    unpack_row<DT, C>(__builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes)), ar);
+                }
 #pragma unroll
                 for (int c = 0; c < C; c++)
                     acc += ((bits[i] >> c) & 1u) ? __uint_as_float(ar[c]) : 0.f;

@@ -637,6 +637,8 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<8, kMaskU8> : approx_sel_bf16_kernel<8, kMaskBits>;
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 16 && N == 8)
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<16, kMaskU8> : approx_sel_bf16_kernel<16, kMaskBits>;
+    // the exact kernel for bf16 8:16 gives a lane half a strip: twice the workgroups
+    const uint32_t unit_split = (SOLVER == kSolveExact && 2 * N == M && exact_half_strips(dt, M)) ? 2u : 1u;
     hipStream_t stream = (hipStream_t)stream_;
     uint32_t partial0 = 0;
     for (int first = 0; first < n_mats; first += kMaxBatch) {
@@ -652,7 +654,7 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             fill_desc(args.m[k], h, dt, M, tiles);
             rargs.objective[k] = t.objective;
             rargs.tile0[k] = tiles;
-            tiles += tiles_of(args.m[k].n_strips);
+            tiles += tiles_of(args.m[k].n_strips * unit_split);
         }
         rargs.tile0[nb] = tiles;
         args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;

@@ -208,13 +208,18 @@ def test_exact_non_finite_stays_valid():
         assert np.all(b.sum(axis=3) == N) and np.all(b.sum(axis=2) == N)
 
 
-def test_exact_batched():
-    ws = [_inputs("f32", 32, 48, 2400), _inputs("f32", 16, 1040, 2401), _inputs("f32", 64, 64, 2402)]
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+def test_exact_batched(kind):
+    # several matrices in one launch, rows wider than the matrices; the third one fills more than one workgroup at
+    # every N:M (at bf16 8:16 a lane takes half a strip and the launch has twice the workgroups)
+    ws = [_inputs(kind, 32, 48, 2400), _inputs(kind, 16, 1040, 2401), _inputs(kind, 64, 1024, 2402)]
     for N, M in NM:
-        masks, obj = run_masks(tm.tmask_exact, ws, N, M, ld_pad=16)
-        for k, w in enumerate(ws):
-            _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
-            _check_exact(w, masks[k], N, M, opb)
+        for fmt in FMTS:
+            masks, obj = run_masks(tm.tmask_exact, ws, N, M, fmt, ld_pad=16)
+            for k, w in enumerate(ws):
+                _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
+                _check_exact(w, masks[k], N, M, opb)
+                assert obj[k] == pytest.approx(oobj, rel=1e-5)
             assert obj[k] == pytest.approx(oobj, rel=1e-5)
 
 
