@@ -85,6 +85,15 @@ def test_fused_4of8_one_pass(dt, fmt, with_mask):
     _check(ws, 4, 8, got, masks, objs, with_mask)
 
 
+@pytest.mark.parametrize("dt,N,M", [("f32", 2, 4), ("bf16", 2, 4), ("f32", 4, 8), ("bf16", 4, 8)])
+def test_fused_tall_narrow_with_objective(dt, N, M):
+    # one block column, thousands of block rows: the one-pass kernels keep one partial sum per tile of 64 or 128
+    # rows, many more than the mask kernels' tiles of 256 strips; a workspace sized by tmask_workspace_bytes holds them
+    ws = [_w(dt, 16384, 8, seed=5250 + M)]
+    got, masks, objs = run_fused(ws, N, M)
+    _check(ws, N, M, got, masks, objs)
+
+
 @pytest.mark.parametrize("N,M", [(8, 16), (1, 4), (3, 4), (5, 8)])
 def test_fused_other_nm_runs_both_steps(N, M):
     for dt in ("f32", "bf16"):
