@@ -169,13 +169,13 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
         rank = dpp_read<0xA0>(rank);   // quad_perm [0,0,2,2]
     if constexpr (G == 4)
         rank = dpp_read<0x00>(rank);   // quad_perm [0,0,0,0]
-    ssrc[rank * G + gpos] = (uint16_t)tid;
+    ssrc[rank * G + gpos] = (uint16_t)(tid | (e << 8));      // where the block's rows and start are, and its excess
     if (leader)
         sorig[rank] = valid ? s : 0xFFFFFFFFu;
     __syncthreads();
 
     // ---- this lane continues with the block sorted into its position: rows and start of the lane that loaded it ----
-    const uint32_t from = ssrc[tid];
+    const uint32_t from = ssrc[tid] & 0xFFu, my_e = ssrc[tid] >> 8;
     const uint32_t my_s = sorig[tid / G];
     const bool my_valid = my_s != 0xFFFFFFFFu;
     if constexpr (PARK) {
@@ -203,13 +203,14 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
             for (int c = 0; c < C; c++)
                 asm volatile("" : "+v"(a[i][c]));
         }
-        {
+#pragma unroll
+        for (int c = 0; c < C; c++)
+            xcol[c] = (xpack[c / XPW] >> ((c % XPW) * M)) & ((1u << M) - 1u);
+        // most wavefronts hold only blocks whose start is already balanced: nothing to search
+        if (__any(my_e != 0u)) {
             int cost[M][C];
             uint32_t cnt[M];
             exact_costs<M, C, G>(a, cost);
-#pragma unroll
-            for (int c = 0; c < C; c++)
-                xcol[c] = (xpack[c / XPW] >> ((c % XPW) * M)) & ((1u << M) - 1u);
             exact_counts<M, C, G>(xcol, cnt);
             (void)exact_phases<M, C, G>(cost, (uint32_t)(M / 2), gpos, xcol, cnt, M * M);
         }
