@@ -256,31 +256,41 @@ struct ReduceArgs {
     const double *partials;
 };
 
-// Second stage of the objective: workgroup m adds the partials of matrix m in a fixed order.
-__global__ __launch_bounds__(kThreads) void objective_reduce_kernel(const ReduceArgs args)
+// Second stage of the objective: workgroup m adds the partials of matrix m in a fixed order.  1024 threads: one
+// matrix can have hundreds of thousands of partials, and the loop is a chain of load latencies.
+constexpr int kReduceThreads = 1024;
+
+__global__ __launch_bounds__(kReduceThreads) void objective_reduce_kernel(const ReduceArgs args)
 {
-    __shared__ double red[kThreads / 64];
+    __shared__ double red[kReduceThreads / 64];
     const uint32_t m = blockIdx.x;
     double *dst = args.objective[m];
     if (!dst)
         return;
-    // four independent partial sums per thread keep several loads in flight (one matrix can have
-    // tens of thousands of partials); the order of additions is fixed
+    // four independent partial sums per thread keep several loads in flight; the order of additions is fixed
     const uint32_t t0 = args.tile0[m], t1 = args.tile0[m + 1];
     const double *src = args.partials + args.partial0;
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     uint32_t t = t0 + threadIdx.x;
-    for (; t + 3 * kThreads < t1; t += 4 * kThreads) {
+    for (; t + 3 * kReduceThreads < t1; t += 4 * kReduceThreads) {
         a0 += src[t];
-        a1 += src[t + kThreads];
-        a2 += src[t + 2 * kThreads];
-        a3 += src[t + 3 * kThreads];
+        a1 += src[t + kReduceThreads];
+        a2 += src[t + 2 * kReduceThreads];
+        a3 += src[t + 3 * kReduceThreads];
     }
-    for (; t < t1; t += kThreads)
+    for (; t < t1; t += kReduceThreads)
         a0 += src[t];
-    const double total = block_sum((a0 + a1) + (a2 + a3), red);
-    if (threadIdx.x == 0)
+    const double w = wave_sum((a0 + a1) + (a2 + a3));
+    if ((threadIdx.x & 63) == 0)
+        red[threadIdx.x >> 6] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double total = red[0];
+#pragma unroll
+        for (int k = 1; k < kReduceThreads / 64; k++)
+            total += red[k];
         dst[0] = total;
+    }
 }
 
 struct ScorePartial {
@@ -668,7 +678,7 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             return hip_fail(e, "mask kernel launch");
         if (want_obj) {
             rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)ws;
-            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
+            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
             e = hipGetLastError();
             if (e != hipSuccess)
                 return hip_fail(e, "objective reduce launch");
@@ -970,7 +980,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
             return hip_fail(e, "fused approx+pack kernel launch");
         if (want_obj) {
             rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)workspace;
-            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
+            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
             e = hipGetLastError();
             if (e != hipSuccess)
                 return hip_fail(e, "objective reduce launch");
