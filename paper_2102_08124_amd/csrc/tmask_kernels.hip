@@ -770,8 +770,17 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
 
 typedef void (*pack_kernel_t)(const PackArgs);
 
-static pack_kernel_t pick_pack_kernel(int dt, int M, int mf)
+static pack_kernel_t pick_pack_kernel(int dt, int M, int mf, int N)
 {
+    if (2 * N == M) {   // N known at compile time
+#define TMASK_PICK(DT, MM, FM) \
+    if (dt == DT && M == MM && mf == FM) return pack_kernel<DT, MM, FM, MM / 2>;
+        TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
+        TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
+        TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
+        TMASK_PICK(kBF16, 4, kMaskBits) TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+#undef TMASK_PICK
+    }
 #define TMASK_PICK(DT, MM, FM) \
     if (dt == DT && M == MM && mf == FM) return pack_kernel<DT, MM, FM>;
     TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
@@ -799,7 +808,7 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
         if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
             return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 4-byte aligned", i);
     }
-    pack_kernel_t kern = pick_pack_kernel((int)dt, M, (int)mf);
+    pack_kernel_t kern = pick_pack_kernel((int)dt, M, (int)mf, N);
     uint32_t TC = 256 / (uint32_t)elem_size((int)dt);
     bool fast24 = (M == 4 && N == 2);
     for (int i = 0; i < n && fast24; i++)

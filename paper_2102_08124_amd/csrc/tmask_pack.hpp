@@ -116,7 +116,9 @@ __device__ __forceinline__ void lds_or_bits(uint32_t *words, uint32_t off, unsig
         atomicOr(&words[w + 2], hi);
 }
 
-template <int DT, int M, int FMT>
+// NN = N when it is known at compile time (N = M/2: slot loops unrolled, a row group's values leave as 16-byte
+// stores), 0 = any N (args.N).
+template <int DT, int M, int FMT, int NN = 0>
 __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
 {
     using T = typename std::conditional<DT == kF32, uint32_t, uint16_t>::type;
@@ -151,9 +153,10 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
             hi = mid - 1;
     }
     const PackDev d = args.d[lo];
-    const uint32_t N = args.N;
+    const uint32_t N = NN ? (uint32_t)NN : args.N;
     const uint32_t tl = tile - d.tile0;
-    const uint32_t ty = tl / d.tiles_x, tx = tl - ty * d.tiles_x;
+    uint32_t ty, tx;
+    tile_coords(tl, d.tiles_x, (d.rows + TR - 1) / TR, kPackRunRows / TR, ty, tx);
     const uint32_t row0 = ty * TR, col0 = tx * TC;
     const uint32_t tid = threadIdx.x;
     const uint32_t g_valid = min((uint32_t)GPT, (d.cols - col0) / M);   // groups of this tile inside the matrix
@@ -226,6 +229,31 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
             T *dst = (T *)d.vals + (size_t)(row0 + r) * pitch + (size_t)(col0 / M + g) * N;
             unsigned long long code = 0;
             uint32_t pend = 0;
+            if constexpr (NN != 0 && (NN * ES) % 16 == 0) {
+                if ((((uintptr_t)d.vals | (pitch * ES)) & 15) == 0) {
+                    // the group's NN values as whole 16-byte pieces
+                    uint32_t out[NN * ES / 4];
+#pragma unroll
+                    for (int q = 0; q < NN * ES / 4; q++)
+                        out[q] = 0;
+#pragma unroll
+                    for (int sl = 0; sl < NN; sl++) {
+                        const uint32_t p = (uint32_t)__builtin_ctz(rem);
+                        rem &= rem - 1u;
+                        const uint32_t val = ((sel >> p) & 1u) ? (uint32_t)V[r][g * M + p] : 0u;
+                        if constexpr (ES == 4)
+                            out[sl] = val;
+                        else
+                            out[sl / 2] |= val << (16 * (sl & 1));
+                        code |= (unsigned long long)p << (sl * IB);
+                    }
+#pragma unroll
+                    for (int q = 0; q < NN * ES / 16; q++)
+                        stream_store(u32x4{out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]}, (u32x4 *)dst + q);
+                    lds_or_bits(IDX[r], g * N * IB, code);
+                    continue;
+                }
+            }
             for (uint32_t sl = 0; sl < N; sl++) {
                 const uint32_t p = (uint32_t)__builtin_ctz(rem);
                 rem &= rem - 1u;
@@ -257,11 +285,21 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
         uint32_t sel, rem;
         choose_slots<M>(kb, N, sel, rem);
         unsigned long long code = 0;
-        for (uint32_t sl = 0; sl < N; sl++) {
-            const uint32_t p = (uint32_t)__builtin_ctz(rem);
-            rem &= rem - 1u;
-            OT[c][b * N + sl] = ((sel >> p) & 1u) ? V[b * M + p][c] : (T)0;
-            code |= (unsigned long long)p << (sl * IB);
+        if constexpr (NN != 0) {
+#pragma unroll
+            for (int sl = 0; sl < NN; sl++) {
+                const uint32_t p = (uint32_t)__builtin_ctz(rem);
+                rem &= rem - 1u;
+                OT[c][b * NN + sl] = ((sel >> p) & 1u) ? V[b * M + p][c] : (T)0;
+                code |= (unsigned long long)p << (sl * IB);
+            }
+        } else {
+            for (uint32_t sl = 0; sl < N; sl++) {
+                const uint32_t p = (uint32_t)__builtin_ctz(rem);
+                rem &= rem - 1u;
+                OT[c][b * N + sl] = ((sel >> p) & 1u) ? V[b * M + p][c] : (T)0;
+                code |= (unsigned long long)p << (sl * IB);
+            }
         }
         lds_or_bits(IDXT[c], b * N * IB, code);
     }
