@@ -118,6 +118,20 @@ __device__ __forceinline__ void lds_or_bits(uint32_t *words, uint32_t off, unsig
 
 // NN = N when it is known at compile time (N = M/2: slot loops unrolled, a row group's values leave as 16-byte
 // stores), 0 = any N (args.N).
+// The BITS position bits of group number `g` of a line into the line's bit string (cleared beforehand): whole words are
+// stored, anything else is ORed in.
+template <int BITS>
+__device__ __forceinline__ void put_code(uint32_t *words, uint32_t g, unsigned long long code)
+{
+    if constexpr (BITS % 32 == 0) {
+#pragma unroll
+        for (int w = 0; w < BITS / 32; w++)
+            words[g * (BITS / 32) + w] = (uint32_t)(code >> (32 * w));
+    } else {
+        lds_or_bits(words, g * BITS, code);
+    }
+}
+
 template <int DT, int M, int FMT, int NN = 0>
 __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
 {
@@ -250,7 +264,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
 #pragma unroll
                     for (int q = 0; q < NN * ES / 16; q++)
                         stream_store(u32x4{out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]}, (u32x4 *)dst + q);
-                    lds_or_bits(IDX[r], g * N * IB, code);
+                    put_code<NN * IB>(IDX[r], g, code);
                     continue;
                 }
             }
@@ -301,7 +315,10 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
                 code |= (unsigned long long)p << (sl * IB);
             }
         }
-        lds_or_bits(IDXT[c], b * N * IB, code);
+        if constexpr (NN != 0)
+            put_code<NN * IB>(IDXT[c], b, code);
+        else
+            lds_or_bits(IDXT[c], b * N * IB, code);
     }
     __syncthreads();
 
@@ -312,11 +329,13 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
         const size_t pitch = (size_t)(d.rows / M) * N;
         T *dst = (T *)d.valsT + (size_t)col0 * pitch + (size_t)(row0 / M) * N;
         if (ES == 4 || (((run | (uint32_t)pitch | (uint32_t)((row0 / M) * N)) & 1u) == 0)) {
-            constexpr uint32_t LW = ES == 4 ? 64 : 32;       // lanes per output row (a run has at most LW dwords)
+            // lanes per output row: a run has at most BPT * (M - 1) * ES / 4 dwords, BPT * M / 2 * ES / 4 when N = M/2
+            constexpr uint32_t LWMAX = ES == 4 ? 64 : 32;
+            constexpr uint32_t LW = (NN != 0 && 2 * NN == M) ? LWMAX / 2 : LWMAX;
             const uint32_t rd = run * ES / 4, x = tid % LW;
             if (x < rd)
                 for (uint32_t c = tid / LW; c < c_valid; c += kThreads / LW)
-                    ((uint32_t *)(dst + (size_t)c * pitch))[x] = ((const uint32_t *)&OT[c][0])[x];
+                    stream_store(((const uint32_t *)&OT[c][0])[x], (uint32_t *)(dst + (size_t)c * pitch) + x);
         } else {
             for (uint32_t k = tid; k < c_valid * run; k += kThreads) {
                 const uint32_t c = k / run, x = k - c * run;
