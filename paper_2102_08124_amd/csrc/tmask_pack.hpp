@@ -143,9 +143,11 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
     constexpr int IB = Log2<M>::v;
     constexpr int GPT = TC / M;                // groups per tile row
     constexpr int BPT = TR / M;                // block-rows per tile
-    constexpr int OTP = TR + 4 / ES;           // pitch of the transposed staging (bank-conflict free)
-    constexpr int IDXW = (GPT * (M - 1) * IB + 31) / 32 + 2;
-    constexpr int IDXTW = (BPT * (M - 1) * IB + 31) / 32 + 2 + 1;
+    constexpr int OTR = NN ? TR * NN / M : TR; // staged W^T values per column: N per block-row (at most M - 1 if N is not known)
+    constexpr int OTP = OTR + 4 / ES;          // pitch of the transposed staging (bank-conflict free)
+    constexpr int NMAX = NN ? NN : M - 1;      // slots per group the staging must hold
+    constexpr int IDXW = (GPT * NMAX * IB + 31) / 32 + 2;
+    constexpr int IDXTW = (BPT * NMAX * IB + 31) / 32 + 2 + 1;
     constexpr int NRU = TR * GPT / kThreads;   // row-direction units per thread
     constexpr int NCU = BPT * TC / kThreads;   // column-direction units per thread
     static_assert(TR * GPT % kThreads == 0 && BPT * TC % kThreads == 0, "units must tile the workgroup");
