@@ -153,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
     static_assert(TR * GPT % kThreads == 0 && BPT * TC % kThreads == 0, "units must tile the workgroup");
 
     __shared__ __attribute__((aligned(16))) T V[TR][TC];   // masked tile
-    __shared__ __attribute__((aligned(16))) uint8_t FB[TR][TC];
+    __shared__ __attribute__((aligned(16))) uint8_t FN[TR][16];   // keep flags of each 16-byte chunk (C bits), 16 chunks per tile row
     __shared__ T OT[TC][OTP];
     __shared__ uint32_t IDX[TR][IDXW];
     __shared__ uint32_t IDXT[TC][IDXTW];
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
 #pragma unroll
             for (int c = 0; c < 4; c++)
                 w4[c] = ((flags >> c) & 1u) ? w4[c] : 0u;
-            *(uint32_t *)&FB[r][ch * C] = bits_to_bytes4(flags);
+            FN[r][ch] = (uint8_t)flags;
         } else {
 #pragma unroll
             for (int c = 0; c < 4; c++) {
@@ -218,8 +218,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
                 const uint32_t keep_hi = ((flags >> (2 * c + 1)) & 1u) ? 0xFFFF0000u : 0u;
                 w4[c] &= keep_lo | keep_hi;
             }
-            *(uint32_t *)&FB[r][ch * C] = bits_to_bytes4(flags & 0xFu);
-            *(uint32_t *)&FB[r][ch * C + 4] = bits_to_bytes4(flags >> 4);
+            FN[r][ch] = (uint8_t)flags;
         }
         u32x4 mv = {w4[0], w4[1], w4[2], w4[3]};
         *(u32x4 *)&V[r][ch * C] = mv;
@@ -237,9 +236,13 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
             if (r >= r_valid || g >= g_valid)
                 continue;   // outside the matrix: must not leave index bits in a row's padding
             uint32_t kb = 0;
+            if constexpr (M >= C) {
 #pragma unroll
-            for (int q = 0; q < M / 4; q++)
-                kb |= bytes4_to_bits(*(const uint32_t *)&FB[r][g * M + 4 * q]) << (4 * q);
+                for (int q = 0; q < M / C; q++)
+                    kb |= (uint32_t)FN[r][g * (M / C) + q] << (C * q);
+            } else {
+                kb = ((uint32_t)FN[r][g / (C / M)] >> (M * (g % (C / M)))) & ((1u << M) - 1u);
+            }
             uint32_t sel, rem;
             choose_slots<M>(kb, N, sel, rem);
             T *dst = (T *)d.vals + (size_t)(row0 + r) * pitch + (size_t)(col0 / M + g) * N;
@@ -297,7 +300,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
         uint32_t kb = 0;
 #pragma unroll
         for (int p = 0; p < M; p++)
-            kb |= (uint32_t)FB[b * M + p][c] << p;
+            kb |= (((uint32_t)FN[b * M + p][c / C] >> (c % C)) & 1u) << p;
         uint32_t sel, rem;
         choose_slots<M>(kb, N, sel, rem);
         unsigned long long code = 0;
