@@ -133,3 +133,29 @@ def test_pack_and_one_pass_random_shapes(dt, N, M):
         om = oracle.approx(w, N, M)[0]
         assert np.array_equal(gmasks[k] != 0, om != 0), k
         _same(got_f[k], oracle.apply_pack(w, om, N, M))
+
+
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (8, 16)])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_pack_outputs_only_four_byte_aligned(dt, N, M):
+    # vals and valsT four bytes off a 16-byte boundary: the specialised kernels (8-byte stores) and the 16-byte
+    # stores of the general one must step aside for the element-wise path; same bytes as ever
+    from tests.gpu_util import to_dev, mask_to_dev
+    w = _w(dt, 6 * M, 272, seed=4800 + M)
+    mask = oracle.approx(w, N, M)[0]
+    wd = to_dev(w)
+    vs, is_, vts, its = tm.packed_shapes(w.shape[0], w.shape[1], N, M)
+    off = 1 if dt == "f32" else 2                      # elements = four bytes
+    def shifted(shape):
+        n = int(np.prod(shape))
+        buf = torch.zeros(n + 8, dtype=wd.dtype, device="cuda")
+        return buf[off:off + n].view(*shape)
+    packed = (shifted(vs), torch.zeros(is_, dtype=torch.uint8, device="cuda"),
+              shifted(vts), torch.zeros(its, dtype=torch.uint8, device="cuda"))
+    assert packed[0].data_ptr() % 16 == 4 and packed[2].data_ptr() % 16 == 4
+    tm.tmask_apply_pack([wd], [mask_to_dev(mask, tm.TMASK_MASK_U8)], [packed], N, M)
+    torch.cuda.synchronize()
+    got = []
+    for t in packed:
+        got.append(t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.cpu().numpy())
+    _same(tuple(got), oracle.apply_pack(w, mask, N, M))
