@@ -437,12 +437,13 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
 // term of any pruning with those counts is the same sum over rows of price x count, so being cheapest under
 // cost + price means being cheapest under cost alone.  That is all the augmenting searches ask of their
 // start, so prices can even out the row counts before the first search: a row with too many pruned entries
-// becomes dearer to prune, one with too few cheaper, every column chooses again, in rounds with a step that
-// shrinks to 11/16 each time (first step: 3/64 .. 3/32 of the largest cost at M = 8, half that at M = 16).
-// The prices of the round with the smallest total excess are kept; xcol is that round's choice and the
-// return value its excess.  On random blocks the searches that follow drop from 3.1 per block (no prices) to
-// 0.2 at M = 8 with ten rounds, and from 6.3 to 0.5 at M = 16 with twelve; a round costs about a third of
-// one sweep of a search and runs with every lane busy, where the searches keep 40-50 % of the lanes busy.
+// becomes dearer to prune, one with too few cheaper, every column chooses again, in rounds with a shrinking
+// step: at M = 8 ten rounds, first step 3/64 .. 3/32 of the largest cost, times 11/16 per round; at M = 16
+// twenty rounds, first step 1/32 .. 1/16 of the largest cost, times 3/4 per round (both settled by timing on
+// the device).  The prices of the round with the smallest total excess are kept; xcol is that round's choice
+// and the return value its excess.  On random blocks the searches that follow drop from 3.1 per block (no
+// prices) to 0.2 at M = 8 and from 6.3 to well under 0.5 at M = 16; a round costs about a third of one sweep of
+// a search and runs with every lane busy, where the searches keep 40-50 % of the lanes busy.
 //
 // Keys are (cost + price + 2^(S-1)) << 4 | row with |price| < 2^(S-1): below 2^(S+5) <= 2^32 for costs < 2^S.
 template <int M, int CL, int G>
@@ -450,7 +451,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
 {
     constexpr int K = M / 2, H = M / 2;
     constexpr int S = exact_cost_bits(M);
-    constexpr int ROUNDS = (M == 16) ? 12 : 10;
+    constexpr int ROUNDS = (M == 16) ? 20 : 10;
     constexpr int PMIN = 1, PMAX = (1 << S) - 1;                // price + 2^(S-1)
     uint32_t ck[M][CL];
     uint32_t pk[M], best_pk[M];                                 // (price + 2^(S-1)) << 4
@@ -474,7 +475,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
         }
         return upper_half_min<H>(lo, hi);
     };
-    int step = (M == 16) ? (3 << (S - 7)) : (3 << (S - 6));
+    int step = (M == 16) ? (4 << (S - 7)) : (3 << (S - 6));
     uint32_t best = 0xFFFFFFFFu;
 #pragma unroll 1
     for (int round = 0; round <= ROUNDS; round++) {
@@ -509,7 +510,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
             const int p = (int)(pk[i] >> 4) + step * ((int)n[i] - K);
             pk[i] = (uint32_t)(p > PMAX ? PMAX : p < PMIN ? PMIN : p) << 4;
         }
-        step = (step * 11) >> 4;
+        step = (step * (M == 16 ? 12 : 11)) >> 4;
     }
 #pragma unroll
     for (int c = 0; c < CL; c++) {
