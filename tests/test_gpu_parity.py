@@ -200,6 +200,20 @@ def test_exact_structured_blocks(N, M, dt):
     assert obj[0] == pytest.approx(oobj, rel=1e-5)
 
 
+@pytest.mark.parametrize("N,M", NM)
+def test_exact_is_deterministic(N, M):
+    # tie-heavy input has many equally good masks; the same call must return the same one every time (the sort of
+    # blocks inside a workgroup and the searches use no atomics and no arrival order)
+    w = _inputs("ties_bf16", 6 * M, 2064, seed=2600 + M)
+    first = None
+    for rep in range(3):
+        (mask,), obj = run_masks(tm.tmask_exact, [w], N, M)
+        if first is None:
+            first = (mask.copy(), obj.copy())
+        else:
+            assert np.array_equal(mask, first[0]) and np.array_equal(obj, first[1])
+
+
 def test_exact_non_finite_stays_valid():
     w = wl.special_values_f32(32, 256, seed=2300)
     for N, M in NM:
