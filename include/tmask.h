@@ -237,6 +237,17 @@ int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int 
                       tmask_mask_fmt mf, void *hip_stream);
 
 /*
+ * Algorithm 1 and the dense masked copy in one call (Sec. 4, Algorithm 1; Sec. 4.1: the training loop keeps a
+ * dense copy of the weights and masks it before the forward pass): out <- W (.) S with S the mask tmask_approx
+ * computes, in W's type, pruned entries +0.  `mask` is an OUTPUT here and may be NULL for all matrices (then no
+ * mask is written; give it for all or for none, else TMASK_ERR_NULL); `out` may be `w` itself.  One pass over W.
+ * Shape and alignment requirements are those of tmask_approx for `w` and the mask and of tmask_apply_dense for
+ * `out` (16-byte aligned, ld_out >= cols, row pitch a multiple of 16 bytes).  No workspace, no objective.
+ */
+int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                       void *hip_stream);
+
+/*
  * Mask diversity (Sec. 3, Eq. 2): the number of masks a structure constraint admits on a tensor of
  * T elements at sparsity level N/M, as the paper's four closed forms; *log10_md (HOST pointer)
  * receives log10 of it (the counts overflow doubles already for small tensors).  Pure host arithmetic.

@@ -248,6 +248,86 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
     }
 }
 
+// tmask_approx_dense: Algorithm 1 and the masked copy W (.) S in one pass.  Same tiling as the kernels above; the
+// keep flags come from the same routines (HALFN: N = M/2, the lane-mask form at M = 4 and the threshold networks at
+// M = 8, 16; else the rank form for any N).  md.aux = the output matrix, md.pad = its leading dimension in elements;
+// the mask is written only if md.mask is not NULL.
+template <int DT, int M, int FMT, bool HALFN>
+__global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs args)
+{
+    using Ge = Geo<DT, M>;
+    constexpr int C = Ge::C, ES = Ge::ES;
+    const uint32_t tile = blockIdx.x;
+    const MatDev md = args.m[find_matrix(args, tile)];
+    const uint32_t s = (tile - md.tile0) * kThreads + threadIdx.x;
+    const uint32_t gpos = threadIdx.x & (Ge::G - 1);
+    if (s >= md.n_strips)
+        return;
+    const StripPos pos = strip_pos(md, s);
+    uint32_t bits[M];                  // bit c = column c of the lane's strip kept
+    u32x4 raw[M];
+    if constexpr (HALFN && DT == kBF16 && M >= 8) {
+        const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * 8) * 2;
+        const size_t row_bytes = (size_t)md.ld * 2;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
+        (void)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+            bits[i] = bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4);
+        });
+    } else {
+        uint32_t a[M][C];
+        load_strip<DT, M>(md, pos, a, raw);
+        if constexpr (HALFN && M == 4) {
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                bits[i] = 0;
+#pragma unroll
+            for (int b = 0; b < C / 4; b++) {
+                uint32_t k[4][4], bytes[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+#pragma unroll
+                    for (int c = 0; c < 4; c++)
+                        k[i][c] = a[i][4 * b + c];
+                (void)approx_2of4_block(k, bytes);
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    bits[i] |= bytes4_to_bits(bytes[i]) << (4 * b);
+            }
+        } else if constexpr (HALFN && DT == kF32 && M >= 8) {
+            uint32_t rowbytes[M];
+            float unused = 0.f;
+            const bool tie = approx_half_f32<M>(a, gpos, rowbytes, unused);
+            if (__any(tie)) {
+                approx_keep<kF32, M, false>(a, (uint32_t)(M / 2), gpos, bits);
+            } else {
+#pragma unroll
+                for (int i = 0; i < M; i++)
+                    bits[i] = bytes4_to_bits(rowbytes[i]);
+            }
+        } else {
+            approx_keep<DT, M, false>(a, args.K, gpos, bits);
+        }
+    }
+    if (md.mask)
+        store_mask<DT, M, FMT>(md, pos, bits);
+    char *ob = (char *)md.aux + ((size_t)pos.br * M * md.pad + (size_t)pos.sc * C) * ES;
+    const size_t out_row_bytes = (size_t)md.pad * ES;
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        uint32_t d[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            if constexpr (DT == kF32)
+                d[q] &= 0u - ((bits[i] >> q) & 1u);
+            else
+                d[q] &= ((0u - ((bits[i] >> (2 * q)) & 1u)) & 0xFFFFu) | ((0u - ((bits[i] >> (2 * q + 1)) & 1u)) << 16);
+        }
+        stream_store(u32x4{d[0], d[1], d[2], d[3]}, (u32x4 *)(ob + i * out_row_bytes));
+    }
+}
+
 struct ReduceArgs {
     double *objective[kMaxBatch];
     uint32_t tile0[kMaxBatch + 1];
@@ -995,6 +1075,66 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
                 return hip_fail(e, "objective reduce launch");
         }
         partial0 += tiles;
+    }
+    return TMASK_OK;
+}
+
+int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                       void *hip_stream)
+{
+    int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
+    if (rc)
+        return rc;
+    const int64_t es = elem_size((int)dt);
+    int with_mask = 0;
+    for (int i = 0; i < n; i++) {
+        const tmask_dense_desc &p = descs[i];
+        with_mask += p.mask ? 1 : 0;
+        const HostMat h{p.w, p.rows, p.cols, p.ld, const_cast<void *>(p.mask), p.mask_ld, nullptr};
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, p.mask != nullptr)))
+            return rc;
+        if (!p.out)
+            return fail(TMASK_ERR_NULL, "matrix %d: out is NULL", i);
+        if (p.ld_out < p.cols || p.ld_out * es > 0x7FFFFFFFll)
+            return fail(TMASK_ERR_SHAPE, "matrix %d: ld_out=%lld must cover a row of %lld columns", i, (long long)p.ld_out,
+                        (long long)p.cols);
+        if (((uintptr_t)p.out | (uint64_t)(p.ld_out * es)) & 15)
+            return fail(TMASK_ERR_ALIGN, "matrix %d: out and its row pitch must be 16-byte aligned", i);
+    }
+    if (with_mask != 0 && with_mask != n)
+        return fail(TMASK_ERR_NULL, "mask must be given for all matrices or for none (%d of %d have one)", with_mask, n);
+    batch_kernel_t kern = nullptr;
+    const bool halfn = 2 * N == M;
+#define TMASK_PICK(DT, MM, FM) \
+    if ((int)dt == DT && M == MM && (int)mf == FM) \
+        kern = halfn ? approx_dense_kernel<DT, MM, FM, true> : approx_dense_kernel<DT, MM, FM, false>;
+    TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
+    TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
+    TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
+    TMASK_PICK(kBF16, 4, kMaskBits) TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+#undef TMASK_PICK
+    hipStream_t stream = (hipStream_t)hip_stream;
+    for (int first = 0; first < n; first += kMaxBatch) {
+        const int nb = n - first < kMaxBatch ? n - first : kMaxBatch;
+        BatchArgs args;
+        memset(&args, 0, sizeof args);
+        uint32_t tiles = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_dense_desc &p = descs[first + k];
+            const HostMat h{p.w, p.rows, p.cols, p.ld, const_cast<void *>(p.mask), p.mask_ld, nullptr};
+            fill_desc(args.m[k], h, (int)dt, M, tiles);
+            args.m[k].aux = p.out;
+            args.m[k].pad = (uint32_t)p.ld_out;
+            tiles += tiles_of(args.m[k].n_strips);
+        }
+        args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
+        {
+            ProfileScope prof(stream, first + kMaxBatch >= n);
+            hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), 0, stream, args);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "approx_dense kernel launch");
     }
     return TMASK_OK;
 }

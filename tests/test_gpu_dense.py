@@ -99,3 +99,58 @@ def test_rejects_bad_arguments():
         tm.tmask_apply_dense([w[:, :48]], [m[:, :48]], [w[:, :48]], 32, True)   # cols not a multiple of M
     with pytest.raises(tm.TmaskError):
         tm.tmask_apply_dense([w[:, 1:5]], [m[:, :4]], [w[:, 1:5]])      # misaligned
+
+
+# ---------------------------------------------------------------- Algorithm 1 + masked copy in one pass ----------
+
+@pytest.mark.parametrize("with_mask", [True, False])
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (8, 16), (1, 4), (3, 8), (5, 16)])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_approx_dense_matches_approx_then_masked_copy(dt, N, M, fmt, with_mask):
+    """tmask_approx_dense = the oracle's Algorithm 1 followed by its masked copy, bit for bit; the mask, when asked
+    for, is Algorithm 1's.  Batch of ragged shapes with padded rows; tie-heavy and special values included."""
+    shapes = [(5 * M, 1008), (M, 16), (3 * M, 2064)]
+    ws = [_weights(r, c, 8600 + 10 * M + k, dt) for k, (r, c) in enumerate(shapes)]
+    t = wl.tie_heavy_f32(4 * M, 528, seed=8650 + M)
+    sp = wl.special_values_f32(2 * M, 272, seed=8660 + M)
+    if dt == "bf16":
+        t, sp = wl.f32_to_bf16_bits(t), wl.f32_to_bf16_bits(sp)
+    ws += [t, sp]
+    dws = [to_dev(w, ld=w.shape[1] + 24) for w in ws]
+    outs = [torch.full_like(d, 7.0) for d in dws]
+    masks = tm.alloc_masks(dws, fmt) if with_mask else None
+    if masks is not None:
+        for m in masks:
+            m.fill_(0xCD)
+    tm.tmask_approx_dense(dws, masks, outs, N, M, mask_fmt=fmt)
+    torch.cuda.synchronize()
+    from tests.gpu_util import mask_to_host
+    for k, w in enumerate(ws):
+        om, _ = oracle.approx(w, N, M)
+        if masks is not None:
+            assert np.array_equal(mask_to_host(masks[k], w.shape[1], fmt) != 0, om != 0), k
+        got = outs[k].view(torch.int16 if dt == "bf16" else torch.int32).cpu().numpy()
+        want = np.where(om != 0, w.view(np.uint16 if dt == "bf16" else np.uint32), 0)
+        assert np.array_equal(got.view(want.dtype), want), k      # bit patterns: NaN payloads and -0 included
+
+
+def test_approx_dense_in_place_and_errors():
+    w = _weights(64, 256, 8700, "f32")
+    d = to_dev(w)
+    tm.tmask_approx_dense([d], None, [d], 2, 4)                       # out = w
+    torch.cuda.synchronize()
+    om, _ = oracle.approx(w, 2, 4)
+    assert np.array_equal(d.cpu().numpy().view(np.uint32), np.where(om != 0, w.view(np.uint32), 0))
+    d2 = to_dev(w)
+    with pytest.raises(tm.TmaskError) as e:                             # masks for some matrices only
+        lib = tm.load_library()
+        arr = (tm.tmask_dense_desc * 2)()
+        m = tm.alloc_masks([d2])[0]
+        arr[0] = tm.tmask_dense_desc(d2.data_ptr(), 256, m.data_ptr(), 256, d2.data_ptr(), 256, 64, 256)
+        arr[1] = tm.tmask_dense_desc(d2.data_ptr(), 256, None, 0, d2.data_ptr(), 256, 64, 256)
+        tm._check(lib.tmask_approx_dense(arr, 2, tm.TMASK_F32, 2, 4, tm.TMASK_MASK_U8, None))
+    assert e.value.code == tm.TMASK_ERR_NULL
+    with pytest.raises(tm.TmaskError) as e:                             # shape not a multiple of M
+        tm.tmask_approx_dense([d2[:, :252]], None, [torch.empty_like(d2)[:, :252]], 4, 8)
+    assert e.value.code in (tm.TMASK_ERR_SHAPE, tm.TMASK_ERR_ALIGN)
