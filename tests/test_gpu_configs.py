@@ -87,6 +87,13 @@ def test_config2_resnet50_full():
         for g, t in zip(fpacked[k], want):
             assert np.array_equal(g.cpu().numpy().view(np.uint8), t.view(np.uint8)), "fused pack, matrix %d" % k
         assert fobj[k] == pytest.approx(aobj[k], rel=1e-5)
+    # and through the one-pass masked copy (Algorithm 1's mask applied to W, no mask written)
+    douts = [torch.empty_like(w) for w in ws]
+    tm.tmask_approx_dense(ws, None, douts, N, M)
+    torch.cuda.synchronize()
+    for k, w in enumerate(mats):
+        want = np.where(amasks[k].cpu().numpy() != 0, w.view(np.uint32), 0)
+        assert np.array_equal(douts[k].cpu().numpy().view(np.uint32), want), "approx_dense, matrix %d" % k
     # the 7x7 stem conv (64 x 147) is not a multiple of 4 wide: rejected, the caller keeps it dense
     stem = torch.zeros((64, 148), device="cuda")[:, :147]
     with pytest.raises(tm.TmaskError) as e:
