@@ -73,3 +73,64 @@ def test_step_in_a_graph_replays_exactly():
         for a, b in zip(got, want):
             assert np.array_equal(a.cpu().numpy().view(np.uint8), b.cpu().numpy().view(np.uint8)), rep
         del junk
+
+
+def test_four_of_eight_calls_in_a_graph_replay_exactly():
+    """The 4:8 calls (threshold-network approximation, augmenting paths from a priced start, the 4:8 pack kernel, the
+    one-pass compression and the one-pass masked copy) recorded into one graph: replays reproduce the eager run."""
+    N, M = 4, 8
+    shapes = [(64, 64), (128, 576), (512, 1024)]
+    ws = [torch.from_numpy(wl.gaussian_f32(r, c, seed=8100 + k, std=0.05)).cuda() for k, (r, c) in enumerate(shapes)]
+    wsp = tm.alloc_workspace(ws, N, M)
+
+    def state():
+        n = len(ws)
+        return {"amask": tm.alloc_masks(ws), "emask": tm.alloc_masks(ws),
+                "aobj": torch.zeros(n, dtype=torch.float64, device="cuda"),
+                "eobj": torch.zeros(n, dtype=torch.float64, device="cuda"),
+                "packed": [tm.alloc_packed(w, N, M) for w in ws], "fpacked": [tm.alloc_packed(w, N, M) for w in ws],
+                "dense": [torch.empty_like(w) for w in ws]}
+
+    def step(st, stream=None):
+        tm.tmask_approx(ws, st["amask"], N, M, objective=st["aobj"], workspace=wsp, stream=stream)
+        tm.tmask_exact(ws, st["emask"], N, M, objective=st["eobj"], workspace=wsp, stream=stream)
+        tm.tmask_apply_pack(ws, st["emask"], st["packed"], N, M, stream=stream)
+        tm.tmask_approx_pack(ws, None, st["fpacked"], N, M, stream=stream)
+        tm.tmask_approx_dense(ws, None, st["dense"], N, M, stream=stream)
+
+    def snapshot(st):
+        out = [m.clone() for m in st["amask"] + st["emask"] + st["dense"]] + [st["aobj"].clone(), st["eobj"].clone()]
+        for pk in st["packed"] + st["fpacked"]:
+            out += [t.clone() for t in pk]
+        return out
+
+    eager = state()
+    step(eager)
+    torch.cuda.synchronize()
+    want = snapshot(eager)
+    st = state()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(st)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        step(st)
+    for rep in range(3):
+        for m in st["amask"] + st["emask"]:
+            m.fill_(0x5A)
+        for t in st["dense"]:
+            t.fill_(9.0)
+        for pk in st["packed"] + st["fpacked"]:
+            for t in pk:
+                t.view(torch.uint8).fill_(0xEE)
+        junk = torch.randn(1 << 20, device="cuda").sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = snapshot(st)
+        for a, b in zip(got, want):
+            assert np.array_equal(a.cpu().numpy().view(np.uint8), b.cpu().numpy().view(np.uint8)), rep
+        del junk
