@@ -248,6 +248,17 @@ int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int
                        void *hip_stream);
 
 /*
+ * Structured N:M pruning along rows and the dense masked copy in one call, optionally with the bias fix of
+ * Sec. 5 (Sec. 3, constraint 2: in every group of M consecutive elements of a row the N heaviest are kept;
+ * Sec. 5: a model is forced into the N:M pattern this way, and the mean of each group's pruned weights is absorbed
+ * into its kept ones).  out <- what tmask_prune_1d followed by tmask_apply_dense(absorb_mean) gives, in one pass
+ * over W; `mask` is an OUTPUT and may be NULL for all matrices; `out` may be `w` itself.  Requirements as for
+ * tmask_approx_dense.  No workspace, no objective.
+ */
+int tmask_prune_1d_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, int absorb_mean,
+                         tmask_mask_fmt mf, void *hip_stream);
+
+/*
  * Mask diversity (Sec. 3, Eq. 2): the number of masks a structure constraint admits on a tensor of
  * T elements at sparsity level N/M, as the paper's four closed forms; *log10_md (HOST pointer)
  * receives log10 of it (the counts overflow doubles already for small tensors).  Pure host arithmetic.

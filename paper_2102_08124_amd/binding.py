@@ -21,7 +21,7 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_apply_dense", "tmask_approx_dense", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_apply_dense", "tmask_approx_dense", "tmask_prune_1d_dense", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
            "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
@@ -95,6 +95,8 @@ def load_library():
     L.tmask_apply_dense.argtypes = [C.POINTER(tmask_dense_desc), ci, ci, ci, ci, ci, vp]
     L.tmask_approx_dense.restype = ci
     L.tmask_approx_dense.argtypes = [C.POINTER(tmask_dense_desc), ci, ci, ci, ci, ci, vp]
+    L.tmask_prune_1d_dense.restype = ci
+    L.tmask_prune_1d_dense.argtypes = [C.POINTER(tmask_dense_desc), ci, ci, ci, ci, ci, ci, vp]
     L.tmask_mask_diversity.restype = ci
     L.tmask_mask_diversity.argtypes = [ci, ci, ci, C.c_int64, C.POINTER(C.c_double)]
     L.tmask_nm_sparse_probability.restype = ci
@@ -382,9 +384,8 @@ def tmask_apply_dense(ws, masks, outs, M: int = 0, absorb_mean: bool = False, ma
     _check(load_library().tmask_apply_dense(arr, n, dt, M, 1 if absorb_mean else 0, mask_fmt, _stream_ptr(stream)))
 
 
-def tmask_approx_dense(ws, masks, outs, N: int, M: int, mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
-    """Algorithm 1 and the masked copy in one pass: outs[k] = ws[k] with the entries Algorithm 1 prunes set to +0
-    (outs[k] may be ws[k]); masks[k] receives the mask, or masks is None and no mask is written."""
+def _dense_descs(ws, masks, outs):
+    """Descriptors for the calls that write a masked copy and, optionally, the mask they computed."""
     n = len(ws)
     arr = (tmask_dense_desc * n)()
     dt = dtype_code(ws[0])
@@ -401,7 +402,22 @@ def tmask_approx_dense(ws, masks, outs, N: int, M: int, mask_fmt: int = TMASK_MA
             if mr != rows:
                 raise ValueError("w and mask must describe the same matrix")
         arr[k] = tmask_dense_desc(pw, ld, pm, mld, po, old, rows, cols)
+    return arr, n, dt
+
+
+def tmask_approx_dense(ws, masks, outs, N: int, M: int, mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
+    """Algorithm 1 and the masked copy in one pass: outs[k] = ws[k] with the entries Algorithm 1 prunes set to +0
+    (outs[k] may be ws[k]); masks[k] receives the mask, or masks is None and no mask is written."""
+    arr, n, dt = _dense_descs(ws, masks, outs)
     _check(load_library().tmask_approx_dense(arr, n, dt, N, M, mask_fmt, _stream_ptr(stream)))
+
+
+def tmask_prune_1d_dense(ws, masks, outs, N: int, M: int, absorb_mean: bool = False,
+                         mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
+    """N:M pruning along rows and the masked copy in one pass (outs[k] may be ws[k]); with absorb_mean the mean of
+    every row group's pruned weights is added to its kept ones.  masks[k] receives the mask, or masks is None."""
+    arr, n, dt = _dense_descs(ws, masks, outs)
+    _check(load_library().tmask_prune_1d_dense(arr, n, dt, N, M, 1 if absorb_mean else 0, mask_fmt, _stream_ptr(stream)))
 
 
 def tmask_mask_diversity(kind: str, N: int, M: int, T: int) -> float:

@@ -248,13 +248,19 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
     }
 }
 
-// tmask_approx_dense: Algorithm 1 and the masked copy W (.) S in one pass.  Same tiling as the kernels above; the
-// keep flags come from the same routines (HALFN: N = M/2, the lane-mask form at M = 4 and the threshold networks at
-// M = 8, 16; else the rank form for any N).  md.aux = the output matrix, md.pad = its leading dimension in elements;
-// the mask is written only if md.mask is not NULL.
-template <int DT, int M, int FMT, bool HALFN>
+// tmask_approx_dense / tmask_prune_1d_dense: a mask and the masked copy W (.) S in one pass.  Same tiling as the
+// kernels above; the keep flags come from the same routines.  MODE: kDenseApprox = Algorithm 1 in the rank form for
+// any N, kDenseApproxHalf = Algorithm 1 at N = M/2 (the lane-mask form at M = 4, the threshold networks at M = 8, 16),
+// kDenseRow1D = N:M pruning along rows, kDenseRow1DAbsorb = the same with the mean of every row group's pruned
+// weights added to its kept ones (Sec. 5; fp32 sums inside the lane in position order, then across the lanes of the
+// group pairwise; bf16 results rounded to nearest even).  md.aux = the output matrix, md.pad = its leading dimension
+// in elements; the mask is written only if md.mask is not NULL.
+enum { kDenseApprox = 0, kDenseApproxHalf = 1, kDenseRow1D = 2, kDenseRow1DAbsorb = 3 };
+
+template <int DT, int M, int FMT, int MODE>
 __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs args)
 {
+    constexpr bool HALFN = MODE == kDenseApproxHalf;
     using Ge = Geo<DT, M>;
     constexpr int C = Ge::C, ES = Ge::ES;
     const uint32_t tile = blockIdx.x;
@@ -306,6 +312,11 @@ __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs 
                 for (int i = 0; i < M; i++)
                     bits[i] = bytes4_to_bits(rowbytes[i]);
             }
+        } else if constexpr (MODE == kDenseRow1D || MODE == kDenseRow1DAbsorb) {
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                bits[i] = (1u << C) - 1u;
+            row_rank_keep<M, C, Ge::G, Ge::B, false>(a, args.K, gpos, bits);
         } else {
             approx_keep<DT, M, false>(a, args.K, gpos, bits);
         }
@@ -317,12 +328,65 @@ __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs 
 #pragma unroll
     for (int i = 0; i < M; i++) {
         uint32_t d[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+        if constexpr (MODE == kDenseRow1DAbsorb) {
+            constexpr int S = M < C ? M : C;          // entries of one row group inside the lane
+            float v[C];
+            if constexpr (DT == kF32) {
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-            if constexpr (DT == kF32)
-                d[q] &= 0u - ((bits[i] >> q) & 1u);
-            else
-                d[q] &= ((0u - ((bits[i] >> (2 * q)) & 1u)) & 0xFFFFu) | ((0u - ((bits[i] >> (2 * q + 1)) & 1u)) << 16);
+                for (int c = 0; c < 4; c++)
+                    v[c] = __uint_as_float(d[c]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    v[2 * c] = __uint_as_float(d[c] << 16);
+                    v[2 * c + 1] = __uint_as_float(d[c] & 0xFFFF0000u);
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < C / S; g++) {
+                float ps = 0.f;
+                uint32_t pc = 0;
+#pragma unroll
+                for (int c = g * S; c < (g + 1) * S; c++) {
+                    const bool k = (bits[i] >> c) & 1u;
+                    ps += k ? 0.f : v[c];
+                    pc += k ? 0u : 1u;
+                }
+                if constexpr (Ge::G >= 2) {
+                    ps += __uint_as_float(quad_xor<1>(__float_as_uint(ps)));
+                    pc += quad_xor<1>(pc);
+                }
+                if constexpr (Ge::G == 4) {
+                    ps += __uint_as_float(quad_xor<2>(__float_as_uint(ps)));
+                    pc += quad_xor<2>(pc);
+                }
+                const float mean = (pc != 0u && pc != (uint32_t)M) ? ps / (float)pc : 0.f;
+#pragma unroll
+                for (int c = g * S; c < (g + 1) * S; c++)
+                    v[c] = ((bits[i] >> c) & 1u) ? v[c] + mean : 0.f;
+            }
+            if constexpr (DT == kF32) {
+#pragma unroll
+                for (int c = 0; c < 4; c++)
+                    d[c] = __float_as_uint(v[c]);
+            } else {
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    union { bf16x2 h; uint32_t w; } cv;
+                    cv.h = __builtin_convertvector(f32x2{v[2 * c], v[2 * c + 1]}, bf16x2);   // round to nearest even
+                    d[c] = cv.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                if constexpr (DT == kF32)
+                    d[q] &= 0u - ((bits[i] >> q) & 1u);
+                else
+                    d[q] &= ((0u - ((bits[i] >> (2 * q)) & 1u)) & 0xFFFFu) | ((0u - ((bits[i] >> (2 * q + 1)) & 1u)) << 16);
+            }
         }
         stream_store(u32x4{d[0], d[1], d[2], d[3]}, (u32x4 *)(ob + i * out_row_bytes));
     }
@@ -1079,8 +1143,8 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     return TMASK_OK;
 }
 
-int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
-                       void *hip_stream)
+static int run_mask_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                          int mode, void *hip_stream)
 {
     int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
     if (rc)
@@ -1104,10 +1168,12 @@ int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int
     if (with_mask != 0 && with_mask != n)
         return fail(TMASK_ERR_NULL, "mask must be given for all matrices or for none (%d of %d have one)", with_mask, n);
     batch_kernel_t kern = nullptr;
-    const bool halfn = 2 * N == M;
 #define TMASK_PICK(DT, MM, FM) \
     if ((int)dt == DT && M == MM && (int)mf == FM) \
-        kern = halfn ? approx_dense_kernel<DT, MM, FM, true> : approx_dense_kernel<DT, MM, FM, false>;
+        kern = mode == kDenseApprox ? approx_dense_kernel<DT, MM, FM, kDenseApprox> \
+             : mode == kDenseApproxHalf ? approx_dense_kernel<DT, MM, FM, kDenseApproxHalf> \
+             : mode == kDenseRow1D ? approx_dense_kernel<DT, MM, FM, kDenseRow1D> \
+                                   : approx_dense_kernel<DT, MM, FM, kDenseRow1DAbsorb>;
     TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
     TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
     TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
@@ -1134,9 +1200,21 @@ int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int
         }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess)
-            return hip_fail(e, "approx_dense kernel launch");
+            return hip_fail(e, "mask + dense copy kernel launch");
     }
     return TMASK_OK;
+}
+
+int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                       void *hip_stream)
+{
+    return run_mask_dense(descs, n, dt, N, M, mf, 2 * N == M ? kDenseApproxHalf : kDenseApprox, hip_stream);
+}
+
+int tmask_prune_1d_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, int absorb_mean,
+                         tmask_mask_fmt mf, void *hip_stream)
+{
+    return run_mask_dense(descs, n, dt, N, M, mf, absorb_mean ? kDenseRow1DAbsorb : kDenseRow1D, hip_stream);
 }
 
 size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M)

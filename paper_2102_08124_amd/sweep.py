@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Per-kernel timing of the four entry points over dtype x N:M on one square matrix.
 
-    python -m paper_2102_08124_amd.sweep [--side 8192] [--calls approx,exact,score,pack,fused,fusedm,prune1d,flip,dense,absorb,adense] [--dts f32,bf16] [--ms 4,8,16]
+    python -m paper_2102_08124_amd.sweep [--side 8192] [--calls approx,exact,score,pack,fused,fusedm,prune1d,flip,dense,absorb,adense,p1dense,p1absorb] [--dts f32,bf16] [--ms 4,8,16]
 
 Each line: main-kernel time from hipEvents recorded around the kernel (marker overhead removed),
 algorithmic GB/s, fraction of the 8 TB/s HBM peak, weights/s.  Inputs are N(0, 0.02) generated on the
@@ -53,7 +53,7 @@ def main():
             ib = (M - 1).bit_length()
             byts = {"approx": T * es + mb, "exact": T * es + mb, "score": T * es + mb + 4 * T // (M * M),
                     "pack": T * es + mb + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8,
-                    "prune1d": T * es + mb, "flip": 2 * mb, "dense": 2 * T * es + mb, "absorb": 2 * T * es + mb, "adense": 2 * T * es,
+                    "prune1d": T * es + mb, "flip": 2 * mb, "dense": 2 * T * es + mb, "absorb": 2 * T * es + mb, "adense": 2 * T * es, "p1dense": 2 * T * es, "p1absorb": 2 * T * es,
                     "fused": T * es + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8,
                     "fusedm": T * es + mb + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8}
             for call in a.calls.split(","):
@@ -73,6 +73,8 @@ def main():
                         tm.tmask_apply_dense([w], [m], [dense_out], M, call == "absorb", mask_fmt=a.fmt)
                     elif call == "adense":              # Algorithm 1 + masked copy in one pass, no mask written
                         tm.tmask_approx_dense([w], None, [dense_out], N, M, mask_fmt=a.fmt)
+                    elif call in ("p1dense", "p1absorb"):   # row pruning + masked copy (+ mean absorption), no mask written
+                        tm.tmask_prune_1d_dense([w], None, [dense_out], N, M, call == "p1absorb", mask_fmt=a.fmt)
                     elif call == "fused":      # Algorithm 1 + compression in one call, no mask written (2:4 only)
                         tm.tmask_approx_pack([w], None, [packed], N, M, mask_fmt=a.fmt)
                     elif call == "fusedm":     # the same with the mask written too

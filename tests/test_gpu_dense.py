@@ -154,3 +154,50 @@ def test_approx_dense_in_place_and_errors():
     with pytest.raises(tm.TmaskError) as e:                             # shape not a multiple of M
         tm.tmask_approx_dense([d2[:, :252]], None, [torch.empty_like(d2)[:, :252]], 4, 8)
     assert e.value.code in (tm.TMASK_ERR_SHAPE, tm.TMASK_ERR_ALIGN)
+
+
+# ---------------------------------------------------------------- row pruning + masked copy (+ absorption) ------
+
+@pytest.mark.parametrize("absorb", [False, True])
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (8, 16), (1, 4), (3, 8), (12, 16)])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_prune_1d_dense_matches_the_two_steps(dt, N, M, fmt, absorb):
+    """tmask_prune_1d_dense = the oracle's row pruning followed by its masked copy (bit for bit), or by its mean
+    absorption (same tolerance as tmask_apply_dense's); the mask written is the row pruning's."""
+    shapes = [(5 * M, 1008), (M, 16), (3 * M, 2064)]
+    ws = [_weights(r, c, 8800 + 10 * M + k, dt) for k, (r, c) in enumerate(shapes)]
+    t = wl.tie_heavy_f32(4 * M, 528, seed=8850 + M)
+    ws.append(wl.f32_to_bf16_bits(t) if dt == "bf16" else t)
+    dws = [to_dev(w, ld=w.shape[1] + 24) for w in ws]
+    outs = [torch.full_like(d, 7.0) for d in dws]
+    masks = tm.alloc_masks(dws, fmt)
+    tm.tmask_prune_1d_dense(dws, masks, outs, N, M, absorb, mask_fmt=fmt)
+    torch.cuda.synchronize()
+    from tests.gpu_util import mask_to_host
+    for k, w in enumerate(ws):
+        om, _ = oracle.prune_1d(w, N, M)
+        assert np.array_equal(mask_to_host(masks[k], w.shape[1], fmt) != 0, om != 0), k
+        if absorb:
+            _check_absorb(_out_f64(outs[k]), _as_f64(w), om, M, dt == "bf16")
+        else:
+            got = outs[k].view(torch.int16 if dt == "bf16" else torch.int32).cpu().numpy()
+            want = np.where(om != 0, w.view(np.uint16 if dt == "bf16" else np.uint32), 0)
+            assert np.array_equal(got.view(want.dtype), want), k
+
+
+def test_prune_1d_dense_without_mask_equals_apply_dense_on_the_pruned_mask():
+    # no mask written; the result is bit-identical to tmask_prune_1d + tmask_apply_dense with absorption
+    for dt in ("f32", "bf16"):
+        w = _weights(96, 2048, 8900, dt)
+        d = to_dev(w)
+        one = torch.empty_like(d)
+        tm.tmask_prune_1d_dense([d], None, [one], 4, 8, True)
+        m = tm.alloc_masks([d])
+        tm.tmask_prune_1d([d], m, 4, 8)
+        two = torch.empty_like(d)
+        tm.tmask_apply_dense([d], m, [two], 8, True)
+        torch.cuda.synchronize()
+        a = one.view(torch.int16 if dt == "bf16" else torch.int32).cpu().numpy()
+        b = two.view(torch.int16 if dt == "bf16" else torch.int32).cpu().numpy()
+        assert np.array_equal(a, b)
