@@ -207,6 +207,17 @@ def flip_count(mask_a: np.ndarray, mask_b: np.ndarray) -> int:
     return int(((np.asarray(mask_a) != 0) != (np.asarray(mask_b) != 0)).sum())
 
 
+def pattern_violations(w: np.ndarray, mask: np.ndarray) -> int:
+    """Pattern violations of Sec. 5: active (non-zero) weights that the mask removes -- what forcing an N:M pattern on
+    an unstructured-sparse model costs.  -0 counts as zero, NaN as non-zero; bf16 weights come as uint16 bit patterns."""
+    w = np.asarray(w)
+    if w.dtype == np.uint16:
+        nonzero = (w & np.uint16(0x7FFF)) != 0
+    else:
+        nonzero = (w.view(np.uint32) & np.uint32(0x7FFFFFFF)) != 0 if w.dtype == np.float32 else (w != 0) | np.isnan(w)
+    return int((nonzero & (np.asarray(mask) == 0)).sum())
+
+
 def mask_diversity_log10(kind: str, N: int, M: int, T: int) -> float:
     """log10 of the mask diversity of Sec. 3 (Eq. 2) in exact integer arithmetic.
     kind: 'unstructured' | 'structured' | 'transposable' | 'sequential'; T = tensor size, sparsity N/M."""
