@@ -212,6 +212,24 @@ typedef struct {
 int tmask_flip_count(const tmask_flip_desc *descs, int n, tmask_mask_fmt mf, void *hip_stream);
 
 /*
+ * Pattern violations (Sec. 5): the number of active (non-zero) weights that a mask removes -- what forcing an
+ * N:M pattern on an unstructured-sparse model costs (the paper sets N:M per layer so that few such flips are
+ * needed).  count[0] <- #{(i,j): W_ij is not +-0 (NaN counts as active) and S_ij = 0}.  Any mask is accepted.
+ * w, mask, count: device; ld in elements, mask_ld in bytes; mask in format mf; count 8-byte aligned.
+ * Requirements: cols a multiple of 16 bytes' worth of elements, w and its row pitch 16-byte aligned, a U8 mask and
+ * its pitch aligned to 4 (fp32) or 8 (bf16) bytes, BITS masks need cols to be a multiple of 8.  No workspace; exact.
+ */
+typedef struct {
+    const void *w; int64_t ld;
+    const void *mask; int64_t mask_ld;
+    int64_t rows, cols;
+    uint64_t *count;
+} tmask_violation_desc;
+
+int tmask_pattern_violations(const tmask_violation_desc *descs, int n, tmask_dtype dt, tmask_mask_fmt mf,
+                             void *hip_stream);
+
+/*
  * Dense masked copy: out = W (.) S in W's own type, pruned entries as +0 -- the masked weights a
  * training step multiplies with where the sparse products are emulated by dense ones (Sec. 4.1; the
  * dense copy W stays untouched and the mask is taken from it again later).  out may be w itself

@@ -21,8 +21,13 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_apply_dense", "tmask_approx_dense", "tmask_prune_1d_dense", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
+EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_apply_dense", "tmask_approx_dense", "tmask_prune_1d_dense", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_pattern_violations", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
            "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
+
+
+class tmask_violation_desc(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("ld", C.c_int64), ("mask", C.c_void_p), ("mask_ld", C.c_int64),
+                ("rows", C.c_int64), ("cols", C.c_int64), ("count", C.c_void_p)]
 
 
 class TmaskError(RuntimeError):
@@ -97,6 +102,8 @@ def load_library():
     L.tmask_approx_dense.argtypes = [C.POINTER(tmask_dense_desc), ci, ci, ci, ci, ci, vp]
     L.tmask_prune_1d_dense.restype = ci
     L.tmask_prune_1d_dense.argtypes = [C.POINTER(tmask_dense_desc), ci, ci, ci, ci, ci, ci, vp]
+    L.tmask_pattern_violations.restype = ci
+    L.tmask_pattern_violations.argtypes = [C.POINTER(tmask_violation_desc), ci, ci, ci, vp]
     L.tmask_mask_diversity.restype = ci
     L.tmask_mask_diversity.argtypes = [ci, ci, ci, C.c_int64, C.POINTER(C.c_double)]
     L.tmask_nm_sparse_probability.restype = ci
@@ -363,6 +370,24 @@ def tmask_flip_count(masks_a, masks_b, cols, flips: torch.Tensor, mask_fmt: int 
             raise ValueError("masks must have the same shape")
         arr[k] = tmask_flip_desc(pa, lda, pb, ldb, ra, int(cols[k]), flips.data_ptr() + 8 * k)
     _check(load_library().tmask_flip_count(arr, n, mask_fmt, _stream_ptr(stream)))
+
+
+def tmask_pattern_violations(ws, masks, counts: torch.Tensor, mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
+    """counts[k] (int64 device tensor) = number of non-zero entries of ws[k] that masks[k] removes (Sec. 5)."""
+    n = len(ws)
+    if counts.dtype != torch.int64 or counts.numel() < n or not counts.is_contiguous():
+        raise ValueError("counts must be a contiguous int64 tensor with one entry per matrix")
+    arr = (tmask_violation_desc * n)()
+    dt = dtype_code(ws[0])
+    for k, (w, m) in enumerate(zip(ws, masks)):
+        if dtype_code(w) != dt:
+            raise ValueError("all matrices of a call share one dtype")
+        pw, rows, cols, ld = _mat2d(w, "w")
+        pm, mr, _, mld = _mat2d(m, "mask")
+        if mr != rows:
+            raise ValueError("w and mask must describe the same matrix")
+        arr[k] = tmask_violation_desc(pw, ld, pm, mld, rows, cols, counts.data_ptr() + 8 * k)
+    _check(load_library().tmask_pattern_violations(arr, n, dt, mask_fmt, _stream_ptr(stream)))
 
 
 def tmask_apply_dense(ws, masks, outs, M: int = 0, absorb_mean: bool = False, mask_fmt: int = TMASK_MASK_U8,

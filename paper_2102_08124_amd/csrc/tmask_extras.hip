@@ -1,5 +1,5 @@
 // Small companions of the mask kernels: the mask-flip counter of a dynamic-mask training loop, the dense masked
-// copy with mean absorption, and the mask-diversity formulas (arXiv 2102.08124, Sec. 3, Eq. 2) with the N:M probability of Sec. 5, Eq. 4.
+// copy with mean absorption, the pattern-violation counter of Sec. 5, and the mask-diversity formulas (arXiv 2102.08124, Sec. 3, Eq. 2) with the N:M probability of Sec. 5, Eq. 4.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -393,6 +393,153 @@ extern "C" int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dty
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return hip_fail(e, "apply_dense launch");
+    }
+    return TMASK_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Pattern violations (Sec. 5): non-zero weights that a mask removes.  Streams W and the mask like the dense copy
+// (DenseDev with `out` = the matrix' counter), counts with integer atomics like the flip counter.
+// ---------------------------------------------------------------------------------------------------------
+namespace tmask {
+
+__global__ void violation_zero_kernel(const DenseArgs args)
+{
+    if (threadIdx.x < args.n)
+        *(unsigned long long *)args.d[threadIdx.x].out = 0ull;
+}
+
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void violation_count_kernel(const DenseArgs args)
+{
+    constexpr int C = DT == kF32 ? 4 : 8;
+    __shared__ uint32_t red[kThreads / 64];
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].wg0 <= blockIdx.x)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const DenseDev d = args.d[lo];
+    const uint32_t total = d.rows * d.chunks_per_row;
+    const uint32_t stride = d.n_wg * kThreads;
+    uint32_t cnt = 0;
+    constexpr int U = 4;
+    for (uint32_t base = (blockIdx.x - d.wg0) * U * kThreads; base < total; base += U * stride) {
+        u32x4 raw[U];
+        uint32_t keep[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const uint32_t c = base + (uint32_t)u * kThreads + threadIdx.x;
+            raw[u] = u32x4{0u, 0u, 0u, 0u};
+            keep[u] = 0u;
+            if (c < total) {
+                const uint32_t r = c / d.chunks_per_row, j = c - r * d.chunks_per_row;
+                raw[u] = __builtin_nontemporal_load((const u32x4 *)(d.w + (size_t)r * d.ld_b + (size_t)j * 16u));
+                const unsigned char *mrow = d.mask + (size_t)r * d.mask_ld;
+                if constexpr (FMT == kMaskU8) {
+                    if constexpr (C == 4) {
+                        keep[u] = bytes4_to_bits(__builtin_nontemporal_load((const uint32_t *)(mrow + (size_t)j * 4u)));
+                    } else {
+                        const u32x2 mb = __builtin_nontemporal_load((const u32x2 *)(mrow + (size_t)j * 8u));
+                        keep[u] = bytes4_to_bits(mb.x) | (bytes4_to_bits(mb.y) << 4);
+                    }
+                } else {
+                    if constexpr (C == 4)
+                        keep[u] = ((uint32_t)mrow[j >> 1] >> ((j & 1u) * 4u)) & 0xFu;
+                    else
+                        keep[u] = (uint32_t)mrow[j];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const uint32_t q[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+            uint32_t active = 0;                         // bit c = entry c is not +-0
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                if constexpr (DT == kF32) {
+                    active |= ((q[c] & 0x7FFFFFFFu) != 0u ? 1u : 0u) << c;
+                } else {
+                    active |= ((q[c] & 0x00007FFFu) != 0u ? 1u : 0u) << (2 * c);
+                    active |= ((q[c] & 0x7FFF0000u) != 0u ? 1u : 0u) << (2 * c + 1);
+                }
+            }
+            cnt += (uint32_t)__builtin_popcount(active & ~keep[u]);      // lanes past the end hold zeros: nothing active
+        }
+    }
+    const uint32_t t = block_sum(cnt, red);
+    if (threadIdx.x == 0 && t)
+        atomicAdd((unsigned long long *)d.out, (unsigned long long)t);   // integer sum: order does not matter
+}
+
+}  // namespace tmask
+
+extern "C" int tmask_pattern_violations(const tmask_violation_desc *descs, int n, tmask_dtype dt, tmask_mask_fmt mf,
+                                        void *hip_stream)
+{
+    if (!descs)
+        return fail(TMASK_ERR_NULL, "descriptor array is NULL");
+    if (n <= 0)
+        return fail(TMASK_ERR_SHAPE, "n=%d must be positive", n);
+    if (dt != TMASK_F32 && dt != TMASK_BF16)
+        return fail(TMASK_ERR_DTYPE, "unknown dtype %d", (int)dt);
+    if (mf != TMASK_MASK_U8 && mf != TMASK_MASK_BITS)
+        return fail(TMASK_ERR_DTYPE, "unknown mask format %d", (int)mf);
+    const int64_t es = dt == TMASK_F32 ? 4 : 2, per_chunk = 16 / es;
+    for (int i = 0; i < n; i++) {
+        const tmask_violation_desc &f = descs[i];
+        if (!f.w || !f.mask || !f.count)
+            return fail(TMASK_ERR_NULL, "matrix %d: w, mask or count is NULL", i);
+        if (f.rows <= 0 || f.cols <= 0 || f.cols % per_chunk || (mf == TMASK_MASK_BITS && f.cols % 8))
+            return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld (cols must be a multiple of %lld%s)", i,
+                        (long long)f.rows, (long long)f.cols, (long long)per_chunk,
+                        mf == TMASK_MASK_BITS ? " and of 8 for BITS masks" : "");
+        const int64_t mask_row = mf == TMASK_MASK_U8 ? f.cols : f.cols / 8;
+        if (f.ld < f.cols || f.mask_ld < mask_row || f.ld * es > 0x7FFFFFFFll || f.mask_ld > 0x7FFFFFFFll ||
+            f.rows * (f.cols / per_chunk) >= 0xFFFFFFFFll)
+            return fail(TMASK_ERR_SHAPE, "matrix %d: leading dimensions must cover a row; at most 2^32 - 1 chunks of 16 bytes", i);
+        if (((uintptr_t)f.w | (uint64_t)(f.ld * es)) & 15)
+            return fail(TMASK_ERR_ALIGN, "matrix %d: w and its row pitch must be 16-byte aligned", i);
+        if (mf == TMASK_MASK_U8 && (((uintptr_t)f.mask | (uint64_t)f.mask_ld) & (uint64_t)(per_chunk - 1)))
+            return fail(TMASK_ERR_ALIGN, "matrix %d: a U8 mask and its row pitch must be %lld-byte aligned", i,
+                        (long long)per_chunk);
+        if ((uintptr_t)f.count & 7)
+            return fail(TMASK_ERR_ALIGN, "matrix %d: count must be 8-byte aligned", i);
+    }
+    dense_kernel_t kern = dt == TMASK_F32 ? (mf == TMASK_MASK_U8 ? violation_count_kernel<kF32, kMaskU8>
+                                                                 : violation_count_kernel<kF32, kMaskBits>)
+                                          : (mf == TMASK_MASK_U8 ? violation_count_kernel<kBF16, kMaskU8>
+                                                                 : violation_count_kernel<kBF16, kMaskBits>);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    for (int first = 0; first < n; first += kMaxDenseBatch) {
+        const int nb = n - first < kMaxDenseBatch ? n - first : kMaxDenseBatch;
+        DenseArgs args;
+        memset(&args, 0, sizeof args);
+        uint32_t wgs = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_violation_desc &f = descs[first + k];
+            DenseDev &d = args.d[k];
+            d.w = (const char *)f.w; d.mask = (const unsigned char *)f.mask; d.out = (char *)f.count;
+            d.rows = (uint32_t)f.rows; d.chunks_per_row = (uint32_t)(f.cols / per_chunk);
+            d.ld_b = (uint32_t)(f.ld * es); d.ld_out_b = 0; d.mask_ld = (uint32_t)f.mask_ld;
+            const uint64_t chunks = (uint64_t)d.rows * d.chunks_per_row;
+            uint64_t nw = (chunks + 4ull * kThreads - 1) / (4ull * kThreads);
+            nw = nw < 1 ? 1 : nw > 1024 ? 1024 : nw;       // one atomic per workgroup: keep them few, as in the flip counter
+            d.n_wg = (uint32_t)nw; d.wg0 = wgs;
+            wgs += d.n_wg;
+        }
+        args.n = (uint32_t)nb;
+        hipLaunchKernelGGL(violation_zero_kernel, dim3(1), dim3(kMaxDenseBatch), 0, stream, args);
+        {
+            ProfileScope prof(stream, first + kMaxDenseBatch >= n);
+            hipLaunchKernelGGL(kern, dim3(wgs), dim3(kThreads), 0, stream, args);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "pattern violation count launch");
     }
     return TMASK_OK;
 }

@@ -1,0 +1,71 @@
+"""GPU parity for tmask_pattern_violations (Sec. 5): exact counts against the oracle's definition."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2102_08124_amd import workloads as wl
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2102_08124_amd import binding as tm            # noqa: E402
+from tests.gpu_util import mask_to_dev, to_dev             # noqa: E402
+
+
+def _sparse_weights(rows, cols, seed, dt, rho):
+    rng = np.random.default_rng(seed)
+    w = wl.gaussian_f32(rows, cols, seed=seed)
+    w[rng.random(w.shape) < rho] = 0.0
+    w[rng.random(w.shape) < 0.01] = -0.0               # a zero all the same
+    w[rng.random(w.shape) < 0.002] = np.nan            # an active weight
+    w[rng.random(w.shape) < 0.002] = np.float32(1e-42)  # denormal: active
+    return w if dt == "f32" else wl.f32_to_bf16_bits(w)
+
+
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_pattern_violations_batch(dt, fmt):
+    shapes = [(64, 64), (5, 1008), (128, 4096), (3, 8), (17, 24), (1000, 1040)]
+    ws = [_sparse_weights(r, c, 9100 + k, dt, 0.6) for k, (r, c) in enumerate(shapes)]
+    rng = np.random.default_rng(91)
+    masks = [(rng.random(w.shape) < 0.5).astype(np.uint8) for w in ws]
+    masks[0][:] = 1
+    masks[1][:] = 0
+    counts = torch.full((len(ws),), -1, dtype=torch.int64, device="cuda")
+    tm.tmask_pattern_violations([to_dev(w, ld=w.shape[1] + 16) for w in ws], [mask_to_dev(m, fmt) for m in masks], counts,
+                                mask_fmt=fmt)
+    torch.cuda.synchronize()
+    got = counts.cpu().numpy()
+    for k, (w, m) in enumerate(zip(ws, masks)):
+        assert int(got[k]) == oracle.pattern_violations(w, m), k
+    assert int(got[0]) == 0
+
+
+def test_forcing_a_pattern_on_an_unstructured_sparse_matrix():
+    """The use the paper makes of it: a matrix with 70 % zeros is forced into 4:8 and into 2:8 along rows; both
+    counts equal the oracle's, and keeping fewer entries per group removes more active weights."""
+    w = _sparse_weights(512, 2048, 9200, "f32", 0.7)
+    d = to_dev(w)
+    counts = torch.zeros(2, dtype=torch.int64, device="cuda")
+    masks = tm.alloc_masks([d, d])
+    tm.tmask_prune_1d([d], [masks[0]], 4, 8)
+    tm.tmask_prune_1d([d], [masks[1]], 2, 8)
+    tm.tmask_pattern_violations([d, d], masks, counts)
+    torch.cuda.synchronize()
+    want = [oracle.pattern_violations(w, oracle.prune_1d(w, N, 8)[0]) for N in (4, 2)]
+    assert [int(c) for c in counts.cpu().numpy()] == want
+    assert want[0] < want[1]          # keeping fewer per group removes more active weights
+
+
+def test_pattern_violations_argument_errors():
+    w = to_dev(wl.gaussian_f32(16, 16, seed=9300))
+    m = tm.alloc_masks([w])[0]
+    with pytest.raises(ValueError):
+        tm.tmask_pattern_violations([w], [m], torch.zeros(1, dtype=torch.int32, device="cuda"))
+    lib = tm.load_library()
+    arr = (tm.tmask_violation_desc * 1)()
+    arr[0] = tm.tmask_violation_desc(w.data_ptr(), 16, m.data_ptr(), 16, 16, 16, None)
+    assert lib.tmask_pattern_violations(arr, 1, tm.TMASK_F32, tm.TMASK_MASK_U8, None) == tm.TMASK_ERR_NULL
+    c = torch.zeros(1, dtype=torch.int64, device="cuda")
+    arr[0] = tm.tmask_violation_desc(w.data_ptr(), 16, m.data_ptr(), 16, 16, 18, c.data_ptr())
+    assert lib.tmask_pattern_violations(arr, 1, tm.TMASK_F32, tm.TMASK_MASK_U8, None) == tm.TMASK_ERR_SHAPE
