@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Per-kernel timing of the four entry points over dtype x N:M on one square matrix.
 
-    python -m paper_2102_08124_amd.sweep [--side 8192] [--calls approx,exact,score,pack,fused,fusedm,prune1d,flip,dense,absorb,adense,p1dense,p1absorb] [--dts f32,bf16] [--ms 4,8,16]
+    python -m paper_2102_08124_amd.sweep [--side 8192] [--calls approx,exact,score,pack,fused,fusedm,prune1d,flip,dense,absorb,adense,p1dense,p1absorb,viol] [--dts f32,bf16] [--ms 4,8,16]
 
 Each line: main-kernel time from hipEvents recorded around the kernel (marker overhead removed),
 algorithmic GB/s, fraction of the 8 TB/s HBM peak, weights/s.  Inputs are N(0, 0.02) generated on the
@@ -48,12 +48,13 @@ def main():
             packeds = [tm.alloc_packed(ws[0], N, M) for _ in range(nb)]
             flips = torch.zeros(1, dtype=torch.int64, device="cuda")
             dense_outs = [torch.empty_like(ws[0]) for _ in range(nb)]
+            viol_count = torch.zeros(1, dtype=torch.int64, device="cuda")
             T = side * side
             mb = T if a.fmt == 0 else T // 8
             ib = (M - 1).bit_length()
             byts = {"approx": T * es + mb, "exact": T * es + mb, "score": T * es + mb + 4 * T // (M * M),
                     "pack": T * es + mb + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8,
-                    "prune1d": T * es + mb, "flip": 2 * mb, "dense": 2 * T * es + mb, "absorb": 2 * T * es + mb, "adense": 2 * T * es, "p1dense": 2 * T * es, "p1absorb": 2 * T * es,
+                    "prune1d": T * es + mb, "flip": 2 * mb, "dense": 2 * T * es + mb, "absorb": 2 * T * es + mb, "adense": 2 * T * es, "p1dense": 2 * T * es, "p1absorb": 2 * T * es, "viol": T * es + mb,
                     "fused": T * es + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8,
                     "fusedm": T * es + mb + 2 * (T * N // M) * es + 2 * (T * N // M) * ib // 8}
             for call in a.calls.split(","):
@@ -73,6 +74,8 @@ def main():
                         tm.tmask_apply_dense([w], [m], [dense_out], M, call == "absorb", mask_fmt=a.fmt)
                     elif call == "adense":              # Algorithm 1 + masked copy in one pass, no mask written
                         tm.tmask_approx_dense([w], None, [dense_out], N, M, mask_fmt=a.fmt)
+                    elif call == "viol":                # pattern violations: non-zero weights the mask removes
+                        tm.tmask_pattern_violations([w], [m], viol_count, mask_fmt=a.fmt)
                     elif call in ("p1dense", "p1absorb"):   # row pruning + masked copy (+ mean absorption), no mask written
                         tm.tmask_prune_1d_dense([w], None, [dense_out], N, M, call == "p1absorb", mask_fmt=a.fmt)
                     elif call == "fused":      # Algorithm 1 + compression in one call, no mask written (2:4 only)
@@ -81,7 +84,7 @@ def main():
                         tm.tmask_approx_pack([w], [m], [packed], N, M, mask_fmt=a.fmt)
                     else:
                         tm.tmask_apply_pack([w], [m], [packed], N, M, mask_fmt=a.fmt)
-                if call in ("score", "pack", "flip", "dense", "absorb"):
+                if call in ("score", "pack", "flip", "dense", "absorb", "viol"):
                     for k in range(nb):
                         tm.tmask_approx([ws[k]], [masks[k]], N, M, mask_fmt=a.fmt)
                 run(0)
