@@ -103,6 +103,39 @@ __device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_
 }
 
 
+// The row half alone (structured N:M pruning along rows at N = M/2): bit c of bits[i] = entry (i, c) of the lane's
+// strip is among the N heaviest of its row group under the (magnitude, position) order.
+template <int M>
+__device__ __forceinline__ void row_half_keep_bf16(const u32x4 (&raw)[M], uint32_t gpos, uint32_t (&bits)[M])
+{
+    const uint32_t j0 = (M == 16) ? gpos * 8u : 0u;
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        uint32_t a[8];
+#pragma unroll
+        for (int c = 0; c < 8; c++)
+            a[c] = bf16_mag_hi(raw[i], c) | (j0 + (uint32_t)c);
+        uint32_t trow;
+        if constexpr (M == 8) {
+            uint32_t lo[4] = {a[0], a[1], a[2], a[3]};
+            uint32_t hi[4] = {a[4], a[5], a[6], a[7]};
+            trow = upper_half_min<4>(lo, hi);
+        } else {
+            uint32_t srt[8];
+#pragma unroll
+            for (int c = 0; c < 8; c++)
+                srt[c] = a[c];
+            trow = upper_half_min_pair<8>(srt);
+        }
+        uint32_t b = 0;
+#pragma unroll
+        for (int c = 0; c < 8; c++)
+            b |= (a[c] >= trow ? 1u : 0u) << c;
+        bits[i] = b;
+        __builtin_amdgcn_sched_barrier(0);   // one row at a time
+    }
+}
+
 // =================================================================================================
 // fp32, N = M/2, M = 8 or 16.  A 31-bit magnitude leaves no room for the index, so thresholds are
 // taken on magnitudes alone: t = N-th largest of a line, u = (N+1)-th largest.  If t > u in every

@@ -50,10 +50,19 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
         } else if constexpr (SOLVER == kSolveRow1D) {
             // structured N:M along rows only: an entry is kept iff at least K entries of its group of M
             // precede it in the (magnitude, position) order
+            bool done = false;
+            if constexpr (DT == kBF16 && M >= 8) {
+                if (2u * args.K == (uint32_t)M) {      // N = M/2: thresholds on unique keys instead of pairwise ranks
+                    row_half_keep_bf16<M>(raw, gpos, bits);
+                    done = true;
+                }
+            }
+            if (!done) {
 #pragma unroll
-            for (int i = 0; i < M; i++)
-                bits[i] = (1u << Ge::C) - 1u;
-            row_rank_keep<M, Ge::C, Ge::G, Ge::B, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
+                for (int i = 0; i < M; i++)
+                    bits[i] = (1u << Ge::C) - 1u;
+                row_rank_keep<M, Ge::C, Ge::G, Ge::B, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
+            }
         } else if constexpr (M == 4) {
             {
 #pragma unroll
@@ -255,12 +264,17 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
 // weights added to its kept ones (Sec. 5; fp32 sums inside the lane in position order, then across the lanes of the
 // group pairwise; bf16 results rounded to nearest even).  md.aux = the output matrix, md.pad = its leading dimension
 // in elements; the mask is written only if md.mask is not NULL.
-enum { kDenseApprox = 0, kDenseApproxHalf = 1, kDenseRow1D = 2, kDenseRow1DAbsorb = 3 };
+// kDenseRow1DHalf / kDenseRow1DHalfAbsorb: the row modes at N = M/2 for bf16 with M = 8, 16, where the row rule is a
+// threshold on unique keys (row_half_keep_bf16) and only the raw rows need registers.
+enum { kDenseApprox = 0, kDenseApproxHalf = 1, kDenseRow1D = 2, kDenseRow1DAbsorb = 3, kDenseRow1DHalf = 4, kDenseRow1DHalfAbsorb = 5 };
 
 template <int DT, int M, int FMT, int MODE>
 __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs args)
 {
     constexpr bool HALFN = MODE == kDenseApproxHalf;
+    constexpr bool ROWHALF = MODE == kDenseRow1DHalf || MODE == kDenseRow1DHalfAbsorb;
+    constexpr bool ABSORB = MODE == kDenseRow1DAbsorb || MODE == kDenseRow1DHalfAbsorb;
+    static_assert(!ROWHALF || (DT == kBF16 && M >= 8), "the threshold form of the row rule exists for bf16, M = 8, 16");
     using Ge = Geo<DT, M>;
     constexpr int C = Ge::C, ES = Ge::ES;
     const uint32_t tile = blockIdx.x;
@@ -272,15 +286,19 @@ __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs 
     const StripPos pos = strip_pos(md, s);
     uint32_t bits[M];                  // bit c = column c of the lane's strip kept
     u32x4 raw[M];
-    if constexpr (HALFN && DT == kBF16 && M >= 8) {
+    if constexpr ((HALFN || ROWHALF) && DT == kBF16 && M >= 8) {
         const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * 8) * 2;
         const size_t row_bytes = (size_t)md.ld * 2;
 #pragma unroll
         for (int i = 0; i < M; i++)
             raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
-        (void)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
-            bits[i] = bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4);
-        });
+        if constexpr (HALFN) {
+            (void)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+                bits[i] = bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4);
+            });
+        } else {
+            row_half_keep_bf16<M>(raw, gpos, bits);
+        }
     } else {
         uint32_t a[M][C];
         load_strip<DT, M>(md, pos, a, raw);
@@ -328,7 +346,7 @@ __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs 
 #pragma unroll
     for (int i = 0; i < M; i++) {
         uint32_t d[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
-        if constexpr (MODE == kDenseRow1DAbsorb) {
+        if constexpr (ABSORB) {
             constexpr int S = M < C ? M : C;          // entries of one row group inside the lane
             float v[C];
             if constexpr (DT == kF32) {
@@ -1173,11 +1191,17 @@ static int run_mask_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, 
         kern = mode == kDenseApprox ? approx_dense_kernel<DT, MM, FM, kDenseApprox> \
              : mode == kDenseApproxHalf ? approx_dense_kernel<DT, MM, FM, kDenseApproxHalf> \
              : mode == kDenseRow1D ? approx_dense_kernel<DT, MM, FM, kDenseRow1D> \
-                                   : approx_dense_kernel<DT, MM, FM, kDenseRow1DAbsorb>;
+             : mode == kDenseRow1DAbsorb ? approx_dense_kernel<DT, MM, FM, kDenseRow1DAbsorb> : kern;
     TMASK_PICK(kF32, 4, kMaskU8) TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8)
     TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
     TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
     TMASK_PICK(kBF16, 4, kMaskBits) TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+#undef TMASK_PICK
+#define TMASK_PICK(MM, FM) \
+    if ((int)dt == kBF16 && M == MM && (int)mf == FM && mode >= kDenseRow1DHalf) \
+        kern = mode == kDenseRow1DHalf ? approx_dense_kernel<kBF16, MM, FM, kDenseRow1DHalf> \
+                                       : approx_dense_kernel<kBF16, MM, FM, kDenseRow1DHalfAbsorb>;
+    TMASK_PICK(8, kMaskU8) TMASK_PICK(16, kMaskU8) TMASK_PICK(8, kMaskBits) TMASK_PICK(16, kMaskBits)
 #undef TMASK_PICK
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int first = 0; first < n; first += kMaxBatch) {
@@ -1214,7 +1238,10 @@ int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int
 int tmask_prune_1d_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, int absorb_mean,
                          tmask_mask_fmt mf, void *hip_stream)
 {
-    return run_mask_dense(descs, n, dt, N, M, mf, absorb_mean ? kDenseRow1DAbsorb : kDenseRow1D, hip_stream);
+    const bool half = dt == TMASK_BF16 && M >= 8 && 2 * N == M;
+    const int mode = half ? (absorb_mean ? kDenseRow1DHalfAbsorb : kDenseRow1DHalf)
+                          : (absorb_mean ? kDenseRow1DAbsorb : kDenseRow1D);
+    return run_mask_dense(descs, n, dt, N, M, mf, mode, hip_stream);
 }
 
 size_t tmask_workspace_bytes(const tmask_mat *mats, int n_mats, int N, int M)
