@@ -262,7 +262,14 @@ int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int 
  * Shape and alignment requirements are those of tmask_approx for `w` and the mask and of tmask_apply_dense for
  * `out` (16-byte aligned, ld_out >= cols, row pitch a multiple of 16 bytes).  No workspace, no objective.
  */
-int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+typedef struct {
+    const void *w; int64_t ld;
+    void *mask; int64_t mask_ld;          /* output, nullable (see above) */
+    void *out; int64_t ld_out;
+    int64_t rows, cols;
+} tmask_mask_dense_desc;                  /* same layout as tmask_dense_desc; the mask is written here */
+
+int tmask_approx_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
                        void *hip_stream);
 
 /*
@@ -273,7 +280,7 @@ int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int
  * over W; `mask` is an OUTPUT and may be NULL for all matrices; `out` may be `w` itself.  Requirements as for
  * tmask_approx_dense.  No workspace, no objective.
  */
-int tmask_prune_1d_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, int absorb_mean,
+int tmask_prune_1d_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, int absorb_mean,
                          tmask_mask_fmt mf, void *hip_stream);
 
 /*

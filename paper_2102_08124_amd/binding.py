@@ -64,6 +64,9 @@ class tmask_dense_desc(C.Structure):
                 ("out", C.c_void_p), ("ld_out", C.c_int64), ("rows", C.c_int64), ("cols", C.c_int64)]
 
 
+tmask_mask_dense_desc = tmask_dense_desc
+
+
 class tmask_score_out(C.Structure):
     _fields_ = [("retained_l1", C.c_double), ("total_l1", C.c_double), ("kept", C.c_uint64),
                 ("row_violations", C.c_uint64), ("col_violations", C.c_uint64),

@@ -1161,7 +1161,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     return TMASK_OK;
 }
 
-static int run_mask_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+static int run_mask_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
                           int mode, void *hip_stream)
 {
     int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
@@ -1170,9 +1170,9 @@ static int run_mask_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, 
     const int64_t es = elem_size((int)dt);
     int with_mask = 0;
     for (int i = 0; i < n; i++) {
-        const tmask_dense_desc &p = descs[i];
+        const tmask_mask_dense_desc &p = descs[i];
         with_mask += p.mask ? 1 : 0;
-        const HostMat h{p.w, p.rows, p.cols, p.ld, const_cast<void *>(p.mask), p.mask_ld, nullptr};
+        const HostMat h{p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, nullptr};
         if ((rc = check_mat(h, i, (int)dt, M, (int)mf, p.mask != nullptr)))
             return rc;
         if (!p.out)
@@ -1210,8 +1210,8 @@ static int run_mask_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, 
         memset(&args, 0, sizeof args);
         uint32_t tiles = 0;
         for (int k = 0; k < nb; k++) {
-            const tmask_dense_desc &p = descs[first + k];
-            const HostMat h{p.w, p.rows, p.cols, p.ld, const_cast<void *>(p.mask), p.mask_ld, nullptr};
+            const tmask_mask_dense_desc &p = descs[first + k];
+            const HostMat h{p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, nullptr};
             fill_desc(args.m[k], h, (int)dt, M, tiles);
             args.m[k].aux = p.out;
             args.m[k].pad = (uint32_t)p.ld_out;
@@ -1229,13 +1229,13 @@ static int run_mask_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, 
     return TMASK_OK;
 }
 
-int tmask_approx_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+int tmask_approx_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
                        void *hip_stream)
 {
     return run_mask_dense(descs, n, dt, N, M, mf, 2 * N == M ? kDenseApproxHalf : kDenseApprox, hip_stream);
 }
 
-int tmask_prune_1d_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, int absorb_mean,
+int tmask_prune_1d_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype dt, int N, int M, int absorb_mean,
                          tmask_mask_fmt mf, void *hip_stream)
 {
     const bool half = dt == TMASK_BF16 && M >= 8 && 2 * N == M;

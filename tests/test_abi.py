@@ -40,4 +40,6 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(tm.tmask_fused_desc) == 88
     assert ctypes.sizeof(tm.tmask_flip_desc) == 56
     assert ctypes.sizeof(tm.tmask_dense_desc) == 64
+    assert tm.tmask_mask_dense_desc is tm.tmask_dense_desc          # same layout, writable mask on the C side
+    assert ctypes.sizeof(tm.tmask_violation_desc) == 56
     assert ctypes.sizeof(tm.tmask_score_out) == 56
