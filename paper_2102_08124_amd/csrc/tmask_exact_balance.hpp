@@ -83,40 +83,40 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
         const size_t col = (size_t)pos.sc * Ge::C + (HALF ? (unit & 1u) * 4u : 0u);
         return (const char *)md.w + ((size_t)pos.br * M * md.ld + col) * Ge::ES;
     };
-    auto load_block = [&](bool ok, uint32_t strip_no) {
-#pragma unroll
-    for (int i = 0; i < M; i++) {
-        uint32_t d[4];
-#pragma unroll
-        for (int q = 0; q < 4; q++) {
-            if constexpr (DT == kF32) {
-                const uint32_t j = gpos * 4u + (uint32_t)q;
-                d[q] = (((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u;
-            } else if (HALF && q >= 2) {
-                d[q] = 0u;
-            } else {
-                const uint32_t j = gpos * (uint32_t)C + 2u * (uint32_t)q;
-                d[q] = ((((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F80u : 0u) |
-                       ((((uint32_t)i + j + 1u) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u);
-            }
-        }
-        raw[i] = u32x4{d[0], d[1], d[2], d[3]};
-    }
-    if (ok) {
-        const char *base = block_base(strip_no);
-        const size_t row_bytes = (size_t)md.ld * Ge::ES;
+    auto load_block = [&](bool ok, uint32_t unit) {
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            if constexpr (PARK) {
-                raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
-            } else if constexpr (HALF) {
-                const u32x2 h = *(const u32x2 *)(base + i * row_bytes);
-                raw[i] = u32x4{h.x, h.y, 0u, 0u};
-            } else {
-                raw[i] = *(const u32x4 *)(base + i * row_bytes);     // read again below: may stay in the cache
+            uint32_t d[4];
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                if constexpr (DT == kF32) {
+                    const uint32_t j = gpos * 4u + (uint32_t)q;
+                    d[q] = (((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u;
+                } else if (HALF && q >= 2) {
+                    d[q] = 0u;
+                } else {
+                    const uint32_t j = gpos * (uint32_t)C + 2u * (uint32_t)q;
+                    d[q] = ((((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F80u : 0u) |
+                           ((((uint32_t)i + j + 1u) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u);
+                }
+            }
+            raw[i] = u32x4{d[0], d[1], d[2], d[3]};
+        }
+        if (ok) {
+            const char *base = block_base(unit);
+            const size_t row_bytes = (size_t)md.ld * Ge::ES;
+#pragma unroll
+            for (int i = 0; i < M; i++) {
+                if constexpr (PARK) {
+                    raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
+                } else if constexpr (HALF) {
+                    const u32x2 h = *(const u32x2 *)(base + i * row_bytes);
+                    raw[i] = u32x4{h.x, h.y, 0u, 0u};
+                } else {
+                    raw[i] = *(const u32x4 *)(base + i * row_bytes);     // read again below: may stay in the cache
+                }
             }
         }
-    }
     };
     load_block(valid, s);
 
