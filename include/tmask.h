@@ -16,8 +16,8 @@
  *
  * Memory and execution
  *   Every `w`, `mask`, `vals*`, `idx*`, `objective`, `out`, `per_block_obj` and `workspace` pointer
- *   is DEVICE memory owned by the caller; descriptor arrays (`tmask_mat*`, `tmask_pack_desc*`, `tmask_fused_desc*`) are
- *   HOST memory read before the call returns.  Work is enqueued on `hip_stream` (a hipStream_t,
+ *   is DEVICE memory owned by the caller; descriptor arrays (`tmask_mat*`, `tmask_pack_desc*`, `tmask_fused_desc*`
+ *   and the other `*_desc` types) are HOST memory read before the call returns.  Work is enqueued on `hip_stream` (a hipStream_t,
  *   NULL = default stream); the library never synchronises, allocates or frees device memory, and
  *   holds no state between calls.  Outputs are valid once the stream has been synchronised.
  *   The workspace (at least tmask_workspace_bytes(), 256-byte aligned) is scratch for the duration
@@ -298,8 +298,8 @@ int tmask_mask_diversity(tmask_md_kind kind, int N, int M, int64_t T, double *lo
  * Probability that a block of M independent entries, each prunable with probability rho, is N:M
  * sparse in the sense of Sec. 5 (at least N of the M can be pruned): Eq. 4, the upper tail of a
  * binomial distribution.  *prob is a HOST pointer.  Pure host arithmetic.  (The number of
- * "pattern violations" that forcing an N:M mask onto an unstructured one costs is what
- * tmask_flip_count returns for the two masks.)
+ * "pattern violations" that forcing an N:M mask onto an unstructured-sparse W costs is what
+ * tmask_pattern_violations returns for W and that mask.)
  */
 int tmask_nm_sparse_probability(int N, int M, double rho, double *prob);
 
