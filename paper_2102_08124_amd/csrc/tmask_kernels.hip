@@ -576,8 +576,8 @@ struct ScoreReduceArgs {
 
 __global__ __launch_bounds__(kThreads) void score_reduce_kernel(const ScoreReduceArgs args)
 {
-    __shared__ double redd[kThreads / 64];
-    __shared__ unsigned long long redu[kThreads / 64];
+    __shared__ double redd[2][kThreads / 64];
+    __shared__ unsigned long long redu[5][kThreads / 64];
     const uint32_t m = blockIdx.x;
     double retained = 0.0, total = 0.0;
     unsigned long long kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
@@ -586,17 +586,37 @@ __global__ __launch_bounds__(kThreads) void score_reduce_kernel(const ScoreReduc
         retained += p.retained; total += p.total;
         kept += p.kept; rowv += p.rowv; colv += p.colv; rowne += p.rowne; colne += p.colne;
     }
-    const double r0 = block_sum(retained, redd);
-    const double r1 = block_sum(total, redd);
-    const unsigned long long u0 = block_sum(kept, redu);
-    const unsigned long long u1 = block_sum(rowv, redu);
-    const unsigned long long u2 = block_sum(colv, redu);
-    const unsigned long long u3 = block_sum(rowne, redu);
-    const unsigned long long u4 = block_sum(colne, redu);
+    // all seven sums per wavefront first, one barrier, then thread 0 adds the wavefronts in a fixed order
+    const double d[2] = {wave_sum(retained), wave_sum(total)};
+    const unsigned long long u[5] = {wave_sum(kept), wave_sum(rowv), wave_sum(colv), wave_sum(rowne), wave_sum(colne)};
+    if ((threadIdx.x & 63) == 0) {
+        const uint32_t w = threadIdx.x >> 6;
+#pragma unroll
+        for (int k = 0; k < 2; k++)
+            redd[k][w] = d[k];
+#pragma unroll
+        for (int k = 0; k < 5; k++)
+            redu[k][w] = u[k];
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+        double r[2];
+        unsigned long long c[5];
+#pragma unroll
+        for (int k = 0; k < 2; k++) {
+            r[k] = redd[k][0];
+            for (int w = 1; w < (int)(kThreads / 64); w++)
+                r[k] += redd[k][w];
+        }
+#pragma unroll
+        for (int k = 0; k < 5; k++) {
+            c[k] = redu[k][0];
+            for (int w = 1; w < (int)(kThreads / 64); w++)
+                c[k] += redu[k][w];
+        }
         tmask_score_out *o = args.out + m;
-        o->retained_l1 = r0; o->total_l1 = r1;
-        o->kept = u0; o->row_violations = u1; o->col_violations = u2; o->row_not_n = u3; o->col_not_n = u4;
+        o->retained_l1 = r[0]; o->total_l1 = r[1];
+        o->kept = c[0]; o->row_violations = c[1]; o->col_violations = c[2]; o->row_not_n = c[3]; o->col_not_n = c[4];
     }
 }
 
