@@ -56,6 +56,7 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
     constexpr int C = HALF ? 4 : Ge::C, G = HALF ? 4 : Ge::G;     // columns per lane, lanes per block
     constexpr int NB = kThreads / G;          // blocks per workgroup
     constexpr int NBUCKET = 16;
+    static_assert(kThreads <= 256 && NBUCKET <= 16, "a lane number and an excess bucket share sixteen bits (ssrc)");
     constexpr int XPW = 32 / M;               // pruned-row sets (M bits per column) per exchanged word
     constexpr int XW = C / XPW;
     // PARK: the raw rows of every block stay in LDS, at the loading lane's place; else they are read from memory again
