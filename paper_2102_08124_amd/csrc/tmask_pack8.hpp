@@ -409,6 +409,16 @@ struct Pack8F32Geo {
     static constexpr int IDXTB = NBR * 12 / 8;         // position bytes per tile column
 };
 
+// All-ones if bit `pos` of x is set, else zero (one v_bfe_i32), and m ? a : b bit by bit (one v_bfi_b32, written as an
+// instruction so that the compiler does not turn chains of such selects into indexed loads from a copy in scratch).
+__device__ __forceinline__ uint32_t bit_mask(uint32_t x, uint32_t pos) { return (uint32_t)__builtin_amdgcn_sbfe((int)x, pos, 1u); }
+__device__ __forceinline__ uint32_t bit_select(uint32_t m, uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(m), "v"(a), "v"(b));
+    return r;
+}
+
 // bits 0, 4, ..., 28 of y gathered into bits 0..7
 __device__ __forceinline__ uint32_t gather_every_fourth_bit(uint32_t y)
 {
@@ -606,13 +616,12 @@ __global__ __launch_bounds__(256) void pack48_f32_kernel(const ARGS args)
             for (int t = 0; t < 2; t++) {
                 // (selects written as instructions: as plain conditionals the compiler turns them into indexed
                 // loads from a copy of the block in scratch memory)
-                const lanemask_t b0 = lm((x & (1u << (3 * t))) != 0u), b1 = lm((x & (2u << (3 * t))) != 0u),
-                                 b2 = lm((x & (4u << (3 * t))) != 0u);
-                const uint32_t t0 = lm_select(b0, e[i][1], e[i][0]);
-                const uint32_t t1 = lm_select(b0, e[i][3], e[i][2]);
-                const uint32_t t2 = lm_select(b0, r1, r0);
-                const uint32_t u = lm_select(b1, t1, t0);
-                o[t] = lm_select(b2, t2, u);
+                const uint32_t b0 = bit_mask(x, 3 * t), b1 = bit_mask(x, 3 * t + 1), b2 = bit_mask(x, 3 * t + 2);
+                const uint32_t t0 = bit_select(b0, e[i][1], e[i][0]);
+                const uint32_t t1 = bit_select(b0, e[i][3], e[i][2]);
+                const uint32_t t2 = bit_select(b0, r1, r0);
+                const uint32_t u = bit_select(b1, t1, t0);
+                o[t] = bit_select(b2, t2, u);
             }
             if (!ok)
                 code = 0;                                 // nothing of this strip may show up in a row's padding bits
@@ -641,12 +650,11 @@ __global__ __launch_bounds__(256) void pack48_f32_kernel(const ARGS args)
             const uint32_t gaps = code - 0x688u;          // slot s sits (position - s) rows below row s: 0..4 each
 #pragma unroll
             for (int sl = 0; sl < 4; sl++) {
-                const lanemask_t b0 = lm((gaps & (1u << (3 * sl))) != 0u), b1 = lm((gaps & (2u << (3 * sl))) != 0u),
-                                 b2 = lm((gaps & (4u << (3 * sl))) != 0u);
-                const uint32_t t0 = lm_select(b0, e[sl + 1][c], e[sl][c]);
-                const uint32_t t1 = lm_select(b0, e[sl + 3][c], e[sl + 2][c]);
-                const uint32_t u = lm_select(b1, t1, t0);
-                oc[sl][c] = lm_select(b2, e[sl + 4][c], u);
+                const uint32_t b0 = bit_mask(gaps, 3 * sl), b1 = bit_mask(gaps, 3 * sl + 1), b2 = bit_mask(gaps, 3 * sl + 2);
+                const uint32_t t0 = bit_select(b0, e[sl + 1][c], e[sl][c]);
+                const uint32_t t1 = bit_select(b0, e[sl + 3][c], e[sl + 2][c]);
+                const uint32_t u = bit_select(b1, t1, t0);
+                oc[sl][c] = bit_select(b2, e[sl + 4][c], u);
             }
             tcode[c] |= (ok ? code : 0u) << (12 * q);
         }
