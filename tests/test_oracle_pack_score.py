@@ -143,3 +143,59 @@ def test_spmm_identity_and_linearity():
     lhs = float((y * gf).sum())
     rhs = float((xf * oracle.spmm(valsT, idxT, 64, 16, 2, 4, g)).sum())
     assert lhs == pytest.approx(rhs, rel=1e-12)
+
+
+# ---- flip_count: the number of entries whose kept / pruned state differs (Sec. 4.1: the mask is re-extracted as the
+# weights move; the flip fraction is this count over rows * cols).  Pinned by hand-counted masks, not by its own formula.
+
+def test_flip_count_hand_counted():
+    # kept = any non-zero byte.  Positions that differ in STATE, counted by hand: (0,1) kept->pruned, (0,3) pruned->kept,
+    # (1,0) pruned->kept, (2,2) kept->pruned = 4.  (0,0) 1 vs 255 and (1,3) 7 vs 1 differ as bytes but not in state.
+    a = np.array([[1, 9, 0, 0],
+                  [0, 0, 1, 7],
+                  [0, 1, 200, 0]], dtype=np.uint8)
+    b = np.array([[255, 0, 0, 3],
+                  [1, 0, 1, 1],
+                  [0, 1, 0, 0]], dtype=np.uint8)
+    assert oracle.flip_count(a, b) == 4
+    assert oracle.flip_count(b, a) == 4                       # symmetric
+    assert oracle.flip_count(a, a) == 0                       # identical masks
+    assert oracle.flip_count(a, (a != 0).astype(np.uint8)) == 0   # byte values do not matter, only kept / pruned
+    # byte equality would have said 6 here: the two same-state pairs with different bytes must not count
+    assert int((a != b).sum()) == 6
+
+
+def test_flip_count_all_flipped_and_brute_force():
+    rng = np.random.default_rng(77)
+    a = (rng.random((13, 40)) < 0.4).astype(np.uint8)
+    assert oracle.flip_count(a, 1 - a) == a.size              # every entry changes state
+    assert oracle.flip_count(np.zeros_like(a), a) == int(a.sum())
+    b = (rng.random((13, 40)) < 0.6).astype(np.uint8) * rng.integers(1, 256, size=(13, 40)).astype(np.uint8)
+    n = 0
+    for i in range(13):                                       # plain loops over the definition
+        for j in range(40):
+            ka, kb = a[i, j] != 0, b[i, j] != 0
+            n += 1 if (ka and not kb) or (kb and not ka) else 0
+    assert oracle.flip_count(a, b) == n
+    # triangle inequality and additivity over a partition of the entries
+    c = (rng.random((13, 40)) < 0.5).astype(np.uint8)
+    assert oracle.flip_count(a, c) <= oracle.flip_count(a, b) + oracle.flip_count(b, c)
+    assert oracle.flip_count(a, b) == oracle.flip_count(a[:, :24], b[:, :24]) + oracle.flip_count(a[:, 24:], b[:, 24:])
+
+
+def test_flip_count_strided_view_and_bit_masks():
+    rng = np.random.default_rng(78)
+    big_a = (rng.random((9, 64)) < 0.5).astype(np.uint8)
+    big_b = (rng.random((9, 80)) < 0.5).astype(np.uint8)
+    a, b = big_a[:, 8:40], big_b[:, 16:48]                    # column slices: row stride > cols
+    want = sum(int(bool(a[i, j]) != bool(b[i, j])) for i in range(9) for j in range(32))
+    assert oracle.flip_count(a, b) == want
+    # BITS masks (bit c % 8 of byte c / 8, LSB first): popcount of the xor of the packed bytes is the same count
+    pa = np.packbits(a, axis=1, bitorder="little")
+    pb = np.packbits(b, axis=1, bitorder="little")
+    assert pa[0, 0] & 1 == a[0, 0] and (pa[0, 0] >> 3) & 1 == a[0, 3]          # LSB-first layout
+    xor_pop = sum(bin(int(x)).count("1") for x in (pa ^ pb).ravel())
+    assert xor_pop == want
+    ua = np.unpackbits(pa, axis=1, bitorder="little")[:, :32]
+    ub = np.unpackbits(pb, axis=1, bitorder="little")[:, :32]
+    assert oracle.flip_count(ua, ub) == want
