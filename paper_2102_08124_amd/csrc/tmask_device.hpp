@@ -33,9 +33,11 @@ constexpr int kBF16 = 1;
 constexpr int kMaskU8 = 0;
 constexpr int kMaskBits = 1;
 constexpr int kThreads = 256;        // workgroup size of the streaming kernels
-constexpr int kMaxBatch = 64;        // matrices per launch (descriptor table travels as kernel argument)
+constexpr int kMaxBatch = 256;       // matrices per launch (descriptor table travels as kernel argument, 14 KiB)
 
-// One matrix as the kernels see it. 56 bytes; 64 of them fit the 4 KiB kernel-argument segment.
+// One matrix as the kernels see it, 56 bytes.  The table of a launch is passed by value: the kernel-argument
+// segment takes tens of KiB (launches with 64 KiB of arguments were checked on the device), workgroups read only the
+// entries their binary search touches, with scalar loads, and nothing has to be uploaded or allocated per call.
 struct MatDev {
     const void *w;
     void *mask;
@@ -59,7 +61,7 @@ struct BatchArgs {
     void *partials;      // workspace
 };
 
-static_assert(sizeof(BatchArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+static_assert(sizeof(BatchArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
 
 template <int DT, int M>
 struct Geo {

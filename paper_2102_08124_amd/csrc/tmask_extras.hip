@@ -12,7 +12,7 @@
 
 namespace tmask {
 
-constexpr int kMaxFlipBatch = 64;
+constexpr int kMaxFlipBatch = 256;
 
 struct FlipDev {
     const unsigned char *a, *b;
@@ -26,7 +26,7 @@ struct FlipArgs {
     FlipDev d[kMaxFlipBatch];
     uint32_t n;
 };
-static_assert(sizeof(FlipArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+static_assert(sizeof(FlipArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
 
 __global__ void flip_zero_kernel(const FlipArgs args)
 {
@@ -177,7 +177,7 @@ extern "C" int tmask_flip_count(const tmask_flip_desc *descs, int n, tmask_mask_
 // ---------------------------------------------------------------------------------------------------------
 namespace tmask {
 
-constexpr int kMaxDenseBatch = 64;
+constexpr int kMaxDenseBatch = 256;
 
 struct DenseDev {
     const char *w;
@@ -192,7 +192,7 @@ struct DenseArgs {
     DenseDev d[kMaxDenseBatch];
     uint32_t n;
 };
-static_assert(sizeof(DenseArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+static_assert(sizeof(DenseArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
 
 // A lane owns 16 bytes of a row: C = 4 (fp32) or 8 (bf16) entries.  A group of M entries is either a part of
 // the lane's chunk (M <= C) or spans G = M / C neighbouring lanes, whose partial sums meet in a butterfly.

@@ -18,7 +18,7 @@
 
 namespace tmask {
 
-constexpr int kMaxPackBatch = 56;   // 56 descriptors of 72 bytes fit the 4 KiB kernel-argument segment
+constexpr int kMaxPackBatch = 224;  // descriptors of 72 bytes, passed by value as kernel argument (16 KiB)
 constexpr int kPackTR = 64;
 
 struct PackDev {
@@ -35,7 +35,7 @@ struct PackArgs {
     uint32_t n;
     uint32_t N;
 };
-static_assert(sizeof(PackArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+static_assert(sizeof(PackArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
 
 // Arguments of the kernels that compute the mask themselves (tmask_approx_pack).
 struct FusedArgs {
@@ -44,7 +44,7 @@ struct FusedArgs {
     uint32_t partial0;          // index of this launch's first partial in the workspace
     void *partials;             // one double per workgroup, or null
 };
-static_assert(sizeof(FusedArgs) <= 4096, "descriptor table must fit the kernel-argument segment");
+static_assert(sizeof(FusedArgs) <= 16384 + 64, "descriptor table is sized to stay a small kernel argument");
 
 
 // Tile number inside a matrix -> tile coordinates, for the kernels that write W^T in short runs per column.
