@@ -84,6 +84,22 @@ int tmask_approx(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M
                  void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * tmask_approx for callers that cannot allocate device memory and have no workspace to hand over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (minus the workspace), same
+ * kernels and bit-identical results as tmask_approx; the per-workgroup partial sums of the objectives go to a
+ * 512 KiB array that lives inside the library's device code (one copy per GPU, kept until the process ends) instead
+ * of a caller workspace.  The call allocates and frees nothing, on the host side of HIP or on the device.
+ * Limit: at most 65536 workgroups of 256 strips over the whole batch when any objective is requested, i.e.
+ * sum over matrices of ceil(rows/M * cols/C / 256) <= 65536 with C = 4 (fp32) or 8 (bf16) columns per strip
+ * (268 M fp32 or 536 M bf16 weights at M = 4; proportionally more at M = 8, 16); beyond that TMASK_ERR_WORKSPACE is
+ * returned before anything is enqueued.  Without objectives there is no limit.
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams or threads) race
+ * on the objectives (the masks are unaffected); calls enqueued on one stream are safe.
+ */
+int tmask_approx_noalloc(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                         void *hip_stream);
+
+/*
  * Optimal mask of Eq. 3 per block (Sec. 4, "Reduction to Min-Cost Flow", Fig. 3): exactly N kept
  * per row and column, maximum retained L1.  2:4 blocks are solved by evaluating all 90 feasible
  * patterns in fp32; other (N, M) by successive shortest augmenting paths on the bipartite

@@ -21,7 +21,7 @@ TMASK_OK = 0
 TMASK_ERR_NULL, TMASK_ERR_SHAPE, TMASK_ERR_NM, TMASK_ERR_DTYPE = -1, -2, -3, -4
 TMASK_ERR_WORKSPACE, TMASK_ERR_HIP, TMASK_ERR_ALIGN = -5, -6, -7
 
-EXPORTS = ("tmask_approx", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_apply_dense", "tmask_approx_dense", "tmask_prune_1d_dense", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_pattern_violations", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
+EXPORTS = ("tmask_approx", "tmask_approx_noalloc", "tmask_exact", "tmask_prune_1d", "tmask_apply_pack", "tmask_apply_dense", "tmask_approx_dense", "tmask_prune_1d_dense", "tmask_approx_pack", "tmask_spmm24", "tmask_flip_count", "tmask_pattern_violations", "tmask_mask_diversity", "tmask_nm_sparse_probability", "tmask_score",
            "tmask_workspace_bytes", "tmask_profile_next", "tmask_last_error", "tmask_version")
 
 
@@ -91,6 +91,8 @@ def load_library():
         f = getattr(L, name)
         f.restype = ci
         f.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp, sz, vp]
+    L.tmask_approx_noalloc.restype = ci
+    L.tmask_approx_noalloc.argtypes = [C.POINTER(tmask_mat), ci, ci, ci, ci, ci, vp]
     L.tmask_apply_pack.restype = ci
     L.tmask_apply_pack.argtypes = [C.POINTER(tmask_pack_desc), ci, ci, ci, ci, ci, vp, sz, vp]
     L.tmask_approx_pack.restype = ci
@@ -269,6 +271,13 @@ def tmask_approx(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = 
                  mask_fmt: int = TMASK_MASK_U8, workspace: Optional[torch.Tensor] = None, stream=None) -> None:
     """Algorithm 1 on every M x M block of every matrix; masks (and objective[k]) are written in place."""
     _run_mask(load_library().tmask_approx, ws, masks, N, M, objective, mask_fmt, workspace, stream)
+
+
+def tmask_approx_noalloc(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = None,
+                         mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
+    """tmask_approx without a workspace: the partial sums live in the library's own static device array."""
+    b = ws if isinstance(ws, MatBatch) else MatBatch(ws, masks, objective)
+    _check(load_library().tmask_approx_noalloc(b.arr, b.n, b.dt, N, M, mask_fmt, _stream_ptr(stream)))
 
 
 def tmask_exact(ws, masks, N: int, M: int, objective: Optional[torch.Tensor] = None,

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 #include <vector>
 
@@ -783,9 +784,42 @@ int hip_fail(hipError_t e, const char *what)
 // One-shot profiling events (tmask_profile_next): recorded around the main kernel of the next call.
 thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 
+// Scratch memory of tmask_approx_noalloc: the per-workgroup partial sums of the objective, which the other entry
+// points keep in the caller's workspace.  One copy per GPU, held until the process ends; every call on a GPU shares
+// it, so calls that overlap on one GPU race.  Nothing in it has to start at zero: every partial a call reads was
+// written by that call.
+constexpr size_t kScratchPartials = 65536;      // 512 KiB: one double per workgroup of 256 strips
+static __device__ __align__(256) __attribute__((used)) double scratch[kScratchPartials];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];        // device address of `scratch` on each GPU (the array's name is only a
+static std::mutex g_scratch_lock;               // host-side handle, never a device address)
+
+// Address of the current device's copy of `scratch`, looked up once per device.
+static int scratch_of_current_device(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(TMASK_ERR_HIP, "device ordinal %d is outside the %d this library keeps scratch addresses for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return TMASK_OK;
+}
+
+// own_scratch: the partial sums go to the library's static array instead of a caller workspace (ws, ws_bytes unused).
 template <int SOLVER>
 static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, void *ws, size_t ws_bytes,
-                    void *stream_)
+                    void *stream_, bool own_scratch = false)
 {
     int rc = check_common(mats, n_mats, dt, N, M, mf);
     if (rc)
@@ -798,8 +832,22 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             return rc;
         want_obj = want_obj || mats[i].objective;
     }
-    if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes)))
+    if (own_scratch) {
+        size_t tiles = 0;
+        for (int i = 0; i < n_mats; i++) {
+            const HostMat h{mats[i].w, mats[i].rows, mats[i].cols, mats[i].ld, nullptr, 0, nullptr};
+            tiles += tiles_of(strips_of(h, dt, M));
+        }
+        if (want_obj && tiles > kScratchPartials)
+            return fail(TMASK_ERR_WORKSPACE,
+                        "this call needs %zu partial sums (one per 256 strips of 16 bytes x M rows); the library's own scratch "
+                        "array holds %zu: split the batch, or use the entry point that takes a caller workspace",
+                        tiles, kScratchPartials);
+        if ((rc = scratch_of_current_device(&ws)))
+            return rc;
+    } else if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes))) {
         return rc;
+    }
     batch_kernel_t kern = pick_mask_kernel<SOLVER>(dt, M, mf);
     if (SOLVER == kSolveApprox && M == 4 && N == 2) {
         if (dt == kF32)
@@ -880,6 +928,12 @@ int tmask_approx(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M
                  size_t workspace_bytes, void *hip_stream)
 {
     return run_mask<kSolveApprox>(mats, n_mats, (int)dt, N, M, (int)mf, workspace, workspace_bytes, hip_stream);
+}
+
+int tmask_approx_noalloc(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf,
+                         void *hip_stream)
+{
+    return run_mask<kSolveApprox>(mats, n_mats, (int)dt, N, M, (int)mf, nullptr, 0, hip_stream, true);
 }
 
 int tmask_prune_1d(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M, tmask_mask_fmt mf, void *workspace,
