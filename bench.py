@@ -1,18 +1,29 @@
 #!/usr/bin/env python3
-"""Benchmark of the transposable-mask hot path on one MI355X.
+"""Benchmark of the transposable-mask hot path on one MI355X.  Prints ONE JSON line.
 
-A "step" is one pass of the whole path over one batch of synthetic input, everything resident in
-HBM: tmask_approx (Algorithm 1) + tmask_exact (Eq. 3 optimum) + tmask_apply_pack (with the exact
-mask) + tmask_score (of the approximate mask, per-block objectives included), each with its
-objective reduction.  Workload at N=1: the ResNet-50-shaped conv weight set (52 matrices,
-23,445,504 fp32 weights, Kaiming-normal, seeded), N:M = 2:4, every call one batched launch over all
-layers.  Several distinct copies of all buffers are rotated so the working set exceeds the
-last-level cache.  Prints ONE JSON line.
+Headline workload (N=1): the BERT-large-shaped set of linear layers -- 144 bf16 matrices, 301,989,888 weights,
+N(0, 0.02), seeded -- at N:M = 2:4.  A "step" is one pass of the whole path over that set, everything resident in
+HBM: tmask_approx (Algorithm 1) + tmask_exact (Eq. 3 optimum) + tmask_apply_pack (with the exact mask) +
+tmask_score (of the approximate mask, per-block objectives included), each ONE batched launch over all 144 matrices
+followed by its one reduce launch.  `value` = weights / step time.
+
+Per-kernel figures come from hipEvents the library records directly around each main kernel (tmask_profile_next),
+whole-call figures from events recorded around the call (main kernel + reduce launch); both ride inside the timed
+region on separate steps.  Event times are reported as measured (the two marker packets of a bracket add a few
+microseconds, printed as `marker_overhead_ms`, and are NOT subtracted), so the fractions are conservative and agree
+with a rocprofv3 kernel trace of the same command within a few percent.
+
+Further sections (same JSON line): the same set at 4:8, the one-pass calls, the ResNet-50-shaped fp32 set, the
+8192^2 Laplace matrix (quality ratios and time per mask at 2:4 / 4:8 / 8:16), the 16384^2 bf16 drifting-weights
+loop, the products with the packed operands, a plain device copy, and the CPU oracle on host cores.
+
+    python bench.py                                    # everything, a few minutes
+    python bench.py --sections step                    # the headline step only (what the profiles/ traces run)
+    python bench.py --square 8192 --calls approx,exact --dts f32 --ms 8,16      # one square matrix, chosen calls
 """
 from __future__ import annotations
 
 import argparse
-import ctypes
 import json
 import os
 import re
@@ -25,32 +36,45 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-N_KEEP, M_BLOCK = 2, 4
-# main kernel behind each call on this workload (names as rocprofv3 lists them)
-KERNEL_NAMES = {"approx": "approx24_kernel<0, 0>", "exact": "exact24_kernel<0, 0>", "pack": "pack24_kernel<0, 0, 64, 4, 4>",
-                "score": "score_kernel<0, 4, 0>"}
-
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # dense bf16
+ALL_SECTIONS = ("step", "four_of_eight", "one_pass", "config2", "config4", "config5", "spmm24", "device_copy",
+                "cpu_baseline")
 
 from paper_2102_08124_amd.hipevents import HipEvents  # noqa: E402
 
 
-def algorithmic_bytes(weights: int, n_mats: int, es: int, N: int, M: int):
-    """Bytes each call must move per launch (U8 mask): what is read plus what is written."""
+# ------------------------------------------------------------------------------------------------------------------
+# bytes the method must move per call (what is read plus what is written), U8 or bit masks
+# ------------------------------------------------------------------------------------------------------------------
+
+def algorithmic_bytes(weights: int, n_mats: int, es: int, N: int, M: int, bit_masks: bool = False):
     ib = (M - 1).bit_length()
-    mask = weights
+    mask = weights // 8 if bit_masks else weights
     blocks = weights // (M * M)
-    pack_out = 2 * (weights * N // M) * es + 2 * (weights * N // M) * ib // 8
+    packed = 2 * (weights * N // M) * es + 2 * (weights * N // M) * ib // 8
     return {
         "approx": weights * es + mask + 8 * n_mats,
         "exact": weights * es + mask + 8 * n_mats,
-        "pack": weights * es + mask + pack_out,
+        "prune1d": weights * es + mask + 8 * n_mats,
+        "pack": weights * es + mask + packed,
         "score": weights * es + mask + 4 * blocks + 56 * n_mats,
+        "approx_pack": weights * es + packed + 8 * n_mats,
+        "approx_pack_mask": weights * es + mask + packed + 8 * n_mats,
+        "approx_dense": 2 * weights * es,
+        "dense": 2 * weights * es + mask,
+        "flip": 2 * mask,
+        "viol": weights * es + mask,
     }
 
 
+def hbm(byts: int, ms: float):
+    gbs = byts / (ms * 1e-3) / 1e9
+    return {"ms": ms, "algorithmic_bytes": byts, "achieved_GBs": gbs, "frac": gbs / HBM_PEAK_GBS}
+
+
 def read_pmc_traffic(path: str):
-    """Per-launch HBM traffic measured with rocprofv3 --pmc (committed summary), or {}.
-    Lines look like: `traffic <kernel> fetch_bytes=<int> write_bytes=<int>`."""
+    """Per-launch HBM traffic from a committed rocprofv3 --pmc summary (not measured in this run), or {}.
+    Lines look like: `traffic <call> fetch_bytes=<int> write_bytes=<int>`."""
     out = {}
     if os.path.exists(path):
         for line in open(path):
@@ -60,223 +84,485 @@ def read_pmc_traffic(path: str):
     return out
 
 
-def cpu_baseline(mats_np, min_s: float = 10.0, budget_s: float = 30.0):
-    """The oracle as it stands, one thread, on the same workload: full steps until min_s has passed."""
-    import oracle
-    t0 = time.perf_counter()
-    weights = 0
-    while time.perf_counter() - t0 < min_s:
-        for w in mats_np:
-            am, _ = oracle.approx(w, N_KEEP, M_BLOCK)
-            em, _ = oracle.exact(w, N_KEEP, M_BLOCK)
-            oracle.apply_pack(w, em, N_KEEP, M_BLOCK)
-            oracle.score(w, am, N_KEEP, M_BLOCK)
-            weights += w.size
-            if time.perf_counter() - t0 > budget_s:
-                break
-    dt = time.perf_counter() - t0
-    total = sum(w.size for w in mats_np)
-    return {"value": weights / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
-            "sample": "full steps (approx+exact+pack+score) of the C oracle, gcc -O2, 1 thread, over %d weights "
-                      "(the workload has %d), %.1f s" % (weights, total, dt)}
+class Timer:
+    """hipEvent brackets on the launch stream: around the main kernel of a call (recorded by the library) or around
+    the whole call (recorded here)."""
 
+    def __init__(self, tm, torch):
+        self.tm, self.torch = tm, torch
+        self.ev = HipEvents()
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.marker_ms = self.ev.empty_bracket_ms(self.stream)
 
-def largest_config_approx(tm, torch, ev, reps: int, bit_masks: bool = False):
-    """Approximation alone on the largest configuration (16384^2 bf16, 2:4): kernel time and HBM fraction,
-    with the mask written as bytes (as in the step above) or as bits."""
-    side = 16384
-    fmt = tm.TMASK_MASK_BITS if bit_masks else tm.TMASK_MASK_U8
-    gen = torch.Generator(device="cuda").manual_seed(5)
-    sets = []
-    for _ in range(2):
-        w = (torch.randn((side, side), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
-        mask = tm.alloc_masks([w], fmt)[0]
-        obj = torch.zeros(1, dtype=torch.float64, device="cuda")
-        sets.append(tm.MatBatch([w], [mask], obj))
-    wsp = tm.alloc_workspace(sets[0].ws, N_KEEP, M_BLOCK)
-    evs = [(ev.create(), ev.create()) for _ in range(reps)]
-    for b in sets:
-        tm.tmask_approx(b, None, N_KEEP, M_BLOCK, mask_fmt=fmt, workspace=wsp)
-    torch.cuda.synchronize()
-    for k in range(reps):
-        tm.tmask_profile_next(*evs[k])
-        tm.tmask_approx(sets[k % 2], None, N_KEEP, M_BLOCK, mask_fmt=fmt, workspace=wsp)
-    torch.cuda.synchronize()
-    ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
-    weights = side * side
-    byts = weights * 2 + (weights // 8 if bit_masks else weights) + 8
-    return {"workload": "16384x16384 bf16 N(0,0.02), 2:4, tmask_approx, %s mask" % ("bit" if bit_masks else "U8"),
-            "kernel_ms": ms, "weights_per_s": weights / (ms * 1e-3), "achieved_GBs": byts / (ms * 1e-3) / 1e9,
-            "frac_of_hbm_peak": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    def pair(self):
+        return (self.ev.create(), self.ev.create())
 
+    def kernel(self, pair, fn):
+        self.tm.tmask_profile_next(*pair)
+        fn()
 
-def fused_approx_pack(tm, torch, ev, mats_np, copies: int, reps: int):
-    """tmask_approx_pack (Algorithm 1 + compression in one pass, no mask written) on the bench workload:
-    what a training step that refreshes its packed operands would call instead of approx + apply_pack."""
-    N, M = N_KEEP, M_BLOCK
-    weights = sum(w.size for w in mats_np)
-    sets = []
-    for _ in range(copies):
-        ws = [torch.from_numpy(w).cuda() for w in mats_np]
-        sets.append(tm.FusedBatch(ws, None, [tm.alloc_packed(w, N, M) for w in ws], N, M))
-    for b in sets:
-        tm.tmask_approx_pack(b, None, None, N, M)
-    torch.cuda.synchronize()
-    evs = [(ev.create(), ev.create()) for _ in range(reps)]
-    for k in range(reps):
-        tm.tmask_profile_next(*evs[k])
-        tm.tmask_approx_pack(sets[k % copies], None, None, N, M)
-    torch.cuda.synchronize()
-    ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
-    byts = weights * 4 + 2 * (weights * N // M) * 4 + 2 * (weights * N // M) * 2 // 8
-    return {"what": "tmask_approx_pack on the same workload, one batched launch, no mask written",
-            "kernel_ms": ms, "algorithmic_bytes": byts, "achieved_GBs": byts / (ms * 1e-3) / 1e9,
-            "frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "weights_per_s": weights / (ms * 1e-3)}
+    def call(self, pair, fn):
+        self.ev.record(pair[0], self.stream)
+        fn()
+        self.ev.record(pair[1], self.stream)
 
+    def ms(self, pairs, reduce=np.median):
+        return float(reduce([self.ev.elapsed_ms(a, b) for a, b in pairs]))
 
-def approx_dense(tm, torch, ev, mats_np, copies: int, reps: int):
-    """tmask_approx_dense (Algorithm 1 + dense masked copy in one pass, no mask written) on the bench workload: what
-    a dense-emulated training step calls before its forward pass."""
-    N, M = N_KEEP, M_BLOCK
-    weights = sum(w.size for w in mats_np)
-    sets = []
-    for _ in range(copies):
-        ws = [torch.from_numpy(w).cuda() for w in mats_np]
-        sets.append((ws, [torch.empty_like(w) for w in ws]))
-    for ws, outs in sets:
-        tm.tmask_approx_dense(ws, None, outs, N, M)
-    torch.cuda.synchronize()
-    evs = [(ev.create(), ev.create()) for _ in range(reps)]
-    for k in range(reps):
-        ws, outs = sets[k % copies]
-        tm.tmask_profile_next(*evs[k])
-        tm.tmask_approx_dense(ws, None, outs, N, M)
-    torch.cuda.synchronize()
-    ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
-    byts = weights * 4 * 2
-    return {"what": "tmask_approx_dense on the same workload, one batched launch, no mask written",
-            "kernel_ms": ms, "algorithmic_bytes": byts, "achieved_GBs": byts / (ms * 1e-3) / 1e9,
-            "frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "weights_per_s": weights / (ms * 1e-3)}
-
-
-def four_of_eight(tm, torch, ev, mats_np, copies: int, reps: int):
-    """The same workload at 4:8, the paper's transposable setting for M = 8 (Sec. 4, Table 2): kernel times of the
-    approximation, the exact solver (augmenting paths from a priced start), the compression and the one-pass call.
-    The 7x7 stem aside every ResNet-50 conv matrix has dimensions that are multiples of 8."""
-    N, M = 4, 8
-    keep = [w for w in mats_np if w.shape[0] % M == 0 and w.shape[1] % M == 0]
-    weights = sum(w.size for w in keep)
-    sets = []
-    for _ in range(copies):
-        ws = [torch.from_numpy(w).cuda() for w in keep]
-        masks = tm.alloc_masks(ws)
-        obj = torch.zeros(len(ws), dtype=torch.float64, device="cuda")
-        packed = [tm.alloc_packed(w, N, M) for w in ws]
-        sets.append((tm.MatBatch(ws, masks, obj), tm.PackBatch(ws, masks, packed, N, M), tm.FusedBatch(ws, None, packed, N, M)))
-    wsp = tm.alloc_workspace(sets[0][0].ws, N, M)
-    calls = {"approx": lambda b: tm.tmask_approx(b[0], None, N, M, workspace=wsp),
-             "exact": lambda b: tm.tmask_exact(b[0], None, N, M, workspace=wsp),
-             "apply_pack": lambda b: tm.tmask_apply_pack(b[1], None, None, N, M),
-             "approx_pack": lambda b: tm.tmask_approx_pack(b[2], None, None, N, M)}
-    out = {"what": "4:8 on %d of the %d matrices (%d weights), one batched launch per call" % (len(keep), len(mats_np), weights)}
-    empty = ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
-    for name, fn in calls.items():
-        for b in sets:
-            fn(b)
-        torch.cuda.synchronize()
-        evs = [(ev.create(), ev.create()) for _ in range(reps)]
+    def measure(self, fn, reps: int, warm: int = 2):
+        """fn(k) enqueues one call.  Returns (kernel ms, whole-call ms), medians over reps, as measured."""
+        for k in range(warm):
+            fn(k)
+        self.torch.cuda.synchronize()
+        kp = [self.pair() for _ in range(reps)]
         for k in range(reps):
-            tm.tmask_profile_next(*evs[k])
-            fn(sets[k % copies])
-        torch.cuda.synchronize()
-        ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - empty
-        out[name] = {"kernel_ms": ms, "weights_per_s": weights / (ms * 1e-3)}
+            self.kernel(kp[k], lambda: fn(k))
+        self.torch.cuda.synchronize()
+        cp = [self.pair() for _ in range(reps)]
+        for k in range(reps):
+            self.call(cp[k], lambda: fn(k))
+        self.torch.cuda.synchronize()
+        return self.ms(kp), self.ms(cp)
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# buffer sets
+# ------------------------------------------------------------------------------------------------------------------
+
+def to_device(torch, w_np):
+    if w_np.dtype == np.uint16:
+        return torch.from_numpy(w_np.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(w_np).cuda()
+
+
+def make_sets(tm, torch, mats_np, N, M, copies, with_pack=True, with_fused=False):
+    """`copies` distinct device copies of the inputs with their own outputs, rotated so that nothing is served from
+    the last-level cache."""
+    n = len(mats_np)
+    weights = sum(w.size for w in mats_np)
+    base = [to_device(torch, w) for w in mats_np]
+    sets = []
+    for c in range(copies):
+        ws = base if c == 0 else [w.clone() for w in base]
+        amask, emask = tm.alloc_masks(ws), tm.alloc_masks(ws)
+        aobj = torch.zeros(n, dtype=torch.float64, device="cuda")
+        eobj = torch.zeros(n, dtype=torch.float64, device="cuda")
+        s = {"ws": ws, "approx": tm.MatBatch(ws, amask, aobj), "exact": tm.MatBatch(ws, emask, eobj),
+             "score": tm.MatBatch(ws, amask, None), "aobj": aobj, "eobj": eobj,
+             "sout": torch.zeros(n * tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda"),
+             "pb": torch.zeros(weights // (M * M), dtype=torch.float32, device="cuda")}
+        if with_pack:
+            packed = [tm.alloc_packed(w, N, M) for w in ws]
+            s["pack"] = tm.PackBatch(ws, emask, packed, N, M)
+            if with_fused:
+                s["fused"] = tm.FusedBatch(ws, None, packed, N, M, aobj)
+                s["fused_mask"] = tm.FusedBatch(ws, amask, packed, N, M, aobj)
+        sets.append(s)
+    return sets
+
+
+# ------------------------------------------------------------------------------------------------------------------
+# sections
+# ------------------------------------------------------------------------------------------------------------------
+
+def step_section(tm, torch, T, mats_np, N, M, steps, warmup, copies, event_every, kernel_names, label):
+    """The whole path over one workload: timed steps, per-kernel and per-call event times inside the timed region."""
+    n_mats = len(mats_np)
+    weights = sum(w.size for w in mats_np)
+    es = mats_np[0].dtype.itemsize
+    sets = make_sets(tm, torch, mats_np, N, M, copies)
+    wsp = tm.alloc_workspace(sets[0]["ws"], N, M)
+    names = ("approx", "exact", "pack", "score")
+
+    def calls(s):
+        return {"approx": lambda: tm.tmask_approx(s["approx"], None, N, M, workspace=wsp),
+                "exact": lambda: tm.tmask_exact(s["exact"], None, N, M, workspace=wsp),
+                "pack": lambda: tm.tmask_apply_pack(s["pack"], None, None, N, M),
+                "score": lambda: tm.tmask_score(s["score"], None, N, M, s["sout"], per_block_obj=s["pb"], workspace=wsp)}
+
+    def step(k, kernel_pairs=None, call_pairs=None):
+        c = calls(sets[k % copies])
+        for nme in names:
+            if kernel_pairs:
+                T.kernel(kernel_pairs[nme], c[nme])
+            elif call_pairs:
+                T.call(call_pairs[nme], c[nme])
+            else:
+                c[nme]()
+
+    for k in range(warmup):
+        step(k)
+    torch.cuda.synchronize()
+    kprobe = {k: {nme: T.pair() for nme in names} for k in range(steps) if event_every and k % event_every == 0}
+    cprobe = {k: {nme: T.pair() for nme in names} for k in range(steps)
+              if event_every and k % event_every == event_every // 2 and k not in kprobe}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(k, kprobe.get(k), cprobe.get(k))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    alg = algorithmic_bytes(weights, n_mats, es, N, M)
+    traffic = read_pmc_traffic(os.path.join(ROOT, "profiles", "pmc_traffic_%s.md" % label))
+    kernels = {}
+    for nme in names:
+        k = {"kernel": kernel_names[nme], "algorithmic_bytes": alg[nme]}
+        if kprobe:
+            kms = T.ms([p[nme] for p in kprobe.values()], np.mean)
+            k.update({"kernel_ms": kms, "achieved_GBs": alg[nme] / (kms * 1e-3) / 1e9,
+                      "frac": alg[nme] / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS, "weights_per_s": weights / (kms * 1e-3)})
+        if cprobe:
+            cms = T.ms([p[nme] for p in cprobe.values()], np.mean)
+            k.update({"call_ms": cms, "call_frac": alg[nme] / (cms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "call_weights_per_s": weights / (cms * 1e-3)})
+        k["traffic"] = traffic.get(nme)
+        kernels[nme] = k
+    # objectives and scores of the last step's buffers, as a sanity line (retained L1 as a fraction of sum |W|)
+    last = sets[(steps - 1) % copies]
+    sc = tm.read_scores(last["sout"], n_mats)
+    total = sum(s["total_l1"] for s in sc)
+    quality = {"approx_retained_frac": float(last["aobj"].sum().item()) / total,
+               "exact_retained_frac": float(last["eobj"].sum().item()) / total,
+               "score_retained_frac_of_approx_mask": sum(s["retained_l1"] for s in sc) / total,
+               "approx_row_violations": sum(s["row_violations"] for s in sc),
+               "approx_col_violations": sum(s["col_violations"] for s in sc)}
+    del sets
+    return {"ms_per_step": ms_per_step, "weights": weights, "matrices": n_mats, "kernels": kernels,
+            "quality": quality, "traffic_source": ("profiles/pmc_traffic_%s.md (rocprofv3 --pmc FETCH_SIZE / "
+                                                   "WRITE_SIZE runs of this command, committed; not measured in this run)" % label)
+            if traffic else None}
+
+
+def four_of_eight_section(tm, torch, T, mats_np, copies, reps):
+    """The headline set at 4:8, the paper's transposable setting for M = 8 (Sec. 4, Table 2): approximation, exact
+    solver (augmenting paths from a priced start), compression and the one-pass call."""
+    N, M = 4, 8
+    weights = sum(w.size for w in mats_np)
+    es = mats_np[0].dtype.itemsize
+    sets = make_sets(tm, torch, mats_np, N, M, copies, with_fused=True)
+    wsp = tm.alloc_workspace(sets[0]["ws"], N, M)
+    alg = algorithmic_bytes(weights, len(mats_np), es, N, M)
+    out = {"what": "4:8 on the same %d matrices, one batched launch per call; kernel_ms = main kernel, call_ms = whole "
+                   "call with its reduce launch" % len(mats_np)}
+    for name, key, fn in (
+            ("approx", "approx", lambda k: tm.tmask_approx(sets[k % copies]["approx"], None, N, M, workspace=wsp)),
+            ("exact", "exact", lambda k: tm.tmask_exact(sets[k % copies]["exact"], None, N, M, workspace=wsp)),
+            ("apply_pack", "pack", lambda k: tm.tmask_apply_pack(sets[k % copies]["pack"], None, None, N, M)),
+            ("approx_pack", "approx_pack", lambda k: tm.tmask_approx_pack(sets[k % copies]["fused"], None, None, N, M,
+                                                                           workspace=wsp))):
+        kms, cms = T.measure(fn, reps)
+        out[name] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(alg[key], kms)["frac"],
+                     "call_frac": hbm(alg[key], cms)["frac"], "weights_per_s": weights / (cms * 1e-3)}
+    out["exact_over_approx_time"] = out["exact"]["call_ms"] / out["approx"]["call_ms"]
     return out
 
 
-def spmm24_products(tm, torch, ev, reps: int = 20, tokens: int = 8192):
-    """The two training products with the packed 2:4 operands of one BERT-large-shaped bf16 layer
-    (W: 4096 x 1024): forward y = x W^T with (vals, idx), backward dx = g W with (valsT, idxT).  MFMA-bound work
-    with its own roofline: dense-equivalent flops (2 * tokens * rows * cols) against the dense bf16 peak."""
+def one_pass_section(tm, torch, T, mats_np, copies, reps):
+    """tmask_approx_pack (Algorithm 1 + compression, no mask written) and tmask_approx_dense (Algorithm 1 + masked
+    dense copy) at 2:4 on the headline set: what a training step that refreshes its operands calls."""
+    N, M = 2, 4
+    weights = sum(w.size for w in mats_np)
+    es = mats_np[0].dtype.itemsize
+    sets = make_sets(tm, torch, mats_np, N, M, copies, with_fused=True)
+    wsp = tm.alloc_workspace(sets[0]["ws"], N, M)
+    alg = algorithmic_bytes(weights, len(mats_np), es, N, M)
+    out = {}
+    kms, cms = T.measure(lambda k: tm.tmask_approx_pack(sets[k % copies]["fused"], None, None, N, M, workspace=wsp), reps)
+    out["approx_pack"] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(alg["approx_pack"], kms)["frac"],
+                          "call_frac": hbm(alg["approx_pack"], cms)["frac"], "weights_per_s": weights / (cms * 1e-3)}
+    outs = [[torch.empty_like(w) for w in s["ws"]] for s in sets]
+    kms, cms = T.measure(lambda k: tm.tmask_approx_dense(sets[k % copies]["ws"], None, outs[k % copies], N, M), reps)
+    out["approx_dense"] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(alg["approx_dense"], kms)["frac"],
+                           "call_frac": hbm(alg["approx_dense"], cms)["frac"], "weights_per_s": weights / (cms * 1e-3)}
+    return out
+
+
+def config4_section(tm, torch, T, wl, reps):
+    """8192^2 fp32 Laplace(0, 1): retained L1 of the approximation, the optimum and 1-D row pruning, the paper's
+    ratio W(P)/W* on pruned mass (Sec. 4: bounded by 2, about 1.2 in practice), and time per mask."""
+    w_np = wl.config4()
+    weights = w_np.size
+    ws = [to_device(torch, w_np), to_device(torch, w_np)]
+    out = {"what": "8192x8192 fp32 Laplace(0,1), seed 4; times are whole calls (main kernel + reduce launch), medians"}
+    for N, M in ((2, 4), (4, 8), (8, 16)):
+        masks = [tm.alloc_masks([w])[0] for w in ws]
+        obj = torch.zeros(3, dtype=torch.float64, device="cuda")
+        wsp = tm.alloc_workspace([ws[0]], N, M)
+        sout = torch.zeros(tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda")
+        res = {}
+        for j, (name, fn) in enumerate((("approx", tm.tmask_approx), ("exact", tm.tmask_exact), ("prune_1d", tm.tmask_prune_1d))):
+            kms, cms = T.measure(lambda k: fn([ws[k % 2]], [masks[k % 2]], N, M, objective=obj[j:j + 1], workspace=wsp), reps)
+            res[name + "_kernel_ms"], res[name + "_call_ms"] = kms, cms
+            res[name + "_weights_per_s"] = weights / (cms * 1e-3)
+        tm.tmask_score([ws[0]], [masks[0]], N, M, sout, workspace=wsp)
+        torch.cuda.synchronize()
+        total = tm.read_scores(sout, 1)[0]["total_l1"]
+        o = obj.cpu().numpy()
+        res.update({"approx_retained_frac": o[0] / total, "exact_retained_frac": o[1] / total,
+                    "prune_1d_retained_frac": o[2] / total, "retained_approx_over_exact": o[0] / o[1],
+                    "pruned_mass_approx_over_optimal": (total - o[0]) / (total - o[1]),
+                    "exact_over_approx_time": res["exact_call_ms"] / res["approx_call_ms"]})
+        out["%d:%d" % (N, M)] = res
+    return out
+
+
+def config5_section(tm, torch, T, steps: int):
+    """16384^2 bf16 drifting weights (W += 1e-3 * N(0, 0.02), added in fp32, rounded back to bf16): the 2:4 mask is
+    recomputed every step and compared with the previous one.  Weight update = input generation (torch)."""
+    side = 16384
+    weights = side * side
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    w = (torch.randn((side, side), generator=gen, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    noise = torch.empty((side, side), device="cuda", dtype=torch.float32)
+    out = {"what": "16384x16384 bf16, %d steps of W += 1e-3*N(0,0.02); tmask_approx 2:4 per step + tmask_flip_count "
+                   "against the previous mask; times as measured by events around the calls, medians of the second half" % steps}
+    for fmt, label in ((tm.TMASK_MASK_U8, "u8_masks"), (tm.TMASK_MASK_BITS, "bit_masks")):
+        masks = [tm.alloc_masks([w], fmt)[0] for _ in range(2)]
+        obj = torch.zeros(1, dtype=torch.float64, device="cuda")
+        batches = [tm.MatBatch([w], [m], obj) for m in masks]
+        wsp = tm.alloc_workspace([w], 2, 4)
+        flips = torch.zeros(steps + 1, dtype=torch.int64, device="cuda")
+        tm.tmask_approx(batches[0], None, 2, 4, mask_fmt=fmt, workspace=wsp)
+        pk, pc, pf = [], [], []
+        for t in range(1, steps + 1):
+            noise.normal_(0.0, 0.02 * 1e-3, generator=gen)
+            w.copy_((w.float() + noise).to(torch.bfloat16))
+            a, c = T.pair(), T.pair()
+            run = lambda: tm.tmask_approx(batches[t & 1], None, 2, 4, mask_fmt=fmt, workspace=wsp)   # noqa: E731
+            if t % 2:
+                T.kernel(a, run)
+                pk.append(a)
+            else:
+                T.call(a, run)
+                pc.append(a)
+            T.call(c, lambda: tm.tmask_flip_count([masks[t & 1]], [masks[(t - 1) & 1]], [side], flips[t:t + 1], mask_fmt=fmt))
+            pf.append(c)
+        torch.cuda.synchronize()
+        half = steps // 2
+        kms, cms, fms = T.ms(pk[half // 2:]), T.ms(pc[half // 2:]), T.ms(pf[half:])
+        byts = algorithmic_bytes(weights, 1, 2, 2, 4, bit_masks=(fmt == tm.TMASK_MASK_BITS))["approx"]
+        fr = flips[1:].cpu().numpy() / float(weights)
+        out[label] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(byts, kms)["frac"], "call_frac": hbm(byts, cms)["frac"],
+                      "weights_per_s": weights / (cms * 1e-3), "flip_count_ms": fms,
+                      "flip_fraction_mean": float(fr.mean()), "flip_fraction_last": float(fr[-1])}
+    return out
+
+
+def spmm24_section(tm, torch, T, reps: int = 20, tokens: int = 8192):
+    """The two training products with the packed 2:4 operands of one BERT-large-shaped bf16 layer (W: 4096 x 1024):
+    forward y = x W^T with (vals, idx), backward dx = g W with (valsT, idxT).  MFMA-bound work with its own roofline:
+    the flops the method executes (half of the dense product's: tokens * rows * cols) and the dense-equivalent figure,
+    both against the dense bf16 peak, next to the dense library product of the same shape."""
     rows, cols = 4096, 1024
     w = (torch.randn((rows, cols), device="cuda") * 0.02).to(torch.bfloat16)
-    pk = tm.alloc_packed(w, N_KEEP, M_BLOCK)
-    tm.tmask_approx_pack([w], None, [pk], N_KEEP, M_BLOCK)
+    pk = tm.alloc_packed(w, 2, 4)
+    tm.tmask_approx_pack([w], None, [pk], 2, 4)
     out = {}
-    ovh = ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
     for name, vals, idx, r, c in (("forward", pk[0], pk[1], rows, cols), ("backward", pk[2], pk[3], cols, rows)):
         xs = [torch.randn((tokens, c), device="cuda").to(torch.bfloat16) for _ in range(3)]
         ys = [torch.empty((tokens, r), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
-        for k in range(3):
-            tm.tmask_spmm24(vals, idx, r, c, xs[k], ys[k])
-        torch.cuda.synchronize()
-        evs = [(ev.create(), ev.create()) for _ in range(reps)]
-        for k in range(reps):
-            tm.tmask_profile_next(*evs[k])
-            tm.tmask_spmm24(vals, idx, r, c, xs[k % 3], ys[k % 3])
-        torch.cuda.synchronize()
-        ms = float(np.median([ev.elapsed_ms(a, b) for a, b in evs])) - ovh
-        tflops = 2.0 * tokens * r * c / (ms * 1e-3) / 1e12
-        # the dense library product of the same shape, for context
+        kms, _ = T.measure(lambda k: tm.tmask_spmm24(vals, idx, r, c, xs[k % 3], ys[k % 3]), reps, warm=3)
         wd = torch.randn((r, c), device="cuda").to(torch.bfloat16)
         for k in range(3):
             torch.matmul(xs[k], wd.t(), out=ys[k])
         torch.cuda.synchronize()
-        tev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for k, (a, b) in enumerate(tev):
-            a.record()
-            torch.matmul(xs[k % 3], wd.t(), out=ys[k % 3])
-            b.record()
+        pairs = [T.pair() for _ in range(reps)]
+        for k in range(reps):
+            T.call(pairs[k], lambda: torch.matmul(xs[k % 3], wd.t(), out=ys[k % 3]))
         torch.cuda.synchronize()
-        dms = float(np.median([a.elapsed_time(b) for a, b in tev]))
-        out[name] = {"shape": "tokens %d x Wd %d x %d, bf16 in, bf16 out" % (tokens, r, c), "kernel_ms": ms,
-                     "roofline": {"bound": "mfma", "achieved": tflops, "peak": 2500.0, "unit": "TFLOP/s",
-                                  "frac": tflops / 2500.0, "traffic": None,
-                                  "note": "dense-equivalent flops against the dense bf16 peak"},
-                     "dense_library_ms": dms}
+        dms = T.ms(pairs)
+        own = 1.0 * tokens * r * c / (kms * 1e-3) / 1e12          # 2 flops x half the products
+        out[name] = {"shape": "tokens %d x Wd %d x %d, bf16 in, bf16 out" % (tokens, r, c), "kernel_ms": kms,
+                     "roofline": {"bound": "mfma", "achieved": own, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": own / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                                  "note": "flops the kernel executes (the kept half of the products) against the dense bf16 peak"},
+                     "dense_equivalent_TFLOPs": 2 * own, "dense_equivalent_frac": 2 * own / MFMA_BF16_PEAK_TFLOPS,
+                     "dense_library_ms": dms, "speedup_over_dense_library": dms / kms}
     return out
 
 
-def device_copy_rate(torch, mib: int = 256, reps: int = 10):
-    """Context for the roofline fractions: what a plain device-to-device copy (as many bytes written as read)
-    reaches on this GPU, three rotating buffer pairs, median of `reps`."""
+def device_copy_section(torch, T, mib: int = 256, reps: int = 10):
+    """Context for the fractions: what a plain device-to-device copy reaches, three rotating buffer pairs."""
     n = mib * 1024 * 1024 // 4
     src = [torch.ones(n, dtype=torch.float32, device="cuda") for _ in range(3)]
     dst = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(3)]
     for k in range(3):
         dst[k].copy_(src[k])
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for k, (a, b) in enumerate(evs):
-        a.record()
-        dst[k % 3].copy_(src[k % 3])
-        b.record()
+    pairs = [T.pair() for _ in range(reps)]
+    for k in range(reps):
+        T.call(pairs[k], lambda: dst[k % 3].copy_(src[k % 3]))
     torch.cuda.synchronize()
-    ms = float(np.median([a.elapsed_time(b) for a, b in evs]))
-    gbs = 2 * n * 4 / (ms * 1e-3) / 1e9
-    return {"what": "torch copy_ of %d MiB fp32, bytes read + bytes written" % mib, "ms": ms, "achieved_GBs": gbs,
-            "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    ms = T.ms(pairs)
+    r = hbm(2 * n * 4, ms)
+    return {"what": "torch copy_ of %d MiB fp32, bytes read + bytes written" % mib, "ms": ms,
+            "achieved_GBs": r["achieved_GBs"], "frac_of_hbm_peak": r["frac"]}
 
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline_section(mats_np, N, M, min_s: float = 10.0, many_s: float = 6.0):
+    """The oracle as it stands (plain C, gcc -O2, never tuned) on host cores, on a bounded sample of the headline
+    workload: full steps (approx + exact + apply_pack + score).  One thread, then all host cores this process may use:
+    the same single-thread routines run on row bands of the sample side by side (blocks are independent)."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+
+    sample = mats_np[:6]                      # one encoder layer: 4 x 1024^2, 4096x1024, 1024x4096
+    sample_weights = sum(w.size for w in sample)
+
+    def full_step(w):
+        am, _ = oracle.approx(w, N, M)
+        em, _ = oracle.exact(w, N, M)
+        oracle.apply_pack(w, em, N, M)
+        oracle.score(w, am, N, M)
+        return w.size
+
+    t0 = time.perf_counter()
+    done = 0
+    while time.perf_counter() - t0 < min_s:
+        for w in sample:
+            done += full_step(w)
+            if time.perf_counter() - t0 > 3 * min_s:
+                break
+    one_dt = time.perf_counter() - t0
+    one = {"value": done / one_dt, "unit": "weights/s", "cores": 1, "seconds": one_dt, "weights": done}
+
+    usable = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cap = int(os.environ.get("OMP_NUM_THREADS", "0") or 0)
+    threads = max(1, min(usable, cap) if cap > 0 else usable)
+    bands = []
+    for w in sample:
+        step_rows = 256
+        bands += [np.ascontiguousarray(w[r:r + step_rows]) for r in range(0, w.shape[0], step_rows)]
+    t0 = time.perf_counter()
+    done_many = 0
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        while time.perf_counter() - t0 < many_s:
+            done_many += sum(pool.map(full_step, bands))
+    many_dt = time.perf_counter() - t0
+    return {"value": done_many / many_dt, "unit": "weights/s", "cores": threads, "kind": "oracle",
+            "sample": "full steps (approx+exact+apply_pack+score, %d:%d) of the C oracle, gcc -O2, on one encoder layer of the "
+                      "headline set (6 bf16 matrices, %d weights of the workload's %d), repeated for %.1f s; all cores = "
+                      "the single-thread routines on 256-row bands side by side in %d threads" %
+                      (N, M, sample_weights, sum(w.size for w in mats_np), many_dt, threads),
+            "single_thread": one, "cpu_model": cpu_model(), "host_logical_cpus": os.cpu_count(),
+            "cpus_usable_by_this_process": usable}
+
+
+def square_sweep(tm, torch, T, side, calls, dts, ms, fmt, reps):
+    """One square matrix, chosen calls, dtype x N:M (N = M/2): kernel and whole-call event times, as measured."""
+    out = {"side": side, "mask_format": "bits" if fmt else "u8", "marker_overhead_ms": T.marker_ms, "rows": []}
+    for dt in dts:
+        nb = 3
+        ws = [(torch.randn((side, side), device="cuda") * 0.02).to(torch.float32 if dt == "f32" else torch.bfloat16)
+              for _ in range(nb)]
+        es = 4 if dt == "f32" else 2
+        Tw = side * side
+        for M in ms:
+            N = M // 2
+            masks = [tm.alloc_masks([w], fmt)[0] for w in ws]
+            obj = torch.zeros(1, dtype=torch.float64, device="cuda")
+            wsp = tm.alloc_workspace([ws[0]], N, M)
+            sout = torch.zeros(tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda")
+            pb = torch.zeros(Tw // (M * M), dtype=torch.float32, device="cuda")
+            packeds = [tm.alloc_packed(ws[0], N, M) for _ in range(nb)]
+            flips = torch.zeros(1, dtype=torch.int64, device="cuda")
+            douts = [torch.empty_like(ws[0]) for _ in range(nb)]
+            viol = torch.zeros(1, dtype=torch.int64, device="cuda")
+            alg = algorithmic_bytes(Tw, 1, es, N, M, bit_masks=bool(fmt))
+            table = {
+                "approx": ("approx", lambda k: tm.tmask_approx([ws[k % nb]], [masks[k % nb]], N, M, objective=obj, mask_fmt=fmt, workspace=wsp)),
+                "exact": ("exact", lambda k: tm.tmask_exact([ws[k % nb]], [masks[k % nb]], N, M, objective=obj, mask_fmt=fmt, workspace=wsp)),
+                "prune1d": ("prune1d", lambda k: tm.tmask_prune_1d([ws[k % nb]], [masks[k % nb]], N, M, objective=obj, mask_fmt=fmt, workspace=wsp)),
+                "score": ("score", lambda k: tm.tmask_score([ws[k % nb]], [masks[k % nb]], N, M, sout, per_block_obj=pb, mask_fmt=fmt, workspace=wsp)),
+                "pack": ("pack", lambda k: tm.tmask_apply_pack([ws[k % nb]], [masks[k % nb]], [packeds[k % nb]], N, M, mask_fmt=fmt)),
+                "fused": ("approx_pack", lambda k: tm.tmask_approx_pack([ws[k % nb]], None, [packeds[k % nb]], N, M, mask_fmt=fmt)),
+                "fusedm": ("approx_pack_mask", lambda k: tm.tmask_approx_pack([ws[k % nb]], [masks[k % nb]], [packeds[k % nb]], N, M, mask_fmt=fmt)),
+                "flip": ("flip", lambda k: tm.tmask_flip_count([masks[k % nb]], [masks[(k + 1) % nb]], [side], flips, mask_fmt=fmt)),
+                "dense": ("dense", lambda k: tm.tmask_apply_dense([ws[k % nb]], [masks[k % nb]], [douts[k % nb]], M, False, mask_fmt=fmt)),
+                "absorb": ("dense", lambda k: tm.tmask_apply_dense([ws[k % nb]], [masks[k % nb]], [douts[k % nb]], M, True, mask_fmt=fmt)),
+                "adense": ("approx_dense", lambda k: tm.tmask_approx_dense([ws[k % nb]], None, [douts[k % nb]], N, M, mask_fmt=fmt)),
+                "p1dense": ("approx_dense", lambda k: tm.tmask_prune_1d_dense([ws[k % nb]], None, [douts[k % nb]], N, M, False, mask_fmt=fmt)),
+                "p1absorb": ("approx_dense", lambda k: tm.tmask_prune_1d_dense([ws[k % nb]], None, [douts[k % nb]], N, M, True, mask_fmt=fmt)),
+                "viol": ("viol", lambda k: tm.tmask_pattern_violations([ws[k % nb]], [masks[k % nb]], viol, mask_fmt=fmt)),
+            }
+            for call in calls:
+                key, fn = table[call]
+                if call in ("score", "pack", "flip", "dense", "absorb", "viol"):
+                    for k in range(nb):
+                        tm.tmask_approx([ws[k]], [masks[k]], N, M, mask_fmt=fmt)
+                kms, cms = T.measure(fn, reps)
+                out["rows"].append({"call": call, "dtype": dt, "N": N, "M": M, "kernel_ms": kms, "call_ms": cms,
+                                    "frac": hbm(alg[key], kms)["frac"], "call_frac": hbm(alg[key], cms)["frac"],
+                                    "weights_per_s": Tw / (kms * 1e-3)})
+                print("# %-8s %-4s %d:%-2d kernel %8.1f us (%4.1f%% of 8 TB/s)  call %8.1f us" %
+                      (call, dt, N, M, kms * 1e3, 100 * hbm(alg[key], kms)["frac"], cms * 1e3), file=sys.stderr, flush=True)
+        del ws
+    return out
+
+
+def spmm_sweep(tm, torch, T, shapes, tokens, reps):
+    out = []
+    for rows, cols in shapes:
+        w = (torch.randn((rows, cols), device="cuda") * 0.02).to(torch.bfloat16)
+        pk = tm.alloc_packed(w, 2, 4)
+        tm.tmask_approx_pack([w], None, [pk], 2, 4)
+        xs = [torch.randn((tokens, cols), device="cuda").to(torch.bfloat16) for _ in range(3)]
+        ys = [torch.empty((tokens, rows), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+        kms, _ = T.measure(lambda k: tm.tmask_spmm24(pk[0], pk[1], rows, cols, xs[k % 3], ys[k % 3]), reps, warm=3)
+        wd = w.clone()
+        pairs = [T.pair() for _ in range(reps)]
+        for k in range(3):
+            torch.matmul(xs[k], wd.t(), out=ys[k])
+        for k in range(reps):
+            T.call(pairs[k], lambda: torch.matmul(xs[k % 3], wd.t(), out=ys[k % 3]))
+        torch.cuda.synchronize()
+        dms = T.ms(pairs)
+        own = 1.0 * tokens * rows * cols / (kms * 1e-3) / 1e12
+        out.append({"rows": rows, "cols": cols, "tokens": tokens, "kernel_ms": kms, "own_TFLOPs": own,
+                    "own_frac": own / MFMA_BF16_PEAK_TFLOPS, "dense_library_ms": dms})
+        print("# spmm24 %dx%d tokens %d: %.1f us, %.0f TFLOP/s own (%.1f%%), dense library %.1f us" %
+              (rows, cols, tokens, kms * 1e3, own, 100 * own / MFMA_BF16_PEAK_TFLOPS, dms * 1e3), file=sys.stderr, flush=True)
+    return out
+
+
+# ------------------------------------------------------------------------------------------------------------------
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--copies", type=int, default=8, help="distinct buffer sets rotated through")
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--copies", type=int, default=3, help="distinct buffer sets rotated through (each 1.9 GB on the headline set)")
+    ap.add_argument("--sections", default=",".join(ALL_SECTIONS), help="comma list of: " + ", ".join(ALL_SECTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-largest", action="store_true")
     ap.add_argument("--event-every", type=int, default=4,
-                    help="bracket the four main kernels with hipEvents on every n-th timed step (0 = never)")
-    ap.add_argument("--graph", action="store_true",
-                    help="steps without kernel events replay a HIP graph of the step's seven launches, one graph per "
-                         "buffer set (measured slightly slower than eager launches here: 132 vs 128 us per step)")
+                    help="kernel events on every n-th timed step, whole-call events n/2 steps later (0 = never)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) for scaling rocprofv3 --pmc counters")
+    ap.add_argument("--square", type=int, default=0, help="instead of the sections: sweep calls on one SIDE x SIDE matrix")
+    ap.add_argument("--calls", default="approx,exact,score,pack")
+    ap.add_argument("--dts", default="f32,bf16")
+    ap.add_argument("--ms", default="4,8,16")
+    ap.add_argument("--fmt", type=int, default=0, help="--square: 0 = U8 masks, 1 = bit masks")
+    ap.add_argument("--reps", type=int, default=10)
+    ap.add_argument("--spmm-shapes", default="", help="instead of the sections: tmask_spmm24 on ROWSxCOLS,... shapes")
+    ap.add_argument("--tokens", type=int, default=8192)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (blocks are independent: the path shards by matrix or by block-row band without any exchange); "
-              "run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (blocks are independent: the path shards by "
+              "matrix or by block-row band without any exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -287,123 +573,62 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     tm.load_library()
-    ev = HipEvents()
+    T = Timer(tm, torch)
 
-    mats_np = wl.config2()
-    n_mats = len(mats_np)
-    weights = sum(w.size for w in mats_np)
-    N, M = N_KEEP, M_BLOCK
-
-    sets = []
-    for _ in range(args.copies):
-        ws = [torch.from_numpy(w).cuda() for w in mats_np]
-        amask, emask = tm.alloc_masks(ws), tm.alloc_masks(ws)
-        aobj = torch.zeros(n_mats, dtype=torch.float64, device="cuda")
-        eobj = torch.zeros(n_mats, dtype=torch.float64, device="cuda")
-        packed = [tm.alloc_packed(w, N, M) for w in ws]
-        sout = torch.zeros(n_mats * tm.SCORE_OUT_BYTES, dtype=torch.uint8, device="cuda")
-        pb = torch.zeros(weights // (M * M), dtype=torch.float32, device="cuda")
-        sets.append({
-            "approx": tm.MatBatch(ws, amask, aobj), "exact": tm.MatBatch(ws, emask, eobj),
-            "pack": tm.PackBatch(ws, emask, packed, N, M), "score": tm.MatBatch(ws, amask, None),
-            "sout": sout, "pb": pb,
-        })
-    wsp = tm.alloc_workspace(sets[0]["approx"].ws, N, M)
-    names = ("approx", "exact", "pack", "score")
-
-    def step(k: int, events=None):
-        s = sets[k % args.copies]
-        if events:
-            tm.tmask_profile_next(*events["approx"])
-        tm.tmask_approx(s["approx"], None, N, M, workspace=wsp)
-        if events:
-            tm.tmask_profile_next(*events["exact"])
-        tm.tmask_exact(s["exact"], None, N, M, workspace=wsp)
-        if events:
-            tm.tmask_profile_next(*events["pack"])
-        tm.tmask_apply_pack(s["pack"], None, None, N, M)
-        if events:
-            tm.tmask_profile_next(*events["score"])
-        tm.tmask_score(s["score"], None, N, M, s["sout"], per_block_obj=s["pb"], workspace=wsp)
-
-    for k in range(args.warmup):
-        step(k)
-    torch.cuda.synchronize()
-
-    # Optional: the step's seven short launches (four main kernels, three second-stage reductions) recorded once
-    # per buffer set into a HIP graph.
-    graphs = None
-    if args.graph:
-        try:
-            side = torch.cuda.Stream()
-            graphs = []
-            for k in range(args.copies):
-                side.wait_stream(torch.cuda.current_stream())
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g, stream=side):
-                    step(k)
-                graphs.append(g)
-            torch.cuda.synchronize()
-            for g in graphs:
-                g.replay()
-            torch.cuda.synchronize()
-        except Exception as e:      # capture unavailable: fall back to eager launches and say so
-            print("bench.py: graph capture failed (%s), launching eagerly" % e, file=sys.stderr)
-            graphs = None
-
-    # timed region: exactly --steps steps; per-kernel hipEvents ride along inside it
-    probe = [k for k in range(args.steps) if args.event_every and k % args.event_every == 0]
-    evs = {k: {n: (ev.create(), ev.create()) for n in names} for k in probe}
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        if graphs is not None and k not in evs:
-            graphs[k % args.copies].replay()
-        else:
-            step(k, evs.get(k))
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    overhead_ms = ev.empty_bracket_ms(torch.cuda.current_stream().cuda_stream)
-    if not evs:
-        print(json.dumps({"ms_per_step": ms_per_step, "value": weights / (ms_per_step * 1e-3), "note": "no kernel events"}))
+    if args.square:
+        print(json.dumps(square_sweep(tm, torch, T, args.square, args.calls.split(","), args.dts.split(","),
+                                      [int(x) for x in args.ms.split(",")], args.fmt, args.reps)))
         return
-    raw_ms = {n: float(np.mean([ev.elapsed_ms(*e[n]) for e in evs.values()])) for n in names}
-    # a bracketed kernel's elapsed time includes the two marker packets; take that constant out
-    kern_ms = {n: max(raw_ms[n] - overhead_ms, 1e-6) for n in names}
-    alg = algorithmic_bytes(weights, n_mats, 4, N, M)
-    traffic = read_pmc_traffic(os.path.join(ROOT, "profiles", "pmc_traffic_resnet50_f32_2of4.md"))
-    kernels = {}
-    for n in names:
-        gbs = alg[n] / (kern_ms[n] * 1e-3) / 1e9
-        kernels[n] = {"kernel_ms": kern_ms[n], "event_ms_raw": raw_ms[n], "algorithmic_bytes": alg[n], "achieved_GBs": gbs,
-                      "frac": gbs / HBM_PEAK_GBS, "weights_per_s": weights / (kern_ms[n] * 1e-3),
-                      "traffic": traffic.get(n)}
-    dom = max(names, key=lambda n: kern_ms[n])
+    if args.spmm_shapes:
+        shapes = [tuple(int(v) for v in s.split("x")) for s in args.spmm_shapes.split(",")]
+        print(json.dumps({"spmm24": spmm_sweep(tm, torch, T, shapes, args.tokens, args.reps)}))
+        return
+
+    sections = [s for s in args.sections.split(",") if s]
+    if args.no_cpu_baseline and "cpu_baseline" in sections:
+        sections.remove("cpu_baseline")
+    N, M = 2, 4
+    t_gen = time.perf_counter()
+    mats_np = wl.config3()
+    weights = sum(w.size for w in mats_np)
+    t_gen = time.perf_counter() - t_gen
+    names3 = {"approx": "approx24_kernel<1, 0>", "exact": "exact24_kernel<1, 0>",
+              "pack": "pack24_kernel<1, 0, 32, 4, 4>", "score": "score_kernel<1, 4, 0>"}
 
     result = {
         "metric": "transposable-mask weights/sec (approx & exact) + % of HBM roofline, 1xMI355X",
-        "value": weights / (ms_per_step * 1e-3),
-        "unit": "weights/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "value": None, "unit": "weights/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "ResNet-50-shaped conv weight set: 52 fp32 matrices, 23445504 weights, "
-                               "Kaiming-normal, seeded; N:M=2:4; one step = approx+exact+apply_pack+score, "
-                               "each one batched launch over all layers; U8 masks; %d rotating buffer sets" % args.copies,
-                   "N": N, "M": M, "mask_format": "u8", "weights": weights, "matrices": n_mats},
-        "roofline": {"bound": "hbm", "kernel": KERNEL_NAMES[dom], "achieved": kernels[dom]["achieved_GBs"],
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["frac"],
-                     "traffic": kernels[dom]["traffic"]},
-        "kernels": kernels,
-        "approx_weights_per_s": kernels["approx"]["weights_per_s"],
-        "exact_weights_per_s": kernels["exact"]["weights_per_s"],
-        "exact_over_approx_time": kern_ms["exact"] / kern_ms["approx"],
-        "event_overhead_ms": overhead_ms,
-        "launch": ("HIP graph replay of the step (one graph per buffer set); every %d-th step eager with kernel events"
-                   % args.event_every) if graphs is not None else "eager",
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "BERT-large-shaped linear set (the largest configuration): 144 bf16 matrices (24 x {4 x "
+                               "1024x1024, 4096x1024, 1024x4096}), 301989888 weights, N(0,0.02) rounded to bf16, seeded; "
+                               "N:M=2:4; one step = tmask_approx + tmask_exact + tmask_apply_pack + tmask_score, each one "
+                               "batched launch over all matrices plus its reduce launch; U8 masks; %d rotating buffer sets"
+                               % args.copies,
+                   "N": N, "M": M, "mask_format": "u8", "weights": weights, "matrices": len(mats_np)},
+        "marker_overhead_ms": T.marker_ms,
+        "input_generation_s": t_gen,
     }
+    if "step" in sections:
+        st = step_section(tm, torch, T, mats_np, N, M, args.steps, args.warmup, args.copies, args.event_every, names3,
+                          "bert_large_bf16_2of4")
+        k = st["kernels"]
+        result["ms_per_step"] = st["ms_per_step"]
+        result["value"] = weights / (st["ms_per_step"] * 1e-3)
+        if "kernel_ms" in k["approx"]:
+            dom = max(k, key=lambda n: k[n]["kernel_ms"])
+            result["roofline"] = {"bound": "hbm", "kernel": k[dom]["kernel"], "achieved": k[dom]["achieved_GBs"],
+                                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k[dom]["frac"],
+                                  "traffic": k[dom]["traffic"], "traffic_source": st["traffic_source"],
+                                  "timing": "hipEvents recorded by the library around the kernel, inside the timed region, as "
+                                            "measured (marker overhead not subtracted)"}
+            result["approx_weights_per_s"] = k["approx"]["weights_per_s"]
+            result["exact_weights_per_s"] = k["exact"]["weights_per_s"]
+            result["approx_frac_of_hbm_peak"] = k["approx"]["frac"]
+            result["exact_over_approx_time"] = k["exact"]["kernel_ms"] / k["approx"]["kernel_ms"]
+        result["kernels"] = k
+        result["quality"] = st["quality"]
     if args.pmc_calibration:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -411,17 +636,29 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_largest:
-        result["largest_config"] = largest_config_approx(tm, torch, ev, reps=20)
-        result["largest_config_bit_masks"] = largest_config_approx(tm, torch, ev, reps=20, bit_masks=True)
-    del sets
-    result["fused_approx_pack"] = fused_approx_pack(tm, torch, ev, mats_np, copies=min(args.copies, 6), reps=24)
-    result["approx_dense"] = approx_dense(tm, torch, ev, mats_np, copies=min(args.copies, 6), reps=24)
-    result["four_of_eight"] = four_of_eight(tm, torch, ev, mats_np, copies=min(args.copies, 3), reps=12)
-    result["spmm24"] = spmm24_products(tm, torch, ev)
-    result["device_copy"] = device_copy_rate(torch)
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(mats_np)
+    if "four_of_eight" in sections:
+        result["four_of_eight"] = four_of_eight_section(tm, torch, T, mats_np, copies=2, reps=10)
+    if "one_pass" in sections:
+        result["one_pass"] = one_pass_section(tm, torch, T, mats_np, copies=2, reps=10)
+    if "config2" in sections:
+        m2 = wl.config2()
+        names2 = {"approx": "approx24_kernel<0, 0>", "exact": "exact24_kernel<0, 0>",
+                  "pack": "pack24_kernel<0, 0, 64, 4, 4>", "score": "score_kernel<0, 4, 0>"}
+        st2 = step_section(tm, torch, T, m2, 2, 4, 200, 20, 8, 4, names2, "resnet50_f32_2of4")
+        st2["what"] = ("ResNet-50-shaped conv set: 52 fp32 matrices, 23445504 weights, Kaiming-normal, 2:4, same step, "
+                       "8 rotating buffer sets")
+        st2["value"] = st2["weights"] / (st2["ms_per_step"] * 1e-3)
+        result["config2"] = st2
+    if "config4" in sections:
+        result["config4"] = config4_section(tm, torch, T, wl, reps=6)
+    if "config5" in sections:
+        result["config5"] = config5_section(tm, torch, T, steps=24)
+    if "spmm24" in sections:
+        result["spmm24"] = spmm24_section(tm, torch, T)
+    if "device_copy" in sections:
+        result["device_copy"] = device_copy_section(torch, T)
+    if "cpu_baseline" in sections:
+        result["cpu_baseline"] = cpu_baseline_section(mats_np, N, M)
     print(json.dumps(result))
 
 
