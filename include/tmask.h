@@ -8,7 +8,7 @@
  *
  * Conventions
  *   N            entries KEPT per row and per column of a block (Eq. 3: row/column sums of S are N);
- *                K = M - N entries are pruned.  Supported: M in {4, 8, 16}, 0 < N < M.
+ *                K = M - N entries are pruned.  Supported: M in {4, 8, 16, 32}, 0 < N < M.
  *   S_ij = 1     W_ij is kept (Eq. 3).
  *   magnitude    |W_ij| is ordered by its bit pattern with the sign cleared, compared as an unsigned
  *                integer: -0 == +0, denormals are not flushed, +Inf > finite, NaN > Inf.
@@ -24,12 +24,17 @@
  *   of the enqueued work; calls that overlap on different streams need different workspaces.
  *
  * Layout requirements (checked; violations return TMASK_ERR_SHAPE / TMASK_ERR_ALIGN)
- *   rows and cols multiples of M; ld >= cols (ld in elements); rows*cols/M^2 < 2^31;
- *   `w` 16-byte aligned, ld*sizeof(element) and cols*sizeof(element) multiples of 16
- *   (i.e. ld, cols multiples of 4 for fp32 and of 8 for bf16): tiles are read with 16-byte loads.
- *   U8 mask: mask_ld >= cols; mask pointer and mask_ld multiples of 4 (fp32) or 8 (bf16) bytes.
- *   BITS mask: cols a multiple of 8, mask_ld >= cols/8 bytes.
- *   Packed outputs: vals and valsT 4-byte aligned, dense (no leading dimension).
+ *   rows and cols multiples of M (the paper's only requirement: Sec. 4 speaks of the M x M blocks of a weight
+ *   matrix); ld >= cols (ld in elements); ld, mask_ld < 2^31; rows/M * ceil(cols/4) < 2^31; every pointer aligned
+ *   to its element type.  U8 mask: mask_ld >= cols.  BITS mask: cols a multiple of 8, mask_ld >= cols/8 bytes.
+ *   Packed outputs are dense (no leading dimension).
+ * Fast and slow paths (same results, bit for bit where the result is unique)
+ *   The streaming kernels read 16-byte strips: they need `w` 16-byte aligned with ld*sizeof(element) and
+ *   cols*sizeof(element) multiples of 16 (ld, cols multiples of 4 for fp32, of 8 for bf16), a U8 mask pointer and
+ *   mask_ld that are multiples of 4 (fp32) or 8 (bf16) bytes, packed value arrays 4-byte aligned (8-byte for the
+ *   one-pass tmask_approx_pack kernels), dense outputs 16-byte aligned with a 16-byte pitch.  A call in which some
+ *   matrix misses any of this, and every call with M = 32, runs on element-wise kernels instead (one lane per
+ *   column of a block): correct for every layout above, bound by the vector ALU instead of by memory.
  *
  * Errors
  *   All argument errors are detected on the host before anything is enqueued and leave the outputs
@@ -56,11 +61,11 @@ enum {
     TMASK_OK = 0,
     TMASK_ERR_NULL = -1,      /* a required pointer is NULL */
     TMASK_ERR_SHAPE = -2,     /* sizes <= 0, rows/cols not multiples of M, ld < cols, too many blocks */
-    TMASK_ERR_NM = -3,        /* need M in {4,8,16} and 0 < N < M */
+    TMASK_ERR_NM = -3,        /* need M in {4,8,16,32} and 0 < N < M */
     TMASK_ERR_DTYPE = -4,     /* unknown dtype or mask format */
     TMASK_ERR_WORKSPACE = -5, /* workspace NULL, misaligned or smaller than tmask_workspace_bytes() */
     TMASK_ERR_HIP = -6,       /* a HIP call failed; text in tmask_last_error() */
-    TMASK_ERR_ALIGN = -7      /* pointer / leading-dimension alignment (see layout requirements) */
+    TMASK_ERR_ALIGN = -7      /* a pointer that is not aligned to its element type (see layout requirements) */
 };
 
 /* One 2-D weight matrix and where its mask goes. */
@@ -103,9 +108,10 @@ int tmask_approx_noalloc(const tmask_mat *mats, int n_mats, tmask_dtype dt, int 
  * Optimal mask of Eq. 3 per block (Sec. 4, "Reduction to Min-Cost Flow", Fig. 3): exactly N kept
  * per row and column, maximum retained L1.  2:4 blocks are solved by evaluating all 90 feasible
  * patterns in fp32; other (N, M) by successive shortest augmenting paths on the bipartite
- * row/column network with magnitudes truncated per block to 27 (M<=8) or 26 (M=16) significant
- * bits below the block maximum, which costs less than M*(M-N)*2^-26 (resp. 2^-25) of the block
- * maximum in retained L1 (below 1e-5 relative for every supported N:M).  Among equally good
+ * row/column network with magnitudes truncated per block to 27 (M<=8), 26 (M=16) or 25 (M=32) significant
+ * bits below the block maximum, which costs less than M*(M-N)*2^-26 (resp. 2^-25, 2^-24) of the block
+ * maximum in retained L1 (below 1e-5 relative for M <= 16; at M = 32 below 6e-5 in the worst case and
+ * about 1e-7 on real-valued data).  Among equally good
  * masks the choice is deterministic but unspecified.  Inputs must be finite for optimality; with
  * NaN/Inf present the mask is still valid (exactly N per row/column).
  */
@@ -157,8 +163,8 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
  * and `mask` is required (TMASK_ERR_NULL without it).
  * A workspace is needed only if some `objective` is given.  The `w`, mask and packed-output layout
  * requirements are those of tmask_approx and tmask_apply_pack; for 2:4, `vals` and `valsT` must
- * be 8-byte aligned (TMASK_ERR_ALIGN); for 4:8 outputs that are not 8-byte aligned take the
- * two-step path (and then need `mask`).
+ * be 8-byte aligned for the one-pass kernels; a call whose matrices or outputs miss that (or the alignment of the
+ * strip kernels, see above) takes the two-step path (and then needs `mask`).
  */
 typedef struct {
     const void *w; int64_t rows, cols, ld;
@@ -275,8 +281,9 @@ int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int 
  * dense copy of the weights and masks it before the forward pass): out <- W (.) S with S the mask tmask_approx
  * computes, in W's type, pruned entries +0.  `mask` is an OUTPUT here and may be NULL for all matrices (then no
  * mask is written; give it for all or for none, else TMASK_ERR_NULL); `out` may be `w` itself.  One pass over W.
- * Shape and alignment requirements are those of tmask_approx for `w` and the mask and of tmask_apply_dense for
- * `out` (16-byte aligned, ld_out >= cols, row pitch a multiple of 16 bytes).  No workspace, no objective.
+ * Shape requirements are those of tmask_approx for `w` and the mask; ld_out >= cols.  (An `out` that is not 16-byte
+ * aligned with a 16-byte pitch sends the call to the element-wise kernels, like an unaligned `w`.)  No workspace, no
+ * objective.
  */
 typedef struct {
     const void *w; int64_t ld;

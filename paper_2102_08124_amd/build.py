@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtmask.so")
-SOURCES = ["tmask_kernels.hip", "tmask_spmm.hip", "tmask_extras.hip"]
+SOURCES = ["tmask_kernels.hip", "tmask_colwise.hip", "tmask_spmm.hip", "tmask_extras.hip"]
 HEADERS = ["tmask_device.hpp", "tmask_solvers.hpp", "tmask_pack.hpp", "tmask_approx4.hpp", "tmask_networks.hpp", "tmask_approx_sel.hpp", "tmask_pack4.hpp", "tmask_pack8.hpp", "tmask_exact_balance.hpp", "tmask_fused4.hpp", "tmask_host.hpp", os.path.join("..", "..", "include", "tmask.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

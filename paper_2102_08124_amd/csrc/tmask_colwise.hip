@@ -1,0 +1,839 @@
+// tmask: the column-per-lane kernels.  They serve (a) M = 32 for every entry point and (b) M = 4, 8, 16 when a matrix
+// misses the 16-byte alignment the strip kernels read with (only the paper's own requirement is left: rows and cols
+// multiples of M; arXiv 2102.08124, Sec. 4, "a block of size M x M in a weight matrix").  gfx950 only.
+//
+// Layout.  A workgroup is one wavefront and works through tiles of M rows x 64 columns: lane l holds column l of the
+// tile, all M rows, in registers, read and written element by element (no alignment needed).  A block is the M
+// neighbouring lanes [b*M, b*M + M); the wavefront holds 64 / M blocks side by side.  Column-direction work is
+// lane-local; for row-direction work the block is transposed through LDS (pitch M + 1 words, conflict-free), so that
+// lane j of a block holds row j, and the answer travels back as one bit word per row.  Yes/no facts about a row of
+// the block are also read off a wavefront ballot: bits [b*M, b*M + M) of ballot(flag of row i) are row i of block b.
+//
+// These kernels are bound by the vector ALU (pairwise ranks: M - 1 compares per entry and direction), not by HBM.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "../../include/tmask.h"
+#include "tmask_device.hpp"
+#include "tmask_host.hpp"
+
+namespace tmask {
+
+constexpr int kCwThreads = 64;
+constexpr int kMaxCwBatch = 224;
+
+struct CwMat {
+    const void *w;
+    void *mask;          // output of the mask kernels (may be null for the dense one-pass calls), input of score / pack
+    void *aux;           // mask kernels: dense output (or null); score: per-block objective of this matrix (or null)
+    uint32_t ld, mask_ld, ld_aux, cols;
+    uint32_t tpr;        // tiles per block-row = ceil(cols / 64)
+    uint32_t n_tiles;    // tpr * rows / M
+    uint32_t wg0, n_wg;  // first workgroup of this matrix in the launch, and how many it has (each strides over tiles)
+    uint32_t div_mul, div_shift;   // t / tpr
+};
+
+struct CwArgs {
+    CwMat m[kMaxCwBatch];
+    uint32_t n, K, N, partial0;
+    void *partials;
+};
+static_assert(sizeof(CwArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
+
+__device__ __forceinline__ int cw_find(const CwArgs &a, uint32_t wg)
+{
+    int lo = 0, hi = (int)a.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (a.m[mid].wg0 <= wg)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t cw_load(const void *w, size_t idx)
+{
+    if constexpr (DT == kF32)
+        return __builtin_nontemporal_load((const uint32_t *)w + idx);
+    else
+        return (uint32_t)__builtin_nontemporal_load((const uint16_t *)w + idx);
+}
+
+template <int DT>
+__device__ __forceinline__ void cw_store(void *w, size_t idx, uint32_t v)
+{
+    if constexpr (DT == kF32)
+        ((uint32_t *)w)[idx] = v;
+    else
+        ((uint16_t *)w)[idx] = (uint16_t)v;
+}
+
+// |W| as an fp32 bit pattern: the ordering key, and (as a float) the magnitude itself
+template <int DT>
+__device__ __forceinline__ uint32_t cw_key(uint32_t raw)
+{
+    return DT == kF32 ? (raw & 0x7FFFFFFFu) : ((raw << 16) & 0x7FFF0000u);
+}
+
+template <int M>
+__device__ __forceinline__ uint32_t seg_mask()
+{
+    return (uint32_t)((1ull << M) - 1ull);
+}
+
+// bits [blk*M, blk*M + M) of a wavefront ballot
+template <int M>
+__device__ __forceinline__ uint32_t seg_of(lanemask_t b, uint32_t blk)
+{
+    return (uint32_t)(b >> (blk * M)) & seg_mask<M>();
+}
+
+// sum / max over the M lanes of a block (butterfly, fixed order: deterministic)
+template <int M>
+__device__ __forceinline__ float seg_sum(float v)
+{
+#pragma unroll
+    for (int off = M / 2; off >= 1; off >>= 1)
+        v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+template <int M>
+__device__ __forceinline__ uint32_t seg_max(uint32_t v)
+{
+#pragma unroll
+    for (int off = M / 2; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+struct CwTile {
+    uint32_t br, col;
+    bool active;
+};
+
+__device__ __forceinline__ CwTile cw_tile(const CwMat &md, uint32_t t)
+{
+    CwTile p;
+    p.br = (uint32_t)(((uint64_t)t * md.div_mul) >> md.div_shift);
+    p.col = (t - p.br * md.tpr) * 64u + threadIdx.x;
+    p.active = p.col < md.cols;
+    return p;
+}
+
+// ranks of M keys held by one lane under the (key, position) order: r[i] = number of keys that precede key i
+template <int M>
+__device__ __forceinline__ void cw_ranks(const uint32_t (&key)[M], uint32_t (&r)[M])
+{
+#pragma unroll
+    for (int i = 0; i < M; i++)
+        r[i] = 0;
+#pragma unroll
+    for (int i = 0; i < M; i++)
+#pragma unroll
+        for (int i2 = i + 1; i2 < M; i2++) {
+            const uint32_t le = key[i] <= key[i2] ? 1u : 0u;      // position i precedes i2 on ties
+            r[i2] += le;
+            r[i] += 1u - le;
+        }
+}
+
+// Writes the keep flags of the lane's column (bit i of `keep` = row i) as mask entries.
+template <int M, int FMT>
+__device__ __forceinline__ void cw_store_mask(const CwMat &md, const CwTile &p, uint32_t keep)
+{
+    if constexpr (FMT == kMaskU8) {
+        if (p.active) {
+            unsigned char *mb = (unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + p.col;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                mb[(size_t)i * md.mask_ld] = (unsigned char)((keep >> i) & 1u);
+        }
+    } else {
+        // the 64 flags of a row are a ballot; lanes 0..7 each store one of its bytes (cols is a multiple of 8)
+        const uint32_t lane = threadIdx.x;
+        const uint32_t col0 = p.col - lane;
+        unsigned char *mb = (unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + (col0 >> 3) + lane;
+        const bool writer = lane < 8u && col0 + lane * 8u < md.cols;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            const lanemask_t b = lm(p.active && ((keep >> i) & 1u));
+            if (writer)
+                mb[(size_t)i * md.mask_ld] = (unsigned char)(b >> (lane * 8u));
+        }
+    }
+}
+
+// Reads the mask entries of the lane's column into bit i = row i.
+template <int M, int FMT>
+__device__ __forceinline__ uint32_t cw_load_mask(const CwMat &md, const CwTile &p)
+{
+    uint32_t bits = 0;
+    if (p.active) {
+        if constexpr (FMT == kMaskU8) {
+            const unsigned char *mb = (const unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + p.col;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                bits |= (mb[(size_t)i * md.mask_ld] != 0 ? 1u : 0u) << i;
+        } else {
+            const unsigned char *mb = (const unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + (p.col >> 3);
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                bits |= (((uint32_t)mb[(size_t)i * md.mask_ld] >> (p.col & 7u)) & 1u) << i;
+        }
+    }
+    return bits;
+}
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u)
+        return (u >> 16) | 0x0040u;                      // NaN stays NaN
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// =====================================================================================================================
+// Algorithm 1 (rank form), row pruning, and their dense one-pass forms
+// =====================================================================================================================
+
+enum { kCwApprox = 0, kCwRow1D = 1, kCwRow1DAbsorb = 2 };
+
+// keep(i,j) <=> at least K entries of row i precede (i,j) and (Algorithm 1 only) at least K entries of column j do:
+// the rank form of the greedy sweep under the (magnitude, row-major index) order.
+template <int SOLVER, int DT, int M, int FMT>
+__global__ __launch_bounds__(kCwThreads) void cw_mask_kernel(const CwArgs args)
+{
+    constexpr int NB = 64 / M;
+    __shared__ uint32_t T[NB][M][M + 1];
+    __shared__ uint32_t RK[NB][M];
+    const CwMat md = args.m[cw_find(args, blockIdx.x)];
+    const uint32_t lane = threadIdx.x, blk = lane / M, j = lane % M;
+    const uint32_t K = args.K;
+    double total = 0.0;
+    for (uint32_t t = blockIdx.x - md.wg0; t < md.n_tiles; t += md.n_wg) {
+        const CwTile p = cw_tile(md, t);
+        uint32_t raw[M], key[M];
+        const size_t base = (size_t)p.br * M * md.ld + p.col;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            raw[i] = p.active ? cw_load<DT>(md.w, base + (size_t)i * md.ld) : 0u;
+            key[i] = cw_key<DT>(raw[i]);
+        }
+        uint32_t keep = seg_mask<M>();
+        if constexpr (SOLVER == kCwApprox) {
+            uint32_t r[M];
+            cw_ranks<M>(key, r);
+            keep = 0;
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                keep |= (r[i] >= K ? 1u : 0u) << i;
+        }
+        // rows: lane j of the block takes row j
+        __syncthreads();                                  // the previous tile's readers are done
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            T[blk][i][j] = key[i];
+        __syncthreads();
+        {
+            uint32_t rk[M], r[M];
+#pragma unroll
+            for (int c = 0; c < M; c++)
+                rk[c] = T[blk][j][c];
+            cw_ranks<M>(rk, r);
+            uint32_t rowkeep = 0;
+#pragma unroll
+            for (int c = 0; c < M; c++)
+                rowkeep |= (r[c] >= K ? 1u : 0u) << c;
+            RK[blk][j] = rowkeep;
+        }
+        __syncthreads();
+        uint32_t kr = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            kr |= ((RK[blk][i] >> j) & 1u) << i;
+        keep &= kr;
+        if (md.mask)
+            cw_store_mask<M, FMT>(md, p, keep);
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            acc += ((keep >> i) & 1u) ? __uint_as_float(key[i]) : 0.f;
+        total += (double)wave_sum(acc);
+        if (md.aux) {
+            // dense masked copy; with absorption the mean of a row group's pruned weights goes to its kept ones
+            const size_t ob = (size_t)p.br * M * md.ld_aux + p.col;
+#pragma unroll
+            for (int i = 0; i < M; i++) {
+                const bool k = (keep >> i) & 1u;
+                uint32_t o = k ? raw[i] : 0u;
+                if constexpr (SOLVER == kCwRow1DAbsorb) {
+                    const float v = DT == kF32 ? __uint_as_float(raw[i]) : __uint_as_float(raw[i] << 16);
+                    const float ps = seg_sum<M>(k ? 0.f : v);
+                    const uint32_t pc = (uint32_t)M - (uint32_t)__builtin_popcount(seg_of<M>(lm(k), blk));
+                    const float mean = (pc != 0u && pc != (uint32_t)M) ? ps / (float)pc : 0.f;
+                    const float res = k ? v + mean : 0.f;
+                    o = DT == kF32 ? __float_as_uint(res) : f32_to_bf16_rne(res);
+                }
+                if (p.active)
+                    cw_store<DT>(md.aux, ob + (size_t)i * md.ld_aux, o);
+            }
+        }
+    }
+    if (args.partials && threadIdx.x == 0)
+        ((double *)args.partials)[args.partial0 + blockIdx.x] = total;
+}
+
+// =====================================================================================================================
+// Exact: the optimum of Eq. 3 per block by successive shortest augmenting paths on the network of Fig. 3.
+//
+// Costs are integers (|W| scaled by a power of two so that the block maximum lies in [2^(S-1), 2^S), truncated), so
+// path sums are exact and label-correcting search terminates with a predecessor forest.  Start: every column prunes
+// its K lightest rows (cheapest for the row counts it has).  While some row has more than K pruned entries: labels of
+// all rows from the rows with excess (Bellman-Ford, alternating a column step -- reach column j through a pruned
+// entry, lane j holds column j -- and a row step -- leave it through an unpruned entry, lane j holds row j; labels
+// and predecessors are exchanged through LDS), then one augmentation per block along the predecessor chain of its
+// first reachable row that lacks pruned entries.  At convergence every predecessor edge is tight, so the pruning stays
+// cheapest for its row counts, and after (total excess) augmentations it is the optimum.
+// =====================================================================================================================
+
+constexpr int kCwInf = 0x70000000;        // unreachable; kCwInf - 2^S is still above kCwReachable
+constexpr int kCwReachable = 0x40000000;  // |label| <= (M - 1) * 2^S < 2^30
+constexpr uint32_t kCwNone = 0xFFu;
+
+constexpr int cw_cost_bits(int M) { return M == 32 ? 25 : M == 16 ? 26 : 27; }
+
+template <int DT, int M, int FMT>
+__global__ __launch_bounds__(kCwThreads) void cw_exact_kernel(const CwArgs args)
+{
+    constexpr int NB = 64 / M;
+    constexpr int S = cw_cost_bits(M);
+    static_assert((M - 1) * (1ll << S) < kCwReachable, "labels must stay below the reachability threshold");
+    __shared__ uint32_t T[NB][M][M + 1];
+    __shared__ int DROW[NB][M], DCOL[NB][M];
+    __shared__ uint32_t PROW[NB][M], PCOL[NB][M];
+    const CwMat md = args.m[cw_find(args, blockIdx.x)];
+    const uint32_t lane = threadIdx.x, blk = lane / M, j = lane % M;
+    const uint32_t K = args.K;
+    double total = 0.0;
+    for (uint32_t t = blockIdx.x - md.wg0; t < md.n_tiles; t += md.n_wg) {
+        const CwTile p = cw_tile(md, t);
+        uint32_t key[M];
+        const size_t base = (size_t)p.br * M * md.ld + p.col;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            key[i] = cw_key<DT>(p.active ? cw_load<DT>(md.w, base + (size_t)i * md.ld) : 0u);
+        // ---- integer costs, by column (ccol) and, through LDS, by row (crow) ----
+        uint32_t kmax = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            kmax = key[i] > kmax ? key[i] : kmax;
+        kmax = seg_max<M>(kmax);
+        const uint32_t emax = (kmax >> 23) ? (kmax >> 23) : 1u;
+        int ccol[M], crow[M];
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            const uint32_t e = key[i] >> 23;
+            const uint32_t mant = (key[i] & 0x7FFFFFu) | (e ? 0x800000u : 0u);
+            const uint32_t sh = emax - (e ? e : 1u);
+            ccol[i] = sh < 32u ? (int)((mant << (S - 24)) >> sh) : 0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            T[blk][i][j] = (uint32_t)ccol[i];
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < M; c++)
+            crow[c] = (int)T[blk][j][c];
+        // ---- start: the K lightest rows of the lane's column (ties: lower row first) ----
+        uint32_t xcol = 0, xrow = 0;       // bit i of xcol: (i, j) pruned; bit c of xrow: (j, c) pruned
+        {
+            uint32_t ck[M], r[M];
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                ck[i] = (uint32_t)ccol[i];
+            cw_ranks<M>(ck, r);
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                xcol |= (r[i] < K ? 1u : 0u) << i;
+        }
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            const uint32_t rowbits = seg_of<M>(lm((xcol >> i) & 1u), blk);
+            xrow = (j == (uint32_t)i) ? rowbits : xrow;
+        }
+        // a block outside the matrix takes no part: it counts as balanced
+        uint32_t cnt = p.active ? (uint32_t)__builtin_popcount(xrow) : K;
+
+        // ---- augment until no row has more than K pruned entries; at most M*K augmentations per block ----
+        for (int round = 0; round < M * M; round++) {
+            const bool excess = cnt > K;
+            const bool blk_excess = seg_of<M>(lm(excess), blk) != 0u;
+            if (!__any(excess))
+                break;
+            int drow = excess ? 0 : kCwInf;
+            uint32_t prow = kCwNone;
+            __syncthreads();
+            DROW[blk][j] = drow;
+            PROW[blk][j] = prow;
+            __syncthreads();
+            // Labels only ever fall, and a predecessor changes only when its label falls strictly: with exact integer
+            // sums and no negative cycle the predecessor graph is then a forest, also among entries of equal cost.
+            int dcol = kCwInf;
+            uint32_t pcol = 0;
+            for (int it = 0; it <= M; it++) {
+                // column step: the cheapest way into column j, through a pruned entry of a reached row
+#pragma unroll
+                for (int i = 0; i < M; i++) {
+                    const int d = DROW[blk][i];
+                    const int v = d - ccol[i];
+                    const bool better = ((xcol >> i) & 1u) && d < kCwReachable && v < dcol;
+                    dcol = better ? v : dcol;
+                    pcol = better ? (uint32_t)i : pcol;
+                }
+                DCOL[blk][j] = dcol;
+                PCOL[blk][j] = pcol;
+                __syncthreads();
+                // row step: leave a column through an unpruned entry of row j
+                bool changed = false;
+#pragma unroll
+                for (int c = 0; c < M; c++) {
+                    const int v = DCOL[blk][c] + crow[c];
+                    const bool better = !((xrow >> c) & 1u) && v < drow;
+                    drow = better ? v : drow;
+                    prow = better ? (uint32_t)c : prow;
+                    changed = changed || better;
+                }
+                DROW[blk][j] = drow;
+                PROW[blk][j] = prow;
+                __syncthreads();
+                if (!__any(changed))
+                    break;
+            }
+            // the block's first reachable row that lacks pruned entries takes its chain
+            const uint32_t cand = seg_of<M>(lm(cnt < K && drow < kCwReachable), blk);
+            bool walking = blk_excess && cand != 0u;
+            if (!__any(walking))
+                break;                      // cannot happen for 0 < K < M; guards against looping on corrupt state
+            const uint32_t target = walking ? (uint32_t)__builtin_ctz(cand) : 0u;
+            uint32_t r = target, src = kCwNone;
+            for (int step = 0; step < M && __any(walking); step++) {
+                if (walking) {
+                    const uint32_t c = PROW[blk][r];
+                    if (c == kCwNone) {
+                        src = r;
+                        walking = false;
+                    } else {
+                        const uint32_t f = PCOL[blk][c];          // (r, c) becomes pruned, (f, c) becomes unpruned
+                        if (j == c)
+                            xcol ^= (1u << r) | (1u << f);
+                        if (j == r || j == f)
+                            xrow ^= 1u << c;
+                        r = f;
+                    }
+                }
+            }
+            if (walking) {                   // chain of full length: its last row must be the source
+                src = (PROW[blk][r] == kCwNone) ? r : kCwNone;
+            }
+            if (src != kCwNone)
+                cnt += (j == target ? 1u : 0u) - (j == src ? 1u : 0u);
+        }
+        const uint32_t keep = ~xcol & seg_mask<M>();
+        cw_store_mask<M, FMT>(md, p, keep);
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            acc += (p.active && ((keep >> i) & 1u)) ? __uint_as_float(key[i]) : 0.f;
+        total += (double)wave_sum(acc);
+    }
+    if (args.partials && threadIdx.x == 0)
+        ((double *)args.partials)[args.partial0 + blockIdx.x] = total;
+}
+
+// =====================================================================================================================
+// Score (Eq. 3's objective and constraints for a given mask)
+// =====================================================================================================================
+
+template <int DT, int M, int FMT>
+__global__ __launch_bounds__(kCwThreads) void cw_score_kernel(const CwArgs args)
+{
+    const CwMat md = args.m[cw_find(args, blockIdx.x)];
+    const uint32_t lane = threadIdx.x, blk = lane / M, j = lane % M;
+    const uint32_t N = args.N;
+    double retained = 0.0, total = 0.0;
+    unsigned long long kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
+    for (uint32_t t = blockIdx.x - md.wg0; t < md.n_tiles; t += md.n_wg) {
+        const CwTile p = cw_tile(md, t);
+        const size_t base = (size_t)p.br * M * md.ld + p.col;
+        const uint32_t bits = cw_load_mask<M, FMT>(md, p);
+        float ret = 0.f, tot = 0.f;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            const float v = __uint_as_float(cw_key<DT>(p.active ? cw_load<DT>(md.w, base + (size_t)i * md.ld) : 0u));
+            tot += v;
+            ret += ((bits >> i) & 1u) ? v : 0.f;
+        }
+        uint32_t rowcnt = 0;                       // kept entries of row j of the block
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            const uint32_t rb = seg_of<M>(lm((bits >> i) & 1u), blk);
+            rowcnt = (j == (uint32_t)i) ? (uint32_t)__builtin_popcount(rb) : rowcnt;
+        }
+        const uint32_t colcnt = (uint32_t)__builtin_popcount(bits);
+        const uint32_t a = p.active ? 1u : 0u;
+        const uint32_t w_kept = wave_sum(colcnt);
+        const uint32_t w_flags = wave_sum((a & (rowcnt > N ? 1u : 0u)) | ((a & (colcnt > N ? 1u : 0u)) << 8) |
+                                          ((a & (rowcnt != N ? 1u : 0u)) << 16) | ((a & (colcnt != N ? 1u : 0u)) << 24));
+        kept += w_kept;
+        rowv += w_flags & 0xFFu; colv += (w_flags >> 8) & 0xFFu; rowne += (w_flags >> 16) & 0xFFu; colne += w_flags >> 24;
+        const float blk_ret = seg_sum<M>(ret);
+        if (md.aux && p.active && j == 0u)
+            ((float *)md.aux)[(size_t)p.br * (md.cols / M) + p.col / M] = blk_ret;
+        retained += (double)wave_sum(ret);
+        total += (double)wave_sum(tot);
+    }
+    if (threadIdx.x == 0) {
+        ScorePartial *out = (ScorePartial *)args.partials + args.partial0 + blockIdx.x;
+        out->retained = retained; out->total = total;
+        out->kept = kept; out->rowv = rowv; out->colv = colv; out->rowne = rowne; out->colne = colne;
+    }
+}
+
+// =====================================================================================================================
+// Apply + pack, one thread per group of M, two passes in one launch: groups along rows (vals, idx), then groups down
+// columns (valsT, idxT).  A workgroup takes 32 lines x 8 consecutive groups, so that the position bits it assembles
+// in LDS are whole bytes (8 * N * log2(M) bits) wherever the line does not end.
+// =====================================================================================================================
+
+constexpr int kCwPackThreads = 256;
+
+struct CwPack {
+    const void *w;
+    const void *mask;
+    void *vals, *idx, *valsT, *idxT;
+    uint32_t rows, cols, ld, mask_ld;
+    uint32_t wg0, row_wgs;   // first workgroup of this matrix; how many of its workgroups do the row pass
+};
+
+struct CwPackArgs {
+    CwPack d[kMaxCwBatch];
+    uint32_t n, N;
+};
+static_assert(sizeof(CwPackArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
+
+template <int M>
+struct CwLog2 {
+    static constexpr int v = (M == 4) ? 2 : (M == 8) ? 3 : (M == 16) ? 4 : 5;
+};
+
+template <int DT, int M, int FMT>
+__global__ __launch_bounds__(kCwPackThreads) void cw_pack_kernel(const CwPackArgs args)
+{
+    constexpr int IB = CwLog2<M>::v;
+    constexpr int WORDS = (8 * (M - 1) * IB + 31) / 32 + 2;
+    __shared__ uint32_t IDX[32][WORDS];
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].wg0 <= blockIdx.x)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const CwPack d = args.d[lo];
+    const uint32_t N = args.N;
+    uint32_t wg = blockIdx.x - d.wg0;
+    const bool transposed = wg >= d.row_wgs;
+    if (transposed)
+        wg -= d.row_wgs;
+    // the pass's view: n_lines lines of gpl groups; element q of group g of line L is W[L][g*M + q] (row pass) or
+    // W[g*M + q][L] (column pass)
+    const uint32_t n_lines = transposed ? d.cols : d.rows;
+    const uint32_t gpl = (transposed ? d.rows : d.cols) / M;
+    const uint32_t chunks = (gpl + 7u) / 8u;
+    const uint32_t lb = wg / chunks, ch = wg - lb * chunks;
+    const uint32_t tid = threadIdx.x;
+    // row pass: eight neighbouring threads take eight neighbouring groups of a row; column pass: 32 neighbouring
+    // threads take 32 neighbouring columns (their loads fall into the same rows of W)
+    const uint32_t ll = transposed ? (tid & 31u) : (tid >> 3);
+    const uint32_t gl = transposed ? (tid >> 5) : (tid & 7u);
+    const uint32_t line = lb * 32u + ll, g = ch * 8u + gl;
+    for (uint32_t k = tid; k < 32u * WORDS; k += kCwPackThreads)
+        (&IDX[0][0])[k] = 0;
+    __syncthreads();
+    void *vals = transposed ? d.valsT : d.vals;
+    unsigned char *idx = (unsigned char *)(transposed ? d.idxT : d.idx);
+    if (line < n_lines && g < gpl) {
+        uint32_t v[M], kb = 0;
+#pragma unroll
+        for (int q = 0; q < M; q++) {
+            const uint32_t r = transposed ? g * M + q : line, c = transposed ? line : g * M + q;
+            v[q] = cw_load<DT>(d.w, (size_t)r * d.ld + c);
+            uint32_t f;
+            if constexpr (FMT == kMaskU8)
+                f = ((const unsigned char *)d.mask)[(size_t)r * d.mask_ld + c] != 0 ? 1u : 0u;
+            else
+                f = (((const unsigned char *)d.mask)[(size_t)r * d.mask_ld + (c >> 3)] >> (c & 7u)) & 1u;
+            kb |= f << q;
+        }
+        // slots: the kept positions in order (the first N if the mask keeps more), then the lowest other positions
+        uint32_t sel = kb, cnt = (uint32_t)__builtin_popcount(kb);
+        while (cnt > N) {
+            sel &= ~(0x80000000u >> __builtin_clz(sel));
+            cnt--;
+        }
+        uint32_t z = ~sel & seg_mask<M>(), chosen = sel;
+        for (uint32_t need = N - cnt; need > 0; need--) {
+            const uint32_t low = z & (0u - z);
+            chosen |= low;
+            z ^= low;
+        }
+        const size_t pitch = (size_t)gpl * N;
+        const size_t o = (size_t)line * pitch + (size_t)g * N;
+        uint32_t sl = 0;
+#pragma unroll
+        for (int q = 0; q < M; q++) {
+            if ((chosen >> q) & 1u) {
+                cw_store<DT>(vals, o + sl, ((sel >> q) & 1u) ? v[q] : 0u);
+                const uint32_t off = (gl * N + sl) * IB;
+                const unsigned long long code = (unsigned long long)q << (off & 31u);
+                atomicOr(&IDX[ll][off >> 5], (uint32_t)code);
+                if ((uint32_t)(code >> 32))
+                    atomicOr(&IDX[ll][(off >> 5) + 1], (uint32_t)(code >> 32));
+                sl++;
+            }
+        }
+    }
+    __syncthreads();
+    // the chunk's position bits start on a byte boundary of the line: 8 groups * N * IB bits = N * IB bytes
+    const size_t pitch_b = ((size_t)gpl * N * IB + 7) / 8;
+    const uint32_t g_here = min(8u, gpl - min(gpl, ch * 8u));
+    const uint32_t nbytes = (g_here * N * IB + 7u) / 8u;
+    for (uint32_t k = tid; k < 32u * nbytes; k += kCwPackThreads) {
+        const uint32_t l2 = k / nbytes, x = k - l2 * nbytes;
+        if (lb * 32u + l2 < n_lines)
+            idx[(size_t)(lb * 32u + l2) * pitch_b + (size_t)ch * N * IB + x] = ((const unsigned char *)&IDX[l2][0])[x];
+    }
+}
+
+// =====================================================================================================================
+// Host side
+// =====================================================================================================================
+
+static void cw_magic_div(uint32_t d, uint32_t *mul, uint32_t *shift)
+{
+    uint32_t l = 0;
+    while ((1ull << l) < d)
+        l++;
+    const uint32_t k = 31 + l;
+    *mul = (uint32_t)(((1ull << k) / d) + 1);
+    *shift = k;
+}
+
+// workgroups a matrix gets: one per tile at M = 32; for M <= 16 (the slow path of an unaligned matrix) never more than
+// the per-workgroup partial results the documented workspace bound provides for (one per 256 strips of M rows x 4
+// columns), each workgroup striding over several tiles
+static uint32_t cw_wgs(int64_t rows, int64_t cols, int M, uint32_t n_tiles)
+{
+    if (M == 32)
+        return n_tiles;
+    const uint64_t strips = (uint64_t)((rows + M - 1) / M) * (uint64_t)((cols + 3) / 4);
+    const uint64_t cap = (strips + kThreads - 1) / kThreads;
+    return (uint32_t)(n_tiles < cap ? n_tiles : cap);
+}
+
+size_t cw_workgroups(int64_t rows, int64_t cols, int M)
+{
+    return cw_wgs(rows, cols, M, (uint32_t)((cols + 63) / 64) * (uint32_t)(rows / M));
+}
+
+static void cw_fill(CwMat &m, const void *w, int64_t rows, int64_t cols, int64_t ld, void *mask, int64_t mask_ld, int M,
+                    uint32_t wg0)
+{
+    m.w = w; m.mask = mask; m.aux = nullptr;
+    m.ld = (uint32_t)ld; m.mask_ld = (uint32_t)mask_ld; m.ld_aux = 0; m.cols = (uint32_t)cols;
+    m.tpr = (uint32_t)((cols + 63) / 64);
+    m.n_tiles = m.tpr * (uint32_t)(rows / M);
+    m.wg0 = wg0;
+    m.n_wg = cw_wgs(rows, cols, M, m.n_tiles);
+    cw_magic_div(m.tpr, &m.div_mul, &m.div_shift);
+}
+
+typedef void (*cw_kernel_t)(const CwArgs);
+
+#define CW_PICK_M(KERN, ...)                                                                                         \
+    (M == 4 ? KERN<__VA_ARGS__, 4, kMaskU8> : M == 8 ? KERN<__VA_ARGS__, 8, kMaskU8>                                 \
+     : M == 16 ? KERN<__VA_ARGS__, 16, kMaskU8> : KERN<__VA_ARGS__, 32, kMaskU8>)
+#define CW_PICK_M_BITS(KERN, ...)                                                                                    \
+    (M == 4 ? KERN<__VA_ARGS__, 4, kMaskBits> : M == 8 ? KERN<__VA_ARGS__, 8, kMaskBits>                             \
+     : M == 16 ? KERN<__VA_ARGS__, 16, kMaskBits> : KERN<__VA_ARGS__, 32, kMaskBits>)
+
+static cw_kernel_t cw_pick_mask(int solver, int dt, int M, int mf)
+{
+#define CW_ONE(SV)                                                                                                   \
+    if (solver == SV)                                                                                                \
+        return dt == kF32 ? (mf == kMaskU8 ? CW_PICK_M(cw_mask_kernel, SV, kF32) : CW_PICK_M_BITS(cw_mask_kernel, SV, kF32)) \
+                          : (mf == kMaskU8 ? CW_PICK_M(cw_mask_kernel, SV, kBF16) : CW_PICK_M_BITS(cw_mask_kernel, SV, kBF16));
+    CW_ONE(kCwApprox) CW_ONE(kCwRow1D) CW_ONE(kCwRow1DAbsorb)
+#undef CW_ONE
+    return nullptr;
+}
+
+// solver: 0 = Algorithm 1, 1 = exact, 2 = row pruning.  Arguments are validated by the caller; `ws` (if any objective
+// is wanted) holds at least one double per workgroup.
+int cw_run_mask(int solver, const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, void *ws, hipStream_t stream)
+{
+    bool want_obj = false;
+    for (int i = 0; i < n_mats; i++)
+        want_obj = want_obj || mats[i].objective;
+    cw_kernel_t kern;
+    if (solver == 1)
+        kern = dt == kF32 ? (mf == kMaskU8 ? CW_PICK_M(cw_exact_kernel, kF32) : CW_PICK_M_BITS(cw_exact_kernel, kF32))
+                          : (mf == kMaskU8 ? CW_PICK_M(cw_exact_kernel, kBF16) : CW_PICK_M_BITS(cw_exact_kernel, kBF16));
+    else
+        kern = cw_pick_mask(solver == 0 ? kCwApprox : kCwRow1D, dt, M, mf);
+    uint32_t partial0 = 0;
+    for (int first = 0; first < n_mats; first += kMaxCwBatch) {
+        const int nb = n_mats - first < kMaxCwBatch ? n_mats - first : kMaxCwBatch;
+        CwArgs args;
+        memset(&args, 0, sizeof args);
+        double *objective[kMaxCwBatch];
+        uint32_t wg0[kMaxCwBatch + 1];
+        uint32_t wgs = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_mat &t = mats[first + k];
+            cw_fill(args.m[k], t.w, t.rows, t.cols, t.ld, t.mask, t.mask_ld, M, wgs);
+            objective[k] = t.objective;
+            wg0[k] = wgs;
+            wgs += args.m[k].n_wg;
+        }
+        wg0[nb] = wgs;
+        args.n = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
+        args.partial0 = partial0; args.partials = want_obj ? ws : nullptr;
+        {
+            ProfileScope prof(stream, first + kMaxCwBatch >= n_mats);
+            hipLaunchKernelGGL(kern, dim3(wgs), dim3(kCwThreads), 0, stream, args);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "column-wise mask kernel launch");
+        if (want_obj) {
+            const int rc = launch_objective_reduce(objective, wg0, nb, partial0, ws, stream);
+            if (rc)
+                return rc;
+        }
+        partial0 += wgs;
+    }
+    return TMASK_OK;
+}
+
+int cw_run_score(const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, tmask_score_out *out, float *per_block_obj,
+                 void *ws, hipStream_t stream)
+{
+    const cw_kernel_t kern =
+        dt == kF32 ? (mf == kMaskU8 ? CW_PICK_M(cw_score_kernel, kF32) : CW_PICK_M_BITS(cw_score_kernel, kF32))
+                   : (mf == kMaskU8 ? CW_PICK_M(cw_score_kernel, kBF16) : CW_PICK_M_BITS(cw_score_kernel, kBF16));
+    uint32_t partial0 = 0;
+    size_t block0 = 0;
+    for (int first = 0; first < n_mats; first += kMaxCwBatch) {
+        const int nb = n_mats - first < kMaxCwBatch ? n_mats - first : kMaxCwBatch;
+        CwArgs args;
+        memset(&args, 0, sizeof args);
+        uint32_t wg0[kMaxCwBatch + 1];
+        uint32_t wgs = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_mat &t = mats[first + k];
+            cw_fill(args.m[k], t.w, t.rows, t.cols, t.ld, t.mask, t.mask_ld, M, wgs);
+            args.m[k].aux = per_block_obj ? (void *)(per_block_obj + block0) : nullptr;
+            block0 += (size_t)(t.rows / M) * (size_t)(t.cols / M);
+            wg0[k] = wgs;
+            wgs += args.m[k].n_wg;
+        }
+        wg0[nb] = wgs;
+        args.n = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
+        args.partial0 = partial0; args.partials = ws;
+        {
+            ProfileScope prof(stream, first + kMaxCwBatch >= n_mats);
+            hipLaunchKernelGGL(kern, dim3(wgs), dim3(kCwThreads), 0, stream, args);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "column-wise score kernel launch");
+        const int rc = launch_score_reduce(wg0, nb, partial0, ws, out + first, stream);
+        if (rc)
+            return rc;
+        partial0 += wgs;
+    }
+    return TMASK_OK;
+}
+
+// mode: 0 = Algorithm 1, 1 = row pruning, 2 = row pruning with mean absorption; out <- W (.) S, mask on request
+int cw_run_dense(const tmask_mask_dense_desc *descs, int n, int dt, int N, int M, int mf, int mode, hipStream_t stream)
+{
+    const cw_kernel_t kern = cw_pick_mask(mode == 0 ? kCwApprox : mode == 1 ? kCwRow1D : kCwRow1DAbsorb, dt, M, mf);
+    for (int first = 0; first < n; first += kMaxCwBatch) {
+        const int nb = n - first < kMaxCwBatch ? n - first : kMaxCwBatch;
+        CwArgs args;
+        memset(&args, 0, sizeof args);
+        uint32_t wgs = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_mask_dense_desc &p = descs[first + k];
+            cw_fill(args.m[k], p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, M, wgs);
+            args.m[k].aux = p.out;
+            args.m[k].ld_aux = (uint32_t)p.ld_out;
+            wgs += args.m[k].n_wg;
+        }
+        args.n = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
+        {
+            ProfileScope prof(stream, first + kMaxCwBatch >= n);
+            hipLaunchKernelGGL(kern, dim3(wgs), dim3(kCwThreads), 0, stream, args);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "column-wise mask + dense copy kernel launch");
+    }
+    return TMASK_OK;
+}
+
+typedef void (*cw_pack_kernel_t)(const CwPackArgs);
+
+int cw_run_pack(const tmask_pack_desc *descs, int n, int dt, int N, int M, int mf, hipStream_t stream)
+{
+    const cw_pack_kernel_t kern =
+        dt == kF32 ? (mf == kMaskU8 ? CW_PICK_M(cw_pack_kernel, kF32) : CW_PICK_M_BITS(cw_pack_kernel, kF32))
+                   : (mf == kMaskU8 ? CW_PICK_M(cw_pack_kernel, kBF16) : CW_PICK_M_BITS(cw_pack_kernel, kBF16));
+    for (int first = 0; first < n; first += kMaxCwBatch) {
+        const int nb = n - first < kMaxCwBatch ? n - first : kMaxCwBatch;
+        CwPackArgs args;
+        memset(&args, 0, sizeof args);
+        uint32_t wgs = 0;
+        for (int k = 0; k < nb; k++) {
+            const tmask_pack_desc &p = descs[first + k];
+            CwPack &d = args.d[k];
+            d.w = p.w; d.mask = p.mask; d.vals = p.vals; d.idx = p.idx; d.valsT = p.valsT; d.idxT = p.idxT;
+            d.rows = (uint32_t)p.rows; d.cols = (uint32_t)p.cols; d.ld = (uint32_t)p.ld; d.mask_ld = (uint32_t)p.mask_ld;
+            d.wg0 = wgs;
+            d.row_wgs = (uint32_t)((p.rows + 31) / 32) * (uint32_t)((p.cols / M + 7) / 8);
+            wgs += d.row_wgs + (uint32_t)((p.cols + 31) / 32) * (uint32_t)((p.rows / M + 7) / 8);
+        }
+        args.n = (uint32_t)nb; args.N = (uint32_t)N;
+        {
+            ProfileScope prof(stream, first + kMaxCwBatch >= n);
+            hipLaunchKernelGGL(kern, dim3(wgs), dim3(kCwPackThreads), 0, stream, args);
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return hip_fail(e, "column-wise pack kernel launch");
+    }
+    return TMASK_OK;
+}
+
+}  // namespace tmask

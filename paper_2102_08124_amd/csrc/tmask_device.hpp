@@ -61,6 +61,12 @@ struct BatchArgs {
     void *partials;      // workspace
 };
 
+// What a workgroup of the score kernels leaves for the second-stage reduction.
+struct ScorePartial {
+    double retained, total;
+    unsigned long long kept, rowv, colv, rowne, colne;
+};
+
 static_assert(sizeof(BatchArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
 
 template <int DT, int M>

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include "../../include/tmask.h"
+
 namespace tmask {
 
 // Records a thread-local, human-readable description of the failure and returns `code`.
@@ -27,6 +29,23 @@ struct ProfileScope {
         }
     }
 };
+
+// Second-stage reductions (tmask_kernels.hip) for kernels of other translation units: first0[k] = index, inside the
+// launch, of the first partial result of matrix k; first0[nb] = their number.
+int launch_objective_reduce(double *const *objective, const uint32_t *first0, int nb, uint32_t partial0, const void *partials,
+                            hipStream_t stream);
+int launch_score_reduce(const uint32_t *first0, int nb, uint32_t partial0, const void *partials, tmask_score_out *out,
+                        hipStream_t stream);
+
+// The column-per-lane kernels (tmask_colwise.hip): M = 32, and matrices that miss the strip kernels' alignment.
+// Arguments are validated by the callers.  solver: 0 = Algorithm 1, 1 = exact, 2 = row pruning; dense mode: 0 =
+// Algorithm 1, 1 = row pruning, 2 = row pruning with mean absorption.
+int cw_run_mask(int solver, const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, void *ws, hipStream_t stream);
+int cw_run_score(const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf, tmask_score_out *out, float *per_block_obj,
+                 void *ws, hipStream_t stream);
+int cw_run_pack(const tmask_pack_desc *descs, int n, int dt, int N, int M, int mf, hipStream_t stream);
+int cw_run_dense(const tmask_mask_dense_desc *descs, int n, int dt, int N, int M, int mf, int mode, hipStream_t stream);
+size_t cw_workgroups(int64_t rows, int64_t cols, int M);     // workgroups (= partial results) cw_run_mask uses for a matrix
 
 // Compute units of the current device (256 if the query fails); asked once per thread and device.
 inline int cu_count()

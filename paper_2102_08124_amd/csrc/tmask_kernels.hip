@@ -456,11 +456,6 @@ __global__ __launch_bounds__(kReduceThreads) void objective_reduce_kernel(const 
     }
 }
 
-struct ScorePartial {
-    double retained, total;
-    unsigned long long kept, rowv, colv, rowne, colne;
-};
-
 template <int DT, int M, int FMT>
 __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
 {
@@ -636,7 +631,7 @@ int fail(int code, const char *fmt, ...)
     return code;
 }
 
-static bool valid_nm(int N, int M) { return (M == 4 || M == 8 || M == 16) && N > 0 && N < M; }
+static bool valid_nm(int N, int M) { return (M == 4 || M == 8 || M == 16 || M == 32) && N > 0 && N < M; }
 
 static size_t elem_size(int dt) { return dt == TMASK_F32 ? 4 : 2; }
 
@@ -657,8 +652,10 @@ struct HostMat {
     double *objective;
 };
 
-// Validates one matrix for (dt, N, M, mf). what: text for error messages.
-static int check_mat(const HostMat &h, int idx, int dt, int M, int mf, bool need_mask)
+// Validates one matrix for (dt, N, M, mf).  *aligned is cleared (never set) when the matrix misses what the strip
+// kernels read and write with -- w 16-byte aligned with ld and cols multiples of 16 bytes, a U8 mask and its pitch
+// multiples of the strip width -- in which case the call runs on the column-per-lane kernels instead.
+static int check_mat(const HostMat &h, int idx, int dt, int M, int mf, bool need_mask, bool *aligned)
 {
     const size_t es = elem_size(dt);
     const int64_t C = 16 / (int64_t)es;
@@ -667,18 +664,18 @@ static int check_mat(const HostMat &h, int idx, int dt, int M, int mf, bool need
     if (h.rows <= 0 || h.cols <= 0 || h.rows % M || h.cols % M || h.ld < h.cols)
         return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld ld=%lld must be positive multiples of M=%d with ld >= cols",
                     idx, (long long)h.rows, (long long)h.cols, (long long)h.ld, M);
-    if (h.ld > 0x7FFFFFFFll || h.mask_ld > 0x7FFFFFFFll || (h.rows / M) * (h.cols / C) >= 0x7FFFFFFFll)
+    if (h.ld > 0x7FFFFFFFll || h.mask_ld > 0x7FFFFFFFll || (h.rows / M) * ((h.cols + 3) / 4) >= 0x7FFFFFFFll)
         return fail(TMASK_ERR_SHAPE, "matrix %d: too large (ld, mask_ld and strip count must stay below 2^31)", idx);
+    if ((uintptr_t)h.w % es)
+        return fail(TMASK_ERR_ALIGN, "matrix %d: w must be aligned to its element size", idx);
     if (((uintptr_t)h.w & 15) || (h.ld * es) % 16 || (h.cols * es) % 16)
-        return fail(TMASK_ERR_ALIGN, "matrix %d: w must be 16-byte aligned and ld, cols multiples of %lld elements", idx,
-                    (long long)C);
-    if (need_mask) {
+        *aligned = false;
+    if (h.mask) {
         if (mf == TMASK_MASK_U8) {
             if (h.mask_ld < h.cols)
                 return fail(TMASK_ERR_SHAPE, "matrix %d: mask_ld=%lld < cols", idx, (long long)h.mask_ld);
             if (((uintptr_t)h.mask % C) || (h.mask_ld % C))
-                return fail(TMASK_ERR_ALIGN, "matrix %d: U8 mask and mask_ld must be multiples of %lld bytes", idx,
-                            (long long)C);
+                *aligned = false;
         } else {
             if (h.cols % 8)
                 return fail(TMASK_ERR_SHAPE, "matrix %d: BITS masks need cols to be a multiple of 8", idx);
@@ -746,7 +743,7 @@ static int check_common(const void *mats, int n_mats, int dt, int N, int M, int 
     if (mf != TMASK_MASK_U8 && mf != TMASK_MASK_BITS)
         return fail(TMASK_ERR_DTYPE, "unknown mask format %d", mf);
     if (!valid_nm(N, M))
-        return fail(TMASK_ERR_NM, "unsupported N:M = %d:%d (need M in {4,8,16}, 0 < N < M)", N, M);
+        return fail(TMASK_ERR_NM, "unsupported N:M = %d:%d (need M in {4,8,16,32}, 0 < N < M)", N, M);
     return TMASK_OK;
 }
 
@@ -758,7 +755,8 @@ static size_t workspace_need(const tmask_mat *mats, int n_mats, int M)
         if (mats[i].rows <= 0 || mats[i].cols <= 0)
             return 0;
         const size_t strips = (size_t)((mats[i].rows + M - 1) / M) * (size_t)((mats[i].cols + 3) / 4);
-        tiles += (strips + kThreads - 1) / kThreads;
+        // M = 32 runs on the column-per-lane kernels: one partial result per tile of 32 rows x 64 columns
+        tiles += M == 32 ? (size_t)((mats[i].rows + 31) / 32) * (size_t)((mats[i].cols + 63) / 64) : (strips + kThreads - 1) / kThreads;
         // tmask_approx_pack keeps one fp64 partial per tile of its one-pass kernels (64 rows x 256 columns at least)
         pack_tiles += (size_t)((mats[i].rows + 63) / 64) * (size_t)((mats[i].cols + 255) / 256);
     }
@@ -824,11 +822,11 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     int rc = check_common(mats, n_mats, dt, N, M, mf);
     if (rc)
         return rc;
-    bool want_obj = false;
+    bool want_obj = false, aligned = (M != 32);
     for (int i = 0; i < n_mats; i++) {
         const HostMat h{mats[i].w, mats[i].rows, mats[i].cols, mats[i].ld, mats[i].mask, mats[i].mask_ld,
                         mats[i].objective};
-        if ((rc = check_mat(h, i, dt, M, mf, true)))
+        if ((rc = check_mat(h, i, dt, M, mf, true, &aligned)))
             return rc;
         want_obj = want_obj || mats[i].objective;
     }
@@ -836,7 +834,7 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         size_t tiles = 0;
         for (int i = 0; i < n_mats; i++) {
             const HostMat h{mats[i].w, mats[i].rows, mats[i].cols, mats[i].ld, nullptr, 0, nullptr};
-            tiles += tiles_of(strips_of(h, dt, M));
+            tiles += aligned ? tiles_of(strips_of(h, dt, M)) : cw_workgroups(h.rows, h.cols, M);
         }
         if (want_obj && tiles > kScratchPartials)
             return fail(TMASK_ERR_WORKSPACE,
@@ -848,6 +846,9 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     } else if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes))) {
         return rc;
     }
+    if (!aligned)     // M = 32, or a matrix that the 16-byte strips cannot read: the column-per-lane kernels
+        return cw_run_mask(SOLVER == kSolveApprox ? 0 : SOLVER == kSolveExact ? 1 : 2, mats, n_mats, dt, N, M, mf, ws,
+                           (hipStream_t)stream_);
     batch_kernel_t kern = pick_mask_kernel<SOLVER>(dt, M, mf);
     if (SOLVER == kSolveApprox && M == 4 && N == 2) {
         if (dt == kF32)
@@ -918,6 +919,38 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     return TMASK_OK;
 }
 
+// Second-stage reductions for the kernels of other translation units: first0[k] = index (inside this launch) of the
+// first partial result of matrix k, first0[nb] = their total number.
+int launch_objective_reduce(double *const *objective, const uint32_t *first0, int nb, uint32_t partial0, const void *partials,
+                            hipStream_t stream)
+{
+    ReduceArgs rargs;
+    memset(&rargs, 0, sizeof rargs);
+    for (int k = 0; k < nb; k++) {
+        rargs.objective[k] = objective[k];
+        rargs.tile0[k] = first0[k];
+    }
+    rargs.tile0[nb] = first0[nb];
+    rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)partials;
+    hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TMASK_OK : hip_fail(e, "objective reduce launch");
+}
+
+int launch_score_reduce(const uint32_t *first0, int nb, uint32_t partial0, const void *partials, tmask_score_out *out,
+                        hipStream_t stream)
+{
+    ScoreReduceArgs rargs;
+    memset(&rargs, 0, sizeof rargs);
+    for (int k = 0; k <= nb; k++)
+        rargs.tile0[k] = first0[k];
+    rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0;
+    rargs.partials = (const ScorePartial *)partials; rargs.out = out;
+    hipLaunchKernelGGL(score_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TMASK_OK : hip_fail(e, "score reduce launch");
+}
+
 }  // namespace tmask
 
 using namespace tmask;
@@ -956,13 +989,18 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
         return rc;
     if (!out)
         return fail(TMASK_ERR_NULL, "out is NULL");
+    bool aligned = (M != 32);
     for (int i = 0; i < n_mats; i++) {
         const HostMat h{mats[i].w, mats[i].rows, mats[i].cols, mats[i].ld, mats[i].mask, mats[i].mask_ld, nullptr};
-        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, true)))
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, true, &aligned)))
             return rc;
     }
     if ((rc = check_workspace(mats, n_mats, M, workspace, workspace_bytes)))
         return rc;
+    if (per_block_obj && ((uintptr_t)per_block_obj & 3))
+        return fail(TMASK_ERR_ALIGN, "per_block_obj must be 4-byte aligned");
+    if (!aligned)
+        return cw_run_score(mats, n_mats, (int)dt, N, M, (int)mf, out, per_block_obj, workspace, (hipStream_t)hip_stream);
     const batch_kernel_t kern = pick_score_kernel((int)dt, M, (int)mf);
     hipStream_t stream = (hipStream_t)hip_stream;
     uint32_t partial0 = 0;
@@ -1034,16 +1072,21 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
     int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
     if (rc)
         return rc;
+    bool aligned = (M != 32);
     for (int i = 0; i < n; i++) {
         const tmask_pack_desc &p = descs[i];
         const HostMat h{p.w, p.rows, p.cols, p.ld, const_cast<void *>(p.mask), p.mask_ld, nullptr};
-        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, true)))
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, true, &aligned)))
             return rc;
         if (!p.vals || !p.idx || !p.valsT || !p.idxT)
             return fail(TMASK_ERR_NULL, "matrix %d: a packed output pointer is NULL", i);
+        if (((uintptr_t)p.vals | (uintptr_t)p.valsT) % elem_size((int)dt))
+            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be aligned to the element size", i);
         if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
-            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 4-byte aligned", i);
+            aligned = false;
     }
+    if (!aligned)
+        return cw_run_pack(descs, n, (int)dt, N, M, (int)mf, (hipStream_t)hip_stream);
     pack_kernel_t kern = pick_pack_kernel((int)dt, M, (int)mf, N);
     uint32_t TC = 256 / (uint32_t)elem_size((int)dt);
     bool fast24 = (M == 4 && N == 2);
@@ -1118,30 +1161,31 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
     int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
     if (rc)
         return rc;
-    const bool fused24 = (M == 4 && N == 2);
-    bool fused48 = (M == 8 && N == 4);                         // needs 8-byte aligned outputs, else two steps
+    bool fused24 = (M == 4 && N == 2);                         // both need aligned inputs and 8-byte aligned outputs,
+    bool fused48 = (M == 8 && N == 4);                         // else the call runs as two steps
     int with_mask = 0;
-    bool want_obj = false;
+    bool want_obj = false, aligned = (M != 32);
     for (int i = 0; i < n; i++) {
         const tmask_fused_desc &p = descs[i];
         with_mask += p.mask ? 1 : 0;
         want_obj = want_obj || p.objective;
         const HostMat h{p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, p.objective};
-        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, p.mask != nullptr)))
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, p.mask != nullptr, &aligned)))
             return rc;
         if (!p.vals || !p.idx || !p.valsT || !p.idxT)
             return fail(TMASK_ERR_NULL, "matrix %d: a packed output pointer is NULL", i);
-        if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
-            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 4-byte aligned", i);
-        if (fused24 && ((((uintptr_t)p.vals | (uintptr_t)p.valsT) & 7) != 0))
-            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be 8-byte aligned for 2:4", i);
-        fused48 = fused48 && ((((uintptr_t)p.vals | (uintptr_t)p.valsT) & 7) == 0);
+        if (((uintptr_t)p.vals | (uintptr_t)p.valsT) % elem_size((int)dt))
+            return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be aligned to the element size", i);
+        const bool out8 = ((((uintptr_t)p.vals | (uintptr_t)p.valsT) & 7) == 0);
+        fused24 = fused24 && out8;
+        fused48 = fused48 && out8;
     }
-    const bool fused = fused24 || fused48;
+    const bool fused = aligned && (fused24 || fused48);
     if (with_mask != 0 && with_mask != n)
         return fail(TMASK_ERR_NULL, "mask must be given for all matrices or for none (%d of %d have one)", with_mask, n);
     if (!fused && with_mask == 0)
-        return fail(TMASK_ERR_NULL, "N:M = %d:%d runs as two steps and needs the mask buffers", N, M);
+        return fail(TMASK_ERR_NULL, "this call (N:M = %d:%d, or matrices / outputs that miss the alignment of the one-pass "
+                                    "kernels) runs as two steps and needs the mask buffers", N, M);
 
     if (!fused) {
         std::vector<tmask_mat> mats((size_t)n);
@@ -1243,22 +1287,30 @@ static int run_mask_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype
         return rc;
     const int64_t es = elem_size((int)dt);
     int with_mask = 0;
+    bool aligned = (M != 32);
     for (int i = 0; i < n; i++) {
         const tmask_mask_dense_desc &p = descs[i];
         with_mask += p.mask ? 1 : 0;
         const HostMat h{p.w, p.rows, p.cols, p.ld, p.mask, p.mask_ld, nullptr};
-        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, p.mask != nullptr)))
+        if ((rc = check_mat(h, i, (int)dt, M, (int)mf, p.mask != nullptr, &aligned)))
             return rc;
         if (!p.out)
             return fail(TMASK_ERR_NULL, "matrix %d: out is NULL", i);
         if (p.ld_out < p.cols || p.ld_out * es > 0x7FFFFFFFll)
             return fail(TMASK_ERR_SHAPE, "matrix %d: ld_out=%lld must cover a row of %lld columns", i, (long long)p.ld_out,
                         (long long)p.cols);
+        if ((uintptr_t)p.out % (uintptr_t)es)
+            return fail(TMASK_ERR_ALIGN, "matrix %d: out must be aligned to its element size", i);
         if (((uintptr_t)p.out | (uint64_t)(p.ld_out * es)) & 15)
-            return fail(TMASK_ERR_ALIGN, "matrix %d: out and its row pitch must be 16-byte aligned", i);
+            aligned = false;
     }
     if (with_mask != 0 && with_mask != n)
         return fail(TMASK_ERR_NULL, "mask must be given for all matrices or for none (%d of %d have one)", with_mask, n);
+    if (!aligned) {
+        const bool absorb = mode == kDenseRow1DAbsorb || mode == kDenseRow1DHalfAbsorb;
+        const bool rows_only = absorb || mode == kDenseRow1D || mode == kDenseRow1DHalf;
+        return cw_run_dense(descs, n, (int)dt, N, M, (int)mf, absorb ? 2 : rows_only ? 1 : 0, (hipStream_t)hip_stream);
+    }
     batch_kernel_t kern = nullptr;
 #define TMASK_PICK(DT, MM, FM) \
     if ((int)dt == DT && M == MM && (int)mf == FM) \

@@ -138,12 +138,12 @@ def test_fused_argument_errors():
     with pytest.raises(tm.TmaskError) as e:
         tm.tmask_approx_pack([w], None, [pk], 2, 4, objective=obj)
     assert e.value.code == tm.TMASK_ERR_WORKSPACE
-    # vals not 8-byte aligned
+    # vals not 8-byte aligned: the one-pass kernel cannot write it, the two-step path needs the mask buffers
     vals_off = torch.empty(16 * 8 + 1, dtype=torch.float32, device="cuda")[1:].view(16, 8)
     arr1 = (tm.tmask_fused_desc * 1)()
     arr1[0] = tm.tmask_fused_desc(w.data_ptr(), 16, 16, 16, None, 0, vals_off.data_ptr(), pk[1].data_ptr(),
                                   pk[2].data_ptr(), pk[3].data_ptr(), None)
-    assert lib.tmask_approx_pack(arr1, 1, tm.TMASK_F32, 2, 4, tm.TMASK_MASK_U8, None, 0, None) == tm.TMASK_ERR_ALIGN
+    assert lib.tmask_approx_pack(arr1, 1, tm.TMASK_F32, 2, 4, tm.TMASK_MASK_U8, None, 0, None) == tm.TMASK_ERR_NULL
     # a NULL packed output
     arr1[0] = tm.tmask_fused_desc(w.data_ptr(), 16, 16, 16, None, 0, None, pk[1].data_ptr(), pk[2].data_ptr(),
                                   pk[3].data_ptr(), None)

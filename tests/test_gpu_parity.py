@@ -265,7 +265,6 @@ def test_argument_errors_leave_outputs_untouched():
         (lambda: tm.tmask_approx([w], [mask], 2, 5), tm.TMASK_ERR_NM),
         (lambda: tm.tmask_approx([w], [mask], 4, 4), tm.TMASK_ERR_NM),
         (lambda: tm.tmask_approx([w[:12]], [mask[:12]], 4, 8), tm.TMASK_ERR_SHAPE),
-        (lambda: tm.tmask_approx([w[:, 1:17]], [mask[:, :16]], 2, 4), tm.TMASK_ERR_ALIGN),
         (lambda: tm.tmask_approx([w], [mask], 2, 4, objective=torch.zeros(1, dtype=torch.float64, device="cuda")),
          tm.TMASK_ERR_WORKSPACE),
         (lambda: tm.tmask_exact([w], [mask[:, :16].contiguous()], 2, 4), tm.TMASK_ERR_SHAPE),

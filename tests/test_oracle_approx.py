@@ -93,7 +93,7 @@ def test_tie_break_is_row_major_index():
     assert np.array_equal(mask, expect)
 
 
-CASES = [(N, M) for M in (2, 4, 6, 8, 16) for N in range(1, M)]
+CASES = [(N, M) for M in (2, 4, 6, 8, 16) for N in range(1, M)] + [(N, 32) for N in (1, 5, 16, 20, 31)]
 
 
 @pytest.mark.parametrize("N,M", CASES)
@@ -105,7 +105,7 @@ def test_matches_k_lightest_rule_random(N, M):
     assert obj == pytest.approx(float((refs.magnitudes(w) * mask).sum()), rel=1e-12)
 
 
-@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (3, 4), (4, 8), (8, 16), (3, 6)])
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (3, 4), (4, 8), (8, 16), (3, 6), (16, 32), (7, 32)])
 def test_matches_k_lightest_rule_ties_and_zeros(N, M):
     w = wl.tie_heavy_f32(8 * M, 8 * M, seed=7 + M, levels=4)
     mask, _ = oracle.approx(w, N, M)

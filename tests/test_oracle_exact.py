@@ -48,7 +48,7 @@ def test_config1_exact_equals_90_pattern_enumeration():
     np.testing.assert_allclose(pb, best, rtol=1e-13)
 
 
-@pytest.mark.parametrize("N,M", [(4, 8), (8, 16), (3, 8), (5, 8), (2, 6)])
+@pytest.mark.parametrize("N,M", [(4, 8), (8, 16), (3, 8), (5, 8), (2, 6), (16, 32), (9, 32)])
 def test_equals_lp_optimum(N, M):
     for k, w in enumerate((wl.gaussian_f32(2 * M, 3 * M, seed=210 + M), wl.laplace_f32(2 * M, 2 * M, seed=211),
                            wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(wl.gaussian_f32(2 * M, 2 * M, 212, std=0.02))))):

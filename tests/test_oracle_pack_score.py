@@ -67,7 +67,7 @@ def _roundtrip(w, mask, N, M):
     return vals, valsT
 
 
-@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (8, 16), (1, 4), (3, 8)])
+@pytest.mark.parametrize("N,M", [(2, 4), (4, 8), (8, 16), (1, 4), (3, 8), (16, 32), (5, 32)])
 def test_pack_roundtrip_exact_and_approx_masks(N, M):
     w = wl.gaussian_f32(4 * M, 6 * M, seed=310 + M)
     w[0, 0] = -0.0
