@@ -37,7 +37,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0 # dense bf16
-ALL_SECTIONS = ("step", "four_of_eight", "one_pass", "config2", "config4", "config5", "spmm24", "device_copy",
+ALL_SECTIONS = ("step", "isolated", "four_of_eight", "one_pass", "config2", "config4", "config5", "spmm24", "device_copy",
                 "cpu_baseline")
 
 from paper_2102_08124_amd.hipevents import HipEvents  # noqa: E402
@@ -165,14 +165,15 @@ def make_sets(tm, torch, mats_np, N, M, copies, with_pack=True, with_fused=False
 # sections
 # ------------------------------------------------------------------------------------------------------------------
 
-def step_section(tm, torch, T, mats_np, N, M, steps, warmup, copies, event_every, kernel_names, label):
+def step_section(tm, torch, T, mats_np, N, M, steps, warmup, copies, event_every, kernel_names, label,
+                 order=("approx", "exact", "pack", "score")):
     """The whole path over one workload: timed steps, per-kernel and per-call event times inside the timed region."""
     n_mats = len(mats_np)
     weights = sum(w.size for w in mats_np)
     es = mats_np[0].dtype.itemsize
     sets = make_sets(tm, torch, mats_np, N, M, copies)
     wsp = tm.alloc_workspace(sets[0]["ws"], N, M)
-    names = ("approx", "exact", "pack", "score")
+    names = tuple(order)
 
     def calls(s):
         return {"approx": lambda: tm.tmask_approx(s["approx"], None, N, M, workspace=wsp),
@@ -256,6 +257,33 @@ def four_of_eight_section(tm, torch, T, mats_np, copies, reps):
         out[name] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(alg[key], kms)["frac"],
                      "call_frac": hbm(alg[key], cms)["frac"], "weights_per_s": weights / (cms * 1e-3)}
     out["exact_over_approx_time"] = out["exact"]["call_ms"] / out["approx"]["call_ms"]
+    return out
+
+
+def isolated_section(tm, torch, T, mats_np, N, M, copies, reps):
+    """Each call of the step on its own (back-to-back launches of the same call over rotating buffer sets): separates
+    what a kernel can do from what the sequence of the step costs it."""
+    weights = sum(w.size for w in mats_np)
+    es = mats_np[0].dtype.itemsize
+    sets = make_sets(tm, torch, mats_np, N, M, copies)
+    wsp = tm.alloc_workspace(sets[0]["ws"], N, M)
+    alg = algorithmic_bytes(weights, len(mats_np), es, N, M)
+    for s in sets:                                  # masks must exist before pack / score read them
+        tm.tmask_approx(s["approx"], None, N, M, workspace=wsp)
+        tm.tmask_exact(s["exact"], None, N, M, workspace=wsp)
+    out = {}
+    for name, fn in (
+            ("approx", lambda k: tm.tmask_approx(sets[k % copies]["approx"], None, N, M, workspace=wsp)),
+            ("exact", lambda k: tm.tmask_exact(sets[k % copies]["exact"], None, N, M, workspace=wsp)),
+            ("pack", lambda k: tm.tmask_apply_pack(sets[k % copies]["pack"], None, None, N, M)),
+            ("score", lambda k: tm.tmask_score(sets[k % copies]["score"], None, N, M, sets[k % copies]["sout"],
+                                               per_block_obj=sets[k % copies]["pb"], workspace=wsp)),
+            ("score_no_per_block", lambda k: tm.tmask_score(sets[k % copies]["score"], None, N, M, sets[k % copies]["sout"],
+                                                            workspace=wsp))):
+        kms, cms = T.measure(fn, reps)
+        key = "score" if name.startswith("score") else name
+        byts = alg[key] - (4 * (weights // (M * M)) if name == "score_no_per_block" else 0)
+        out[name] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(byts, kms)["frac"], "call_frac": hbm(byts, cms)["frac"]}
     return out
 
 
@@ -547,6 +575,8 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct buffer sets rotated through (each 1.9 GB on the headline set)")
     ap.add_argument("--sections", default=",".join(ALL_SECTIONS), help="comma list of: " + ", ".join(ALL_SECTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--order", default="approx,exact,pack,score",
+                    help="order of the four calls inside a step (pack needs exact's mask, score needs approx's)")
     ap.add_argument("--event-every", type=int, default=4,
                     help="kernel events on every n-th timed step, whole-call events n/2 steps later (0 = never)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -612,7 +642,7 @@ def main():
     }
     if "step" in sections:
         st = step_section(tm, torch, T, mats_np, N, M, args.steps, args.warmup, args.copies, args.event_every, names3,
-                          "bert_large_bf16_2of4")
+                          "bert_large_bf16_2of4", order=tuple(args.order.split(",")))
         k = st["kernels"]
         result["ms_per_step"] = st["ms_per_step"]
         result["value"] = weights / (st["ms_per_step"] * 1e-3)
@@ -636,6 +666,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if "isolated" in sections:
+        result["isolated"] = isolated_section(tm, torch, T, mats_np, N, M, copies=args.copies, reps=args.reps if args.reps != 10 else 12)
     if "four_of_eight" in sections:
         result["four_of_eight"] = four_of_eight_section(tm, torch, T, mats_np, copies=2, reps=10)
     if "one_pass" in sections:

@@ -161,19 +161,22 @@ __device__ __forceinline__ void middle_pair(uint32_t (&a)[H], uint32_t (&b)[H], 
     }
 }
 
-// Row of 8 over two lanes (4 values each).
+template <>
+__device__ __forceinline__ void middle_pair<4>(uint32_t (&a)[4], uint32_t (&b)[4], uint32_t &t, uint32_t &u)
+{
+    const uint32_t v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    const Eight e = columns_of_8(v);
+    t = fifth_of_8(e);
+    u = fourth_of_8(e);
+}
+
+// Row of 8 over two lanes (4 values each): both lanes take the neighbour's four values and run the same network.
 __device__ __forceinline__ void middle_pair_row8(uint32_t (&s)[4], uint32_t &t, uint32_t &u)
 {
-    sort_asc<4>(s);
-    t = 0xFFFFFFFFu;
-    u = 0u;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const uint32_t y = quad_xor<1>(s[3 - i]);
-        const uint32_t hi = s[i] > y ? s[i] : y, lo = s[i] > y ? y : s[i];
-        t = hi < t ? hi : t;
-        u = lo > u ? lo : u;
-    }
+    const uint32_t v[8] = {s[0], s[1], s[2], s[3], quad_xor<1>(s[0]), quad_xor<1>(s[1]), quad_xor<1>(s[2]), quad_xor<1>(s[3])};
+    const Eight e = columns_of_8(v);
+    t = fifth_of_8(e);
+    u = fourth_of_8(e);
 }
 
 // Row of 16 over four lanes (4 values each): merge lane pairs into sorted runs of 8, then split the

@@ -456,6 +456,90 @@ __global__ __launch_bounds__(kReduceThreads) void objective_reduce_kernel(const 
     }
 }
 
+// Score of a bf16 strip at M = 4 with byte masks (4 rows x 8 columns = two blocks per lane) in packed arithmetic: the
+// mask bytes of a row group are normalised to 0x80 / 0x00 once, column counts are byte-wise sums, row counts popcounts
+// packed one per byte, "more than N" / "not N" are byte-wise tests followed by a popcount, and the sums run two
+// magnitudes at a time through the bf16 dot-product instruction against (1, 1), pruned entries cleared to +0 first
+// (a select, so a pruned Inf or NaN does not reach the sum).  About 5 vector instructions per weight instead of 15,
+// which matters because bf16 leaves 18 to 24 per weight at HBM speed.
+typedef __bf16 score_bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2_ones(uint32_t pair, float acc)
+{
+    union { uint32_t u; score_bf16x2 v; } a, o;
+    a.u = pair;
+    o.u = 0x3F803F80u;
+    return __builtin_amdgcn_fdot2_f32_bf16(a.v, o.v, acc, false);
+}
+
+__device__ __forceinline__ uint32_t bytes_nonzero(uint32_t v)      // 0x80 in every byte of v that is not zero
+{
+    return (((v & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | v) & 0x80808080u;
+}
+
+__device__ __forceinline__ void score_strip_bf16_m4(const MatDev &md, StripPos pos, uint32_t N, float &retained, float &total,
+                                                    uint32_t &kept, uint32_t &rowv, uint32_t &colv, uint32_t &rowne,
+                                                    uint32_t &colne)
+{
+    const char *base = (const char *)md.w + ((size_t)pos.br * 4 * md.ld + (size_t)pos.sc * 8) * 2;
+    const size_t row_bytes = (size_t)md.ld * 2;
+    const char *mb = (const char *)md.mask + (size_t)pos.br * 4 * md.mask_ld + (size_t)pos.sc * 8;
+    u32x4 raw[4];
+    u32x2 mk[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
+        mk[i] = __builtin_nontemporal_load((const u32x2 *)(mb + (size_t)i * md.mask_ld));
+    }
+    const uint32_t nrep = N * 0x01010101u;
+    float blk[2] = {0.f, 0.f}, tot = 0.f;
+    uint32_t colsum[2] = {0u, 0u}, rowpk[2] = {0u, 0u};     // kept per column / per row of a block, one count per byte
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+#pragma unroll
+        for (int b = 0; b < 2; b++) {
+            const uint32_t nz = bytes_nonzero(b ? mk[i].y : mk[i].x);
+            const uint32_t one = nz >> 7;
+            colsum[b] += one;
+            rowpk[b] |= (uint32_t)__builtin_popcount(nz) << (8 * i);
+            const uint32_t ff = (nz - one) | nz;                                   // 0xFF in every kept byte
+            const uint32_t lo = __builtin_amdgcn_perm(ff, ff, 0x01010000u);        // columns 0, 1 as 16-bit masks
+            const uint32_t hi = __builtin_amdgcn_perm(ff, ff, 0x03030202u);        // columns 2, 3
+            const uint32_t d0 = (b ? raw[i].z : raw[i].x) & 0x7FFF7FFFu;
+            const uint32_t d1 = (b ? raw[i].w : raw[i].y) & 0x7FFF7FFFu;
+            tot = dot2_ones(d0, tot);
+            tot = dot2_ones(d1, tot);
+            blk[b] = dot2_ones(d0 & lo, blk[b]);
+            blk[b] = dot2_ones(d1 & hi, blk[b]);
+        }
+    }
+    // counts are at most 4 and N at most 3: byte + (0x7F - N) has its top bit set exactly when the count exceeds N
+    auto over = [&](uint32_t c) { return (uint32_t)__builtin_popcount((c + (0x7F7F7F7Fu - nrep)) & 0x80808080u); };
+    auto differ = [&](uint32_t c) { return (uint32_t)__builtin_popcount(bytes_nonzero(c ^ nrep)); };
+#pragma unroll
+    for (int b = 0; b < 2; b++) {
+        kept += __builtin_amdgcn_sad_u8(colsum[b], 0u, 0u);
+        colv += over(colsum[b]);
+        colne += differ(colsum[b]);
+        rowv += over(rowpk[b]);
+        rowne += differ(rowpk[b]);
+    }
+    if (md.aux) {   // the lane's two per-block sums are neighbours in memory; streamed, not left dirty in the caches
+        u32x2 o;
+        o.x = __float_as_uint(blk[0]);
+        o.y = __float_as_uint(blk[1]);
+        float *dst = (float *)md.aux + (size_t)pos.br * (md.spr * 2u) + pos.sc * 2u;
+        if (((uintptr_t)dst & 7u) == 0u) {
+            stream_store(o, (u32x2 *)dst);
+        } else {
+            stream_store(o.x, (uint32_t *)dst);
+            stream_store(o.y, (uint32_t *)dst + 1);
+        }
+    }
+    retained = blk[0] + blk[1];
+    total = tot;
+}
+
 template <int DT, int M, int FMT>
 __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
 {
@@ -470,7 +554,10 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
     const uint32_t N = args.N;
     float retained = 0.f, total = 0.f;
     uint32_t kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
-    if (s < md.n_strips) {
+    if constexpr (DT == kBF16 && M == 4 && FMT == kMaskU8) {
+        if (s < md.n_strips)
+            score_strip_bf16_m4(md, strip_pos(md, s), N, retained, total, kept, rowv, colv, rowne, colne);
+    } else if (s < md.n_strips) {
         const StripPos pos = strip_pos(md, s);
         uint32_t a[M][C];
         u32x4 raw[M];
@@ -523,7 +610,7 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
                 // block index inside the matrix: block-row-major
                 const uint32_t bpr = md.spr * Ge::B / Ge::G;
                 const uint32_t bc = pos.sc * Ge::B / Ge::G + b;
-                ((float *)md.aux)[(size_t)pos.br * bpr + bc] = blk;
+                stream_store(blk, (float *)md.aux + (size_t)pos.br * bpr + bc);
             }
         }
     }

@@ -53,4 +53,66 @@ __device__ __forceinline__ uint32_t upper_half_min(uint32_t (&a)[H], uint32_t (&
     return t;
 }
 
+// ---- eight values: order statistics from three-input instructions ----------------------------------------------
+// The median of nine values laid out 3 x 3 is med3(max of the column minima, med3 of the column medians, min of the
+// column maxima).  With +inf as the ninth value that median is the 5th smallest of the other eight, with 0 it is
+// their 4th smallest; the two share the column sorts.  12 instructions for one of them, 16 for both, against 27 and
+// 36 with two sorted halves.  Values may repeat (order statistics of a multiset).
+
+__device__ __forceinline__ uint32_t min3u(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t r;
+    asm("v_min3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+__device__ __forceinline__ uint32_t max3u(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t r;
+    asm("v_max3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+__device__ __forceinline__ uint32_t med3u(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+struct Eight {
+    uint32_t l0, m0, h0, l1, m1, h1, l2, h2;   // sorted (v0,v1,v2), sorted (v3,v4,v5), min and max of (v6,v7)
+};
+
+__device__ __forceinline__ Eight columns_of_8(const uint32_t (&v)[8])
+{
+    Eight e;
+    e.l0 = min3u(v[0], v[1], v[2]); e.m0 = med3u(v[0], v[1], v[2]); e.h0 = max3u(v[0], v[1], v[2]);
+    e.l1 = min3u(v[3], v[4], v[5]); e.m1 = med3u(v[3], v[4], v[5]); e.h1 = max3u(v[3], v[4], v[5]);
+    e.l2 = v[6] < v[7] ? v[6] : v[7];
+    e.h2 = v[6] < v[7] ? v[7] : v[6];
+    return e;
+}
+
+// 5th smallest of eight (the smallest of their upper half): ninth value +inf, whose column is (l2, h2, inf)
+__device__ __forceinline__ uint32_t fifth_of_8(const Eight &e)
+{
+    const uint32_t hh = e.h0 < e.h1 ? e.h0 : e.h1;
+    return med3u(max3u(e.l0, e.l1, e.l2), med3u(e.m0, e.m1, e.h2), hh);
+}
+
+// 4th smallest of eight (the largest of their lower half): ninth value 0, whose column is (0, l2, h2)
+__device__ __forceinline__ uint32_t fourth_of_8(const Eight &e)
+{
+    const uint32_t ll = e.l0 > e.l1 ? e.l0 : e.l1;
+    return med3u(ll, med3u(e.m0, e.m1, e.l2), min3u(e.h0, e.h1, e.h2));
+}
+
+template <>
+__device__ __forceinline__ uint32_t upper_half_min<4>(uint32_t (&a)[4], uint32_t (&b)[4])
+{
+    const uint32_t v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    return fifth_of_8(columns_of_8(v));
+}
+
 }  // namespace tmask

@@ -256,6 +256,24 @@ def test_score_matches_oracle(dt, N, M, fmt):
         np.testing.assert_allclose(pb, o.per_block, rtol=1e-5, atol=1e-30)
 
 
+def test_score_bf16_2of4_any_nonzero_byte_is_kept_and_pruned_non_finite_stays_out():
+    # mask bytes other than 0 / 1 count as kept; pruned Inf / NaN entries must not reach the retained sum
+    N, M = 2, 4
+    w = wl.f32_to_bf16_bits(wl.gaussian_f32(5 * M, 1008, seed=3050, std=0.02))
+    rng = np.random.default_rng(3051)
+    keep = rng.random(w.shape) < 0.5
+    bad = rng.random(w.shape) < 0.01
+    keep &= ~bad
+    w[bad] = rng.choice(np.array([0x7F80, 0xFF80, 0x7FC0, 0x0001], dtype=np.uint16), size=int(bad.sum()))
+    mask = np.where(keep, rng.choice(np.array([1, 2, 7, 128, 255], dtype=np.uint8), size=w.shape), 0).astype(np.uint8)
+    (sc,), (pb,) = run_score([w], [mask], N, M)
+    o = oracle.score(w, (mask != 0).astype(np.uint8), N, M)
+    assert (sc["kept"], sc["row_violations"], sc["col_violations"], sc["row_not_n"], sc["col_not_n"]) == \
+           (o.kept, o.row_violations, o.col_violations, o.row_not_n, o.col_not_n)
+    assert np.isfinite(o.retained_l1) and sc["retained_l1"] == pytest.approx(o.retained_l1, rel=1e-5)
+    np.testing.assert_allclose(pb, o.per_block, rtol=1e-5, atol=1e-30)
+
+
 # ---------------------------------------------------------------- error paths (host-side) ------
 
 def test_argument_errors_leave_outputs_untouched():
