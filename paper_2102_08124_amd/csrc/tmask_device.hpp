@@ -52,8 +52,21 @@ struct MatDev {
     uint32_t pad;
 };
 
+// Which matrix does workgroup `tile` belong to?  A binary search over the table costs a chain of dependent scalar
+// loads before a workgroup can issue its first vector load (eight for 144 matrices: several percent of a workgroup's
+// life).  The host therefore adds a coarse index: the workgroups of a launch are cut into at most 256 buckets of
+// 2^shift, and entry b packs the matrix of the bucket's first workgroup (low half) with that of the next bucket's
+// first workgroup (high half).  One load narrows the search to that range, usually a single matrix.
+constexpr int kCoarse = 256;
+
+struct CoarseIndex {
+    uint32_t shift;
+    uint32_t e[kCoarse];
+};
+
 struct BatchArgs {
     MatDev m[kMaxBatch];
+    CoarseIndex ci;
     uint32_t n_mats;
     uint32_t K;          // pruned per row/column = M - N
     uint32_t N;
@@ -190,7 +203,8 @@ __device__ __forceinline__ double block_sum_f32(float v, double *lds /* kThreads
 // Which matrix of the batch does workgroup `tile` belong to (largest m with tile0[m] <= tile).
 __device__ __forceinline__ int find_matrix(const BatchArgs &a, uint32_t tile)
 {
-    int lo = 0, hi = (int)a.n_mats - 1;
+    const uint32_t e = a.ci.e[tile >> a.ci.shift];
+    int lo = (int)(e & 0xFFFFu), hi = (int)(e >> 16);
     while (lo < hi) {
         int mid = (lo + hi + 1) >> 1;
         if (a.m[mid].tile0 <= tile)

@@ -28,15 +28,7 @@ __global__ __launch_bounds__(kThreads) void approx_pack24_kernel(const FusedArgs
     // the four doubles of the objective's workgroup sum reuse the first bytes of IDX once the tile is written out
 
     const uint32_t tile = blockIdx.x;
-    int lo = 0, hi = (int)args.n - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (args.d[mid].tile0 <= tile)
-            lo = mid;
-        else
-            hi = mid - 1;
-    }
-    const PackDev d = args.d[lo];
+    const PackDev d = args.d[find_pack_desc(args, tile)];
     const uint32_t tl = tile - d.tile0;
     uint32_t ty, tx;
     tile_coords(tl, d.tiles_x, (d.rows + TR - 1) / TR, kPackRunRows / TR, ty, tx);

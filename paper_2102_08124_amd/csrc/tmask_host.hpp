@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include "../../include/tmask.h"
+#include "tmask_device.hpp"
 
 namespace tmask {
 
@@ -46,6 +47,28 @@ int cw_run_score(const tmask_mat *mats, int n_mats, int dt, int N, int M, int mf
 int cw_run_pack(const tmask_pack_desc *descs, int n, int dt, int N, int M, int mf, hipStream_t stream);
 int cw_run_dense(const tmask_mask_dense_desc *descs, int n, int dt, int N, int M, int mf, int mode, hipStream_t stream);
 size_t cw_workgroups(int64_t rows, int64_t cols, int M);     // workgroups (= partial results) cw_run_mask uses for a matrix
+
+// Fills the coarse index of a launch (see CoarseIndex): first0[k] = first workgroup of matrix k, n matrices,
+// `total` workgroups.
+inline void fill_coarse(CoarseIndex &ci, const uint32_t *first0, int n, uint32_t total)
+{
+    uint32_t shift = 0;
+    while (total > 0 && ((total - 1u) >> shift) >= (uint32_t)kCoarse)
+        shift++;
+    ci.shift = shift;
+    const uint32_t buckets = total ? ((total - 1u) >> shift) + 1u : 1u;
+    uint32_t first[kCoarse + 1];
+    int m = 0;
+    for (uint32_t b = 0; b < buckets; b++) {
+        const uint32_t t = b << shift;
+        while (m + 1 < n && first0[m + 1] <= t)
+            m++;
+        first[b] = (uint32_t)m;
+    }
+    first[buckets] = (uint32_t)(n - 1);
+    for (uint32_t b = 0; b < (uint32_t)kCoarse; b++)
+        ci.e[b] = b < buckets ? (first[b] | (first[b + 1] << 16)) : 0u;
+}
 
 // Compute units of the current device (256 if the query fails); asked once per thread and device.
 inline int cu_count()

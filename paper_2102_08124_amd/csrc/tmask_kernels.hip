@@ -985,6 +985,7 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             tiles += tiles_of(args.m[k].n_strips * unit_split);
         }
         rargs.tile0[nb] = tiles;
+        fill_coarse(args.ci, rargs.tile0, nb, tiles);
         args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
         args.partial0 = partial0; args.partials = want_obj ? ws : nullptr;
         {
@@ -1109,6 +1110,7 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
             tiles += tiles_of(args.m[k].n_strips);
         }
         rargs.tile0[nb] = tiles;
+        fill_coarse(args.ci, rargs.tile0, nb, tiles);
         args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
         args.partial0 = partial0; args.partials = workspace;
         {
@@ -1230,6 +1232,13 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
             d.tile0 = tiles;
             tiles += d.tiles_x * ((d.rows + TR - 1) / TR);
         }
+        {
+            uint32_t first0[kMaxPackBatch + 1];
+            for (int k = 0; k < nb; k++)
+                first0[k] = args.d[k].tile0;
+            first0[nb] = tiles;
+            fill_coarse(args.ci, first0, nb, tiles);
+        }
         args.n = (uint32_t)nb; args.N = (uint32_t)N;
         {
             ProfileScope prof(stream, first + kMaxPackBatch >= n);
@@ -1345,6 +1354,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
             tiles += d.tiles_x * ((d.rows + kPack4Rows - 1) / kPack4Rows);
         }
         rargs.tile0[nb] = tiles;
+        fill_coarse(args.ci, rargs.tile0, nb, tiles);
         args.n = (uint32_t)nb; args.partial0 = partial0; args.partials = want_obj ? workspace : nullptr;
         {
             ProfileScope prof(stream, first + kMaxPackBatch >= n);
@@ -1429,6 +1439,13 @@ static int run_mask_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype
             args.m[k].aux = p.out;
             args.m[k].pad = (uint32_t)p.ld_out;
             tiles += tiles_of(args.m[k].n_strips);
+        }
+        {
+            uint32_t first0[kMaxBatch + 1];
+            for (int k = 0; k < nb; k++)
+                first0[k] = args.m[k].tile0;
+            first0[nb] = tiles;
+            fill_coarse(args.ci, first0, nb, tiles);
         }
         args.n_mats = (uint32_t)nb; args.K = (uint32_t)(M - N); args.N = (uint32_t)N;
         {

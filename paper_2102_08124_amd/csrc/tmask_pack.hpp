@@ -32,19 +32,21 @@ struct PackDev {
 
 struct PackArgs {
     PackDev d[kMaxPackBatch];
+    CoarseIndex ci;
     uint32_t n;
     uint32_t N;
 };
-static_assert(sizeof(PackArgs) <= 16384, "descriptor table is sized to stay a small kernel argument");
+static_assert(sizeof(PackArgs) <= 16384 + 2048, "descriptor table is sized to stay a small kernel argument");
 
 // Arguments of the kernels that compute the mask themselves (tmask_approx_pack).
 struct FusedArgs {
     PackDev d[kMaxPackBatch];   // mask = output here (may be null when WMASK is false)
+    CoarseIndex ci;
     uint32_t n;
     uint32_t partial0;          // index of this launch's first partial in the workspace
     void *partials;             // one double per workgroup, or null
 };
-static_assert(sizeof(FusedArgs) <= 16384 + 64, "descriptor table is sized to stay a small kernel argument");
+static_assert(sizeof(FusedArgs) <= 16384 + 2048, "descriptor table is sized to stay a small kernel argument");
 
 
 // Tile number inside a matrix -> tile coordinates, for the kernels that write W^T in short runs per column.
@@ -55,6 +57,22 @@ static_assert(sizeof(FusedArgs) <= 16384 + 64, "descriptor table is sized to sta
 // peak at 8192 x 8192; shorter runs lose it again, full-height runs cost the bf16 kernels 5 points).
 // Bands beyond the last multiple of eight are walked column by column.
 constexpr uint32_t kPackRunRows = 4096;
+
+// Which descriptor does workgroup `tile` belong to (PackArgs or FusedArgs): coarse index, then a short binary search.
+template <typename Args>
+__device__ __forceinline__ int find_pack_desc(const Args &args, uint32_t tile)
+{
+    const uint32_t e = args.ci.e[tile >> args.ci.shift];
+    int lo = (int)(e & 0xFFFFu), hi = (int)(e >> 16);
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].tile0 <= tile)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
 
 __device__ __forceinline__ void tile_coords(uint32_t tl, uint32_t tiles_x, uint32_t tiles_y, uint32_t run, uint32_t &ty,
                                             uint32_t &tx)
@@ -160,15 +178,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
 
     // ---- which tile ----
     const uint32_t tile = blockIdx.x;
-    int lo = 0, hi = (int)args.n - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (args.d[mid].tile0 <= tile)
-            lo = mid;
-        else
-            hi = mid - 1;
-    }
-    const PackDev d = args.d[lo];
+    const PackDev d = args.d[find_pack_desc(args, tile)];
     const uint32_t N = NN ? (uint32_t)NN : args.N;
     const uint32_t tl = tile - d.tile0;
     uint32_t ty, tx;
