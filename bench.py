@@ -300,8 +300,8 @@ def one_pass_section(tm, torch, T, mats_np, copies, reps):
     kms, cms = T.measure(lambda k: tm.tmask_approx_pack(sets[k % copies]["fused"], None, None, N, M, workspace=wsp), reps)
     out["approx_pack"] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(alg["approx_pack"], kms)["frac"],
                           "call_frac": hbm(alg["approx_pack"], cms)["frac"], "weights_per_s": weights / (cms * 1e-3)}
-    outs = [[torch.empty_like(w) for w in s["ws"]] for s in sets]
-    kms, cms = T.measure(lambda k: tm.tmask_approx_dense(sets[k % copies]["ws"], None, outs[k % copies], N, M), reps)
+    dense = [tm.DenseBatch(s["ws"], None, [torch.empty_like(w) for w in s["ws"]]) for s in sets]
+    kms, cms = T.measure(lambda k: tm.tmask_approx_dense(dense[k % copies], None, None, N, M), reps)
     out["approx_dense"] = {"kernel_ms": kms, "call_ms": cms, "frac": hbm(alg["approx_dense"], kms)["frac"],
                            "call_frac": hbm(alg["approx_dense"], cms)["frac"], "weights_per_s": weights / (cms * 1e-3)}
     return out
@@ -314,7 +314,7 @@ def config4_section(tm, torch, T, wl, reps):
     weights = w_np.size
     ws = [to_device(torch, w_np), to_device(torch, w_np)]
     out = {"what": "8192x8192 fp32 Laplace(0,1), seed 4; times are whole calls (main kernel + reduce launch), medians"}
-    for N, M in ((2, 4), (4, 8), (8, 16)):
+    for N, M in ((2, 4), (4, 8), (8, 16), (16, 32)):
         masks = [tm.alloc_masks([w])[0] for w in ws]
         obj = torch.zeros(3, dtype=torch.float64, device="cuda")
         wsp = tm.alloc_workspace([ws[0]], N, M)

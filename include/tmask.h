@@ -19,7 +19,9 @@
  *   is DEVICE memory owned by the caller; descriptor arrays (`tmask_mat*`, `tmask_pack_desc*`, `tmask_fused_desc*`
  *   and the other `*_desc` types) are HOST memory read before the call returns.  Work is enqueued on `hip_stream` (a hipStream_t,
  *   NULL = default stream); the library never synchronises, allocates or frees device memory, and
- *   holds no state between calls.  Outputs are valid once the stream has been synchronised.
+ *   holds no state between calls (two documented exceptions: the one-shot events of tmask_profile_next, which are
+ *   thread-local, and the static scratch array of tmask_approx_noalloc).  Outputs are valid once the stream has
+ *   been synchronised.
  *   The workspace (at least tmask_workspace_bytes(), 256-byte aligned) is scratch for the duration
  *   of the enqueued work; calls that overlap on different streams need different workspaces.
  *

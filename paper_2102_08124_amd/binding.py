@@ -442,18 +442,30 @@ def _dense_descs(ws, masks, outs):
     return arr, n, dt
 
 
+class DenseBatch:
+    """Host descriptor array for tmask_approx_dense / tmask_prune_1d_dense, marshalled once (keeps the tensors alive).
+    masks: list of mask tensors to be written, or None."""
+
+    def __init__(self, ws, masks, outs):
+        self.ws, self.outs = list(ws), list(outs)
+        self.masks = None if masks is None else list(masks)
+        self.arr, self.n, self.dt = _dense_descs(self.ws, self.masks, self.outs)
+
+
 def tmask_approx_dense(ws, masks, outs, N: int, M: int, mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
     """Algorithm 1 and the masked copy in one pass: outs[k] = ws[k] with the entries Algorithm 1 prunes set to +0
-    (outs[k] may be ws[k]); masks[k] receives the mask, or masks is None and no mask is written."""
-    arr, n, dt = _dense_descs(ws, masks, outs)
+    (outs[k] may be ws[k]); masks[k] receives the mask, or masks is None and no mask is written.  `ws` may be a
+    DenseBatch (then masks and outs are ignored)."""
+    arr, n, dt = (ws.arr, ws.n, ws.dt) if isinstance(ws, DenseBatch) else _dense_descs(ws, masks, outs)
     _check(load_library().tmask_approx_dense(arr, n, dt, N, M, mask_fmt, _stream_ptr(stream)))
 
 
 def tmask_prune_1d_dense(ws, masks, outs, N: int, M: int, absorb_mean: bool = False,
                          mask_fmt: int = TMASK_MASK_U8, stream=None) -> None:
     """N:M pruning along rows and the masked copy in one pass (outs[k] may be ws[k]); with absorb_mean the mean of
-    every row group's pruned weights is added to its kept ones.  masks[k] receives the mask, or masks is None."""
-    arr, n, dt = _dense_descs(ws, masks, outs)
+    every row group's pruned weights is added to its kept ones.  masks[k] receives the mask, or masks is None.  `ws` may
+    be a DenseBatch."""
+    arr, n, dt = (ws.arr, ws.n, ws.dt) if isinstance(ws, DenseBatch) else _dense_descs(ws, masks, outs)
     _check(load_library().tmask_prune_1d_dense(arr, n, dt, N, M, 1 if absorb_mean else 0, mask_fmt, _stream_ptr(stream)))
 
 
