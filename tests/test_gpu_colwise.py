@@ -290,3 +290,49 @@ def test_unaligned_packed_outputs_only():
     for g, t in zip(packed, oracle.apply_pack(w, mask, N, M)):
         gh = g.contiguous().view(torch.int16).cpu().numpy().view(np.uint16) if g.dtype == torch.bfloat16 else g.cpu().numpy()
         assert np.array_equal(gh.view(np.uint8), t.view(np.uint8))
+
+
+# ---------------------------------------------------------------- batches beyond one launch ------
+
+def test_batches_of_300_matrices_cross_the_launch_limit_and_share_index_buckets():
+    # 300 matrices: more than one launch holds (256; 224 for the pack kernels), most of them one workgroup each, so many
+    # matrices fall into one bucket of the coarse index and the search inside a bucket is exercised; a few larger ones
+    # make the buckets uneven.  approx + exact + score + apply_pack + approx_pack + approx_dense, 2:4 fp32 and 4:8 bf16.
+    rng = np.random.default_rng(4000)
+    for dt, N, M in (("f32", 2, 4), ("bf16", 4, 8)):
+        shapes = [(16, 16), (16, 32), (32, 16), (8 * M, 1040), (16, 64)]
+        picks = rng.integers(0, len(shapes), size=300)
+        picks[[7, 150, 299]] = 3
+        ws = [_inputs(dt, *shapes[int(p)], seed=4100 + k) for k, p in enumerate(picks)]
+        want = [oracle.approx(w, N, M) for w in ws]
+        masks, obj = run_masks(tm.tmask_approx, ws, N, M)
+        for k in range(300):
+            assert np.array_equal(masks[k], want[k][0]), "approx, matrix %d" % k
+            assert obj[k] == pytest.approx(want[k][1], rel=1e-5)
+        emasks, eobj = run_masks(tm.tmask_exact, ws, N, M)
+        for k in range(0, 300, 7):
+            _, oobj, opb = oracle.exact(ws[k], N, M, per_block=True)
+            _check_exact(ws[k], emasks[k], N, M, opb)
+            assert eobj[k] == pytest.approx(oobj, rel=1e-5)
+        scores, pbs = run_score(ws, masks, N, M)
+        for k in range(0, 300, 5):
+            o = oracle.score(ws[k], masks[k], N, M)
+            assert (scores[k]["kept"], scores[k]["row_not_n"], scores[k]["col_not_n"]) == (o.kept, o.row_not_n, o.col_not_n)
+            np.testing.assert_allclose(pbs[k], o.per_block, rtol=1e-5, atol=1e-30)
+        packed = run_pack(ws, masks, N, M)
+        fused, fmasks, fobj = run_fused(ws, N, M)
+        for k in range(300):
+            assert np.array_equal(fmasks[k], want[k][0]), "approx_pack, matrix %d" % k
+        for k in range(0, 300, 5):
+            ref = oracle.apply_pack(ws[k], masks[k], N, M)
+            for g, f, t in zip(packed[k], fused[k], ref):
+                assert np.array_equal(g.view(np.uint8), t.view(np.uint8)), "apply_pack, matrix %d" % k
+                assert np.array_equal(f.view(np.uint8), t.view(np.uint8)), "approx_pack, matrix %d" % k
+        wd = [to_dev(w) for w in ws]
+        outs = [torch.empty_like(w) for w in wd]
+        tm.tmask_approx_dense(wd, None, outs, N, M)
+        torch.cuda.synchronize()
+        it = torch.int16 if dt == "bf16" else torch.int32
+        for k in range(0, 300, 5):
+            raw = wd[k].view(it).cpu().numpy()
+            assert np.array_equal(outs[k].view(it).cpu().numpy(), np.where(want[k][0] != 0, raw, 0)), "approx_dense, matrix %d" % k
