@@ -240,8 +240,10 @@ int tmask_flip_count(const tmask_flip_desc *descs, int n, tmask_mask_fmt mf, voi
  * N:M pattern on an unstructured-sparse model costs (the paper sets N:M per layer so that few such flips are
  * needed).  count[0] <- #{(i,j): W_ij is not +-0 (NaN counts as active) and S_ij = 0}.  Any mask is accepted.
  * w, mask, count: device; ld in elements, mask_ld in bytes; mask in format mf; count 8-byte aligned.
- * Requirements: cols a multiple of 16 bytes' worth of elements, w and its row pitch 16-byte aligned, a U8 mask and
- * its pitch aligned to 4 (fp32) or 8 (bf16) bytes, BITS masks need cols to be a multiple of 8.  No workspace; exact.
+ * Requirements: any rows, cols > 0 (BITS masks need cols to be a multiple of 8); w aligned to its element type.
+ * The streaming kernel runs when cols is a multiple of 16 bytes' worth of elements, w and its row pitch are 16-byte
+ * aligned and a U8 mask and its pitch are aligned to 4 (fp32) or 8 (bf16) bytes; a call in which some matrix misses
+ * that is counted element by element, with the same result.  No workspace; exact.
  */
 typedef struct {
     const void *w; int64_t ld;
@@ -264,9 +266,12 @@ int tmask_pattern_violations(const tmask_violation_desc *descs, int n, tmask_dty
  * bf16 results are rounded to nearest even.  Any mask is accepted (transposable, 1-D, unstructured):
  * neither N nor the pattern is checked.  Without absorb_mean, M is ignored.
  * w, mask, out: device; ld, ld_out in elements, mask_ld in bytes; mask in format mf.
- * Requirements (checked): cols a multiple of 16 bytes' worth of elements (and of M with absorb_mean,
- * M in {2, 4, 8, 16, 32}); w, out and their row pitches 16-byte aligned; a U8 mask and its pitch
- * aligned to 4 (fp32) or 8 (bf16) bytes; BITS masks need cols to be a multiple of 8.  No workspace.
+ * Requirements (checked): any rows, cols > 0 (cols a multiple of M with absorb_mean, M in
+ * {2, 4, 8, 16, 32}; of 8 for BITS masks); w and out aligned to the element type.  The streaming
+ * kernel runs when cols is a multiple of 16 bytes' worth of elements, w, out and their row pitches
+ * are 16-byte aligned and a U8 mask and its pitch are aligned to 4 (fp32) or 8 (bf16) bytes; a call
+ * in which some matrix misses that takes an element-wise kernel (same masked copy; with absorb_mean
+ * the group's pruned weights are summed pairwise over the whole group).  No workspace.
  */
 typedef struct {
     const void *w; int64_t ld;

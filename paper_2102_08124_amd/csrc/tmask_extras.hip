@@ -328,6 +328,118 @@ static dense_kernel_t pick_dense(int M, bool absorb)
 
 }  // namespace tmask
 
+namespace tmask {
+
+// Element-wise forms of the masked copy and of the violation count, for matrices that miss the 16-byte alignment of
+// the kernels above: a lane takes one entry, a wavefront 64 consecutive columns of a row (a group of M <= 32 columns
+// is then an aligned run of lanes: sums by butterfly, counts from the wavefront's ballot).  d.pad = cols,
+// d.chunks_per_row = runs of 64 columns per row.  MODE 0: out = W (.) S; 1: the same with the mean of every group's
+// pruned weights added to its kept ones; 2: count the non-zero entries the mask removes.
+template <int DT, int FMT, int MODE>
+__global__ __launch_bounds__(kThreads) void dense_elementwise_kernel(const DenseArgs args, const uint32_t M)
+{
+    __shared__ uint32_t red[kThreads / 64];
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].wg0 <= blockIdx.x)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const DenseDev d = args.d[lo];
+    constexpr uint32_t ES = DT == kF32 ? 4u : 2u;
+    const uint32_t cols = d.pad, lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t total = d.rows * d.chunks_per_row;
+    uint32_t cnt = 0;
+    for (uint32_t u = (blockIdx.x - d.wg0) * (kThreads / 64) + wave; u < total; u += d.n_wg * (kThreads / 64)) {
+        const uint32_t r = u / d.chunks_per_row, c = (u - r * d.chunks_per_row) * 64u + lane;
+        const bool active = c < cols;
+        uint32_t raw = 0;
+        bool keep = false;
+        if (active) {
+            const char *src = d.w + (size_t)r * d.ld_b + (size_t)c * ES;
+            raw = DT == kF32 ? *(const uint32_t *)src : (uint32_t) * (const uint16_t *)src;
+            if constexpr (FMT == kMaskU8)
+                keep = d.mask[(size_t)r * d.mask_ld + c] != 0;
+            else
+                keep = ((d.mask[(size_t)r * d.mask_ld + (c >> 3)] >> (c & 7u)) & 1u) != 0;
+        }
+        if constexpr (MODE == 2) {
+            const uint32_t mag = DT == kF32 ? (raw & 0x7FFFFFFFu) : (raw & 0x7FFFu);
+            cnt += (active && mag != 0u && !keep) ? 1u : 0u;
+        } else {
+            uint32_t o = keep ? raw : 0u;
+            if constexpr (MODE == 1) {
+                const float v = DT == kF32 ? __uint_as_float(raw) : __uint_as_float(raw << 16);
+                float ps = (active && !keep) ? v : 0.f;
+                for (uint32_t off = M >> 1; off >= 1u; off >>= 1)
+                    ps += __shfl_xor(ps, (int)off, 64);
+                const unsigned long long kb = __builtin_amdgcn_ballot_w64(keep);
+                const uint32_t seg = (uint32_t)(kb >> (lane & ~(M - 1u))) & (uint32_t)((1ull << M) - 1ull);
+                const uint32_t pc = M - (uint32_t)__builtin_popcount(seg);
+                const float mean = (pc != 0u && pc != M) ? ps / (float)pc : 0.f;
+                const float res = keep ? v + mean : 0.f;
+                if constexpr (DT == kF32) {
+                    o = __float_as_uint(res);
+                } else {
+                    const uint32_t b = __float_as_uint(res);
+                    o = ((b & 0x7FFFFFFFu) > 0x7F800000u) ? ((b >> 16) | 0x0040u) : ((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+                }
+            }
+            if (active) {
+                char *dst = d.out + (size_t)r * d.ld_out_b + (size_t)c * ES;
+                if constexpr (DT == kF32)
+                    *(uint32_t *)dst = o;
+                else
+                    *(uint16_t *)dst = (uint16_t)o;
+            }
+        }
+    }
+    if constexpr (MODE == 2) {
+        const uint32_t t = block_sum(cnt, red);
+        if (threadIdx.x == 0 && t)
+            atomicAdd((unsigned long long *)d.out, (unsigned long long)t);
+    }
+}
+
+typedef void (*dense_elementwise_t)(const DenseArgs, const uint32_t);
+
+__global__ void violation_zero_kernel(const DenseArgs args);
+
+template <int MODE>
+static dense_elementwise_t pick_elementwise(int dt, int mf)
+{
+    return dt == TMASK_F32 ? (mf == TMASK_MASK_U8 ? dense_elementwise_kernel<kF32, kMaskU8, MODE> : dense_elementwise_kernel<kF32, kMaskBits, MODE>)
+                           : (mf == TMASK_MASK_U8 ? dense_elementwise_kernel<kBF16, kMaskU8, MODE> : dense_elementwise_kernel<kBF16, kMaskBits, MODE>);
+}
+
+// launches the element-wise kernel over descriptors already filled except for the work split
+static int launch_elementwise(dense_elementwise_t kern, DenseArgs &args, int nb, uint32_t M, bool zero_first, hipStream_t stream,
+                              bool last)
+{
+    uint32_t wgs = 0;
+    for (int k = 0; k < nb; k++) {
+        DenseDev &d = args.d[k];
+        const uint64_t units = (uint64_t)d.rows * d.chunks_per_row;
+        uint64_t nw = (units + 15) / 16;                    // four wavefronts per workgroup, four runs each
+        nw = nw < 1 ? 1 : nw > 4096 ? 4096 : nw;
+        d.n_wg = (uint32_t)nw; d.wg0 = wgs;
+        wgs += d.n_wg;
+    }
+    args.n = (uint32_t)nb;
+    if (zero_first)
+        hipLaunchKernelGGL(violation_zero_kernel, dim3(1), dim3(kMaxDenseBatch), 0, stream, args);
+    {
+        ProfileScope prof(stream, last);
+        hipLaunchKernelGGL(kern, dim3(wgs), dim3(kThreads), 0, stream, args, M);
+    }
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? TMASK_OK : hip_fail(e, "element-wise masked copy / count launch");
+}
+
+}  // namespace tmask
+
 extern "C" int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dtype dt, int M, int absorb_mean,
                                  tmask_mask_fmt mf, void *hip_stream)
 {
@@ -342,27 +454,48 @@ extern "C" int tmask_apply_dense(const tmask_dense_desc *descs, int n, tmask_dty
     if (absorb_mean && M != 2 && M != 4 && M != 8 && M != 16 && M != 32)
         return fail(TMASK_ERR_NM, "mean absorption needs M in {2, 4, 8, 16, 32} (M=%d)", M);
     const int64_t es = dt == TMASK_F32 ? 4 : 2, per_chunk = 16 / es;
+    bool aligned = true;
     for (int i = 0; i < n; i++) {
         const tmask_dense_desc &f = descs[i];
         if (!f.w || !f.mask || !f.out)
             return fail(TMASK_ERR_NULL, "matrix %d: w, mask or out is NULL", i);
-        if (f.rows <= 0 || f.cols <= 0 || f.cols % per_chunk || (absorb_mean && f.cols % M) ||
-            (mf == TMASK_MASK_BITS && f.cols % 8))
-            return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld (cols must be a multiple of %lld%s%s)", i,
-                        (long long)f.rows, (long long)f.cols, (long long)per_chunk, absorb_mean ? " and of M" : "",
-                        mf == TMASK_MASK_BITS ? " and of 8 for BITS masks" : "");
+        if (f.rows <= 0 || f.cols <= 0 || (absorb_mean && f.cols % M) || (mf == TMASK_MASK_BITS && f.cols % 8))
+            return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld (cols must be positive%s%s)", i,
+                        (long long)f.rows, (long long)f.cols, absorb_mean ? ", a multiple of M" : "",
+                        mf == TMASK_MASK_BITS ? ", a multiple of 8 for BITS masks" : "");
         const int64_t mask_row = mf == TMASK_MASK_U8 ? f.cols : f.cols / 8;
         if (f.ld < f.cols || f.ld_out < f.cols || f.mask_ld < mask_row || f.ld * es > 0x7FFFFFFFll ||
-            f.ld_out * es > 0x7FFFFFFFll || f.mask_ld > 0x7FFFFFFFll || f.rows * (f.cols / per_chunk) >= 0xFFFFFFFFll)
+            f.ld_out * es > 0x7FFFFFFFll || f.mask_ld > 0x7FFFFFFFll || f.rows * ((f.cols + per_chunk - 1) / per_chunk) >= 0xFFFFFFFFll)
             return fail(TMASK_ERR_SHAPE, "matrix %d: leading dimensions must cover a row; at most 2^32 - 1 chunks of 16 bytes",
                         i);
-        if (((uintptr_t)f.w | (uintptr_t)f.out | (uint64_t)(f.ld * es) | (uint64_t)(f.ld_out * es)) & 15)
-            return fail(TMASK_ERR_ALIGN, "matrix %d: w, out and their row pitches must be 16-byte aligned", i);
+        if (((uintptr_t)f.w | (uintptr_t)f.out) % (uintptr_t)es)
+            return fail(TMASK_ERR_ALIGN, "matrix %d: w and out must be aligned to the element size", i);
+        if ((((uintptr_t)f.w | (uintptr_t)f.out | (uint64_t)(f.ld * es) | (uint64_t)(f.ld_out * es)) & 15) || f.cols % per_chunk)
+            aligned = false;
         if (mf == TMASK_MASK_U8 && (((uintptr_t)f.mask | (uint64_t)f.mask_ld) & (uint64_t)(per_chunk - 1)))
-            return fail(TMASK_ERR_ALIGN, "matrix %d: a U8 mask and its row pitch must be %lld-byte aligned", i,
-                        (long long)per_chunk);
+            aligned = false;
     }
     const bool absorb = absorb_mean != 0;
+    if (!aligned) {      // element-wise kernel: any layout
+        const dense_elementwise_t ek = absorb ? pick_elementwise<1>((int)dt, (int)mf) : pick_elementwise<0>((int)dt, (int)mf);
+        for (int first = 0; first < n; first += kMaxDenseBatch) {
+            const int nb = n - first < kMaxDenseBatch ? n - first : kMaxDenseBatch;
+            DenseArgs args;
+            memset(&args, 0, sizeof args);
+            for (int k = 0; k < nb; k++) {
+                const tmask_dense_desc &f = descs[first + k];
+                DenseDev &d = args.d[k];
+                d.w = (const char *)f.w; d.mask = (const unsigned char *)f.mask; d.out = (char *)f.out;
+                d.rows = (uint32_t)f.rows; d.chunks_per_row = (uint32_t)((f.cols + 63) / 64); d.pad = (uint32_t)f.cols;
+                d.ld_b = (uint32_t)(f.ld * es); d.ld_out_b = (uint32_t)(f.ld_out * es); d.mask_ld = (uint32_t)f.mask_ld;
+            }
+            const int rc = launch_elementwise(ek, args, nb, (uint32_t)(absorb ? M : 1), false, (hipStream_t)hip_stream,
+                                              first + kMaxDenseBatch >= n);
+            if (rc)
+                return rc;
+        }
+        return TMASK_OK;
+    }
     dense_kernel_t kern = dt == TMASK_F32 ? (mf == TMASK_MASK_U8 ? pick_dense<kF32, kMaskU8>(M, absorb)
                                                                  : pick_dense<kF32, kMaskBits>(M, absorb))
                                           : (mf == TMASK_MASK_U8 ? pick_dense<kBF16, kMaskU8>(M, absorb)
@@ -489,25 +622,45 @@ extern "C" int tmask_pattern_violations(const tmask_violation_desc *descs, int n
     if (mf != TMASK_MASK_U8 && mf != TMASK_MASK_BITS)
         return fail(TMASK_ERR_DTYPE, "unknown mask format %d", (int)mf);
     const int64_t es = dt == TMASK_F32 ? 4 : 2, per_chunk = 16 / es;
+    bool aligned = true;
     for (int i = 0; i < n; i++) {
         const tmask_violation_desc &f = descs[i];
         if (!f.w || !f.mask || !f.count)
             return fail(TMASK_ERR_NULL, "matrix %d: w, mask or count is NULL", i);
-        if (f.rows <= 0 || f.cols <= 0 || f.cols % per_chunk || (mf == TMASK_MASK_BITS && f.cols % 8))
-            return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld (cols must be a multiple of %lld%s)", i,
-                        (long long)f.rows, (long long)f.cols, (long long)per_chunk,
-                        mf == TMASK_MASK_BITS ? " and of 8 for BITS masks" : "");
+        if (f.rows <= 0 || f.cols <= 0 || (mf == TMASK_MASK_BITS && f.cols % 8))
+            return fail(TMASK_ERR_SHAPE, "matrix %d: rows=%lld cols=%lld (cols must be positive%s)", i,
+                        (long long)f.rows, (long long)f.cols, mf == TMASK_MASK_BITS ? ", a multiple of 8 for BITS masks" : "");
         const int64_t mask_row = mf == TMASK_MASK_U8 ? f.cols : f.cols / 8;
         if (f.ld < f.cols || f.mask_ld < mask_row || f.ld * es > 0x7FFFFFFFll || f.mask_ld > 0x7FFFFFFFll ||
-            f.rows * (f.cols / per_chunk) >= 0xFFFFFFFFll)
+            f.rows * ((f.cols + per_chunk - 1) / per_chunk) >= 0xFFFFFFFFll)
             return fail(TMASK_ERR_SHAPE, "matrix %d: leading dimensions must cover a row; at most 2^32 - 1 chunks of 16 bytes", i);
-        if (((uintptr_t)f.w | (uint64_t)(f.ld * es)) & 15)
-            return fail(TMASK_ERR_ALIGN, "matrix %d: w and its row pitch must be 16-byte aligned", i);
+        if ((uintptr_t)f.w % (uintptr_t)es)
+            return fail(TMASK_ERR_ALIGN, "matrix %d: w must be aligned to the element size", i);
+        if ((((uintptr_t)f.w | (uint64_t)(f.ld * es)) & 15) || f.cols % per_chunk)
+            aligned = false;
         if (mf == TMASK_MASK_U8 && (((uintptr_t)f.mask | (uint64_t)f.mask_ld) & (uint64_t)(per_chunk - 1)))
-            return fail(TMASK_ERR_ALIGN, "matrix %d: a U8 mask and its row pitch must be %lld-byte aligned", i,
-                        (long long)per_chunk);
+            aligned = false;
         if ((uintptr_t)f.count & 7)
             return fail(TMASK_ERR_ALIGN, "matrix %d: count must be 8-byte aligned", i);
+    }
+    if (!aligned) {      // element-wise kernel: any layout
+        const dense_elementwise_t ek = pick_elementwise<2>((int)dt, (int)mf);
+        for (int first = 0; first < n; first += kMaxDenseBatch) {
+            const int nb = n - first < kMaxDenseBatch ? n - first : kMaxDenseBatch;
+            DenseArgs args;
+            memset(&args, 0, sizeof args);
+            for (int k = 0; k < nb; k++) {
+                const tmask_violation_desc &f = descs[first + k];
+                DenseDev &d = args.d[k];
+                d.w = (const char *)f.w; d.mask = (const unsigned char *)f.mask; d.out = (char *)f.count;
+                d.rows = (uint32_t)f.rows; d.chunks_per_row = (uint32_t)((f.cols + 63) / 64); d.pad = (uint32_t)f.cols;
+                d.ld_b = (uint32_t)(f.ld * es); d.ld_out_b = 0; d.mask_ld = (uint32_t)f.mask_ld;
+            }
+            const int rc = launch_elementwise(ek, args, nb, 1u, true, (hipStream_t)hip_stream, first + kMaxDenseBatch >= n);
+            if (rc)
+                return rc;
+        }
+        return TMASK_OK;
     }
     dense_kernel_t kern = dt == TMASK_F32 ? (mf == TMASK_MASK_U8 ? violation_count_kernel<kF32, kMaskU8>
                                                                  : violation_count_kernel<kF32, kMaskBits>)

@@ -435,6 +435,13 @@ __global__ __launch_bounds__(kReduceThreads) void objective_reduce_kernel(const 
     const double *src = args.partials + args.partial0;
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     uint32_t t = t0 + threadIdx.x;
+    for (; t + 7 * kReduceThreads < t1; t += 8 * kReduceThreads) {
+        const double v0 = src[t], v1 = src[t + kReduceThreads], v2 = src[t + 2 * kReduceThreads], v3 = src[t + 3 * kReduceThreads];
+        const double v4 = src[t + 4 * kReduceThreads], v5 = src[t + 5 * kReduceThreads], v6 = src[t + 6 * kReduceThreads],
+                     v7 = src[t + 7 * kReduceThreads];
+        a0 += v0; a1 += v1; a2 += v2; a3 += v3;
+        a0 += v4; a1 += v5; a2 += v6; a3 += v7;
+    }
     for (; t + 3 * kReduceThreads < t1; t += 4 * kReduceThreads) {
         a0 += src[t];
         a1 += src[t + kReduceThreads];
@@ -657,15 +664,47 @@ struct ScoreReduceArgs {
     tmask_score_out *out;   // entry of the first matrix of this launch
 };
 
-__global__ __launch_bounds__(kThreads) void score_reduce_kernel(const ScoreReduceArgs args)
+// 1024 threads, two records in flight per thread: the loop is a chain of load latencies.  A matrix of 16384 x 16384
+// leaves 32768 (bf16) or 65536 (fp32) records, which one workgroup still needs 24 / 41 us for, so large matrices are
+// reduced in two launches: STAGE 1, workgroup (m, s) adds slice s of matrix m's records and leaves the sum in the
+// slice's first record (only this workgroup reads the slice); STAGE 2, workgroup m adds those first records.
+// STAGE 0 is the single launch: workgroup m adds all records of matrix m.
+constexpr uint32_t kReduceSlices = 32;
+constexpr uint32_t kReduceTwoStageFrom = 8192;    // records of the largest matrix of a launch
+
+template <int STAGE>
+__global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(const ScoreReduceArgs args)
 {
-    __shared__ double redd[2][kThreads / 64];
-    __shared__ unsigned long long redu[5][kThreads / 64];
+    __shared__ double redd[2][kReduceThreads / 64];
+    __shared__ unsigned long long redu[5][kReduceThreads / 64];
     const uint32_t m = blockIdx.x;
     double retained = 0.0, total = 0.0;
     unsigned long long kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
-    for (uint32_t t = args.tile0[m] + threadIdx.x; t < args.tile0[m + 1]; t += kThreads) {
-        const ScorePartial p = args.partials[args.partial0 + t];
+    const uint32_t t0 = args.tile0[m], t1 = args.tile0[m + 1];
+    const uint32_t len = (t1 - t0 + kReduceSlices - 1) / kReduceSlices;     // records per slice
+    // records base + i * stride, i < count
+    uint32_t base = t0, count = t1 - t0, stride = 1;
+    if constexpr (STAGE == 1) {
+        base = t0 + blockIdx.y * len;
+        if (base >= t1)
+            return;                                   // the whole workgroup: nothing in this slice
+        count = t1 - base < len ? t1 - base : len;
+    } else if constexpr (STAGE == 2) {
+        stride = len;
+        count = len ? (t1 - t0 + len - 1) / len : 0;
+    }
+    const ScorePartial *src = args.partials + args.partial0 + base;
+    uint32_t i = threadIdx.x;
+    for (; i + kReduceThreads < count; i += 2 * kReduceThreads) {
+        const ScorePartial p = src[(size_t)i * stride];
+        const ScorePartial q = src[(size_t)(i + kReduceThreads) * stride];
+        retained += p.retained; total += p.total;
+        kept += p.kept; rowv += p.rowv; colv += p.colv; rowne += p.rowne; colne += p.colne;
+        retained += q.retained; total += q.total;
+        kept += q.kept; rowv += q.rowv; colv += q.colv; rowne += q.rowne; colne += q.colne;
+    }
+    for (; i < count; i += kReduceThreads) {
+        const ScorePartial p = src[(size_t)i * stride];
         retained += p.retained; total += p.total;
         kept += p.kept; rowv += p.rowv; colv += p.colv; rowne += p.rowne; colne += p.colne;
     }
@@ -681,25 +720,31 @@ __global__ __launch_bounds__(kThreads) void score_reduce_kernel(const ScoreReduc
         for (int k = 0; k < 5; k++)
             redu[k][w] = u[k];
     }
-    __syncthreads();
+    __syncthreads();          // every thread's records have arrived by now: STAGE 1 may overwrite the slice's first one
     if (threadIdx.x == 0) {
         double r[2];
         unsigned long long c[5];
 #pragma unroll
         for (int k = 0; k < 2; k++) {
             r[k] = redd[k][0];
-            for (int w = 1; w < (int)(kThreads / 64); w++)
+            for (int w = 1; w < (int)(kReduceThreads / 64); w++)
                 r[k] += redd[k][w];
         }
 #pragma unroll
         for (int k = 0; k < 5; k++) {
             c[k] = redu[k][0];
-            for (int w = 1; w < (int)(kThreads / 64); w++)
+            for (int w = 1; w < (int)(kReduceThreads / 64); w++)
                 c[k] += redu[k][w];
         }
-        tmask_score_out *o = args.out + m;
-        o->retained_l1 = r[0]; o->total_l1 = r[1];
-        o->kept = c[0]; o->row_violations = c[1]; o->col_violations = c[2]; o->row_not_n = c[3]; o->col_not_n = c[4];
+        if constexpr (STAGE == 1) {
+            ScorePartial *o = const_cast<ScorePartial *>(src);
+            o->retained = r[0]; o->total = r[1];
+            o->kept = c[0]; o->rowv = c[1]; o->colv = c[2]; o->rowne = c[3]; o->colne = c[4];
+        } else {
+            tmask_score_out *o = args.out + m;
+            o->retained_l1 = r[0]; o->total_l1 = r[1];
+            o->kept = c[0]; o->row_violations = c[1]; o->col_violations = c[2]; o->row_not_n = c[3]; o->col_not_n = c[4];
+        }
     }
 }
 
@@ -1034,7 +1079,15 @@ int launch_score_reduce(const uint32_t *first0, int nb, uint32_t partial0, const
         rargs.tile0[k] = first0[k];
     rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0;
     rargs.partials = (const ScorePartial *)partials; rargs.out = out;
-    hipLaunchKernelGGL(score_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
+    uint32_t most = 0;
+    for (int k = 0; k < nb; k++)
+        most = first0[k + 1] - first0[k] > most ? first0[k + 1] - first0[k] : most;
+    if (most >= kReduceTwoStageFrom) {
+        hipLaunchKernelGGL(score_reduce_kernel<1>, dim3(nb, kReduceSlices), dim3(kReduceThreads), 0, stream, rargs);
+        hipLaunchKernelGGL(score_reduce_kernel<2>, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
+    } else {
+        hipLaunchKernelGGL(score_reduce_kernel<0>, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
+    }
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? TMASK_OK : hip_fail(e, "score reduce launch");
 }
@@ -1120,12 +1173,9 @@ int tmask_score(const tmask_mat *mats, int n_mats, tmask_dtype dt, int N, int M,
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return hip_fail(e, "score kernel launch");
-        rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0;
-        rargs.partials = (const ScorePartial *)workspace; rargs.out = out + first;
-        hipLaunchKernelGGL(score_reduce_kernel, dim3(nb), dim3(kThreads), 0, stream, rargs);
-        e = hipGetLastError();
-        if (e != hipSuccess)
-            return hip_fail(e, "score reduce launch");
+        const int rc = launch_score_reduce(rargs.tile0, nb, partial0, workspace, out + first, stream);
+        if (rc)
+            return rc;
         partial0 += tiles;
     }
     return TMASK_OK;

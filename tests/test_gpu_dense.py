@@ -94,11 +94,55 @@ def test_rejects_bad_arguments():
     with pytest.raises(tm.TmaskError):
         tm.tmask_apply_dense([w], [m], [w], 6, True)                    # M not a power of two
     with pytest.raises(tm.TmaskError):
-        tm.tmask_apply_dense([w[:, :62]], [m[:, :62]], [w[:, :62]])     # cols not a whole number of 16-byte pieces
-    with pytest.raises(tm.TmaskError):
         tm.tmask_apply_dense([w[:, :48]], [m[:, :48]], [w[:, :48]], 32, True)   # cols not a multiple of M
     with pytest.raises(tm.TmaskError):
-        tm.tmask_apply_dense([w[:, 1:5]], [m[:, :4]], [w[:, 1:5]])      # misaligned
+        tm.tmask_apply_dense([w[:, :60]], [m[:, :60]], [w[:, :60]], mask_fmt=tm.TMASK_MASK_BITS)   # bits: cols % 8
+
+
+def _strided_dev(a, ld, off, fill):
+    """A device copy of the 2-D array `a` that starts `off` elements into its buffer with row pitch `ld`; also the buffer."""
+    rows, cols = a.shape
+    src = to_dev(a) if a.dtype != np.uint8 else torch.from_numpy(a).cuda()
+    flat = torch.full((rows * ld + off + 8,), fill, dtype=src.dtype, device="cuda")
+    view = flat[off:off + rows * ld].view(rows, ld)[:, :cols]
+    view.copy_(src)
+    return view, flat
+
+
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("M,absorb", [(4, False), (4, True), (8, True), (32, True), (2, True)])
+def test_unaligned_matrices_take_the_element_wise_kernel(dt, M, absorb, fmt):
+    # odd element offsets and pitches; without absorption also a column count that is no whole number of 16-byte pieces
+    rng = np.random.default_rng(77 + M)
+    shapes = [(37, 224 if absorb else 200, 259, 3), (5, 64, 64, 1), (130, 96 if absorb else 72, 101, 5)]
+    ws, ms, outs, keep_all = [], [], [], []
+    for k, (rows, cols, ld, off) in enumerate(shapes):
+        w = _weights(rows, cols, 8300 + 10 * M + k, dt)
+        keep = (rng.random((rows, cols)) < 0.45).astype(np.uint8)
+        keep[0, :M] = 1                      # a group with nothing pruned
+        keep[1, :M] = 0                      # and one with nothing kept
+        wd, _ = _strided_dev(w, ld, off, 7.0)
+        od, oflat = _strided_dev(np.zeros_like(w), ld, off, -3.0)
+        if fmt == tm.TMASK_MASK_U8:
+            md, _ = _strided_dev(keep, cols + 3, 1, 0)
+        else:
+            bits = np.packbits(keep, axis=1, bitorder="little")
+            md, _ = _strided_dev(bits, bits.shape[1] + 1, 1, 0)
+        ws.append((w, wd)); ms.append(md); outs.append((od, oflat, off, ld)); keep_all.append(keep)
+    tm.tmask_apply_dense([d for _, d in ws], ms, [o for o, _, _, _ in outs], M, absorb, mask_fmt=fmt)
+    torch.cuda.synchronize()
+    for (w, _), keep, (od, oflat, off, ld) in zip(ws, keep_all, outs):
+        rows, cols = w.shape
+        got, w64 = _out_f64(od), _as_f64(w)
+        if absorb:
+            _check_absorb(got, w64, keep, M, dt == "bf16")
+        else:
+            assert np.array_equal(got, oracle.apply_dense(w64, keep, M, False))
+        whole = oflat.float().cpu().numpy()
+        outside = np.ones(whole.shape, dtype=bool)
+        outside[(off + np.arange(rows)[:, None] * ld + np.arange(cols)[None, :]).ravel()] = False
+        assert (whole[outside] == -3.0).all()          # nothing outside the matrix is written
 
 
 # ---------------------------------------------------------------- Algorithm 1 + masked copy in one pass ----------

@@ -274,6 +274,24 @@ def test_score_bf16_2of4_any_nonzero_byte_is_kept_and_pruned_non_finite_stays_ou
     np.testing.assert_allclose(pb, o.per_block, rtol=1e-5, atol=1e-30)
 
 
+@pytest.mark.parametrize("dt,rows,cols", [("f32", 4100, 8200), ("bf16", 8196, 8200)])
+def test_score_of_a_large_matrix_goes_through_the_two_launch_reduction(dt, rows, cols):
+    # more than 8192 workgroup records for one matrix, next to a small one in the same call; random masks, so every
+    # counter is non-trivial
+    N, M = 2, 4
+    ws = [_inputs(dt, rows, cols, seed=3060), _inputs(dt, 8, 64, seed=3061)]
+    rng = np.random.default_rng(3062)
+    masks = [(rng.random(w.shape) < 0.5).astype(np.uint8) for w in ws]
+    scores, pbs = run_score(ws, masks, N, M)
+    for w, m, sc, pb in zip(ws, masks, scores, pbs):
+        o = oracle.score(w, m, N, M)
+        assert sc["retained_l1"] == pytest.approx(o.retained_l1, rel=1e-6)
+        assert sc["total_l1"] == pytest.approx(o.total_l1, rel=1e-6)
+        assert (sc["kept"], sc["row_violations"], sc["col_violations"], sc["row_not_n"], sc["col_not_n"]) == \
+               (o.kept, o.row_violations, o.col_violations, o.row_not_n, o.col_not_n)
+        np.testing.assert_allclose(pb, o.per_block, rtol=1e-5, atol=1e-30)
+
+
 # ---------------------------------------------------------------- error paths (host-side) ------
 
 def test_argument_errors_leave_outputs_untouched():

@@ -41,6 +41,33 @@ def test_pattern_violations_batch(dt, fmt):
     assert int(got[0]) == 0
 
 
+@pytest.mark.parametrize("fmt", [tm.TMASK_MASK_U8, tm.TMASK_MASK_BITS])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_pattern_violations_unaligned_matrices(dt, fmt):
+    # element offsets, odd pitches, and column counts that are no whole number of 16-byte pieces: counted element-wise
+    shapes = [(37, 200, 259, 3), (5, 64, 64, 1), (130, 72, 101, 5), (3, 8, 9, 1)]
+    rng = np.random.default_rng(93)
+    ws, dws, dms, masks = [], [], [], []
+    for k, (rows, cols, ld, off) in enumerate(shapes):
+        w = _sparse_weights(rows, cols, 9400 + k, dt, 0.6)
+        m = (rng.random(w.shape) < 0.5).astype(np.uint8)
+        src = to_dev(w)
+        flat = torch.full((rows * ld + off + 8,), 5.0, dtype=src.dtype, device="cuda")     # active weights all around
+        view = flat[off:off + rows * ld].view(rows, ld)[:, :cols]
+        view.copy_(src)
+        hm = m if fmt == tm.TMASK_MASK_U8 else np.packbits(m, axis=1, bitorder="little")
+        mflat = torch.zeros((rows * (hm.shape[1] + 3) + 1,), dtype=torch.uint8, device="cuda")
+        mview = mflat[1:1 + rows * (hm.shape[1] + 3)].view(rows, hm.shape[1] + 3)[:, :hm.shape[1]]
+        mview.copy_(torch.from_numpy(hm).cuda())
+        ws.append(w); masks.append(m); dws.append(view); dms.append(mview)
+    counts = torch.full((len(ws),), -1, dtype=torch.int64, device="cuda")
+    tm.tmask_pattern_violations(dws, dms, counts, mask_fmt=fmt)
+    torch.cuda.synchronize()
+    got = counts.cpu().numpy()
+    for k, (w, m) in enumerate(zip(ws, masks)):
+        assert int(got[k]) == oracle.pattern_violations(w, m), k
+
+
 def test_forcing_a_pattern_on_an_unstructured_sparse_matrix():
     """The use the paper makes of it: a matrix with 70 % zeros is forced into 4:8 and into 2:8 along rows; both
     counts equal the oracle's, and keeping fewer entries per group removes more active weights."""

@@ -54,6 +54,9 @@ def test_noalloc_matches_workspace_entry_point_two_calls_in_a_row(fmt):
     third = [wl.f32_to_bf16_bits(wl.gaussian_f32(r, c, seed=9300 + k, std=0.02)) for k, (r, c) in
              enumerate([(512, 512), (64, 136)])]
     _both(third, 4, 8, fmt)
+    # M = 32 runs on the column-per-lane kernels: one partial sum per tile of 32 rows x 64 columns
+    fourth = [wl.gaussian_f32(r, c, seed=9350 + k) for k, (r, c) in enumerate([(128, 416), (32, 32)])]
+    _both(fourth, 16, 32, fmt)
 
 
 def test_noalloc_rejects_what_does_not_fit_and_needs_no_scratch_without_objective():
