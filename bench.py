@@ -109,10 +109,16 @@ class Timer:
     def ms(self, pairs, reduce=np.median):
         return float(reduce([self.ev.elapsed_ms(a, b) for a, b in pairs]))
 
-    def measure(self, fn, reps: int, warm: int = 2):
-        """fn(k) enqueues one call.  Returns (kernel ms, whole-call ms), medians over reps, as measured."""
-        for k in range(warm):
+    def measure(self, fn, reps: int, warm_ms: float = 25.0):
+        """fn(k) enqueues one call.  Returns (kernel ms, whole-call ms), medians over reps, as measured.  Warm-up runs
+        for warm_ms of wall time: after an idle stretch (the allocations before a section) the first twenty-odd calls run
+        up to 10 % slower than the steady state."""
+        t0, k = time.perf_counter(), 0
+        while k < 4 or (time.perf_counter() - t0) * 1e3 < warm_ms:
             fn(k)
+            k += 1
+            if k % 8 == 0:
+                self.torch.cuda.synchronize()
         self.torch.cuda.synchronize()
         kp = [self.pair() for _ in range(reps)]
         for k in range(reps):
@@ -391,7 +397,7 @@ def spmm24_section(tm, torch, T, reps: int = 20, tokens: int = 8192):
     for name, vals, idx, r, c in (("forward", pk[0], pk[1], rows, cols), ("backward", pk[2], pk[3], cols, rows)):
         xs = [torch.randn((tokens, c), device="cuda").to(torch.bfloat16) for _ in range(3)]
         ys = [torch.empty((tokens, r), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
-        kms, _ = T.measure(lambda k: tm.tmask_spmm24(vals, idx, r, c, xs[k % 3], ys[k % 3]), reps, warm=3)
+        kms, _ = T.measure(lambda k: tm.tmask_spmm24(vals, idx, r, c, xs[k % 3], ys[k % 3]), reps)
         wd = torch.randn((r, c), device="cuda").to(torch.bfloat16)
         for k in range(3):
             torch.matmul(xs[k], wd.t(), out=ys[k])
@@ -548,7 +554,7 @@ def spmm_sweep(tm, torch, T, shapes, tokens, reps):
         tm.tmask_approx_pack([w], None, [pk], 2, 4)
         xs = [torch.randn((tokens, cols), device="cuda").to(torch.bfloat16) for _ in range(3)]
         ys = [torch.empty((tokens, rows), dtype=torch.bfloat16, device="cuda") for _ in range(3)]
-        kms, _ = T.measure(lambda k: tm.tmask_spmm24(pk[0], pk[1], rows, cols, xs[k % 3], ys[k % 3]), reps, warm=3)
+        kms, _ = T.measure(lambda k: tm.tmask_spmm24(pk[0], pk[1], rows, cols, xs[k % 3], ys[k % 3]), reps)
         wd = w.clone()
         pairs = [T.pair() for _ in range(reps)]
         for k in range(3):
@@ -571,7 +577,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--copies", type=int, default=3, help="distinct buffer sets rotated through (each 1.9 GB on the headline set)")
     ap.add_argument("--sections", default=",".join(ALL_SECTIONS), help="comma list of: " + ", ".join(ALL_SECTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
