@@ -101,6 +101,15 @@ __device__ __forceinline__ uint32_t quad_xor(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, ctrl, 0xF, 0xF, false);
 }
 
+// v + the value of lane (lane ^ X) within the quad.  The source lane always exists and every lane is enabled, so
+// "0 where the source is missing" never applies; written that way the move folds into the add (v_add_u32_dpp).
+template <int X>
+__device__ __forceinline__ uint32_t quad_xor_sum(uint32_t v)
+{
+    constexpr int ctrl = (X == 1) ? 0xB1 : (X == 2) ? 0x4E : 0x1B;
+    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, 0xF, 0xF, true);
+}
+
 // A wavefront-wide boolean: bit l = the predicate in lane l.  Held in a scalar register pair, so
 // logic on it is scalar-ALU work.
 typedef unsigned long long lanemask_t;

@@ -446,6 +446,9 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
 // a search and runs with every lane busy, where the searches keep 40-50 % of the lanes busy.
 //
 // Keys are (cost + price + 2^(S-1)) << 4 | row with |price| < 2^(S-1): below 2^(S+5) <= 2^32 for costs < 2^S.
+// Prices are held unshifted (the shift rides on the add that forms a key); the step times the count is a 24-bit
+// multiply-add (step < 2^23, counts <= M), the full 32-bit multiply runs at a quarter of the rate; the excess is
+// taken as half the sum of |count - K| (the counts of a block always add up to M*K), one instruction per row.
 template <int M, int CL, int G>
 __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL], uint32_t (&xcol)[CL])
 {
@@ -454,20 +457,20 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
     constexpr int ROUNDS = (M == 16) ? 20 : 10;
     constexpr int PMIN = 1, PMAX = (1 << S) - 1;                // price + 2^(S-1)
     uint32_t ck[M][CL];
-    uint32_t pk[M], best_pk[M];                                 // (price + 2^(S-1)) << 4
+    int pr[M], best_pr[M];                                      // price + 2^(S-1)
 #pragma unroll
     for (int i = 0; i < M; i++) {
-        pk[i] = (uint32_t)(1 << (S - 1)) << 4;
+        pr[i] = 1 << (S - 1);
 #pragma unroll
         for (int c = 0; c < CL; c++)
             ck[i][c] = ((uint32_t)cost[i][c] << 4) | (uint32_t)i;
     }
     // the column's threshold key under the prices p: the K pruned rows are the keys below it
-    auto threshold = [&](int c, const uint32_t (&p)[M], uint32_t (&k)[M]) {
+    auto threshold = [&](int c, const int (&p)[M], uint32_t (&k)[M]) {
         uint32_t lo[H], hi[H];
 #pragma unroll
         for (int i = 0; i < M; i++)
-            k[i] = ck[i][c] + p[i];
+            k[i] = ((uint32_t)p[i] << 4) + ck[i][c];
 #pragma unroll
         for (int i = 0; i < H; i++) {
             lo[i] = k[i];
@@ -476,7 +479,8 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
         return upper_half_min<H>(lo, hi);
     };
     int step = (M == 16) ? (4 << (S - 7)) : (3 << (S - 6));
-    uint32_t best = 0xFFFFFFFFu;
+    static_assert(((M == 16) ? (4 << (S - 7)) : (3 << (S - 6))) < (1 << 23), "the step is an operand of a 24-bit multiply");
+    uint32_t best = 0xFFFFFFFFu;                                 // twice the excess
 #pragma unroll 1
     for (int round = 0; round <= ROUNDS; round++) {
         uint32_t n[M];
@@ -486,43 +490,44 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
 #pragma unroll
         for (int c = 0; c < CL; c++) {
             uint32_t k[M];
-            const uint32_t t = threshold(c, pk, k);
+            const uint32_t t = threshold(c, pr, k);
 #pragma unroll
             for (int i = 0; i < M; i++)
                 lm_inc(n[i], lm(k[i] < t));
             if constexpr (CL > 4)
                 __builtin_amdgcn_sched_barrier(0);   // one column at a time: interleaving them costs M registers each
         }
-        uint32_t e = 0;
+        uint32_t e2 = 0;
 #pragma unroll
         for (int i = 0; i < M; i++) {
             if constexpr (G >= 2)
-                n[i] += quad_xor<1>(n[i]);
+                n[i] = quad_xor_sum<1>(n[i]);
             if constexpr (G == 4)
-                n[i] += quad_xor<2>(n[i]);
-            e += n[i] > (uint32_t)K ? n[i] - (uint32_t)K : 0u;
+                n[i] = quad_xor_sum<2>(n[i]);
+            e2 = __builtin_amdgcn_sad_u8(n[i], (uint32_t)K, e2);      // counts are below 256: |n - K| of the low byte
         }
-        const bool better = e < best;
-        best = better ? e : best;
+        const bool better = e2 < best;
+        best = better ? e2 : best;
+        const int back = step * K;
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            best_pk[i] = better ? pk[i] : best_pk[i];
-            const int p = (int)(pk[i] >> 4) + step * ((int)n[i] - K);
-            pk[i] = (uint32_t)(p > PMAX ? PMAX : p < PMIN ? PMIN : p) << 4;
+            best_pr[i] = better ? pr[i] : best_pr[i];
+            const int p = __mul24(step, (int)n[i]) + pr[i] - back;
+            pr[i] = p > PMAX ? PMAX : p < PMIN ? PMIN : p;
         }
         step = (step * (M == 16 ? 12 : 11)) >> 4;
     }
 #pragma unroll
     for (int c = 0; c < CL; c++) {
         uint32_t k[M];
-        const uint32_t t = threshold(c, best_pk, k);
+        const uint32_t t = threshold(c, best_pr, k);
         uint32_t x = 0;
 #pragma unroll
         for (int i = 0; i < M; i++)
             x |= (k[i] < t ? 1u : 0u) << i;
         xcol[c] = x;
     }
-    return best;
+    return best >> 1;
 }
 
 // Up to max_phases searches, each followed by its augmentations; cnt is kept up to date.  Returns true when
