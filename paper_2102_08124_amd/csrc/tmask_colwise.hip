@@ -9,7 +9,8 @@
 // lane j of a block holds row j, and the answer travels back as one bit word per row.  Yes/no facts about a row of
 // the block are also read off a wavefront ballot: bits [b*M, b*M + M) of ballot(flag of row i) are row i of block b.
 //
-// These kernels are bound by the vector ALU (pairwise ranks: M - 1 compares per entry and direction), not by HBM.
+// These kernels are bound by the vector ALU (M < 32: pairwise ranks, M - 1 compares per entry and direction; M = 32:
+// a threshold from two sorted halves per line of 32), not by HBM.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
@@ -17,6 +18,7 @@
 #include "../../include/tmask.h"
 #include "tmask_device.hpp"
 #include "tmask_host.hpp"
+#include "tmask_networks.hpp"
 
 namespace tmask {
 
@@ -114,7 +116,7 @@ __device__ __forceinline__ uint32_t seg_max(uint32_t v)
 }
 
 struct CwTile {
-    uint32_t br, col;
+    uint32_t br, col0, col;   // block-row, first column of the tile (both the same in every lane), the lane's column
     bool active;
 };
 
@@ -122,9 +124,33 @@ __device__ __forceinline__ CwTile cw_tile(const CwMat &md, uint32_t t)
 {
     CwTile p;
     p.br = (uint32_t)(((uint64_t)t * md.div_mul) >> md.div_shift);
-    p.col = (t - p.br * md.tpr) * 64u + threadIdx.x;
+    p.col0 = (t - p.br * md.tpr) * 64u;
+    p.col = p.col0 + threadIdx.x;
     p.active = p.col < md.cols;
     return p;
+}
+
+// The lane's column of the tile, M rows.  A row of the tile starts at an address that is the same in every lane (it
+// advances in scalar registers), the lane adds its own column: one load instruction per row and nothing else.
+template <int DT, int M>
+__device__ __forceinline__ void cw_load_column(const CwMat &md, const CwTile &p, uint32_t (&raw)[M])
+{
+    constexpr size_t ES = DT == kF32 ? 4 : 2;
+    const char *row = (const char *)md.w + ((size_t)p.br * M * md.ld + p.col0) * ES;
+    const size_t pitch = (size_t)md.ld * ES;
+#pragma unroll
+    for (int i = 0; i < M; i++)
+        raw[i] = 0u;
+    if (p.active) {
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            if constexpr (DT == kF32)
+                raw[i] = __builtin_nontemporal_load((const uint32_t *)row + threadIdx.x);
+            else
+                raw[i] = (uint32_t)__builtin_nontemporal_load((const uint16_t *)row + threadIdx.x);
+            row += pitch;
+        }
+    }
 }
 
 // ranks of M keys held by one lane under the (key, position) order: r[i] = number of keys that precede key i
@@ -144,16 +170,80 @@ __device__ __forceinline__ void cw_ranks(const uint32_t (&key)[M], uint32_t (&r)
         }
 }
 
+// Thirty-two magnitudes held by one lane: bit i of the result is set when entry i is among the first K of the
+// (magnitude, position) order, i.e. pruned.  Threshold form: the (K+1)-th smallest key comes out of two sorted halves
+// (K = 16: min over i of max(a_i, b_15-i); any other K: a bitonic merge of the halves and a select), entries below it
+// are pruned.  bf16 keys carry the position in their low bits (15 + 5 bits), so they are distinct.  fp32 magnitudes
+// are compared as they are; if the threshold value occurs on both sides of the cut, fewer than K entries lie below it
+// and the missing ones are the entries equal to it at the lowest positions (a wavefront-uniform detour).
+// 350-550 instructions against 1500 for pairwise ranks.
+template <int DT>
+__device__ __forceinline__ uint32_t cw_pruned32(const uint32_t (&mag)[32], uint32_t K)
+{
+    uint32_t k[32], a[16], b[16];
+#pragma unroll
+    for (int i = 0; i < 32; i++)
+        k[i] = DT == kF32 ? mag[i] : ((mag[i] >> 11) | (uint32_t)i);
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        a[i] = k[i];
+        b[i] = k[16 + i];
+    }
+    sort_asc<16>(a);
+    sort_asc<16>(b);
+    uint32_t t;
+    if (K == 16u) {
+        t = 0xFFFFFFFFu;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            const uint32_t m = a[i] > b[15 - i] ? a[i] : b[15 - i];
+            t = m < t ? m : t;
+        }
+    } else {
+        uint32_t s[32];
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            s[i] = a[i];
+            s[16 + i] = b[15 - i];
+        }
+        bitonic_merge_asc<32>(s);
+        t = s[__builtin_amdgcn_readfirstlane(K) & 31u];      // the same index in every lane: a relative register read
+    }
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 31; i >= 0; i--)
+        lm_shift_in(w, lm(k[i] < t));
+    if constexpr (DT == kF32) {
+        const uint32_t lt = (uint32_t)__builtin_popcount(w);
+        if (lm(lt != K) != 0) {
+            uint32_t eq = 0;
+#pragma unroll
+            for (int i = 31; i >= 0; i--)
+                lm_shift_in(eq, lm(k[i] == t));
+            uint32_t q = K - lt;
+            while (lm(q != 0u) != 0) {
+                const uint32_t low = q != 0u ? (eq & (0u - eq)) : 0u;
+                w |= low;
+                eq ^= low;
+                q -= q != 0u ? 1u : 0u;
+            }
+        }
+    }
+    return w;
+}
+
 // Writes the keep flags of the lane's column (bit i of `keep` = row i) as mask entries.
 template <int M, int FMT>
 __device__ __forceinline__ void cw_store_mask(const CwMat &md, const CwTile &p, uint32_t keep)
 {
     if constexpr (FMT == kMaskU8) {
         if (p.active) {
-            unsigned char *mb = (unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + p.col;
+            unsigned char *row = (unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + p.col0;   // same in every lane
 #pragma unroll
-            for (int i = 0; i < M; i++)
-                mb[(size_t)i * md.mask_ld] = (unsigned char)((keep >> i) & 1u);
+            for (int i = 0; i < M; i++) {
+                row[threadIdx.x] = (unsigned char)((keep >> i) & 1u);
+                row += md.mask_ld;
+            }
         }
     } else {
         // the 64 flags of a row are a ballot; lanes 0..7 each store one of its bytes (cols is a multiple of 8)
@@ -177,10 +267,12 @@ __device__ __forceinline__ uint32_t cw_load_mask(const CwMat &md, const CwTile &
     uint32_t bits = 0;
     if (p.active) {
         if constexpr (FMT == kMaskU8) {
-            const unsigned char *mb = (const unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + p.col;
+            const unsigned char *row = (const unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + p.col0;
 #pragma unroll
-            for (int i = 0; i < M; i++)
-                bits |= (mb[(size_t)i * md.mask_ld] != 0 ? 1u : 0u) << i;
+            for (int i = 0; i < M; i++) {
+                bits |= (row[threadIdx.x] != 0 ? 1u : 0u) << i;
+                row += md.mask_ld;
+            }
         } else {
             const unsigned char *mb = (const unsigned char *)md.mask + (size_t)p.br * M * md.mask_ld + (p.col >> 3);
 #pragma unroll
@@ -208,7 +300,7 @@ enum { kCwApprox = 0, kCwRow1D = 1, kCwRow1DAbsorb = 2 };
 // keep(i,j) <=> at least K entries of row i precede (i,j) and (Algorithm 1 only) at least K entries of column j do:
 // the rank form of the greedy sweep under the (magnitude, row-major index) order.
 template <int SOLVER, int DT, int M, int FMT>
-__global__ __launch_bounds__(kCwThreads) void cw_mask_kernel(const CwArgs args)
+__global__ __launch_bounds__(kCwThreads, M == 32 ? 4 : 1) void cw_mask_kernel(const CwArgs args)
 {
     constexpr int NB = 64 / M;
     __shared__ uint32_t T[NB][M][M + 1];
@@ -219,38 +311,52 @@ __global__ __launch_bounds__(kCwThreads) void cw_mask_kernel(const CwArgs args)
     double total = 0.0;
     for (uint32_t t = blockIdx.x - md.wg0; t < md.n_tiles; t += md.n_wg) {
         const CwTile p = cw_tile(md, t);
+        // M = 32: the raw column is not held across the sorts (32 registers that cost a wavefront of occupancy); the
+        // dense output, when asked for, reads it again
+        constexpr bool kHoldRaw = M < 32;
         uint32_t raw[M], key[M];
-        const size_t base = (size_t)p.br * M * md.ld + p.col;
+        cw_load_column<DT, M>(md, p, key);
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            raw[i] = p.active ? cw_load<DT>(md.w, base + (size_t)i * md.ld) : 0u;
-            key[i] = cw_key<DT>(raw[i]);
+            if constexpr (kHoldRaw)
+                raw[i] = key[i];
+            key[i] = cw_key<DT>(key[i]);
         }
-        uint32_t keep = seg_mask<M>();
-        if constexpr (SOLVER == kCwApprox) {
-            uint32_t r[M];
-            cw_ranks<M>(key, r);
-            keep = 0;
-#pragma unroll
-            for (int i = 0; i < M; i++)
-                keep |= (r[i] >= K ? 1u : 0u) << i;
-        }
-        // rows: lane j of the block takes row j
+        // rows: lane j of the block takes row j.  The magnitudes go to the transposition buffer first; the column pass
+        // below is then their last use in registers
         __syncthreads();                                  // the previous tile's readers are done
 #pragma unroll
         for (int i = 0; i < M; i++)
             T[blk][i][j] = key[i];
+        uint32_t keep = seg_mask<M>();
+        if constexpr (SOLVER == kCwApprox) {
+            if constexpr (M == 32) {
+                keep = ~cw_pruned32<DT>(key, K);
+            } else {
+                uint32_t r[M];
+                cw_ranks<M>(key, r);
+                keep = 0;
+#pragma unroll
+                for (int i = 0; i < M; i++)
+                    keep |= (r[i] >= K ? 1u : 0u) << i;
+            }
+        }
         __syncthreads();
         {
-            uint32_t rk[M], r[M];
+            uint32_t rk[M];
 #pragma unroll
             for (int c = 0; c < M; c++)
                 rk[c] = T[blk][j][c];
-            cw_ranks<M>(rk, r);
             uint32_t rowkeep = 0;
+            if constexpr (M == 32) {
+                rowkeep = ~cw_pruned32<DT>(rk, K);
+            } else {
+                uint32_t r[M];
+                cw_ranks<M>(rk, r);
 #pragma unroll
-            for (int c = 0; c < M; c++)
-                rowkeep |= (r[c] >= K ? 1u : 0u) << c;
+                for (int c = 0; c < M; c++)
+                    rowkeep |= (r[c] >= K ? 1u : 0u) << c;
+            }
             RK[blk][j] = rowkeep;
         }
         __syncthreads();
@@ -263,12 +369,19 @@ __global__ __launch_bounds__(kCwThreads) void cw_mask_kernel(const CwArgs args)
             cw_store_mask<M, FMT>(md, p, keep);
         float acc = 0.f;
 #pragma unroll
-        for (int i = 0; i < M; i++)
-            acc += ((keep >> i) & 1u) ? __uint_as_float(key[i]) : 0.f;
+        for (int i = 0; i < M; i++) {
+            // M = 32: the lane's magnitudes come back from the transposition buffer (its own writes), so that they hold
+            // no registers while the rows are sorted
+            const uint32_t mag = M == 32 ? T[blk][i][j] : key[i];
+            acc += ((keep >> i) & 1u) ? __uint_as_float(mag) : 0.f;
+        }
         total += (double)wave_sum(acc);
         if (md.aux) {
             // dense masked copy; with absorption the mean of a row group's pruned weights goes to its kept ones
-            const size_t ob = (size_t)p.br * M * md.ld_aux + p.col;
+            constexpr size_t ES = DT == kF32 ? 4 : 2;
+            if constexpr (!kHoldRaw)
+                cw_load_column<DT, M>(md, p, raw);        // every entry is read and written by the same lane: in place is fine
+            char *orow = (char *)md.aux + ((size_t)p.br * M * md.ld_aux + p.col0) * ES;      // same in every lane
 #pragma unroll
             for (int i = 0; i < M; i++) {
                 const bool k = (keep >> i) & 1u;
@@ -281,8 +394,13 @@ __global__ __launch_bounds__(kCwThreads) void cw_mask_kernel(const CwArgs args)
                     const float res = k ? v + mean : 0.f;
                     o = DT == kF32 ? __float_as_uint(res) : f32_to_bf16_rne(res);
                 }
-                if (p.active)
-                    cw_store<DT>(md.aux, ob + (size_t)i * md.ld_aux, o);
+                if (p.active) {
+                    if constexpr (DT == kF32)
+                        ((uint32_t *)orow)[threadIdx.x] = o;
+                    else
+                        ((uint16_t *)orow)[threadIdx.x] = (uint16_t)o;
+                }
+                orow += (size_t)md.ld_aux * ES;
             }
         }
     }
@@ -310,7 +428,7 @@ constexpr uint32_t kCwNone = 0xFFu;
 constexpr int cw_cost_bits(int M) { return M == 32 ? 25 : M == 16 ? 26 : 27; }
 
 template <int DT, int M, int FMT>
-__global__ __launch_bounds__(kCwThreads) void cw_exact_kernel(const CwArgs args)
+__global__ __launch_bounds__(kCwThreads, M == 32 ? 3 : 1) void cw_exact_kernel(const CwArgs args)
 {
     constexpr int NB = 64 / M;
     constexpr int S = cw_cost_bits(M);
@@ -325,10 +443,10 @@ __global__ __launch_bounds__(kCwThreads) void cw_exact_kernel(const CwArgs args)
     for (uint32_t t = blockIdx.x - md.wg0; t < md.n_tiles; t += md.n_wg) {
         const CwTile p = cw_tile(md, t);
         uint32_t key[M];
-        const size_t base = (size_t)p.br * M * md.ld + p.col;
+        cw_load_column<DT, M>(md, p, key);
 #pragma unroll
         for (int i = 0; i < M; i++)
-            key[i] = cw_key<DT>(p.active ? cw_load<DT>(md.w, base + (size_t)i * md.ld) : 0u);
+            key[i] = cw_key<DT>(key[i]);
         // ---- integer costs, by column (ccol) and, through LDS, by row (crow) ----
         uint32_t kmax = 0;
 #pragma unroll
@@ -472,12 +590,13 @@ __global__ __launch_bounds__(kCwThreads) void cw_score_kernel(const CwArgs args)
     unsigned long long kept = 0, rowv = 0, colv = 0, rowne = 0, colne = 0;
     for (uint32_t t = blockIdx.x - md.wg0; t < md.n_tiles; t += md.n_wg) {
         const CwTile p = cw_tile(md, t);
-        const size_t base = (size_t)p.br * M * md.ld + p.col;
         const uint32_t bits = cw_load_mask<M, FMT>(md, p);
+        uint32_t raw[M];
+        cw_load_column<DT, M>(md, p, raw);
         float ret = 0.f, tot = 0.f;
 #pragma unroll
         for (int i = 0; i < M; i++) {
-            const float v = __uint_as_float(cw_key<DT>(p.active ? cw_load<DT>(md.w, base + (size_t)i * md.ld) : 0u));
+            const float v = __uint_as_float(cw_key<DT>(raw[i]));
             tot += v;
             ret += ((bits >> i) & 1u) ? v : 0.f;
         }

@@ -129,6 +129,13 @@ __device__ __forceinline__ void lm_inc(uint32_t &r, lanemask_t m)
     asm("v_addc_co_u32_e64 %0, %1, 0, %0, %2" : "+v"(r), "=s"(carry_out) : "s"(m));
 }
 
+// r = 2 r + (1 in the lanes whose bit is set in m): shifts a flag into a bit word, one add-with-carry-in.
+__device__ __forceinline__ void lm_shift_in(uint32_t &r, lanemask_t m)
+{
+    lanemask_t carry_out;
+    asm("v_addc_co_u32_e64 %0, %1, %0, %0, %2" : "+v"(r), "=s"(carry_out) : "s"(m));
+}
+
 // Wavefront sums by DPP, in a fixed order (deterministic): quad, then the four quads of a row of 16
 // lanes by row rotation, then the four rows through scalar reads.  All 64 lanes must be active.
 // The result is uniform.

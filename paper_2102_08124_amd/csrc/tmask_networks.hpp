@@ -38,6 +38,66 @@ __device__ __forceinline__ void sort_asc<8>(uint32_t (&v)[8])
     cmpx(v[1], v[2]); cmpx(v[3], v[4]); cmpx(v[5], v[6]);
 }
 
+// Sixteen keys: Batcher's odd-even merge sort, 63 compare-exchanges.  The comparator list is worked out at compile
+// time and expanded with static indices, so the keys stay in registers.
+struct OddEvenNet16 {
+    int n;
+    int a[64], b[64];
+};
+
+constexpr OddEvenNet16 make_odd_even_net16()
+{
+    OddEvenNet16 net{};
+    constexpr int N = 16;
+    for (int p = 1; p < N; p *= 2)
+        for (int k = p; k >= 1; k /= 2)
+            for (int j = k % p; j <= N - 1 - k; j += 2 * k)
+                for (int i = 0; i <= (k - 1 < N - j - k - 1 ? k - 1 : N - j - k - 1); i++)
+                    if ((i + j) / (2 * p) == (i + j + k) / (2 * p)) {
+                        net.a[net.n] = i + j;
+                        net.b[net.n] = i + j + k;
+                        net.n++;
+                    }
+    return net;
+}
+
+template <int... I>
+struct IntSeq {};
+template <int N, int... I>
+struct MakeIntSeq : MakeIntSeq<N - 1, N - 1, I...> {};
+template <int... I>
+struct MakeIntSeq<0, I...> {
+    typedef IntSeq<I...> type;
+};
+
+template <int... I>
+__device__ __forceinline__ void sort16_apply(uint32_t (&v)[16], IntSeq<I...>)
+{
+    constexpr OddEvenNet16 net = make_odd_even_net16();
+    (cmpx(v[net.a[I]], v[net.b[I]]), ...);
+}
+
+template <>
+__device__ __forceinline__ void sort_asc<16>(uint32_t (&v)[16])
+{
+    constexpr OddEvenNet16 net = make_odd_even_net16();
+    static_assert(net.n == 63, "odd-even merge sort of 16 keys");
+    sort16_apply(v, typename MakeIntSeq<net.n>::type());
+}
+
+// v[0..N/2) ascending followed by v[N/2..N) descending (a bitonic sequence) -> all of v ascending: log2 N rounds of
+// N/2 compare-exchanges at distance N/2, N/4, ..., 1
+template <int N>
+__device__ __forceinline__ void bitonic_merge_asc(uint32_t (&v)[N])
+{
+#pragma unroll
+    for (int k = N / 2; k >= 1; k /= 2)
+#pragma unroll
+        for (int i = 0; i < N; i++)
+            if ((i & k) == 0)
+                cmpx(v[i], v[i + k]);
+}
+
 // (H)-th largest of the 2H distinct keys lo[0..H) u hi[0..H): both halves get sorted in place.
 template <int H>
 __device__ __forceinline__ uint32_t upper_half_min(uint32_t (&a)[H], uint32_t (&b)[H])
