@@ -627,9 +627,13 @@ __global__ __launch_bounds__(kCwThreads) void cw_score_kernel(const CwArgs args)
 }
 
 // =====================================================================================================================
-// Apply + pack, one thread per group of M, two passes in one launch: groups along rows (vals, idx), then groups down
-// columns (valsT, idxT).  A workgroup takes 32 lines x 8 consecutive groups, so that the position bits it assembles
-// in LDS are whole bytes (8 * N * log2(M) bits) wherever the line does not end.
+// Apply + pack, two passes in one launch: groups along rows (vals, idx), then groups down columns (valsT, idxT).
+// A workgroup takes 32 lines x 8 consecutive groups (so the position bits it assembles are whole bytes, 8 * N * log2 M
+// bits, wherever the line does not end): the weights and keep flags of that piece are loaded with neighbouring lanes on
+// neighbouring addresses and staged in LDS, one thread per group then compacts its group in place (slot s never lies
+// behind position s), and the compacted values leave as one contiguous run per line.  The LDS pitches are chosen per
+// pass so that the threads of a wavefront (8 lines x 8 groups in the row pass, 32 lines x 2 groups in the column pass)
+// fall into different banks.
 // =====================================================================================================================
 
 constexpr int kCwPackThreads = 256;
@@ -653,93 +657,177 @@ struct CwLog2 {
     static constexpr int v = (M == 4) ? 2 : (M == 8) ? 3 : (M == 16) ? 4 : 5;
 };
 
+// where a piece lies: matrix, pass and position (all the same in every thread of the workgroup)
+struct CwPiece {
+    const void *w;
+    const unsigned char *mask;
+    void *vals;              // vals / valsT of the pass
+    unsigned char *idx;      // idx / idxT of the pass
+    uint32_t ld, mask_ld;
+    uint32_t n_lines, gpl;   // lines of the pass, groups per line
+    uint32_t lb, ch;         // block of 32 lines, chunk of 8 groups
+    uint32_t g_here;         // groups in this chunk (the last chunk of a line may be short)
+    bool transposed;
+};
+
+template <int M>
+__device__ __forceinline__ CwPiece cw_piece(const CwPackArgs &args, uint32_t piece)
+{
+    int lo = 0, hi = (int)args.n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.d[mid].wg0 <= piece)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    const CwPack &d = args.d[lo];
+    CwPiece p;
+    uint32_t wg = piece - d.wg0;
+    p.transposed = wg >= d.row_wgs;
+    if (p.transposed)
+        wg -= d.row_wgs;
+    // the pass's view: n_lines lines of gpl groups; element q of group g of line L is W[L][g*M + q] (row pass) or
+    // W[g*M + q][L] (column pass)
+    p.w = d.w; p.mask = (const unsigned char *)d.mask; p.ld = d.ld; p.mask_ld = d.mask_ld;
+    p.vals = p.transposed ? d.valsT : d.vals;
+    p.idx = (unsigned char *)(p.transposed ? d.idxT : d.idx);
+    p.n_lines = p.transposed ? d.cols : d.rows;
+    p.gpl = (p.transposed ? d.rows : d.cols) / M;
+    const uint32_t chunks = (p.gpl + 7u) / 8u;
+    p.lb = wg / chunks;
+    p.ch = wg - p.lb * chunks;
+    p.g_here = min(8u, p.gpl - p.ch * 8u);
+    return p;
+}
+
+// One workgroup per piece.  (Persistent workgroups that load their next piece into registers while they compact the
+// current one were slower, 322 against 262 us on 8192^2 fp32 16:32: all workgroups then load at the same moments.)
 template <int DT, int M, int FMT>
 __global__ __launch_bounds__(kCwPackThreads) void cw_pack_kernel(const CwPackArgs args)
 {
     constexpr int IB = CwLog2<M>::v;
     constexpr int WORDS = (8 * (M - 1) * IB + 31) / 32 + 2;
+    constexpr uint32_t GP = M + 1;                       // words per group in LDS (one of padding)
+    constexpr uint32_t PITCH_ROW = ((8 * GP + 55) / 64) * 64 + 8;   // = 8 (mod 64), >= 8 * GP
+    constexpr uint32_t PITCH_COL = PITCH_ROW + 1;                   // odd
+    constexpr uint32_t KP = 8 * M + 4;                   // bytes of keep flags per line
+    constexpr uint32_t EPL = 8u * M;                     // elements per line of a full piece
+    constexpr uint32_t STEPS = 32u * EPL / kCwPackThreads;
+    __shared__ uint32_t WT[32 * PITCH_COL];
+    __shared__ uint32_t KF[32 * KP / 4];
     __shared__ uint32_t IDX[32][WORDS];
-    int lo = 0, hi = (int)args.n - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (args.d[mid].wg0 <= blockIdx.x)
-            lo = mid;
-        else
-            hi = mid - 1;
-    }
-    const CwPack d = args.d[lo];
     const uint32_t N = args.N;
-    uint32_t wg = blockIdx.x - d.wg0;
-    const bool transposed = wg >= d.row_wgs;
-    if (transposed)
-        wg -= d.row_wgs;
-    // the pass's view: n_lines lines of gpl groups; element q of group g of line L is W[L][g*M + q] (row pass) or
-    // W[g*M + q][L] (column pass)
-    const uint32_t n_lines = transposed ? d.cols : d.rows;
-    const uint32_t gpl = (transposed ? d.rows : d.cols) / M;
-    const uint32_t chunks = (gpl + 7u) / 8u;
-    const uint32_t lb = wg / chunks, ch = wg - lb * chunks;
     const uint32_t tid = threadIdx.x;
-    // row pass: eight neighbouring threads take eight neighbouring groups of a row; column pass: 32 neighbouring
-    // threads take 32 neighbouring columns (their loads fall into the same rows of W)
-    const uint32_t ll = transposed ? (tid & 31u) : (tid >> 3);
-    const uint32_t gl = transposed ? (tid >> 5) : (tid & 7u);
-    const uint32_t line = lb * 32u + ll, g = ch * 8u + gl;
-    for (uint32_t k = tid; k < 32u * WORDS; k += kCwPackThreads)
-        (&IDX[0][0])[k] = 0;
-    __syncthreads();
-    void *vals = transposed ? d.valsT : d.vals;
-    unsigned char *idx = (unsigned char *)(transposed ? d.idxT : d.idx);
-    if (line < n_lines && g < gpl) {
-        uint32_t v[M], kb = 0;
+    unsigned char *kf = (unsigned char *)KF;
+    uint32_t v[STEPS], f[STEPS];
+
+    // All of a thread's loads of a piece are issued back to back (up to 32 of each kind); entries outside the matrix
+    // read element (0, 0) and are dropped when the piece is staged.
+    // row pass: neighbouring lanes = neighbouring elements of a line; column pass: neighbouring lines (columns)
+    auto issue_loads = [&](const CwPiece &p) __attribute__((always_inline)) {
+        const uint32_t e_here = p.g_here * M;
 #pragma unroll
-        for (int q = 0; q < M; q++) {
-            const uint32_t r = transposed ? g * M + q : line, c = transposed ? line : g * M + q;
-            v[q] = cw_load<DT>(d.w, (size_t)r * d.ld + c);
-            uint32_t f;
+        for (uint32_t b = 0; b < STEPS; b++) {
+            const uint32_t k = tid + b * kCwPackThreads;
+            const uint32_t l = p.transposed ? (k & 31u) : (k / EPL);
+            const uint32_t e = p.transposed ? (k >> 5) : (k % EPL);
+            const uint32_t line = p.lb * 32u + l;
+            const bool in = line < p.n_lines && e < e_here;
+            const uint32_t along = p.ch * EPL + e;
+            const uint32_t r = in ? (p.transposed ? along : line) : 0u, c = in ? (p.transposed ? line : along) : 0u;
+            v[b] = cw_load<DT>(p.w, (size_t)r * p.ld + c);
             if constexpr (FMT == kMaskU8)
-                f = ((const unsigned char *)d.mask)[(size_t)r * d.mask_ld + c] != 0 ? 1u : 0u;
+                f[b] = (uint32_t)p.mask[(size_t)r * p.mask_ld + c];
             else
-                f = (((const unsigned char *)d.mask)[(size_t)r * d.mask_ld + (c >> 3)] >> (c & 7u)) & 1u;
-            kb |= f << q;
+                f[b] = ((uint32_t)p.mask[(size_t)r * p.mask_ld + (c >> 3)] >> (c & 7u)) & 1u;
         }
-        // slots: the kept positions in order (the first N if the mask keeps more), then the lowest other positions
-        uint32_t sel = kb, cnt = (uint32_t)__builtin_popcount(kb);
-        while (cnt > N) {
-            sel &= ~(0x80000000u >> __builtin_clz(sel));
-            cnt--;
-        }
-        uint32_t z = ~sel & seg_mask<M>(), chosen = sel;
-        for (uint32_t need = N - cnt; need > 0; need--) {
-            const uint32_t low = z & (0u - z);
-            chosen |= low;
-            z ^= low;
-        }
-        const size_t pitch = (size_t)gpl * N;
-        const size_t o = (size_t)line * pitch + (size_t)g * N;
-        uint32_t sl = 0;
+    };
+
+    const CwPiece p = cw_piece<M>(args, blockIdx.x);
+    issue_loads(p);
+    {
+        const uint32_t pitch = p.transposed ? PITCH_COL : PITCH_ROW;
+        const uint32_t e_here = p.g_here * M;
+        for (uint32_t k = tid; k < 32u * WORDS; k += kCwPackThreads)
+            (&IDX[0][0])[k] = 0;
+        // ---- stage the piece: weights as words, keep flags as bytes (0 / 1) ----
 #pragma unroll
-        for (int q = 0; q < M; q++) {
-            if ((chosen >> q) & 1u) {
-                cw_store<DT>(vals, o + sl, ((sel >> q) & 1u) ? v[q] : 0u);
-                const uint32_t off = (gl * N + sl) * IB;
-                const unsigned long long code = (unsigned long long)q << (off & 31u);
-                atomicOr(&IDX[ll][off >> 5], (uint32_t)code);
-                if ((uint32_t)(code >> 32))
-                    atomicOr(&IDX[ll][(off >> 5) + 1], (uint32_t)(code >> 32));
-                sl++;
+        for (uint32_t b = 0; b < STEPS; b++) {
+            const uint32_t k = tid + b * kCwPackThreads;
+            const uint32_t l = p.transposed ? (k & 31u) : (k / EPL);
+            const uint32_t e = p.transposed ? (k >> 5) : (k % EPL);
+            if (p.lb * 32u + l < p.n_lines && e < e_here) {
+                WT[l * pitch + (e / M) * GP + (e % M)] = v[b];
+                kf[l * KP + e] = (unsigned char)(f[b] != 0u ? 1u : 0u);
             }
         }
-    }
-    __syncthreads();
-    // the chunk's position bits start on a byte boundary of the line: 8 groups * N * IB bits = N * IB bytes
-    const size_t pitch_b = ((size_t)gpl * N * IB + 7) / 8;
-    const uint32_t g_here = min(8u, gpl - min(gpl, ch * 8u));
-    const uint32_t nbytes = (g_here * N * IB + 7u) / 8u;
-    for (uint32_t k = tid; k < 32u * nbytes; k += kCwPackThreads) {
-        const uint32_t l2 = k / nbytes, x = k - l2 * nbytes;
-        if (lb * 32u + l2 < n_lines)
-            idx[(size_t)(lb * 32u + l2) * pitch_b + (size_t)ch * N * IB + x] = ((const unsigned char *)&IDX[l2][0])[x];
+        __syncthreads();
+        // ---- one thread per group: slots, compaction in place, position codes ----
+        // row pass: eight neighbouring threads take eight neighbouring groups of a line; column pass: 32 neighbouring
+        // threads take 32 neighbouring lines
+        const uint32_t ll = p.transposed ? (tid & 31u) : (tid >> 3);
+        const uint32_t gl = p.transposed ? (tid >> 5) : (tid & 7u);
+        if (p.lb * 32u + ll < p.n_lines && gl < p.g_here) {
+            uint32_t kb = 0;
+#pragma unroll
+            for (int q4 = 0; q4 < M / 4; q4++) {
+                const uint32_t f4 = KF[(ll * KP + gl * M) / 4 + q4];          // four flag bytes, each 0 or 1
+                kb |= ((f4 * 0x01020408u) >> 24) << (4 * q4);
+            }
+            // slots: the kept positions in order (the first N if the mask keeps more), then the lowest other positions
+            uint32_t sel = kb, cnt = (uint32_t)__builtin_popcount(kb);
+            while (cnt > N) {
+                sel &= ~(0x80000000u >> __builtin_clz(sel));
+                cnt--;
+            }
+            uint32_t z = ~sel & seg_mask<M>(), chosen = sel;
+            for (uint32_t need = N - cnt; need > 0; need--) {
+                const uint32_t low = z & (0u - z);
+                chosen |= low;
+                z ^= low;
+            }
+            uint32_t *grp = &WT[ll * pitch + gl * GP];
+            uint32_t gv[M];
+#pragma unroll
+            for (int q = 0; q < M; q++)
+                gv[q] = grp[q];
+            uint32_t sl = 0;
+#pragma unroll
+            for (int q = 0; q < M; q++) {
+                if ((chosen >> q) & 1u) {
+                    grp[sl] = ((sel >> q) & 1u) ? gv[q] : 0u;                  // the group is compacted in place
+                    const uint32_t off = (gl * N + sl) * IB;
+                    const unsigned long long code = (unsigned long long)q << (off & 31u);
+                    atomicOr(&IDX[ll][off >> 5], (uint32_t)code);
+                    if ((uint32_t)(code >> 32))
+                        atomicOr(&IDX[ll][(off >> 5) + 1], (uint32_t)(code >> 32));
+                    sl++;
+                }
+            }
+        }
+        __syncthreads();
+        // ---- copy-out: per line one run of g_here * N values and one of position bytes ----
+        const size_t vpitch = (size_t)p.gpl * N;
+        const uint32_t run = p.g_here * N;
+        const float inv_n = 1.0f / (float)N;
+        for (uint32_t l = tid >> 6; l < 32u; l += kCwPackThreads / 64) {
+            if (p.lb * 32u + l >= p.n_lines)
+                break;
+            const size_t o = (size_t)(p.lb * 32u + l) * vpitch + (size_t)p.ch * 8u * N;
+            for (uint32_t x = tid & 63u; x < run; x += 64u) {
+                const uint32_t g = (uint32_t)(((float)x + 0.5f) * inv_n);     // x / N, exact for x < 256, N < 32
+                cw_store<DT>(p.vals, o + x, WT[l * pitch + g * GP + (x - g * N)]);
+            }
+        }
+        // the chunk's position bits start on a byte boundary of the line: 8 groups * N * IB bits = N * IB bytes
+        const size_t pitch_b = ((size_t)p.gpl * N * IB + 7) / 8;
+        const uint32_t nbytes = (p.g_here * N * IB + 7u) / 8u;
+        for (uint32_t k = tid; k < 32u * nbytes; k += kCwPackThreads) {
+            const uint32_t l2 = k / nbytes, x = k - l2 * nbytes;
+            if (p.lb * 32u + l2 < p.n_lines)
+                p.idx[(size_t)(p.lb * 32u + l2) * pitch_b + (size_t)p.ch * N * IB + x] = ((const unsigned char *)&IDX[l2][0])[x];
+        }
     }
 }
 
