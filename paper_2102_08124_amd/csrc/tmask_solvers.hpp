@@ -438,7 +438,7 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
 // cost + price means being cheapest under cost alone.  That is all the augmenting searches ask of their
 // start, so prices can even out the row counts before the first search: a row with too many pruned entries
 // becomes dearer to prune, one with too few cheaper, every column chooses again, in rounds with a shrinking
-// step: at M = 8 ten rounds, first step 3/64 .. 3/32 of the largest cost, times 11/16 per round; at M = 16
+// step: at M = 8 twelve rounds, first step 3/64 .. 3/32 of the largest cost, times 11/16 per round; at M = 16
 // twenty rounds, first step 1/32 .. 1/16 of the largest cost, times 3/4 per round (both settled by timing on
 // the device).  The prices of the round with the smallest total excess are kept; xcol is that round's choice
 // and the return value its excess.  On random blocks the searches that follow drop from 3.1 per block (no
@@ -454,7 +454,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
 {
     constexpr int K = M / 2, H = M / 2;
     constexpr int S = exact_cost_bits(M);
-    constexpr int ROUNDS = (M == 16) ? 20 : 10;
+    constexpr int ROUNDS = (M == 16) ? 20 : 12;
     constexpr int PMIN = 1, PMAX = (1 << S) - 1;                // price + 2^(S-1)
     uint32_t ck[M][CL];
     int pr[M], best_pr[M];                                      // price + 2^(S-1)
