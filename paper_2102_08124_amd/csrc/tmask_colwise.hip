@@ -177,13 +177,10 @@ __device__ __forceinline__ void cw_ranks(const uint32_t (&key)[M], uint32_t (&r)
 // are compared as they are; if the threshold value occurs on both sides of the cut, fewer than K entries lie below it
 // and the missing ones are the entries equal to it at the lowest positions (a wavefront-uniform detour).
 // 350-550 instructions against 1500 for pairwise ranks.
-template <int DT>
-__device__ __forceinline__ uint32_t cw_pruned32(const uint32_t (&mag)[32], uint32_t K)
+// the (K+1)-th smallest of 32 keys (1 <= K <= 31; the keys may repeat)
+__device__ __forceinline__ uint32_t cw_threshold32(const uint32_t (&k)[32], uint32_t K)
 {
-    uint32_t k[32], a[16], b[16];
-#pragma unroll
-    for (int i = 0; i < 32; i++)
-        k[i] = DT == kF32 ? mag[i] : ((mag[i] >> 11) | (uint32_t)i);
+    uint32_t a[16], b[16];
 #pragma unroll
     for (int i = 0; i < 16; i++) {
         a[i] = k[i];
@@ -209,6 +206,17 @@ __device__ __forceinline__ uint32_t cw_pruned32(const uint32_t (&mag)[32], uint3
         bitonic_merge_asc<32>(s);
         t = s[__builtin_amdgcn_readfirstlane(K) & 31u];      // the same index in every lane: a relative register read
     }
+    return t;
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t cw_pruned32(const uint32_t (&mag)[32], uint32_t K)
+{
+    uint32_t k[32];
+#pragma unroll
+    for (int i = 0; i < 32; i++)
+        k[i] = DT == kF32 ? mag[i] : ((mag[i] >> 11) | (uint32_t)i);
+    const uint32_t t = cw_threshold32(k, K);
     uint32_t w = 0;
 #pragma unroll
     for (int i = 31; i >= 0; i--)
@@ -230,6 +238,28 @@ __device__ __forceinline__ uint32_t cw_pruned32(const uint32_t (&mag)[32], uint3
         }
     }
     return w;
+}
+
+// A 32 x 32 bit matrix held as one word per lane by the 32 lanes of a block (lane l, bit i) -> its transpose (lane i,
+// bit l): five rounds of swapping the off-diagonal quarters at sizes 16, 8, 4, 2, 1 with the lane 16, 8, ... away.
+__device__ __forceinline__ uint32_t cw_transpose32(uint32_t w)
+{
+#pragma unroll
+    for (int s = 16; s >= 1; s >>= 1) {
+        const uint32_t m = s == 16 ? 0x0000FFFFu : s == 8 ? 0x00FF00FFu : s == 4 ? 0x0F0F0F0Fu : s == 2 ? 0x33333333u : 0x55555555u;
+        const uint32_t o = (uint32_t)__shfl_xor((int)w, s, 64);
+        w = (threadIdx.x & (uint32_t)s) ? ((w & ~m) | ((o >> s) & m)) : ((w & m) | ((o << s) & ~m));
+    }
+    return w;
+}
+
+template <int M>
+__device__ __forceinline__ uint32_t seg_sum_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = M / 2; off >= 1; off >>= 1)
+        v += (uint32_t)__shfl_xor((int)v, off, 64);
+    return v;
 }
 
 // Writes the keep flags of the lane's column (bit i of `keep` = row i) as mask entries.
@@ -436,6 +466,7 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 3 : 1) void cw_exact_kernel(c
     __shared__ uint32_t T[NB][M][M + 1];
     __shared__ int DROW[NB][M], DCOL[NB][M];
     __shared__ uint32_t PROW[NB][M], PCOL[NB][M];
+    __shared__ uint32_t PK[NB][M];
     const CwMat md = args.m[cw_find(args, blockIdx.x)];
     const uint32_t lane = threadIdx.x, blk = lane / M, j = lane % M;
     const uint32_t K = args.K;
@@ -467,12 +498,51 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 3 : 1) void cw_exact_kernel(c
         for (int i = 0; i < M; i++)
             T[blk][i][j] = (uint32_t)ccol[i];
         __syncthreads();
-#pragma unroll
-        for (int c = 0; c < M; c++)
-            crow[c] = (int)T[blk][j][c];
-        // ---- start: the K lightest rows of the lane's column (ties: lower row first) ----
         uint32_t xcol = 0, xrow = 0;       // bit i of xcol: (i, j) pruned; bit c of xrow: (j, c) pruned
-        {
+        if constexpr (M == 32) {
+            // ---- start under row prices: column j prunes the K rows with the smallest cost + price.  Whatever the
+            // prices, that is the cheapest pruning for the row counts it has, which is all the searches below ask of
+            // their start; the prices are moved against the imbalance (price_i += step * (count_i - K), the step
+            // shrinking by 12/16 per round from 1/64 of the largest cost, 16 rounds: more rounds leave fewer
+            // searches but cost more than those, measured) and the round with the least excess is kept.  Lane j owns the price of row j; the prices travel through LDS, the counts come from the
+            // transposed flag words.  On random blocks the excess left falls from 36 to about 0.5 per block.  Keys: (cost + price) << 5 | row < 2^31.
+            constexpr int ROUNDS = 16;
+            int pr = 1 << (S - 1), best_pr = pr;
+            uint32_t best = 0xFFFFFFFFu;
+            int step = 1 << (S - 6);
+            for (int round = 0; round <= ROUNDS + 1; round++) {
+                const bool last = round == ROUNDS + 1;        // the kept prices once more, for their flags
+                __syncthreads();
+                PK[blk][j] = ((uint32_t)(last ? best_pr : pr) << 5) | j;
+                __syncthreads();
+                uint32_t k[M];
+#pragma unroll
+                for (int i = 0; i < M; i++)
+                    k[i] = ((uint32_t)ccol[i] << 5) + PK[blk][i];
+                const uint32_t t = cw_threshold32(k, K);
+                uint32_t w = 0;
+#pragma unroll
+                for (int i = M - 1; i >= 0; i--)
+                    lm_shift_in(w, lm(k[i] < t));
+                const uint32_t wr = cw_transpose32(w);
+                xcol = w;
+                xrow = wr;
+                if (last)
+                    break;
+                const uint32_t n = (uint32_t)__builtin_popcount(wr);
+                uint32_t e = seg_sum_u32<M>(n > K ? n - K : 0u);
+                e = p.active ? e : 0u;
+                const bool better = e < best;
+                best = better ? e : best;
+                best_pr = better ? pr : best_pr;
+                if (!__any(best != 0u))
+                    break;                                   // both blocks balanced: this round's flags are the start
+                const int q = pr + step * ((int)n - (int)K);
+                pr = q < 1 ? 1 : q > (1 << S) - 1 ? (1 << S) - 1 : q;
+                step = (step * 12) >> 4;
+            }
+        } else {
+            // ---- start: the K lightest rows of the lane's column (ties: lower row first) ----
             uint32_t ck[M], r[M];
 #pragma unroll
             for (int i = 0; i < M; i++)
@@ -481,12 +551,15 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 3 : 1) void cw_exact_kernel(c
 #pragma unroll
             for (int i = 0; i < M; i++)
                 xcol |= (r[i] < K ? 1u : 0u) << i;
+#pragma unroll
+            for (int i = 0; i < M; i++) {
+                const uint32_t rowbits = seg_of<M>(lm((xcol >> i) & 1u), blk);
+                xrow = (j == (uint32_t)i) ? rowbits : xrow;
+            }
         }
 #pragma unroll
-        for (int i = 0; i < M; i++) {
-            const uint32_t rowbits = seg_of<M>(lm((xcol >> i) & 1u), blk);
-            xrow = (j == (uint32_t)i) ? rowbits : xrow;
-        }
+        for (int c = 0; c < M; c++)
+            crow[c] = (int)T[blk][j][c];
         // a block outside the matrix takes no part: it counts as balanced
         uint32_t cnt = p.active ? (uint32_t)__builtin_popcount(xrow) : K;
 
@@ -566,6 +639,13 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 3 : 1) void cw_exact_kernel(c
         }
         const uint32_t keep = ~xcol & seg_mask<M>();
         cw_store_mask<M, FMT>(md, p, keep);
+        if constexpr (M == 32) {
+            // the magnitudes are read again for the objective: they hold no registers during the solve
+            cw_load_column<DT, M>(md, p, key);
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                key[i] = cw_key<DT>(key[i]);
+        }
         float acc = 0.f;
 #pragma unroll
         for (int i = 0; i < M; i++)
