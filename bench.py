@@ -495,7 +495,8 @@ def cpu_baseline_section(mats_np, N, M, min_s: float = 10.0, many_s: float = 6.0
 
 
 def square_sweep(tm, torch, T, side, calls, dts, ms, fmt, reps):
-    """One square matrix, chosen calls, dtype x N:M (N = M/2): kernel and whole-call event times, as measured."""
+    """One square matrix, chosen calls, dtype x N:M (entries of ms: M, meaning N = M/2, or (N, M)): kernel and whole-call
+    event times, as measured."""
     out = {"side": side, "mask_format": "bits" if fmt else "u8", "marker_overhead_ms": T.marker_ms, "rows": []}
     for dt in dts:
         nb = 3
@@ -504,7 +505,7 @@ def square_sweep(tm, torch, T, side, calls, dts, ms, fmt, reps):
         es = 4 if dt == "f32" else 2
         Tw = side * side
         for M in ms:
-            N = M // 2
+            N, M = M if isinstance(M, tuple) else (M // 2, M)
             masks = [tm.alloc_masks([w], fmt)[0] for w in ws]
             obj = torch.zeros(1, dtype=torch.float64, device="cuda")
             wsp = tm.alloc_workspace([ws[0]], N, M)
@@ -590,7 +591,7 @@ def main():
     ap.add_argument("--square", type=int, default=0, help="instead of the sections: sweep calls on one SIDE x SIDE matrix")
     ap.add_argument("--calls", default="approx,exact,score,pack")
     ap.add_argument("--dts", default="f32,bf16")
-    ap.add_argument("--ms", default="4,8,16")
+    ap.add_argument("--ms", default="4,8,16", help="--square: block sizes M (N = M/2), or N:M pairs such as 1:4,3:8")
     ap.add_argument("--fmt", type=int, default=0, help="--square: 0 = U8 masks, 1 = bit masks")
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--spmm-shapes", default="", help="instead of the sections: tmask_spmm24 on ROWSxCOLS,... shapes")
@@ -613,7 +614,8 @@ def main():
 
     if args.square:
         print(json.dumps(square_sweep(tm, torch, T, args.square, args.calls.split(","), args.dts.split(","),
-                                      [int(x) for x in args.ms.split(",")], args.fmt, args.reps)))
+                                      [tuple(int(y) for y in x.split(":")) if ":" in x else int(x) for x in args.ms.split(",")],
+                                      args.fmt, args.reps)))
         return
     if args.spmm_shapes:
         shapes = [tuple(int(v) for v in s.split("x")) for s in args.spmm_shapes.split(",")]

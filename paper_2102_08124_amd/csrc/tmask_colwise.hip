@@ -177,56 +177,73 @@ __device__ __forceinline__ void cw_ranks(const uint32_t (&key)[M], uint32_t (&r)
 // are compared as they are; if the threshold value occurs on both sides of the cut, fewer than K entries lie below it
 // and the missing ones are the entries equal to it at the lowest positions (a wavefront-uniform detour).
 // 350-550 instructions against 1500 for pairwise ranks.
-// the (K+1)-th smallest of 32 keys (1 <= K <= 31; the keys may repeat)
-__device__ __forceinline__ uint32_t cw_threshold32(const uint32_t (&k)[32], uint32_t K)
+// the (K+1)-th smallest of M keys (1 <= K <= M - 1; the keys may repeat).  M = 32: two halves of 16 sorted by network,
+// for K = 16 the minimum over i of max(a_i, b_15-i), for any other K a bitonic merge and a register read at an index
+// that is the same in every lane.  M <= 16: one sorting network and that register read.
+template <int M>
+__device__ __forceinline__ uint32_t cw_threshold(const uint32_t (&k)[M], uint32_t K)
 {
-    uint32_t a[16], b[16];
-#pragma unroll
-    for (int i = 0; i < 16; i++) {
-        a[i] = k[i];
-        b[i] = k[16 + i];
-    }
-    sort_asc<16>(a);
-    sort_asc<16>(b);
-    uint32_t t;
-    if (K == 16u) {
-        t = 0xFFFFFFFFu;
+    if constexpr (M == 32) {
+        uint32_t a[16], b[16];
 #pragma unroll
         for (int i = 0; i < 16; i++) {
-            const uint32_t m = a[i] > b[15 - i] ? a[i] : b[15 - i];
-            t = m < t ? m : t;
+            a[i] = k[i];
+            b[i] = k[16 + i];
         }
+        sort_asc<16>(a);
+        sort_asc<16>(b);
+        uint32_t t;
+        if (K == 16u) {
+            t = 0xFFFFFFFFu;
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const uint32_t m = a[i] > b[15 - i] ? a[i] : b[15 - i];
+                t = m < t ? m : t;
+            }
+        } else {
+            uint32_t s[32];
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                s[i] = a[i];
+                s[16 + i] = b[15 - i];
+            }
+            bitonic_merge_asc<32>(s);
+            t = s[__builtin_amdgcn_readfirstlane(K) & 31u];
+        }
+        return t;
     } else {
-        uint32_t s[32];
+        uint32_t s[M];
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            s[i] = a[i];
-            s[16 + i] = b[15 - i];
-        }
-        bitonic_merge_asc<32>(s);
-        t = s[__builtin_amdgcn_readfirstlane(K) & 31u];      // the same index in every lane: a relative register read
+        for (int i = 0; i < M; i++)
+            s[i] = k[i];
+        sort_asc<M>(s);
+        return s[__builtin_amdgcn_readfirstlane(K) & (uint32_t)(M - 1)];
     }
-    return t;
 }
 
-template <int DT>
-__device__ __forceinline__ uint32_t cw_pruned32(const uint32_t (&mag)[32], uint32_t K)
+// M magnitudes held by one lane: bit i of the result is set when entry i is among the first K of the (magnitude,
+// position) order, i.e. pruned: the entries below the (K+1)-th smallest key.  bf16 keys carry the position in their low
+// bits (15 + 5 bits), so they are distinct.  fp32 magnitudes are compared as they are; if the threshold value occurs
+// on both sides of the cut, fewer than K entries lie below it and the missing ones are the entries equal to it at the
+// lowest positions (a wavefront-uniform detour).  At M = 32: 350-550 instructions against 1500 for pairwise ranks.
+template <int DT, int M>
+__device__ __forceinline__ uint32_t cw_pruned(const uint32_t (&mag)[M], uint32_t K)
 {
-    uint32_t k[32];
+    uint32_t k[M];
 #pragma unroll
-    for (int i = 0; i < 32; i++)
+    for (int i = 0; i < M; i++)
         k[i] = DT == kF32 ? mag[i] : ((mag[i] >> 11) | (uint32_t)i);
-    const uint32_t t = cw_threshold32(k, K);
+    const uint32_t t = cw_threshold<M>(k, K);
     uint32_t w = 0;
 #pragma unroll
-    for (int i = 31; i >= 0; i--)
+    for (int i = M - 1; i >= 0; i--)
         lm_shift_in(w, lm(k[i] < t));
     if constexpr (DT == kF32) {
         const uint32_t lt = (uint32_t)__builtin_popcount(w);
         if (lm(lt != K) != 0) {
             uint32_t eq = 0;
 #pragma unroll
-            for (int i = 31; i >= 0; i--)
+            for (int i = M - 1; i >= 0; i--)
                 lm_shift_in(eq, lm(k[i] == t));
             uint32_t q = K - lt;
             while (lm(q != 0u) != 0) {
@@ -240,12 +257,13 @@ __device__ __forceinline__ uint32_t cw_pruned32(const uint32_t (&mag)[32], uint3
     return w;
 }
 
-// A 32 x 32 bit matrix held as one word per lane by the 32 lanes of a block (lane l, bit i) -> its transpose (lane i,
-// bit l): five rounds of swapping the off-diagonal quarters at sizes 16, 8, 4, 2, 1 with the lane 16, 8, ... away.
-__device__ __forceinline__ uint32_t cw_transpose32(uint32_t w)
+// An M x M bit matrix held as one word per lane by the M lanes of a block (lane l, bit i) -> its transpose (lane i,
+// bit l): log2 M rounds of swapping the off-diagonal quarters at sizes M/2, ..., 1 with the lane that far away.
+template <int M>
+__device__ __forceinline__ uint32_t cw_transpose(uint32_t w)
 {
 #pragma unroll
-    for (int s = 16; s >= 1; s >>= 1) {
+    for (int s = M / 2; s >= 1; s >>= 1) {
         const uint32_t m = s == 16 ? 0x0000FFFFu : s == 8 ? 0x00FF00FFu : s == 4 ? 0x0F0F0F0Fu : s == 2 ? 0x33333333u : 0x55555555u;
         const uint32_t o = (uint32_t)__shfl_xor((int)w, s, 64);
         w = (threadIdx.x & (uint32_t)s) ? ((w & ~m) | ((o >> s) & m)) : ((w & m) | ((o << s) & ~m));
@@ -334,7 +352,6 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 4 : 1) void cw_mask_kernel(co
 {
     constexpr int NB = 64 / M;
     __shared__ uint32_t T[NB][M][M + 1];
-    __shared__ uint32_t RK[NB][M];
     const CwMat md = args.m[cw_find(args, blockIdx.x)];
     const uint32_t lane = threadIdx.x, blk = lane / M, j = lane % M;
     const uint32_t K = args.K;
@@ -360,16 +377,7 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 4 : 1) void cw_mask_kernel(co
             T[blk][i][j] = key[i];
         uint32_t keep = seg_mask<M>();
         if constexpr (SOLVER == kCwApprox) {
-            if constexpr (M == 32) {
-                keep = ~cw_pruned32<DT>(key, K);
-            } else {
-                uint32_t r[M];
-                cw_ranks<M>(key, r);
-                keep = 0;
-#pragma unroll
-                for (int i = 0; i < M; i++)
-                    keep |= (r[i] >= K ? 1u : 0u) << i;
-            }
+            keep = ~cw_pruned<DT, M>(key, K) & seg_mask<M>();
         }
         __syncthreads();
         {
@@ -377,24 +385,9 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 4 : 1) void cw_mask_kernel(co
 #pragma unroll
             for (int c = 0; c < M; c++)
                 rk[c] = T[blk][j][c];
-            uint32_t rowkeep = 0;
-            if constexpr (M == 32) {
-                rowkeep = ~cw_pruned32<DT>(rk, K);
-            } else {
-                uint32_t r[M];
-                cw_ranks<M>(rk, r);
-#pragma unroll
-                for (int c = 0; c < M; c++)
-                    rowkeep |= (r[c] >= K ? 1u : 0u) << c;
-            }
-            RK[blk][j] = rowkeep;
+            // back to columns: bit c of row j's word becomes bit j of column c's
+            keep &= cw_transpose<M>(~cw_pruned<DT, M>(rk, K) & seg_mask<M>());
         }
-        __syncthreads();
-        uint32_t kr = 0;
-#pragma unroll
-        for (int i = 0; i < M; i++)
-            kr |= ((RK[blk][i] >> j) & 1u) << i;
-        keep &= kr;
         if (md.mask)
             cw_store_mask<M, FMT>(md, p, keep);
         float acc = 0.f;
@@ -499,32 +492,36 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 3 : 1) void cw_exact_kernel(c
             T[blk][i][j] = (uint32_t)ccol[i];
         __syncthreads();
         uint32_t xcol = 0, xrow = 0;       // bit i of xcol: (i, j) pruned; bit c of xrow: (j, c) pruned
-        if constexpr (M == 32) {
+        {
             // ---- start under row prices: column j prunes the K rows with the smallest cost + price.  Whatever the
             // prices, that is the cheapest pruning for the row counts it has, which is all the searches below ask of
             // their start; the prices are moved against the imbalance (price_i += step * (count_i - K), the step
-            // shrinking by 12/16 per round from 1/64 of the largest cost, 16 rounds: more rounds leave fewer
-            // searches but cost more than those, measured) and the round with the least excess is kept.  Lane j owns the price of row j; the prices travel through LDS, the counts come from the
-            // transposed flag words.  On random blocks the excess left falls from 36 to about 0.5 per block.  Keys: (cost + price) << 5 | row < 2^31.
-            constexpr int ROUNDS = 16;
+            // shrinking per round) and the round with the least excess is kept.  Lane j owns the price of row j; the
+            // prices travel through LDS, the counts come from the transposed flag words.  Rounds, first step (as a
+            // fraction of the largest cost) and decay: M = 32: 16, 1/64, 12/16 (more rounds leave fewer searches but
+            // cost more than those, measured; excess left on random blocks 36 -> 0.5); M = 16: 20, 1/32, 12/16;
+            // M <= 8: 12, 3/64, 11/16.  Keys: (cost + price) << log2 M | row < 2^31.
+            constexpr int ROUNDS = M == 32 ? 16 : M == 16 ? 20 : 12;
+            constexpr int LOGM = M == 32 ? 5 : M == 16 ? 4 : M == 8 ? 3 : 2;
+            static_assert(S + 1 + LOGM <= 31, "keys fit 31 bits");
             int pr = 1 << (S - 1), best_pr = pr;
             uint32_t best = 0xFFFFFFFFu;
-            int step = 1 << (S - 6);
+            int step = M == 32 ? (1 << (S - 6)) : M == 16 ? (4 << (S - 7)) : (3 << (S - 6));
             for (int round = 0; round <= ROUNDS + 1; round++) {
                 const bool last = round == ROUNDS + 1;        // the kept prices once more, for their flags
                 __syncthreads();
-                PK[blk][j] = ((uint32_t)(last ? best_pr : pr) << 5) | j;
+                PK[blk][j] = ((uint32_t)(last ? best_pr : pr) << LOGM) | j;
                 __syncthreads();
                 uint32_t k[M];
 #pragma unroll
                 for (int i = 0; i < M; i++)
-                    k[i] = ((uint32_t)ccol[i] << 5) + PK[blk][i];
-                const uint32_t t = cw_threshold32(k, K);
+                    k[i] = ((uint32_t)ccol[i] << LOGM) + PK[blk][i];
+                const uint32_t t = cw_threshold<M>(k, K);
                 uint32_t w = 0;
 #pragma unroll
                 for (int i = M - 1; i >= 0; i--)
                     lm_shift_in(w, lm(k[i] < t));
-                const uint32_t wr = cw_transpose32(w);
+                const uint32_t wr = cw_transpose<M>(w);
                 xcol = w;
                 xrow = wr;
                 if (last)
@@ -536,25 +533,10 @@ __global__ __launch_bounds__(kCwThreads, M == 32 ? 3 : 1) void cw_exact_kernel(c
                 best = better ? e : best;
                 best_pr = better ? pr : best_pr;
                 if (!__any(best != 0u))
-                    break;                                   // both blocks balanced: this round's flags are the start
+                    break;                                   // every block balanced: this round's flags are the start
                 const int q = pr + step * ((int)n - (int)K);
                 pr = q < 1 ? 1 : q > (1 << S) - 1 ? (1 << S) - 1 : q;
-                step = (step * 12) >> 4;
-            }
-        } else {
-            // ---- start: the K lightest rows of the lane's column (ties: lower row first) ----
-            uint32_t ck[M], r[M];
-#pragma unroll
-            for (int i = 0; i < M; i++)
-                ck[i] = (uint32_t)ccol[i];
-            cw_ranks<M>(ck, r);
-#pragma unroll
-            for (int i = 0; i < M; i++)
-                xcol |= (r[i] < K ? 1u : 0u) << i;
-#pragma unroll
-            for (int i = 0; i < M; i++) {
-                const uint32_t rowbits = seg_of<M>(lm((xcol >> i) & 1u), blk);
-                xrow = (j == (uint32_t)i) ? rowbits : xrow;
+                step = (step * (M <= 8 ? 11 : 12)) >> 4;
             }
         }
 #pragma unroll

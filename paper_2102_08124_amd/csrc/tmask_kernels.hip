@@ -173,8 +173,9 @@ __global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArg
     }
 }
 
-// tmask_exact for 2:4: every block by enumeration (all 90 patterns), the kept sum comes with the optimum.
-template <int DT, int FMT>
+// tmask_exact at M = 4: every block by enumeration (NK = 2: all 90 patterns; NK = 1, 3: the 24 permutations, kept
+// resp. pruned), the kept sum comes with the optimum.
+template <int DT, int FMT, int NK = 2>
 __global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
 {
     using Ge = Geo<DT, 4>;
@@ -199,7 +200,19 @@ __global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
                 for (int c = 0; c < 4; c++)
                     v[i][c] = __uint_as_float(a[i][b * 4 + c]);
             float best;
-            const uint32_t m16 = exact24_block(v, best);
+            uint32_t m16;
+            if constexpr (NK == 2) {
+                m16 = exact24_block(v, best);
+            } else if constexpr (NK == 1) {
+                m16 = best_permutation4<true>(v, best);
+            } else {
+                m16 = ~best_permutation4<false>(v, best) & 0xFFFFu;
+                float all = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    all += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+                best = all - best;
+            }
             sum += best;
 #pragma unroll
             for (int i = 0; i < 4; i++)
@@ -978,7 +991,10 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     } else if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes))) {
         return rc;
     }
-    if (!aligned)     // M = 32, or a matrix that the 16-byte strips cannot read: the column-per-lane kernels
+    // N != M/2 at M = 16 (masks) and at M = 8, 16 (exact): the strip kernels have only their rank form and an unpriced
+    // start there; the column-per-lane kernels take a threshold from a sorting network and start under row prices
+    const bool general_n = 2 * N != M && (M == 16 || (M == 8 && SOLVER == kSolveExact));
+    if (!aligned || general_n)     // also M = 32, or a matrix that the 16-byte strips cannot read
         return cw_run_mask(SOLVER == kSolveApprox ? 0 : SOLVER == kSolveExact ? 1 : 2, mats, n_mats, dt, N, M, mf, ws,
                            (hipStream_t)stream_);
     batch_kernel_t kern = pick_mask_kernel<SOLVER>(dt, M, mf);
@@ -993,6 +1009,18 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             kern = mf == kMaskU8 ? exact24_kernel<kF32, kMaskU8> : exact24_kernel<kF32, kMaskBits>;
         else
             kern = mf == kMaskU8 ? exact24_kernel<kBF16, kMaskU8> : exact24_kernel<kBF16, kMaskBits>;
+    }
+    if (SOLVER == kSolveExact && M == 4 && N == 1) {
+        if (dt == kF32)
+            kern = mf == kMaskU8 ? exact24_kernel<kF32, kMaskU8, 1> : exact24_kernel<kF32, kMaskBits, 1>;
+        else
+            kern = mf == kMaskU8 ? exact24_kernel<kBF16, kMaskU8, 1> : exact24_kernel<kBF16, kMaskBits, 1>;
+    }
+    if (SOLVER == kSolveExact && M == 4 && N == 3) {
+        if (dt == kF32)
+            kern = mf == kMaskU8 ? exact24_kernel<kF32, kMaskU8, 3> : exact24_kernel<kF32, kMaskBits, 3>;
+        else
+            kern = mf == kMaskU8 ? exact24_kernel<kBF16, kMaskU8, 3> : exact24_kernel<kBF16, kMaskBits, 3>;
     }
     if (SOLVER == kSolveExact && (M == 8 || M == 16) && 2 * N == M) {
 #define TMASK_PICK(DT, MM, FM) \

@@ -1,6 +1,7 @@
 // Per-block solvers working on the strip layout (see tmask_device.hpp).
 //   approx_keep   : Algorithm 1 of arXiv 2102.08124 (Sec. 4) in rank form
 //   exact24_block : Eq. 3 optimum for 2:4 over all 90 feasible patterns (factored enumeration)
+//   best_permutation4 : Eq. 3 optimum for 1:4 and 3:4 over the 24 permutations
 //   exact_general : Eq. 3 optimum for any (N, M) by successive shortest augmenting paths on the
 //                   bipartite row/column network of Fig. 3
 #pragma once
@@ -297,6 +298,45 @@ __device__ __forceinline__ uint32_t exact24_block(const float (&v)[4][4], float 
             bm = better ? m : bm;
         }
     }
+    return bm;
+}
+
+// 1:4 and 3:4: one entry per row and per column is kept (1:4) or pruned (3:4), i.e. the pattern is one of the 24
+// permutations.  v[r][c] = |W| of one 4x4 block.  Returns the 16-bit mask (row r in bits 4r..4r+3) of the permutation
+// with the largest (LARGEST) or smallest sum, the first one in a fixed evaluation order, and that sum in `best`.  Rows
+// 0 and 1 take an ordered pair of columns (12 ways); rows 2 and 3 share the two columns left and take the better of
+// their two assignments.
+template <bool LARGEST>
+__device__ __forceinline__ uint32_t best_permutation4(const float (&v)[4][4], float &best)
+{
+    uint32_t bm = 0;
+    bool first = true;
+#pragma unroll
+    for (int c0 = 0; c0 < 4; c0++)
+#pragma unroll
+        for (int c1 = 0; c1 < 4; c1++) {
+            if (c1 == c0)
+                continue;
+            int x = -1, y = -1;
+#pragma unroll
+            for (int c = 0; c < 4; c++)
+                if (c != c0 && c != c1) {
+                    if (x < 0)
+                        x = c;
+                    else
+                        y = c;
+                }
+            const float top = v[0][c0] + v[1][c1];
+            const float b1 = v[2][x] + v[3][y], b2 = v[2][y] + v[3][x];
+            const bool swap = LARGEST ? b2 > b1 : b2 < b1;
+            const float s = top + (swap ? b2 : b1);
+            const uint32_t m = (1u << c0) | (1u << (4 + c1)) |
+                               (swap ? ((1u << (8 + y)) | (1u << (12 + x))) : ((1u << (8 + x)) | (1u << (12 + y))));
+            const bool better = first || (LARGEST ? s > best : s < best);
+            best = better ? s : best;
+            bm = better ? m : bm;
+            first = false;
+        }
     return bm;
 }
 
