@@ -47,9 +47,12 @@ constexpr bool exact_half_strips(int dt, int M) { return dt == kBF16 && M == 16;
 constexpr bool exact_rows_in_lds(int dt, int M) { return M != 16; }
 constexpr int exact_workgroups_per_cu(int dt, int M) { return M == 16 ? 3 : (dt == kF32 ? 4 : 3); }
 
-template <int DT, int M, int FMT>
+// GENERAL: any N (K = args.K pruned per line); otherwise N = M/2.
+template <int DT, int M, int FMT, bool GENERAL = false>
 __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exact_balanced_kernel(const BatchArgs args)
 {
+    const uint32_t K = GENERAL ? args.K : (uint32_t)(M / 2);
+    const uint32_t NKEEP = (uint32_t)M - K;
     constexpr bool PARK = exact_rows_in_lds(DT, M);
     using Ge = Geo<DT, M>;
     constexpr bool HALF = exact_half_strips(DT, M);
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
 
     // ---- load the block this lane sits on ----
     // Lanes past the matrix' last strip take part in the exchange with a filler block whose start has
-    // no excess (a band of ones: entry (i, j) is 1 iff (i + j) mod M < M/2), so they cost the solver nothing.
+    // no excess (a band of ones: entry (i, j) is 1 iff (i + j) mod M < N), so they cost the solver nothing.
     u32x4 raw[M];
     // first byte of the lane's part of row 0 of the block that strip (or half strip) `unit` belongs to
     auto block_base = [&](uint32_t unit) {
@@ -92,13 +95,13 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
             for (int q = 0; q < 4; q++) {
                 if constexpr (DT == kF32) {
                     const uint32_t j = gpos * 4u + (uint32_t)q;
-                    d[q] = (((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u;
+                    d[q] = (((uint32_t)i + j) & (M - 1)) < NKEEP ? 0x3F800000u : 0u;
                 } else if (HALF && q >= 2) {
                     d[q] = 0u;
                 } else {
                     const uint32_t j = gpos * (uint32_t)C + 2u * (uint32_t)q;
-                    d[q] = ((((uint32_t)i + j) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F80u : 0u) |
-                           ((((uint32_t)i + j + 1u) & (M - 1)) < (uint32_t)(M / 2) ? 0x3F800000u : 0u);
+                    d[q] = ((((uint32_t)i + j) & (M - 1)) < NKEEP ? 0x3F80u : 0u) |
+                           ((((uint32_t)i + j + 1u) & (M - 1)) < NKEEP ? 0x3F800000u : 0u);
                 }
             }
             raw[i] = u32x4{d[0], d[1], d[2], d[3]};
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
                 asm volatile("" : "+v"(a[i][c]));   // the raw rows end here
         }
         exact_costs<M, C, G>(a, cost);
-        e = exact_priced_start<M, C, G>(cost, xcol);
+        e = exact_priced_start<M, C, G, GENERAL>(cost, xcol, K);
         e = e < (uint32_t)(NBUCKET - 1) ? e : (uint32_t)(NBUCKET - 1);
 #pragma unroll
         for (int q = 0; q < XW; q++) {
@@ -213,7 +216,7 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
             uint32_t cnt[M];
             exact_costs<M, C, G>(a, cost);
             exact_counts<M, C, G>(xcol, cnt);
-            (void)exact_phases<M, C, G>(cost, (uint32_t)(M / 2), gpos, xcol, cnt, M * M);
+            (void)exact_phases<M, C, G>(cost, K, gpos, xcol, cnt, M * M);
         }
 #pragma unroll
         for (int i = 0; i < M; i++) {

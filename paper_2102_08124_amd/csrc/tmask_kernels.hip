@@ -991,9 +991,9 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     } else if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes))) {
         return rc;
     }
-    // N != M/2 at M = 16 (masks) and at M = 8, 16 (exact): the strip kernels have only their rank form and an unpriced
-    // start there; the column-per-lane kernels take a threshold from a sorting network and start under row prices
-    const bool general_n = 2 * N != M && (M == 16 || (M == 8 && SOLVER == kSolveExact));
+    // N != M/2 at M = 16, Algorithm 1 and row pruning: the strip kernels have only their rank form there; the
+    // column-per-lane kernels take a threshold from a sorting network
+    const bool general_n = 2 * N != M && M == 16 && SOLVER != kSolveExact;
     if (!aligned || general_n)     // also M = 32, or a matrix that the 16-byte strips cannot read
         return cw_run_mask(SOLVER == kSolveApprox ? 0 : SOLVER == kSolveExact ? 1 : 2, mats, n_mats, dt, N, M, mf, ws,
                            (hipStream_t)stream_);
@@ -1022,9 +1022,10 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         else
             kern = mf == kMaskU8 ? exact24_kernel<kBF16, kMaskU8, 3> : exact24_kernel<kBF16, kMaskBits, 3>;
     }
-    if (SOLVER == kSolveExact && (M == 8 || M == 16) && 2 * N == M) {
+    if (SOLVER == kSolveExact && (M == 8 || M == 16)) {
 #define TMASK_PICK(DT, MM, FM) \
-    if (dt == DT && M == MM && mf == FM) kern = exact_balanced_kernel<DT, MM, FM>;
+    if (dt == DT && M == MM && mf == FM) \
+        kern = 2 * N == M ? exact_balanced_kernel<DT, MM, FM, false> : exact_balanced_kernel<DT, MM, FM, true>;
         TMASK_PICK(kF32, 8, kMaskU8) TMASK_PICK(kF32, 16, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8)
         TMASK_PICK(kBF16, 16, kMaskU8) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
         TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
@@ -1039,7 +1040,7 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 16 && N == 8)
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<16, kMaskU8> : approx_sel_bf16_kernel<16, kMaskBits>;
     // the exact kernel for bf16 8:16 gives a lane half a strip: twice the workgroups
-    const uint32_t unit_split = (SOLVER == kSolveExact && 2 * N == M && exact_half_strips(dt, M)) ? 2u : 1u;
+    const uint32_t unit_split = (SOLVER == kSolveExact && exact_half_strips(dt, M)) ? 2u : 1u;
     hipStream_t stream = (hipStream_t)stream_;
     uint32_t partial0 = 0;
     for (int first = 0; first < n_mats; first += kMaxBatch) {

@@ -489,10 +489,13 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
 // Prices are held unshifted (the shift rides on the add that forms a key); the step times the count is a 24-bit
 // multiply-add (step < 2^23, counts <= M), the full 32-bit multiply runs at a quarter of the rate; the excess is
 // taken as half the sum of |count - K| (the counts of a block always add up to M*K), one instruction per row.
-template <int M, int CL, int G>
-__device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL], uint32_t (&xcol)[CL])
+// GENERAL: any 0 < K < M, the same in every lane (the threshold then comes from a full sort of the column's keys and a
+// register read at that index; 38 instead of 12 instructions at M = 8, 126 instead of 91 at M = 16); otherwise K = M/2.
+template <int M, int CL, int G, bool GENERAL = false>
+__device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL], uint32_t (&xcol)[CL], uint32_t k_general = 0)
 {
-    constexpr int K = M / 2, H = M / 2;
+    constexpr int H = M / 2;
+    const int K = GENERAL ? (int)__builtin_amdgcn_readfirstlane(k_general) : M / 2;
     constexpr int S = exact_cost_bits(M);
     constexpr int ROUNDS = (M == 16) ? 20 : 12;
     constexpr int PMIN = 1, PMAX = (1 << S) - 1;                // price + 2^(S-1)
@@ -516,7 +519,16 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
             lo[i] = k[i];
             hi[i] = k[H + i];
         }
-        return upper_half_min<H>(lo, hi);
+        if constexpr (GENERAL) {
+            uint32_t srt[M];
+#pragma unroll
+            for (int i = 0; i < M; i++)
+                srt[i] = k[i];
+            sort_asc<M>(srt);
+            return srt[(uint32_t)K & (uint32_t)(M - 1)];      // the (K+1)-th smallest; the index is the same in every lane
+        } else {
+            return upper_half_min<H>(lo, hi);
+        }
     };
     int step = (M == 16) ? (4 << (S - 7)) : (3 << (S - 6));
     static_assert(((M == 16) ? (4 << (S - 7)) : (3 << (S - 6))) < (1 << 23), "the step is an operand of a 24-bit multiply");
