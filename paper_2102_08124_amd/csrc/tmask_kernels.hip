@@ -46,9 +46,10 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
         u32x4 raw[M];
         uint32_t bits[M];
         load_strip<DT, M>(md, pos, a, raw);
+        static_assert(SOLVER == kSolveApprox || SOLVER == kSolveRow1D, "the exact solvers have kernels of their own");
         if constexpr (SOLVER == kSolveApprox) {
             approx_keep<DT, M, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
-        } else if constexpr (SOLVER == kSolveRow1D) {
+        } else {
             // structured N:M along rows only: an entry is kept iff at least K entries of its group of M
             // precede it in the (magnitude, position) order
             bool done = false;
@@ -63,37 +64,6 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
                 for (int i = 0; i < M; i++)
                     bits[i] = (1u << Ge::C) - 1u;
                 row_rank_keep<M, Ge::C, Ge::G, Ge::B, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
-            }
-        } else if constexpr (M == 4) {
-            {
-#pragma unroll
-                for (int i = 0; i < 4; i++)
-                    bits[i] = 0;
-#pragma unroll
-                for (int b = 0; b < Ge::B; b++) {
-                    uint32_t key[4][4], xcol[4];
-#pragma unroll
-                    for (int i = 0; i < 4; i++)
-#pragma unroll
-                        for (int c = 0; c < 4; c++)
-                            key[i][c] = a[i][b * 4 + c];
-                    exact_general<4, 4, 1>(key, args.K, 0u, xcol);
-#pragma unroll
-                    for (int i = 0; i < 4; i++)
-#pragma unroll
-                        for (int c = 0; c < 4; c++)
-                            bits[i] |= (((xcol[c] >> i) & 1u) ^ 1u) << (4 * b + c);
-                }
-            }
-        } else {
-            uint32_t xcol[Ge::C];
-            exact_general<M, Ge::C, Ge::G>(a, args.K, gpos, xcol);
-#pragma unroll
-            for (int i = 0; i < M; i++) {
-                bits[i] = 0;
-#pragma unroll
-                for (int c = 0; c < Ge::C; c++)
-                    bits[i] |= (((xcol[c] >> i) & 1u) ^ 1u) << c;
             }
         }
         store_mask<DT, M, FMT>(md, pos, bits);
@@ -997,7 +967,9 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     if (!aligned || general_n)     // also M = 32, or a matrix that the 16-byte strips cannot read
         return cw_run_mask(SOLVER == kSolveApprox ? 0 : SOLVER == kSolveExact ? 1 : 2, mats, n_mats, dt, N, M, mf, ws,
                            (hipStream_t)stream_);
-    batch_kernel_t kern = pick_mask_kernel<SOLVER>(dt, M, mf);
+    batch_kernel_t kern = nullptr;
+    if constexpr (SOLVER != kSolveExact)      // exact: enumeration at M = 4, the balanced kernel at M = 8, 16 (below)
+        kern = pick_mask_kernel<SOLVER>(dt, M, mf);
     if (SOLVER == kSolveApprox && M == 4 && N == 2) {
         if (dt == kF32)
             kern = mf == kMaskU8 ? approx24_kernel<kF32, kMaskU8> : approx24_kernel<kF32, kMaskBits>;

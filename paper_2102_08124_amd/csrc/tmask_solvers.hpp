@@ -2,8 +2,9 @@
 //   approx_keep   : Algorithm 1 of arXiv 2102.08124 (Sec. 4) in rank form
 //   exact24_block : Eq. 3 optimum for 2:4 over all 90 feasible patterns (factored enumeration)
 //   best_permutation4 : Eq. 3 optimum for 1:4 and 3:4 over the 24 permutations
-//   exact_general : Eq. 3 optimum for any (N, M) by successive shortest augmenting paths on the
-//                   bipartite row/column network of Fig. 3
+//   exact_costs / exact_priced_start / exact_phases : the pieces of the Eq. 3 optimum for M = 8, 16 by successive
+//                   shortest augmenting paths on the bipartite row/column network of Fig. 3 (put together in
+//                   tmask_exact_balance.hpp)
 #pragma once
 #include "tmask_device.hpp"
 #include "tmask_networks.hpp"
@@ -350,7 +351,8 @@ __device__ __forceinline__ uint32_t best_permutation4(const float (&v)[4][4], fl
 // graph is a forest; truncation costs less than M*K*2^-(S-1) of the block maximum in retained L1
 // (S = 27 for M <= 8, 26 for M = 16).
 //
-// Start: every column prunes its K lightest rows -- a flow that saturates the column->sink edges and
+// Start: every column prunes the K rows that are lightest under row prices (exact_priced_start) -- a flow that
+// saturates the column->sink edges and
 // is cheapest among all flows with the same row imbalances.  Then, while some row has more than K
 // pruned entries, find the cheapest alternating path from any such row to a row with fewer than K
 // (row r -> column j through a pruned entry (r,j), column j -> row r' through an unpruned entry
@@ -405,52 +407,6 @@ __device__ __forceinline__ void exact_costs(const uint32_t (&key)[M][CL], int (&
             const uint32_t sh = emax - (e ? e : 1u);
             cost[i][c] = sh < 32u ? (int)((mant << (S - 24)) >> sh) : 0;
         }
-
-}
-
-// Start: xcol[c] bit i = entry (i, c) pruned.
-template <int M, int CL, int G>
-__device__ __forceinline__ void exact_start(const int (&cost)[M][CL], uint32_t K, uint32_t (&xcol)[CL])
-{
-    // ---- start: K lightest rows of every column (ties: lower row first) ----
-    if (2 * K == (uint32_t)M) {
-        // cost << 4 | row is a distinct key (cost < 2^27, resp. 2^26 with 4 index bits at M = 16):
-        // the K lightest are the keys below the smallest key of the upper half
-        constexpr int H = M / 2;
-#pragma unroll
-        for (int c = 0; c < CL; c++) {
-            uint32_t lo[H], hi[H];
-#pragma unroll
-            for (int i = 0; i < H; i++) {
-                lo[i] = ((uint32_t)cost[i][c] << 4) | (uint32_t)i;
-                hi[i] = ((uint32_t)cost[H + i][c] << 4) | (uint32_t)(H + i);
-            }
-            const uint32_t t = upper_half_min<H>(lo, hi);
-            uint32_t x = 0;
-#pragma unroll
-            for (int i = 0; i < M; i++)
-                x |= ((((uint32_t)cost[i][c] << 4) | (uint32_t)i) < t ? 1u : 0u) << i;
-            xcol[c] = x;
-        }
-    } else {
-#pragma unroll
-        for (int c = 0; c < CL; c++) {
-            uint32_t r[M];
-#pragma unroll
-            for (int i = 0; i < M; i++)
-                r[i] = 0;
-#pragma unroll
-            for (int i = 0; i < M; i++)
-#pragma unroll
-                for (int i2 = i + 1; i2 < M; i2++)
-                    rank_pair<M>(cost[i][c] <= cost[i2][c], r[i], r[i2]);
-            uint32_t x = 0;
-#pragma unroll
-            for (int i = 0; i < M; i++)
-                x |= (r[i] < K ? 1u : 0u) << i;
-            xcol[c] = x;
-        }
-    }
 
 }
 
@@ -741,18 +697,6 @@ __device__ __forceinline__ bool exact_phases(const int (&cost)[M][CL], uint32_t 
     for (int i = 0; i < M; i++)
         excess |= cnt[i] > K;
     return !excess;
-}
-
-template <int M, int CL, int G>
-__device__ __forceinline__ void exact_general(const uint32_t (&key)[M][CL], uint32_t K, uint32_t gpos,
-                                              uint32_t (&xcol)[CL])
-{
-    int cost[M][CL];
-    uint32_t cnt[M];
-    exact_costs<M, CL, G>(key, cost);
-    exact_start<M, CL, G>(cost, K, xcol);
-    exact_counts<M, CL, G>(xcol, cnt);
-    (void)exact_phases<M, CL, G>(cost, K, gpos, xcol, cnt, M * M);
 }
 
 }  // namespace tmask
