@@ -35,8 +35,9 @@ __device__ __forceinline__ void unpack_row(const u32x4 &r, uint32_t (&a)[C])
     }
 }
 
-// Workgroups per compute unit: a bf16 lane holds eight columns of its block (an fp32 lane four), and at M = 8
-// that needs more than the 128 registers that four workgroups would leave it.  At M = 16 eight columns of sixteen
+// Workgroups per compute unit: four at M = 8.  A bf16 lane holds eight columns of its block (an fp32 lane four) and
+// would like 154 registers; held to 128 it keeps 35 values in scratch memory and is still 1-4 % faster than with
+// three workgroups (headline set at 4:8: 1084 -> 1045 us).  At M = 16 eight columns of sixteen
 // rows do not fit a lane at all (256 registers, spills): there a bf16 lane takes half a strip, four columns, and
 // four lanes share a block as at fp32 (exact_half_strips; the host launches twice the workgroups).
 // Where the raw rows wait for the lane that runs their block's searches: in LDS (M x 16 bytes per lane), except at
@@ -45,7 +46,7 @@ __device__ __forceinline__ void unpack_row(const u32x4 &r, uint32_t (&a)[C])
 // (8192 x 8192 fp32: 890 -> 714 us; the M = 8 cases measured the same or 2-4 % slower without the LDS copy).
 constexpr bool exact_half_strips(int dt, int M) { return dt == kBF16 && M == 16; }
 constexpr bool exact_rows_in_lds(int dt, int M) { return M != 16; }
-constexpr int exact_workgroups_per_cu(int dt, int M) { return M == 16 ? 3 : (dt == kF32 ? 4 : 3); }
+constexpr int exact_workgroups_per_cu(int dt, int M) { return M == 16 ? 3 : 4; }
 
 // GENERAL: any N (K = args.K pruned per line); otherwise N = M/2.
 template <int DT, int M, int FMT, bool GENERAL = false>
