@@ -630,7 +630,7 @@ def main():
     mats_np = wl.config3()
     weights = sum(w.size for w in mats_np)
     t_gen = time.perf_counter() - t_gen
-    names3 = {"approx": "approx24_kernel<1, 0>", "exact": "exact24_kernel<1, 0>",
+    names3 = {"approx": "approx24_kernel<1, 0>", "exact": "exact24_kernel<1, 0, 2>",
               "pack": "pack24_kernel<1, 0, 32, 4, 4>", "score": "score_kernel<1, 4, 0>"}
 
     result = {
@@ -682,7 +682,7 @@ def main():
         result["one_pass"] = one_pass_section(tm, torch, T, mats_np, copies=2, reps=10)
     if "config2" in sections:
         m2 = wl.config2()
-        names2 = {"approx": "approx24_kernel<0, 0>", "exact": "exact24_kernel<0, 0>",
+        names2 = {"approx": "approx24_kernel<0, 0>", "exact": "exact24_kernel<0, 0, 2>",
                   "pack": "pack24_kernel<0, 0, 64, 4, 4>", "score": "score_kernel<0, 4, 0>"}
         st2 = step_section(tm, torch, T, m2, 2, 4, 200, 20, 8, 4, names2, "resnet50_f32_2of4")
         st2["what"] = ("ResNet-50-shaped conv set: 52 fp32 matrices, 23445504 weights, Kaiming-normal, 2:4, same step, "
