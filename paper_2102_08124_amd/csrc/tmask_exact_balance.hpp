@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kThreads, exact_workgroups_per_cu(DT, M)) void exac
                 asm volatile("" : "+v"(a[i][c]));   // the raw rows end here
         }
         exact_costs<M, C, G>(a, cost);
-        e = exact_priced_start<M, C, G, GENERAL>(cost, xcol, K);
+        e = exact_priced_start<M, C, G, GENERAL>(cost, gpos, xcol, K);
         e = e < (uint32_t)(NBUCKET - 1) ? e : (uint32_t)(NBUCKET - 1);
 #pragma unroll
         for (int q = 0; q < XW; q++) {

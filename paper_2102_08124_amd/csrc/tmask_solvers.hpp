@@ -441,14 +441,19 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
 // prices) to 0.2 at M = 8 and from 6.3 to well under 0.5 at M = 16; a round costs about a third of one sweep of
 // a search and runs with every lane busy, where the searches keep 40-50 % of the lanes busy.
 //
-// Keys are (cost + price + 2^(S-1)) << 4 | row with |price| < 2^(S-1): below 2^(S+5) <= 2^32 for costs < 2^S.
+// Keys are (cost + price + 2^(S-1)) << 4 | tie-break with |price| < 2^(S-1): below 2^(S+5) <= 2^32 for costs < 2^S.
+// The tie-break of entry (i, j) is (i - j) mod M, not the row alone: columns with equal costs (blocks of an
+// unstructured-sparse matrix are full of zeros) then prune different rows, a band, instead of all the same ones,
+// which no row price could tell apart (4096^2 fp32 with 90 % zeros: 4:8 270 -> 146 us, 8:16 931 -> 370 us; all zeros:
+// 181 -> 57 us, 544 -> 120 us).
 // Prices are held unshifted (the shift rides on the add that forms a key); the step times the count is a 24-bit
 // multiply-add (step < 2^23, counts <= M), the full 32-bit multiply runs at a quarter of the rate; the excess is
 // taken as half the sum of |count - K| (the counts of a block always add up to M*K), one instruction per row.
 // GENERAL: any 0 < K < M, the same in every lane (the threshold then comes from a full sort of the column's keys and a
 // register read at that index; 38 instead of 12 instructions at M = 8, 126 instead of 91 at M = 16); otherwise K = M/2.
 template <int M, int CL, int G, bool GENERAL = false>
-__device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL], uint32_t (&xcol)[CL], uint32_t k_general = 0)
+__device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL], uint32_t gpos, uint32_t (&xcol)[CL],
+                                                       uint32_t k_general = 0)
 {
     constexpr int H = M / 2;
     const int K = GENERAL ? (int)__builtin_amdgcn_readfirstlane(k_general) : M / 2;
@@ -462,7 +467,7 @@ __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL],
         pr[i] = 1 << (S - 1);
 #pragma unroll
         for (int c = 0; c < CL; c++)
-            ck[i][c] = ((uint32_t)cost[i][c] << 4) | (uint32_t)i;
+            ck[i][c] = ((uint32_t)cost[i][c] << 4) | (((uint32_t)i - (gpos * (uint32_t)CL + (uint32_t)c)) & (uint32_t)(M - 1));
     }
     // the column's threshold key under the prices p: the K pruned rows are the keys below it
     auto threshold = [&](int c, const int (&p)[M], uint32_t (&k)[M]) {
