@@ -163,6 +163,21 @@ def test_exact_heavy_tailed_and_degenerate(N, M):
     _check_exact(w, mask, N, M, opb)
 
 
+@pytest.mark.parametrize("kind", ["f32", "bf16"])
+@pytest.mark.parametrize("zeros", [0.5, 0.9, 0.99])
+@pytest.mark.parametrize("N,M", [(2, 4), (1, 4), (4, 8), (3, 8), (8, 16), (5, 16), (16, 32), (8, 32)])
+def test_exact_on_unstructured_sparse_matrices(N, M, zeros, kind):
+    """Sec. 5's use: a matrix that is already unstructured-sparse.  Most costs are zero and equal, columns look alike,
+    and the cut of many columns falls among the zeros: the optimum must still be reached."""
+    w = _inputs(kind, 4 * M, 32 * M, seed=2300 + M + N)
+    rng = np.random.default_rng(2301 + M)
+    w[rng.random(w.shape) < zeros] = 0
+    (mask,), obj = run_masks(tm.tmask_exact, [w], N, M)
+    _, oobj, opb = oracle.exact(w, N, M, per_block=True, threads=8)
+    _check_exact(w, mask, N, M, opb)
+    assert obj[0] == pytest.approx(oobj, rel=1e-5, abs=1e-30)
+
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("N,M", NM)
 def test_exact_structured_blocks(N, M, dt):
