@@ -140,7 +140,7 @@ __device__ __forceinline__ void row_half_keep_bf16(const u32x4 (&raw)[M], uint32
 // fp32, N = M/2, M = 8 or 16.  A 31-bit magnitude leaves no room for the index, so thresholds are
 // taken on magnitudes alone: t = N-th largest of a line, u = (N+1)-th largest.  If t > u in every
 // line of the strip, "key >= t" is exactly the rank test (no tie straddles the cut).  If some line has
-// t == u the index order matters there; the caller then redoes the strip with the rank form.
+// t == u the index order matters there; the caller then redoes the strip with approx_half_f32_ties (below).
 // A line of a column (M rows) is lane-local; a line of a row is spread over G = M/4 lanes.
 // =================================================================================================
 
@@ -249,6 +249,95 @@ __device__ __forceinline__ bool approx_half_f32(const uint32_t (&a)[M][4], uint3
         __builtin_amdgcn_sched_barrier(0);
     }
     return tie;
+}
+
+// The same result when some line has its cut among equal values: of the entries equal to the line's threshold t (the
+// N-th largest value) the last N - #(entries above t) in position order stay, which is what the (magnitude, position)
+// order of the sweep decides.  A column is lane-local; a row is spread over G = M/4 lanes, and an entry's share of the
+// equal ones that stay is what the lanes to its right leave over.  About a quarter of the rank form's instructions.
+template <int M>
+__device__ __forceinline__ void approx_half_f32_ties(const uint32_t (&a_in)[M][4], uint32_t gpos, uint32_t (&rowbytes)[M],
+                                                     float &sum)
+{
+    constexpr int H = M / 2, G = M / 4;
+    constexpr uint32_t N = M / 2;
+    // The keys pass through an empty asm: the thresholds are then worked out again here.  Otherwise the compiler reuses
+    // the ones approx_half_f32 computed, which keeps all of them (and more) in registers on the way that has no ties:
+    // 209 instead of 119 registers at M = 16, half the wavefronts per SIMD.
+    uint32_t a[M][4];
+#pragma unroll
+    for (int i = 0; i < M; i++)
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            a[i][c] = a_in[i][c];
+            asm volatile("" : "+v"(a[i][c]));
+        }
+    uint32_t colkeep[4];            // bit i: entry (i, c) stays as far as its column is concerned
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        uint32_t lo[H], hi[H], t, u;
+#pragma unroll
+        for (int i = 0; i < H; i++) {
+            lo[i] = a[i][c];
+            hi[i] = a[H + i][c];
+        }
+        middle_pair<H>(lo, hi, t, u);
+        uint32_t gt = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            gt += a[i][c] > t ? 1u : 0u;
+        uint32_t need = N - gt, w = 0;
+#pragma unroll
+        for (int i = M - 1; i >= 0; i--) {
+            const bool take = a[i][c] == t && need != 0u;
+            need -= take ? 1u : 0u;
+            w |= ((a[i][c] > t || take) ? 1u : 0u) << i;
+        }
+        colkeep[c] = w;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        uint32_t s[4] = {a[i][0], a[i][1], a[i][2], a[i][3]};
+        uint32_t t, u;
+        if constexpr (M == 8)
+            middle_pair_row8(s, t, u);
+        else
+            middle_pair_row16(s, gpos, t, u);
+        uint32_t gt = 0, eq = 0;
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            gt += a[i][c] > t ? 1u : 0u;
+            eq += a[i][c] == t ? 1u : 0u;
+        }
+        // entries equal to t in the lanes to the right of this one (higher columns of the row)
+        // (every cross-lane read happens with all lanes of the block enabled; only the use is conditional)
+        uint32_t right;
+        const uint32_t eq_next = quad_xor<1>(eq);
+        if constexpr (G == 2) {
+            gt += quad_xor<1>(gt);
+            right = gpos == 0u ? eq_next : 0u;
+        } else {
+            gt += quad_xor<1>(gt);
+            gt += quad_xor<2>(gt);
+            const uint32_t pair_far = quad_xor<2>(eq + eq_next);
+            right = ((gpos & 1u) ? 0u : eq_next) + (gpos < 2u ? pair_far : 0u);
+        }
+        const uint32_t stay = N - gt;                       // equal entries of the whole row that stay
+        uint32_t need = stay > right ? stay - right : 0u;   // ... and of this lane, from its last column down
+        uint32_t bytes = 0;
+#pragma unroll
+        for (int c = 3; c >= 0; c--) {
+            const bool take = a[i][c] == t && need != 0u;
+            need -= take ? 1u : 0u;
+            const bool keep = (a[i][c] > t || take) && ((colkeep[c] >> i) & 1u);
+            bytes |= keep ? (1u << (8 * c)) : 0u;
+            sum += keep ? __uint_as_float(a[i][c]) : 0.f;
+        }
+        rowbytes[i] = bytes;
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 }  // namespace tmask

@@ -422,7 +422,7 @@ __device__ __forceinline__ uint32_t gather_every_fourth_bit(uint32_t y)
 
 // APPROX = false: tmask_apply_pack (ARGS = PackArgs, the mask is read).  APPROX = true: tmask_approx_pack (ARGS =
 // FusedArgs): the keep flags come from Algorithm 1 in its threshold form on the lane pair's block
-// (approx_half_f32; a wavefront in which some line has a tie across its cut redoes its blocks in the rank form),
+// (approx_half_f32; a wavefront in which some line has a tie across its cut redoes its blocks with approx_half_f32_ties),
 // the mask is written if WMASK, the kept magnitudes' sum goes to the workgroup's partial.
 template <int FMT, int S, bool APPROX, bool WMASK, typename ARGS>
 __global__ __launch_bounds__(256) void pack48_f32_kernel(const ARGS args)
@@ -535,14 +535,8 @@ __global__ __launch_bounds__(256) void pack48_f32_kernel(const ARGS args)
             }
             float part = 0.f;
             const bool tie = approx_half_f32<8>(a, l & 1u, mk[q], part);
-            if (__any(tie)) {
-                uint32_t bits[8];
-                approx_keep<kF32, 8, false>(a, 4u, l & 1u, bits);
-                part = kept_sum<8, 4>(a, bits);
-#pragma unroll
-                for (int i = 0; i < 8; i++)
-                    mk[q][i] = bits_to_bytes4(bits[i]);
-            }
+            if (__any(tie))
+                approx_half_f32_ties<8>(a, l & 1u, mk[q], part);
             acc += part;
             // the flags exist as bytes from here on, and the sum is complete (see pack48_bf16_kernel)
 #pragma unroll
