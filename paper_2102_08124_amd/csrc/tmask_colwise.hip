@@ -1,6 +1,7 @@
-// tmask: the column-per-lane kernels.  They serve (a) M = 32 for every entry point and (b) M = 4, 8, 16 when a matrix
-// misses the 16-byte alignment the strip kernels read with (only the paper's own requirement is left: rows and cols
-// multiples of M; arXiv 2102.08124, Sec. 4, "a block of size M x M in a weight matrix").  gfx950 only.
+// tmask: the column-per-lane kernels.  They serve (a) M = 32 for every entry point, (b) M = 4, 8, 16 when a matrix
+// misses the 16-byte alignment the strip kernels read with (only the method's own requirement is left: rows and cols
+// multiples of M, the masks being defined per M x M block; arXiv 2102.08124, Sec. 4) and (c) Algorithm 1 and row
+// pruning with N != M/2 at M = 16, where the strip kernels have only their rank form.  gfx950 only.
 //
 // Layout.  A workgroup is one wavefront and works through tiles of M rows x 64 columns: lane l holds column l of the
 // tile, all M rows, in registers, read and written element by element (no alignment needed).  A block is the M
@@ -9,8 +10,8 @@
 // lane j of a block holds row j, and the answer travels back as one bit word per row.  Yes/no facts about a row of
 // the block are also read off a wavefront ballot: bits [b*M, b*M + M) of ballot(flag of row i) are row i of block b.
 //
-// These kernels are bound by the vector ALU (M < 32: pairwise ranks, M - 1 compares per entry and direction; M = 32:
-// a threshold from two sorted halves per line of 32), not by HBM.
+// The mask and exact kernels are bound by the vector ALU (a threshold from a sorting network per line of M keys and,
+// for the exact solver, per price round), the pack kernel by LDS traffic; none of them by HBM.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
@@ -153,30 +154,6 @@ __device__ __forceinline__ void cw_load_column(const CwMat &md, const CwTile &p,
     }
 }
 
-// ranks of M keys held by one lane under the (key, position) order: r[i] = number of keys that precede key i
-template <int M>
-__device__ __forceinline__ void cw_ranks(const uint32_t (&key)[M], uint32_t (&r)[M])
-{
-#pragma unroll
-    for (int i = 0; i < M; i++)
-        r[i] = 0;
-#pragma unroll
-    for (int i = 0; i < M; i++)
-#pragma unroll
-        for (int i2 = i + 1; i2 < M; i2++) {
-            const uint32_t le = key[i] <= key[i2] ? 1u : 0u;      // position i precedes i2 on ties
-            r[i2] += le;
-            r[i] += 1u - le;
-        }
-}
-
-// Thirty-two magnitudes held by one lane: bit i of the result is set when entry i is among the first K of the
-// (magnitude, position) order, i.e. pruned.  Threshold form: the (K+1)-th smallest key comes out of two sorted halves
-// (K = 16: min over i of max(a_i, b_15-i); any other K: a bitonic merge of the halves and a select), entries below it
-// are pruned.  bf16 keys carry the position in their low bits (15 + 5 bits), so they are distinct.  fp32 magnitudes
-// are compared as they are; if the threshold value occurs on both sides of the cut, fewer than K entries lie below it
-// and the missing ones are the entries equal to it at the lowest positions (a wavefront-uniform detour).
-// 350-550 instructions against 1500 for pairwise ranks.
 // the (K+1)-th smallest of M keys (1 <= K <= M - 1; the keys may repeat).  M = 32: two halves of 16 sorted by network,
 // for K = 16 the minimum over i of max(a_i, b_15-i), for any other K a bitonic merge and a register read at an index
 // that is the same in every lane.  M <= 16: one sorting network and that register read.
