@@ -36,7 +36,8 @@
  *   mask_ld that are multiples of 4 (fp32) or 8 (bf16) bytes, packed value arrays 4-byte aligned (8-byte for the
  *   one-pass tmask_approx_pack kernels), dense outputs 16-byte aligned with a 16-byte pitch.  A call in which some
  *   matrix misses any of this, and every call with M = 32, runs on element-wise kernels instead (one lane per
- *   column of a block): correct for every layout above, bound by the vector ALU instead of by memory.
+ *   column of a block): correct for every layout above, bound by the vector ALU or by LDS traffic instead of by
+ *   memory.
  *
  * Errors
  *   All argument errors are detected on the host before anything is enqueued and leave the outputs
@@ -107,9 +108,9 @@ int tmask_approx_noalloc(const tmask_mat *mats, int n_mats, tmask_dtype dt, int 
                          void *hip_stream);
 
 /*
- * Optimal mask of Eq. 3 per block (Sec. 4, "Reduction to Min-Cost Flow", Fig. 3): exactly N kept
- * per row and column, maximum retained L1.  2:4 blocks are solved by evaluating all 90 feasible
- * patterns in fp32; other (N, M) by successive shortest augmenting paths on the bipartite
+ * Optimal mask of Eq. 3 per block (Sec. 4, the reduction to a min-cost flow, Fig. 3): exactly N kept
+ * per row and column, maximum retained L1.  4 x 4 blocks are solved by evaluating all feasible
+ * patterns in fp32 (90 at 2:4, the 24 permutations at 1:4 and 3:4); M >= 8 by successive shortest augmenting paths on the bipartite
  * row/column network with magnitudes truncated per block to 27 (M<=8), 26 (M=16) or 25 (M=32) significant
  * bits below the block maximum, which costs less than M*(M-N)*2^-26 (resp. 2^-25, 2^-24) of the block
  * maximum in retained L1 (below 1e-5 relative for M <= 16; at M = 32 below 6e-5 in the worst case and
