@@ -11,7 +11,8 @@
 // the block are also read off a wavefront ballot: bits [b*M, b*M + M) of ballot(flag of row i) are row i of block b.
 //
 // The mask and exact kernels are bound by the vector ALU (a threshold from a sorting network per line of M keys and,
-// for the exact solver, per price round), the pack kernel by LDS traffic; none of them by HBM.
+// for the exact solver, per price round), the pack kernel by latency (three workgroups per compute unit, barriers
+// between its phases); none of them by HBM.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
