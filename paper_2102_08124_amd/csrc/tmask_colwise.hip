@@ -11,8 +11,8 @@
 // the block are also read off a wavefront ballot: bits [b*M, b*M + M) of ballot(flag of row i) are row i of block b.
 //
 // The mask and exact kernels are bound by the vector ALU (a threshold from a sorting network per line of M keys and,
-// for the exact solver, per price round), the pack kernel by latency (three workgroups per compute unit, barriers
-// between its phases); none of them by HBM.
+// for the exact solver, per price round; the index arithmetic of staging, compaction and copy-out in the pack
+// kernel), none of them by HBM.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
@@ -752,6 +752,167 @@ __device__ __forceinline__ CwPiece cw_piece(const CwPackArgs &args, uint32_t pie
     return p;
 }
 
+// One piece, one pass (T: the column pass).  The pass is a template argument so that everything that depends on it --
+// which thread loads what, where it lands in LDS -- is a constant per load instead of arithmetic per load.
+template <int DT, int M, int FMT, bool T, int WORDS>
+__device__ __forceinline__ void cw_pack_piece(const CwPiece &p, const uint32_t N, uint32_t *WT, uint32_t *KF,
+                                              uint32_t (*IDX)[WORDS])
+{
+    constexpr int IB = CwLog2<M>::v;
+    constexpr size_t ES = DT == kF32 ? 4 : 2;
+    constexpr uint32_t GP = M + 1;                       // words per group in LDS (one of padding)
+    constexpr uint32_t PITCH_ROW = ((8 * GP + 55) / 64) * 64 + 8;   // = 8 (mod 64), >= 8 * GP
+    constexpr uint32_t pitch = T ? PITCH_ROW + 1 : PITCH_ROW;       // column pass: odd
+    constexpr uint32_t KP = 8 * M + 4;                   // bytes of keep flags per line
+    constexpr uint32_t EPL = 8u * M;                     // elements per line of a full piece
+    constexpr uint32_t STEPS = 32u * EPL / kCwPackThreads;
+    constexpr uint32_t DL = T ? 0u : kCwPackThreads / EPL;   // lines a thread moves down per load (row pass)
+    constexpr uint32_t DE = T ? 8u : 0u;                      // elements it moves along the line (column pass)
+    const uint32_t tid = threadIdx.x;
+    unsigned char *kf = (unsigned char *)KF;
+    const uint32_t e_here = p.g_here * M;
+
+    // ---- loads.  All of a thread's loads are issued back to back (up to 32 of each kind), none inside a branch (its
+    // result would be waited for at the join); entries outside the matrix read element (0, 0) and are dropped below.
+    // row pass: neighbouring lanes = neighbouring elements of a line; column pass: neighbouring lines (columns).  From
+    // one load of a thread to its next the matrix row advances by the same amount, DL + DE rows.
+    const uint32_t l0 = T ? (tid & 31u) : (tid / EPL);
+    const uint32_t e0 = T ? (tid >> 5) : (tid % EPL);
+    const uint32_t line0 = p.lb * 32u + l0;
+    const uint32_t lines_left = p.n_lines > line0 ? p.n_lines - line0 : 0u;
+    const uint32_t elems_left = e_here > e0 ? e_here - e0 : 0u;
+    // the first n_in of the thread's entries lie inside the matrix
+    const uint32_t n_in = T ? (lines_left ? (elems_left + 7u) / 8u : 0u) : (elems_left ? (lines_left + DL - 1u) / DL : 0u);
+    uint32_t v[STEPS], f[STEPS];
+    {
+        const uint32_t r0 = T ? p.ch * EPL + e0 : line0, c0 = T ? line0 : p.ch * EPL + e0;
+        const char *wp = (const char *)p.w + ((size_t)r0 * p.ld + c0) * ES;
+        const unsigned char *mp = p.mask + (size_t)r0 * p.mask_ld + (FMT == kMaskU8 ? c0 : (c0 >> 3));
+        const size_t wstep = (size_t)__builtin_amdgcn_readfirstlane((DL + DE) * (uint32_t)ES) * __builtin_amdgcn_readfirstlane(p.ld);
+        const size_t mstep = (size_t)(DL + DE) * __builtin_amdgcn_readfirstlane(p.mask_ld);
+#pragma unroll
+        for (uint32_t b = 0; b < STEPS; b++) {
+            const bool in = b < n_in;
+            const char *wa = in ? wp : (const char *)p.w;
+            const unsigned char *ma = in ? mp : p.mask;
+            if constexpr (DT == kF32)
+                v[b] = __builtin_nontemporal_load((const uint32_t *)wa);
+            else
+                v[b] = (uint32_t)__builtin_nontemporal_load((const uint16_t *)wa);
+            if constexpr (FMT == kMaskU8)
+                f[b] = (uint32_t)*ma;
+            else
+                f[b] = ((uint32_t)*ma >> (c0 & 7u)) & 1u;
+            wp += wstep;
+            mp += mstep;
+        }
+    }
+    for (uint32_t k = tid; k < 32u * WORDS; k += kCwPackThreads)
+        (&IDX[0][0])[k] = 0;
+    // ---- stage the piece: weights as words, keep flags as bytes (0 / 1); the place of load b is the place of load 0
+    // plus a constant ----
+    {
+        uint32_t *w0 = WT + l0 * pitch + (e0 / M) * GP + (e0 % M);
+        unsigned char *k0 = kf + l0 * KP + e0;
+#pragma unroll
+        for (uint32_t b = 0; b < STEPS; b++) {
+            // row pass: DL lines further down; column pass: 8 elements further along (e0 < 8, so e0 % M + 8 * b stays
+            // inside the group for 8 * (b % (M / 8)) and moves on by whole groups otherwise)
+            const uint32_t woff = T ? ((8u * b) / M) * GP + (8u * b) % M : b * DL * pitch;
+            const uint32_t koff = T ? 8u * b : b * DL * KP;
+            if (b < n_in) {
+                w0[woff] = v[b];
+                k0[koff] = (unsigned char)(f[b] != 0u ? 1u : 0u);
+            }
+        }
+    }
+    __syncthreads();
+    // ---- one thread per group: slots, compaction in place, position codes ----
+    // row pass: eight neighbouring threads take eight neighbouring groups of a line; column pass: 32 neighbouring
+    // threads take 32 neighbouring lines
+    const uint32_t ll = T ? (tid & 31u) : (tid >> 3);
+    const uint32_t gl = T ? (tid >> 5) : (tid & 7u);
+    if (p.lb * 32u + ll < p.n_lines && gl < p.g_here) {
+        uint32_t kb = 0;
+#pragma unroll
+        for (int q4 = 0; q4 < M / 4; q4++) {
+            const uint32_t f4 = KF[(ll * KP + gl * M) / 4 + q4];          // four flag bytes, each 0 or 1
+            kb |= ((f4 * 0x01020408u) >> 24) << (4 * q4);
+        }
+        // slots: the kept positions in order (the first N if the mask keeps more), then the lowest other positions
+        uint32_t sel = kb, cnt = (uint32_t)__builtin_popcount(kb);
+        while (cnt > N) {
+            sel &= ~(0x80000000u >> __builtin_clz(sel));
+            cnt--;
+        }
+        uint32_t z = ~sel & seg_mask<M>(), chosen = sel;
+        for (uint32_t need = N - cnt; need > 0; need--) {
+            const uint32_t low = z & (0u - z);
+            chosen |= low;
+            z ^= low;
+        }
+        uint32_t *grp = &WT[ll * pitch + gl * GP];
+        uint32_t gv[M];
+#pragma unroll
+        for (int q = 0; q < M; q++)
+            gv[q] = grp[q];
+        uint32_t sl = 0, off = gl * N * IB;
+#pragma unroll
+        for (int q = 0; q < M; q++) {
+            if ((chosen >> q) & 1u) {
+                grp[sl] = ((sel >> q) & 1u) ? gv[q] : 0u;                  // the group is compacted in place
+                const unsigned long long code = (unsigned long long)q << (off & 31u);
+                atomicOr(&IDX[ll][off >> 5], (uint32_t)code);
+                if ((uint32_t)(code >> 32))
+                    atomicOr(&IDX[ll][(off >> 5) + 1], (uint32_t)(code >> 32));
+                sl++;
+                off += IB;
+            }
+        }
+    }
+    __syncthreads();
+    // ---- copy-out: per line one run of g_here * N values and one of position bytes.  A thread keeps its place x in
+    // the run from line to line, so which group and slot that is is worked out once ----
+    const size_t vpitch = (size_t)p.gpl * N;
+    const uint32_t run = p.g_here * N;
+    const float inv_n = 1.0f / (float)N;
+    constexpr uint32_t XS = (8u * (M - 1) + 63u) / 64u;          // places per thread: a run has at most 8 * (M - 1) values
+    uint32_t src[XS];
+#pragma unroll
+    for (uint32_t k = 0; k < XS; k++) {
+        const uint32_t x = (tid & 63u) + 64u * k;
+        const uint32_t g = (uint32_t)(((float)x + 0.5f) * inv_n);     // x / N, exact for x < 256, N < 32
+        src[k] = g * GP + (x - g * N);
+    }
+    const uint32_t first_line = tid >> 6;
+    if (p.lb * 32u + first_line < p.n_lines) {
+        char *out = (char *)p.vals + ((size_t)(p.lb * 32u + first_line) * vpitch + (size_t)p.ch * 8u * N + (tid & 63u)) * ES;
+        const size_t out_step = (size_t)__builtin_amdgcn_readfirstlane((uint32_t)(kCwPackThreads / 64)) * vpitch * ES;
+        const uint32_t n_lines_here = min(32u, p.n_lines - p.lb * 32u);
+        for (uint32_t l = first_line; l < n_lines_here; l += kCwPackThreads / 64) {
+#pragma unroll
+            for (uint32_t k = 0; k < XS; k++) {
+                if ((tid & 63u) + 64u * k < run) {
+                    const uint32_t val = WT[l * pitch + src[k]];
+                    if constexpr (DT == kF32)
+                        *(uint32_t *)(out + 64u * k * ES) = val;
+                    else
+                        *(uint16_t *)(out + 64u * k * ES) = (uint16_t)val;
+                }
+            }
+            out += out_step;
+        }
+    }
+    // the chunk's position bits start on a byte boundary of the line: 8 groups * N * IB bits = N * IB bytes
+    const size_t pitch_b = ((size_t)p.gpl * N * IB + 7) / 8;
+    const uint32_t nbytes = (p.g_here * N * IB + 7u) / 8u;
+    for (uint32_t k = tid; k < 32u * nbytes; k += kCwPackThreads) {
+        const uint32_t l2 = k / nbytes, x = k - l2 * nbytes;
+        if (p.lb * 32u + l2 < p.n_lines)
+            p.idx[(size_t)(p.lb * 32u + l2) * pitch_b + (size_t)p.ch * N * IB + x] = ((const unsigned char *)&IDX[l2][0])[x];
+    }
+}
+
 // One workgroup per piece.  (Persistent workgroups that load their next piece into registers while they compact the
 // current one were slower, 322 against 262 us on 8192^2 fp32 16:32: all workgroups then load at the same moments.)
 template <int DT, int M, int FMT>
@@ -759,127 +920,17 @@ __global__ __launch_bounds__(kCwPackThreads) void cw_pack_kernel(const CwPackArg
 {
     constexpr int IB = CwLog2<M>::v;
     constexpr int WORDS = (8 * (M - 1) * IB + 31) / 32 + 2;
-    constexpr uint32_t GP = M + 1;                       // words per group in LDS (one of padding)
-    constexpr uint32_t PITCH_ROW = ((8 * GP + 55) / 64) * 64 + 8;   // = 8 (mod 64), >= 8 * GP
-    constexpr uint32_t PITCH_COL = PITCH_ROW + 1;                   // odd
-    constexpr uint32_t KP = 8 * M + 4;                   // bytes of keep flags per line
-    constexpr uint32_t EPL = 8u * M;                     // elements per line of a full piece
-    constexpr uint32_t STEPS = 32u * EPL / kCwPackThreads;
-    __shared__ uint32_t WT[32 * PITCH_COL];
+    constexpr uint32_t GP = M + 1;
+    constexpr uint32_t PITCH_ROW = ((8 * GP + 55) / 64) * 64 + 8;
+    constexpr uint32_t KP = 8 * M + 4;
+    __shared__ uint32_t WT[32 * (PITCH_ROW + 1)];
     __shared__ uint32_t KF[32 * KP / 4];
     __shared__ uint32_t IDX[32][WORDS];
-    const uint32_t N = args.N;
-    const uint32_t tid = threadIdx.x;
-    unsigned char *kf = (unsigned char *)KF;
-    uint32_t v[STEPS], f[STEPS];
-
-    // All of a thread's loads of a piece are issued back to back (up to 32 of each kind); entries outside the matrix
-    // read element (0, 0) and are dropped when the piece is staged.
-    // row pass: neighbouring lanes = neighbouring elements of a line; column pass: neighbouring lines (columns)
-    auto issue_loads = [&](const CwPiece &p) __attribute__((always_inline)) {
-        const uint32_t e_here = p.g_here * M;
-#pragma unroll
-        for (uint32_t b = 0; b < STEPS; b++) {
-            const uint32_t k = tid + b * kCwPackThreads;
-            const uint32_t l = p.transposed ? (k & 31u) : (k / EPL);
-            const uint32_t e = p.transposed ? (k >> 5) : (k % EPL);
-            const uint32_t line = p.lb * 32u + l;
-            const bool in = line < p.n_lines && e < e_here;
-            const uint32_t along = p.ch * EPL + e;
-            const uint32_t r = in ? (p.transposed ? along : line) : 0u, c = in ? (p.transposed ? line : along) : 0u;
-            v[b] = cw_load<DT>(p.w, (size_t)r * p.ld + c);
-            if constexpr (FMT == kMaskU8)
-                f[b] = (uint32_t)p.mask[(size_t)r * p.mask_ld + c];
-            else
-                f[b] = ((uint32_t)p.mask[(size_t)r * p.mask_ld + (c >> 3)] >> (c & 7u)) & 1u;
-        }
-    };
-
     const CwPiece p = cw_piece<M>(args, blockIdx.x);
-    issue_loads(p);
-    {
-        const uint32_t pitch = p.transposed ? PITCH_COL : PITCH_ROW;
-        const uint32_t e_here = p.g_here * M;
-        for (uint32_t k = tid; k < 32u * WORDS; k += kCwPackThreads)
-            (&IDX[0][0])[k] = 0;
-        // ---- stage the piece: weights as words, keep flags as bytes (0 / 1) ----
-#pragma unroll
-        for (uint32_t b = 0; b < STEPS; b++) {
-            const uint32_t k = tid + b * kCwPackThreads;
-            const uint32_t l = p.transposed ? (k & 31u) : (k / EPL);
-            const uint32_t e = p.transposed ? (k >> 5) : (k % EPL);
-            if (p.lb * 32u + l < p.n_lines && e < e_here) {
-                WT[l * pitch + (e / M) * GP + (e % M)] = v[b];
-                kf[l * KP + e] = (unsigned char)(f[b] != 0u ? 1u : 0u);
-            }
-        }
-        __syncthreads();
-        // ---- one thread per group: slots, compaction in place, position codes ----
-        // row pass: eight neighbouring threads take eight neighbouring groups of a line; column pass: 32 neighbouring
-        // threads take 32 neighbouring lines
-        const uint32_t ll = p.transposed ? (tid & 31u) : (tid >> 3);
-        const uint32_t gl = p.transposed ? (tid >> 5) : (tid & 7u);
-        if (p.lb * 32u + ll < p.n_lines && gl < p.g_here) {
-            uint32_t kb = 0;
-#pragma unroll
-            for (int q4 = 0; q4 < M / 4; q4++) {
-                const uint32_t f4 = KF[(ll * KP + gl * M) / 4 + q4];          // four flag bytes, each 0 or 1
-                kb |= ((f4 * 0x01020408u) >> 24) << (4 * q4);
-            }
-            // slots: the kept positions in order (the first N if the mask keeps more), then the lowest other positions
-            uint32_t sel = kb, cnt = (uint32_t)__builtin_popcount(kb);
-            while (cnt > N) {
-                sel &= ~(0x80000000u >> __builtin_clz(sel));
-                cnt--;
-            }
-            uint32_t z = ~sel & seg_mask<M>(), chosen = sel;
-            for (uint32_t need = N - cnt; need > 0; need--) {
-                const uint32_t low = z & (0u - z);
-                chosen |= low;
-                z ^= low;
-            }
-            uint32_t *grp = &WT[ll * pitch + gl * GP];
-            uint32_t gv[M];
-#pragma unroll
-            for (int q = 0; q < M; q++)
-                gv[q] = grp[q];
-            uint32_t sl = 0;
-#pragma unroll
-            for (int q = 0; q < M; q++) {
-                if ((chosen >> q) & 1u) {
-                    grp[sl] = ((sel >> q) & 1u) ? gv[q] : 0u;                  // the group is compacted in place
-                    const uint32_t off = (gl * N + sl) * IB;
-                    const unsigned long long code = (unsigned long long)q << (off & 31u);
-                    atomicOr(&IDX[ll][off >> 5], (uint32_t)code);
-                    if ((uint32_t)(code >> 32))
-                        atomicOr(&IDX[ll][(off >> 5) + 1], (uint32_t)(code >> 32));
-                    sl++;
-                }
-            }
-        }
-        __syncthreads();
-        // ---- copy-out: per line one run of g_here * N values and one of position bytes ----
-        const size_t vpitch = (size_t)p.gpl * N;
-        const uint32_t run = p.g_here * N;
-        const float inv_n = 1.0f / (float)N;
-        for (uint32_t l = tid >> 6; l < 32u; l += kCwPackThreads / 64) {
-            if (p.lb * 32u + l >= p.n_lines)
-                break;
-            const size_t o = (size_t)(p.lb * 32u + l) * vpitch + (size_t)p.ch * 8u * N;
-            for (uint32_t x = tid & 63u; x < run; x += 64u) {
-                const uint32_t g = (uint32_t)(((float)x + 0.5f) * inv_n);     // x / N, exact for x < 256, N < 32
-                cw_store<DT>(p.vals, o + x, WT[l * pitch + g * GP + (x - g * N)]);
-            }
-        }
-        // the chunk's position bits start on a byte boundary of the line: 8 groups * N * IB bits = N * IB bytes
-        const size_t pitch_b = ((size_t)p.gpl * N * IB + 7) / 8;
-        const uint32_t nbytes = (p.g_here * N * IB + 7u) / 8u;
-        for (uint32_t k = tid; k < 32u * nbytes; k += kCwPackThreads) {
-            const uint32_t l2 = k / nbytes, x = k - l2 * nbytes;
-            if (p.lb * 32u + l2 < p.n_lines)
-                p.idx[(size_t)(p.lb * 32u + l2) * pitch_b + (size_t)p.ch * N * IB + x] = ((const unsigned char *)&IDX[l2][0])[x];
-        }
-    }
+    if (p.transposed)
+        cw_pack_piece<DT, M, FMT, true, WORDS>(p, args.N, WT, KF, IDX);
+    else
+        cw_pack_piece<DT, M, FMT, false, WORDS>(p, args.N, WT, KF, IDX);
 }
 
 // =====================================================================================================================
