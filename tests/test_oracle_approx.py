@@ -163,7 +163,7 @@ def test_lemma_bound_with_brute_force_optimum():
 
 
 def test_empirical_ratio_band():
-    # Sec. 4.1 quotes "within a factor of 1.2 from the optimal" on trained nets (pruned L1);
+    # Sec. 4.1 reports a pruned L1 about 1.2 times the optimum on trained nets;
     # on i.i.d. blocks the mean ratio lands close to that.
     w = wl.gaussian_f32(512, 512, seed=41)
     pats = refs.valid_patterns(2, 4)
