@@ -194,27 +194,44 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
         (&IDX[0][0])[k] = 0;
     for (uint32_t k = tid; k < TC * IDXTW; k += kThreads)
         (&IDXT[0][0])[k] = 0;
+    // all loads of the thread go out before the first is used, none inside a branch (its result would be waited for
+    // at the join): chunks outside the matrix read chunk (0, 0) and are dropped
+    constexpr int PASSES = TR / 16;
+    u32x4 raws[PASSES];
+    uint32_t mlo[PASSES], mhi[PASSES];
 #pragma unroll
-    for (int pass = 0; pass < TR / 16; pass++) {
+    for (int pass = 0; pass < PASSES; pass++) {
         const uint32_t r = pass * 16 + (tid >> 4), ch = tid & 15u;
         const uint32_t row = row0 + r, col = col0 + ch * C;
-        u32x4 raw = {0u, 0u, 0u, 0u};
-        uint32_t flags = 0;
-        if (row < d.rows && col < d.cols) {
-            raw = __builtin_nontemporal_load((const u32x4 *)((const char *)d.w + ((size_t)row * d.ld + col) * ES));
-            if constexpr (FMT == kMaskU8) {
-                const char *mp = (const char *)d.mask + (size_t)row * d.mask_ld + col;
-                if constexpr (C == 4) {
-                    flags = bytes4_to_bits(__builtin_nontemporal_load((const uint32_t *)mp));
-                } else {
-                    const u32x2 mv = __builtin_nontemporal_load((const u32x2 *)mp);
-                    flags = bytes4_to_bits(mv.x) | (bytes4_to_bits(mv.y) << 4);
-                }
+        const bool ok = row < d.rows && col < d.cols;
+        const uint32_t rowc = ok ? row : 0u, colc = ok ? col : 0u;
+        raws[pass] = __builtin_nontemporal_load((const u32x4 *)((const char *)d.w + ((size_t)rowc * d.ld + colc) * ES));
+        mhi[pass] = 0;
+        if constexpr (FMT == kMaskU8) {
+            const char *mp = (const char *)d.mask + (size_t)rowc * d.mask_ld + colc;
+            if constexpr (C == 4) {
+                mlo[pass] = __builtin_nontemporal_load((const uint32_t *)mp);
             } else {
-                const uint32_t byte = ((const unsigned char *)d.mask)[(size_t)row * d.mask_ld + (col >> 3)];
-                flags = (C == 8) ? byte : ((byte >> (col & 4u)) & 0xFu);
+                const u32x2 mv = __builtin_nontemporal_load((const u32x2 *)mp);
+                mlo[pass] = mv.x;
+                mhi[pass] = mv.y;
             }
+        } else {
+            mlo[pass] = ((const unsigned char *)d.mask)[(size_t)rowc * d.mask_ld + (colc >> 3)];
         }
+    }
+#pragma unroll
+    for (int pass = 0; pass < PASSES; pass++) {
+        const uint32_t r = pass * 16 + (tid >> 4), ch = tid & 15u;
+        const uint32_t row = row0 + r, col = col0 + ch * C;
+        const bool ok = row < d.rows && col < d.cols;
+        u32x4 raw = raws[pass];
+        uint32_t flags;
+        if constexpr (FMT == kMaskU8)
+            flags = (C == 4) ? bytes4_to_bits(mlo[pass]) : (bytes4_to_bits(mlo[pass]) | (bytes4_to_bits(mhi[pass]) << 4));
+        else
+            flags = (C == 8) ? mlo[pass] : ((mlo[pass] >> (col & 4u)) & 0xFu);
+        flags = ok ? flags : 0u;                 // everything of such a chunk is then masked to zero below
         uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
         if constexpr (DT == kF32) {
 #pragma unroll
