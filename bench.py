@@ -494,14 +494,18 @@ def cpu_baseline_section(mats_np, N, M, min_s: float = 10.0, many_s: float = 6.0
             "cpus_usable_by_this_process": usable}
 
 
-def square_sweep(tm, torch, T, side, calls, dts, ms, fmt, reps):
+def square_sweep(tm, torch, T, side, calls, dts, ms, fmt, reps, zeros=0.0):
     """One square matrix, chosen calls, dtype x N:M (entries of ms: M, meaning N = M/2, or (N, M)): kernel and whole-call
     event times, as measured."""
-    out = {"side": side, "mask_format": "bits" if fmt else "u8", "marker_overhead_ms": T.marker_ms, "rows": []}
+    out = {"side": side, "mask_format": "bits" if fmt else "u8", "zeros": zeros, "marker_overhead_ms": T.marker_ms, "rows": []}
     for dt in dts:
         nb = 3
-        ws = [(torch.randn((side, side), device="cuda") * 0.02).to(torch.float32 if dt == "f32" else torch.bfloat16)
-              for _ in range(nb)]
+        ws = []
+        for _ in range(nb):
+            w = torch.randn((side, side), device="cuda") * 0.02
+            if zeros > 0.0:                       # an unstructured-sparse matrix: this share of exact zeros
+                w[torch.rand_like(w) < zeros] = 0.0
+            ws.append(w.to(torch.float32 if dt == "f32" else torch.bfloat16))
         es = 4 if dt == "f32" else 2
         Tw = side * side
         for M in ms:
@@ -593,6 +597,7 @@ def main():
     ap.add_argument("--dts", default="f32,bf16")
     ap.add_argument("--ms", default="4,8,16", help="--square: block sizes M (N = M/2), or N:M pairs such as 1:4,3:8")
     ap.add_argument("--fmt", type=int, default=0, help="--square: 0 = U8 masks, 1 = bit masks")
+    ap.add_argument("--zeros", type=float, default=0.0, help="--square: share of the weights set to exact zero")
     ap.add_argument("--reps", type=int, default=10)
     ap.add_argument("--spmm-shapes", default="", help="instead of the sections: tmask_spmm24 on ROWSxCOLS,... shapes")
     ap.add_argument("--tokens", type=int, default=8192)
@@ -615,7 +620,7 @@ def main():
     if args.square:
         print(json.dumps(square_sweep(tm, torch, T, args.square, args.calls.split(","), args.dts.split(","),
                                       [tuple(int(y) for y in x.split(":")) if ":" in x else int(x) for x in args.ms.split(",")],
-                                      args.fmt, args.reps)))
+                                      args.fmt, args.reps, args.zeros)))
         return
     if args.spmm_shapes:
         shapes = [tuple(int(v) for v in s.split("x")) for s in args.spmm_shapes.split(",")]
