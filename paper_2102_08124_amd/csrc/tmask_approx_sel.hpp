@@ -24,8 +24,7 @@ __device__ __forceinline__ uint32_t upper_half_min_pair(uint32_t (&a)[H])
     uint32_t t = 0xFFFFFFFFu;
 #pragma unroll
     for (int i = 0; i < H; i++) {
-        const uint32_t o = quad_xor<1>(a[H - 1 - i]);
-        const uint32_t m = a[i] > o ? a[i] : o;
+        const uint32_t m = quad_xor_max<1>(a[i], a[H - 1 - i]);
         t = m < t ? m : t;
     }
     return t;
@@ -188,8 +187,7 @@ __device__ __forceinline__ void middle_pair_row16(uint32_t (&s)[4], uint32_t gpo
     uint32_t m[4];
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-        const uint32_t y = quad_xor<1>(s[3 - i]);
-        const uint32_t hi = s[i] > y ? s[i] : y, lo = s[i] > y ? y : s[i];
+        const uint32_t hi = quad_xor_max<1>(s[i], s[3 - i]), lo = quad_xor_min<1>(s[i], s[3 - i]);
         m[i] = upper ? hi : lo;
     }
     // m is bitonic: two merge stages sort it
@@ -197,14 +195,12 @@ __device__ __forceinline__ void middle_pair_row16(uint32_t (&s)[4], uint32_t gpo
     uint32_t tl = 0xFFFFFFFFu, ul = 0u;
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-        const uint32_t y = quad_xor<3>(m[3 - i]);
-        const uint32_t hi = m[i] > y ? m[i] : y, lo = m[i] > y ? y : m[i];
+        const uint32_t hi = quad_xor_max<3>(m[i], m[3 - i]), lo = quad_xor_min<3>(m[i], m[3 - i]);
         tl = hi < tl ? hi : tl;
         ul = lo > ul ? lo : ul;
     }
-    const uint32_t to = quad_xor<1>(tl), uo = quad_xor<1>(ul);
-    t = to < tl ? to : tl;
-    u = uo > ul ? uo : ul;
+    t = quad_xor_min<1>(tl, tl);
+    u = quad_xor_max<1>(ul, ul);
 }
 
 // a[i][c] = magnitude keys of the lane's strip (4 columns).  Fills bits[i] (bit c = keep) and the

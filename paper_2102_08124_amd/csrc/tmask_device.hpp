@@ -110,6 +110,24 @@ __device__ __forceinline__ uint32_t quad_xor_sum(uint32_t v)
     return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, 0xF, 0xF, true);
 }
 
+// max / min of a and the value that lane (lane ^ X) of the quad holds in o, the move folded into the operation the same
+// way (v_max_u32_dpp / v_min_u32_dpp: one instruction, and no wait states between a move and its use).
+template <int X>
+__device__ __forceinline__ uint32_t quad_xor_max(uint32_t a, uint32_t o)
+{
+    constexpr int ctrl = (X == 1) ? 0xB1 : (X == 2) ? 0x4E : 0x1B;
+    const uint32_t y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)o, ctrl, 0xF, 0xF, true);
+    return a > y ? a : y;
+}
+
+template <int X>
+__device__ __forceinline__ uint32_t quad_xor_min(uint32_t a, uint32_t o)
+{
+    constexpr int ctrl = (X == 1) ? 0xB1 : (X == 2) ? 0x4E : 0x1B;
+    const uint32_t y = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)o, ctrl, 0xF, 0xF, true);
+    return a < y ? a : y;
+}
+
 // A wavefront-wide boolean: bit l = the predicate in lane l.  Held in a scalar register pair, so
 // logic on it is scalar-ALU work.
 typedef unsigned long long lanemask_t;

@@ -52,10 +52,13 @@ __device__ __forceinline__ void sort_asc<2>(uint32_t (&v)[2])
     cmpx(v[0], v[1]);
 }
 
+// Four keys: sort the first three, then the last three.  v[3] is then the maximum and v[1] <= v[2]; v[2], the median
+// of the old v[1], v[2], v[3], is at least the old v[1] (two of the three are) and so at least v[0]: only v[0] and v[1]
+// can still be out of order.  8 instructions against 10 for five compare-exchanges.
 template <>
 __device__ __forceinline__ void sort_asc<4>(uint32_t (&v)[4])
 {
-    cmpx(v[0], v[1]); cmpx(v[2], v[3]); cmpx(v[0], v[2]); cmpx(v[1], v[3]); cmpx(v[1], v[2]);
+    sort3(v[0], v[1], v[2]); sort3(v[1], v[2], v[3]); cmpx(v[0], v[1]);
 }
 
 // Eight keys by eight three-key sorts: 24 instructions against 38 for the best network of compare-exchanges (19).  The
