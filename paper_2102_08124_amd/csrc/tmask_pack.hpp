@@ -56,7 +56,14 @@ static_assert(sizeof(FusedArgs) <= 16384 + 2048, "descriptor table is sized to s
 // in memory and arrive close in time, which the memory system rewards (fp32 2:4 pack: 66 -> 73 % of the HBM
 // peak at 8192 x 8192; shorter runs lose it again, full-height runs cost the bf16 kernels 5 points).
 // Bands beyond the last multiple of eight are walked column by column.
+// ADJ > 1: an XCD takes ADJ neighbouring tile columns together, one after the other at each height: for kernels whose
+// tiles are narrower than a cache line of the mask or of an index row, so that the tiles sharing such a line meet in
+// one L2 instead of each fetching (or partly writing) it.  The generic kernel (256-byte tiles: 64 mask bytes and 16
+// index bytes per tile row at fp32 8:16) fetched 1.20x and wrote 1.14x its algorithmic bytes without it; with four
+// columns together 8192^2 fp32 8:16 goes from 145 to 121 us, 16384^2 from 715 to 505 us, 3:8 from 192 to 143 us.  The
+// kernels with 1 KB tiles lose with it (fp32 2:4: 107 -> 115 us), except the bf16 4:8 pack with two (78 -> 73 us).
 constexpr uint32_t kPackRunRows = 4096;
+
 
 // Which descriptor does workgroup `tile` belong to (PackArgs or FusedArgs): coarse index, then a short binary search.
 template <typename Args>
@@ -74,23 +81,25 @@ __device__ __forceinline__ int find_pack_desc(const Args &args, uint32_t tile)
     return lo;
 }
 
+template <uint32_t ADJ = 1>
 __device__ __forceinline__ void tile_coords(uint32_t tl, uint32_t tiles_x, uint32_t tiles_y, uint32_t run, uint32_t &ty,
                                             uint32_t &tx)
 {
-    const uint32_t bands8 = tiles_x / 8u, full = bands8 * 8u * tiles_y;
+    const uint32_t bands8 = tiles_x / (8u * ADJ), full = bands8 * 8u * ADJ * tiles_y;
     if (tl < full) {
-        const uint32_t x = tl & 7u, k = tl >> 3;
+        const uint32_t x = tl & 7u, ka = tl >> 3;
+        const uint32_t a = ka % ADJ, k = ka / ADJ;
         const uint32_t per_chunk = run * bands8;
         const uint32_t chunk = k / per_chunk, rk = k - chunk * per_chunk;
         const uint32_t rows_here = min(run, tiles_y - chunk * run);       // the last chunk may be shorter
         const uint32_t band = rk / rows_here;
         ty = chunk * run + (rk - band * rows_here);
-        tx = band * 8u + x;
+        tx = (band * 8u + x) * ADJ + a;
     } else {
         const uint32_t r = tl - full;
         const uint32_t c = r / tiles_y;
         ty = r - c * tiles_y;
-        tx = bands8 * 8u + c;
+        tx = bands8 * 8u * ADJ + c;
     }
 }
 
@@ -182,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
     const uint32_t N = NN ? (uint32_t)NN : args.N;
     const uint32_t tl = tile - d.tile0;
     uint32_t ty, tx;
-    tile_coords(tl, d.tiles_x, (d.rows + TR - 1) / TR, kPackRunRows / TR, ty, tx);
+    tile_coords<4>(tl, d.tiles_x, (d.rows + TR - 1) / TR, kPackRunRows / TR, ty, tx);
     const uint32_t row0 = ty * TR, col0 = tx * TC;
     const uint32_t tid = threadIdx.x;
     const uint32_t g_valid = min((uint32_t)GPT, (d.cols - col0) / M);   // groups of this tile inside the matrix

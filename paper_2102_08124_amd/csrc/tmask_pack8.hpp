@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void pack48_bf16_kernel(const ARGS args)
     const PackDev d = args.d[find_pack_desc(args, tile)];
     const uint32_t tl = tile - d.tile0;
     uint32_t ty, tx;
-    tile_coords(tl, d.tiles_x, (d.rows + TR - 1) / TR, kPackRunRows / TR, ty, tx);
+    tile_coords<APPROX ? 1 : 2>(tl, d.tiles_x, (d.rows + TR - 1) / TR, kPackRunRows / TR, ty, tx);
     const uint32_t row0 = ty * TR, col0 = tx * TC;
     const uint32_t w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t strip = l % (uint32_t)S, sub = l / (uint32_t)S;
