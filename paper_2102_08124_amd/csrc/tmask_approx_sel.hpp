@@ -247,6 +247,31 @@ __device__ __forceinline__ bool approx_half_f32(const uint32_t (&a)[M][4], uint3
     return tie;
 }
 
+// The row half alone (N:M pruning along rows at N = M/2, fp32): bit c of bits[i] = entry (i, c) is at least the N-th
+// largest magnitude of its row group.  Returns true if some group had a tie across its cut (result then invalid: the
+// caller redoes the strip in the rank form).
+template <int M>
+__device__ __forceinline__ bool row_half_keep_f32(const uint32_t (&a)[M][4], uint32_t gpos, uint32_t (&bits)[M])
+{
+    bool tie = false;
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        uint32_t s[4] = {a[i][0], a[i][1], a[i][2], a[i][3]};
+        uint32_t trow, u;
+        if constexpr (M == 8)
+            middle_pair_row8(s, trow, u);
+        else
+            middle_pair_row16(s, gpos, trow, u);
+        tie |= trow == u;
+        uint32_t b = 0;
+#pragma unroll
+        for (int c = 0; c < 4; c++)
+            b |= (a[i][c] >= trow ? 1u : 0u) << c;
+        bits[i] = b;
+    }
+    return tie;
+}
+
 // The same result when some line has its cut among equal values: of the entries equal to the line's threshold t (the
 // N-th largest value) the last N - #(entries above t) in position order stay, which is what the (magnitude, position)
 // order of the sweep decides.  A column is lane-local; a row is spread over G = M/4 lanes, and an entry's share of the

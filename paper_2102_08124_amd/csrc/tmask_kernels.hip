@@ -59,6 +59,12 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
                     done = true;
                 }
             }
+            if constexpr (DT == kF32 && M == 16) {
+                // N = M/2: thresholds on magnitudes (8192^2 8:16: 89 -> 63 us); a wavefront with a cut among equal
+                // values falls through to the ranks.  At M = 8 the ranks already run at the speed of the memory.
+                if (2u * args.K == (uint32_t)M)
+                    done = !__any(row_half_keep_f32<M>(a, gpos, bits));
+            }
             if (!done) {
 #pragma unroll
                 for (int i = 0; i < M; i++)
@@ -332,10 +338,17 @@ __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs 
                     bits[i] = bytes4_to_bits(rowbytes[i]);
             }
         } else if constexpr (MODE == kDenseRow1D || MODE == kDenseRow1DAbsorb) {
+            bool done = false;
+            if constexpr (DT == kF32 && M == 16) {
+                if (2u * args.K == (uint32_t)M)
+                    done = !__any(row_half_keep_f32<M>(a, gpos, bits));
+            }
+            if (!done) {
 #pragma unroll
-            for (int i = 0; i < M; i++)
-                bits[i] = (1u << C) - 1u;
-            row_rank_keep<M, C, Ge::G, Ge::B, false>(a, args.K, gpos, bits);
+                for (int i = 0; i < M; i++)
+                    bits[i] = (1u << C) - 1u;
+                row_rank_keep<M, C, Ge::G, Ge::B, false>(a, args.K, gpos, bits);
+            }
         } else {
             approx_keep<DT, M, false>(a, args.K, gpos, bits);
         }
