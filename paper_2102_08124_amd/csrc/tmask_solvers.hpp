@@ -450,7 +450,7 @@ __device__ __forceinline__ void exact_counts(const uint32_t (&xcol)[CL], uint32_
 // multiply-add (step < 2^23, counts <= M), the full 32-bit multiply runs at a quarter of the rate; the excess is
 // taken as half the sum of |count - K| (the counts of a block always add up to M*K), one instruction per row.
 // GENERAL: any 0 < K < M, the same in every lane (the threshold then comes from a full sort of the column's keys and a
-// register read at that index; 38 instead of 12 instructions at M = 8, 126 instead of 91 at M = 16); otherwise K = M/2.
+// register read at that index; 24 instead of 12 instructions at M = 8, 91 instead of 60 at M = 16); otherwise K = M/2.
 template <int M, int CL, int G, bool GENERAL = false>
 __device__ __forceinline__ uint32_t exact_priced_start(const int (&cost)[M][CL], uint32_t gpos, uint32_t (&xcol)[CL],
                                                        uint32_t k_general = 0)
