@@ -217,8 +217,9 @@ __global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
     }
 }
 
-// tmask_approx for bf16 with N = M/2, M = 8 or 16: thresholds from min/max networks on unique keys.
-template <int M, int FMT>
+// tmask_approx for bf16 with N = M/2, M = 8 or 16: thresholds from min/max networks on unique keys.  GENERAL (M = 8):
+// any N, the threshold read from the sorted line at index K = M - N (8192^2 3:8: 63 us in the rank form).
+template <int M, int FMT, bool GENERAL = false>
 __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchArgs args)
 {
     using Ge = Geo<kBF16, M>;
@@ -239,17 +240,17 @@ __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchAr
         if constexpr (FMT == kMaskU8) {
             char *mb = (char *)md.mask + (size_t)pos.br * M * md.mask_ld + (size_t)pos.sc * 8;
             const uint32_t mld = md.mask_ld;
-            acc = approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+            acc = approx_half_bf16<M, GENERAL>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
                 u32x2 v;
                 v.x = b0;
                 v.y = b1;
                 stream_store(v, (u32x2 *)(mb + (size_t)i * mld));
-            });
+            }, args.K);
         } else {
             uint32_t bits[M];
-            acc = approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+            acc = approx_half_bf16<M, GENERAL>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
                 bits[i] = bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4);
-            });
+            }, args.K);
             store_mask<kBF16, M, kMaskBits>(md, pos, bits);
         }
     }
@@ -289,16 +290,17 @@ __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs 
     const StripPos pos = strip_pos(md, s);
     uint32_t bits[M];                  // bit c = column c of the lane's strip kept
     u32x4 raw[M];
-    if constexpr ((HALFN || ROWHALF) && DT == kBF16 && M >= 8) {
+    constexpr bool GEN8 = MODE == kDenseApprox && DT == kBF16 && M == 8;   // any N at bf16 M = 8: threshold form too
+    if constexpr ((HALFN || ROWHALF || GEN8) && DT == kBF16 && M >= 8) {
         const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * 8) * 2;
         const size_t row_bytes = (size_t)md.ld * 2;
 #pragma unroll
         for (int i = 0; i < M; i++)
             raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
-        if constexpr (HALFN) {
-            (void)approx_half_bf16<M>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
+        if constexpr (HALFN || GEN8) {
+            (void)approx_half_bf16<M, GEN8>(raw, gpos, [&](int i, uint32_t b0, uint32_t b1) {
                 bits[i] = bytes4_to_bits(b0) | (bytes4_to_bits(b1) << 4);
-            });
+            }, args.K);
         } else {
             row_half_keep_bf16<M>(raw, gpos, bits);
         }
@@ -1041,6 +1043,8 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<8, kMaskU8> : approx_sel_bf16_kernel<8, kMaskBits>;
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 16 && N == 8)
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<16, kMaskU8> : approx_sel_bf16_kernel<16, kMaskBits>;
+    if (SOLVER == kSolveApprox && dt == kBF16 && M == 8 && N != 4)
+        kern = mf == kMaskU8 ? approx_sel_bf16_kernel<8, kMaskU8, true> : approx_sel_bf16_kernel<8, kMaskBits, true>;
     // the exact kernel for bf16 8:16 gives a lane half a strip: twice the workgroups
     const uint32_t unit_split = (SOLVER == kSolveExact && exact_half_strips(dt, M)) ? 2u : 1u;
     hipStream_t stream = (hipStream_t)stream_;

@@ -57,7 +57,7 @@ def test_approx_bit_exact_ragged(kind, N, M, fmt):
         assert obj[0] == pytest.approx(oobj, rel=1e-5)
 
 
-@pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (2, 8), (6, 8), (3, 16), (12, 16)])
+@pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (1, 8), (2, 8), (3, 8), (5, 8), (6, 8), (7, 8), (3, 16), (12, 16)])
 def test_approx_other_n(N, M):
     for kind in ("f32", "bf16"):
         w = _inputs(kind, 3 * M, 512, seed=1100 + N)
