@@ -222,10 +222,14 @@ __device__ __forceinline__ void middle_pair_row16(uint32_t (&s)[4], uint32_t gpo
 
 // a[i][c] = magnitude keys of the lane's strip (4 columns).  Fills bits[i] (bit c = keep) and the
 // kept sum; returns true if some line had a tie across its cut (result then invalid).
-template <int M>
+// GENERAL (M = 8 only): any number K of pruned entries per line, the same in every lane: the line's eight keys are
+// sorted, t = the (K+1)-th smallest and u = the K-th smallest are read at a register index that every lane shares.
+template <int M, bool GENERAL = false>
 __device__ __forceinline__ bool approx_half_f32(const uint32_t (&a)[M][4], uint32_t gpos, uint32_t (&rowbytes)[M],
-                                                float &sum)
+                                                float &sum, uint32_t k_general = 0)
 {
+    static_assert(!GENERAL || M == 8, "a line of eight keys: one lane's column, two lanes' row");
+    const uint32_t kidx = GENERAL ? (__builtin_amdgcn_readfirstlane(k_general) & 7u) : 0u;
     constexpr int H = M / 2;
     uint32_t tcol[4];
     bool tie = false;
@@ -237,7 +241,14 @@ __device__ __forceinline__ bool approx_half_f32(const uint32_t (&a)[M][4], uint3
             lo[i] = a[i][c];
             hi[i] = a[H + i][c];
         }
-        middle_pair<H>(lo, hi, tcol[c], u);
+        if constexpr (GENERAL) {
+            uint32_t srt[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            sort_asc<8>(srt);
+            tcol[c] = srt[kidx];
+            u = srt[(kidx - 1u) & 7u];
+        } else {
+            middle_pair<H>(lo, hi, tcol[c], u);
+        }
         tie |= tcol[c] == u;
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -246,7 +257,12 @@ __device__ __forceinline__ bool approx_half_f32(const uint32_t (&a)[M][4], uint3
     for (int i = 0; i < M; i++) {
         uint32_t s[4] = {a[i][0], a[i][1], a[i][2], a[i][3]};
         uint32_t trow, u;
-        if constexpr (M == 8)
+        if constexpr (GENERAL) {
+            uint32_t srt[8] = {s[0], s[1], s[2], s[3], quad_xor<1>(s[0]), quad_xor<1>(s[1]), quad_xor<1>(s[2]), quad_xor<1>(s[3])};
+            sort_asc<8>(srt);
+            trow = srt[kidx];
+            u = srt[(kidx - 1u) & 7u];
+        } else if constexpr (M == 8)
             middle_pair_row8(s, trow, u);
         else
             middle_pair_row16(s, gpos, trow, u);

@@ -108,7 +108,8 @@ __global__ __launch_bounds__(kThreads) void approx24_kernel(const BatchArgs args
 
 // tmask_approx for fp32 with N = M/2, M = 8 or 16: thresholds on magnitudes; a wavefront in which some
 // line has a tie across its cut redoes its strips with the form that resolves ties by position (uniform branch).
-template <int M, int FMT>
+// GENERAL (M = 8): any N, thresholds read from the sorted line; ties send the wavefront to the rank form.
+template <int M, int FMT, bool GENERAL = false>
 __global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArgs args)
 {
     using Ge = Geo<kF32, M>;
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArg
         u32x4 raw[M];
         load_strip<kF32, M>(md, pos, a, raw);
         uint32_t rowbytes[M];
-        const bool tie = approx_half_f32<M>(a, gpos, rowbytes, acc);
+        const bool tie = approx_half_f32<M, GENERAL>(a, gpos, rowbytes, acc, args.K);
         uint32_t bits[M];
         // Some cut among equal values (a matrix full of zeros, say).  M = 8: the form that sorts them out by position
         // (8192^2 with 90 % zeros: 80 -> 60 us).  M = 16: the rank form; the other one takes the kernel from 119 to
@@ -132,10 +133,10 @@ __global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArg
         // saves here (165 -> 118 us).
         bool stored = false;
         if (__any(tie)) {
-            if constexpr (M == 8) {
+            if constexpr (M == 8 && !GENERAL) {
                 approx_half_f32_ties<M>(a, gpos, rowbytes, acc);
             } else {
-                approx_keep<kF32, M, (M >= 16 && FMT == kMaskBits)>(a, (uint32_t)(M / 2), gpos, bits);
+                approx_keep<kF32, M, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
                 acc = kept_sum<M, 4>(a, bits);
                 store_mask<kF32, M, FMT>(md, pos, bits);
                 stored = true;
@@ -1039,6 +1040,8 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         kern = mf == kMaskU8 ? approx_sel_f32_kernel<8, kMaskU8> : approx_sel_f32_kernel<8, kMaskBits>;
     if (SOLVER == kSolveApprox && dt == kF32 && M == 16 && N == 8)
         kern = mf == kMaskU8 ? approx_sel_f32_kernel<16, kMaskU8> : approx_sel_f32_kernel<16, kMaskBits>;
+    if (SOLVER == kSolveApprox && dt == kF32 && M == 8 && N != 4)
+        kern = mf == kMaskU8 ? approx_sel_f32_kernel<8, kMaskU8, true> : approx_sel_f32_kernel<8, kMaskBits, true>;
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 8 && N == 4)
         kern = mf == kMaskU8 ? approx_sel_bf16_kernel<8, kMaskU8> : approx_sel_bf16_kernel<8, kMaskBits>;
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 16 && N == 8)

@@ -59,7 +59,9 @@ def test_approx_bit_exact_ragged(kind, N, M, fmt):
 
 @pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (1, 8), (2, 8), (3, 8), (5, 8), (6, 8), (7, 8), (3, 16), (12, 16)])
 def test_approx_other_n(N, M):
-    for kind in ("f32", "bf16"):
+    # "ties": the threshold forms for any N at M = 8 must notice cuts among equal values (fp32) or settle them by
+    # position (bf16)
+    for kind in ("f32", "bf16", "ties", "ties_bf16"):
         w = _inputs(kind, 3 * M, 512, seed=1100 + N)
         (mask,), obj = run_masks(tm.tmask_approx, [w], N, M)
         omask, oobj = oracle.approx(w, N, M)
