@@ -121,9 +121,13 @@ __device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_
 
 // The row half alone (structured N:M pruning along rows at N = M/2): bit c of bits[i] = entry (i, c) of the lane's
 // strip is among the N heaviest of its row group under the (magnitude, position) order.
-template <int M>
-__device__ __forceinline__ void row_half_keep_bf16(const u32x4 (&raw)[M], uint32_t gpos, uint32_t (&bits)[M])
+// GENERAL (M = 8): any N, the threshold read from the sorted row group at index k_general = M - N.
+template <int M, bool GENERAL = false>
+__device__ __forceinline__ void row_half_keep_bf16(const u32x4 (&raw)[M], uint32_t gpos, uint32_t (&bits)[M],
+                                                   uint32_t k_general = 0)
 {
+    static_assert(!GENERAL || M == 8, "a whole row group in one lane");
+    const uint32_t kidx = GENERAL ? (__builtin_amdgcn_readfirstlane(k_general) & 7u) : 0u;
     const uint32_t j0 = (M == 16) ? gpos * 8u : 0u;
 #pragma unroll
     for (int i = 0; i < M; i++) {
@@ -132,7 +136,14 @@ __device__ __forceinline__ void row_half_keep_bf16(const u32x4 (&raw)[M], uint32
         for (int c = 0; c < 8; c++)
             a[c] = bf16_mag_hi(raw[i], c) | (j0 + (uint32_t)c);
         uint32_t trow;
-        if constexpr (M == 8) {
+        if constexpr (GENERAL) {
+            uint32_t srt[8];
+#pragma unroll
+            for (int c = 0; c < 8; c++)
+                srt[c] = a[c];
+            sort_asc<8>(srt);
+            trow = srt[kidx];
+        } else if constexpr (M == 8) {
             uint32_t lo[4] = {a[0], a[1], a[2], a[3]};
             uint32_t hi[4] = {a[4], a[5], a[6], a[7]};
             trow = upper_half_min<4>(lo, hi);

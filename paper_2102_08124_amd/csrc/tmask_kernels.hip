@@ -57,6 +57,9 @@ __global__ __launch_bounds__(kThreads) void mask_kernel(const BatchArgs args)
                 if (2u * args.K == (uint32_t)M) {      // N = M/2: thresholds on unique keys instead of pairwise ranks
                     row_half_keep_bf16<M>(raw, gpos, bits);
                     done = true;
+                } else if constexpr (M == 8) {         // any N: the sorted row group read at index K
+                    row_half_keep_bf16<M, true>(raw, gpos, bits, args.K);
+                    done = true;
                 }
             }
             if constexpr (DT == kF32 && M == 16) {

@@ -338,7 +338,7 @@ def test_argument_errors_leave_outputs_untouched():
 # ---------------------------------------------------------------- 1-D (non-transposable) pruning
 
 @pytest.mark.parametrize("fmt", FMTS)
-@pytest.mark.parametrize("N,M", NM + [(1, 4), (3, 4), (5, 8), (3, 16)])
+@pytest.mark.parametrize("N,M", NM + [(1, 4), (3, 4), (2, 8), (5, 8), (7, 8), (3, 16)])
 @pytest.mark.parametrize("kind", ["f32", "bf16", "ties", "ties_bf16", "special"])
 def test_prune_1d_bit_exact_ragged(kind, N, M, fmt):
     w = _inputs(kind, 5 * M, 1008, seed=1900 + M)
