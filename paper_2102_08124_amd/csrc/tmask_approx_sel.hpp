@@ -42,13 +42,13 @@ __device__ __forceinline__ uint32_t bf16_mag_hi(const u32x4 &r, int c)
 // Returns the kept magnitudes' sum; emit_row(i, b0, b1) receives the keep flags of row i as 0/1 bytes.
 // Keys are built where they are used (column keys carry the row index, row keys the column index)
 // so that only the raw rows stay live between the two passes.
-// GENERAL (M = 8 only): any number K of pruned entries per line, the same in every lane; the threshold is then the
-// (K+1)-th smallest key of the line, read from the sorted line at a register index that is the same in every lane.
+// GENERAL: any number K of pruned entries per line, the same in every lane; the threshold is then the (K+1)-th
+// smallest key of the line, read from the sorted line at a register index that is the same in every lane.  A row of
+// sixteen lies in two lanes: each sorts its eight keys, takes the neighbour's sorted eight and merges the two runs.
 template <int M, bool GENERAL = false, typename EmitRow>
 __device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_t gpos, EmitRow emit_row, uint32_t k_general = 0)
 {
-    static_assert(!GENERAL || M == 8, "a whole line of eight keys in one lane");
-    const uint32_t kidx = GENERAL ? (__builtin_amdgcn_readfirstlane(k_general) & 7u) : 0u;
+    const uint32_t kidx = GENERAL ? (__builtin_amdgcn_readfirstlane(k_general) & (uint32_t)(M - 1)) : 0u;
     constexpr int H = M / 2;
     // column thresholds: all M rows of a column are in the lane; key = |w| << 16 | i
     uint32_t tcol[8];
@@ -61,8 +61,13 @@ __device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_
             b[i] = bf16_mag_hi(raw[H + i], c) | (uint32_t)(H + i);
         }
         if constexpr (GENERAL) {
-            uint32_t srt[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-            sort_asc<8>(srt);
+            uint32_t srt[M];
+#pragma unroll
+            for (int i = 0; i < H; i++) {
+                srt[i] = a[i];
+                srt[H + i] = b[i];
+            }
+            sort_asc<M>(srt);
             tcol[c] = srt[kidx];
         } else {
             tcol[c] = upper_half_min<H>(a, b);
@@ -90,7 +95,18 @@ __device__ __forceinline__ float approx_half_bf16(const u32x4 (&raw)[M], uint32_
             for (int c = 0; c < 8; c++)
                 srt[c] = a[c];
             sort_asc<8>(srt);
-            trow = srt[kidx];
+            if constexpr (M == 8) {
+                trow = srt[kidx];
+            } else {
+                uint32_t both[16];
+#pragma unroll
+                for (int c = 0; c < 8; c++) {
+                    both[c] = srt[c];
+                    both[8 + c] = quad_xor<1>(srt[c]);
+                }
+                merge_sorted8_asc(both);
+                trow = both[kidx];
+            }
         } else if constexpr (M == 8) {
             uint32_t lo[4] = {a[0], a[1], a[2], a[3]};
             uint32_t hi[4] = {a[4], a[5], a[6], a[7]};

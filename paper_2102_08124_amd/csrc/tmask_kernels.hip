@@ -221,8 +221,8 @@ __global__ __launch_bounds__(kThreads) void exact24_kernel(const BatchArgs args)
     }
 }
 
-// tmask_approx for bf16 with N = M/2, M = 8 or 16: thresholds from min/max networks on unique keys.  GENERAL (M = 8):
-// any N, the threshold read from the sorted line at index K = M - N (8192^2 3:8: 63 us in the rank form).
+// tmask_approx for bf16 with N = M/2, M = 8 or 16: thresholds from min/max networks on unique keys.  GENERAL: any N,
+// the threshold read from the sorted line at index K = M - N (8192^2 3:8: 40 us; 63 us in the rank form).
 template <int M, int FMT, bool GENERAL = false>
 __global__ __launch_bounds__(kThreads) void approx_sel_bf16_kernel(const BatchArgs args)
 {
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void approx_dense_kernel(const BatchArgs 
     const StripPos pos = strip_pos(md, s);
     uint32_t bits[M];                  // bit c = column c of the lane's strip kept
     u32x4 raw[M];
-    constexpr bool GEN8 = MODE == kDenseApprox && DT == kBF16 && M == 8;   // any N at bf16 M = 8: threshold form too
+    constexpr bool GEN8 = MODE == kDenseApprox && DT == kBF16 && M >= 8;   // any N at bf16 M = 8, 16: threshold form too
     if constexpr ((HALFN || ROWHALF || GEN8) && DT == kBF16 && M >= 8) {
         const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * 8) * 2;
         const size_t row_bytes = (size_t)md.ld * 2;
@@ -997,9 +997,10 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
     } else if (want_obj && (rc = check_workspace(mats, n_mats, M, ws, ws_bytes))) {
         return rc;
     }
-    // N != M/2 at M = 16, Algorithm 1 and row pruning: the strip kernels have only their rank form there; the
-    // column-per-lane kernels take a threshold from a sorting network
-    const bool general_n = 2 * N != M && M == 16 && SOLVER != kSolveExact;
+    // N != M/2 at M = 16, Algorithm 1 and row pruning: the strip kernels have only their rank form there (except
+    // Algorithm 1 at bf16, where keys are unique and a row lies in two lanes); the column-per-lane kernels take a
+    // threshold from a sorting network
+    const bool general_n = 2 * N != M && M == 16 && SOLVER != kSolveExact && !(SOLVER == kSolveApprox && dt == kBF16);
     if (!aligned || general_n)     // also M = 32, or a matrix that the 16-byte strips cannot read
         return cw_run_mask(SOLVER == kSolveApprox ? 0 : SOLVER == kSolveExact ? 1 : 2, mats, n_mats, dt, N, M, mf, ws,
                            (hipStream_t)stream_);
@@ -1043,6 +1044,8 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
         kern = mf == kMaskU8 ? approx_sel_f32_kernel<8, kMaskU8> : approx_sel_f32_kernel<8, kMaskBits>;
     if (SOLVER == kSolveApprox && dt == kF32 && M == 16 && N == 8)
         kern = mf == kMaskU8 ? approx_sel_f32_kernel<16, kMaskU8> : approx_sel_f32_kernel<16, kMaskBits>;
+    if (SOLVER == kSolveApprox && dt == kBF16 && M == 16 && N != 8)
+        kern = mf == kMaskU8 ? approx_sel_bf16_kernel<16, kMaskU8, true> : approx_sel_bf16_kernel<16, kMaskBits, true>;
     if (SOLVER == kSolveApprox && dt == kF32 && M == 8 && N != 4)
         kern = mf == kMaskU8 ? approx_sel_f32_kernel<8, kMaskU8, true> : approx_sel_f32_kernel<8, kMaskBits, true>;
     if (SOLVER == kSolveApprox && dt == kBF16 && M == 8 && N == 4)
@@ -1496,7 +1499,7 @@ static int run_mask_dense(const tmask_mask_dense_desc *descs, int n, tmask_dtype
         return fail(TMASK_ERR_NULL, "mask must be given for all matrices or for none (%d of %d have one)", with_mask, n);
     // Algorithm 1 with N != M/2 at M = 16: the strip kernels have only their rank form there (see run_mask); the
     // row modes are faster on the strips (8192^2 fp32 5:16 with absorption: 101 against 121 us)
-    if (!aligned || (2 * N != M && M == 16 && mode == kDenseApprox)) {
+    if (!aligned || (2 * N != M && M == 16 && mode == kDenseApprox && dt != kBF16)) {
         const bool absorb = mode == kDenseRow1DAbsorb || mode == kDenseRow1DHalfAbsorb;
         const bool rows_only = absorb || mode == kDenseRow1D || mode == kDenseRow1DHalf;
         return cw_run_dense(descs, n, (int)dt, N, M, (int)mf, absorb ? 2 : rows_only ? 1 : 0, (hipStream_t)hip_stream);

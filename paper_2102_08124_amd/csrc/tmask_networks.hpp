@@ -71,6 +71,16 @@ __device__ __forceinline__ void sort_asc<8>(uint32_t (&v)[8])
     sort3(v[2], v[3], v[5]); sort3(v[5], v[6], v[7]); sort3(v[3], v[4], v[5]); sort3(v[1], v[2], v[3]);
 }
 
+// v[0..8) and v[8..16), each ascending -> all of v ascending: thirteen three-key sorts and two compare-exchanges (43
+// instructions; Batcher's odd-even merge of two runs of eight takes 25 compare-exchanges, 50 instructions).
+__device__ __forceinline__ void merge_sorted8_asc(uint32_t (&v)[16])
+{
+    sort3(v[0], v[4], v[12]); sort3(v[1], v[5], v[13]); sort3(v[2], v[6], v[14]); sort3(v[7], v[14], v[15]);
+    sort3(v[3], v[7], v[11]); sort3(v[2], v[6], v[10]); sort3(v[1], v[5], v[9]); sort3(v[4], v[6], v[8]);
+    sort3(v[0], v[2], v[4]); sort3(v[3], v[5], v[6]); sort3(v[7], v[8], v[9]); sort3(v[9], v[10], v[12]);
+    sort3(v[11], v[12], v[13]); cmpx(v[3], v[4]); cmpx(v[1], v[2]);
+}
+
 // Sixteen keys: both halves by sort_asc<8>, then a merge of two sorted runs of eight out of thirteen three-key sorts and
 // two compare-exchanges (found and checked the same way, on the 81 zero-one inputs with sorted halves): 91 instructions
 // against 126 for Batcher's odd-even merge sort.
@@ -90,10 +100,7 @@ __device__ __forceinline__ void sort_asc<16>(uint32_t (&v)[16])
         v[i] = a[i];
         v[8 + i] = b[i];
     }
-    sort3(v[0], v[4], v[12]); sort3(v[1], v[5], v[13]); sort3(v[2], v[6], v[14]); sort3(v[7], v[14], v[15]);
-    sort3(v[3], v[7], v[11]); sort3(v[2], v[6], v[10]); sort3(v[1], v[5], v[9]); sort3(v[4], v[6], v[8]);
-    sort3(v[0], v[2], v[4]); sort3(v[3], v[5], v[6]); sort3(v[7], v[8], v[9]); sort3(v[9], v[10], v[12]);
-    sort3(v[11], v[12], v[13]); cmpx(v[3], v[4]); cmpx(v[1], v[2]);
+    merge_sorted8_asc(v);
 }
 
 // v[0..N/2) ascending followed by v[N/2..N) descending (a bitonic sequence) -> all of v ascending: log2 N rounds of

@@ -57,7 +57,8 @@ def test_approx_bit_exact_ragged(kind, N, M, fmt):
         assert obj[0] == pytest.approx(oobj, rel=1e-5)
 
 
-@pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (1, 8), (2, 8), (3, 8), (5, 8), (6, 8), (7, 8), (3, 16), (12, 16)])
+@pytest.mark.parametrize("N,M", [(1, 4), (3, 4), (1, 8), (2, 8), (3, 8), (5, 8), (6, 8), (7, 8), (1, 16), (3, 16), (5, 16), (12, 16),
+                                 (15, 16)])
 def test_approx_other_n(N, M):
     # "ties": the threshold forms for any N at M = 8 must notice cuts among equal values (fp32) or settle them by
     # position (bf16)

@@ -9,10 +9,10 @@ import numpy as np
 HEADER = os.path.join(os.path.dirname(__file__), "..", "paper_2102_08124_amd", "csrc", "tmask_networks.hpp")
 
 
-def _body(n):
+def _body(n, name=None):
     src = open(HEADER).read()
-    m = re.search(r"void sort_asc<%d>\(uint32_t \(&v\)\[%d\]\)\s*\{(.*?)\n\}" % (n, n), src, re.S)
-    assert m, "sort_asc<%d> not found" % n
+    m = re.search(r"void %s\(uint32_t \(&v\)\[%d\]\)\s*\{(.*?)\n\}" % (name or "sort_asc<%d>" % n, n), src, re.S)
+    assert m, "%s not found" % (name or "sort_asc<%d>" % n)
     return m.group(1)
 
 
@@ -48,8 +48,9 @@ def test_sort4_and_sort8_sort_every_zero_one_input():
 
 def test_sort16_sorts_every_zero_one_input_and_random_keys_with_repeats():
     body = _body(16)
-    assert body.count("sort_asc<8>(") == 2                              # both halves first ...
-    merge = _ops(body)                                                  # ... then the merge on v[0..16)
+    assert body.count("sort_asc<8>(") == 2 and body.count("merge_sorted8_asc(v)") == 1   # both halves, then the merge
+    assert body.index("merge_sorted8_asc(v)") > body.rindex("sort_asc<8>(")
+    merge = _ops(_body(16, "merge_sorted8_asc"))
     assert sum(3 if len(o) == 3 else 2 for o in merge) == 43
     sort8 = _ops(_body(8))
     halves = sort8 + [tuple(i + 8 for i in o) for o in sort8]
