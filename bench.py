@@ -694,7 +694,7 @@ def main():
                        "8 rotating buffer sets")
         st2["value"] = st2["weights"] / (st2["ms_per_step"] * 1e-3)
         # the same step at 4:8, the paper's transposable setting for M = 8: what the exact mask costs on small layers
-        names48 = {"approx": "approx_sel_f32_kernel<8, 0>", "exact": "exact_balanced_kernel<0, 8, 0, false>",
+        names48 = {"approx": "approx_sel_f32_kernel<8, 0, false>", "exact": "exact_balanced_kernel<0, 8, 0, false>",
                    "pack": "pack48_f32_kernel<0, 64, false, false, PackArgs>", "score": "score_kernel<0, 8, 0>"}
         st48 = step_section(tm, torch, T, m2, 4, 8, 100, 10, 8, 4, names48, "resnet50_f32_4of8")
         st48["exact_over_approx_call"] = st48["kernels"]["exact"]["call_ms"] / st48["kernels"]["approx"]["call_ms"]

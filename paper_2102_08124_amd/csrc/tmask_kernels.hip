@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void approx24_kernel(const BatchArgs args
 // line has a tie across its cut redoes its strips with the form that resolves ties by position (uniform branch).
 // GENERAL (M = 8): any N, thresholds read from the sorted line; ties send the wavefront to the rank form.
 template <int M, int FMT, bool GENERAL = false>
-__global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArgs args)
+__global__ __launch_bounds__(kThreads, (M == 16 && FMT == kMaskBits) ? 4 : 1) void approx_sel_f32_kernel(const BatchArgs args)
 {
     using Ge = Geo<kF32, M>;
     __shared__ double red[kThreads / 64];
@@ -141,22 +141,27 @@ __global__ __launch_bounds__(kThreads) void approx_sel_f32_kernel(const BatchArg
             } else {
                 approx_keep<kF32, M, (M >= 16 && FMT == kMaskBits)>(a, args.K, gpos, bits);
                 acc = kept_sum<M, 4>(a, bits);
-                store_mask<kF32, M, FMT>(md, pos, bits);
+                if constexpr (FMT == kMaskU8)
+                    store_mask<kF32, M, FMT>(md, pos, bits);
                 stored = true;
             }
         }
-        if (!stored) {
-            if constexpr (FMT == kMaskU8) {
+        if constexpr (FMT == kMaskU8) {
+            if (!stored) {
                 char *mb = (char *)md.mask + (size_t)pos.br * M * md.mask_ld + (size_t)pos.sc * 4;
 #pragma unroll
                 for (int i = 0; i < M; i++)
                     stream_store(rowbytes[i], (uint32_t *)(mb + (size_t)i * md.mask_ld));
-            } else {
+            }
+        } else {
+            // bit masks leave through one place (the cross-lane assembly of a row's bytes is long code: twice it cost
+            // the M = 16 kernel a wavefront of occupancy)
+            if (!stored) {
 #pragma unroll
                 for (int i = 0; i < M; i++)
                     bits[i] = bytes4_to_bits(rowbytes[i]);
-                store_mask<kF32, M, kMaskBits>(md, pos, bits);
             }
+            store_mask<kF32, M, kMaskBits>(md, pos, bits);
         }
     }
     if (args.partials) {
