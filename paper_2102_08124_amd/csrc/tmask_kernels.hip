@@ -588,6 +588,86 @@ __global__ __launch_bounds__(kThreads) void score_kernel(const BatchArgs args)
     if constexpr (DT == kBF16 && M == 4 && FMT == kMaskU8) {
         if (s < md.n_strips)
             score_strip_bf16_m4(md, strip_pos(md, s), N, retained, total, kept, rowv, colv, rowne, colne);
+    } else if (M >= 16 && s < md.n_strips) {
+        // M = 16 (one block per lane group, B = 1): a row at a time, so that only the raw rows and the mask bits stay
+        // in registers (with every magnitude unpacked up front the bf16 8:16 kernel held 248 registers: two wavefronts
+        // per SIMD; now 94, 8192^2 bf16 8:16: 42 -> 39 us).  Same order of additions as below.  At M = 8 the form below is
+        // the faster one (it keeps more loads and additions in flight).
+        const StripPos pos = strip_pos(md, s);
+        u32x4 raw[M];
+        uint32_t bits[M];
+        const char *base = (const char *)md.w + ((size_t)pos.br * M * md.ld + (size_t)pos.sc * C) * Ge::ES;
+        const size_t row_bytes = (size_t)md.ld * Ge::ES;
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            raw[i] = __builtin_nontemporal_load((const u32x4 *)(base + i * row_bytes));
+        load_mask<DT, M, FMT>(md, pos, bits);
+        // opaque from here on: otherwise every bit test below is rewritten as a test on the intermediate values of the
+        // byte-to-bit conversion, all of which then stay in registers
+#pragma unroll
+        for (int i = 0; i < M; i++)
+            asm volatile("" : "+v"(bits[i]));
+        float tot = 0.f, blk = 0.f;
+        uint32_t colcnt[C];
+#pragma unroll
+        for (int c = 0; c < C; c++)
+            colcnt[c] = 0;
+#pragma unroll
+        for (int i = 0; i < M; i++) {
+            u32x4 r = raw[i];
+            asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w));    // unpack here, not ahead of the loop
+            const uint32_t d[4] = {r.x, r.y, r.z, r.w};
+            float m[C];
+            if constexpr (DT == kF32) {
+#pragma unroll
+                for (int c = 0; c < 4; c++)
+                    m[c] = __uint_as_float(d[c] & 0x7FFFFFFFu);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    m[2 * c] = __uint_as_float((d[c] << 16) & 0x7FFF0000u);
+                    m[2 * c + 1] = __uint_as_float(d[c] & 0x7FFF0000u);
+                }
+            }
+            uint32_t cnt = __builtin_popcount(bits[i] & ((1u << C) - 1u));
+            if constexpr (Ge::G >= 2)
+                cnt = quad_xor_sum<1>(cnt);
+            if constexpr (Ge::G == 4)
+                cnt = quad_xor_sum<2>(cnt);
+            if (gpos == 0) {
+                rowv += cnt > N ? 1u : 0u;
+                rowne += cnt != N ? 1u : 0u;
+            }
+#pragma unroll
+            for (int c = 0; c < C; c++) {
+                const bool k = (bits[i] >> c) & 1u;
+                tot += m[c];
+                blk += k ? m[c] : 0.f;
+                colcnt[c] += k ? 1u : 0u;
+            }
+            // the row's contributions are added here and now (left alone, the additions sink to the end of the kernel
+            // and every magnitude stays in a register until then)
+            asm volatile("" : "+v"(tot), "+v"(blk), "+v"(rowv), "+v"(rowne));
+#pragma unroll
+            for (int c = 0; c < C; c++)
+                asm volatile("" : "+v"(colcnt[c]));
+        }
+        total = tot;
+        retained = blk;
+#pragma unroll
+        for (int c = 0; c < C; c++) {
+            kept += colcnt[c];
+            colv += colcnt[c] > N ? 1u : 0u;
+            colne += colcnt[c] != N ? 1u : 0u;
+        }
+        if constexpr (Ge::G >= 2)
+            blk += __uint_as_float(quad_xor<1>(__float_as_uint(blk)));
+        if constexpr (Ge::G == 4)
+            blk += __uint_as_float(quad_xor<2>(__float_as_uint(blk)));
+        if (md.aux && gpos == 0) {
+            const uint32_t bpr = md.spr / Ge::G;        // blocks per block-row
+            stream_store(blk, (float *)md.aux + (size_t)pos.br * bpr + pos.sc / Ge::G);
+        }
     } else if (s < md.n_strips) {
         const StripPos pos = strip_pos(md, s);
         uint32_t a[M][C];
