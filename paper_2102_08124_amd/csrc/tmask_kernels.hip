@@ -1321,6 +1321,7 @@ static pack_kernel_t pick_pack_kernel(int dt, int M, int mf, int N)
         TMASK_PICK(kBF16, 4, kMaskU8) TMASK_PICK(kBF16, 8, kMaskU8) TMASK_PICK(kBF16, 16, kMaskU8)
         TMASK_PICK(kF32, 4, kMaskBits) TMASK_PICK(kF32, 8, kMaskBits) TMASK_PICK(kF32, 16, kMaskBits)
         TMASK_PICK(kBF16, 4, kMaskBits) TMASK_PICK(kBF16, 8, kMaskBits) TMASK_PICK(kBF16, 16, kMaskBits)
+        TMASK_PICK(kF32, 32, kMaskU8) TMASK_PICK(kBF16, 32, kMaskU8) TMASK_PICK(kF32, 32, kMaskBits) TMASK_PICK(kBF16, 32, kMaskBits)
 #undef TMASK_PICK
     }
 #define TMASK_PICK(DT, MM, FM) \
@@ -1340,7 +1341,8 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
     int rc = check_common(descs, n, (int)dt, N, M, (int)mf);
     if (rc)
         return rc;
-    bool aligned = (M != 32);
+    // M = 32: the tiled kernel at 16:32 (a tile row's position bits are then whole bytes), the column-per-lane one else
+    bool aligned = (M != 32) || (N == 16);
     for (int i = 0; i < n; i++) {
         const tmask_pack_desc &p = descs[i];
         const HostMat h{p.w, p.rows, p.cols, p.ld, const_cast<void *>(p.mask), p.mask_ld, nullptr};
@@ -1351,6 +1353,8 @@ int tmask_apply_pack(const tmask_pack_desc *descs, int n, tmask_dtype dt, int N,
         if (((uintptr_t)p.vals | (uintptr_t)p.valsT) % elem_size((int)dt))
             return fail(TMASK_ERR_ALIGN, "matrix %d: vals and valsT must be aligned to the element size", i);
         if (((uintptr_t)p.vals & 3) || ((uintptr_t)p.valsT & 3))
+            aligned = false;
+        if (M == 32 && ((uintptr_t)p.vals & 15))     // its row groups leave as 16-byte stores only
             aligned = false;
     }
     if (!aligned)

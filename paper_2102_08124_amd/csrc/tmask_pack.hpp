@@ -105,7 +105,7 @@ __device__ __forceinline__ void tile_coords(uint32_t tl, uint32_t tiles_x, uint3
 
 template <int M>
 struct Log2 {
-    static constexpr int v = (M == 4) ? 2 : (M == 8) ? 3 : 4;
+    static constexpr int v = (M == 4) ? 2 : (M == 8) ? 3 : (M == 16) ? 4 : 5;
 };
 
 // Which positions of a group of M fill its N slots.  kbits = keep flags (bit p = position p).
@@ -120,7 +120,7 @@ __device__ __forceinline__ void choose_slots(uint32_t kbits, uint32_t N, uint32_
         sel &= ~(0x80000000u >> __builtin_clz(sel));
         cnt--;
     }
-    uint32_t z = ~sel & ((1u << M) - 1u), f = 0;
+    uint32_t z = ~sel & (M == 32 ? 0xFFFFFFFFu : ((1u << (M & 31)) - 1u)), f = 0;
     for (uint32_t need = N - cnt; need > 0; need--) {   // approximate masks: usually zero to two rounds
         const uint32_t low = z & (0u - z);
         f |= low;
@@ -175,9 +175,15 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
     constexpr int NMAX = NN ? NN : M - 1;      // slots per group the staging must hold
     constexpr int IDXW = (GPT * NMAX * IB + 31) / 32 + 2;
     constexpr int IDXTW = (BPT * NMAX * IB + 31) / 32 + 2 + 1;
-    constexpr int NRU = TR * GPT / kThreads;   // row-direction units per thread
-    constexpr int NCU = BPT * TC / kThreads;   // column-direction units per thread
-    static_assert(TR * GPT % kThreads == 0 && BPT * TC % kThreads == 0, "units must tile the workgroup");
+    constexpr int NRU = (TR * GPT + kThreads - 1) / kThreads;   // row-direction units per thread
+    constexpr int NCU = (BPT * TC + kThreads - 1) / kThreads;   // column-direction units per thread
+    static_assert((TR * GPT % kThreads == 0 || TR * GPT < kThreads) && (BPT * TC % kThreads == 0 || BPT * TC < kThreads),
+                  "units tile the workgroup, or there are fewer of them than threads (fp32 at M = 32)");
+    // Position codes of a group: NN * IB bits.  Beyond 64 bits (16:32: 80) they are kept as two halves of NN / 2 slots,
+    // which go into the bit string as groups number 2g and 2g + 1 of half the width.
+    constexpr bool SPLIT = NN * IB > 64;
+    constexpr int HS = SPLIT ? NN / 2 : NN;    // slots per code word
+    static_assert(M < 32 || NN == 16, "M = 32 comes here at 16:32 only (whole bytes of position bits per tile row)");
 
     __shared__ __attribute__((aligned(16))) T V[TR][TC];   // masked tile
     __shared__ __attribute__((aligned(16))) uint8_t FN[TR][16];   // keep flags of each 16-byte chunk (C bits), 16 chunks per tile row
@@ -269,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
 #pragma unroll
         for (int k = 0; k < NRU; k++) {
             const uint32_t u = tid + k * kThreads, r = u / GPT, g = u % GPT;
-            if (r >= r_valid || g >= g_valid)
+            if (u >= (uint32_t)(TR * GPT) || r >= r_valid || g >= g_valid)
                 continue;   // outside the matrix: must not leave index bits in a row's padding
             uint32_t kb = 0;
             if constexpr (M >= C) {
@@ -282,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
             uint32_t sel, rem;
             choose_slots<M>(kb, N, sel, rem);
             T *dst = (T *)d.vals + (size_t)(row0 + r) * pitch + (size_t)(col0 / M + g) * N;
-            unsigned long long code = 0;
+            unsigned long long code = 0, code_hi = 0;
             uint32_t pend = 0;
             if constexpr (NN != 0 && (NN * ES) % 16 == 0) {
                 if ((((uintptr_t)d.vals | (pitch * ES)) & 15) == 0) {
@@ -300,15 +306,25 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
                             out[sl] = val;
                         else
                             out[sl / 2] |= val << (16 * (sl & 1));
-                        code |= (unsigned long long)p << (sl * IB);
+                        if (sl < HS)
+                            code |= (unsigned long long)p << (sl * IB);
+                        else
+                            code_hi |= (unsigned long long)p << ((sl - HS) * IB);
                     }
 #pragma unroll
                     for (int q = 0; q < NN * ES / 16; q++)
                         stream_store(u32x4{out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]}, (u32x4 *)dst + q);
-                    put_code<NN * IB>(IDX[r], g, code);
+                    if constexpr (SPLIT) {
+                        put_code<HS * IB>(IDX[r], 2u * g, code);
+                        put_code<HS * IB>(IDX[r], 2u * g + 1u, code_hi);
+                    } else {
+                        put_code<NN * IB>(IDX[r], g, code);
+                    }
                     continue;
                 }
             }
+            if constexpr (M == 32)
+                continue;   // not reached: the host sends 16:32 here only with vals aligned to 16 bytes
             for (uint32_t sl = 0; sl < N; sl++) {
                 const uint32_t p = (uint32_t)__builtin_ctz(rem);
                 rem &= rem - 1u;
@@ -331,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
 #pragma unroll
     for (int k = 0; k < NCU; k++) {
         const uint32_t u = tid + k * kThreads, b = u / TC, c = u % TC;
-        if (b >= b_valid || c >= c_valid)
+        if (u >= (uint32_t)(BPT * TC) || b >= b_valid || c >= c_valid)
             continue;
         uint32_t kb = 0;
 #pragma unroll
@@ -339,14 +355,17 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
             kb |= (((uint32_t)FN[b * M + p][c / C] >> (c % C)) & 1u) << p;
         uint32_t sel, rem;
         choose_slots<M>(kb, N, sel, rem);
-        unsigned long long code = 0;
+        unsigned long long code = 0, code_hi = 0;
         if constexpr (NN != 0) {
 #pragma unroll
             for (int sl = 0; sl < NN; sl++) {
                 const uint32_t p = (uint32_t)__builtin_ctz(rem);
                 rem &= rem - 1u;
                 OT[c][b * NN + sl] = ((sel >> p) & 1u) ? V[b * M + p][c] : (T)0;
-                code |= (unsigned long long)p << (sl * IB);
+                if (sl < HS)
+                    code |= (unsigned long long)p << (sl * IB);
+                else
+                    code_hi |= (unsigned long long)p << ((sl - HS) * IB);
             }
         } else {
             for (uint32_t sl = 0; sl < N; sl++) {
@@ -356,10 +375,14 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const PackArgs args)
                 code |= (unsigned long long)p << (sl * IB);
             }
         }
-        if constexpr (NN != 0)
+        if constexpr (SPLIT) {
+            put_code<HS * IB>(IDXT[c], 2u * b, code);
+            put_code<HS * IB>(IDXT[c], 2u * b + 1u, code_hi);
+        } else if constexpr (NN != 0) {
             put_code<NN * IB>(IDXT[c], b, code);
-        else
+        } else {
             lds_or_bits(IDXT[c], b * N * IB, code);
+        }
     }
     __syncthreads();
 

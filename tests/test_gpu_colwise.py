@@ -121,6 +121,26 @@ def test_m32_score_and_pack_match_oracle(dt, fmt):
             assert np.array_equal(g.view(np.uint8), t.view(np.uint8))
 
 
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_m32_tiled_pack_ragged_tiles_and_degenerate_masks(dt, fmt):
+    """16:32 on matrices aligned for 16-byte loads runs the tiled pack kernel (64 rows x 256 bytes per tile): tiles cut
+    by the matrix edge in both directions, padded rows, and masks that keep too many, too few, all or nothing."""
+    N, M = 16, 32
+    rng = np.random.default_rng(3650)
+    ws, masks = [], []
+    for k, (rows, cols) in enumerate([(32, 32), (64, 64), (96, 160), (160, 416), (32, 1056)]):
+        w = _inputs(dt, rows, cols, seed=3651 + k)
+        ws += [w, w, w]
+        masks += [(rng.random(w.shape) < 0.5).astype(np.uint8), np.zeros(w.shape, np.uint8), np.ones(w.shape, np.uint8)]
+    for pad in (0, 24):
+        got = run_pack(ws, masks, N, M, fmt, ld_pad=pad)
+        for k, (w, m) in enumerate(zip(ws, masks)):
+            want = oracle.apply_pack(w, m, N, M)
+            for g, t in zip(got[k], want):
+                assert np.array_equal(g.view(np.uint8), t.view(np.uint8)), (k, pad)
+
+
 def test_m32_approx_pack_and_dense_calls():
     N, M = 16, 32
     for dt in ("f32", "bf16"):
