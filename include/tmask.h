@@ -35,8 +35,8 @@
  *   cols*sizeof(element) multiples of 16 (ld, cols multiples of 4 for fp32, of 8 for bf16), a U8 mask pointer and
  *   mask_ld that are multiples of 4 (fp32) or 8 (bf16) bytes, packed value arrays 4-byte aligned (8-byte for the
  *   one-pass tmask_approx_pack kernels), dense outputs 16-byte aligned with a 16-byte pitch.  A call in which some
- *   matrix misses any of this, and every call with M = 32, runs on element-wise kernels instead (one lane per
- *   column of a block): correct for every layout above, bound by the vector ALU or by LDS traffic instead of by
+ *   matrix misses any of this, and every call with M = 32 (tmask_apply_pack at 16:32 with `vals` 16-byte aligned
+ *   excepted), runs on element-wise kernels instead (one lane per column of a block): correct for every layout above, bound by the vector ALU or by LDS traffic instead of by
  *   memory.
  *
  * Errors

@@ -1,4 +1,5 @@
-// tmask: the column-per-lane kernels.  They serve (a) M = 32 for every entry point, (b) M = 4, 8, 16 when a matrix
+// tmask: the column-per-lane kernels.  They serve (a) M = 32 for every entry point (the compression at 16:32 of aligned
+// matrices excepted: the tiled pack kernel takes it), (b) M = 4, 8, 16 when a matrix
 // misses the 16-byte alignment the strip kernels read with (only the method's own requirement is left: rows and cols
 // multiples of M, the masks being defined per M x M block; arXiv 2102.08124, Sec. 4) and (c) Algorithm 1 and row
 // pruning with N != M/2 at M = 16, where the strip kernels have only their rank form (Algorithm 1 at bf16 excepted: it
