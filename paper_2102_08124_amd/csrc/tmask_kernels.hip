@@ -446,9 +446,12 @@ struct ReduceArgs {
 // Second stage of the objective: workgroup m adds the partials of matrix m in a fixed order.  1024 threads: one
 // matrix can have hundreds of thousands of partials, and the loop is a chain of load latencies.
 constexpr int kReduceThreads = 1024;
+constexpr int kReduceThreadsSmall = 256;    // when no matrix of the launch has more than 512 partial results
 
-__global__ __launch_bounds__(kReduceThreads) void objective_reduce_kernel(const ReduceArgs args)
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void objective_reduce_kernel(const ReduceArgs args)
 {
+    constexpr int kReduceThreads = THREADS;           // shadows the file-scope constant inside this kernel
     __shared__ double red[kReduceThreads / 64];
     const uint32_t m = blockIdx.x;
     double *dst = args.objective[m];
@@ -485,6 +488,18 @@ __global__ __launch_bounds__(kReduceThreads) void objective_reduce_kernel(const 
             total += red[k];
         dst[0] = total;
     }
+}
+
+// One workgroup per matrix; 256 threads instead of 1024 when every matrix has at most 512 partial results.
+static void enqueue_objective_reduce(const ReduceArgs &rargs, int nb, hipStream_t stream)
+{
+    uint32_t most = 0;
+    for (int k = 0; k < nb; k++)
+        most = rargs.tile0[k + 1] - rargs.tile0[k] > most ? rargs.tile0[k + 1] - rargs.tile0[k] : most;
+    if (most <= 2 * kReduceThreadsSmall)
+        hipLaunchKernelGGL(objective_reduce_kernel<kReduceThreadsSmall>, dim3(nb), dim3(kReduceThreadsSmall), 0, stream, rargs);
+    else
+        hipLaunchKernelGGL(objective_reduce_kernel<kReduceThreads>, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
 }
 
 // Score of a bf16 strip at M = 4 with byte masks (4 rows x 8 columns = two blocks per lane) in packed arithmetic: the
@@ -776,9 +791,12 @@ struct ScoreReduceArgs {
 constexpr uint32_t kReduceSlices = 32;
 constexpr uint32_t kReduceTwoStageFrom = 8192;    // records of the largest matrix of a launch
 
-template <int STAGE>
-__global__ __launch_bounds__(kReduceThreads) void score_reduce_kernel(const ScoreReduceArgs args)
+// THREADS: 1024, or 256 when no matrix of the launch has more than 512 records (a batch of ordinary layers): four
+// wavefronts to start, reduce and add up instead of sixteen.
+template <int STAGE, int THREADS = kReduceThreads>
+__global__ __launch_bounds__(THREADS) void score_reduce_kernel(const ScoreReduceArgs args)
 {
+    constexpr uint32_t kReduceThreads = THREADS;      // shadows the file-scope constant inside this kernel
     __shared__ double redd[2][kReduceThreads / 64];
     __shared__ unsigned long long redu[5][kReduceThreads / 64];
     const uint32_t m = blockIdx.x;
@@ -1171,7 +1189,7 @@ static int run_mask(const tmask_mat *mats, int n_mats, int dt, int N, int M, int
             return hip_fail(e, "mask kernel launch");
         if (want_obj) {
             rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)ws;
-            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
+            enqueue_objective_reduce(rargs, nb, stream);
             e = hipGetLastError();
             if (e != hipSuccess)
                 return hip_fail(e, "objective reduce launch");
@@ -1194,7 +1212,7 @@ int launch_objective_reduce(double *const *objective, const uint32_t *first0, in
     }
     rargs.tile0[nb] = first0[nb];
     rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)partials;
-    hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
+    enqueue_objective_reduce(rargs, nb, stream);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? TMASK_OK : hip_fail(e, "objective reduce launch");
 }
@@ -1215,7 +1233,10 @@ int launch_score_reduce(const uint32_t *first0, int nb, uint32_t partial0, const
         hipLaunchKernelGGL(score_reduce_kernel<1>, dim3(nb, kReduceSlices), dim3(kReduceThreads), 0, stream, rargs);
         hipLaunchKernelGGL(score_reduce_kernel<2>, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
     } else {
-        hipLaunchKernelGGL(score_reduce_kernel<0>, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
+        if (most <= 2 * kReduceThreadsSmall)
+            hipLaunchKernelGGL((score_reduce_kernel<0, kReduceThreadsSmall>), dim3(nb), dim3(kReduceThreadsSmall), 0, stream, rargs);
+        else
+            hipLaunchKernelGGL(score_reduce_kernel<0>, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
     }
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? TMASK_OK : hip_fail(e, "score reduce launch");
@@ -1549,7 +1570,7 @@ int tmask_approx_pack(const tmask_fused_desc *descs, int n, tmask_dtype dt, int 
             return hip_fail(e, "fused approx+pack kernel launch");
         if (want_obj) {
             rargs.n_mats = (uint32_t)nb; rargs.partial0 = partial0; rargs.partials = (const double *)workspace;
-            hipLaunchKernelGGL(objective_reduce_kernel, dim3(nb), dim3(kReduceThreads), 0, stream, rargs);
+            enqueue_objective_reduce(rargs, nb, stream);
             e = hipGetLastError();
             if (e != hipSuccess)
                 return hip_fail(e, "objective reduce launch");
